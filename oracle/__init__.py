@@ -1,0 +1,197 @@
+"""CPU oracle (test infrastructure only): ctypes front for ``ppv_oracle.c``.
+
+Only tests, the smoke check and the CPU-baseline leg of the benchmark may import this
+package; the HIP path never does, and this package imports nothing from the HIP path.
+
+``Trie``            pointer-based prefix tree over S (Section 2.1, "Prefix-tree")
+``Trie.query``      valid-next-token masks, rank ranges [lo,hi) in sorted S, membership
+``Trie.step``       query + one constrained decoding step per row (Algorithm 1, SampleCandidate body)
+``decode_loop``     Algorithm 1's SampleCandidate for a batch of rows: extend until the row is in S
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+import subprocess
+from dataclasses import dataclass
+from typing import Callable, Optional
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "ppv_oracle.c")
+_LIB = os.path.join(_HERE, "liboracle.so")
+_lib = None
+
+
+def build_oracle(force: bool = False) -> str:
+    """Compile the C oracle with gcc (plain C, OpenMP over rows)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        cmd = ["gcc", "-O2", "-std=c11", "-fopenmp", "-fPIC", "-shared", "-o", _LIB, _SRC, "-lm"]
+        subprocess.run(cmd, check=True)
+    return _LIB
+
+
+def _load():
+    global _lib
+    if _lib is not None:
+        return _lib
+    build_oracle()
+    lib = C.CDLL(_LIB)
+    p = C.c_void_p
+    lib.oracle_trie_build.restype = p
+    lib.oracle_trie_build.argtypes = [p, p, C.c_int64, C.c_int32]
+    lib.oracle_trie_free.argtypes = [p]
+    lib.oracle_trie_members.restype = C.c_int64
+    lib.oracle_trie_members.argtypes = [p]
+    lib.oracle_trie_nodes.restype = C.c_int64
+    lib.oracle_trie_nodes.argtypes = [p]
+    lib.oracle_trie_lmax.restype = C.c_int32
+    lib.oracle_trie_lmax.argtypes = [p]
+    lib.oracle_step_batch.restype = None
+    lib.oracle_step_batch.argtypes = [p, p, C.c_int32, p, C.c_int32, p, p, p, p, p, p, p, p, p, p, p, C.c_int32]
+    lib.oracle_max_threads.restype = C.c_int32
+    _lib = lib
+    return lib
+
+
+def max_threads() -> int:
+    return int(_load().oracle_max_threads())
+
+
+def _ptr(a: Optional[np.ndarray]):
+    return None if a is None else a.ctypes.data_as(C.c_void_p)
+
+
+@dataclass
+class StepResult:
+    mask: np.ndarray          # uint8 [B, V], one byte per token
+    lo: np.ndarray            # int64 [B]
+    hi: np.ndarray            # int64 [B]
+    member: np.ndarray        # int32 [B]
+    ids: Optional[np.ndarray] = None          # int32 [B]
+    logZ_valid: Optional[np.ndarray] = None   # float64 [B]
+    logZ_all: Optional[np.ndarray] = None     # float64 [B]
+    cdf_lo: Optional[np.ndarray] = None       # float64 [B]
+    cdf_hi: Optional[np.ndarray] = None       # float64 [B]
+
+
+class Trie:
+    def __init__(self, tokens: np.ndarray, offsets: np.ndarray, vocab: int):
+        lib = _load()
+        tokens = np.ascontiguousarray(tokens, dtype=np.int32)
+        offsets = np.ascontiguousarray(offsets, dtype=np.int64)
+        self.vocab = int(vocab)
+        self._h = lib.oracle_trie_build(_ptr(tokens), _ptr(offsets), int(offsets.shape[0] - 1), int(vocab))
+        if not self._h:
+            raise ValueError("oracle_trie_build rejected S (empty set, empty sequence or token out of range)")
+        self.n_members = int(lib.oracle_trie_members(self._h))
+        self.n_nodes = int(lib.oracle_trie_nodes(self._h))
+        self.l_max = int(lib.oracle_trie_lmax(self._h))
+
+    def close(self):
+        if getattr(self, "_h", None):
+            _load().oracle_trie_free(self._h)
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def _run(self, prefixes, lens, logits, uniforms, want_mask, threads) -> StepResult:
+        prefixes = np.ascontiguousarray(prefixes, dtype=np.int32)
+        if prefixes.ndim == 1:
+            prefixes = prefixes[None, :]
+        lens = np.ascontiguousarray(lens, dtype=np.int32)
+        B, stride = prefixes.shape
+        assert lens.shape == (B,) and (lens >= 0).all() and (lens <= stride).all()
+        V = self.vocab
+        mask = np.empty((B, V), dtype=np.uint8) if want_mask else None
+        lo = np.empty(B, dtype=np.int64)
+        hi = np.empty(B, dtype=np.int64)
+        member = np.empty(B, dtype=np.int32)
+        res = StepResult(mask, lo, hi, member)
+        if logits is not None:
+            logits = np.ascontiguousarray(logits, dtype=np.float32)
+            uniforms = np.ascontiguousarray(uniforms, dtype=np.float32)
+            assert logits.shape == (B, V) and uniforms.shape == (B,)
+            res.ids = np.empty(B, dtype=np.int32)
+            res.logZ_valid = np.empty(B, dtype=np.float64)
+            res.logZ_all = np.empty(B, dtype=np.float64)
+            res.cdf_lo = np.empty(B, dtype=np.float64)
+            res.cdf_hi = np.empty(B, dtype=np.float64)
+        _load().oracle_step_batch(self._h, _ptr(prefixes), stride, _ptr(lens), B, _ptr(logits), _ptr(uniforms),
+                                  _ptr(mask), _ptr(lo), _ptr(hi), _ptr(member), _ptr(res.ids),
+                                  _ptr(res.logZ_valid), _ptr(res.logZ_all), _ptr(res.cdf_lo), _ptr(res.cdf_hi),
+                                  int(threads))
+        return res
+
+    def query(self, prefixes, lens, want_mask: bool = True, threads: int = 1) -> StepResult:
+        """mask / [lo,hi) / member for a batch of prefixes (int32 [B, stride], lens int32 [B])."""
+        return self._run(prefixes, lens, None, None, want_mask, threads)
+
+    def step(self, prefixes, lens, logits_f32, uniforms, want_mask: bool = True, threads: int = 1) -> StepResult:
+        """query + masked softmax mass + inverse-CDF sample per row."""
+        return self._run(prefixes, lens, logits_f32, uniforms, want_mask, threads)
+
+
+@dataclass
+class LoopResult:
+    seqs: np.ndarray        # int32 [B, l_max] generated sequences (unused slots = -1)
+    lens: np.ndarray        # int32 [B]
+    logx: np.ndarray        # float64 [B]: log of the importance score x = prod of per-step valid masses
+    steps: int              # decode steps run until every row was in S
+    ids_per_step: list      # list of int32 [B] (-1 for rows already finished)
+    logZ_per_step: list     # list of float64 [B] (nan for rows already finished)
+    cdf_lo_per_step: list
+    cdf_hi_per_step: list
+    active_per_step: list   # list of bool [B]: row took part in that step
+
+
+def decode_loop(trie: Trie, B: int, logits_f32_for_step: Callable[[int, np.ndarray, np.ndarray], np.ndarray],
+                uniforms_for_step: Callable[[int], np.ndarray], threads: int = 1,
+                force_ids: Optional[Callable[[int], np.ndarray]] = None) -> LoopResult:
+    """Algorithm 1, SampleCandidate, for B independent rows: start from the empty sequence and
+    repeat {distribution, mask, sample, append, x *= valid mass} while the row is not in S.
+    A row stops the first time it is a member, also when that member has extensions.
+    `logits_f32_for_step(step, seqs, lens)` returns the [B, V] logits of that step (the stand-in
+    for L(a, T); it may look at the rows' current sequences).
+    `force_ids(step)` (tests only) overrides the sampled tokens so that two implementations can be
+    kept on the same path after an excused boundary disagreement."""
+    l_max = trie.l_max
+    seqs = np.full((B, l_max), -1, dtype=np.int32)
+    lens = np.zeros(B, dtype=np.int32)
+    logx = np.zeros(B, dtype=np.float64)
+    active = np.ones(B, dtype=bool)
+    out = LoopResult(seqs, lens, logx, 0, [], [], [], [], [])
+    step = 0
+    while active.any():
+        assert step < l_max, "a row outlived the longest member of S"
+        rows = np.nonzero(active)[0]
+        lg = logits_f32_for_step(step, seqs, lens)[rows]
+        un = uniforms_for_step(step)[rows]
+        r = trie.step(seqs[rows], lens[rows], lg, un, want_mask=False, threads=threads)
+        ids = np.full(B, -1, dtype=np.int32)
+        lz = np.full(B, np.nan)
+        cl = np.full(B, np.nan)
+        ch = np.full(B, np.nan)
+        ids[rows], lz[rows], cl[rows], ch[rows] = r.ids, r.logZ_valid, r.cdf_lo, r.cdf_hi
+        out.ids_per_step.append(ids.copy())
+        if force_ids is not None:
+            f = force_ids(step)
+            ids[rows] = f[rows]
+        out.logZ_per_step.append(lz)
+        out.cdf_lo_per_step.append(cl)
+        out.cdf_hi_per_step.append(ch)
+        out.active_per_step.append(active.copy())
+        assert (ids[rows] >= 0).all(), "an active row had an empty mask"
+        seqs[rows, lens[rows]] = ids[rows]
+        lens[rows] += 1
+        logx[rows] += lz[rows]
+        q = trie.query(seqs[rows], lens[rows], want_mask=False, threads=threads)
+        active[rows] = q.member == 0
+        step += 1
+    out.steps = step
+    return out

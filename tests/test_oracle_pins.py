@@ -1,0 +1,402 @@
+"""Pins for the CPU oracle: it is checked against things other than itself -- the plain
+definition by brute force, closed forms, library routines on special cases, invariants, and the
+paper's worked examples -- so that a dropped term, a wrong sign/index or a transposed operand in
+the oracle fails here.  No GPU needed."""
+import math
+import os
+
+import numpy as np
+import pytest
+from scipy.special import logsumexp
+from scipy.stats import chisquare
+
+import oracle
+from paper_2504_09135_amd import workloads as W
+
+GOLD = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def read_golden(name):
+    out = {}
+    with open(os.path.join(GOLD, name)) as f:
+        for line in f:
+            line = line.split("#")[0].strip()
+            if line:
+                k, v = line.split()
+                out[k] = float(v)
+    return out
+
+
+# ------------------------------------------------------------------ brute force from the definition
+def u32(t):
+    return int(t) & 0xFFFFFFFF
+
+
+def brute(S_lists, vocab, prefix):
+    """Valid set A_{x,S} (Section 2.1), membership, and rank range by scanning S."""
+    members = sorted({tuple(u32(t) for t in s) for s in S_lists})
+    x = tuple(u32(t) for t in prefix)
+    t = len(x)
+    mask = np.zeros(vocab, dtype=np.uint8)
+    for s in members:
+        if len(s) > t and s[:t] == x:
+            mask[s[t]] = 1
+    lo = sum(1 for s in members if s < x)              # tuple order = lexicographic, prefix first
+    cnt = sum(1 for s in members if s[:t] == x)
+    return mask, lo, lo + cnt, int(x in set(members) and t > 0)
+
+
+def as_lists(S: W.ConstraintSet):
+    return [S.seq(i).tolist() for i in range(S.n)]
+
+
+def check_against_brute(S_lists, vocab, prefixes):
+    S = W.constraint_set_from_lists(S_lists, vocab)
+    trie = oracle.Trie(S.tokens, S.offsets, vocab)
+    stride = max(1, max(len(p) for p in prefixes))
+    P = np.full((len(prefixes), stride), W.PAD_TOKEN, dtype=np.int32)
+    L = np.zeros(len(prefixes), dtype=np.int32)
+    for i, p in enumerate(prefixes):
+        P[i, :len(p)] = np.array(p, dtype=np.int64).astype(np.int32)
+        L[i] = len(p)
+    r = trie.query(P, L)
+    for i, p in enumerate(prefixes):
+        m, lo, hi, mem = brute(S_lists, vocab, p)
+        assert np.array_equal(r.mask[i], m), (i, p)
+        assert (r.lo[i], r.hi[i], r.member[i]) == (lo, hi, mem), (i, p, r.lo[i], r.hi[i], r.member[i], lo, hi, mem)
+    return trie
+
+
+def test_mask_range_member_vs_bruteforce_C1():
+    cfg = W.CONFIGS["C1"]
+    S = W.make_constraint_set(cfg)
+    assert S.n == 1000 and S.l_max == 8
+    pb = W.make_prefix_batch(cfg, S, batch=64)
+    prefixes = [pb.prefixes[b, :pb.lens[b]].tolist() for b in range(64)]
+    prefixes += [[], S.seq(0).tolist(), S.seq(5).tolist() + [3]]
+    trie = check_against_brute(as_lists(S), cfg.vocab, prefixes)
+    assert trie.n_members == 1000 and trie.l_max == 8
+
+
+def test_mask_range_member_adversarial_sets():
+    V = 70  # not a multiple of 32; token V-1 in use
+    # a member that is a proper prefix of another, a long shared prefix, duplicates, single tokens
+    S = [[5, 6, 7], [5, 6], [5, 6, 7, 69], [5, 6, 7, 0], [69], [0], [5, 6, 7, 69],
+         [1, 1, 1, 1, 1, 1, 1, 2], [1, 1, 1, 1, 1, 1, 1, 3], [1, 1, 1, 1, 1, 1, 1], [33, 0, 33]]
+    prefixes = [[], [5], [5, 6], [5, 6, 7], [5, 6, 7, 69], [5, 6, 7, 69, 1], [5, 6, 8], [5, 7], [4], [6],
+                [69], [69, 0], [0], [70], [-1], [2 ** 31 - 1], [1, 1, 1, 1, 1, 1, 1], [1, 1, 1, 1, 1, 1, 1, 2],
+                [1, 1, 1, 1, 1, 1, 1, 1], [1] * 12, [33], [33, 0], [33, 0, 33], [33, 0, 34], [33, 1], [5, 6, -5],
+                [5, 6, 7, 0, 0, 0, 0, 0, 0, 0]]
+    check_against_brute(S, V, prefixes)
+
+
+def test_single_sequence_set_and_duplicates():
+    trie = check_against_brute([[3, 1, 2]] * 4, 8, [[], [3], [3, 1], [3, 1, 2], [3, 1, 2, 0], [0], [7], [3, 0], [3, 2]])
+    assert trie.n_members == 1
+
+
+def test_mask_empty_iff_not_in_S_or_leaf():
+    """mask empty <=> (lo == hi) or (the prefix is a member with no extension)."""
+    cfg = W.scaled(W.CONFIGS["C2"], 3000)
+    S = W.make_constraint_set(cfg)
+    trie = oracle.Trie(S.tokens, S.offsets, cfg.vocab)
+    pb = W.make_prefix_batch(cfg, S, batch=400)
+    r = trie.query(pb.prefixes, pb.lens)
+    empty = r.mask.sum(axis=1) == 0
+    expect = (r.lo == r.hi) | ((r.hi - r.lo == 1) & (r.member == 1))
+    assert np.array_equal(empty, expect)
+    assert empty.any() and (~empty).any()
+    # rows drawn as proper prefixes of members are in S's prefix closure: never an empty range
+    assert ((r.hi > r.lo) | ~pb.drawn_valid).all()
+
+
+def test_rejects_bad_sets():
+    for toks, offs, V in [([], [0], 4), ([1, 2], [0, 0, 2], 4), ([1, 4], [0, 2], 4), ([1, -1], [0, 2], 4)]:
+        with pytest.raises(ValueError):
+            oracle.Trie(np.array(toks, dtype=np.int32), np.array(offs, dtype=np.int64), V)
+
+
+def test_ranges_second_route_sorted_matrix():
+    """Ranks from the trie's subtree counts == ranks from numpy sorting of the padded matrix
+    (pad below every token), an independent route."""
+    cfg = W.scaled(W.CONFIGS["C3"], 20000)
+    S = W.make_constraint_set(cfg)
+    trie = oracle.Trie(S.tokens, S.offsets, cfg.vocab)
+    M = S.padded(pad=-1).astype(np.int64)
+    order = np.lexsort(M.T[::-1])
+    M = M[order]
+    pb = W.make_prefix_batch(W.scaled(cfg, cfg.n_seq, batch=200), S)
+    # make a fifth of them invalid
+    pb.prefixes[::5, 0] = (pb.prefixes[::5, 0] + 7) % cfg.vocab
+    pb.lens[::5] = np.maximum(pb.lens[::5], 1)
+    r = trie.query(pb.prefixes, pb.lens, want_mask=False)
+    for b in range(200):
+        t = int(pb.lens[b])
+        x = pb.prefixes[b, :t].astype(np.int64)
+        less = np.zeros(S.n, dtype=bool)
+        eq = np.ones(S.n, dtype=bool)
+        for c in range(t):
+            less |= eq & (M[:, c] < x[c])
+            eq &= M[:, c] == x[c]
+        lo = int(less.sum())
+        assert (r.lo[b], r.hi[b]) == (lo, lo + int(eq.sum()))
+
+
+# ------------------------------------------------------------------ masked log-softmax
+def one_step(logits, mask_bytes, u):
+    """Run the oracle's masked step on a hand-made mask via a one-level S = {[v] : mask[v]}."""
+    V = len(logits)
+    valid = np.nonzero(mask_bytes)[0]
+    if len(valid) == 0:
+        seqs, prefix = [[0, 0]], [1]            # prefix [1] is not in S: empty mask
+    else:
+        seqs, prefix = [[int(v)] for v in valid], []
+    S = W.constraint_set_from_lists(seqs, V)
+    trie = oracle.Trie(S.tokens, S.offsets, V)
+    P = np.full((1, 1), W.PAD_TOKEN, dtype=np.int32)
+    if prefix:
+        P[0, 0] = prefix[0]
+    r = trie.step(P, np.array([len(prefix)], dtype=np.int32), np.asarray(logits, dtype=np.float32)[None, :],
+                  np.array([u], dtype=np.float32))
+    assert np.array_equal(r.mask[0], np.asarray(mask_bytes, dtype=np.uint8))
+    return r
+
+
+def test_logZ_matches_library_logsumexp_and_closed_forms():
+    rng = np.random.default_rng(1)
+    V = 257
+    l = (rng.standard_normal(V) * 3).astype(np.float32)
+    mask = (rng.random(V) < 0.3).astype(np.uint8)
+    r = one_step(l, mask, 0.5)
+    ld = l.astype(np.float64)
+    assert r.logZ_all[0] == pytest.approx(logsumexp(ld), abs=1e-12)
+    assert r.logZ_valid[0] == pytest.approx(logsumexp(ld[mask == 1]) - logsumexp(ld), abs=1e-12)
+    assert r.logZ_valid[0] <= 0
+    # mask = everything => mass 1
+    assert one_step(l, np.ones(V, np.uint8), 0.5).logZ_valid[0] == pytest.approx(0.0, abs=1e-12)
+    # mask = {v} => log softmax(l)_v
+    one = np.zeros(V, np.uint8)
+    one[123] = 1
+    r1 = one_step(l, one, 0.9)
+    assert r1.logZ_valid[0] == pytest.approx(ld[123] - logsumexp(ld), abs=1e-12) and r1.ids[0] == 123
+    # complement identity: the two masses add up to 1
+    rc = one_step(l, 1 - mask, 0.5)
+    assert math.exp(r.logZ_valid[0]) + math.exp(rc.logZ_valid[0]) == pytest.approx(1.0, abs=1e-12)
+    # shift invariance (exact shift in fp32: integers)
+    li = np.round(l * 8).astype(np.float32)
+    a, b = one_step(li, mask, 0.5), one_step(li + 64, mask, 0.5)
+    assert a.logZ_valid[0] == pytest.approx(b.logZ_valid[0], abs=1e-12) and a.ids[0] == b.ids[0]
+    # constant logits: mass = (#valid)/V
+    rcst = one_step(np.full(V, 1.5, np.float32), mask, 0.5)
+    assert rcst.logZ_valid[0] == pytest.approx(math.log(mask.sum() / V), abs=1e-12)
+    # empty mask
+    re = one_step(l, np.zeros(V, np.uint8), 0.5)
+    assert re.ids[0] == -1 and re.logZ_valid[0] == -np.inf
+
+
+def test_logZ_far_below_max_does_not_underflow():
+    l = np.full(64, -900.0, np.float32)
+    l[0] = 0.0
+    mask = np.zeros(64, np.uint8)
+    mask[10] = mask[20] = 1
+    r = one_step(l, mask, 0.75)
+    assert r.logZ_valid[0] == pytest.approx(-900.0 + math.log(2.0), abs=1e-6)  # logsumexp(all) ~ 0
+    assert r.ids[0] == 20
+
+
+def test_inverse_cdf_known_boundaries():
+    p = np.array([0.1, 0.2, 0.3, 0.4])
+    l = np.log(p).astype(np.float32)
+    allm = np.ones(4, np.uint8)
+    for u, want in [(0.0, 0), (0.05, 0), (0.15, 1), (0.29, 1), (0.35, 2), (0.59, 2), (0.65, 3), (0.999, 3)]:
+        assert one_step(l, allm, u).ids[0] == want
+    m = np.array([1, 0, 1, 1], np.uint8)               # renormalised (0.1, 0.3, 0.4)/0.8: cuts 0.125, 0.5
+    for u, want in [(0.0, 0), (0.12, 0), (0.13, 2), (0.49, 2), (0.51, 3), (0.9999, 3)]:
+        r = one_step(l, m, u)
+        assert r.ids[0] == want
+        assert r.cdf_lo[0] <= u < r.cdf_hi[0]
+    r = one_step(l, m, 0.3)
+    assert r.cdf_lo[0] == pytest.approx(0.125, abs=1e-7) and r.cdf_hi[0] == pytest.approx(0.5, abs=1e-7)
+    assert r.logZ_valid[0] == pytest.approx(math.log(0.8), abs=1e-7)
+    # a zero-weight valid token is never chosen: u = 0 skips it, u -> 1 falls back to the last positive one
+    lz = np.array([-np.inf, 0.0, 0.0, -np.inf], np.float32)
+    assert one_step(lz, allm, 0.0).ids[0] == 1
+    assert one_step(lz, allm, np.float32(1.0) - np.float32(2 ** -24)).ids[0] == 2
+
+
+def test_sampling_distribution_chi_square():
+    rng = np.random.default_rng(7)
+    V = 16
+    l = rng.standard_normal(V).astype(np.float32)
+    mask = np.array([1, 1, 0, 1, 0, 0, 1, 1, 1, 0, 1, 1, 0, 1, 1, 0], np.uint8)
+    S = W.constraint_set_from_lists([[int(v)] for v in np.nonzero(mask)[0]], V)
+    trie = oracle.Trie(S.tokens, S.offsets, V)
+    n = 200_000
+    us = rng.random(n, dtype=np.float32)
+    P = np.full((n, 1), W.PAD_TOKEN, np.int32)
+    r = trie.step(P, np.zeros(n, np.int32), np.broadcast_to(l, (n, V)), us, want_mask=False, threads=4)
+    p = np.exp(l.astype(np.float64)) * mask
+    p /= p.sum()
+    counts = np.bincount(r.ids, minlength=V)
+    assert counts[mask == 0].sum() == 0
+    stat = chisquare(counts[mask == 1], p[mask == 1] * n)
+    assert stat.pvalue > 1e-4
+
+
+# ------------------------------------------------------------------ loop identities
+def toy_lm(prefix, V, seed=11):
+    """Deterministic stand-in for L(a, T): logits are a seeded function of the prefix."""
+    h = seed
+    for t in prefix:
+        h = (h * 1000003 + int(t) + 1) % (2 ** 61 - 1)
+    return np.random.default_rng(h).standard_normal(V).astype(np.float32) * 1.5
+
+
+def test_identity_sum_over_S_of_PL_over_x_is_one():
+    """sum_{a in S} P_L(a)/x(a) = 1 and P^CD(a) = P_L(a)/x(a) (appendix, proof of Theorem 3.1),
+    on a prefix-free toy S; a missing or extra valid token anywhere breaks the sum."""
+    V = 6
+    rng = np.random.default_rng(3)
+    seqs = {tuple(rng.integers(0, V, size=3).tolist()) for _ in range(60)}      # fixed length => prefix-free
+    seqs = sorted(seqs)
+    S = W.constraint_set_from_lists([list(s) for s in seqs], V)
+    trie = oracle.Trie(S.tokens, S.offsets, V)
+    total = 0.0
+    accept = 0.0
+    for a in seqs:
+        logp, logx = 0.0, 0.0
+        for i in range(len(a)):
+            l = toy_lm(a[:i], V)
+            P = np.full((1, 3), W.PAD_TOKEN, np.int32)
+            P[0, :i] = a[:i]
+            r = trie.step(P, np.array([i], np.int32), l[None, :], np.array([0.5], np.float32))
+            logp += float(l[a[i]]) - r.logZ_all[0]
+            logx += r.logZ_valid[0]
+        total += math.exp(logp - logx)
+        accept += math.exp(logp)            # = P^CD(a) * x(a)
+    assert total == pytest.approx(1.0, abs=1e-9)
+    # acceptance probability of one draw = P_L(S) <= 1
+    assert 0 < accept < 1
+
+
+def test_decode_loop_law_is_PL_over_x():
+    V = 5
+    seqs = [[0, 1], [0, 2, 3], [0, 2, 4], [1], [2, 0, 0, 1], [2, 0, 0, 2], [3, 3]]
+    S = W.constraint_set_from_lists(seqs, V)
+    trie = oracle.Trie(S.tokens, S.offsets, V)
+    B = 60_000
+    rng = np.random.default_rng(5)
+    us = [rng.random(B, dtype=np.float32) for _ in range(4)]
+
+    def logits_for_step(step, seqs_now, lens_now):
+        out = np.zeros((B, V), np.float32)
+        cache = {}
+        for b in range(B):
+            key = tuple(seqs_now[b, :lens_now[b]].tolist())
+            if key not in cache:
+                cache[key] = toy_lm(key, V)
+            out[b] = cache[key]
+        return out
+
+    res = oracle.decode_loop(trie, B, logits_for_step, lambda s: us[s], threads=4)
+    seqs_arr, lens, logx = res.seqs, res.lens, res.logx
+    # expected law: P^CD(a) = P_L(a)/x(a)
+    expect, xs = [], []
+    for a in seqs:
+        logp, lx = 0.0, 0.0
+        for i in range(len(a)):
+            l = toy_lm(tuple(a[:i]), V).astype(np.float64)
+            r = trie.step(np.array([a[:i] + [W.PAD_TOKEN] * (4 - i)], np.int32), np.array([i], np.int32),
+                          l[None, :].astype(np.float32), np.array([0.5], np.float32))
+            logp += l[a[i]] - r.logZ_all[0]
+            lx += r.logZ_valid[0]
+        expect.append(math.exp(logp - lx))
+        xs.append(lx)
+    assert sum(expect) == pytest.approx(1.0, abs=1e-9)
+    counts = []
+    for a, lx in zip(seqs, xs):
+        hit = (lens == len(a)) & (seqs_arr[:, :len(a)] == np.array(a)).all(axis=1)
+        counts.append(int(hit.sum()))
+        assert np.allclose(logx[hit], lx, atol=1e-9)
+    assert sum(counts) == B
+    assert chisquare(counts, np.array(expect) * B).pvalue > 1e-4
+
+
+def test_decode_loop_function_runs_and_stops_at_first_member():
+    V = 4
+    seqs = [[1], [1, 2], [0, 3], [0, 3, 3]]     # [1] and [0,3] are members with extensions
+    S = W.constraint_set_from_lists(seqs, V)
+    trie = oracle.Trie(S.tokens, S.offsets, V)
+    B = 64
+    rng = np.random.default_rng(0)
+    lg = rng.standard_normal((3, B, V)).astype(np.float32)
+    un = rng.random((3, B), dtype=np.float32)
+    r = oracle.decode_loop(trie, B, lambda s, *_: lg[s], lambda s: un[s])
+    got = {tuple(r.seqs[b, :r.lens[b]].tolist()) for b in range(B)}
+    assert got == {(1,), (0, 3)}                # stops the first time the row is in S (Algorithm 1)
+    assert r.steps == 2
+    assert (r.logx <= 1e-12).all()
+
+
+# ------------------------------------------------------------------ the paper's worked examples
+def run_toy_chain(seqs, V, cond_probs, path):
+    """Valid masses along `path` with conditional next-token probabilities given per prefix."""
+    S = W.constraint_set_from_lists(seqs, V)
+    trie = oracle.Trie(S.tokens, S.offsets, V)
+    masses, pcd, pl = [], 1.0, 1.0
+    for i in range(len(path)):
+        p = np.array(cond_probs[tuple(path[:i])], dtype=np.float64)
+        with np.errstate(divide="ignore"):
+            l = np.log(p).astype(np.float32)
+        P = np.full((1, 4), W.PAD_TOKEN, np.int32)
+        P[0, :i] = path[:i]
+        r = trie.step(P, np.array([i], np.int32), l[None, :], np.array([0.5], np.float32))
+        mass = math.exp(r.logZ_valid[0])
+        masses.append(mass)
+        pcd *= p[path[i]] / mass
+        pl *= p[path[i]]
+    return masses, pcd, pl
+
+
+def test_theorem_2_1_construction():
+    g = read_golden("thm21_construction.txt")
+    pb, eps = g["p_b"], g["eps"]
+    seqs = [[0, 0], [0, 1], [1, 0]]
+    cond = {(): [1 - pb, pb], (0,): [0.5, 0.5], (1,): [eps, 1 - eps]}
+    tol = 1e-7  # logits pass through fp32
+    m, pcd, pl = run_toy_chain(seqs, 2, cond, [0, 0])
+    assert m == pytest.approx([g["mass_root"], g["mass_after_v1"]], abs=tol)
+    assert pcd == pytest.approx(g["pcd_v1v1"], abs=tol)
+    m, pcd2, pl2 = run_toy_chain(seqs, 2, cond, [0, 1])
+    assert pcd2 == pytest.approx(g["pcd_v1v2"], abs=tol)
+    m, pcd3, pl3 = run_toy_chain(seqs, 2, cond, [1, 0])
+    assert m == pytest.approx([g["mass_root"], g["mass_after_v2"]], abs=tol)
+    assert pcd3 == pytest.approx(g["pcd_v2v1"], abs=tol)
+    assert m[0] * m[1] == pytest.approx(g["x_v2v1"], abs=tol)
+    # acceptance = sum_a P^CD(a) x(a) = P_L(S)
+    acc = pcd * g["x_v1v1"] + pcd2 * g["x_v1v2"] + pcd3 * g["x_v2v1"]
+    assert acc == pytest.approx(g["accept"], abs=tol)
+    assert pl + pl2 + pl3 == pytest.approx(g["accept"], abs=tol)
+    # the valid sets the proof states: both tokens at the root and after v1, only v1 after v2
+    S = W.constraint_set_from_lists(seqs, 2)
+    trie = oracle.Trie(S.tokens, S.offsets, 2)
+    q = trie.query(np.array([[9, 9], [0, 9], [1, 9]], np.int32), np.array([0, 1, 1], np.int32))
+    assert q.mask.tolist() == [[1, 1], [1, 1], [1, 0]]
+
+
+def test_figure_1_caption_numbers():
+    g = read_golden("fig1_caption.txt")
+    soccer, used, gloves, shoes, shirts = range(5)
+    seqs = [[soccer, gloves], [used, shirts], [used, soccer, shoes]]
+    z = 0.0
+    cond = {(): [0.6, 0.4, z, z, z], (soccer,): [z, z, 0.1, 0.9, z], (used,): [0.9, z, z, z, 0.1],
+            (used, soccer): [z, z, 0.1, 0.9, z]}
+    tol = 1e-7
+    m, pcd, pl = run_toy_chain(seqs, 5, cond, [soccer, gloves])
+    assert pl == pytest.approx(g["pl_soccer_gloves"], abs=tol)
+    assert pcd == pytest.approx(g["pcd_soccer_gloves"], abs=tol)
+    assert m == pytest.approx([g["mass_root"], g["mass_after_soccer"]], abs=tol)
+    m, pcd, pl = run_toy_chain(seqs, 5, cond, [used, soccer, shoes])
+    assert pl == pytest.approx(g["pl_used_soccer_shoes"], abs=tol)
+    assert pcd == pytest.approx(g["pcd_used_soccer_shoes"], abs=tol)
+    assert m == pytest.approx([g["mass_root"], g["mass_after_used"], g["mass_after_used_soccer"]], abs=tol)
