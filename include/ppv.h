@@ -1,0 +1,158 @@
+/*
+ * ppv.h -- C ABI of the MI355X (gfx950) parallel prefix-verification library.
+ *
+ * The library implements the per-step hot path of set-constrained decoding: for a batch of
+ * decoding prefixes it produces each prefix's valid-next-token mask over the whole vocabulary
+ * (PPV with M = |V|, Section 3.2 "Selection of top candidate tokens": the exact valid set
+ * A_{a,S} of Section 2.1), and a fused masked log-softmax that returns the probability mass the
+ * model puts on valid tokens, |P (.) mask|_1, together with a token sampled from
+ * P (.) mask / |P (.) mask|_1 (Algorithm 1, SampleCandidate).
+ *
+ * Conventions
+ *   - "host" pointers are ordinary CPU memory; "device" pointers are HIP device memory on the
+ *     GPU that was current when the index was built.  The caller owns every buffer it passes.
+ *   - Every call returns a ppv_status and never throws or aborts across this boundary.  Outputs
+ *     are unspecified when the status is not PPV_OK.
+ *   - Calls that take a `stream` (a hipStream_t passed as void*, NULL = the default stream) only
+ *     enqueue work on it and do not synchronise with the host.  Argument checks that need device
+ *     data are not made; checks on host-visible arguments are.
+ *   - An index is immutable after it is built; calls on different streams may run concurrently.
+ *   - Token order is integer order (Section 2.1, footnote on the ordered vocabulary); sequences
+ *     are ordered lexicographically, left to right, a proper prefix before its extensions
+ *     (Section 3.2 "Array Preparation").  Query tokens are compared as unsigned 32-bit values:
+ *     a token outside [0, V) matches nothing and sorts after every real token.
+ *   - Mask layout: row b is ceil(V/32) uint32 words; token v is bit (v & 31), least significant
+ *     first, of word (v >> 5); bits at positions >= V are 0.
+ */
+#ifndef PPV_H
+#define PPV_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct ppv_index ppv_index_t; /* opaque; owns its device memory */
+
+typedef enum {
+    PPV_OK = 0,
+    PPV_EINVAL = -1,  /* bad argument: null pointer, bad size, empty S, empty sequence, token out of range */
+    PPV_ENOMEM = -2,  /* host or device allocation failed */
+    PPV_EDEVICE = -3, /* a HIP call failed (no device, launch error) */
+    PPV_ERANGE = -4   /* a size exceeds what the library supports (see PPV_MAX_VOCAB) */
+} ppv_status;
+
+typedef enum { PPV_F32 = 0, PPV_BF16 = 1 } ppv_dtype;
+
+#define PPV_MAX_VOCAB 262144 /* the per-row bit image (V/8 bytes) is staged in one workgroup's LDS */
+
+const char *ppv_status_string(ppv_status s);
+
+/*
+ * ppv_build_index -- Algorithm 2, "Prepare"; Section 3.2 "Array Preparation".
+ * Builds the device-resident index of the constraint set S: S sorted lexicographically and
+ * de-duplicated (S is a set), stored flat without padding, plus per-depth arrays that list, for
+ * every distinct prefix of a member, its token, its rank range in sorted S and where its
+ * children start at the next depth.
+ *   tokens   host, int32[offsets[n_seq]]: sequence i is tokens[offsets[i] .. offsets[i+1])
+ *   offsets  host, int64[n_seq + 1], non-decreasing, offsets[0] == 0
+ *   n_seq    number of sequences given (duplicates allowed, any order), > 0
+ *   vocab    |V|; every token must lie in [0, vocab); 0 < vocab <= PPV_MAX_VOCAB
+ *   out      receives the handle; release with ppv_free_index
+ * The inputs are copied; the caller keeps ownership.  Synchronous.
+ * Errors: PPV_EINVAL (null pointer, n_seq <= 0, an empty sequence, a token outside [0, vocab),
+ * decreasing offsets), PPV_ERANGE (vocab too large, or more than 2^32 - 2 rows or prefixes),
+ * PPV_ENOMEM, PPV_EDEVICE.
+ */
+ppv_status ppv_build_index(const int32_t *tokens, const int64_t *offsets, int64_t n_seq, int32_t vocab,
+                           ppv_index_t **out);
+
+/* Sizes of a built index.  Any output pointer may be NULL.
+ *   n_distinct   |S| after de-duplication        l_max   longest member
+ *   n_prefixes   number of distinct non-empty prefixes of members (entries of the per-depth arrays)
+ *   device_bytes device memory the index holds */
+ppv_status ppv_index_info(const ppv_index_t *index, int64_t *n_distinct, int32_t *l_max, int32_t *vocab,
+                          int64_t *n_prefixes, int64_t *device_bytes);
+
+/* Copies the sorted, de-duplicated S back to the host (for inspection and tests).
+ *   tokens_out   host, int32[sum of member lengths] or NULL     offsets_out  host, int64[n_distinct + 1] or NULL
+ *   n_tokens     receives the total number of tokens, may be NULL.  Synchronous. */
+ppv_status ppv_index_export(const ppv_index_t *index, int32_t *tokens_out, int64_t *offsets_out, int64_t *n_tokens);
+
+void ppv_free_index(ppv_index_t *index); /* NULL is allowed */
+
+/*
+ * ppv_next_token_mask -- Algorithm 2 with M = |V| (verification of every token at once);
+ * valid set of Section 2.1; Section 3.2 "Parallel Verification".
+ * For each prefix a_b (the first lens[b] tokens of row b of `prefixes`):
+ *   mask[b]      the packed valid set A_{a_b,S} (all zero when a_b is a prefix of no member, and
+ *                when a_b is a member without extensions)
+ *   range_lo[b]  number of members that sort before a_b
+ *   range_hi[b]  range_lo[b] + number of members that a_b is a prefix of; for a prefix of no
+ *                member both equal the rank at which a_b would be inserted (the lower bound
+ *                the binary search of Section 3.2 ends on)
+ *   member[b]    1 iff a_b is itself in S (the loop condition of Algorithm 1), else 0
+ * Arguments (all device pointers):
+ *   prefixes  int32[B, prefix_stride] row-major; only the first lens[b] entries of a row are read
+ *   lens      int32[B], 0 <= lens[b] <= prefix_stride (values outside are clamped into that range)
+ *   mask      uint32[B, ceil(V/32)], fully written
+ *   range_lo, range_hi  uint32[B], each may be NULL      member  uint8[B], may be NULL
+ * B == 0 is allowed and does nothing.  Errors: PPV_EINVAL (null index/prefixes/lens/mask, B < 0,
+ * prefix_stride < 0), PPV_EDEVICE.
+ */
+ppv_status ppv_next_token_mask(const ppv_index_t *index, const int32_t *prefixes, int32_t prefix_stride,
+                               const int32_t *lens, int32_t B, uint32_t *mask, uint32_t *range_lo,
+                               uint32_t *range_hi, uint8_t *member, void *stream);
+
+/*
+ * constrained_sample -- Algorithm 1, SampleCandidate: "Sample a token t from P (.) mask /
+ * |P (.) mask|_1" and the factor |P (.) mask|_1 that multiplies the importance score x,
+ * with P = softmax(logits) (temperature 1, Section 4.1 "Methods").
+ * Per row b:
+ *   logZ_valid[b] = log sum_{v in mask} exp(l_v) - log sum_{all v} exp(l_v)   (<= 0; -inf if the mask is empty)
+ *   logZ_all[b]   = log sum_{all v} exp(l_v)
+ *   ids[b]        = the first valid token, in increasing token id, whose cumulative weight
+ *                   sum_{w <= v, w in mask} exp(l_w) exceeds uniforms[b] * sum_{w in mask} exp(l_w)
+ *                   (inverse-CDF sampling; the paper fixes no procedure); if rounding lets no token
+ *                   exceed it, the last valid token with positive weight; -1 if the mask is empty.
+ * Arguments (all device pointers):
+ *   logits      [B rows] of V elements of type dt, row b starts at element b*row_stride
+ *               (row_stride >= V; rows must be 16-byte aligned: row_stride a multiple of 4 (f32) / 8 (bf16))
+ *   mask        uint32[B, ceil(V/32)] in the layout above
+ *   uniforms    float[B], each in [0, 1)
+ *   ids         int32[B]     logZ_valid  float[B]     logZ_all  float[B] or NULL
+ * Logits must be finite or -inf; accumulation is in fp32 with fp64 across partial sums.
+ * Errors: PPV_EINVAL (null pointer, B < 0, V <= 0, row_stride < V or misaligned, bad dt),
+ * PPV_ERANGE (V > PPV_MAX_VOCAB), PPV_EDEVICE.
+ */
+ppv_status constrained_sample(const void *logits, ppv_dtype dt, int64_t row_stride, const uint32_t *mask,
+                              const float *uniforms, int32_t B, int32_t V, int32_t *ids, float *logZ_valid,
+                              float *logZ_all, void *stream);
+
+/*
+ * ppv_decode_step -- one iteration of the while loop of Algorithm 1's SampleCandidate for B rows,
+ * fused: mask = PPV_S(P, a); sample t; a = a + [t]; x = x * |P (.) mask|_1; stop when a is in S.
+ * Equals ppv_next_token_mask + constrained_sample + append + membership test, but the mask never
+ * leaves the chip.  Rows with active[b] == 0 are left untouched.
+ * Arguments (all device pointers):
+ *   prefixes  int32[B, prefix_stride], in/out: the sampled token is written at position lens[b]
+ *   lens      int32[B], in/out: incremented for rows that sampled a token
+ *   active    uint8[B], in/out: cleared when the extended row is a member of S (the row is done),
+ *             and also (with ids[b] = -1, nothing appended) when the row has no valid token or
+ *             no room left (lens[b] == prefix_stride)
+ *   logits, dt, row_stride, uniforms   as in constrained_sample; V is the index's vocabulary
+ *   ids         int32[B] or NULL: token sampled this step (-1 if none); untouched for inactive rows
+ *   logZ_valid  float[B] or NULL: this step's log valid mass; untouched for inactive rows
+ *   logx        float[B] or NULL, in/out: logx[b] += logZ_valid[b]  (log of the importance score x)
+ * Errors: as the two calls above.
+ */
+ppv_status ppv_decode_step(const ppv_index_t *index, int32_t *prefixes, int32_t prefix_stride, int32_t *lens,
+                           uint8_t *active, const void *logits, ppv_dtype dt, int64_t row_stride,
+                           const float *uniforms, int32_t B, int32_t *ids, float *logZ_valid, float *logx,
+                           void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* PPV_H */

@@ -1,0 +1,212 @@
+"""Thin ctypes binding of libppv_hip.so: argument marshalling only.
+
+Same names as the C ABI in include/ppv.h.  Tensors are torch tensors on the GPU (torch provides
+device memory and the current stream, nothing else); every step of the path runs in the library's
+own kernels.  There is no fallback: if the library is missing or a call fails, this raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Optional, Tuple
+
+import numpy as np
+import torch
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG, "libppv_hip.so")
+
+PPV_OK = 0
+PPV_F32, PPV_BF16 = 0, 1
+PPV_MAX_VOCAB = 262144
+
+SYMBOLS = ("ppv_status_string", "ppv_build_index", "ppv_index_info", "ppv_index_export", "ppv_free_index",
+           "ppv_next_token_mask", "constrained_sample", "ppv_decode_step")
+
+_lib = None
+
+
+class PPVError(RuntimeError):
+    def __init__(self, status: int, what: str):
+        self.status = status
+        super().__init__(f"{what}: status {status} ({status_string(status)})")
+
+
+def load_library() -> C.CDLL:
+    """Load libppv_hip.so (built by paper_2504_09135_amd.build); raises if it is not there."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise FileNotFoundError(f"{LIB_PATH} is missing: run `python -m paper_2504_09135_amd.build` "
+                                "(or __graft_entry__.build()) first; there is no fallback path")
+    lib = C.CDLL(LIB_PATH)
+    p, i32, i64 = C.c_void_p, C.c_int32, C.c_int64
+    lib.ppv_status_string.restype = C.c_char_p
+    lib.ppv_status_string.argtypes = [C.c_int]
+    lib.ppv_build_index.restype = C.c_int
+    lib.ppv_build_index.argtypes = [p, p, i64, i32, C.POINTER(p)]
+    lib.ppv_index_info.restype = C.c_int
+    lib.ppv_index_info.argtypes = [p, C.POINTER(i64), C.POINTER(i32), C.POINTER(i32), C.POINTER(i64), C.POINTER(i64)]
+    lib.ppv_index_export.restype = C.c_int
+    lib.ppv_index_export.argtypes = [p, p, p, C.POINTER(i64)]
+    lib.ppv_free_index.restype = None
+    lib.ppv_free_index.argtypes = [p]
+    lib.ppv_next_token_mask.restype = C.c_int
+    lib.ppv_next_token_mask.argtypes = [p, p, i32, p, i32, p, p, p, p, p]
+    lib.constrained_sample.restype = C.c_int
+    lib.constrained_sample.argtypes = [p, C.c_int, i64, p, p, i32, i32, p, p, p, p]
+    lib.ppv_decode_step.restype = C.c_int
+    lib.ppv_decode_step.argtypes = [p, p, i32, p, p, p, C.c_int, i64, p, i32, p, p, p, p]
+    _lib = lib
+    return lib
+
+
+def status_string(status: int) -> str:
+    return load_library().ppv_status_string(int(status)).decode()
+
+
+def _check(status: int, what: str):
+    if status != PPV_OK:
+        raise PPVError(status, what)
+
+
+def _dev(t: Optional[torch.Tensor], dtype, what: str):
+    if t is None:
+        return None
+    if not (t.is_cuda and t.dtype == dtype and t.is_contiguous()):
+        raise TypeError(f"{what}: need a contiguous GPU tensor of {dtype}, got {t.dtype} on {t.device}")
+    return C.c_void_p(t.data_ptr())
+
+
+def _stream(stream) -> C.c_void_p:
+    s = torch.cuda.current_stream() if stream is None else stream
+    return C.c_void_p(s.cuda_stream)
+
+
+class PPVIndex:
+    """Owner of a ppv_index_t handle."""
+
+    def __init__(self, handle: int):
+        self._h = C.c_void_p(handle)
+        self.n_distinct, self.l_max, self.vocab, self.n_prefixes, self.device_bytes = ppv_index_info(self)
+        self.n_words = (self.vocab + 31) // 32
+
+    @property
+    def handle(self) -> C.c_void_p:
+        if not self._h:
+            raise ValueError("index already freed")
+        return self._h
+
+    def free(self):
+        if self._h:
+            load_library().ppv_free_index(self._h)
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.free()
+        except Exception:
+            pass
+
+
+def ppv_build_index(tokens: np.ndarray, offsets: np.ndarray, vocab: int) -> PPVIndex:
+    """S as host CSR arrays (int32 tokens, int64 offsets) -> device index."""
+    lib = load_library()
+    tokens = np.ascontiguousarray(tokens, dtype=np.int32)
+    offsets = np.ascontiguousarray(offsets, dtype=np.int64)
+    out = C.c_void_p()
+    st = lib.ppv_build_index(tokens.ctypes.data_as(C.c_void_p), offsets.ctypes.data_as(C.c_void_p),
+                             int(offsets.shape[0]) - 1, int(vocab), C.byref(out))
+    _check(st, "ppv_build_index")
+    return PPVIndex(out.value)
+
+
+def ppv_index_info(index: PPVIndex) -> Tuple[int, int, int, int, int]:
+    n, l, v, g, by = C.c_int64(), C.c_int32(), C.c_int32(), C.c_int64(), C.c_int64()
+    _check(load_library().ppv_index_info(index.handle, C.byref(n), C.byref(l), C.byref(v), C.byref(g), C.byref(by)),
+           "ppv_index_info")
+    return n.value, l.value, v.value, g.value, by.value
+
+
+def ppv_index_export(index: PPVIndex) -> Tuple[np.ndarray, np.ndarray]:
+    """Sorted, de-duplicated S as host CSR arrays."""
+    lib = load_library()
+    nt = C.c_int64()
+    _check(lib.ppv_index_export(index.handle, None, None, C.byref(nt)), "ppv_index_export")
+    tokens = np.empty(nt.value, dtype=np.int32)
+    offsets = np.empty(index.n_distinct + 1, dtype=np.int64)
+    _check(lib.ppv_index_export(index.handle, tokens.ctypes.data_as(C.c_void_p),
+                                offsets.ctypes.data_as(C.c_void_p), None), "ppv_index_export")
+    return tokens, offsets
+
+
+def ppv_free_index(index: PPVIndex) -> None:
+    index.free()
+
+
+def ppv_next_token_mask(index: PPVIndex, prefixes: torch.Tensor, lens: torch.Tensor, mask: torch.Tensor,
+                        range_lo: Optional[torch.Tensor] = None, range_hi: Optional[torch.Tensor] = None,
+                        member: Optional[torch.Tensor] = None, stream=None) -> None:
+    """prefixes int32 [B, stride], lens int32 [B] -> mask int32 [B, ceil(V/32)] (bit pattern of
+    uint32 words), range_lo/range_hi int32 [B] (bit pattern of uint32), member uint8 [B]."""
+    B, stride = (int(prefixes.shape[0]), int(prefixes.shape[1])) if prefixes.dim() == 2 else (0, 0)
+    if prefixes.dim() != 2 or tuple(lens.shape) != (B,) or tuple(mask.shape) != (B, index.n_words):
+        raise ValueError("ppv_next_token_mask: shape mismatch")
+    for t, nm in ((range_lo, "range_lo"), (range_hi, "range_hi"), (member, "member")):
+        if t is not None and tuple(t.shape) != (B,):
+            raise ValueError(f"ppv_next_token_mask: {nm} must have shape [B]")
+    st = load_library().ppv_next_token_mask(
+        index.handle, _dev(prefixes, torch.int32, "prefixes"), stride, _dev(lens, torch.int32, "lens"), B,
+        _dev(mask, torch.int32, "mask"), _dev(range_lo, torch.int32, "range_lo"),
+        _dev(range_hi, torch.int32, "range_hi"), _dev(member, torch.uint8, "member"), _stream(stream))
+    _check(st, "ppv_next_token_mask")
+
+
+def _logits_args(logits: torch.Tensor):
+    if logits.dim() != 2 or not logits.is_cuda or logits.stride(1) != 1:
+        raise ValueError("logits: need a 2-D GPU tensor with unit stride along the vocabulary")
+    if logits.dtype == torch.float32:
+        dt = PPV_F32
+    elif logits.dtype == torch.bfloat16:
+        dt = PPV_BF16
+    else:
+        raise TypeError(f"logits: float32 or bfloat16, got {logits.dtype}")
+    return C.c_void_p(logits.data_ptr()), dt, int(logits.stride(0)) if logits.shape[0] > 1 else int(logits.shape[1])
+
+
+def constrained_sample(logits: torch.Tensor, mask: torch.Tensor, uniforms: torch.Tensor, ids: torch.Tensor,
+                       logZ_valid: torch.Tensor, logZ_all: Optional[torch.Tensor] = None, stream=None) -> None:
+    """logits [B, V] f32/bf16, mask int32 [B, ceil(V/32)], uniforms f32 [B] -> ids int32 [B],
+    logZ_valid f32 [B], logZ_all f32 [B] (optional)."""
+    ptr, dt, row_stride = _logits_args(logits)
+    B, V = int(logits.shape[0]), int(logits.shape[1])
+    if tuple(mask.shape) != (B, (V + 31) // 32) or tuple(uniforms.shape) != (B,) or tuple(ids.shape) != (B,) \
+            or tuple(logZ_valid.shape) != (B,) or (logZ_all is not None and tuple(logZ_all.shape) != (B,)):
+        raise ValueError("constrained_sample: shape mismatch")
+    st = load_library().constrained_sample(
+        ptr, dt, row_stride, _dev(mask, torch.int32, "mask"), _dev(uniforms, torch.float32, "uniforms"), B, V,
+        _dev(ids, torch.int32, "ids"), _dev(logZ_valid, torch.float32, "logZ_valid"),
+        _dev(logZ_all, torch.float32, "logZ_all"), _stream(stream))
+    _check(st, "constrained_sample")
+
+
+def ppv_decode_step(index: PPVIndex, prefixes: torch.Tensor, lens: torch.Tensor, active: torch.Tensor,
+                    logits: torch.Tensor, uniforms: torch.Tensor, ids: Optional[torch.Tensor] = None,
+                    logZ_valid: Optional[torch.Tensor] = None, logx: Optional[torch.Tensor] = None,
+                    stream=None) -> None:
+    """One fused constrained decoding step, in place on prefixes / lens / active / logx."""
+    ptr, dt, row_stride = _logits_args(logits)
+    B, stride = int(prefixes.shape[0]), int(prefixes.shape[1])
+    if int(logits.shape[0]) != B or int(logits.shape[1]) != index.vocab or tuple(lens.shape) != (B,) \
+            or tuple(active.shape) != (B,) or tuple(uniforms.shape) != (B,):
+        raise ValueError("ppv_decode_step: shape mismatch")
+    for t, nm in ((ids, "ids"), (logZ_valid, "logZ_valid"), (logx, "logx")):
+        if t is not None and tuple(t.shape) != (B,):
+            raise ValueError(f"ppv_decode_step: {nm} must have shape [B]")
+    st = load_library().ppv_decode_step(
+        index.handle, _dev(prefixes, torch.int32, "prefixes"), stride, _dev(lens, torch.int32, "lens"),
+        _dev(active, torch.uint8, "active"), ptr, dt, row_stride, _dev(uniforms, torch.float32, "uniforms"), B,
+        _dev(ids, torch.int32, "ids"), _dev(logZ_valid, torch.float32, "logZ_valid"),
+        _dev(logx, torch.float32, "logx"), _stream(stream))
+    _check(st, "ppv_decode_step")

@@ -1,0 +1,41 @@
+// Internal definitions shared by the sources of libppv_hip.so (not part of the C ABI).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "ppv.h"
+
+// Device view of the index.  The distinct non-empty prefixes of members ("nodes") are stored in
+// breadth-first order: all prefixes of length 1 in sorted order, then all of length 2, ...
+// Node 0 is the empty prefix.  Because each depth is sorted, the children of consecutive nodes
+// are consecutive, so one offsets array describes all of them: the children of node g are the
+// nodes child_off[g] .. child_off[g+1].
+struct IndexView {
+    const uint32_t *node_tok;   // [n_nodes]   last token of the prefix (node 0: unused)
+    const uint32_t *node_lo;    // [n_nodes]   rank of the first member the prefix is a prefix of
+    const uint32_t *node_hi;    // [n_nodes]   one past the rank of the last such member
+    const uint32_t *child_off;  // [n_nodes+1] CSR offsets into the node arrays
+    uint32_t n_nodes;           // including node 0
+    uint32_t n_rows;            // |S| after de-duplication
+    int32_t vocab;
+    int32_t l_max;
+};
+
+struct ppv_index {
+    IndexView view;
+    uint32_t *d_node_tok, *d_node_lo, *d_node_hi, *d_child_off;
+    int32_t *d_x_tok;    // sorted S, flat, no padding: row r is d_x_tok[d_x_off[r] .. d_x_off[r+1])
+    int64_t *d_x_off;    // [n_rows + 1]
+    int64_t n_tokens;
+    int64_t device_bytes;
+    int device;
+};
+
+#define PPV_HIP_TRY(expr)                          \
+    do {                                           \
+        hipError_t e_ = (expr);                    \
+        if (e_ != hipSuccess) {                    \
+            (void)hipGetLastError();               \
+            return (e_ == hipErrorOutOfMemory) ? PPV_ENOMEM : PPV_EDEVICE; \
+        }                                          \
+    } while (0)

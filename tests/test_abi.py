@@ -1,0 +1,62 @@
+"""The C-ABI library loads, exports every function include/ppv.h declares, and rejects bad
+arguments with status codes before touching a device.  No GPU needed."""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "ppv.h")
+
+
+def declared_functions():
+    src = open(HEADER).read()
+    src = re.sub(r"/\*.*?\*/", "", src, flags=re.S)
+    return sorted(set(re.findall(r"\b(ppv_\w+|constrained_sample)\s*\(", src)) - {"ppv_index"})
+
+
+@pytest.fixture(scope="module")
+def lib():
+    from paper_2504_09135_amd import binding
+    return binding.load_library()
+
+
+def test_header_and_binding_agree(lib):
+    from paper_2504_09135_amd import binding
+    names = declared_functions()
+    assert set(names) == set(binding.SYMBOLS)
+    for n in names:
+        assert getattr(lib, n) is not None
+    hdr = open(HEADER).read()
+    assert int(re.search(r"#define PPV_MAX_VOCAB (\d+)", hdr).group(1)) == binding.PPV_MAX_VOCAB
+
+
+def test_status_strings(lib):
+    for s in (0, -1, -2, -3, -4, 77):
+        assert isinstance(lib.ppv_status_string(s), bytes)
+
+
+def test_argument_errors_without_device(lib):
+    from paper_2504_09135_amd.binding import PPV_MAX_VOCAB
+    out = C.c_void_p()
+    tok = np.array([1, 2, 3], dtype=np.int32)
+    off = np.array([0, 2, 3], dtype=np.int64)
+    tp, op = tok.ctypes.data_as(C.c_void_p), off.ctypes.data_as(C.c_void_p)
+    EINVAL, ERANGE = -1, -4
+    assert lib.ppv_build_index(None, op, 2, 8, C.byref(out)) == EINVAL
+    assert lib.ppv_build_index(tp, None, 2, 8, C.byref(out)) == EINVAL
+    assert lib.ppv_build_index(tp, op, 0, 8, C.byref(out)) == EINVAL
+    assert lib.ppv_build_index(tp, op, 2, 0, C.byref(out)) == EINVAL
+    assert lib.ppv_build_index(tp, op, 2, 8, None) == EINVAL
+    assert lib.ppv_build_index(tp, op, 2, PPV_MAX_VOCAB + 1, C.byref(out)) == ERANGE
+    assert out.value is None
+    assert lib.ppv_index_info(None, None, None, None, None, None) == EINVAL
+    assert lib.ppv_index_export(None, None, None, None) == EINVAL
+    lib.ppv_free_index(None)
+    assert lib.ppv_next_token_mask(None, None, 0, None, 0, None, None, None, None, None) == EINVAL
+    assert lib.constrained_sample(None, 0, 8, None, None, 1, 8, None, None, None, None) == EINVAL
+    assert lib.constrained_sample(None, 0, 8, None, None, -1, 8, None, None, None, None) == EINVAL
+    assert lib.constrained_sample(None, 0, 8, None, None, 0, 8, None, None, None, None) == 0
+    assert lib.ppv_decode_step(None, None, 0, None, None, None, 0, 0, None, 0, None, None, None, None) == EINVAL

@@ -1,0 +1,312 @@
+"""Parity of the HIP path (through the C-ABI) with the CPU oracle, element by element, at sizes
+the oracle finishes in seconds that still span several tiles and a ragged tail; plus edge cases."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2504_09135_amd import binding as ppv
+from paper_2504_09135_amd import workloads as W
+
+from gpu_helpers import (DEV, assert_query_parity, check_sample_rows, gpu_query, gpu_sample, logits_to_dev, to_dev,
+                         unpack_mask)
+
+pytestmark = pytest.mark.gpu
+
+# (config, |S|, batch): the five workload recipes, the larger ones scaled down
+CASES = {
+    "C1": (W.CONFIGS["C1"], 1_000, 16),
+    "C2": (W.CONFIGS["C2"], 100_000, 64),
+    "C3s": (W.CONFIGS["C3"], 60_000, 96),
+    "C4s": (W.CONFIGS["C4"], 300_000, 512),
+    "C5s": (W.CONFIGS["C5"], 80_000, 48),
+}
+
+_cache = {}
+
+
+def setup_case(name):
+    if name not in _cache:
+        base, n, batch = CASES[name]
+        cfg = W.scaled(base, n, batch, name=name)
+        S = W.make_constraint_set(cfg)
+        trie = oracle.Trie(S.tokens, S.offsets, cfg.vocab)
+        index = ppv.ppv_build_index(S.tokens, S.offsets, cfg.vocab)
+        _cache[name] = (cfg, S, trie, index)
+    return _cache[name]
+
+
+@pytest.mark.parametrize("name", list(CASES))
+def test_index_is_sorted_deduplicated_S(name):
+    cfg, S, trie, index = setup_case(name)
+    assert index.n_distinct == trie.n_members and index.l_max == trie.l_max and index.vocab == cfg.vocab
+    assert index.n_prefixes == trie.n_nodes - 1
+    tok, off = ppv.ppv_index_export(index)
+    assert off[0] == 0 and off[-1] == tok.shape[0] and (np.diff(off) > 0).all()
+    # rows strictly increasing in lexicographic order (prefix first): compare neighbours column by column
+    n = index.n_distinct
+    L = index.l_max
+    M = np.full((n, L), -1, dtype=np.int64)
+    lens = np.diff(off)
+    M[np.arange(L)[None, :] < lens[:, None]] = tok
+    a, b = M[:-1], M[1:]
+    diff = a != b
+    assert diff.any(axis=1).all(), "duplicate rows"
+    first = diff.argmax(axis=1)
+    r = np.arange(n - 1)
+    assert (a[r, first] < b[r, first]).all(), "rows out of order"
+    # same multiset of rows as the generator's S (S has no duplicates)
+    if n <= 120_000:
+        assert sorted(map(bytes, M.astype(np.int32))) == sorted(map(bytes, S.padded(-1)))
+
+
+@pytest.mark.parametrize("name", list(CASES))
+def test_mask_range_member_parity(name):
+    cfg, S, trie, index = setup_case(name)
+    for it in range(2):
+        pb = W.make_prefix_batch(cfg, S, index=it)
+        assert_query_parity(index, trie, pb.prefixes, pb.lens)
+
+
+@pytest.mark.parametrize("name", list(CASES))
+def test_constrained_sample_parity(name):
+    cfg, S, trie, index = setup_case(name)
+    pb = W.make_prefix_batch(cfg, S, index=3)
+    dmask, _ = assert_query_parity(index, trie, pb.prefixes, pb.lens)
+    logits = W.make_logits(cfg, step=3)
+    un = W.make_uniforms(cfg, step=3)
+    ref = trie.step(pb.prefixes, pb.lens, W.logits_as_f32(cfg, logits), un, threads=8)
+    ids, lzv, lza = gpu_sample(cfg, logits_to_dev(cfg, logits), dmask, un)
+    check_sample_rows(cfg.dtype, ref, lambda b: ref.mask[b], un, ids, lzv, lza)
+    assert (lzv <= 1e-6).all()
+
+
+@pytest.mark.parametrize("name", ["C1", "C2", "C3s"])
+def test_decode_step_equals_mask_plus_sample(name):
+    cfg, S, trie, index = setup_case(name)
+    pb = W.make_prefix_batch(cfg, S, index=5)
+    B = pb.prefixes.shape[0]
+    stride = pb.stride + 1                                   # room to append
+    P = np.full((B, stride), W.PAD_TOKEN, np.int32)
+    P[:, :pb.stride] = pb.prefixes
+    logits = W.make_logits(cfg, step=5)
+    un = W.make_uniforms(cfg, step=5)
+    active = np.ones(B, np.uint8)
+    active[1::7] = 0
+    ref = trie.step(P, pb.lens, W.logits_as_f32(cfg, logits), un, threads=8)
+    dP, dL, dA = to_dev(P), to_dev(pb.lens), to_dev(active)
+    ids = torch.full((B,), -9, dtype=torch.int32, device=DEV)
+    lz = torch.full((B,), 5.0, dtype=torch.float32, device=DEV)
+    logx = torch.full((B,), 0.25, dtype=torch.float32, device=DEV)
+    ppv.ppv_decode_step(index, dP, dL, dA, logits_to_dev(cfg, logits), to_dev(un), ids, lz, logx)
+    torch.cuda.synchronize()
+    gP, gL, gA, gid, glz, glx = (t.cpu().numpy() for t in (dP, dL, dA, ids, lz, logx))
+    on = active == 1
+    # inactive rows untouched
+    assert np.array_equal(gP[~on], P[~on]) and np.array_equal(gL[~on], pb.lens[~on])
+    assert (gid[~on] == -9).all() and (glz[~on] == 5.0).all() and (glx[~on] == 0.25).all() and (gA[~on] == 0).all()
+    rows = np.nonzero(on)[0]
+
+    class Sub:
+        pass
+    sub = Sub()
+    for k in ("ids", "logZ_valid", "logZ_all", "cdf_lo", "cdf_hi"):
+        setattr(sub, k, getattr(ref, k)[rows])
+    check_sample_rows(cfg.dtype, sub, lambda i: ref.mask[rows[i]], un[rows], gid[rows], glz[rows], None, rows=rows)
+    for b in rows:
+        if gid[b] < 0:
+            assert gL[b] == pb.lens[b] and gA[b] == 0 and np.array_equal(gP[b], P[b]) and glx[b] == 0.25
+            continue
+        assert gL[b] == pb.lens[b] + 1 and gP[b, pb.lens[b]] == gid[b]
+        assert np.array_equal(np.delete(gP[b], pb.lens[b]), np.delete(P[b], pb.lens[b]))
+        assert glx[b] == np.float32(0.25) + glz[b]
+    # membership of the extended rows decides `active`
+    ext = rows[gid[rows] >= 0]
+    q = trie.query(gP[ext], gL[ext], want_mask=False)
+    assert np.array_equal(gA[ext], (q.member == 0).astype(np.uint8))
+
+
+def test_decode_loop_parity_small():
+    """Algorithm 1's SampleCandidate loop on a scaled C3: the HIP loop and the oracle loop are kept
+    on the same path (an excused boundary disagreement is forced onto the oracle's side)."""
+    cfg, S, trie, index = setup_case("C3s")
+    B = 64
+    stride = index.l_max
+    dP = torch.full((B, stride), W.PAD_TOKEN, dtype=torch.int32, device=DEV)
+    dL = torch.zeros(B, dtype=torch.int32, device=DEV)
+    dA = torch.ones(B, dtype=torch.uint8, device=DEV)
+    logx = torch.zeros(B, dtype=torch.float32, device=DEV)
+    ids = torch.zeros(B, dtype=torch.int32, device=DEV)
+    lz = torch.zeros(B, dtype=torch.float32, device=DEV)
+    gpu_ids, gpu_lz = [], []
+    lg = lambda s, *_: W.logits_as_f32(cfg, W.make_logits(cfg, batch=B, step=100 + s))
+    un = lambda s: W.make_uniforms(cfg, batch=B, step=100 + s)
+    res = oracle.decode_loop(trie, B, lg, un, threads=8)
+    excused = 0
+    for s in range(res.steps):
+        act_before = dA.cpu().numpy().astype(bool)
+        assert np.array_equal(act_before, res.active_per_step[s]), s
+        ids.fill_(-5)
+        ppv.ppv_decode_step(index, dP, dL, dA, logits_to_dev(cfg, W.make_logits(cfg, batch=B, step=100 + s)),
+                            to_dev(un(s)), ids, lz, logx)
+        torch.cuda.synchronize()
+        gid, glz = ids.cpu().numpy(), lz.cpu().numpy()
+        rows = np.nonzero(act_before)[0]
+        q = trie.query(res.seqs[rows], np.full(len(rows), s, np.int32))   # oracle masks of this step's prefixes
+
+        class Sub:
+            pass
+        sub = Sub()
+        sub.ids = res.ids_per_step[s][rows]
+        sub.logZ_valid = res.logZ_per_step[s][rows]
+        sub.logZ_all = None
+        sub.cdf_lo = res.cdf_lo_per_step[s][rows]
+        sub.cdf_hi = res.cdf_hi_per_step[s][rows]
+        ex = check_sample_rows(cfg.dtype, sub, lambda i: q.mask[i], un(s)[rows], gid[rows], glz[rows], None, rows=rows)
+        assert ex == 0, "no boundary case expected at this size (would need re-steering)"
+    assert not dA.cpu().numpy().any()
+    assert np.array_equal(dL.cpu().numpy(), res.lens)
+    gP = dP.cpu().numpy()
+    for b in range(B):
+        assert np.array_equal(gP[b, :res.lens[b]], res.seqs[b, :res.lens[b]])
+    assert np.allclose(logx.cpu().numpy(), res.logx, rtol=1e-3, atol=1e-3)
+
+
+# ------------------------------------------------------------------------------------------ edge cases
+def brute_rows(S_lists, V, prefixes):
+    from test_oracle_pins import brute
+    return [brute(S_lists, V, p) for p in prefixes]
+
+
+def test_adversarial_set_vs_bruteforce_and_oracle():
+    V = 70
+    Sl = [[5, 6, 7], [5, 6], [5, 6, 7, 69], [5, 6, 7, 0], [69], [0], [5, 6, 7, 69],
+          [1, 1, 1, 1, 1, 1, 1, 2], [1, 1, 1, 1, 1, 1, 1, 3], [1, 1, 1, 1, 1, 1, 1], [33, 0, 33]]
+    prefixes = [[], [5], [5, 6], [5, 6, 7], [5, 6, 7, 69], [5, 6, 7, 69, 1], [5, 6, 8], [5, 7], [4], [6],
+                [69], [69, 0], [0], [70], [-1], [2 ** 31 - 1], [1, 1, 1, 1, 1, 1, 1], [1, 1, 1, 1, 1, 1, 1, 2],
+                [1, 1, 1, 1, 1, 1, 1, 1], [1] * 12, [33], [33, 0], [33, 0, 33], [33, 0, 34], [33, 1], [5, 6, -5],
+                [5, 6, 7, 0, 0, 0, 0, 0, 0, 0]]
+    S = W.constraint_set_from_lists(Sl, V)
+    index = ppv.ppv_build_index(S.tokens, S.offsets, V)
+    trie = oracle.Trie(S.tokens, S.offsets, V)
+    assert index.n_distinct == 10 and index.l_max == 8
+    stride = 12
+    P = np.full((len(prefixes), stride), W.PAD_TOKEN, np.int32)
+    L = np.zeros(len(prefixes), np.int32)
+    for i, p in enumerate(prefixes):
+        P[i, :len(p)] = np.array(p, dtype=np.int64).astype(np.int32)
+        L[i] = len(p)
+    assert_query_parity(index, trie, P, L)
+    _, words, lo, hi, member = gpu_query(index, P, L)
+    got = unpack_mask(words, V)
+    for i, (m, blo, bhi, bmem) in enumerate(brute_rows(Sl, V, prefixes)):
+        assert np.array_equal(got[i], m) and (lo[i], hi[i], member[i]) == (blo, bhi, bmem), (i, prefixes[i])
+
+
+def test_wide_fanout_root_search_rounds():
+    """A root with tens of thousands of children exercises the multi-round 64-way search and every
+    insertion position (first, between, last)."""
+    V = 262_144
+    rng = np.random.default_rng(9)
+    firsts = np.unique(rng.integers(1, V - 1, size=40_000))
+    seqs = [[int(t), 1] for t in firsts]
+    S = W.constraint_set_from_lists(seqs, V)
+    index = ppv.ppv_build_index(S.tokens, S.offsets, V)
+    trie = oracle.Trie(S.tokens, S.offsets, V)
+    q = np.concatenate([firsts[:300], firsts[-300:], rng.integers(0, V, size=1400), [0, V - 1, V, -1]]).astype(np.int64)
+    P = np.full((len(q), 2), 1, np.int32)
+    P[:, 0] = q.astype(np.int32)
+    L = np.ones(len(q), np.int32)
+    L[::3] = 2
+    assert_query_parity(index, trie, P, L)
+    assert_query_parity(index, trie, P[:4], np.zeros(4, np.int32))      # the root's own mask: 40k bits
+
+
+def test_empty_batch_and_null_outputs():
+    cfg, S, trie, index = setup_case("C1")
+    ppv.ppv_next_token_mask(index, torch.zeros((0, 8), dtype=torch.int32, device=DEV),
+                            torch.zeros(0, dtype=torch.int32, device=DEV),
+                            torch.zeros((0, index.n_words), dtype=torch.int32, device=DEV))
+    pb = W.make_prefix_batch(cfg, S)
+    mask = torch.zeros((16, index.n_words), dtype=torch.int32, device=DEV)
+    ppv.ppv_next_token_mask(index, to_dev(pb.prefixes), to_dev(pb.lens), mask)      # no lo/hi/member
+    torch.cuda.synchronize()
+    ref = trie.query(pb.prefixes, pb.lens)
+    assert np.array_equal(unpack_mask(mask.cpu().numpy().view(np.uint32), cfg.vocab), ref.mask)
+
+
+def test_sample_edge_cases():
+    """Hand-made masks: empty row, single token, all tokens, valid tokens far below the maximum,
+    -inf logits, u = 0 and u -> 1, V not a multiple of 32, padded row stride."""
+    V = 1000
+    rng = np.random.default_rng(4)
+    B = 10
+    lg = (rng.standard_normal((B, V)) * 2).astype(np.float32)
+    mask = (rng.random((B, V)) < 0.05).astype(np.uint8)
+    un = rng.random(B, dtype=np.float32)
+    mask[0] = 0                                   # empty
+    mask[1] = 0; mask[1, 999] = 1                 # single (last token)
+    mask[2] = 1                                   # everything
+    lg[3, 5] = 60.0; mask[3, 5] = 0               # valid mass ~ e^-55
+    lg[4, mask[4] == 1] = -np.inf; mask[4, 77] = 1; lg[4, 77] = 0.5    # valid tokens with zero weight
+    un[5] = 0.0
+    un[6] = np.float32(1.0) - np.float32(2 ** -24)
+    lg[7] = 1.25                                   # constant logits: CDF cuts at multiples of 1/count
+    lg[8, :] = -200.0; lg[8, 0] = 0.0; mask[8] = 0; mask[8, 500] = mask[8, 600] = 1   # mass ~ e^-200
+    words = np.packbits(np.pad(mask, ((0, 0), (0, 24))), axis=1, bitorder="little").view(np.uint32)
+    stride = 1008
+    dl = torch.zeros((B, stride), dtype=torch.float32, device=DEV)
+    dl[:, :V] = to_dev(lg)
+    ids = torch.zeros(B, dtype=torch.int32, device=DEV)
+    lzv = torch.zeros(B, dtype=torch.float32, device=DEV)
+    ppv.constrained_sample(dl[:, :V], to_dev(words.view(np.int32)), to_dev(un), ids, lzv)
+    torch.cuda.synchronize()
+    gid, glz = ids.cpu().numpy(), lzv.cpu().numpy()
+    from test_oracle_pins import one_step
+    for b in range(B):
+        r = one_step(lg[b], mask[b], un[b])
+        check_sample_rows("f32", r, lambda i: mask[b], un[b:b + 1], gid[b:b + 1], glz[b:b + 1], None, rows=[b])
+    assert gid[0] == -1 and gid[1] == 999 and gid[4] == 77
+
+
+def test_bf16_sample_matches_f32_on_same_values():
+    cfg, S, trie, index = setup_case("C2")
+    pb = W.make_prefix_batch(cfg, S, index=8)
+    dmask, _ = assert_query_parity(index, trie, pb.prefixes, pb.lens)
+    bits = W.make_logits(cfg, step=8)
+    un = W.make_uniforms(cfg, step=8)
+    a = gpu_sample(cfg, logits_to_dev(cfg, bits), dmask, un)
+    b = gpu_sample(cfg, to_dev(W.bf16_bits_to_f32(bits)), dmask, un)
+    assert np.array_equal(a[0], b[0]) and np.array_equal(a[1], b[1]) and np.array_equal(a[2], b[2])
+
+
+def test_results_are_bit_repeatable():
+    cfg, S, trie, index = setup_case("C5s")
+    pb = W.make_prefix_batch(cfg, S, index=2)
+    logits = logits_to_dev(cfg, W.make_logits(cfg, step=2))
+    un = W.make_uniforms(cfg, step=2)
+    runs = []
+    for _ in range(3):
+        dmask, words, lo, hi, member = gpu_query(index, pb.prefixes, pb.lens)
+        ids, lzv, lza = gpu_sample(cfg, logits, dmask, un)
+        runs.append((words.copy(), lo, hi, member, ids, lzv.view(np.uint32), lza.view(np.uint32)))
+    for r in runs[1:]:
+        for x, y in zip(runs[0], r):
+            assert np.array_equal(x, y)
+
+
+def test_binding_rejects_bad_arguments():
+    cfg, S, trie, index = setup_case("C1")
+    with pytest.raises(ppv.PPVError):
+        ppv.ppv_build_index(np.array([1, 99999], np.int32), np.array([0, 2], np.int64), 1024)   # token out of range
+    with pytest.raises(ppv.PPVError):
+        ppv.ppv_build_index(np.array([1, 2], np.int32), np.array([0, 0, 2], np.int64), 1024)    # empty sequence
+    with pytest.raises(TypeError):
+        ppv.ppv_next_token_mask(index, torch.zeros((2, 8), dtype=torch.int64, device=DEV),
+                                torch.zeros(2, dtype=torch.int32, device=DEV),
+                                torch.zeros((2, index.n_words), dtype=torch.int32, device=DEV))
+    with pytest.raises(ppv.PPVError):     # misaligned row stride for fp32 (not a multiple of 4 elements)
+        base = torch.zeros((2, 1026), dtype=torch.float32, device=DEV)
+        ppv.constrained_sample(base[:, :1022], torch.zeros((2, 32), dtype=torch.int32, device=DEV),
+                               torch.zeros(2, device=DEV), torch.zeros(2, dtype=torch.int32, device=DEV),
+                               torch.zeros(2, device=DEV))
