@@ -43,6 +43,7 @@ def main() -> int:
     ap.add_argument("--config", default="C3", choices=["C3"])
     ap.add_argument("--n-seq", type=int, default=0, help="override |S| (debugging only; invalidates the metric)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--verbose", action="store_true", help="per-decode-step table on stderr")
     args = ap.parse_args()
     if args.gpus != 1:
         print(f"bench.py: this build runs on one GPU only (got --gpus {args.gpus}); the path is data-parallel "
@@ -124,6 +125,10 @@ def main() -> int:
     fan = fanout_along(index, ppv, torch, seqs, final_lens, L, dev)             # [L] mean children of the prefixes reached at step s
     bytes_per_launch = np.array([
         active_per_step[s] * algorithmic_bytes_per_prefix_step(V, 2, fan[s], s, s) for s in range(L)])
+    if args.verbose:
+        for s_ in range(L):
+            print(f"step {s_:2d} active {active_per_step[s_]:4d} fanout {fan[s_]:9.1f} launch {dur_ms[s_] * 1e3:8.2f} us "
+                  f"{bytes_per_launch[s_] / max(dur_ms[s_], 1e-9) / 1e6:8.1f} GB/s", file=sys.stderr)
     launches = int((active_per_step > 0).sum())
     busy = active_per_step > 0
     achieved = float(bytes_per_launch[busy].sum() / (dur_ms[busy].sum() * 1e-3) / 1e9)

@@ -199,7 +199,8 @@ void oracle_masked_sample(const float *logits, int64_t V, const uint8_t *mask, d
     *logZ_all = m_all + log(z_all);
     int any = 0;
     for (int64_t v = 0; v < V; v++) any |= mask[v];
-    if (!any) { *id = -1; *logZ_valid = -INFINITY; *cdf_lo = 0.0; *cdf_hi = 0.0; return; }
+    /* no valid token, or none with positive probability: nothing can be sampled */
+    if (!any || m_val == -INFINITY) { *id = -1; *logZ_valid = -INFINITY; *cdf_lo = 0.0; *cdf_hi = 0.0; return; }
     double z_val = 0.0;
     for (int64_t v = 0; v < V; v++)
         if (mask[v]) z_val += exp((double)logits[v] - m_val);

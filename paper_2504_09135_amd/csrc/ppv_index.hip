@@ -93,7 +93,9 @@ ppv_status build_impl(const int32_t *tokens, const int64_t *offsets, int64_t n_s
                 if (have_open) { node_hi[open] = (uint32_t)r; have_open = false; }
                 if (x_off[(size_t)r + 1] - x_off[(size_t)r] > d) {
                     if (node_tok.size() >= 0xFFFFFFFEull) return PPV_ERANGE;
-                    node_tok.push_back((uint32_t)x_tok[(size_t)(x_off[(size_t)r] + d)]);
+                    // the first row of a prefix's range is the prefix itself iff it ends at depth d
+                    uint32_t term = (x_off[(size_t)r + 1] - x_off[(size_t)r] == d + 1) ? PPV_NODE_TERMINAL : 0u;
+                    node_tok.push_back((uint32_t)x_tok[(size_t)(x_off[(size_t)r] + d)] | term);
                     node_lo.push_back((uint32_t)r);
                     node_hi.push_back(0u);
                     open = node_tok.size() - 1;
@@ -123,6 +125,32 @@ ppv_status build_impl(const int32_t *tokens, const int64_t *offsets, int64_t n_s
         child_off[G] = (uint32_t)G;
     }
 
+    // ---- heavy nodes: ready-made valid-set images and per-word child counts
+    const int n_words = (vocab + 31) / 32;
+    const uint32_t heavy_min = (uint32_t)std::min<int64_t>(vocab / 32, PPV_LIST_MAX);
+    std::vector<uint32_t> heavy_slot, heavy_bits, heavy_rank;
+    size_t n_heavy = 0;
+    for (size_t g = 0; g < G; g++) {
+        uint32_t cb = child_off[g], ce = child_off[g + 1];
+        if (ce - cb <= heavy_min) continue;
+        heavy_slot.resize(g + 1, PPV_NO_SLOT);
+        heavy_slot[g] = (uint32_t)n_heavy;
+        heavy_bits.resize((n_heavy + 1) * (size_t)n_words, 0u);
+        heavy_rank.resize((n_heavy + 1) * (size_t)n_words, 0u);
+        uint32_t *bits = heavy_bits.data() + n_heavy * (size_t)n_words;
+        uint32_t *rank = heavy_rank.data() + n_heavy * (size_t)n_words;
+        for (uint32_t c = cb; c < ce; c++) {
+            uint32_t v = node_tok[c] & PPV_NODE_TOKEN;
+            bits[v >> 5] |= 1u << (v & 31u);
+        }
+        uint32_t acc = 0;
+        for (int w = 0; w < n_words; w++) {
+            rank[w] = acc;
+            acc += (uint32_t)__builtin_popcount(bits[w]);
+        }
+        n_heavy++;
+    }
+
     // ---- upload
     ppv_status st;
     ix->device_bytes = 0;
@@ -130,16 +158,26 @@ ppv_status build_impl(const int32_t *tokens, const int64_t *offsets, int64_t n_s
     if ((st = upload(&ix->d_node_lo, node_lo, &ix->device_bytes)) != PPV_OK) return st;
     if ((st = upload(&ix->d_node_hi, node_hi, &ix->device_bytes)) != PPV_OK) return st;
     if ((st = upload(&ix->d_child_off, child_off, &ix->device_bytes)) != PPV_OK) return st;
+    if ((st = upload(&ix->d_heavy_slot, heavy_slot, &ix->device_bytes)) != PPV_OK) return st;
+    if ((st = upload(&ix->d_heavy_bits, heavy_bits, &ix->device_bytes)) != PPV_OK) return st;
+    if ((st = upload(&ix->d_heavy_rank, heavy_rank, &ix->device_bytes)) != PPV_OK) return st;
     if ((st = upload(&ix->d_x_tok, x_tok, &ix->device_bytes)) != PPV_OK) return st;
     if ((st = upload(&ix->d_x_off, x_off, &ix->device_bytes)) != PPV_OK) return st;
     ix->n_tokens = (int64_t)x_tok.size();
+    ix->n_heavy = (int64_t)n_heavy;
     ix->view.node_tok = ix->d_node_tok;
     ix->view.node_lo = ix->d_node_lo;
     ix->view.node_hi = ix->d_node_hi;
     ix->view.child_off = ix->d_child_off;
+    ix->view.heavy_slot = ix->d_heavy_slot;
+    ix->view.heavy_bits = ix->d_heavy_bits;
+    ix->view.heavy_rank = ix->d_heavy_rank;
+    ix->view.heavy_limit = (uint32_t)heavy_slot.size();
+    ix->view.heavy_min = heavy_min;
     ix->view.n_nodes = (uint32_t)G;
     ix->view.n_rows = (uint32_t)n_rows;
     ix->view.vocab = vocab;
+    ix->view.n_words = n_words;
     ix->view.l_max = l_max;
     return PPV_OK;
 }
@@ -150,6 +188,9 @@ void release(ppv_index *ix) {
     (void)hipFree(ix->d_node_lo);
     (void)hipFree(ix->d_node_hi);
     (void)hipFree(ix->d_child_off);
+    (void)hipFree(ix->d_heavy_slot);
+    (void)hipFree(ix->d_heavy_bits);
+    (void)hipFree(ix->d_heavy_rank);
     (void)hipFree(ix->d_x_tok);
     (void)hipFree(ix->d_x_off);
     delete ix;

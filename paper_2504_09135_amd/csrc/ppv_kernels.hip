@@ -1,12 +1,70 @@
-// Per-step kernels: prefix walk (rank range), next-token scatter (packed mask), masked
-// log-softmax + inverse-CDF sample, and the fused decode step.  gfx950, wave64.
+// Per-step kernels for gfx950 (wave64): prefix walk (rank range), next-token scatter (packed
+// mask), fused masked log-softmax + inverse-CDF sample, and the fused decode step.
+//
+// The logits row is the only large operand.  It is streamed exactly once, in tiles of 4 KB per
+// wavefront (four 16-byte loads per lane, issued before any index work so that they are in
+// flight while the prefix is located).  Each tile yields (max, sum of exp) relative to its own
+// maximum; tiles are combined afterwards, so every tile is independent and a row can be spread
+// over any number of wavefronts.  The valid set enters in one of two ways:
+//   list   at most PPV_LIST_MAX valid tokens: their logits are gathered (they were just streamed,
+//          so they come from cache), summed relative to their own maximum, and the sample is
+//          located by a scan over the list -- no per-element mask work in the stream;
+//   image  more valid tokens: a V-bit image is applied inside the stream (three more ALU
+//          operations per element) and the sample is located by re-reading one tile.
+// Nothing here is a dense contraction, so no MFMA; the bound is HBM bandwidth, with the exp
+// (quarter-rate v_exp_f32) as the main ALU cost.
 #include "ppv_internal.h"
 
 namespace {
 
 constexpr int WAVE = 64;
-constexpr int MASK_THREADS = 256;    // workgroup of the mask kernel: one row per workgroup
-constexpr int SAMPLE_THREADS = 256;  // workgroup of the sample kernel: one row per workgroup
+constexpr int MASK_THREADS = 256;
+constexpr int MAX_WAVES = 16;                 // wavefronts per row (workgroup of up to 1024 threads)
+constexpr int MAX_TILES = 256;                // PPV_MAX_VOCAB / 1024 (fp32 tiles are 1024 tokens)
+constexpr int MAX_SLICES = PPV_LIST_MAX / WAVE;
+constexpr float LOG2E = 1.44269504088896340736f;
+constexpr float LN2F = 0.693147180559945309417f;
+static_assert(PPV_MAX_VOCAB <= MAX_TILES * 1024, "tile bookkeeping too small");
+
+// ------------------------------------------------------------------------------------------
+// wave-level helpers (results are uniform over the wave)
+__device__ inline float wave_max(float x) {
+    for (int o = WAVE / 2; o > 0; o >>= 1) x = fmaxf(x, __shfl_xor(x, o, WAVE));
+    return x;
+}
+__device__ inline float wave_sum(float x) {
+    for (int o = WAVE / 2; o > 0; o >>= 1) x += __shfl_xor(x, o, WAVE);
+    return x;
+}
+__device__ inline double wave_sum(double x) {
+    for (int o = WAVE / 2; o > 0; o >>= 1) x += __shfl_xor(x, o, WAVE);
+    return x;
+}
+__device__ inline int wave_sum(int x) {
+    for (int o = WAVE / 2; o > 0; o >>= 1) x += __shfl_xor(x, o, WAVE);
+    return x;
+}
+__device__ inline double wave_incl_scan(double x, int lane) {
+    for (int o = 1; o < WAVE; o <<= 1) {
+        double y = __shfl_up(x, o, WAVE);
+        if (lane >= o) x += y;
+    }
+    return x;
+}
+__device__ inline int wave_incl_scan(int x, int lane) {
+    for (int o = 1; o < WAVE; o <<= 1) {
+        int y = __shfl_up(x, o, WAVE);
+        if (lane >= o) x += y;
+    }
+    return x;
+}
+__device__ inline float fast_exp2(float y) { return __builtin_amdgcn_exp2f(y); }  // v_exp_f32, 1 ulp
+// exp(d) for d <= 0 with the rounding of d*log2(e) compensated (used once per tile, not per token)
+__device__ inline float exp_scale(float d) {
+    float hi = d * LOG2E;
+    float lo = fmaf(d, LOG2E, -hi);
+    return fast_exp2(hi) * fmaf(lo, LN2F, 1.0f);
+}
 
 // ------------------------------------------------------------------------------------------
 // Prefix walk, one wavefront per prefix (Section 3.2 "Parallel Verification": the search that
@@ -14,23 +72,24 @@ constexpr int SAMPLE_THREADS = 256;  // workgroup of the sample kernel: one row 
 // the children of the current prefix per token, instead of log2|S| probes of whole rows).
 // All 64 lanes call it with the same arguments; every result is wave-uniform.
 struct Walk {
-    uint32_t node;   // the prefix's entry in the per-depth arrays (valid when found)
-    uint32_t lo, hi; // rank range in sorted S; lo == hi == insertion rank when not found
-    bool found;      // the prefix is a prefix of at least one member
+    uint32_t node;    // the prefix's entry in the per-depth arrays (meaningful when found)
+    uint32_t lo, hi;  // rank range in sorted S; lo == hi == insertion rank when not found
+    bool found;       // the prefix is a prefix of at least one member
+    bool member;      // the prefix itself is in S
 };
 
-__device__ inline uint32_t wave_lower_bound(const uint32_t *__restrict__ a, uint32_t begin, uint32_t end,
-                                            uint32_t key, int lane, bool *match) {
-    // first position in [begin, end) whose value is >= key; values are strictly increasing
+// first position in [begin, end) whose token is >= key; tokens are strictly increasing
+__device__ inline uint32_t wave_lower_bound(const uint32_t *__restrict__ tok, uint32_t begin, uint32_t end,
+                                            uint32_t key, int lane, uint32_t *hit) {
     uint32_t lo = begin, hi = end;
     while (hi - lo > (uint32_t)WAVE) {
         uint32_t n = hi - lo;
         uint32_t step = (n + WAVE - 1) / WAVE;
         uint32_t p = (uint32_t)(lane + 1) * step;
         if (p > n) p = n;
-        uint32_t v = a[lo + p - 1];                       // 64 pivots, the last one is a[hi-1]
-        int c = __popcll(__ballot(v < key));              // pivots below the key
-        if (c == WAVE) { lo = hi; break; }                // everything is below the key
+        uint32_t v = tok[lo + p - 1] & PPV_NODE_TOKEN;   // 64 pivots, the last one is tok[hi-1]
+        int c = __popcll(__ballot(v < key));             // pivots below the key
+        if (c == WAVE) { lo = hi; break; }               // everything is below the key
         uint32_t nlo = lo + (uint32_t)c * step;
         uint32_t nhi = lo + (uint32_t)(c + 1) * step;
         if (nhi > hi) nhi = hi;
@@ -38,9 +97,12 @@ __device__ inline uint32_t wave_lower_bound(const uint32_t *__restrict__ a, uint
         hi = nhi;
     }
     bool in = lo + (uint32_t)lane < hi;
-    uint32_t v = in ? a[lo + lane] : 0xFFFFFFFFu;
+    uint32_t raw = in ? tok[lo + lane] : 0xFFFFFFFFu;
+    uint32_t v = in ? (raw & PPV_NODE_TOKEN) : 0xFFFFFFFFu;
     int c = __popcll(__ballot(in && v < key));
-    *match = __ballot(in && v == key) != 0ull;
+    uint64_t eq = __ballot(in && v == key);
+    // the matching entry (token | terminal flag), or PPV_NO_SLOT (no real entry has all bits set)
+    *hit = eq ? (uint32_t)__shfl((int)raw, __ffsll((long long)eq) - 1, WAVE) : PPV_NO_SLOT;
     return lo + (uint32_t)c;
 }
 
@@ -50,55 +112,49 @@ __device__ inline Walk walk_prefix(const IndexView &ix, const int32_t *__restric
     w.lo = 0;
     w.hi = ix.n_rows;
     w.found = true;
+    w.member = false;
+    // the first 64 tokens in one coalesced load; token i is broadcast from lane i
+    int32_t mine = (lane < t) ? prefix[lane] : 0;
     for (int i = 0; i < t; i++) {
-        uint32_t key = (uint32_t)prefix[i];
+        uint32_t key = (uint32_t)((i < WAVE) ? __shfl(mine, i, WAVE) : prefix[i]);
         uint32_t cb = ix.child_off[w.node], ce = ix.child_off[w.node + 1];
-        bool match;
-        uint32_t j = wave_lower_bound(ix.node_tok, cb, ce, key, lane, &match);
-        if (!match) {
-            // every member below child j sorts before the prefix; if there is no such child the
-            // prefix sorts after the whole range of the current node
+        uint32_t hit;
+        uint32_t j = wave_lower_bound(ix.node_tok, cb, ce, key, lane, &hit);
+        if (hit == PPV_NO_SLOT || key > PPV_NODE_TOKEN) {
+            // every member below child j sorts before the prefix; with no such child the prefix
+            // sorts after the whole range of the current node
             uint32_t rank = (j < ce) ? ix.node_lo[j] : w.hi;
             w.lo = rank;
             w.hi = rank;
             w.found = false;
+            w.member = false;
             return w;
         }
         w.node = j;
         w.lo = ix.node_lo[j];
         w.hi = ix.node_hi[j];
+        w.member = (hit & PPV_NODE_TERMINAL) != 0u;
     }
     return w;
 }
 
-// the prefix itself is a member iff its first row is not the first row of its first child
-__device__ inline bool node_is_member(const IndexView &ix, const Walk &w, int t) {
-    if (!w.found || t == 0) return false;
-    uint32_t cb = ix.child_off[w.node], ce = ix.child_off[w.node + 1];
-    return cb == ce || ix.node_lo[cb] != w.lo;
+__device__ inline uint32_t heavy_slot_of(const IndexView &ix, uint32_t node) {
+    return node < ix.heavy_limit ? ix.heavy_slot[node] : PPV_NO_SLOT;
 }
 
 // ------------------------------------------------------------------------------------------
-// Next-token scatter: OR the children's tokens of the reached node into a bit image in LDS.
-// Called by the whole workgroup; img has n_words words and must already be zero.
-__device__ inline void scatter_children(const IndexView &ix, uint32_t node, uint32_t *img, int tid, int nthreads) {
-    uint32_t cb = ix.child_off[node], ce = ix.child_off[node + 1];
-    for (uint32_t i = cb + (uint32_t)tid; i < ce; i += (uint32_t)nthreads) {
-        uint32_t v = ix.node_tok[i];
-        atomicOr(&img[v >> 5], 1u << (v & 31u));
-    }
-}
-
+// ppv_next_token_mask: one workgroup per prefix.
 __global__ __launch_bounds__(MASK_THREADS) void mask_kernel(IndexView ix, const int32_t *__restrict__ prefixes,
                                                             int32_t stride, const int32_t *__restrict__ lens,
-                                                            uint32_t *__restrict__ mask, uint32_t *__restrict__ range_lo,
+                                                            uint32_t *__restrict__ mask,
+                                                            uint32_t *__restrict__ range_lo,
                                                             uint32_t *__restrict__ range_hi,
-                                                            uint8_t *__restrict__ member, int n_words) {
+                                                            uint8_t *__restrict__ member) {
     extern __shared__ __align__(16) uint32_t smem[];
-    uint32_t *img = smem;                 // [n_words]
-    uint32_t *bc = smem + n_words;        // [2]: node, found
+    const int n_words = ix.n_words;
+    uint32_t *img = smem;            // [n_words]
+    uint32_t *bc = smem + n_words;   // [2]: node, found
     const int b = blockIdx.x, tid = threadIdx.x, lane = tid & (WAVE - 1), wave = tid / WAVE;
-    for (int i = tid; i < n_words; i += MASK_THREADS) img[i] = 0u;
     if (wave == 0) {
         int t = lens[b];
         t = t < 0 ? 0 : (t > stride ? stride : t);
@@ -108,132 +164,533 @@ __global__ __launch_bounds__(MASK_THREADS) void mask_kernel(IndexView ix, const 
             bc[1] = w.found ? 1u : 0u;
             if (range_lo) range_lo[b] = w.lo;
             if (range_hi) range_hi[b] = w.hi;
-            if (member) member[b] = node_is_member(ix, w, t) ? 1 : 0;
+            if (member) member[b] = w.member ? 1 : 0;
         }
     }
     __syncthreads();
-    if (bc[1]) scatter_children(ix, bc[0], img, tid, MASK_THREADS);
-    __syncthreads();
+    const uint32_t node = bc[0];
+    const bool found = bc[1] != 0u;
     uint32_t *out = mask + (size_t)b * (size_t)n_words;
+    const uint32_t slot = found ? heavy_slot_of(ix, node) : PPV_NO_SLOT;
+    if (slot != PPV_NO_SLOT) {  // ready-made image: plain copy
+        const uint32_t *src = ix.heavy_bits + (size_t)slot * (size_t)n_words;
+        for (int i = tid; i < n_words; i += MASK_THREADS) out[i] = src[i];
+        return;
+    }
+    uint32_t cb = 0, ce = 0;
+    if (found) {
+        cb = ix.child_off[node];
+        ce = ix.child_off[node + 1];
+    }
+    if (cb == ce) {  // not in S, or a member without extensions
+        for (int i = tid; i < n_words; i += MASK_THREADS) out[i] = 0u;
+        return;
+    }
+    for (int i = tid; i < n_words; i += MASK_THREADS) img[i] = 0u;
+    __syncthreads();
+    for (uint32_t i = cb + (uint32_t)tid; i < ce; i += MASK_THREADS) {
+        uint32_t v = ix.node_tok[i] & PPV_NODE_TOKEN;
+        atomicOr(&img[v >> 5], 1u << (v & 31u));
+    }
+    __syncthreads();
     for (int i = tid; i < n_words; i += MASK_THREADS) out[i] = img[i];
 }
 
 // ------------------------------------------------------------------------------------------
-// Masked log-softmax + inverse-CDF sample of one row by one workgroup.
-template <typename T> __device__ inline float load_logit(const T *p, int v);
-template <> __device__ inline float load_logit<float>(const float *p, int v) { return p[v]; }
-template <> __device__ inline float load_logit<uint16_t>(const uint16_t *p, int v) {
-    return __uint_as_float(((uint32_t)p[v]) << 16);  // bf16 -> fp32 is exact
-}
-
-struct RowResult {
-    int32_t id;
-    float logZ_valid, logZ_all;
+// Tiles.  A tile is what one wavefront loads with four 16-byte loads per lane: 2048 bf16 or 1024
+// fp32 tokens.  Load j of lane l holds the EPL consecutive tokens starting at
+// tile*TILE + j*64*EPL + l*EPL, so token order inside a tile is (j, lane, k).
+template <typename T> struct Elem;
+template <> struct Elem<float> {
+    static constexpr int EPL = 4;  // tokens per 16-byte load
+    __device__ static inline void unpack(const uint4 &r, float x[4]) {
+        x[0] = __uint_as_float(r.x); x[1] = __uint_as_float(r.y);
+        x[2] = __uint_as_float(r.z); x[3] = __uint_as_float(r.w);
+    }
+    __device__ static inline uint32_t pad() { return 0xFF800000u; }  // -inf
+};
+template <> struct Elem<uint16_t> {  // bf16: widening to fp32 is exact
+    static constexpr int EPL = 8;
+    __device__ static inline void unpack(const uint4 &r, float x[8]) {
+        x[0] = __uint_as_float(r.x << 16); x[1] = __uint_as_float(r.x & 0xFFFF0000u);
+        x[2] = __uint_as_float(r.y << 16); x[3] = __uint_as_float(r.y & 0xFFFF0000u);
+        x[4] = __uint_as_float(r.z << 16); x[5] = __uint_as_float(r.z & 0xFFFF0000u);
+        x[6] = __uint_as_float(r.w << 16); x[7] = __uint_as_float(r.w & 0xFFFF0000u);
+    }
+    __device__ static inline uint32_t pad() { return 0xFF80FF80u; }  // two bf16 -inf
+};
+template <typename T> struct TileGeom {
+    static constexpr int EPL = Elem<T>::EPL;
+    static constexpr int PER_LOAD = WAVE * EPL;   // tokens covered by one load of the wave
+    static constexpr int TILE = 4 * PER_LOAD;     // tokens per tile
+    static constexpr int WORDS = TILE / 32;       // mask words per tile
+    static constexpr int LANES_PER_WORD = 32 / EPL;
 };
 
-template <typename Op>
-__device__ inline double block_reduce(double x, double *red, int tid, Op op) {
-    // wave reduction by shuffles, then across the waves through LDS; fixed order => deterministic
-    for (int o = WAVE / 2; o > 0; o >>= 1) x = op(x, __shfl_xor(x, o, WAVE));
-    __syncthreads();
-    if ((tid & (WAVE - 1)) == 0) red[tid / WAVE] = x;
-    __syncthreads();
-    double r = red[0];
-    for (int w = 1; w < SAMPLE_THREADS / WAVE; w++) r = op(r, red[w]);
-    return r;
-}
+struct RawTile { uint4 r[4]; };
 
-// mask_bit(v) tells whether token v is valid; scratch: SAMPLE_THREADS doubles + 8 doubles + 4 ints
-template <typename T, typename MaskFn>
-__device__ inline RowResult sample_row(const T *__restrict__ row, int V, MaskFn mask_bit, float u, double *scratch,
-                                       int tid) {
-    double *red = scratch;                       // [SAMPLE_THREADS/WAVE]
-    double *chunk_sum = scratch + 8;             // [SAMPLE_THREADS]
-    int *ibc = (int *)(scratch + 8 + SAMPLE_THREADS);
-    auto fmaxd = [](double a, double b) { return a > b ? a : b; };
-    auto addd = [](double a, double b) { return a + b; };
-
-    // pass 1: maxima over all tokens and over valid tokens
-    float m_all = -INFINITY, m_val = -INFINITY;
-    for (int v = tid; v < V; v += SAMPLE_THREADS) {
-        float l = load_logit<T>(row, v);
-        m_all = fmaxf(m_all, l);
-        if (mask_bit(v)) m_val = fmaxf(m_val, l);
-    }
-    m_all = (float)block_reduce((double)m_all, red, tid, fmaxd);
-    m_val = (float)block_reduce((double)m_val, red, tid, fmaxd);
-
-    // pass 2: sum over all tokens; valid weights are summed per contiguous chunk in token order
-    double z_all = 0.0;
-    for (int v = tid; v < V; v += SAMPLE_THREADS) z_all += (double)expf(load_logit<T>(row, v) - m_all);
-    z_all = block_reduce(z_all, red, tid, addd);
-
-    RowResult r;
-    r.logZ_all = m_all + (float)log(z_all);
-    if (m_val == -INFINITY) {  // empty mask (or every valid logit is -inf)
-        r.id = -1;
-        r.logZ_valid = -INFINITY;
-        return r;
-    }
-    const int chunk = (V + SAMPLE_THREADS - 1) / SAMPLE_THREADS;
-    const int v0 = tid * chunk, v1 = min(V, v0 + chunk);
-    double mine = 0.0;
-    for (int v = v0; v < v1; v++)
-        if (mask_bit(v)) mine += (double)expf(load_logit<T>(row, v) - m_val);
-    chunk_sum[tid] = mine;
-    __syncthreads();
-    if (tid == 0) {
-        double z = 0.0;
-        for (int i = 0; i < SAMPLE_THREADS; i++) z += chunk_sum[i];
-        double tau = (double)u * z, c = 0.0;
-        int pick = -1, last = -1;
-        for (int i = 0; i < SAMPLE_THREADS; i++) {
-            if (chunk_sum[i] > 0.0) last = i;
-            if (c + chunk_sum[i] > tau) { pick = i; break; }
-            c += chunk_sum[i];
-        }
-        if (pick < 0) { pick = last; c = -1.0; }  // rounding: take the last positive chunk's last token
-        red[0] = z;
-        red[1] = tau;
-        red[2] = c;
-        ibc[0] = pick;
-    }
-    __syncthreads();
-    const double z_val = red[0], tau = red[1], base = red[2];
-    const int pick = ibc[0];
-    __syncthreads();
-    if (tid == pick) {
-        double c = base < 0.0 ? 0.0 : base;
-        int id = -1, last = -1;
-        for (int v = v0; v < v1; v++) {
-            if (!mask_bit(v)) continue;
-            double w = (double)expf(load_logit<T>(row, v) - m_val);
-            c += w;
-            if (w > 0.0) last = v;
-            if (base >= 0.0 && c > tau) { id = v; break; }
-        }
-        ibc[1] = id >= 0 ? id : last;
-    }
-    __syncthreads();
-    r.id = ibc[1];
-    r.logZ_valid = (float)(((double)m_val + log(z_val)) - ((double)m_all + log(z_all)));
-    return r;
-}
-
-constexpr int SAMPLE_SCRATCH_DOUBLES = 8 + SAMPLE_THREADS + 2;
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 template <typename T>
-__global__ __launch_bounds__(SAMPLE_THREADS) void sample_kernel(const T *__restrict__ logits, int64_t row_stride,
-                                                                const uint32_t *__restrict__ mask,
-                                                                const float *__restrict__ uniforms, int V, int n_words,
-                                                                int32_t *__restrict__ ids,
-                                                                float *__restrict__ logZ_valid,
-                                                                float *__restrict__ logZ_all) {
-    __shared__ double scratch[SAMPLE_SCRATCH_DOUBLES];
-    const int b = blockIdx.x, tid = threadIdx.x;
+__device__ inline void load_tile(const T *__restrict__ row, int V, int tile, int lane, RawTile &rt) {
+    using G = TileGeom<T>;
+    const int base = tile * G::TILE + lane * G::EPL;
+    if ((tile + 1) * G::TILE <= V) {  // wave-uniform: whole tile inside the row
+#pragma unroll
+        for (int j = 0; j < 4; j++) {
+            u32x4 v = __builtin_nontemporal_load((const u32x4 *)(row + base + j * G::PER_LOAD));
+            rt.r[j] = make_uint4(v.x, v.y, v.z, v.w);
+        }
+    } else {  // ragged tail: never touch memory at or beyond token V; missing tokens are -inf
+#pragma unroll
+        for (int j = 0; j < 4; j++) {
+            const int g = base + j * G::PER_LOAD;
+            if (g + G::EPL <= V) {
+                rt.r[j] = *(const uint4 *)(row + g);
+            } else {
+                uint32_t w[4] = {Elem<T>::pad(), Elem<T>::pad(), Elem<T>::pad(), Elem<T>::pad()};
+                if (sizeof(T) == 4) {
+                    for (int k = 0; k < 4; k++)
+                        if (g + k < V) w[k] = ((const uint32_t *)row)[g + k];
+                } else {
+                    for (int k = 0; k < 8; k++)
+                        if (g + k < V) {
+                            uint32_t h = ((const uint16_t *)row)[g + k];
+                            w[k >> 1] = (k & 1) ? ((w[k >> 1] & 0x0000FFFFu) | (h << 16))
+                                                : ((w[k >> 1] & 0xFFFF0000u) | h);
+                        }
+                }
+                rt.r[j] = make_uint4(w[0], w[1], w[2], w[3]);
+            }
+        }
+    }
+}
+
+// word wi of a V-bit image, with bits at positions >= V cleared (0 beyond the image)
+__device__ inline uint32_t image_word(const uint32_t *__restrict__ image, int wi, int V) {
+    const int n_words = (V + 31) / 32;
+    if (wi >= n_words) return 0u;
+    uint32_t w = image[wi];
+    if (wi == n_words - 1 && (V & 31)) w &= (1u << (V & 31)) - 1u;
+    return w;
+}
+
+// mask bits of this lane's EPL tokens of load j, from the tile's mask words (lane l < WORDS holds word l)
+template <typename T> __device__ inline uint32_t lane_bits(uint32_t tile_word, int j, int lane) {
+    using G = TileGeom<T>;
+    uint32_t w = (uint32_t)__shfl((int)tile_word, j * (G::WORDS / 4) + lane / G::LANES_PER_WORD, WAVE);
+    return (w >> ((lane % G::LANES_PER_WORD) * G::EPL)) & ((1u << G::EPL) - 1u);
+}
+
+// Statistics of one tile: its maximum m, sum_all = sum exp(x - m), and (IMAGE) sum_val over valid tokens.
+template <typename T, bool IMAGE>
+__device__ inline void tile_stats(const RawTile &rt, uint32_t tile_word, int lane, float &m_out, float &zall_out,
+                                  float &zval_out) {
+    using G = TileGeom<T>;
+    float x[4][G::EPL];
+    float mx = -INFINITY;
+#pragma unroll
+    for (int j = 0; j < 4; j++) {
+        Elem<T>::unpack(rt.r[j], x[j]);
+#pragma unroll
+        for (int k = 0; k < G::EPL; k++) mx = fmaxf(mx, x[j][k]);
+    }
+    mx = wave_max(mx);
+    m_out = mx;
+    if (mx == -INFINITY) {  // nothing but -inf in this tile
+        zall_out = 0.f;
+        zval_out = 0.f;
+        return;
+    }
+    // exp(x - m) = 2^(x*c - m*c); m*c is rounded once (mc), its residual is folded into the tile sums
+    const float mc = mx * LOG2E;
+    const float resid = fmaf(mx, LOG2E, -mc);
+    float zall = 0.f, zval = 0.f;
+#pragma unroll
+    for (int j = 0; j < 4; j++) {
+        uint32_t bits = 0;
+        if (IMAGE) bits = lane_bits<T>(tile_word, j, lane);
+#pragma unroll
+        for (int k = 0; k < G::EPL; k++) {
+            float e = fast_exp2(fmaf(x[j][k], LOG2E, -mc));
+            zall += e;
+            if (IMAGE) {
+                uint32_t keep = (uint32_t)(-(int32_t)((bits >> k) & 1u));
+                zval += __uint_as_float(__float_as_uint(e) & keep);
+            }
+        }
+    }
+    const float fix = fast_exp2(-resid);
+    zall_out = wave_sum(zall) * fix;
+    zval_out = IMAGE ? wave_sum(zval) * fix : 0.f;
+}
+
+// Rare path of the image mode (the valid tokens lie far below the row maximum, so sums relative
+// to the tile maxima would lose them): maximum over the valid tokens of a tile ...
+template <typename T>
+__device__ inline float tile_valid_max(const RawTile &rt, uint32_t tile_word, int lane) {
+    using G = TileGeom<T>;
+    float mv = -INFINITY;
+#pragma unroll
+    for (int j = 0; j < 4; j++) {
+        float x[G::EPL];
+        Elem<T>::unpack(rt.r[j], x);
+        const uint32_t bits = lane_bits<T>(tile_word, j, lane);
+#pragma unroll
+        for (int k = 0; k < G::EPL; k++)
+            if ((bits >> k) & 1u) mv = fmaxf(mv, x[k]);
+    }
+    return wave_max(mv);
+}
+// ... and the valid sum of a tile relative to a given reference (finite)
+template <typename T>
+__device__ inline float tile_valid_sum(const RawTile &rt, uint32_t tile_word, int lane, float ref) {
+    using G = TileGeom<T>;
+    const float mc = ref * LOG2E;
+    const float fix = fast_exp2(-fmaf(ref, LOG2E, -mc));
+    float z = 0.f;
+#pragma unroll
+    for (int j = 0; j < 4; j++) {
+        float x[G::EPL];
+        Elem<T>::unpack(rt.r[j], x);
+        const uint32_t bits = lane_bits<T>(tile_word, j, lane);
+#pragma unroll
+        for (int k = 0; k < G::EPL; k++)
+            if ((bits >> k) & 1u) z += fast_exp2(fmaf(x[k], LOG2E, -mc));
+    }
+    return wave_sum(z) * fix;
+}
+
+// Locate the sample inside one tile (IMAGE path).  target is the cumulative valid weight to exceed,
+// in units of exp(x - m_tile).  Returns the token id (wave-uniform), or -1 if the tile has no valid
+// token with positive weight.  When rounding lets no token exceed the target, the last valid token
+// with positive weight is returned.
+template <typename T>
+__device__ inline int locate_in_tile(const RawTile &rt, uint32_t tile_word, int tile, int lane, float m,
+                                     double target) {
+    using G = TileGeom<T>;
+    const float mc = m * LOG2E;
+    const float fix = fast_exp2(-fmaf(m, LOG2E, -mc));
+    double before = 0.0;  // valid weight of the loads already passed
+    int last_valid = -1;
+    for (int j = 0; j < 4; j++) {
+        float x[G::EPL], e[G::EPL];
+        Elem<T>::unpack(rt.r[j], x);
+        const uint32_t bits = lane_bits<T>(tile_word, j, lane);
+        float grp = 0.f;
+        int my_last = -1;
+#pragma unroll
+        for (int k = 0; k < G::EPL; k++) {
+            e[k] = ((bits >> k) & 1u) ? fast_exp2(fmaf(x[k], LOG2E, -mc)) * fix : 0.f;
+            grp += e[k];
+            if (e[k] > 0.f) my_last = k;
+        }
+        const double incl = before + wave_incl_scan((double)grp, lane);
+        const uint64_t cross = __ballot(incl > target);
+        const int first_tok = tile * G::TILE + j * G::PER_LOAD;
+        if (cross) {
+            const int l = __ffsll((long long)cross) - 1;
+            int id = -1;
+            if (lane == l) {
+                double c = incl - (double)grp;
+                for (int k = 0; k < G::EPL; k++) {
+                    c += (double)e[k];
+                    if (e[k] > 0.f && c > target) { id = k; break; }
+                }
+                if (id < 0) id = my_last;  // rounding inside the group
+                id += first_tok + lane * G::EPL;
+            }
+            return __shfl(id, l, WAVE);
+        }
+        const uint64_t have = __ballot(my_last >= 0);
+        if (have) {
+            const int l = 63 - __clzll((long long)have);
+            last_valid = __shfl(first_tok + lane * G::EPL + my_last, l, WAVE);
+        }
+        before = __shfl(incl, WAVE - 1, WAVE);
+    }
+    return last_valid;
+}
+
+// ------------------------------------------------------------------------------------------
+// One row by one workgroup of `nw` wavefronts.
+struct RowShared {
+    float tile_m[MAX_TILES];
+    float tile_zall[MAX_TILES];
+    float tile_zval[MAX_TILES];
+    float tile_ref[MAX_TILES];         // what tile_zval is relative to (the tile maximum, or the valid maximum)
+    uint32_t list_tok[PPV_LIST_MAX];   // valid tokens in increasing order (list path); bit 31 may carry a flag
+    float list_e[PPV_LIST_MAX];        // exp(l - slice max) per listed token
+    float slice_m[MAX_SLICES];
+    float slice_z[MAX_SLICES];
+    int tile_cnt[MAX_TILES];           // valid tokens per tile (mask -> list conversion)
+    int bc_i[8];
+    float bc_f[4];
+};
+
+struct RowOut {
+    int32_t id;        // sampled token or -1
+    int32_t pos;       // list path: position of the sampled token in the list, else -1
+    float logZ_valid;
+    float logZ_all;
+};
+
+enum ValidMode { VALID_NONE = 0, VALID_LIST = 1, VALID_IMAGE = 2 };
+
+// Streams the row and samples.  Called by every thread of the workgroup with uniform arguments.
+//   first        this wave's first tile, already loaded (the wave owns tiles wave, wave+nw, ...)
+//   mode         VALID_LIST: sh.list_tok[0..n_list) holds the valid tokens (in LDS, barrier done)
+//                VALID_IMAGE: image (global memory, V bits) is the valid set
+//                VALID_NONE: the valid set is empty
+template <typename T>
+__device__ inline RowOut row_sample(const T *__restrict__ row, int V, const RawTile &first, int mode, int n_list,
+                                    const uint32_t *__restrict__ image, float u, RowShared &sh, int tid, int nw) {
+    using G = TileGeom<T>;
+    const int lane = tid & (WAVE - 1), wave = tid / WAVE;
+    const int nt = (V + G::TILE - 1) / G::TILE;
+
+    // ---- stream: every tile once
+    RawTile rt = first;
+    for (int k = wave; k < nt; k += nw) {
+        if (k != wave) load_tile<T>(row, V, k, lane, rt);
+        float m, zall, zval;
+        if (mode == VALID_IMAGE) {
+            const uint32_t word = (lane < G::WORDS) ? image_word(image, k * G::WORDS + lane, V) : 0u;
+            tile_stats<T, true>(rt, word, lane, m, zall, zval);
+        } else {
+            tile_stats<T, false>(rt, 0u, lane, m, zall, zval);
+        }
+        if (lane == 0) {
+            sh.tile_m[k] = m;
+            sh.tile_zall[k] = zall;
+            sh.tile_zval[k] = zval;
+            sh.tile_ref[k] = m;
+        }
+    }
+    // ---- list path: gather the listed tokens' logits (just streamed: cache hits), 64 per slice
+    const int ns = (n_list + WAVE - 1) / WAVE;
+    if (mode == VALID_LIST) {
+        for (int s = wave; s < ns; s += nw) {
+            const int i = s * WAVE + lane;
+            float x = -INFINITY;
+            if (i < n_list) {
+                const uint32_t v = sh.list_tok[i] & PPV_NODE_TOKEN;
+                if (sizeof(T) == 4) x = __uint_as_float(((const uint32_t *)row)[v]);
+                else x = __uint_as_float(((uint32_t)((const uint16_t *)row)[v]) << 16);
+            }
+            const float m = wave_max(x);
+            float e = 0.f;
+            if (m != -INFINITY) {
+                const float mc = m * LOG2E;
+                const float fix = fast_exp2(-fmaf(m, LOG2E, -mc));
+                e = fast_exp2(fmaf(x, LOG2E, -mc)) * fix;   // x = -inf gives 0
+            }
+            if (i < n_list) sh.list_e[i] = e;
+            const float z = wave_sum(e);
+            if (lane == 0) {
+                sh.slice_m[s] = m;
+                sh.slice_z[s] = z;
+            }
+        }
+    }
+    __syncthreads();
+
+    // ---- combine (every wave computes the same row totals from LDS; cheap, and saves a broadcast)
+    float M = -INFINITY;
+    for (int k = lane; k < nt; k += WAVE) M = fmaxf(M, sh.tile_m[k]);
+    M = wave_max(M);
+    double za = 0.0, zv = 0.0;
+    for (int k = lane; k < nt; k += WAVE) {
+        const float m = sh.tile_m[k];
+        if (m != -INFINITY) {
+            const double sc = (double)exp_scale(m - M);
+            za += (double)sh.tile_zall[k] * sc;
+            zv += (double)sh.tile_zval[k] * sc;
+        }
+    }
+    za = wave_sum(za);
+    zv = wave_sum(zv);
+    float R = M;  // reference of the valid sums of the image path
+
+    // ---- image path, rare case: the valid mass is below 2^-18 of the row's largest term, so sums
+    // relative to the tile maxima are inaccurate or have underflowed.  Redo the valid sums relative
+    // to the maximum over valid tokens (the row is re-read; it is still in cache).
+    if (mode == VALID_IMAGE && zv < 3.814697265625e-06) {
+        __syncthreads();  // everyone has read tile_zval
+        for (int k = wave; k < nt; k += nw) {
+            load_tile<T>(row, V, k, lane, rt);
+            const uint32_t word = (lane < G::WORDS) ? image_word(image, k * G::WORDS + lane, V) : 0u;
+            const float mv = tile_valid_max<T>(rt, word, lane);
+            if (lane == 0) sh.tile_ref[k] = mv;
+        }
+        __syncthreads();
+        float Mv = -INFINITY;
+        for (int k = lane; k < nt; k += WAVE) Mv = fmaxf(Mv, sh.tile_ref[k]);
+        Mv = wave_max(Mv);
+        __syncthreads();  // everyone has read the per-tile valid maxima
+        if (Mv != -INFINITY) {
+            for (int k = wave; k < nt; k += nw) {
+                load_tile<T>(row, V, k, lane, rt);
+                const uint32_t word = (lane < G::WORDS) ? image_word(image, k * G::WORDS + lane, V) : 0u;
+                const float z = tile_valid_sum<T>(rt, word, lane, Mv);
+                if (lane == 0) {
+                    sh.tile_zval[k] = z;
+                    sh.tile_ref[k] = Mv;
+                }
+            }
+        } else {
+            for (int k = tid; k < nt; k += nw * WAVE) sh.tile_zval[k] = 0.f;
+        }
+        __syncthreads();
+        R = Mv;
+        zv = 0.0;
+        for (int k = lane; k < nt; k += WAVE) zv += (double)sh.tile_zval[k];
+        zv = wave_sum(zv);
+    }
+
+    // ---- locate: wave 0
+    if (wave == 0) {
+        const double log_za = log(za);
+        int id = -1, pos = -1;
+        float lzv = -INFINITY;
+        if (mode == VALID_IMAGE) {
+            if (zv > 0.0) {
+                lzv = (float)(((double)R - (double)M) + log(zv) - log_za);
+                const double tau = (double)u * zv;
+                // first tile whose cumulative valid weight exceeds tau
+                double carry = 0.0, before = 0.0;
+                int kstar = -1, klast = -1;
+                for (int k0 = 0; k0 < nt && kstar < 0; k0 += WAVE) {
+                    const int k = k0 + lane;
+                    double w = 0.0;
+                    if (k < nt && sh.tile_zval[k] > 0.f)
+                        w = (double)sh.tile_zval[k] * (double)exp_scale(sh.tile_ref[k] - R);
+                    const double incl = carry + wave_incl_scan(w, lane);
+                    const uint64_t cross = __ballot(incl > tau);
+                    const uint64_t have = __ballot(w > 0.0);
+                    if (cross) {
+                        const int l = __ffsll((long long)cross) - 1;
+                        kstar = k0 + l;
+                        before = __shfl(incl - w, l, WAVE);
+                    } else if (have) {
+                        klast = k0 + 63 - __clzll((long long)have);
+                    }
+                    carry = __shfl(incl, WAVE - 1, WAVE);
+                }
+                double target;
+                int kt;
+                if (kstar >= 0) {
+                    kt = kstar;
+                    target = (tau - before) / (double)exp_scale(sh.tile_ref[kt] - R);
+                } else {  // rounding: the total never exceeded tau; take the last valid token
+                    kt = klast;
+                    target = INFINITY;
+                }
+                RawTile lt;
+                load_tile<T>(row, V, kt, lane, lt);
+                const uint32_t word = (lane < G::WORDS) ? image_word(image, kt * G::WORDS + lane, V) : 0u;
+                id = locate_in_tile<T>(lt, word, kt, lane, sh.tile_ref[kt], target);
+            }
+        } else if (mode == VALID_LIST) {
+            float Mv = -INFINITY;
+            if (lane < ns) Mv = sh.slice_m[lane];
+            Mv = wave_max(Mv);
+            if (Mv != -INFINITY) {
+                double w = 0.0, sc = 0.0;
+                if (lane < ns && sh.slice_m[lane] != -INFINITY) {
+                    sc = (double)exp_scale(sh.slice_m[lane] - Mv);
+                    w = (double)sh.slice_z[lane] * sc;
+                }
+                const double incl = wave_incl_scan(w, lane);
+                const double zvl = __shfl(incl, WAVE - 1, WAVE);
+                lzv = (float)(((double)Mv - (double)M) + log(zvl) - log_za);
+                const double tau = (double)u * zvl;
+                const uint64_t cross = __ballot(incl > tau);
+                const uint64_t have = __ballot(w > 0.0);
+                int s;
+                double target;
+                if (cross) {
+                    s = __ffsll((long long)cross) - 1;
+                    target = (tau - __shfl(incl - w, s, WAVE)) / __shfl(sc, s, WAVE);
+                } else {
+                    s = 63 - __clzll((long long)have);
+                    target = INFINITY;
+                }
+                const int i = s * WAVE + lane;
+                const float e = (i < n_list) ? sh.list_e[i] : 0.f;
+                const double ic = wave_incl_scan((double)e, lane);
+                const uint64_t c2 = __ballot(e > 0.f && ic > target);
+                const uint64_t h2 = __ballot(e > 0.f);
+                const int l = c2 ? __ffsll((long long)c2) - 1 : 63 - __clzll((long long)h2);
+                pos = s * WAVE + l;
+                id = (int)(sh.list_tok[pos] & PPV_NODE_TOKEN);
+            }
+        }
+        if (lane == 0) {
+            sh.bc_i[0] = id;
+            sh.bc_i[1] = pos;
+            sh.bc_f[0] = lzv;
+            sh.bc_f[1] = (float)((double)M + log_za);
+        }
+    }
+    __syncthreads();
+    RowOut out;
+    out.id = sh.bc_i[0];
+    out.pos = sh.bc_i[1];
+    out.logZ_valid = sh.bc_f[0];
+    out.logZ_all = sh.bc_f[1];
+    return out;
+}
+
+// ------------------------------------------------------------------------------------------
+// constrained_sample: the valid set arrives as a packed mask.  Count its bits; a small set is
+// unpacked into the token list, a large one is used as an image.
+template <typename T>
+__global__ __launch_bounds__(MAX_WAVES *WAVE) void sample_kernel(const T *__restrict__ logits, int64_t row_stride,
+                                                                  const uint32_t *__restrict__ mask,
+                                                                  const float *__restrict__ uniforms, int V,
+                                                                  int n_words, int list_max,
+                                                                  int32_t *__restrict__ ids,
+                                                                  float *__restrict__ logZ_valid,
+                                                                  float *__restrict__ logZ_all) {
+    using G = TileGeom<T>;
+    __shared__ RowShared sh;
+    const int b = blockIdx.x, tid = threadIdx.x, lane = tid & (WAVE - 1), wave = tid / WAVE;
+    const int nw = blockDim.x / WAVE;
+    const T *row = logits + (size_t)b * (size_t)row_stride;
     const uint32_t *mrow = mask + (size_t)b * (size_t)n_words;
-    auto bit = [=](int v) { return (mrow[v >> 5] >> (v & 31)) & 1u; };
-    RowResult r = sample_row<T>(logits + (size_t)b * (size_t)row_stride, V, bit, uniforms[b], scratch, tid);
+    const int nt = (V + G::TILE - 1) / G::TILE;
+    RawTile first;
+    if (wave < nt) load_tile<T>(row, V, wave, lane, first);   // in flight during the mask work
+
+    // bits per tile (a tile's mask words are consecutive: one word per lane)
+    for (int k = wave; k < nt; k += nw) {
+        const uint32_t w = (lane < G::WORDS) ? image_word(mrow, k * G::WORDS + lane, V) : 0u;
+        const int c = wave_sum((int)__popc(w));
+        if (lane == 0) sh.tile_cnt[k] = c;
+    }
+    __syncthreads();
+    int total = 0;
+    for (int k = lane; k < nt; k += WAVE) total += sh.tile_cnt[k];
+    total = wave_sum(total);
+    const int mode = total == 0 ? VALID_NONE : (total <= list_max ? VALID_LIST : VALID_IMAGE);
+    if (mode == VALID_LIST) {
+        for (int k = wave; k < nt; k += nw) {
+            int base = 0;  // valid tokens in the tiles before k
+            for (int q = lane; q < k; q += WAVE) base += sh.tile_cnt[q];
+            base = wave_sum(base);
+            const int wi = k * G::WORDS + lane;
+            uint32_t w = (lane < G::WORDS) ? image_word(mrow, wi, V) : 0u;
+            int at = base + wave_incl_scan((int)__popc(w), lane) - (int)__popc(w);
+            while (w) {
+                const int bit = __ffs((int)w) - 1;
+                sh.list_tok[at++] = (uint32_t)(wi * 32 + bit);
+                w &= w - 1u;
+            }
+        }
+        __syncthreads();
+    }
+    RowOut r = row_sample<T>(row, V, first, mode, mode == VALID_LIST ? total : 0, mrow, uniforms[b], sh, tid, nw);
     if (tid == 0) {
         ids[b] = r.id;
         logZ_valid[b] = r.logZ_valid;
@@ -242,65 +699,73 @@ __global__ __launch_bounds__(SAMPLE_THREADS) void sample_kernel(const T *__restr
 }
 
 // ------------------------------------------------------------------------------------------
-// Fused decode step: walk + scatter into LDS + sample + append + membership of the extended row.
+// ppv_decode_step: locate the prefix, take its children as the valid set (list, or the ready-made
+// image of a heavy node), stream + sample, append, and report whether the extended row is in S.
 template <typename T>
-__global__ __launch_bounds__(SAMPLE_THREADS) void decode_step_kernel(
+__global__ __launch_bounds__(MAX_WAVES *WAVE) void decode_step_kernel(
     IndexView ix, int32_t *__restrict__ prefixes, int32_t stride, int32_t *__restrict__ lens,
     uint8_t *__restrict__ active, const T *__restrict__ logits, int64_t row_stride,
-    const float *__restrict__ uniforms, int n_words, int32_t *__restrict__ ids, float *__restrict__ logZ_valid,
+    const float *__restrict__ uniforms, int32_t *__restrict__ ids, float *__restrict__ logZ_valid,
     float *__restrict__ logx) {
-    extern __shared__ __align__(16) uint32_t smem[];
-    uint32_t *img = smem;                                        // [n_words]
-    uint32_t *bc = smem + n_words;                               // [4]
-    double *scratch = (double *)(smem + ((n_words + 4 + 1) & ~1));  // 8-byte aligned
+    using G = TileGeom<T>;
+    __shared__ RowShared sh;
     const int b = blockIdx.x, tid = threadIdx.x, lane = tid & (WAVE - 1), wave = tid / WAVE;
-    if (!active[b]) return;                                      // uniform for the workgroup
+    const int nw = blockDim.x / WAVE;
+    if (!active[b]) return;  // uniform for the workgroup
+    const int V = ix.vocab;
+    const T *row = logits + (size_t)b * (size_t)row_stride;
+    const int nt = (V + G::TILE - 1) / G::TILE;
+    RawTile first;
+    if (wave < nt) load_tile<T>(row, V, wave, lane, first);   // in flight during the walk
     int t = lens[b];
     t = t < 0 ? 0 : (t > stride ? stride : t);
-    for (int i = tid; i < n_words; i += SAMPLE_THREADS) img[i] = 0u;
     if (wave == 0) {
         Walk w = walk_prefix(ix, prefixes + (size_t)b * (size_t)stride, t, lane);
         if (lane == 0) {
-            bc[0] = w.node;
-            bc[1] = w.found ? 1u : 0u;
+            sh.bc_i[4] = (int)w.node;
+            sh.bc_i[5] = w.found ? 1 : 0;
         }
     }
     __syncthreads();
-    const uint32_t node = bc[0];
-    const bool found = bc[1] != 0u;
-    if (found) scatter_children(ix, node, img, tid, SAMPLE_THREADS);
-    __syncthreads();
-    auto bit = [=](int v) { return (img[v >> 5] >> (v & 31)) & 1u; };
-    RowResult r = sample_row<T>(logits + (size_t)b * (size_t)row_stride, ix.vocab, bit, uniforms[b], scratch, tid);
-    const bool room = t < stride;
-    if (wave == 0) {
-        bool done = true;  // no valid token or no room: the row cannot continue
+    const uint32_t node = (uint32_t)sh.bc_i[4];
+    const bool found = sh.bc_i[5] != 0;
+    uint32_t cb = 0, ce = 0;
+    if (found) {
+        cb = ix.child_off[node];
+        ce = ix.child_off[node + 1];
+    }
+    const int nchild = (int)(ce - cb);
+    const uint32_t slot = found ? heavy_slot_of(ix, node) : PPV_NO_SLOT;
+    const int mode = nchild == 0 ? VALID_NONE : (slot != PPV_NO_SLOT ? VALID_IMAGE : VALID_LIST);
+    const uint32_t *image = ix.heavy_bits + (size_t)(slot != PPV_NO_SLOT ? slot : 0) * (size_t)ix.n_words;
+    if (mode == VALID_LIST) {  // children are sorted by token: the list is ready as it is
+        for (int i = tid; i < nchild; i += nw * WAVE) sh.list_tok[i] = ix.node_tok[cb + i];
+        __syncthreads();
+    }
+    RowOut r = row_sample<T>(row, V, first, mode, mode == VALID_LIST ? nchild : 0, image, uniforms[b], sh, tid, nw);
+    if (tid == 0) {
+        const bool room = t < stride;
         int32_t id = -1;
+        bool done = true;  // no valid token or no room: the row cannot continue
         if (r.id >= 0 && room) {
             id = r.id;
-            // the extended row's entry is the child carrying the sampled token
-            uint32_t cb = ix.child_off[node], ce = ix.child_off[node + 1];
-            bool match;
-            uint32_t j = wave_lower_bound(ix.node_tok, cb, ce, (uint32_t)id, lane, &match);
-            if (match) {  // always true: the token came from this node's children
-                Walk w2;
-                w2.node = j;
-                w2.lo = ix.node_lo[j];
-                w2.hi = ix.node_hi[j];
-                w2.found = true;
-                done = node_is_member(ix, w2, t + 1);
+            uint32_t entry;
+            if (mode == VALID_LIST) {
+                entry = sh.list_tok[r.pos];
+            } else {  // child index = children before the token's word + set bits below it in the word
+                const uint32_t wv = image[id >> 5];
+                const uint32_t j = cb + ix.heavy_rank[(size_t)slot * (size_t)ix.n_words + (id >> 5)] +
+                                   (uint32_t)__popc(wv & ((1u << (id & 31)) - 1u));
+                entry = ix.node_tok[j];
             }
+            done = (entry & PPV_NODE_TERMINAL) != 0u;   // the extended row is itself a member
+            prefixes[(size_t)b * (size_t)stride + t] = id;
+            lens[b] = t + 1;
+            if (logx) logx[b] += r.logZ_valid;
         }
-        if (lane == 0) {
-            if (id >= 0) {
-                prefixes[(size_t)b * (size_t)stride + t] = id;
-                lens[b] = t + 1;
-                if (logx) logx[b] += r.logZ_valid;
-            }
-            if (ids) ids[b] = id;
-            if (logZ_valid) logZ_valid[b] = r.logZ_valid;
-            if (done) active[b] = 0;
-        }
+        if (ids) ids[b] = id;
+        if (logZ_valid) logZ_valid[b] = r.logZ_valid;
+        if (done) active[b] = 0;
     }
 }
 
@@ -313,6 +778,15 @@ ppv_status check_logits_args(const void *logits, ppv_dtype dt, int64_t row_strid
     return PPV_OK;
 }
 
+// wavefronts per row: one per tile, at most MAX_WAVES, a power of two
+int waves_for(int V, ppv_dtype dt) {
+    const int tile = (dt == PPV_F32) ? TileGeom<float>::TILE : TileGeom<uint16_t>::TILE;
+    const int nt = (V + tile - 1) / tile;
+    int nw = 1;
+    while (nw < nt && nw < MAX_WAVES) nw <<= 1;
+    return nw;
+}
+
 }  // namespace
 
 extern "C" ppv_status ppv_next_token_mask(const ppv_index_t *ix, const int32_t *prefixes, int32_t prefix_stride,
@@ -321,10 +795,9 @@ extern "C" ppv_status ppv_next_token_mask(const ppv_index_t *ix, const int32_t *
     if (!ix || B < 0 || prefix_stride < 0) return PPV_EINVAL;
     if (B == 0) return PPV_OK;  // nothing to do; the (possibly null) buffers are not looked at
     if (!prefixes || !lens || !mask) return PPV_EINVAL;
-    const int n_words = (ix->view.vocab + 31) / 32;
-    const size_t lds = ((size_t)n_words + 2) * sizeof(uint32_t);
+    const size_t lds = ((size_t)ix->view.n_words + 2) * sizeof(uint32_t);
     hipLaunchKernelGGL(mask_kernel, dim3((unsigned)B), dim3(MASK_THREADS), lds, (hipStream_t)stream, ix->view,
-                       prefixes, prefix_stride, lens, mask, range_lo, range_hi, member, n_words);
+                       prefixes, prefix_stride, lens, mask, range_lo, range_hi, member);
     PPV_HIP_TRY(hipGetLastError());
     return PPV_OK;
 }
@@ -338,13 +811,16 @@ extern "C" ppv_status constrained_sample(const void *logits, ppv_dtype dt, int64
     ppv_status st = check_logits_args(logits, dt, row_stride, V);
     if (st != PPV_OK) return st;
     const int n_words = (V + 31) / 32;
+    const int list_max = V / 32 < PPV_LIST_MAX ? V / 32 : PPV_LIST_MAX;
+    const int threads = waves_for(V, dt) * WAVE;
     if (dt == PPV_F32)
-        hipLaunchKernelGGL(sample_kernel<float>, dim3((unsigned)B), dim3(SAMPLE_THREADS), 0, (hipStream_t)stream,
-                           (const float *)logits, row_stride, mask, uniforms, V, n_words, ids, logZ_valid, logZ_all);
-    else
-        hipLaunchKernelGGL(sample_kernel<uint16_t>, dim3((unsigned)B), dim3(SAMPLE_THREADS), 0, (hipStream_t)stream,
-                           (const uint16_t *)logits, row_stride, mask, uniforms, V, n_words, ids, logZ_valid,
+        hipLaunchKernelGGL(sample_kernel<float>, dim3((unsigned)B), dim3(threads), 0, (hipStream_t)stream,
+                           (const float *)logits, row_stride, mask, uniforms, V, n_words, list_max, ids, logZ_valid,
                            logZ_all);
+    else
+        hipLaunchKernelGGL(sample_kernel<uint16_t>, dim3((unsigned)B), dim3(threads), 0, (hipStream_t)stream,
+                           (const uint16_t *)logits, row_stride, mask, uniforms, V, n_words, list_max, ids,
+                           logZ_valid, logZ_all);
     PPV_HIP_TRY(hipGetLastError());
     return PPV_OK;
 }
@@ -358,16 +834,15 @@ extern "C" ppv_status ppv_decode_step(const ppv_index_t *ix, int32_t *prefixes, 
     if (!prefixes || !lens || !active || !uniforms) return PPV_EINVAL;
     ppv_status st = check_logits_args(logits, dt, row_stride, ix->view.vocab);
     if (st != PPV_OK) return st;
-    const int n_words = (ix->view.vocab + 31) / 32;
-    const size_t lds = (((size_t)n_words + 4 + 1) & ~(size_t)1) * sizeof(uint32_t) + SAMPLE_SCRATCH_DOUBLES * sizeof(double);
+    const int threads = waves_for(ix->view.vocab, dt) * WAVE;
     if (dt == PPV_F32)
-        hipLaunchKernelGGL(decode_step_kernel<float>, dim3((unsigned)B), dim3(SAMPLE_THREADS), lds,
-                           (hipStream_t)stream, ix->view, prefixes, prefix_stride, lens, active,
-                           (const float *)logits, row_stride, uniforms, n_words, ids, logZ_valid, logx);
+        hipLaunchKernelGGL(decode_step_kernel<float>, dim3((unsigned)B), dim3(threads), 0, (hipStream_t)stream,
+                           ix->view, prefixes, prefix_stride, lens, active, (const float *)logits, row_stride,
+                           uniforms, ids, logZ_valid, logx);
     else
-        hipLaunchKernelGGL(decode_step_kernel<uint16_t>, dim3((unsigned)B), dim3(SAMPLE_THREADS), lds,
-                           (hipStream_t)stream, ix->view, prefixes, prefix_stride, lens, active,
-                           (const uint16_t *)logits, row_stride, uniforms, n_words, ids, logZ_valid, logx);
+        hipLaunchKernelGGL(decode_step_kernel<uint16_t>, dim3((unsigned)B), dim3(threads), 0, (hipStream_t)stream,
+                           ix->view, prefixes, prefix_stride, lens, active, (const uint16_t *)logits, row_stride,
+                           uniforms, ids, logZ_valid, logx);
     PPV_HIP_TRY(hipGetLastError());
     return PPV_OK;
 }

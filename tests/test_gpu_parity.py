@@ -277,7 +277,11 @@ def test_bf16_sample_matches_f32_on_same_values():
     un = W.make_uniforms(cfg, step=8)
     a = gpu_sample(cfg, logits_to_dev(cfg, bits), dmask, un)
     b = gpu_sample(cfg, to_dev(W.bf16_bits_to_f32(bits)), dmask, un)
-    assert np.array_equal(a[0], b[0]) and np.array_equal(a[1], b[1]) and np.array_equal(a[2], b[2])
+    # same values, different tiling (2048 vs 1024 tokens per tile): same samples, sums equal to rounding
+    assert np.array_equal(a[0], b[0])
+    fin = np.isfinite(a[1])
+    assert np.array_equal(fin, np.isfinite(b[1]))
+    assert np.allclose(a[1][fin], b[1][fin], rtol=2e-6, atol=2e-6) and np.allclose(a[2], b[2], rtol=2e-6, atol=2e-6)
 
 
 def test_results_are_bit_repeatable():
