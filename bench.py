@@ -27,22 +27,100 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0  # MI355X published peak HBM3E bandwidth
 
 
-def algorithmic_bytes_per_prefix_step(V: int, elem: int, n_children: float, depth: float, stride_read: float) -> float:
-    """What one row of one decode step has to move through HBM: the logits row once, the children
-    tokens of the reached prefix (4 bytes each) or at most a V-bit image, one 128-byte line per
-    level of the walk for each of the three per-depth arrays it touches, the prefix itself, and
-    the few scalars written back.  The mask stays on chip in the fused step."""
-    return V * elem + min(4.0 * n_children, V / 8.0) + 3 * 128.0 * depth + 4.0 * stride_read + 24.0
+def algorithmic_bytes_per_prefix_step(V: int, elem: int, n_children: float) -> float:
+    """What one row of one fused decode step has to move through HBM: the logits row once; the
+    valid set, either the children's entries (8 bytes each, plus the one that closes them) or, for a
+    heavy prefix, its V-bit image plus three 128-byte lines to find the sampled child; and about 96
+    bytes of per-row state, scalars and the appended token.  The mask never leaves the chip here."""
+    return V * elem + min(8.0 * (n_children + 1.0), V / 8.0 + 384.0) + 96.0
+
+
+class LoopBench:
+    """The decode loop of one batch: buffers, the eager loop and its HIP graph."""
+
+    def __init__(self, torch, ppv, W, index, logits, uniforms, use_graph=True):
+        self.torch, self.ppv, self.index = torch, ppv, index
+        L, B, V = logits.shape
+        self.L, self.B, self.V = L, B, V
+        dev = logits.device
+        self.prefixes = torch.full((B, L), W.PAD_TOKEN, dtype=torch.int32, device=dev)
+        self.lens = torch.zeros((B,), dtype=torch.int32, device=dev)
+        self.active = torch.zeros((B,), dtype=torch.uint8, device=dev)
+        self.state = torch.zeros((B, ppv.PPV_STATE_WORDS), dtype=torch.int32, device=dev)
+        self.logx = torch.zeros((B,), dtype=torch.float32, device=dev)
+        self.ids = torch.zeros((B,), dtype=torch.int32, device=dev)
+        self.lz = torch.zeros((B,), dtype=torch.float32, device=dev)
+        self.step_logits = [logits[s] for s in range(L)]
+        self.step_uniforms = [uniforms[s] for s in range(L)]
+        self.loop()                                            # eager once: loads the kernels
+        torch.cuda.synchronize()
+        self.graph = None
+        if use_graph:
+            # the launch-bound inner loop is captured once in a HIP graph and replayed
+            side = torch.cuda.Stream()
+            side.wait_stream(torch.cuda.current_stream())
+            with torch.cuda.stream(side):
+                self.loop()
+            torch.cuda.current_stream().wait_stream(side)
+            torch.cuda.synchronize()
+            self.graph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(self.graph):
+                self.loop()
+        self.run = self.graph.replay if self.graph is not None else self.loop
+
+    def loop(self, events=None):
+        """One whole decode loop: start from the empty prefix, then l_max fused step launches."""
+        ppv = self.ppv
+        self.lens.zero_()                                      # a fill kernel (no memset node in a graph)
+        ppv.ppv_decode_begin(self.index, self.prefixes, self.lens, self.state, self.active, self.logx)
+        for s in range(self.L):
+            if events is not None:
+                events[s][0].record()
+            ppv.ppv_decode_step(self.index, self.prefixes, self.lens, self.active, self.step_logits[s],
+                                self.step_uniforms[s], self.ids, self.lz, self.logx, state=self.state)
+            if events is not None:
+                events[s][1].record()
+
+    def time(self, warmup, steps):
+        torch = self.torch
+        for _ in range(warmup):
+            self.run()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            self.run()
+        torch.cuda.synchronize()
+        elapsed = time.perf_counter() - t0
+        assert not self.active.any().item(), "a row did not finish"
+        final_lens = self.lens.cpu().numpy().astype("int64")
+        return elapsed, final_lens
+
+    def launch_durations(self, loops=5):
+        """Average duration of each of the L step launches: HIP events around every eager launch on the
+        launch stream; two graph replays run ahead each time so that the GPU is busy and clocked up."""
+        import numpy as np
+        torch = self.torch
+        events = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(self.L)]
+        dur_ms = np.zeros(self.L)
+        for _ in range(loops):
+            self.run()
+            self.run()
+            self.loop(events)
+            torch.cuda.synchronize()
+            dur_ms += np.array([a.elapsed_time(b) for a, b in events]) / loops
+        return dur_ms
 
 
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--config", default="C3", choices=["C3"])
     ap.add_argument("--n-seq", type=int, default=0, help="override |S| (debugging only; invalidates the metric)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-graph", action="store_true", help="launch every decode step eagerly from Python")
+    ap.add_argument("--no-sweep", action="store_true", help="skip the batch sweep (B = 1024, 4096 replicas)")
     ap.add_argument("--verbose", action="store_true", help="per-decode-step table on stderr")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -64,9 +142,7 @@ def main() -> int:
         cfg = W.scaled(cfg, args.n_seq)
     B, V = cfg.batch, cfg.vocab
 
-    t0 = time.perf_counter()
     S = W.make_constraint_set(cfg)
-    t_gen = time.perf_counter() - t0
     t0 = time.perf_counter()
     index = ppv.ppv_build_index(S.tokens, S.offsets, V)
     torch.cuda.synchronize()
@@ -80,64 +156,30 @@ def main() -> int:
         logits[s] = torch.from_numpy(W.make_logits(cfg, step=s).view(np.int16)).to(dev).view(torch.bfloat16)
         uniforms[s] = torch.from_numpy(W.make_uniforms(cfg, step=s)).to(dev)
 
-    reps = args.warmup + args.steps + 1                    # +1: the pass that times single launches
-    prefixes = torch.full((reps, B, L), W.PAD_TOKEN, dtype=torch.int32, device=dev)
-    lens = torch.zeros((reps, B), dtype=torch.int32, device=dev)
-    active = torch.ones((reps, B), dtype=torch.uint8, device=dev)
-    logx = torch.zeros((reps, B), dtype=torch.float32, device=dev)
-    ids = torch.zeros((B,), dtype=torch.int32, device=dev)
-    lz = torch.zeros((B,), dtype=torch.float32, device=dev)
-
-    def loop(r: int, events=None):
-        for s in range(L):
-            if events is not None:
-                events[s][0].record()
-            ppv.ppv_decode_step(index, prefixes[r], lens[r], active[r], logits[s], uniforms[s], ids, lz, logx[r])
-            if events is not None:
-                events[s][1].record()
-
-    for r in range(args.warmup):
-        loop(r)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for r in range(args.warmup, args.warmup + args.steps):
-        loop(r)
-    torch.cuda.synchronize()
-    elapsed = time.perf_counter() - t0
-
-    # ---- what was processed
-    final_lens = lens[args.warmup].cpu().numpy().astype(np.int64)
-    assert not active[args.warmup:args.warmup + args.steps].any().item(), "a row did not finish"
-    assert (lens[args.warmup:args.warmup + args.steps] == lens[args.warmup]).all().item(), "loops differ"
-    prefix_steps = int(final_lens.sum())                   # row x decode-step pairs per loop
+    lb = LoopBench(torch, ppv, W, index, logits, uniforms, use_graph=not args.no_graph)
+    elapsed, final_lens = lb.time(args.warmup, args.steps)
+    prefix_steps = int(final_lens.sum())                       # row x decode-step pairs per loop
     active_per_step = np.array([(final_lens > s).sum() for s in range(L)], dtype=np.int64)
     ms_per_step = elapsed / args.steps * 1e3
     value = prefix_steps * args.steps / elapsed
 
-    # ---- dominant kernel: average launch duration by HIP events around every launch of one more loop
-    r = reps - 1
-    events = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(L)]
-    loop(r, events)
-    torch.cuda.synchronize()
-    dur_ms = np.array([a.elapsed_time(b) for a, b in events])
-    # algorithmic bytes: per row of step s the reached prefix has depth s; its child count comes from the run
-    seqs = prefixes[args.warmup].cpu().numpy()
-    fan = fanout_along(index, ppv, torch, seqs, final_lens, L, dev)             # [L] mean children of the prefixes reached at step s
-    bytes_per_launch = np.array([
-        active_per_step[s] * algorithmic_bytes_per_prefix_step(V, 2, fan[s], s, s) for s in range(L)])
+    # ---- dominant kernel (the fused decode step): algorithmic bytes per launch / average launch duration
+    dur_ms = lb.launch_durations()
+    seqs = lb.prefixes.cpu().numpy()
+    fan = fanout_along(index, ppv, torch, seqs, final_lens, L, dev)  # mean children of the prefixes reached at step s
+    bytes_per_launch = np.array([active_per_step[s] * algorithmic_bytes_per_prefix_step(V, 2, fan[s]) for s in range(L)])
     if args.verbose:
         for s_ in range(L):
             print(f"step {s_:2d} active {active_per_step[s_]:4d} fanout {fan[s_]:9.1f} launch {dur_ms[s_] * 1e3:8.2f} us "
                   f"{bytes_per_launch[s_] / max(dur_ms[s_], 1e-9) / 1e6:8.1f} GB/s", file=sys.stderr)
-    launches = int((active_per_step > 0).sum())
     busy = active_per_step > 0
     achieved = float(bytes_per_launch[busy].sum() / (dur_ms[busy].sum() * 1e-3) / 1e9)
     roofline = {"bound": "hbm", "kernel": "decode_step_kernel<bf16>", "achieved": round(achieved, 1),
                 "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
-                "avg_launch_us": round(float(dur_ms[busy].mean() * 1e3), 2), "launches_per_step": launches,
+                "avg_launch_us": round(float(dur_ms[busy].mean() * 1e3), 2), "launches_per_step": int(busy.sum()),
                 "bytes_per_launch_avg": int(bytes_per_launch[busy].mean()),
-                "first_launch_us": round(float(dur_ms[0] * 1e3), 2),
-                "first_launch_GBs": round(float(bytes_per_launch[0] / (dur_ms[0] * 1e-3) / 1e9), 1)}
+                "full_batch_launch": {"rows": int(active_per_step[0]), "us": round(float(dur_ms[0] * 1e3), 2),
+                                      "GBs": round(float(bytes_per_launch[0] / (dur_ms[0] * 1e-3) / 1e9), 1)}}
 
     out = {
         "metric": "constrained decode steps (prefixes)/sec at N=1M, V=32k", "value": round(value, 1),
@@ -147,10 +189,34 @@ def main() -> int:
         "config": {"workload": f"{cfg.name}: |S|={index.n_distinct} lengths U[4,32] Zipf(1.1) V={V}; full decode loop, "
                                f"B={B} rows from the empty prefix, {L} fused step launches per loop, "
                                f"{prefix_steps} prefix-steps per loop",
-                   "launch": "one ppv_decode_step per decode step via the C ABI, no host sync inside a loop"},
+                   "launch": ("ppv_decode_begin + one ppv_decode_step per decode step through the C ABI, " +
+                              ("captured once in a HIP graph and replayed" if lb.graph is not None else "launched eagerly") +
+                              ", no host sync inside a loop")},
         "roofline": roofline,
+        "achieved_GBs_whole_loop": round(float(bytes_per_launch.sum() / (elapsed / args.steps) / 1e9), 1),
         "index_build_s": round(t_build, 3), "index_device_MB": round(index.device_bytes / 1e6, 1),
     }
+
+    if not args.no_sweep:
+        # Same loop with R replicas of the batch (logits drawn on the device: same distribution, not
+        # checked against the oracle) to show where the kernel goes once the launch is large enough.
+        out["batch_sweep"] = []
+        del lb
+        for Bs in (1024, 4096):
+            g = torch.Generator(device=dev)
+            g.manual_seed(cfg.seed + Bs)
+            lg = torch.empty((L, Bs, V), dtype=torch.bfloat16, device=dev)
+            for s in range(L):
+                lg[s] = (torch.randn((Bs, V), generator=g, device=dev, dtype=torch.float32) * cfg.sigma).to(torch.bfloat16)
+            un = torch.rand((L, Bs), generator=g, device=dev, dtype=torch.float32)
+            sb = LoopBench(torch, ppv, W, index, lg, un, use_graph=not args.no_graph)
+            el, fl = sb.time(2, 10)
+            ps = int(fl.sum())
+            out["batch_sweep"].append({"B": Bs, "prefix_steps_per_s": round(ps * 10 / el, 1),
+                                       "GBs": round(ps * algorithmic_bytes_per_prefix_step(V, 2, 1.0) * 10 / el / 1e9, 1),
+                                       "frac_of_peak": round(ps * algorithmic_bytes_per_prefix_step(V, 2, 1.0) * 10 / el
+                                                             / 1e9 / HBM_PEAK_GBS, 4)})
+            del sb, lg, un
 
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg, S, B, seqs, final_lens)
@@ -176,28 +242,26 @@ def fanout_along(index, ppv, torch, seqs, final_lens, L, dev):
     return out
 
 
-def cpu_baseline(cfg, S, B, gpu_seqs, gpu_lens):
+def cpu_baseline(cfg, S, B, gpu_seqs, gpu_lens, repeats=8):
     """The CPU oracle (never tuned for this) on the same decode loop, on this machine's cores."""
     import numpy as np
     import oracle
     from paper_2504_09135_amd import workloads as W
     threads = oracle.max_threads()
     trie = oracle.Trie(S.tokens, S.offsets, cfg.vocab)
-    rows = B
-    lg = lambda s, *_: W.logits_as_f32(cfg, W.make_logits(cfg, step=s))[:rows]
-    un = lambda s: W.make_uniforms(cfg, step=s)[:rows]
-    # pre-generate outside the timed region, like the GPU side
-    cache_l, cache_u = {}, {}
-    for s in range(trie.l_max):
-        cache_l[s], cache_u[s] = lg(s), un(s)
+    # inputs are generated outside the timed region, like the GPU side's
+    cache_l = {s: W.logits_as_f32(cfg, W.make_logits(cfg, step=s)) for s in range(trie.l_max)}
+    cache_u = {s: W.make_uniforms(cfg, step=s) for s in range(trie.l_max)}
     t0 = time.perf_counter()
-    res = oracle.decode_loop(trie, rows, lambda s, *_: cache_l[s], lambda s: cache_u[s], threads=threads)
+    for _ in range(repeats):
+        res = oracle.decode_loop(trie, B, lambda s, *_: cache_l[s], lambda s: cache_u[s], threads=threads)
     dt = time.perf_counter() - t0
     steps = int(res.lens.sum())
-    same = int(sum(np.array_equal(res.seqs[b, :res.lens[b]], gpu_seqs[b, :gpu_lens[b]]) for b in range(rows)))
-    return {"value": round(steps / dt, 1), "unit": "prefix-steps/s", "cores": threads, "kind": "oracle",
-            "sample": f"the same full decode loop, all {rows} rows ({steps} prefix-steps, {dt:.1f} s), "
-                      f"OpenMP over rows; trie build excluded; {same}/{rows} rows end on the GPU's sequence"}
+    same = int(sum(np.array_equal(res.seqs[b, :res.lens[b]], gpu_seqs[b, :gpu_lens[b]]) for b in range(B)))
+    return {"value": round(steps * repeats / dt, 1), "unit": "prefix-steps/s", "cores": threads, "kind": "oracle",
+            "sample": f"the same full decode loop, all {B} rows, {repeats} times ({steps * repeats} prefix-steps, "
+                      f"{dt:.1f} s wall, about {dt * threads:.0f} core-seconds), OpenMP over rows; trie build excluded; "
+                      f"{same}/{B} rows end on the GPU's sequence"}
 
 
 if __name__ == "__main__":

@@ -131,6 +131,24 @@ ppv_status constrained_sample(const void *logits, ppv_dtype dt, int64_t row_stri
                               float *logZ_all, void *stream);
 
 /*
+ * ppv_decode_begin -- Algorithm 1, SampleCandidate: "Initialize candidate sequence a = [],
+ * importance score x = 1" (or resume from given prefixes).  Locates each row's current prefix once
+ * and leaves a cursor in `state`, so that every following ppv_decode_step costs one level of the
+ * index instead of a walk from the root.
+ * Arguments (all device pointers):
+ *   prefixes, prefix_stride, lens   as in ppv_next_token_mask (lens[b] = 0: start from the empty prefix)
+ *   state     uint32[B, PPV_STATE_WORDS], written; opaque, only ppv_decode_step reads and updates it
+ *   active    uint8[B], written: 1 iff the row's prefix is a prefix of a member of S and is not
+ *             itself a member (the row has something left to decode)
+ *   logx      float[B] or NULL: set to 0 (log of the importance score x = 1)
+ * Errors: PPV_EINVAL (null index/prefixes/lens/state/active, B < 0, prefix_stride < 0), PPV_EDEVICE.
+ */
+#define PPV_STATE_WORDS 4
+ppv_status ppv_decode_begin(const ppv_index_t *index, const int32_t *prefixes, int32_t prefix_stride,
+                            const int32_t *lens, int32_t B, uint32_t *state, uint8_t *active, float *logx,
+                            void *stream);
+
+/*
  * ppv_decode_step -- one iteration of the while loop of Algorithm 1's SampleCandidate for B rows,
  * fused: mask = PPV_S(P, a); sample t; a = a + [t]; x = x * |P (.) mask|_1; stop when a is in S.
  * Equals ppv_next_token_mask + constrained_sample + append + membership test, but the mask never
@@ -141,6 +159,9 @@ ppv_status constrained_sample(const void *logits, ppv_dtype dt, int64_t row_stri
  *   active    uint8[B], in/out: cleared when the extended row is a member of S (the row is done),
  *             and also (with ids[b] = -1, nothing appended) when the row has no valid token or
  *             no room left (lens[b] == prefix_stride)
+ *   state     uint32[B, PPV_STATE_WORDS] from ppv_decode_begin, in/out; or NULL: the prefix is then
+ *             located from the root in every call (same results, one index level per token slower).
+ *             With a state the caller must not change prefixes/lens of active rows between steps.
  *   logits, dt, row_stride, uniforms   as in constrained_sample; V is the index's vocabulary
  *   ids         int32[B] or NULL: token sampled this step (-1 if none); untouched for inactive rows
  *   logZ_valid  float[B] or NULL: this step's log valid mass; untouched for inactive rows
@@ -148,7 +169,7 @@ ppv_status constrained_sample(const void *logits, ppv_dtype dt, int64_t row_stri
  * Errors: as the two calls above.
  */
 ppv_status ppv_decode_step(const ppv_index_t *index, int32_t *prefixes, int32_t prefix_stride, int32_t *lens,
-                           uint8_t *active, const void *logits, ppv_dtype dt, int64_t row_stride,
+                           uint8_t *active, uint32_t *state, const void *logits, ppv_dtype dt, int64_t row_stride,
                            const float *uniforms, int32_t B, int32_t *ids, float *logZ_valid, float *logx,
                            void *stream);
 

@@ -20,8 +20,10 @@ PPV_OK = 0
 PPV_F32, PPV_BF16 = 0, 1
 PPV_MAX_VOCAB = 262144
 
+PPV_STATE_WORDS = 4
+
 SYMBOLS = ("ppv_status_string", "ppv_build_index", "ppv_index_info", "ppv_index_export", "ppv_free_index",
-           "ppv_next_token_mask", "constrained_sample", "ppv_decode_step")
+           "ppv_next_token_mask", "constrained_sample", "ppv_decode_begin", "ppv_decode_step")
 
 _lib = None
 
@@ -56,8 +58,10 @@ def load_library() -> C.CDLL:
     lib.ppv_next_token_mask.argtypes = [p, p, i32, p, i32, p, p, p, p, p]
     lib.constrained_sample.restype = C.c_int
     lib.constrained_sample.argtypes = [p, C.c_int, i64, p, p, i32, i32, p, p, p, p]
+    lib.ppv_decode_begin.restype = C.c_int
+    lib.ppv_decode_begin.argtypes = [p, p, i32, p, i32, p, p, p, p]
     lib.ppv_decode_step.restype = C.c_int
-    lib.ppv_decode_step.argtypes = [p, p, i32, p, p, p, C.c_int, i64, p, i32, p, p, p, p]
+    lib.ppv_decode_step.argtypes = [p, p, i32, p, p, p, p, C.c_int, i64, p, i32, p, p, p, p]
     _lib = lib
     return lib
 
@@ -191,22 +195,39 @@ def constrained_sample(logits: torch.Tensor, mask: torch.Tensor, uniforms: torch
     _check(st, "constrained_sample")
 
 
+def ppv_decode_begin(index: PPVIndex, prefixes: torch.Tensor, lens: torch.Tensor, state: torch.Tensor,
+                     active: torch.Tensor, logx: Optional[torch.Tensor] = None, stream=None) -> None:
+    """Locate every row's current prefix once: writes state int32 [B, PPV_STATE_WORDS], active uint8 [B]
+    and zeroes logx f32 [B]."""
+    B, stride = int(prefixes.shape[0]), int(prefixes.shape[1])
+    if tuple(lens.shape) != (B,) or tuple(state.shape) != (B, PPV_STATE_WORDS) or tuple(active.shape) != (B,) \
+            or (logx is not None and tuple(logx.shape) != (B,)):
+        raise ValueError("ppv_decode_begin: shape mismatch")
+    st = load_library().ppv_decode_begin(
+        index.handle, _dev(prefixes, torch.int32, "prefixes"), stride, _dev(lens, torch.int32, "lens"), B,
+        _dev(state, torch.int32, "state"), _dev(active, torch.uint8, "active"), _dev(logx, torch.float32, "logx"),
+        _stream(stream))
+    _check(st, "ppv_decode_begin")
+
+
 def ppv_decode_step(index: PPVIndex, prefixes: torch.Tensor, lens: torch.Tensor, active: torch.Tensor,
                     logits: torch.Tensor, uniforms: torch.Tensor, ids: Optional[torch.Tensor] = None,
                     logZ_valid: Optional[torch.Tensor] = None, logx: Optional[torch.Tensor] = None,
-                    stream=None) -> None:
-    """One fused constrained decoding step, in place on prefixes / lens / active / logx."""
+                    state: Optional[torch.Tensor] = None, stream=None) -> None:
+    """One fused constrained decoding step, in place on prefixes / lens / active / logx (and on
+    state int32 [B, PPV_STATE_WORDS] from ppv_decode_begin when given)."""
     ptr, dt, row_stride = _logits_args(logits)
     B, stride = int(prefixes.shape[0]), int(prefixes.shape[1])
     if int(logits.shape[0]) != B or int(logits.shape[1]) != index.vocab or tuple(lens.shape) != (B,) \
-            or tuple(active.shape) != (B,) or tuple(uniforms.shape) != (B,):
+            or tuple(active.shape) != (B,) or tuple(uniforms.shape) != (B,) \
+            or (state is not None and tuple(state.shape) != (B, PPV_STATE_WORDS)):
         raise ValueError("ppv_decode_step: shape mismatch")
     for t, nm in ((ids, "ids"), (logZ_valid, "logZ_valid"), (logx, "logx")):
         if t is not None and tuple(t.shape) != (B,):
             raise ValueError(f"ppv_decode_step: {nm} must have shape [B]")
     st = load_library().ppv_decode_step(
         index.handle, _dev(prefixes, torch.int32, "prefixes"), stride, _dev(lens, torch.int32, "lens"),
-        _dev(active, torch.uint8, "active"), ptr, dt, row_stride, _dev(uniforms, torch.float32, "uniforms"), B,
-        _dev(ids, torch.int32, "ids"), _dev(logZ_valid, torch.float32, "logZ_valid"),
-        _dev(logx, torch.float32, "logx"), _stream(stream))
+        _dev(active, torch.uint8, "active"), _dev(state, torch.int32, "state"), ptr, dt, row_stride,
+        _dev(uniforms, torch.float32, "uniforms"), B, _dev(ids, torch.int32, "ids"),
+        _dev(logZ_valid, torch.float32, "logZ_valid"), _dev(logx, torch.float32, "logx"), _stream(stream))
     _check(st, "ppv_decode_step")

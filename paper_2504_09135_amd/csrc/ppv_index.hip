@@ -154,10 +154,15 @@ ppv_status build_impl(const int32_t *tokens, const int64_t *offsets, int64_t n_s
     // ---- upload
     ppv_status st;
     ix->device_bytes = 0;
-    if ((st = upload(&ix->d_node_tok, node_tok, &ix->device_bytes)) != PPV_OK) return st;
+    std::vector<NodeEnt> ent(G + 1);
+    for (size_t g = 0; g <= G; g++) {
+        ent[g].tok = g < G ? node_tok[g] : PPV_NODE_TOKEN;
+        if (g < heavy_slot.size() && heavy_slot[g] != PPV_NO_SLOT) ent[g].tok |= PPV_NODE_HEAVY;
+        ent[g].child = child_off[g];
+    }
+    if ((st = upload(&ix->d_ent, ent, &ix->device_bytes)) != PPV_OK) return st;
     if ((st = upload(&ix->d_node_lo, node_lo, &ix->device_bytes)) != PPV_OK) return st;
     if ((st = upload(&ix->d_node_hi, node_hi, &ix->device_bytes)) != PPV_OK) return st;
-    if ((st = upload(&ix->d_child_off, child_off, &ix->device_bytes)) != PPV_OK) return st;
     if ((st = upload(&ix->d_heavy_slot, heavy_slot, &ix->device_bytes)) != PPV_OK) return st;
     if ((st = upload(&ix->d_heavy_bits, heavy_bits, &ix->device_bytes)) != PPV_OK) return st;
     if ((st = upload(&ix->d_heavy_rank, heavy_rank, &ix->device_bytes)) != PPV_OK) return st;
@@ -165,10 +170,9 @@ ppv_status build_impl(const int32_t *tokens, const int64_t *offsets, int64_t n_s
     if ((st = upload(&ix->d_x_off, x_off, &ix->device_bytes)) != PPV_OK) return st;
     ix->n_tokens = (int64_t)x_tok.size();
     ix->n_heavy = (int64_t)n_heavy;
-    ix->view.node_tok = ix->d_node_tok;
+    ix->view.ent = ix->d_ent;
     ix->view.node_lo = ix->d_node_lo;
     ix->view.node_hi = ix->d_node_hi;
-    ix->view.child_off = ix->d_child_off;
     ix->view.heavy_slot = ix->d_heavy_slot;
     ix->view.heavy_bits = ix->d_heavy_bits;
     ix->view.heavy_rank = ix->d_heavy_rank;
@@ -184,10 +188,9 @@ ppv_status build_impl(const int32_t *tokens, const int64_t *offsets, int64_t n_s
 
 void release(ppv_index *ix) {
     if (!ix) return;
-    (void)hipFree(ix->d_node_tok);
+    (void)hipFree(ix->d_ent);
     (void)hipFree(ix->d_node_lo);
     (void)hipFree(ix->d_node_hi);
-    (void)hipFree(ix->d_child_off);
     (void)hipFree(ix->d_heavy_slot);
     (void)hipFree(ix->d_heavy_bits);
     (void)hipFree(ix->d_heavy_rank);

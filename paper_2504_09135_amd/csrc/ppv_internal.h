@@ -9,22 +9,29 @@
 // breadth-first order: all prefixes of length 1 in sorted order, then all of length 2, ...
 // Node 0 is the empty prefix.  Because each depth is sorted, the children of consecutive nodes
 // are consecutive, so one offsets array describes all of them: the children of node g are the
-// nodes child_off[g] .. child_off[g+1], in increasing token order.
+// nodes ent[g].child .. ent[g+1].child, in increasing token order.  Token and child offset sit
+// side by side, so the one load that searches (or lists) a node's children also brings each
+// child's own children range.
 //
 // Nodes with more than `heavy_min` children ("heavy": the root and a few shallow prefixes) also
 // carry their valid set as a ready-made V-bit image plus, per 32-bit word of it, the number of
 // children before that word, so that a copy replaces the scatter and the child carrying a given
 // token is found with two loads.
-constexpr uint32_t PPV_NODE_TERMINAL = 0x80000000u;  // flag in node_tok: the prefix itself is in S
-constexpr uint32_t PPV_NODE_TOKEN = 0x7FFFFFFFu;
+constexpr uint32_t PPV_NODE_TERMINAL = 0x80000000u;  // flag in NodeEnt::tok: the prefix itself is in S
+constexpr uint32_t PPV_NODE_HEAVY = 0x40000000u;     // flag in NodeEnt::tok: the node has an image
+constexpr uint32_t PPV_NODE_TOKEN = 0x3FFFFFFFu;
 constexpr uint32_t PPV_NO_SLOT = 0xFFFFFFFFu;
 constexpr int PPV_LIST_MAX = 1024;  // a valid set of at most this many tokens is handled as a list
 
+struct NodeEnt {
+    uint32_t tok;    // last token of the prefix | flags
+    uint32_t child;  // first child; the children end where the next entry's children begin
+};
+
 struct IndexView {
-    const uint32_t *node_tok;    // [n_nodes]   last token of the prefix | PPV_NODE_TERMINAL
+    const NodeEnt *ent;          // [n_nodes+1] (the last entry is a sentinel that closes the offsets)
     const uint32_t *node_lo;     // [n_nodes]   rank of the first member the prefix is a prefix of
     const uint32_t *node_hi;     // [n_nodes]   one past the rank of the last such member
-    const uint32_t *child_off;   // [n_nodes+1] CSR offsets into the node arrays
     const uint32_t *heavy_slot;  // [heavy_limit] slot of a heavy node, PPV_NO_SLOT otherwise
     const uint32_t *heavy_bits;  // [n_heavy, n_words] valid-set images
     const uint32_t *heavy_rank;  // [n_heavy, n_words] children before each word
@@ -37,9 +44,18 @@ struct IndexView {
     int32_t l_max;
 };
 
+// Per-row decoding cursor kept between decode steps (PPV_STATE_WORDS x uint32).
+struct RowState {
+    uint32_t node;   // entry of the row's current prefix; PPV_NO_SLOT: not a prefix of any member
+    uint32_t cb, ce; // its children
+    uint32_t slot;   // heavy slot or PPV_NO_SLOT
+};
+static_assert(sizeof(RowState) == PPV_STATE_WORDS * sizeof(uint32_t), "state layout");
+
 struct ppv_index {
     IndexView view;
-    uint32_t *d_node_tok, *d_node_lo, *d_node_hi, *d_child_off;
+    NodeEnt *d_ent;
+    uint32_t *d_node_lo, *d_node_hi;
     uint32_t *d_heavy_slot, *d_heavy_bits, *d_heavy_rank;
     int32_t *d_x_tok;    // sorted S, flat, no padding: row r is d_x_tok[d_x_off[r] .. d_x_off[r+1])
     int64_t *d_x_off;    // [n_rows + 1]

@@ -13,6 +13,8 @@
 //          operations per element) and the sample is located by re-reading one tile.
 // Nothing here is a dense contraction, so no MFMA; the bound is HBM bandwidth, with the exp
 // (quarter-rate v_exp_f32) as the main ALU cost.
+#include <cstdlib>
+
 #include "ppv_internal.h"
 
 namespace {
@@ -27,38 +29,77 @@ constexpr float LN2F = 0.693147180559945309417f;
 static_assert(PPV_MAX_VOCAB <= MAX_TILES * 1024, "tile bookkeeping too small");
 
 // ------------------------------------------------------------------------------------------
-// wave-level helpers (results are uniform over the wave)
+// wave-level helpers on DPP (data-parallel primitives: a lane reads a neighbour's register inside
+// the VALU instruction, no LDS round trip).  Reductions return a wave-uniform value.
+constexpr int DPP_QUAD_XOR1 = 0xB1;     // quad_perm [1,0,3,2]
+constexpr int DPP_QUAD_XOR2 = 0x4E;     // quad_perm [2,3,0,1]
+constexpr int DPP_ROW_SHR1 = 0x111, DPP_ROW_SHR2 = 0x112, DPP_ROW_SHR3 = 0x113, DPP_ROW_SHR4 = 0x114,
+              DPP_ROW_SHR8 = 0x118;
+constexpr int DPP_ROW_MIRROR = 0x140, DPP_ROW_HALF_MIRROR = 0x141, DPP_ROW_BCAST15 = 0x142, DPP_ROW_BCAST31 = 0x143;
+
+// source lane's value, or 0 where the lane has no source or is masked off
+template <int CTRL, int ROW_MASK = 0xF, int BANK_MASK = 0xF> __device__ inline int dpp0(int x) {
+    return __builtin_amdgcn_update_dpp(0, x, CTRL, ROW_MASK, BANK_MASK, true);
+}
+template <int CTRL, int ROW_MASK = 0xF, int BANK_MASK = 0xF> __device__ inline float dpp0(float x) {
+    return __int_as_float(dpp0<CTRL, ROW_MASK, BANK_MASK>(__float_as_int(x)));
+}
+template <int CTRL, int ROW_MASK = 0xF, int BANK_MASK = 0xF> __device__ inline double dpp0(double x) {
+    return __hiloint2double(dpp0<CTRL, ROW_MASK, BANK_MASK>(__double2hiint(x)),
+                            dpp0<CTRL, ROW_MASK, BANK_MASK>(__double2loint(x)));
+}
+// source lane's value, or the lane's own value where it has no source or is masked off
+template <int CTRL, int ROW_MASK = 0xF, int BANK_MASK = 0xF> __device__ inline float dpp_self(float x) {
+    return __int_as_float(
+        __builtin_amdgcn_update_dpp(__float_as_int(x), __float_as_int(x), CTRL, ROW_MASK, BANK_MASK, false));
+}
+__device__ inline float last_lane(float x) { return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(x), 63)); }
+__device__ inline int last_lane(int x) { return __builtin_amdgcn_readlane(x, 63); }
+__device__ inline double last_lane(double x) {
+    return __hiloint2double(__builtin_amdgcn_readlane(__double2hiint(x), 63),
+                            __builtin_amdgcn_readlane(__double2loint(x), 63));
+}
+
+// value held by lane l (l must be wave-uniform)
+__device__ inline int lane_value(int x, int l) { return __builtin_amdgcn_readlane(x, l); }
+__device__ inline uint32_t lane_value(uint32_t x, int l) { return (uint32_t)__builtin_amdgcn_readlane((int)x, l); }
+__device__ inline double lane_value(double x, int l) {
+    return __hiloint2double(__builtin_amdgcn_readlane(__double2hiint(x), l),
+                            __builtin_amdgcn_readlane(__double2loint(x), l));
+}
+
 __device__ inline float wave_max(float x) {
-    for (int o = WAVE / 2; o > 0; o >>= 1) x = fmaxf(x, __shfl_xor(x, o, WAVE));
-    return x;
+    x = fmaxf(x, dpp_self<DPP_QUAD_XOR1>(x));
+    x = fmaxf(x, dpp_self<DPP_QUAD_XOR2>(x));
+    x = fmaxf(x, dpp_self<DPP_ROW_HALF_MIRROR>(x));
+    x = fmaxf(x, dpp_self<DPP_ROW_MIRROR>(x));           // every lane: maximum of its row of 16
+    x = fmaxf(x, dpp_self<DPP_ROW_BCAST15, 0xA>(x));     // rows 1, 3 take in rows 0, 2
+    x = fmaxf(x, dpp_self<DPP_ROW_BCAST31, 0xC>(x));     // rows 2, 3 take in lane 31
+    return last_lane(x);
 }
-__device__ inline float wave_sum(float x) {
-    for (int o = WAVE / 2; o > 0; o >>= 1) x += __shfl_xor(x, o, WAVE);
-    return x;
+template <typename V> __device__ inline V wave_sum(V x) {
+    x += dpp0<DPP_QUAD_XOR1>(x);
+    x += dpp0<DPP_QUAD_XOR2>(x);
+    x += dpp0<DPP_ROW_HALF_MIRROR>(x);
+    x += dpp0<DPP_ROW_MIRROR>(x);
+    x += dpp0<DPP_ROW_BCAST15, 0xA>(x);
+    x += dpp0<DPP_ROW_BCAST31, 0xC>(x);
+    return last_lane(x);
 }
-__device__ inline double wave_sum(double x) {
-    for (int o = WAVE / 2; o > 0; o >>= 1) x += __shfl_xor(x, o, WAVE);
-    return x;
-}
-__device__ inline int wave_sum(int x) {
-    for (int o = WAVE / 2; o > 0; o >>= 1) x += __shfl_xor(x, o, WAVE);
-    return x;
-}
-__device__ inline double wave_incl_scan(double x, int lane) {
-    for (int o = 1; o < WAVE; o <<= 1) {
-        double y = __shfl_up(x, o, WAVE);
-        if (lane >= o) x += y;
-    }
-    return x;
-}
-__device__ inline int wave_incl_scan(int x, int lane) {
-    for (int o = 1; o < WAVE; o <<= 1) {
-        int y = __shfl_up(x, o, WAVE);
-        if (lane >= o) x += y;
-    }
-    return x;
+// inclusive prefix sum over the 64 lanes (lane order)
+template <typename V> __device__ inline V wave_incl_scan(V x) {
+    V t = x;
+    t += dpp0<DPP_ROW_SHR1>(x);
+    t += dpp0<DPP_ROW_SHR2>(x);
+    t += dpp0<DPP_ROW_SHR3>(x);                          // up to 4 consecutive lanes of the row
+    t += dpp0<DPP_ROW_SHR4, 0xF, 0xE>(t);
+    t += dpp0<DPP_ROW_SHR8, 0xF, 0xC>(t);                // prefix inside each row of 16
+    t += dpp0<DPP_ROW_BCAST15, 0xA>(t);
+    t += dpp0<DPP_ROW_BCAST31, 0xC>(t);
+    return t;
 }
 __device__ inline float fast_exp2(float y) { return __builtin_amdgcn_exp2f(y); }  // v_exp_f32, 1 ulp
+__device__ inline float fast_log2(float y) { return __builtin_amdgcn_logf(y); }   // v_log_f32, 1 ulp (normal inputs)
 // exp(d) for d <= 0 with the rounding of d*log2(e) compensated (used once per tile, not per token)
 __device__ inline float exp_scale(float d) {
     float hi = d * LOG2E;
@@ -72,58 +113,74 @@ __device__ inline float exp_scale(float d) {
 // the children of the current prefix per token, instead of log2|S| probes of whole rows).
 // All 64 lanes call it with the same arguments; every result is wave-uniform.
 struct Walk {
-    uint32_t node;    // the prefix's entry in the per-depth arrays (meaningful when found)
+    uint32_t node;    // the prefix's entry (meaningful when found)
+    uint32_t cb, ce;  // its children (when found)
+    uint32_t tok;     // its entry's token word with flags (when found and t > 0)
     uint32_t lo, hi;  // rank range in sorted S; lo == hi == insertion rank when not found
     bool found;       // the prefix is a prefix of at least one member
     bool member;      // the prefix itself is in S
 };
 
-// first position in [begin, end) whose token is >= key; tokens are strictly increasing
-__device__ inline uint32_t wave_lower_bound(const uint32_t *__restrict__ tok, uint32_t begin, uint32_t end,
-                                            uint32_t key, int lane, uint32_t *hit) {
+// Search `key` among the entries [begin, end) (strictly increasing tokens).  Returns the first
+// position whose token is >= key; on a match *hit is that entry and *next_child the child offset
+// of the entry after it (the end of the match's own children), else hit->tok = PPV_NO_SLOT.
+__device__ inline uint32_t wave_search(const NodeEnt *__restrict__ ent, uint32_t begin, uint32_t end, uint32_t key,
+                                       int lane, NodeEnt *hit, uint32_t *next_child) {
     uint32_t lo = begin, hi = end;
-    while (hi - lo > (uint32_t)WAVE) {
+    while (hi - lo > (uint32_t)(WAVE - 1)) {
         uint32_t n = hi - lo;
         uint32_t step = (n + WAVE - 1) / WAVE;
         uint32_t p = (uint32_t)(lane + 1) * step;
         if (p > n) p = n;
-        uint32_t v = tok[lo + p - 1] & PPV_NODE_TOKEN;   // 64 pivots, the last one is tok[hi-1]
-        int c = __popcll(__ballot(v < key));             // pivots below the key
-        if (c == WAVE) { lo = hi; break; }               // everything is below the key
+        uint32_t v = ent[lo + p - 1].tok & PPV_NODE_TOKEN;  // 64 pivots, the last one is the last entry
+        int c = __popcll(__ballot(v < key));                // pivots below the key
+        if (c == WAVE) { lo = hi; break; }                  // everything is below the key
         uint32_t nlo = lo + (uint32_t)c * step;
         uint32_t nhi = lo + (uint32_t)(c + 1) * step;
         if (nhi > hi) nhi = hi;
         lo = nlo;
         hi = nhi;
     }
-    bool in = lo + (uint32_t)lane < hi;
-    uint32_t raw = in ? tok[lo + lane] : 0xFFFFFFFFu;
-    uint32_t v = in ? (raw & PPV_NODE_TOKEN) : 0xFFFFFFFFu;
-    int c = __popcll(__ballot(in && v < key));
-    uint64_t eq = __ballot(in && v == key);
-    // the matching entry (token | terminal flag), or PPV_NO_SLOT (no real entry has all bits set)
-    *hit = eq ? (uint32_t)__shfl((int)raw, __ffsll((long long)eq) - 1, WAVE) : PPV_NO_SLOT;
+    // at most 63 candidates: lane l takes entry lo+l, one lane more takes the entry after them
+    // (always there: the array ends with a sentinel), which closes the last candidate's children
+    const uint32_t n = hi - lo;
+    NodeEnt e;
+    e.tok = PPV_NO_SLOT;
+    e.child = 0;
+    if ((uint32_t)lane <= n) e = ent[lo + lane];
+    const bool in = (uint32_t)lane < n;
+    const uint32_t v = e.tok & PPV_NODE_TOKEN;
+    const int c = __popcll(__ballot(in && v < key));
+    const uint64_t eq = __ballot(in && v == key);
+    hit->tok = PPV_NO_SLOT;
+    if (eq) {
+        const int l = __ffsll((long long)eq) - 1;
+        hit->tok = lane_value(e.tok, l);
+        hit->child = lane_value(e.child, l);
+        *next_child = lane_value(e.child, l + 1);
+    }
     return lo + (uint32_t)c;
 }
 
 __device__ inline Walk walk_prefix(const IndexView &ix, const int32_t *__restrict__ prefix, int t, int lane) {
     Walk w;
     w.node = 0;
-    w.lo = 0;
-    w.hi = ix.n_rows;
+    w.cb = ix.ent[0].child;
+    w.ce = ix.ent[1].child;
+    w.tok = 0;
     w.found = true;
     w.member = false;
     // the first 64 tokens in one coalesced load; token i is broadcast from lane i
-    int32_t mine = (lane < t) ? prefix[lane] : 0;
+    const int32_t mine = (lane < t) ? prefix[lane] : 0;
     for (int i = 0; i < t; i++) {
-        uint32_t key = (uint32_t)((i < WAVE) ? __shfl(mine, i, WAVE) : prefix[i]);
-        uint32_t cb = ix.child_off[w.node], ce = ix.child_off[w.node + 1];
-        uint32_t hit;
-        uint32_t j = wave_lower_bound(ix.node_tok, cb, ce, key, lane, &hit);
-        if (hit == PPV_NO_SLOT || key > PPV_NODE_TOKEN) {
+        const uint32_t key = (uint32_t)((i < WAVE) ? lane_value(mine, i) : prefix[i]);
+        NodeEnt hit;
+        uint32_t next_child = 0;
+        const uint32_t j = wave_search(ix.ent, w.cb, w.ce, key, lane, &hit, &next_child);
+        if (hit.tok == PPV_NO_SLOT || key > PPV_NODE_TOKEN) {
             // every member below child j sorts before the prefix; with no such child the prefix
             // sorts after the whole range of the current node
-            uint32_t rank = (j < ce) ? ix.node_lo[j] : w.hi;
+            const uint32_t rank = (j < w.ce) ? ix.node_lo[j] : (w.node ? ix.node_hi[w.node] : ix.n_rows);
             w.lo = rank;
             w.hi = rank;
             w.found = false;
@@ -131,10 +188,13 @@ __device__ inline Walk walk_prefix(const IndexView &ix, const int32_t *__restric
             return w;
         }
         w.node = j;
-        w.lo = ix.node_lo[j];
-        w.hi = ix.node_hi[j];
-        w.member = (hit & PPV_NODE_TERMINAL) != 0u;
+        w.tok = hit.tok;
+        w.cb = hit.child;
+        w.ce = next_child;
     }
+    w.lo = w.node ? ix.node_lo[w.node] : 0u;
+    w.hi = w.node ? ix.node_hi[w.node] : ix.n_rows;
+    w.member = (w.tok & PPV_NODE_TERMINAL) != 0u;
     return w;
 }
 
@@ -153,7 +213,7 @@ __global__ __launch_bounds__(MASK_THREADS) void mask_kernel(IndexView ix, const 
     extern __shared__ __align__(16) uint32_t smem[];
     const int n_words = ix.n_words;
     uint32_t *img = smem;            // [n_words]
-    uint32_t *bc = smem + n_words;   // [2]: node, found
+    uint32_t *bc = smem + n_words;   // [4]: node, found, cb, ce
     const int b = blockIdx.x, tid = threadIdx.x, lane = tid & (WAVE - 1), wave = tid / WAVE;
     if (wave == 0) {
         int t = lens[b];
@@ -162,6 +222,8 @@ __global__ __launch_bounds__(MASK_THREADS) void mask_kernel(IndexView ix, const 
         if (lane == 0) {
             bc[0] = w.node;
             bc[1] = w.found ? 1u : 0u;
+            bc[2] = w.found ? w.cb : 0u;
+            bc[3] = w.found ? w.ce : 0u;
             if (range_lo) range_lo[b] = w.lo;
             if (range_hi) range_hi[b] = w.hi;
             if (member) member[b] = w.member ? 1 : 0;
@@ -170,17 +232,12 @@ __global__ __launch_bounds__(MASK_THREADS) void mask_kernel(IndexView ix, const 
     __syncthreads();
     const uint32_t node = bc[0];
     const bool found = bc[1] != 0u;
+    const uint32_t cb = bc[2], ce = bc[3];
     uint32_t *out = mask + (size_t)b * (size_t)n_words;
-    const uint32_t slot = found ? heavy_slot_of(ix, node) : PPV_NO_SLOT;
-    if (slot != PPV_NO_SLOT) {  // ready-made image: plain copy
-        const uint32_t *src = ix.heavy_bits + (size_t)slot * (size_t)n_words;
+    if (found && ce - cb > ix.heavy_min) {  // ready-made image: plain copy
+        const uint32_t *src = ix.heavy_bits + (size_t)heavy_slot_of(ix, node) * (size_t)n_words;
         for (int i = tid; i < n_words; i += MASK_THREADS) out[i] = src[i];
         return;
-    }
-    uint32_t cb = 0, ce = 0;
-    if (found) {
-        cb = ix.child_off[node];
-        ce = ix.child_off[node + 1];
     }
     if (cb == ce) {  // not in S, or a member without extensions
         for (int i = tid; i < n_words; i += MASK_THREADS) out[i] = 0u;
@@ -189,7 +246,7 @@ __global__ __launch_bounds__(MASK_THREADS) void mask_kernel(IndexView ix, const 
     for (int i = tid; i < n_words; i += MASK_THREADS) img[i] = 0u;
     __syncthreads();
     for (uint32_t i = cb + (uint32_t)tid; i < ce; i += MASK_THREADS) {
-        uint32_t v = ix.node_tok[i] & PPV_NODE_TOKEN;
+        uint32_t v = ix.ent[i].tok & PPV_NODE_TOKEN;
         atomicOr(&img[v >> 5], 1u << (v & 31u));
     }
     __syncthreads();
@@ -385,7 +442,7 @@ __device__ inline int locate_in_tile(const RawTile &rt, uint32_t tile_word, int 
             grp += e[k];
             if (e[k] > 0.f) my_last = k;
         }
-        const double incl = before + wave_incl_scan((double)grp, lane);
+        const double incl = before + wave_incl_scan((double)grp);
         const uint64_t cross = __ballot(incl > target);
         const int first_tok = tile * G::TILE + j * G::PER_LOAD;
         if (cross) {
@@ -400,14 +457,14 @@ __device__ inline int locate_in_tile(const RawTile &rt, uint32_t tile_word, int 
                 if (id < 0) id = my_last;  // rounding inside the group
                 id += first_tok + lane * G::EPL;
             }
-            return __shfl(id, l, WAVE);
+            return lane_value(id, l);
         }
         const uint64_t have = __ballot(my_last >= 0);
         if (have) {
             const int l = 63 - __clzll((long long)have);
-            last_valid = __shfl(first_tok + lane * G::EPL + my_last, l, WAVE);
+            last_valid = lane_value(first_tok + lane * G::EPL + my_last, l);
         }
-        before = __shfl(incl, WAVE - 1, WAVE);
+        before = last_lane(incl);
     }
     return last_valid;
 }
@@ -419,7 +476,8 @@ struct RowShared {
     float tile_zall[MAX_TILES];
     float tile_zval[MAX_TILES];
     float tile_ref[MAX_TILES];         // what tile_zval is relative to (the tile maximum, or the valid maximum)
-    uint32_t list_tok[PPV_LIST_MAX];   // valid tokens in increasing order (list path); bit 31 may carry a flag
+    uint32_t list_tok[PPV_LIST_MAX + 1];    // valid tokens in increasing order (list path), flags in the top bits
+    uint32_t list_child[PPV_LIST_MAX + 1];  // decode step: child offsets of the listed entries
     float list_e[PPV_LIST_MAX];        // exp(l - slice max) per listed token
     float slice_m[MAX_SLICES];
     float slice_z[MAX_SLICES];
@@ -449,10 +507,25 @@ __device__ inline RowOut row_sample(const T *__restrict__ row, int V, const RawT
     const int lane = tid & (WAVE - 1), wave = tid / WAVE;
     const int nt = (V + G::TILE - 1) / G::TILE;
 
-    // ---- stream: every tile once
+    // ---- list path, part 1: ask for the listed tokens' logits now (they are being streamed
+    // anyway, so these are cache hits) so that they arrive while the tiles are reduced
+    const int ns = (n_list + WAVE - 1) / WAVE;
+    float gx = -INFINITY;   // this lane's listed logit of the wave's first slice
+    if (mode == VALID_LIST && wave < ns) {
+        const int i = wave * WAVE + lane;
+        if (i < n_list) {
+            const uint32_t v = sh.list_tok[i] & PPV_NODE_TOKEN;
+            if (sizeof(T) == 4) gx = __uint_as_float(((const uint32_t *)row)[v]);
+            else gx = __uint_as_float(((uint32_t)((const uint16_t *)row)[v]) << 16);
+        }
+    }
+
+    // ---- stream: every tile once; the wave's next tile is requested before the current one is reduced
     RawTile rt = first;
     for (int k = wave; k < nt; k += nw) {
-        if (k != wave) load_tile<T>(row, V, k, lane, rt);
+        RawTile nx;
+        const bool more = k + nw < nt;
+        if (more) load_tile<T>(row, V, k + nw, lane, nx);
         float m, zall, zval;
         if (mode == VALID_IMAGE) {
             const uint32_t word = (lane < G::WORDS) ? image_word(image, k * G::WORDS + lane, V) : 0u;
@@ -466,17 +539,20 @@ __device__ inline RowOut row_sample(const T *__restrict__ row, int V, const RawT
             sh.tile_zval[k] = zval;
             sh.tile_ref[k] = m;
         }
+        if (more) rt = nx;
     }
-    // ---- list path: gather the listed tokens' logits (just streamed: cache hits), 64 per slice
-    const int ns = (n_list + WAVE - 1) / WAVE;
+    // ---- list path, part 2: sums per slice of 64 listed tokens, relative to the slice maximum
     if (mode == VALID_LIST) {
         for (int s = wave; s < ns; s += nw) {
             const int i = s * WAVE + lane;
-            float x = -INFINITY;
-            if (i < n_list) {
-                const uint32_t v = sh.list_tok[i] & PPV_NODE_TOKEN;
-                if (sizeof(T) == 4) x = __uint_as_float(((const uint32_t *)row)[v]);
-                else x = __uint_as_float(((uint32_t)((const uint16_t *)row)[v]) << 16);
+            float x = gx;
+            if (s != wave) {
+                x = -INFINITY;
+                if (i < n_list) {
+                    const uint32_t v = sh.list_tok[i] & PPV_NODE_TOKEN;
+                    if (sizeof(T) == 4) x = __uint_as_float(((const uint32_t *)row)[v]);
+                    else x = __uint_as_float(((uint32_t)((const uint16_t *)row)[v]) << 16);
+                }
             }
             const float m = wave_max(x);
             float e = 0.f;
@@ -550,12 +626,12 @@ __device__ inline RowOut row_sample(const T *__restrict__ row, int V, const RawT
 
     // ---- locate: wave 0
     if (wave == 0) {
-        const double log_za = log(za);
+        const float l2za = fast_log2((float)za);
         int id = -1, pos = -1;
         float lzv = -INFINITY;
         if (mode == VALID_IMAGE) {
             if (zv > 0.0) {
-                lzv = (float)(((double)R - (double)M) + log(zv) - log_za);
+                lzv = (R - M) + LN2F * (fast_log2((float)zv) - l2za);
                 const double tau = (double)u * zv;
                 // first tile whose cumulative valid weight exceeds tau
                 double carry = 0.0, before = 0.0;
@@ -565,17 +641,17 @@ __device__ inline RowOut row_sample(const T *__restrict__ row, int V, const RawT
                     double w = 0.0;
                     if (k < nt && sh.tile_zval[k] > 0.f)
                         w = (double)sh.tile_zval[k] * (double)exp_scale(sh.tile_ref[k] - R);
-                    const double incl = carry + wave_incl_scan(w, lane);
+                    const double incl = carry + wave_incl_scan(w);
                     const uint64_t cross = __ballot(incl > tau);
                     const uint64_t have = __ballot(w > 0.0);
                     if (cross) {
                         const int l = __ffsll((long long)cross) - 1;
                         kstar = k0 + l;
-                        before = __shfl(incl - w, l, WAVE);
+                        before = lane_value(incl - w, l);
                     } else if (have) {
                         klast = k0 + 63 - __clzll((long long)have);
                     }
-                    carry = __shfl(incl, WAVE - 1, WAVE);
+                    carry = last_lane(incl);
                 }
                 double target;
                 int kt;
@@ -601,9 +677,9 @@ __device__ inline RowOut row_sample(const T *__restrict__ row, int V, const RawT
                     sc = (double)exp_scale(sh.slice_m[lane] - Mv);
                     w = (double)sh.slice_z[lane] * sc;
                 }
-                const double incl = wave_incl_scan(w, lane);
-                const double zvl = __shfl(incl, WAVE - 1, WAVE);
-                lzv = (float)(((double)Mv - (double)M) + log(zvl) - log_za);
+                const double incl = wave_incl_scan(w);
+                const double zvl = last_lane(incl);
+                lzv = (Mv - M) + LN2F * (fast_log2((float)zvl) - l2za);
                 const double tau = (double)u * zvl;
                 const uint64_t cross = __ballot(incl > tau);
                 const uint64_t have = __ballot(w > 0.0);
@@ -611,14 +687,14 @@ __device__ inline RowOut row_sample(const T *__restrict__ row, int V, const RawT
                 double target;
                 if (cross) {
                     s = __ffsll((long long)cross) - 1;
-                    target = (tau - __shfl(incl - w, s, WAVE)) / __shfl(sc, s, WAVE);
+                    target = (tau - lane_value(incl - w, s)) / lane_value(sc, s);
                 } else {
                     s = 63 - __clzll((long long)have);
                     target = INFINITY;
                 }
                 const int i = s * WAVE + lane;
                 const float e = (i < n_list) ? sh.list_e[i] : 0.f;
-                const double ic = wave_incl_scan((double)e, lane);
+                const double ic = wave_incl_scan((double)e);
                 const uint64_t c2 = __ballot(e > 0.f && ic > target);
                 const uint64_t h2 = __ballot(e > 0.f);
                 const int l = c2 ? __ffsll((long long)c2) - 1 : 63 - __clzll((long long)h2);
@@ -630,7 +706,7 @@ __device__ inline RowOut row_sample(const T *__restrict__ row, int V, const RawT
             sh.bc_i[0] = id;
             sh.bc_i[1] = pos;
             sh.bc_f[0] = lzv;
-            sh.bc_f[1] = (float)((double)M + log_za);
+            sh.bc_f[1] = M + LN2F * l2za;
         }
     }
     __syncthreads();
@@ -681,7 +757,7 @@ __global__ __launch_bounds__(MAX_WAVES *WAVE) void sample_kernel(const T *__rest
             base = wave_sum(base);
             const int wi = k * G::WORDS + lane;
             uint32_t w = (lane < G::WORDS) ? image_word(mrow, wi, V) : 0u;
-            int at = base + wave_incl_scan((int)__popc(w), lane) - (int)__popc(w);
+            int at = base + wave_incl_scan((int)__popc(w)) - (int)__popc(w);
             while (w) {
                 const int bit = __ffs((int)w) - 1;
                 sh.list_tok[at++] = (uint32_t)(wi * 32 + bit);
@@ -699,68 +775,112 @@ __global__ __launch_bounds__(MAX_WAVES *WAVE) void sample_kernel(const T *__rest
 }
 
 // ------------------------------------------------------------------------------------------
-// ppv_decode_step: locate the prefix, take its children as the valid set (list, or the ready-made
+// ppv_decode_begin: one wavefront per row walks the row's current prefix and leaves the cursor.
+__global__ __launch_bounds__(MASK_THREADS) void decode_begin_kernel(IndexView ix, const int32_t *__restrict__ prefixes,
+                                                                    int32_t stride, const int32_t *__restrict__ lens,
+                                                                    int B, RowState *__restrict__ state,
+                                                                    uint8_t *__restrict__ active,
+                                                                    float *__restrict__ logx) {
+    const int lane = threadIdx.x & (WAVE - 1);
+    const int b = blockIdx.x * (MASK_THREADS / WAVE) + threadIdx.x / WAVE;
+    if (b >= B) return;  // uniform per wave
+    int t = lens[b];
+    t = t < 0 ? 0 : (t > stride ? stride : t);
+    const Walk w = walk_prefix(ix, prefixes + (size_t)b * (size_t)stride, t, lane);
+    if (lane == 0) {
+        RowState st;
+        st.node = w.found ? w.node : PPV_NO_SLOT;
+        st.cb = w.found ? w.cb : 0u;
+        st.ce = w.found ? w.ce : 0u;
+        st.slot = (w.found && w.ce - w.cb > ix.heavy_min) ? heavy_slot_of(ix, w.node) : PPV_NO_SLOT;
+        state[b] = st;
+        active[b] = (w.found && !w.member) ? 1 : 0;
+        if (logx) logx[b] = 0.f;
+    }
+}
+
+// ppv_decode_step: take the children of the row's prefix as the valid set (list, or the ready-made
 // image of a heavy node), stream + sample, append, and report whether the extended row is in S.
 template <typename T>
 __global__ __launch_bounds__(MAX_WAVES *WAVE) void decode_step_kernel(
     IndexView ix, int32_t *__restrict__ prefixes, int32_t stride, int32_t *__restrict__ lens,
-    uint8_t *__restrict__ active, const T *__restrict__ logits, int64_t row_stride,
+    uint8_t *__restrict__ active, RowState *__restrict__ state, const T *__restrict__ logits, int64_t row_stride,
     const float *__restrict__ uniforms, int32_t *__restrict__ ids, float *__restrict__ logZ_valid,
     float *__restrict__ logx) {
     using G = TileGeom<T>;
     __shared__ RowShared sh;
     const int b = blockIdx.x, tid = threadIdx.x, lane = tid & (WAVE - 1), wave = tid / WAVE;
     const int nw = blockDim.x / WAVE;
-    if (!active[b]) return;  // uniform for the workgroup
+    // the three independent per-row loads go out together
+    const uint8_t on = active[b];
+    int t = lens[b];
+    RowState st;
+    if (state) st = state[b];
+    const float u = uniforms[b];
+    if (!on) return;  // uniform for the workgroup
     const int V = ix.vocab;
     const T *row = logits + (size_t)b * (size_t)row_stride;
     const int nt = (V + G::TILE - 1) / G::TILE;
     RawTile first;
-    if (wave < nt) load_tile<T>(row, V, wave, lane, first);   // in flight during the walk
-    int t = lens[b];
+    if (wave < nt) load_tile<T>(row, V, wave, lane, first);   // in flight during the index work
     t = t < 0 ? 0 : (t > stride ? stride : t);
-    if (wave == 0) {
-        Walk w = walk_prefix(ix, prefixes + (size_t)b * (size_t)stride, t, lane);
-        if (lane == 0) {
-            sh.bc_i[4] = (int)w.node;
-            sh.bc_i[5] = w.found ? 1 : 0;
+    if (!state) {  // no cursor: locate the prefix from the root (wave 0), then share it
+        if (wave == 0) {
+            const Walk w = walk_prefix(ix, prefixes + (size_t)b * (size_t)stride, t, lane);
+            if (lane == 0) {
+                sh.bc_i[4] = (int)(w.found ? w.node : PPV_NO_SLOT);
+                sh.bc_i[5] = (int)(w.found ? w.cb : 0u);
+                sh.bc_i[6] = (int)(w.found ? w.ce : 0u);
+            }
         }
+        __syncthreads();
+        st.node = (uint32_t)sh.bc_i[4];
+        st.cb = (uint32_t)sh.bc_i[5];
+        st.ce = (uint32_t)sh.bc_i[6];
+        st.slot = (st.node != PPV_NO_SLOT && st.ce - st.cb > ix.heavy_min) ? heavy_slot_of(ix, st.node) : PPV_NO_SLOT;
     }
-    __syncthreads();
-    const uint32_t node = (uint32_t)sh.bc_i[4];
-    const bool found = sh.bc_i[5] != 0;
-    uint32_t cb = 0, ce = 0;
-    if (found) {
-        cb = ix.child_off[node];
-        ce = ix.child_off[node + 1];
-    }
+    const uint32_t cb = st.cb, ce = st.ce, slot = st.slot;
     const int nchild = (int)(ce - cb);
-    const uint32_t slot = found ? heavy_slot_of(ix, node) : PPV_NO_SLOT;
     const int mode = nchild == 0 ? VALID_NONE : (slot != PPV_NO_SLOT ? VALID_IMAGE : VALID_LIST);
     const uint32_t *image = ix.heavy_bits + (size_t)(slot != PPV_NO_SLOT ? slot : 0) * (size_t)ix.n_words;
-    if (mode == VALID_LIST) {  // children are sorted by token: the list is ready as it is
-        for (int i = tid; i < nchild; i += nw * WAVE) sh.list_tok[i] = ix.node_tok[cb + i];
+    if (mode == VALID_LIST) {
+        // children are sorted by token: the list is ready as it is.  One entry more than the
+        // children is taken along: it closes the last child's own children range.
+        for (int i = tid; i <= nchild; i += nw * WAVE) {
+            const NodeEnt e = ix.ent[cb + i];
+            sh.list_tok[i] = e.tok;
+            sh.list_child[i] = e.child;
+        }
         __syncthreads();
     }
-    RowOut r = row_sample<T>(row, V, first, mode, mode == VALID_LIST ? nchild : 0, image, uniforms[b], sh, tid, nw);
+    RowOut r = row_sample<T>(row, V, first, mode, mode == VALID_LIST ? nchild : 0, image, u, sh, tid, nw);
     if (tid == 0) {
         const bool room = t < stride;
         int32_t id = -1;
         bool done = true;  // no valid token or no room: the row cannot continue
         if (r.id >= 0 && room) {
             id = r.id;
-            uint32_t entry;
+            RowState nx;
+            uint32_t tokw;
             if (mode == VALID_LIST) {
-                entry = sh.list_tok[r.pos];
+                nx.node = cb + (uint32_t)r.pos;
+                tokw = sh.list_tok[r.pos];
+                nx.cb = sh.list_child[r.pos];
+                nx.ce = sh.list_child[r.pos + 1];
             } else {  // child index = children before the token's word + set bits below it in the word
                 const uint32_t wv = image[id >> 5];
-                const uint32_t j = cb + ix.heavy_rank[(size_t)slot * (size_t)ix.n_words + (id >> 5)] +
-                                   (uint32_t)__popc(wv & ((1u << (id & 31)) - 1u));
-                entry = ix.node_tok[j];
+                nx.node = cb + ix.heavy_rank[(size_t)slot * (size_t)ix.n_words + (id >> 5)] +
+                          (uint32_t)__popc(wv & ((1u << (id & 31)) - 1u));
+                const NodeEnt e0 = ix.ent[nx.node], e1 = ix.ent[nx.node + 1];
+                tokw = e0.tok;
+                nx.cb = e0.child;
+                nx.ce = e1.child;
             }
-            done = (entry & PPV_NODE_TERMINAL) != 0u;   // the extended row is itself a member
+            nx.slot = (tokw & PPV_NODE_HEAVY) ? heavy_slot_of(ix, nx.node) : PPV_NO_SLOT;
+            done = (tokw & PPV_NODE_TERMINAL) != 0u;   // the extended row is itself a member
             prefixes[(size_t)b * (size_t)stride + t] = id;
             lens[b] = t + 1;
+            if (state) state[b] = nx;
             if (logx) logx[b] += r.logZ_valid;
         }
         if (ids) ids[b] = id;
@@ -778,12 +898,21 @@ ppv_status check_logits_args(const void *logits, ppv_dtype dt, int64_t row_strid
     return PPV_OK;
 }
 
-// wavefronts per row: one per tile, at most MAX_WAVES, a power of two
-int waves_for(int V, ppv_dtype dt) {
+// Wavefronts per row (a power of two, at most one per tile).  A small batch is bound by latency:
+// eight wavefronts per row keep the whole row in flight at once (sixteen measured no better).
+// A large batch is bound by throughput: four wavefronts per row let several rows share a compute
+// unit, so that one row's reduction and sampling overlap another row's loads (measured on the
+// N=1M, V=32k decode loop: 2.1 TB/s with 16, 4.3 TB/s with 4 at B=4096).
+int waves_for(int V, ppv_dtype dt, int B) {
     const int tile = (dt == PPV_F32) ? TileGeom<float>::TILE : TileGeom<uint16_t>::TILE;
     const int nt = (V + tile - 1) / tile;
+    int cap = (B <= 512) ? 8 : 4;
+    if (const char *e = getenv("PPV_WAVES_PER_ROW")) {  // tuning aid
+        const int v = atoi(e);
+        if (v >= 1 && v <= MAX_WAVES) cap = v;
+    }
     int nw = 1;
-    while (nw < nt && nw < MAX_WAVES) nw <<= 1;
+    while (nw < nt && nw * 2 <= cap) nw <<= 1;
     return nw;
 }
 
@@ -795,7 +924,7 @@ extern "C" ppv_status ppv_next_token_mask(const ppv_index_t *ix, const int32_t *
     if (!ix || B < 0 || prefix_stride < 0) return PPV_EINVAL;
     if (B == 0) return PPV_OK;  // nothing to do; the (possibly null) buffers are not looked at
     if (!prefixes || !lens || !mask) return PPV_EINVAL;
-    const size_t lds = ((size_t)ix->view.n_words + 2) * sizeof(uint32_t);
+    const size_t lds = ((size_t)ix->view.n_words + 4) * sizeof(uint32_t);
     hipLaunchKernelGGL(mask_kernel, dim3((unsigned)B), dim3(MASK_THREADS), lds, (hipStream_t)stream, ix->view,
                        prefixes, prefix_stride, lens, mask, range_lo, range_hi, member);
     PPV_HIP_TRY(hipGetLastError());
@@ -812,7 +941,7 @@ extern "C" ppv_status constrained_sample(const void *logits, ppv_dtype dt, int64
     if (st != PPV_OK) return st;
     const int n_words = (V + 31) / 32;
     const int list_max = V / 32 < PPV_LIST_MAX ? V / 32 : PPV_LIST_MAX;
-    const int threads = waves_for(V, dt) * WAVE;
+    const int threads = waves_for(V, dt, B) * WAVE;
     if (dt == PPV_F32)
         hipLaunchKernelGGL(sample_kernel<float>, dim3((unsigned)B), dim3(threads), 0, (hipStream_t)stream,
                            (const float *)logits, row_stride, mask, uniforms, V, n_words, list_max, ids, logZ_valid,
@@ -825,24 +954,38 @@ extern "C" ppv_status constrained_sample(const void *logits, ppv_dtype dt, int64
     return PPV_OK;
 }
 
+extern "C" ppv_status ppv_decode_begin(const ppv_index_t *ix, const int32_t *prefixes, int32_t prefix_stride,
+                                       const int32_t *lens, int32_t B, uint32_t *state, uint8_t *active, float *logx,
+                                       void *stream) {
+    if (!ix || B < 0 || prefix_stride < 0) return PPV_EINVAL;
+    if (B == 0) return PPV_OK;
+    if (!prefixes || !lens || !state || !active) return PPV_EINVAL;
+    const int rows_per_wg = MASK_THREADS / WAVE;
+    hipLaunchKernelGGL(decode_begin_kernel, dim3((unsigned)((B + rows_per_wg - 1) / rows_per_wg)), dim3(MASK_THREADS), 0,
+                       (hipStream_t)stream, ix->view, prefixes, prefix_stride, lens, B, (RowState *)state, active,
+                       logx);
+    PPV_HIP_TRY(hipGetLastError());
+    return PPV_OK;
+}
+
 extern "C" ppv_status ppv_decode_step(const ppv_index_t *ix, int32_t *prefixes, int32_t prefix_stride, int32_t *lens,
-                                      uint8_t *active, const void *logits, ppv_dtype dt, int64_t row_stride,
-                                      const float *uniforms, int32_t B, int32_t *ids, float *logZ_valid, float *logx,
-                                      void *stream) {
+                                      uint8_t *active, uint32_t *state, const void *logits, ppv_dtype dt,
+                                      int64_t row_stride, const float *uniforms, int32_t B, int32_t *ids,
+                                      float *logZ_valid, float *logx, void *stream) {
     if (!ix || B < 0 || prefix_stride < 0) return PPV_EINVAL;
     if (B == 0) return PPV_OK;
     if (!prefixes || !lens || !active || !uniforms) return PPV_EINVAL;
     ppv_status st = check_logits_args(logits, dt, row_stride, ix->view.vocab);
     if (st != PPV_OK) return st;
-    const int threads = waves_for(ix->view.vocab, dt) * WAVE;
+    const int threads = waves_for(ix->view.vocab, dt, B) * WAVE;
     if (dt == PPV_F32)
         hipLaunchKernelGGL(decode_step_kernel<float>, dim3((unsigned)B), dim3(threads), 0, (hipStream_t)stream,
-                           ix->view, prefixes, prefix_stride, lens, active, (const float *)logits, row_stride,
-                           uniforms, ids, logZ_valid, logx);
+                           ix->view, prefixes, prefix_stride, lens, active, (RowState *)state, (const float *)logits,
+                           row_stride, uniforms, ids, logZ_valid, logx);
     else
         hipLaunchKernelGGL(decode_step_kernel<uint16_t>, dim3((unsigned)B), dim3(threads), 0, (hipStream_t)stream,
-                           ix->view, prefixes, prefix_stride, lens, active, (const uint16_t *)logits, row_stride,
-                           uniforms, ids, logZ_valid, logx);
+                           ix->view, prefixes, prefix_stride, lens, active, (RowState *)state,
+                           (const uint16_t *)logits, row_stride, uniforms, ids, logZ_valid, logx);
     PPV_HIP_TRY(hipGetLastError());
     return PPV_OK;
 }

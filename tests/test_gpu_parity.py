@@ -126,16 +126,24 @@ def test_decode_step_equals_mask_plus_sample(name):
     assert np.array_equal(gA[ext], (q.member == 0).astype(np.uint8))
 
 
-def test_decode_loop_parity_small():
-    """Algorithm 1's SampleCandidate loop on a scaled C3: the HIP loop and the oracle loop are kept
-    on the same path (an excused boundary disagreement is forced onto the oracle's side)."""
+@pytest.mark.parametrize("use_state", [False, True])
+def test_decode_loop_parity_small(use_state):
+    """Algorithm 1's SampleCandidate loop on a scaled C3, step by step against the oracle's loop,
+    with the cursor kept by ppv_decode_begin/ppv_decode_step and without it."""
     cfg, S, trie, index = setup_case("C3s")
     B = 64
     stride = index.l_max
     dP = torch.full((B, stride), W.PAD_TOKEN, dtype=torch.int32, device=DEV)
     dL = torch.zeros(B, dtype=torch.int32, device=DEV)
     dA = torch.ones(B, dtype=torch.uint8, device=DEV)
-    logx = torch.zeros(B, dtype=torch.float32, device=DEV)
+    logx = torch.full((B,), 9.0, dtype=torch.float32, device=DEV)
+    state = None
+    if use_state:
+        state = torch.zeros((B, ppv.PPV_STATE_WORDS), dtype=torch.int32, device=DEV)
+        dA.zero_()
+        ppv.ppv_decode_begin(index, dP, dL, state, dA, logx)
+    else:
+        logx.zero_()
     ids = torch.zeros(B, dtype=torch.int32, device=DEV)
     lz = torch.zeros(B, dtype=torch.float32, device=DEV)
     gpu_ids, gpu_lz = [], []
@@ -148,7 +156,7 @@ def test_decode_loop_parity_small():
         assert np.array_equal(act_before, res.active_per_step[s]), s
         ids.fill_(-5)
         ppv.ppv_decode_step(index, dP, dL, dA, logits_to_dev(cfg, W.make_logits(cfg, batch=B, step=100 + s)),
-                            to_dev(un(s)), ids, lz, logx)
+                            to_dev(un(s)), ids, lz, logx, state=state)
         torch.cuda.synchronize()
         gid, glz = ids.cpu().numpy(), lz.cpu().numpy()
         rows = np.nonzero(act_before)[0]
@@ -170,6 +178,46 @@ def test_decode_loop_parity_small():
     for b in range(B):
         assert np.array_equal(gP[b, :res.lens[b]], res.seqs[b, :res.lens[b]])
     assert np.allclose(logx.cpu().numpy(), res.logx, rtol=1e-3, atol=1e-3)
+
+
+def test_decode_begin_from_given_prefixes():
+    """Resuming from arbitrary prefixes: active = (prefix of a member) and not (member); one step with
+    the cursor equals one step without it."""
+    cfg, S, trie, index = setup_case("C2")
+    pb = W.make_prefix_batch(cfg, S, index=11)
+    B = pb.prefixes.shape[0]
+    full = [S.seq(i) for i in range(0, 40, 5)]                 # add some whole members (member => inactive)
+    P = np.full((B + len(full), pb.stride + 1), W.PAD_TOKEN, np.int32)
+    L = np.zeros(B + len(full), np.int32)
+    P[:B, :pb.stride] = pb.prefixes
+    L[:B] = pb.lens
+    for i, q in enumerate(full):
+        P[B + i, :len(q)] = q
+        L[B + i] = len(q)
+    n = B + len(full)
+    ref = trie.query(P, L, want_mask=False)
+    outs = []
+    logits = W.make_logits(cfg, batch=n, step=12)
+    un = W.make_uniforms(cfg, batch=n, step=12)
+    for use_state in (True, False):
+        dP, dL = to_dev(P), to_dev(L)
+        dA = torch.full((n,), 3, dtype=torch.uint8, device=DEV)
+        logx = torch.full((n,), 4.0, dtype=torch.float32, device=DEV)
+        state = torch.zeros((n, ppv.PPV_STATE_WORDS), dtype=torch.int32, device=DEV)
+        ppv.ppv_decode_begin(index, dP, dL, state, dA, logx)
+        torch.cuda.synchronize()
+        want_active = ((ref.hi > ref.lo) & (ref.member == 0)).astype(np.uint8)
+        assert np.array_equal(dA.cpu().numpy(), want_active)
+        assert (logx.cpu().numpy() == 0).all()
+        ids = torch.full((n,), -9, dtype=torch.int32, device=DEV)
+        lz = torch.full((n,), 5.0, dtype=torch.float32, device=DEV)
+        ppv.ppv_decode_step(index, dP, dL, dA, logits_to_dev(cfg, logits), to_dev(un), ids, lz, logx,
+                            state=state if use_state else None)
+        torch.cuda.synchronize()
+        outs.append([t.cpu().numpy() for t in (dP, dL, dA, ids, lz, logx)])
+    for a, b in zip(*outs):
+        assert np.array_equal(a, b)
+    assert (outs[0][3][want_active == 0] == -9).all() and (outs[0][3][want_active == 1] >= 0).all()
 
 
 # ------------------------------------------------------------------------------------------ edge cases
