@@ -26,6 +26,11 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0  # MI355X published peak HBM3E bandwidth
 
+# HBM bytes per launch of the dominant kernel from rocprofv3 counter runs (FETCH_SIZE + WRITE_SIZE, each
+# scaled by what the same counter reads for a plain copy of known size); see profiles/.  Keyed by
+# (workload, batch); None until measured for that shape.
+TRAFFIC_BYTES_PER_LAUNCH = {("C3", 256): 9795931}   # profiles/decode_step_C3_B256.md
+
 
 def algorithmic_bytes_per_prefix_step(V: int, elem: int, n_children: float) -> float:
     """What one row of one fused decode step has to move through HBM: the logits row once; the
@@ -82,15 +87,21 @@ class LoopBench:
                 events[s][1].record()
 
     def time(self, warmup, steps):
+        """Wall-clock seconds of `steps` loops (synchronised on both sides), the same region in GPU time
+        by HIP events on the launch stream, and the rows' final lengths."""
         torch = self.torch
         for _ in range(warmup):
             self.run()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         torch.cuda.synchronize()
         t0 = time.perf_counter()
+        e0.record()
         for _ in range(steps):
             self.run()
+        e1.record()
         torch.cuda.synchronize()
         elapsed = time.perf_counter() - t0
+        self.gpu_seconds = e0.elapsed_time(e1) * 1e-3
         assert not self.active.any().item(), "a row did not finish"
         final_lens = self.lens.cpu().numpy().astype("int64")
         return elapsed, final_lens
@@ -122,6 +133,8 @@ def main() -> int:
     ap.add_argument("--no-graph", action="store_true", help="launch every decode step eagerly from Python")
     ap.add_argument("--no-sweep", action="store_true", help="skip the batch sweep (B = 1024, 4096 replicas)")
     ap.add_argument("--verbose", action="store_true", help="per-decode-step table on stderr")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="only run a plain 256 MiB device copy a few times (reference for the HBM counters) and exit")
     args = ap.parse_args()
     if args.gpus != 1:
         print(f"bench.py: this build runs on one GPU only (got --gpus {args.gpus}); the path is data-parallel "
@@ -137,6 +150,15 @@ def main() -> int:
         print("bench.py: no GPU visible; the HIP path has no CPU fallback", file=sys.stderr)
         return 3
     dev = "cuda:0"
+    if args.copy_calibration:
+        n = 256 << 20
+        src = torch.full((n // 4,), 1.0, dtype=torch.float32, device=dev)
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            torch.add(src, 1.0, out=dst)                       # one elementwise kernel: reads n bytes, writes n bytes
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_calibration_bytes_read": n, "copy_calibration_bytes_written": n, "launches": 5}))
+        return 0
     cfg = W.CONFIGS[args.config]
     if args.n_seq:
         cfg = W.scaled(cfg, args.n_seq)
@@ -163,23 +185,30 @@ def main() -> int:
     ms_per_step = elapsed / args.steps * 1e3
     value = prefix_steps * args.steps / elapsed
 
-    # ---- dominant kernel (the fused decode step): algorithmic bytes per launch / average launch duration
-    dur_ms = lb.launch_durations()
+    # ---- dominant kernel (the fused decode step): algorithmic bytes per launch / average launch duration.
+    # Average duration = GPU time of the timed region (HIP events on the launch stream) / launches in it;
+    # the region also holds one tiny fill and one ppv_decode_begin per loop (about 1 % of it).
+    gpu_seconds = lb.gpu_seconds
+    dur_ms = lb.launch_durations() if args.verbose else None
     seqs = lb.prefixes.cpu().numpy()
     fan = fanout_along(index, ppv, torch, seqs, final_lens, L, dev)  # mean children of the prefixes reached at step s
     bytes_per_launch = np.array([active_per_step[s] * algorithmic_bytes_per_prefix_step(V, 2, fan[s]) for s in range(L)])
     if args.verbose:
+        print("per-launch figures below are eager launches with an event pair around each (a few us of event "
+              "overhead included)", file=sys.stderr)
         for s_ in range(L):
             print(f"step {s_:2d} active {active_per_step[s_]:4d} fanout {fan[s_]:9.1f} launch {dur_ms[s_] * 1e3:8.2f} us "
                   f"{bytes_per_launch[s_] / max(dur_ms[s_], 1e-9) / 1e6:8.1f} GB/s", file=sys.stderr)
-    busy = active_per_step > 0
-    achieved = float(bytes_per_launch[busy].sum() / (dur_ms[busy].sum() * 1e-3) / 1e9)
+    n_launch = L                                               # every loop launches all l_max steps
+    avg_launch_s = gpu_seconds / (args.steps * n_launch)
+    bytes_per_launch_avg = float(bytes_per_launch.sum() / n_launch)
+    achieved = bytes_per_launch_avg / avg_launch_s / 1e9
     roofline = {"bound": "hbm", "kernel": "decode_step_kernel<bf16>", "achieved": round(achieved, 1),
-                "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
-                "avg_launch_us": round(float(dur_ms[busy].mean() * 1e3), 2), "launches_per_step": int(busy.sum()),
-                "bytes_per_launch_avg": int(bytes_per_launch[busy].mean()),
-                "full_batch_launch": {"rows": int(active_per_step[0]), "us": round(float(dur_ms[0] * 1e3), 2),
-                                      "GBs": round(float(bytes_per_launch[0] / (dur_ms[0] * 1e-3) / 1e9), 1)}}
+                "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
+                "traffic": TRAFFIC_BYTES_PER_LAUNCH.get((cfg.name, B)),
+                "avg_launch_us": round(avg_launch_s * 1e6, 2), "launches_per_step": n_launch,
+                "bytes_per_launch": int(bytes_per_launch_avg),
+                "rows_per_launch_avg": round(float(active_per_step.mean()), 1)}
 
     out = {
         "metric": "constrained decode steps (prefixes)/sec at N=1M, V=32k", "value": round(value, 1),
@@ -193,7 +222,6 @@ def main() -> int:
                               ("captured once in a HIP graph and replayed" if lb.graph is not None else "launched eagerly") +
                               ", no host sync inside a loop")},
         "roofline": roofline,
-        "achieved_GBs_whole_loop": round(float(bytes_per_launch.sum() / (elapsed / args.steps) / 1e9), 1),
         "index_build_s": round(t_build, 3), "index_device_MB": round(index.device_bytes / 1e6, 1),
     }
 
