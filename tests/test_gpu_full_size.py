@@ -1,0 +1,151 @@
+"""Parity at the full sizes of the workload configs, in the launch configurations bench.py times:
+C3 (N = 1M, V = 32k) as the whole decode loop replayed from a HIP graph, C4 (N ~ 10M, V = 1,024,
+B = 4,096) and C5 (N = 5M, V = 256k, B = 1,024) as mask call + sample call.  The oracle is fast
+enough here to check every row, so nothing is sampled."""
+import sys
+import time
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2504_09135_amd import binding as ppv
+from paper_2504_09135_amd import workloads as W
+
+from gpu_helpers import DEV, assert_query_parity, check_sample_rows, gpu_sample, logits_to_dev, to_dev
+
+pytestmark = [pytest.mark.gpu, pytest.mark.timeout(900)]
+
+
+def say(msg):
+    print(f"[{time.strftime('%H:%M:%S')}] {msg}", file=sys.stderr, flush=True)
+
+
+def build_both(cfg):
+    say(f"{cfg.name}: generating S")
+    S = W.make_constraint_set(cfg)
+    say(f"{cfg.name}: oracle trie over {S.n} sequences")
+    trie = oracle.Trie(S.tokens, S.offsets, cfg.vocab)
+    say(f"{cfg.name}: device index")
+    index = ppv.ppv_build_index(S.tokens, S.offsets, cfg.vocab)
+    assert index.n_distinct == trie.n_members and index.l_max == trie.l_max
+    assert index.n_prefixes == trie.n_nodes - 1
+    return S, trie, index
+
+
+def test_C3_full_decode_loop_graph():
+    cfg = W.CONFIGS["C3"]
+    S, trie, index = build_both(cfg)
+    B, V, L = cfg.batch, cfg.vocab, index.l_max
+    say("C3: logits for all steps")
+    host_logits = [W.make_logits(cfg, step=s) for s in range(L)]
+    host_un = [W.make_uniforms(cfg, step=s) for s in range(L)]
+    logits = torch.empty((L, B, V), dtype=torch.bfloat16, device=DEV)
+    uniforms = torch.empty((L, B), dtype=torch.float32, device=DEV)
+    for s in range(L):
+        logits[s] = logits_to_dev(cfg, host_logits[s])
+        uniforms[s] = to_dev(host_un[s])
+    prefixes = torch.full((B, L), W.PAD_TOKEN, dtype=torch.int32, device=DEV)
+    lens = torch.zeros(B, dtype=torch.int32, device=DEV)
+    active = torch.zeros(B, dtype=torch.uint8, device=DEV)
+    state = torch.zeros((B, ppv.PPV_STATE_WORDS), dtype=torch.int32, device=DEV)
+    logx = torch.zeros(B, dtype=torch.float32, device=DEV)
+    ids = torch.zeros((L, B), dtype=torch.int32, device=DEV)
+    lz = torch.zeros((L, B), dtype=torch.float32, device=DEV)
+    step_logits = [logits[s] for s in range(L)]
+    step_un = [uniforms[s] for s in range(L)]
+    step_ids = [ids[s] for s in range(L)]
+    step_lz = [lz[s] for s in range(L)]
+
+    def loop():
+        lens.zero_()
+        ids.fill_(-5)
+        ppv.ppv_decode_begin(index, prefixes, lens, state, active, logx)
+        for s in range(L):
+            ppv.ppv_decode_step(index, prefixes, lens, active, step_logits[s], step_un[s], step_ids[s], step_lz[s],
+                                logx, state=state)
+
+    loop()
+    torch.cuda.synchronize()
+    eager = [t.cpu().numpy().copy() for t in (prefixes, lens, ids, lz, logx)]
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        loop()
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        loop()
+    for rep in range(3):                       # every replay must reproduce the eager result bit for bit
+        prefixes.fill_(W.PAD_TOKEN)
+        logx.fill_(7.0)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        got = [t.cpu().numpy() for t in (prefixes, lens, ids, lz, logx)]
+        for a, b in zip(eager, got):
+            assert np.array_equal(a.view(np.int32) if a.dtype == np.float32 else a,
+                                  b.view(np.int32) if b.dtype == np.float32 else b), rep
+    gP, gL, gid, glz, glx = eager
+    assert not active.cpu().numpy().any()
+
+    say("C3: oracle loop")
+    # the oracle makes its own choice at every step (recorded) but is kept on the HIP path's sequence, so
+    # that a disagreement inside the CDF band at one step does not invalidate the comparison of later steps
+    res = oracle.decode_loop(trie, B, lambda s, *_: W.logits_as_f32(cfg, host_logits[s]), lambda s: host_un[s],
+                             threads=16, force_ids=lambda s: gid[s])
+    say("C3: comparing")
+    excused = 0
+    for s in range(res.steps):
+        rows = np.nonzero(res.active_per_step[s])[0]
+        assert (gid[s][~res.active_per_step[s]] == -5).all()
+
+        class Sub:
+            pass
+        sub = Sub()
+        sub.ids = res.ids_per_step[s][rows]
+        sub.logZ_valid = res.logZ_per_step[s][rows]
+        sub.logZ_all = None
+        sub.cdf_lo = res.cdf_lo_per_step[s][rows]
+        sub.cdf_hi = res.cdf_hi_per_step[s][rows]
+        masks = {}
+
+        def mask_of(i, s=s, rows=rows, masks=masks):
+            if i not in masks:
+                masks[i] = trie.query(res.seqs[rows[i]:rows[i] + 1], np.array([s], np.int32)).mask[0]
+            return masks[i]
+        excused += check_sample_rows(cfg.dtype, sub, mask_of, host_un[s][rows], gid[s][rows], glz[s][rows], None,
+                                     rows=rows)
+    for s in range(res.steps, L):
+        assert (gid[s] == -5).all()
+    assert np.array_equal(gL, res.lens)
+    for b in range(B):
+        assert np.array_equal(gP[b, :res.lens[b]], res.seqs[b, :res.lens[b]])
+    assert np.allclose(glx, res.logx, rtol=1e-3, atol=1e-3)
+    say(f"C3: {int(res.lens.sum())} prefix-steps compared, {excused} inside the CDF band")
+    assert excused <= 0.01 * res.lens.sum()
+    # every finished row is a member of S
+    q = trie.query(gP, gL, want_mask=False)
+    assert (q.member == 1).all()
+
+
+@pytest.mark.parametrize("name", ["C4", "C5"])
+def test_full_size_mask_and_sample(name):
+    cfg = W.CONFIGS[name]
+    S, trie, index = build_both(cfg)
+    pb = W.make_prefix_batch(cfg, S)
+    say(f"{name}: masks / ranges / membership, B = {cfg.batch}")
+    dmask, ref_q = assert_query_parity(index, trie, pb.prefixes, pb.lens, threads=16)
+    say(f"{name}: logits")
+    logits = W.make_logits(cfg)
+    un = W.make_uniforms(cfg)
+    say(f"{name}: oracle step")
+    ref = trie.step(pb.prefixes, pb.lens, W.logits_as_f32(cfg, logits), un, want_mask=False, threads=16)
+    say(f"{name}: HIP sample")
+    ids, lzv, lza = gpu_sample(cfg, logits_to_dev(cfg, logits), dmask, un)
+    ex = check_sample_rows(cfg.dtype, ref, lambda b: ref_q.mask[b], un, ids, lzv, lza)
+    say(f"{name}: done, {ex} rows inside the CDF band")
+    n_valid = int((ref.ids >= 0).sum())
+    assert n_valid >= cfg.batch * cfg.valid_frac * 0.9

@@ -149,16 +149,23 @@ def test_decode_loop_parity_small(use_state):
     gpu_ids, gpu_lz = [], []
     lg = lambda s, *_: W.logits_as_f32(cfg, W.make_logits(cfg, batch=B, step=100 + s))
     un = lambda s: W.make_uniforms(cfg, batch=B, step=100 + s)
-    res = oracle.decode_loop(trie, B, lg, un, threads=8)
-    excused = 0
-    for s in range(res.steps):
+    all_ids = []
+    for s in range(index.l_max):
         act_before = dA.cpu().numpy().astype(bool)
-        assert np.array_equal(act_before, res.active_per_step[s]), s
+        if not act_before.any():
+            break
         ids.fill_(-5)
         ppv.ppv_decode_step(index, dP, dL, dA, logits_to_dev(cfg, W.make_logits(cfg, batch=B, step=100 + s)),
                             to_dev(un(s)), ids, lz, logx, state=state)
         torch.cuda.synchronize()
-        gid, glz = ids.cpu().numpy(), lz.cpu().numpy()
+        all_ids.append((act_before, ids.cpu().numpy(), lz.cpu().numpy()))
+    # the oracle makes its own choice at every step but is kept on the HIP path's sequence
+    res = oracle.decode_loop(trie, B, lg, un, threads=8, force_ids=lambda s: all_ids[s][1])
+    assert res.steps == len(all_ids)
+    excused = 0
+    for s in range(res.steps):
+        act_before, gid, glz = all_ids[s]
+        assert np.array_equal(act_before, res.active_per_step[s]), s
         rows = np.nonzero(act_before)[0]
         q = trie.query(res.seqs[rows], np.full(len(rows), s, np.int32))   # oracle masks of this step's prefixes
 
@@ -170,8 +177,9 @@ def test_decode_loop_parity_small(use_state):
         sub.logZ_all = None
         sub.cdf_lo = res.cdf_lo_per_step[s][rows]
         sub.cdf_hi = res.cdf_hi_per_step[s][rows]
-        ex = check_sample_rows(cfg.dtype, sub, lambda i: q.mask[i], un(s)[rows], gid[rows], glz[rows], None, rows=rows)
-        assert ex == 0, "no boundary case expected at this size (would need re-steering)"
+        excused += check_sample_rows(cfg.dtype, sub, lambda i: q.mask[i], un(s)[rows], gid[rows], glz[rows], None,
+                                     rows=rows)
+    assert excused <= 2
     assert not dA.cpu().numpy().any()
     assert np.array_equal(dL.cpu().numpy(), res.lens)
     gP = dP.cpu().numpy()
