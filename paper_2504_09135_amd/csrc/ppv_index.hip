@@ -1,8 +1,24 @@
-// Index construction (Algorithm 2, "Prepare"; Section 3.2 "Array Preparation"), sizes, export, release.
+// Index construction on the device (Algorithm 2, "Prepare"; Section 3.2 "Array Preparation"),
+// plus sizes, export and release.
+//
+// The host hands over S as CSR; everything else runs in kernels:
+//   1. validate (no empty sequence, tokens inside [0, V));
+//   2. sort the rows lexicographically -- token order = integer order, left to right, a sequence
+//      that ends sorts before its extensions -- by a least-significant-digit radix sort over the
+//      columns from the last to the first (key of a row at column d: token + 1, or 0 past its end),
+//      8 bits per pass, each pass a stable counting sort (histogram / scan / scatter);
+//   3. longest common prefix of neighbouring sorted rows; duplicates dropped (S is a set);
+//   4. the per-depth arrays: row r opens a new prefix of length d+1 iff it is longer than d and
+//      shares at most d tokens with the row before it.  One exclusive scan over the depth-major
+//      flags (depth, row) numbers all prefixes in breadth-first order and, because every depth is
+//      sorted, gives each prefix its first child for free;
+//   5. rank ranges: lo = the opening row; hi bottom-up, deepest level first (a prefix ends where
+//      its last child ends, or one row after it opens if it has no child);
+//   6. images and per-word child counts of the heavy prefixes.
 #include <algorithm>
 #include <new>
-#include <vector>
 
+#include "ppv_device.h"
 #include "ppv_internal.h"
 
 extern "C" const char *ppv_status_string(ppv_status s) {
@@ -18,168 +34,561 @@ extern "C" const char *ppv_status_string(ppv_status s) {
 
 namespace {
 
-template <typename T>
-ppv_status upload(T **dst, const std::vector<T> &src, int64_t *bytes) {
-    size_t n = src.size() * sizeof(T);
-    PPV_HIP_TRY(hipMalloc((void **)dst, n ? n : sizeof(T)));
-    if (n) PPV_HIP_TRY(hipMemcpy(*dst, src.data(), n, hipMemcpyHostToDevice));
-    *bytes += (int64_t)(n ? n : sizeof(T));
+constexpr int BT = 256;            // threads per workgroup of the build kernels
+constexpr int SCAN_ITEMS = 8;      // consecutive items per thread in the scans
+constexpr int SCAN_CHUNK = BT * SCAN_ITEMS;
+constexpr int SORT_TILES = 16;     // tiles of BT rows per workgroup in a radix pass
+constexpr int SORT_CHUNK = BT * SORT_TILES;
+constexpr int RADIX = 256;
+static_assert(RADIX == BT, "one thread per digit in the radix kernels");
+
+// ------------------------------------------------------------------------------------------
+// Exclusive scan of f(0..n-1) (uint32 sums; the callers keep totals below 2^32).
+// Three launches: per-chunk sums, scan of the chunk sums by one workgroup, per-chunk scan + base.
+__device__ inline uint32_t block_exclusive_scan(uint32_t x, uint32_t *wave_tot, uint32_t *block_total) {
+    // exclusive prefix of x over the workgroup's BT threads in thread order
+    const int lane = threadIdx.x & (WAVE - 1), wave = threadIdx.x / WAVE;
+    const uint32_t incl = wave_incl_scan(x);
+    if (lane == WAVE - 1) wave_tot[wave] = incl;
+    __syncthreads();
+    uint32_t before = 0, total = 0;
+    for (int w = 0; w < BT / WAVE; w++) {
+        const uint32_t t = wave_tot[w];
+        if (w < wave) before += t;
+        total += t;
+    }
+    __syncthreads();
+    *block_total = total;
+    return before + incl - x;
+}
+
+template <typename F> __global__ __launch_bounds__(BT) void scan_chunk_sums(uint64_t n, F f, uint32_t *__restrict__ sums) {
+    __shared__ uint32_t wave_tot[BT / WAVE];
+    const uint64_t base = (uint64_t)blockIdx.x * SCAN_CHUNK + (uint64_t)threadIdx.x * SCAN_ITEMS;
+    uint32_t s = 0;
+    for (int k = 0; k < SCAN_ITEMS; k++)
+        if (base + k < n) s += f(base + k);
+    s = wave_sum(s);
+    if ((threadIdx.x & (WAVE - 1)) == 0) wave_tot[threadIdx.x / WAVE] = s;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        uint32_t t = 0;
+        for (int w = 0; w < BT / WAVE; w++) t += wave_tot[w];
+        sums[blockIdx.x] = t;
+    }
+}
+
+// in place exclusive scan of m values by ONE workgroup; the grand total goes to *total
+__global__ __launch_bounds__(BT) void scan_of_sums(uint32_t *__restrict__ sums, uint64_t m, uint32_t *__restrict__ total) {
+    __shared__ uint32_t wave_tot[BT / WAVE];
+    uint32_t carry = 0;
+    for (uint64_t b0 = 0; b0 < m; b0 += SCAN_CHUNK) {
+        const uint64_t base = b0 + (uint64_t)threadIdx.x * SCAN_ITEMS;
+        uint32_t v[SCAN_ITEMS], s = 0;
+        for (int k = 0; k < SCAN_ITEMS; k++) {
+            v[k] = (base + k < m) ? sums[base + k] : 0u;
+            s += v[k];
+        }
+        uint32_t tot;
+        uint32_t ex = carry + block_exclusive_scan(s, wave_tot, &tot);
+        for (int k = 0; k < SCAN_ITEMS; k++) {
+            if (base + k < m) sums[base + k] = ex;
+            ex += v[k];
+        }
+        carry += tot;
+    }
+    if (threadIdx.x == 0) *total = carry;
+}
+
+template <typename F>
+__global__ __launch_bounds__(BT) void scan_apply(uint64_t n, F f, const uint32_t *__restrict__ sums, uint32_t *out) {
+    __shared__ uint32_t wave_tot[BT / WAVE];
+    const uint64_t base = (uint64_t)blockIdx.x * SCAN_CHUNK + (uint64_t)threadIdx.x * SCAN_ITEMS;
+    uint32_t v[SCAN_ITEMS], s = 0;
+    for (int k = 0; k < SCAN_ITEMS; k++) {
+        v[k] = (base + k < n) ? f(base + k) : 0u;
+        s += v[k];
+    }
+    uint32_t tot;
+    uint32_t ex = sums[blockIdx.x] + block_exclusive_scan(s, wave_tot, &tot);
+    for (int k = 0; k < SCAN_ITEMS; k++) {
+        if (base + k < n) out[base + k] = ex;
+        ex += v[k];
+    }
+}
+
+// out[i] = sum of f(0..i-1) for i in [0, n); *d_total = sum of all.  sums: scratch of ceil(n / SCAN_CHUNK) words.
+// f may read `out` only at the index it is asked for (the in-place scan of the radix histogram does).
+template <typename F>
+ppv_status exclusive_scan(uint64_t n, F f, uint32_t *out, uint32_t *sums, uint32_t *d_total, hipStream_t st) {
+    const uint64_t nb = (n + SCAN_CHUNK - 1) / SCAN_CHUNK;
+    if (nb == 0) {
+        hipLaunchKernelGGL(scan_of_sums, dim3(1), dim3(BT), 0, st, sums, (uint64_t)0, d_total);  // total = 0
+        PPV_HIP_TRY(hipGetLastError());
+        return PPV_OK;
+    }
+    hipLaunchKernelGGL(scan_chunk_sums<F>, dim3((unsigned)nb), dim3(BT), 0, st, n, f, sums);
+    hipLaunchKernelGGL(scan_of_sums, dim3(1), dim3(BT), 0, st, sums, nb, d_total);
+    hipLaunchKernelGGL(scan_apply<F>, dim3((unsigned)nb), dim3(BT), 0, st, n, f, (const uint32_t *)sums, out);
+    PPV_HIP_TRY(hipGetLastError());
     return PPV_OK;
 }
 
-ppv_status build_impl(const int32_t *tokens, const int64_t *offsets, int64_t n_seq, int32_t vocab, ppv_index *ix) {
-    // ---- validate
+// ------------------------------------------------------------------------------------------
+// 1. validation and the longest row
+__global__ __launch_bounds__(BT) void check_rows(const int64_t *__restrict__ off, int64_t n, int32_t *__restrict__ err,
+                                                 int32_t *__restrict__ l_max) {
+    const int64_t i = (int64_t)blockIdx.x * BT + threadIdx.x;
+    int32_t len = 0;
+    if (i < n) {
+        const int64_t l = off[i + 1] - off[i];
+        if (l <= 0 || l > 0x7FFFFFFF) atomicOr(err, 1);
+        else len = (int32_t)l;
+    }
+    for (int o = WAVE / 2; o > 0; o >>= 1) len = max(len, __shfl_xor(len, o, WAVE));
+    if ((threadIdx.x & (WAVE - 1)) == 0 && len > 0) atomicMax(l_max, len);   // one atomic per wave
+}
+__global__ __launch_bounds__(BT) void check_tokens(const int32_t *__restrict__ tok, int64_t total, int32_t vocab,
+                                                   int32_t *__restrict__ err) {
+    const int64_t i = (int64_t)blockIdx.x * BT + threadIdx.x;
+    if (i < total && (tok[i] < 0 || tok[i] >= vocab)) atomicOr(err, 2);
+}
+__global__ __launch_bounds__(BT) void iota_rows(uint32_t *__restrict__ perm, uint32_t n) {
+    const uint32_t i = blockIdx.x * BT + threadIdx.x;
+    if (i < n) perm[i] = i;
+}
+
+// ------------------------------------------------------------------------------------------
+// 2. one stable counting-sort pass on 8 bits of the column key
+__device__ inline uint32_t column_key(const int32_t *__restrict__ tok, const int64_t *__restrict__ off, uint32_t row,
+                                      int col) {
+    const int64_t a = off[row], b = off[row + 1];
+    return (col < b - a) ? (uint32_t)tok[a + col] + 1u : 0u;  // 0: the row has ended; sorts first
+}
+
+__global__ __launch_bounds__(BT) void radix_histogram(const int32_t *__restrict__ tok, const int64_t *__restrict__ off,
+                                                      const uint32_t *__restrict__ perm, uint32_t n, int col, int shift,
+                                                      uint8_t *__restrict__ digits, uint32_t *__restrict__ hist,
+                                                      uint32_t n_blocks) {
+    __shared__ uint32_t h[RADIX];
+    h[threadIdx.x] = 0;
+    __syncthreads();
+    const uint32_t start = blockIdx.x * SORT_CHUNK;
+    for (int t = 0; t < SORT_TILES; t++) {
+        const uint32_t i = start + t * BT + threadIdx.x;
+        if (i < n) {
+            const uint32_t d = (column_key(tok, off, perm[i], col) >> shift) & (RADIX - 1);
+            digits[i] = (uint8_t)d;
+            atomicAdd(&h[d], 1u);
+        }
+    }
+    __syncthreads();
+    hist[(size_t)threadIdx.x * n_blocks + blockIdx.x] = h[threadIdx.x];  // digit-major for the scan
+}
+
+__global__ __launch_bounds__(BT) void radix_scatter(const uint32_t *__restrict__ perm_in, uint32_t n,
+                                                    const uint8_t *__restrict__ digits,
+                                                    const uint32_t *__restrict__ hist_scanned, uint32_t n_blocks,
+                                                    uint32_t *__restrict__ perm_out) {
+    __shared__ uint32_t base[RADIX];               // next free slot per digit for this workgroup
+    __shared__ uint32_t cnt[BT / WAVE][RADIX];     // rows per digit in the current tile, per wave
+    const int lane = threadIdx.x & (WAVE - 1), wave = threadIdx.x / WAVE;
+    base[threadIdx.x] = hist_scanned[(size_t)threadIdx.x * n_blocks + blockIdx.x];
+    const uint32_t start = blockIdx.x * SORT_CHUNK;
+    for (int t = 0; t < SORT_TILES; t++) {
+        for (int w = 0; w < BT / WAVE; w++) cnt[w][threadIdx.x] = 0;
+        __syncthreads();
+        const uint32_t i = start + t * BT + threadIdx.x;
+        const bool valid = i < n;
+        const uint32_t d = valid ? digits[i] : 0u;
+        // lanes of this wave that hold the same digit
+        uint64_t peers = __ballot(valid);
+        for (int b = 0; b < 8; b++) {
+            const uint64_t bal = __ballot(valid && ((d >> b) & 1u));
+            peers &= ((d >> b) & 1u) ? bal : ~bal;
+        }
+        const uint32_t rank_in_wave = (uint32_t)__popcll(peers & ((1ull << lane) - 1ull));
+        if (valid && rank_in_wave == 0) cnt[wave][d] = (uint32_t)__popcll(peers);
+        __syncthreads();
+        if (valid) {
+            uint32_t pos = base[d] + rank_in_wave;
+            for (int w = 0; w < wave; w++) pos += cnt[w][d];
+            perm_out[pos] = perm_in[i];            // stable: thread order within the tile is kept
+        }
+        __syncthreads();
+        uint32_t add = 0;
+        for (int w = 0; w < BT / WAVE; w++) add += cnt[w][threadIdx.x];
+        base[threadIdx.x] += add;
+        __syncthreads();
+    }
+}
+
+// ------------------------------------------------------------------------------------------
+// 3. common prefix with the previous sorted row; duplicates
+__global__ __launch_bounds__(BT) void neighbour_lcp(const int32_t *__restrict__ tok, const int64_t *__restrict__ off,
+                                                    const uint32_t *__restrict__ perm, uint32_t n,
+                                                    int32_t *__restrict__ lcp, uint8_t *__restrict__ keep) {
+    const uint32_t i = blockIdx.x * BT + threadIdx.x;
+    if (i >= n) return;
+    if (i == 0) { lcp[0] = 0; keep[0] = 1; return; }
+    const uint32_t r = perm[i], q = perm[i - 1];
+    const int32_t *a = tok + off[r], *b = tok + off[q];
+    const int32_t la = (int32_t)(off[r + 1] - off[r]), lb = (int32_t)(off[q + 1] - off[q]);
+    const int32_t m = la < lb ? la : lb;
+    int32_t c = 0;
+    while (c < m && a[c] == b[c]) c++;
+    lcp[i] = c;
+    keep[i] = (c == la && c == lb) ? 0 : 1;
+}
+struct HistValue {
+    const uint32_t *h;
+    __device__ uint32_t operator()(uint64_t i) const { return h[i]; }
+};
+struct KeepFlag {
+    const uint8_t *keep;
+    __device__ uint32_t operator()(uint64_t i) const { return keep[i]; }
+};
+struct KeptLen {  // length of sorted row i if it is kept, else 0
+    const uint8_t *keep;
+    const uint32_t *perm;
+    const int64_t *off;
+    __device__ uint32_t operator()(uint64_t i) const {
+        if (!keep[i]) return 0u;
+        const uint32_t r = perm[i];
+        return (uint32_t)(off[r + 1] - off[r]);
+    }
+};
+// kept sorted row i becomes row dst[i] of the index: its tokens, offset, common prefix
+__global__ __launch_bounds__(BT) void compact_rows(const int32_t *__restrict__ tok, const int64_t *__restrict__ off,
+                                                   const uint32_t *__restrict__ perm, uint32_t n,
+                                                   const uint8_t *__restrict__ keep, const uint32_t *__restrict__ dst,
+                                                   const uint32_t *__restrict__ tok_at, const int32_t *__restrict__ lcp,
+                                                   int32_t *__restrict__ x_tok, int64_t *__restrict__ x_off,
+                                                   int32_t *__restrict__ row_lcp, uint32_t n_rows, uint32_t n_tok) {
+    const uint32_t i = blockIdx.x * BT + threadIdx.x;
+    if (i == 0) x_off[n_rows] = n_tok;
+    if (i >= n || !keep[i]) return;
+    const uint32_t r = perm[i], d = dst[i], at = tok_at[i];
+    const int64_t a = off[r];
+    const int32_t len = (int32_t)(off[r + 1] - a);
+    x_off[d] = at;
+    row_lcp[d] = lcp[i];
+    for (int32_t k = 0; k < len; k++) x_tok[at + k] = tok[a + k];
+}
+
+// ------------------------------------------------------------------------------------------
+// 4. per-depth arrays.  Flattened depth-major index k = d * N + r.
+struct OpensPrefix {  // 1 iff row r opens a new prefix of length d+1
+    const int64_t *x_off;
+    const int32_t *row_lcp;
+    uint64_t n_rows;
+    __device__ uint32_t operator()(uint64_t k) const {
+        const uint64_t d = k / n_rows, r = k - d * n_rows;
+        const int64_t len = x_off[r + 1] - x_off[r];
+        return (len > (int64_t)d && row_lcp[r] <= (int32_t)d) ? 1u : 0u;
+    }
+};
+// pos[k] = prefixes numbered before (d, r); a prefix's number + 1 is its entry (entry 0 = the empty prefix)
+__global__ __launch_bounds__(BT) void fill_nodes(const int32_t *__restrict__ x_tok, const int64_t *__restrict__ x_off,
+                                                 const int32_t *__restrict__ row_lcp, const uint32_t *__restrict__ pos,
+                                                 uint64_t n_rows, int32_t l_max, uint32_t n_nodes,
+                                                 NodeEnt *__restrict__ ent, uint32_t *__restrict__ node_lo) {
+    const uint64_t k = (uint64_t)blockIdx.x * BT + threadIdx.x;
+    if (k == 0) {  // the empty prefix and the closing sentinel
+        ent[0].tok = 0u;
+        ent[0].child = 1u;
+        node_lo[0] = 0u;
+        ent[n_nodes].tok = PPV_NODE_TOKEN;
+        ent[n_nodes].child = n_nodes;
+    }
+    if (k >= n_rows * (uint64_t)l_max) return;
+    const uint64_t d = k / n_rows, r = k - d * n_rows;
+    const int64_t a = x_off[r];
+    const int64_t len = x_off[r + 1] - a;
+    if (!(len > (int64_t)d && row_lcp[r] <= (int32_t)d)) return;
+    const uint32_t g = 1u + pos[k];
+    uint32_t t = (uint32_t)x_tok[a + d];
+    if (len == (int64_t)d + 1) t |= PPV_NODE_TERMINAL;  // the opening row is the prefix itself
+    // first child: the first prefix of length d+2 at or after this row (this row itself if it goes on,
+    // else the next row); depth-major numbering makes that a plain look-up of the scan
+    uint32_t child = n_nodes;
+    if (d + 1 < (uint64_t)l_max) {
+        const uint64_t first = (len > (int64_t)d + 1) ? r : r + 1;   // first == n_rows: start of the next depth
+        child = 1u + pos[(d + 1) * n_rows + first];
+    }
+    ent[g].tok = t;
+    ent[g].child = child;
+    node_lo[g] = (uint32_t)r;
+}
+
+// 5. hi of the entries [g0, g1) of one depth, deeper levels already done
+__global__ __launch_bounds__(BT) void fill_hi(const NodeEnt *__restrict__ ent, const uint32_t *__restrict__ node_lo,
+                                              uint32_t g0, uint32_t g1, uint32_t *__restrict__ node_hi) {
+    const uint32_t g = g0 + blockIdx.x * BT + threadIdx.x;
+    if (g >= g1) return;
+    const uint32_t cb = ent[g].child, ce = ent[g + 1].child;
+    node_hi[g] = (ce > cb) ? node_hi[ce - 1] : node_lo[g] + 1u;
+}
+
+// 6. heavy prefixes
+struct IsHeavy {
+    const NodeEnt *ent;
+    uint32_t heavy_min;
+    __device__ uint32_t operator()(uint64_t g) const { return (ent[g + 1].child - ent[g].child > heavy_min) ? 1u : 0u; }
+};
+__global__ __launch_bounds__(BT) void mark_heavy(NodeEnt *__restrict__ ent, uint32_t n_nodes, uint32_t heavy_min,
+                                                 const uint32_t *__restrict__ slot_of, uint32_t heavy_limit,
+                                                 uint32_t *__restrict__ heavy_slot, uint32_t *__restrict__ heavy_node) {
+    const uint32_t g = blockIdx.x * BT + threadIdx.x;
+    if (g >= n_nodes) return;
+    const bool heavy = ent[g + 1].child - ent[g].child > heavy_min;
+    if (g < heavy_limit) heavy_slot[g] = heavy ? slot_of[g] : PPV_NO_SLOT;
+    if (heavy) {
+        heavy_node[slot_of[g]] = g;
+        atomicOr(&ent[g].tok, PPV_NODE_HEAVY);
+    }
+}
+// one workgroup per heavy prefix: OR its children into the image, then count children before each word
+__global__ __launch_bounds__(BT) void fill_heavy(const NodeEnt *__restrict__ ent, const uint32_t *__restrict__ heavy_node,
+                                                 int n_words, uint32_t *__restrict__ bits, uint32_t *__restrict__ rank) {
+    __shared__ uint32_t wave_tot[BT / WAVE];
+    const uint32_t g = heavy_node[blockIdx.x];
+    uint32_t *b = bits + (size_t)blockIdx.x * (size_t)n_words;
+    uint32_t *rk = rank + (size_t)blockIdx.x * (size_t)n_words;
+    for (uint32_t c = ent[g].child + threadIdx.x; c < ent[g + 1].child; c += BT) {
+        const uint32_t v = ent[c].tok & PPV_NODE_TOKEN;
+        atomicOr(&b[v >> 5], 1u << (v & 31u));   // the image was zeroed before the launch
+    }
+    __threadfence();
+    __syncthreads();
+    uint32_t carry = 0;
+    for (int w0 = 0; w0 < n_words; w0 += BT) {
+        const int w = w0 + threadIdx.x;
+        const uint32_t c = (w < n_words) ? (uint32_t)__popc(__builtin_nontemporal_load(&b[w])) : 0u;
+        uint32_t tot;
+        const uint32_t ex = carry + block_exclusive_scan(c, wave_tot, &tot);
+        if (w < n_words) rk[w] = ex;
+        carry += tot;
+    }
+}
+
+// ------------------------------------------------------------------------------------------
+struct DeviceBuffers {  // temporaries of the build, all released at the end
+    void *p[24];
+    int n = 0;
+    ~DeviceBuffers() {
+        for (int i = 0; i < n; i++) (void)hipFree(p[i]);
+    }
+    template <typename T> ppv_status alloc(T **out, size_t count) {
+        *out = nullptr;
+        if (n >= 24) return PPV_EDEVICE;
+        hipError_t e = hipMalloc((void **)out, (count ? count : 1) * sizeof(T));
+        if (e != hipSuccess) {
+            (void)hipGetLastError();
+            return e == hipErrorOutOfMemory ? PPV_ENOMEM : PPV_EDEVICE;
+        }
+        p[n++] = *out;
+        return PPV_OK;
+    }
+};
+
+template <typename T> ppv_status keep_alloc(T **out, size_t count, int64_t *bytes) {
+    *out = nullptr;
+    hipError_t e = hipMalloc((void **)out, (count ? count : 1) * sizeof(T));
+    if (e != hipSuccess) {
+        (void)hipGetLastError();
+        return e == hipErrorOutOfMemory ? PPV_ENOMEM : PPV_EDEVICE;
+    }
+    *bytes += (int64_t)((count ? count : 1) * sizeof(T));
+    return PPV_OK;
+}
+
+#define TRY(x)                          \
+    do {                                \
+        ppv_status s_ = (x);            \
+        if (s_ != PPV_OK) return s_;    \
+    } while (0)
+
+inline unsigned blocks_for(uint64_t n) { return (unsigned)((n + BT - 1) / BT); }
+
+ppv_status build_on_device(const int32_t *tokens, const int64_t *offsets, int64_t n_seq, int32_t vocab, ppv_index *ix) {
     if (offsets[0] != 0) return PPV_EINVAL;
-    for (int64_t i = 0; i < n_seq; i++)
-        if (offsets[i + 1] <= offsets[i]) return PPV_EINVAL;  // empty sequence or decreasing offsets
     const int64_t total = offsets[n_seq];
-    for (int64_t j = 0; j < total; j++)
-        if (tokens[j] < 0 || tokens[j] >= vocab) return PPV_EINVAL;
-    if (n_seq > 0xFFFFFFFEll) return PPV_ERANGE;
+    if (total < n_seq) return PPV_EINVAL;                          // some sequence is empty (or offsets decrease)
+    if (n_seq > 0xFFFFFFF0ll || total > 0xFFFFFFF0ll) return PPV_ERANGE;
+    const uint32_t n = (uint32_t)n_seq;
+    hipStream_t st = nullptr;
+    DeviceBuffers tmp;
 
-    // ---- sort row ids lexicographically (token order = integer order, prefix before extension)
-    std::vector<int64_t> order((size_t)n_seq);
-    for (int64_t i = 0; i < n_seq; i++) order[(size_t)i] = i;
-    auto less = [&](int64_t a, int64_t b) {
-        const int32_t *pa = tokens + offsets[a], *pb = tokens + offsets[b];
-        int64_t la = offsets[a + 1] - offsets[a], lb = offsets[b + 1] - offsets[b];
-        int64_t n = la < lb ? la : lb;
-        for (int64_t k = 0; k < n; k++)
-            if (pa[k] != pb[k]) return pa[k] < pb[k];
-        return la < lb;
-    };
-    std::sort(order.begin(), order.end(), less);
+    // ---- inputs to the device
+    int32_t *d_tok;
+    int64_t *d_off;
+    int32_t *d_flags;  // [0] error bits, [1] longest row
+    uint32_t *d_total;
+    TRY(tmp.alloc(&d_tok, (size_t)total));
+    TRY(tmp.alloc(&d_off, (size_t)n + 1));
+    TRY(tmp.alloc(&d_flags, 2));
+    TRY(tmp.alloc(&d_total, 4));
+    PPV_HIP_TRY(hipMemcpyAsync(d_tok, tokens, (size_t)total * sizeof(int32_t), hipMemcpyHostToDevice, st));
+    PPV_HIP_TRY(hipMemcpyAsync(d_off, offsets, ((size_t)n + 1) * sizeof(int64_t), hipMemcpyHostToDevice, st));
+    PPV_HIP_TRY(hipMemsetAsync(d_flags, 0, 2 * sizeof(int32_t), st));
 
-    // ---- de-duplicate, flatten, longest common prefix with the previous row
-    std::vector<int32_t> x_tok;
-    std::vector<int64_t> x_off;
-    std::vector<int32_t> lcp;  // lcp[r] = common prefix length of rows r-1 and r (0 for r = 0)
-    x_tok.reserve((size_t)total);
-    x_off.reserve((size_t)n_seq + 1);
-    lcp.reserve((size_t)n_seq);
-    x_off.push_back(0);
-    int32_t l_max = 0;
-    for (int64_t i = 0; i < n_seq; i++) {
-        int64_t s = order[(size_t)i];
-        const int32_t *p = tokens + offsets[s];
-        int64_t len = offsets[s + 1] - offsets[s];
-        int32_t c = 0;
-        if (!lcp.empty() || x_off.size() > 1) {
-            size_t r = x_off.size() - 2;
-            const int32_t *q = x_tok.data() + x_off[r];
-            int64_t ql = x_off[r + 1] - x_off[r];
-            int64_t n = ql < len ? ql : len;
-            while (c < n && p[c] == q[c]) c++;
-            if (c == len && c == ql) continue;  // duplicate of the previous kept row
+    // ---- 1. validate
+    hipLaunchKernelGGL(check_rows, dim3(blocks_for(n)), dim3(BT), 0, st, (const int64_t *)d_off, (int64_t)n, d_flags,
+                       d_flags + 1);
+    hipLaunchKernelGGL(check_tokens, dim3(blocks_for((uint64_t)total)), dim3(BT), 0, st, (const int32_t *)d_tok, total,
+                       vocab, d_flags);
+    int32_t h_flags[2];
+    PPV_HIP_TRY(hipMemcpyAsync(h_flags, d_flags, sizeof(h_flags), hipMemcpyDeviceToHost, st));
+    PPV_HIP_TRY(hipStreamSynchronize(st));
+    if (h_flags[0] != 0) return PPV_EINVAL;                         // empty sequence or token outside [0, vocab)
+    const int32_t l_max = h_flags[1];
+
+    // ---- 2. sort rows: LSD radix over the columns, last column first
+    uint32_t *perm_a, *perm_b, *hist, *sums;
+    uint8_t *digits;
+    const uint32_t sort_blocks = (n + SORT_CHUNK - 1) / SORT_CHUNK;
+    const uint64_t hist_len = (uint64_t)RADIX * sort_blocks;
+    TRY(tmp.alloc(&perm_a, n));
+    TRY(tmp.alloc(&perm_b, n));
+    TRY(tmp.alloc(&digits, n));
+    TRY(tmp.alloc(&hist, (size_t)hist_len));
+    // scratch for every scan of the build: the largest one runs over l_max * n flags
+    const uint64_t biggest_scan = std::max<uint64_t>((uint64_t)l_max * n + 1, hist_len);
+    TRY(tmp.alloc(&sums, (size_t)((biggest_scan + SCAN_CHUNK - 1) / SCAN_CHUNK)));
+    hipLaunchKernelGGL(iota_rows, dim3(blocks_for(n)), dim3(BT), 0, st, perm_a, n);
+    int key_bits = 1;
+    while ((1ll << key_bits) <= (int64_t)vocab) key_bits++;         // keys run over 0 .. vocab
+    for (int col = l_max - 1; col >= 0; col--) {
+        for (int shift = 0; shift < key_bits; shift += 8) {
+            hipLaunchKernelGGL(radix_histogram, dim3(sort_blocks), dim3(BT), 0, st, (const int32_t *)d_tok,
+                               (const int64_t *)d_off, (const uint32_t *)perm_a, n, col, shift, digits, hist,
+                               sort_blocks);
+            TRY(exclusive_scan(hist_len, HistValue{hist}, hist, sums, d_total, st));
+            hipLaunchKernelGGL(radix_scatter, dim3(sort_blocks), dim3(BT), 0, st, (const uint32_t *)perm_a, n,
+                               (const uint8_t *)digits, (const uint32_t *)hist, sort_blocks, perm_b);
+            std::swap(perm_a, perm_b);
         }
-        x_tok.insert(x_tok.end(), p, p + len);
-        x_off.push_back((int64_t)x_tok.size());
-        lcp.push_back(c);
-        if (len > l_max) l_max = (int32_t)len;
     }
-    const int64_t n_rows = (int64_t)x_off.size() - 1;
+    PPV_HIP_TRY(hipGetLastError());
 
-    // ---- per-depth arrays.  A row r opens a new prefix of length d+1 iff it is longer than d and
-    // shares at most d tokens with the row before it; that prefix covers rows up to the next row
-    // whose common prefix with its predecessor is at most d.
-    std::vector<uint32_t> node_tok(1, 0u), node_lo(1, 0u), node_hi(1, (uint32_t)n_rows);
-    std::vector<size_t> level_base((size_t)l_max + 2, 0);
-    level_base[0] = 1;
-    for (int32_t d = 0; d < l_max; d++) {
-        size_t open = 0;
-        bool have_open = false;
-        for (int64_t r = 0; r < n_rows; r++) {
-            if (lcp[(size_t)r] <= d || r == 0) {
-                if (have_open) { node_hi[open] = (uint32_t)r; have_open = false; }
-                if (x_off[(size_t)r + 1] - x_off[(size_t)r] > d) {
-                    if (node_tok.size() >= 0xFFFFFFFEull) return PPV_ERANGE;
-                    // the first row of a prefix's range is the prefix itself iff it ends at depth d
-                    uint32_t term = (x_off[(size_t)r + 1] - x_off[(size_t)r] == d + 1) ? PPV_NODE_TERMINAL : 0u;
-                    node_tok.push_back((uint32_t)x_tok[(size_t)(x_off[(size_t)r] + d)] | term);
-                    node_lo.push_back((uint32_t)r);
-                    node_hi.push_back(0u);
-                    open = node_tok.size() - 1;
-                    have_open = true;
-                }
-            }
-        }
-        if (have_open) node_hi[open] = (uint32_t)n_rows;
-        level_base[(size_t)d + 1] = node_tok.size();
-    }
-    const size_t G = node_tok.size();
-    // children of node g (depth d) = the nodes of depth d+1 whose first row lies in [lo, hi)
-    std::vector<uint32_t> child_off(G + 1, 0u);
-    {
-        size_t lvl_begin = 0, lvl_end = 1;  // the level that holds node 0 alone
-        for (int32_t d = 0; d <= l_max; d++) {  // d = depth of the children of the current level
-            size_t cb = (d < l_max) ? level_base[(size_t)d] : G;
-            size_t ce = (d < l_max) ? level_base[(size_t)d + 1] : G;
-            size_t c = cb;
-            for (size_t g = lvl_begin; g < lvl_end; g++) {
-                child_off[g] = (uint32_t)c;
-                while (c < ce && node_lo[c] < node_hi[g]) c++;
-            }
-            lvl_begin = cb;
-            lvl_end = ce;
-        }
-        child_off[G] = (uint32_t)G;
-    }
+    // ---- 3. neighbours: common prefix, duplicates; compact into the flat sorted S
+    int32_t *lcp;
+    uint8_t *keep;
+    uint32_t *dst, *tok_at;
+    TRY(tmp.alloc(&lcp, n));
+    TRY(tmp.alloc(&keep, n));
+    TRY(tmp.alloc(&dst, n));
+    TRY(tmp.alloc(&tok_at, n));
+    hipLaunchKernelGGL(neighbour_lcp, dim3(blocks_for(n)), dim3(BT), 0, st, (const int32_t *)d_tok,
+                       (const int64_t *)d_off, (const uint32_t *)perm_a, n, lcp, keep);
+    TRY(exclusive_scan(n, KeepFlag{keep}, dst, sums, d_total, st));
+    TRY(exclusive_scan(n, KeptLen{keep, perm_a, d_off}, tok_at, sums, d_total + 1, st));
+    uint32_t h_tot[2];
+    PPV_HIP_TRY(hipMemcpyAsync(h_tot, d_total, sizeof(h_tot), hipMemcpyDeviceToHost, st));
+    PPV_HIP_TRY(hipStreamSynchronize(st));
+    const uint32_t n_rows = h_tot[0], n_tok = h_tot[1];
+    ix->device_bytes = 0;
+    TRY(keep_alloc(&ix->d_x_tok, n_tok, &ix->device_bytes));
+    TRY(keep_alloc(&ix->d_x_off, (size_t)n_rows + 1, &ix->device_bytes));
+    int32_t *row_lcp;
+    TRY(tmp.alloc(&row_lcp, n_rows));
+    hipLaunchKernelGGL(compact_rows, dim3(blocks_for(n)), dim3(BT), 0, st, (const int32_t *)d_tok,
+                       (const int64_t *)d_off, (const uint32_t *)perm_a, n, (const uint8_t *)keep,
+                       (const uint32_t *)dst, (const uint32_t *)tok_at, (const int32_t *)lcp, ix->d_x_tok, ix->d_x_off,
+                       row_lcp, n_rows, n_tok);
 
-    // ---- heavy nodes: ready-made valid-set images and per-word child counts
+    // ---- 4. number the prefixes breadth-first: one scan over the (depth, row) flags
+    const uint64_t n_flags = (uint64_t)l_max * n_rows;
+    if (n_flags + 1 > 0xFFFFFFF0ull) return PPV_ERANGE;
+    uint32_t *pos;
+    TRY(tmp.alloc(&pos, (size_t)n_flags + 1));
+    TRY(exclusive_scan(n_flags, OpensPrefix{ix->d_x_off, row_lcp, n_rows}, pos, sums, d_total + 2, st));
+    uint32_t n_pref;
+    PPV_HIP_TRY(hipMemcpyAsync(&n_pref, d_total + 2, sizeof(uint32_t), hipMemcpyDeviceToHost, st));
+    PPV_HIP_TRY(hipStreamSynchronize(st));
+    if (n_pref > 0xFFFFFFF0u - 2) return PPV_ERANGE;
+    const uint32_t G = n_pref + 1;                                   // with the empty prefix
+    // the scan value one past the end closes the last depth
+    PPV_HIP_TRY(hipMemcpyAsync(pos + n_flags, d_total + 2, sizeof(uint32_t), hipMemcpyDeviceToDevice, st));
+    TRY(keep_alloc(&ix->d_ent, (size_t)G + 1, &ix->device_bytes));
+    TRY(keep_alloc(&ix->d_node_lo, G, &ix->device_bytes));
+    TRY(keep_alloc(&ix->d_node_hi, G, &ix->device_bytes));
+    hipLaunchKernelGGL(fill_nodes, dim3(blocks_for(std::max<uint64_t>(n_flags, 1))), dim3(BT), 0, st,
+                       (const int32_t *)ix->d_x_tok, (const int64_t *)ix->d_x_off, (const int32_t *)row_lcp,
+                       (const uint32_t *)pos, (uint64_t)n_rows, l_max, G, ix->d_ent, ix->d_node_lo);
+
+    // ---- 5. hi, deepest depth first; depth d holds the entries 1 + pos[d * n_rows] .. 1 + pos[(d+1) * n_rows]
+    // (the l_max + 1 bounds are read back in one strided copy)
+    uint32_t *h_base = new (std::nothrow) uint32_t[(size_t)l_max + 1];
+    if (!h_base) return PPV_ENOMEM;
+    hipError_t ce = hipMemcpy2DAsync(h_base, sizeof(uint32_t), pos, (size_t)n_rows * sizeof(uint32_t), sizeof(uint32_t),
+                                     (size_t)l_max + 1, hipMemcpyDeviceToHost, st);
+    if (ce == hipSuccess) ce = hipStreamSynchronize(st);
+    if (ce != hipSuccess) {
+        delete[] h_base;
+        (void)hipGetLastError();
+        return PPV_EDEVICE;
+    }
+    for (int d = l_max - 1; d >= 0; d--) {
+        const uint32_t g0 = 1u + h_base[d], g1 = 1u + h_base[d + 1];
+        if (g1 > g0)
+            hipLaunchKernelGGL(fill_hi, dim3(blocks_for(g1 - g0)), dim3(BT), 0, st, (const NodeEnt *)ix->d_ent,
+                               (const uint32_t *)ix->d_node_lo, g0, g1, ix->d_node_hi);
+    }
+    delete[] h_base;
+    hipLaunchKernelGGL(fill_hi, dim3(1), dim3(BT), 0, st, (const NodeEnt *)ix->d_ent, (const uint32_t *)ix->d_node_lo,
+                       0u, 1u, ix->d_node_hi);                       // the empty prefix: all of S
+    PPV_HIP_TRY(hipGetLastError());
+
+    // ---- 6. heavy prefixes
     const int n_words = (vocab + 31) / 32;
     const uint32_t heavy_min = (uint32_t)std::min<int64_t>(vocab / 32, PPV_LIST_MAX);
-    std::vector<uint32_t> heavy_slot, heavy_bits, heavy_rank;
-    size_t n_heavy = 0;
-    for (size_t g = 0; g < G; g++) {
-        uint32_t cb = child_off[g], ce = child_off[g + 1];
-        if (ce - cb <= heavy_min) continue;
-        heavy_slot.resize(g + 1, PPV_NO_SLOT);
-        heavy_slot[g] = (uint32_t)n_heavy;
-        heavy_bits.resize((n_heavy + 1) * (size_t)n_words, 0u);
-        heavy_rank.resize((n_heavy + 1) * (size_t)n_words, 0u);
-        uint32_t *bits = heavy_bits.data() + n_heavy * (size_t)n_words;
-        uint32_t *rank = heavy_rank.data() + n_heavy * (size_t)n_words;
-        for (uint32_t c = cb; c < ce; c++) {
-            uint32_t v = node_tok[c] & PPV_NODE_TOKEN;
-            bits[v >> 5] |= 1u << (v & 31u);
+    uint32_t *slot_of;
+    TRY(tmp.alloc(&slot_of, G));
+    TRY(exclusive_scan(G, IsHeavy{ix->d_ent, heavy_min}, slot_of, sums, d_total + 3, st));
+    uint32_t n_heavy;
+    PPV_HIP_TRY(hipMemcpyAsync(&n_heavy, d_total + 3, sizeof(uint32_t), hipMemcpyDeviceToHost, st));
+    PPV_HIP_TRY(hipStreamSynchronize(st));
+    // Breadth-first order puts the heavy prefixes (shallow ones) at small entry numbers, so the slot
+    // table only has to reach past the last of them: the first entry that has all n_heavy before it.
+    uint32_t heavy_limit = 0;
+    if (n_heavy > 0) {
+        uint32_t lo = 0, hi = G;
+        while (lo < hi) {
+            const uint32_t mid = lo + (hi - lo) / 2;
+            uint32_t v;
+            PPV_HIP_TRY(hipMemcpy(&v, slot_of + mid, sizeof(uint32_t), hipMemcpyDeviceToHost));
+            if (v >= n_heavy) hi = mid; else lo = mid + 1;
         }
-        uint32_t acc = 0;
-        for (int w = 0; w < n_words; w++) {
-            rank[w] = acc;
-            acc += (uint32_t)__builtin_popcount(bits[w]);
-        }
-        n_heavy++;
+        heavy_limit = lo;
     }
+    uint32_t *heavy_node;
+    TRY(tmp.alloc(&heavy_node, n_heavy));
+    TRY(keep_alloc(&ix->d_heavy_slot, heavy_limit, &ix->device_bytes));
+    TRY(keep_alloc(&ix->d_heavy_bits, (size_t)n_heavy * n_words, &ix->device_bytes));
+    TRY(keep_alloc(&ix->d_heavy_rank, (size_t)n_heavy * n_words, &ix->device_bytes));
+    PPV_HIP_TRY(hipMemsetAsync(ix->d_heavy_bits, 0, std::max<size_t>((size_t)n_heavy * n_words, 1) * sizeof(uint32_t), st));
+    hipLaunchKernelGGL(mark_heavy, dim3(blocks_for(G)), dim3(BT), 0, st, ix->d_ent, G, heavy_min,
+                       (const uint32_t *)slot_of, heavy_limit, ix->d_heavy_slot, heavy_node);
+    if (n_heavy > 0)
+        hipLaunchKernelGGL(fill_heavy, dim3(n_heavy), dim3(BT), 0, st, (const NodeEnt *)ix->d_ent,
+                           (const uint32_t *)heavy_node, n_words, ix->d_heavy_bits, ix->d_heavy_rank);
+    PPV_HIP_TRY(hipGetLastError());
+    PPV_HIP_TRY(hipStreamSynchronize(st));
 
-    // ---- upload
-    ppv_status st;
-    ix->device_bytes = 0;
-    std::vector<NodeEnt> ent(G + 1);
-    for (size_t g = 0; g <= G; g++) {
-        ent[g].tok = g < G ? node_tok[g] : PPV_NODE_TOKEN;
-        if (g < heavy_slot.size() && heavy_slot[g] != PPV_NO_SLOT) ent[g].tok |= PPV_NODE_HEAVY;
-        ent[g].child = child_off[g];
-    }
-    if ((st = upload(&ix->d_ent, ent, &ix->device_bytes)) != PPV_OK) return st;
-    if ((st = upload(&ix->d_node_lo, node_lo, &ix->device_bytes)) != PPV_OK) return st;
-    if ((st = upload(&ix->d_node_hi, node_hi, &ix->device_bytes)) != PPV_OK) return st;
-    if ((st = upload(&ix->d_heavy_slot, heavy_slot, &ix->device_bytes)) != PPV_OK) return st;
-    if ((st = upload(&ix->d_heavy_bits, heavy_bits, &ix->device_bytes)) != PPV_OK) return st;
-    if ((st = upload(&ix->d_heavy_rank, heavy_rank, &ix->device_bytes)) != PPV_OK) return st;
-    if ((st = upload(&ix->d_x_tok, x_tok, &ix->device_bytes)) != PPV_OK) return st;
-    if ((st = upload(&ix->d_x_off, x_off, &ix->device_bytes)) != PPV_OK) return st;
-    ix->n_tokens = (int64_t)x_tok.size();
-    ix->n_heavy = (int64_t)n_heavy;
+    ix->n_tokens = n_tok;
+    ix->n_heavy = n_heavy;
     ix->view.ent = ix->d_ent;
     ix->view.node_lo = ix->d_node_lo;
     ix->view.node_hi = ix->d_node_hi;
     ix->view.heavy_slot = ix->d_heavy_slot;
     ix->view.heavy_bits = ix->d_heavy_bits;
     ix->view.heavy_rank = ix->d_heavy_rank;
-    ix->view.heavy_limit = (uint32_t)heavy_slot.size();
+    ix->view.heavy_limit = heavy_limit;
     ix->view.heavy_min = heavy_min;
-    ix->view.n_nodes = (uint32_t)G;
-    ix->view.n_rows = (uint32_t)n_rows;
+    ix->view.n_nodes = G;
+    ix->view.n_rows = n_rows;
     ix->view.vocab = vocab;
     ix->view.n_words = n_words;
     ix->view.l_max = l_max;
@@ -209,16 +618,18 @@ extern "C" ppv_status ppv_build_index(const int32_t *tokens, const int64_t *offs
     if (vocab > PPV_MAX_VOCAB) return PPV_ERANGE;
     ppv_index *ix = new (std::nothrow) ppv_index();
     if (!ix) return PPV_ENOMEM;
-    if (hipGetDevice(&ix->device) != hipSuccess) { delete ix; return PPV_EDEVICE; }
-    ppv_status st;
-    try {
-        st = build_impl(tokens, offsets, n_seq, vocab, ix);
-    } catch (const std::bad_alloc &) {
-        st = PPV_ENOMEM;
-    } catch (...) {
-        st = PPV_EDEVICE;
+    if (hipGetDevice(&ix->device) != hipSuccess) {
+        (void)hipGetLastError();
+        delete ix;
+        return PPV_EDEVICE;
     }
-    if (st != PPV_OK) { release(ix); return st; }
+    ppv_status st = build_on_device(tokens, offsets, n_seq, vocab, ix);
+    if (st != PPV_OK) {
+        (void)hipDeviceSynchronize();
+        (void)hipGetLastError();
+        release(ix);
+        return st;
+    }
     *out = ix;
     return PPV_OK;
 }

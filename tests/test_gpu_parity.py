@@ -60,6 +60,30 @@ def test_index_is_sorted_deduplicated_S(name):
         assert sorted(map(bytes, M.astype(np.int32))) == sorted(map(bytes, S.padded(-1)))
 
 
+def test_index_build_with_duplicates_and_nesting():
+    """Small alphabet, short ragged rows: many duplicates, many members that are prefixes of others.
+    The exported rows must be exactly sorted(set(S)) in the order of Section 3.2 "Array Preparation"."""
+    rng = np.random.default_rng(21)
+    V = 5
+    seqs = [rng.integers(0, V, size=int(rng.integers(1, 9))).tolist() for _ in range(30_000)]
+    S = W.constraint_set_from_lists(seqs, V)
+    index = ppv.ppv_build_index(S.tokens, S.offsets, V)
+    want = sorted(set(map(tuple, seqs)))                       # tuple order: left to right, prefix first
+    tok, off = ppv.ppv_index_export(index)
+    got = [tuple(tok[off[i]:off[i + 1]].tolist()) for i in range(index.n_distinct)]
+    assert got == want
+    prefixes = {s[:k] for s in want for k in range(1, len(s) + 1)}
+    assert index.n_prefixes == len(prefixes) and index.l_max == max(map(len, want))
+    trie = oracle.Trie(S.tokens, S.offsets, V)
+    q = [list(p) for p in list(prefixes)[:500]] + [list(p) + [4] for p in list(prefixes)[:200]] + [[]]
+    stride = max(map(len, q))
+    P = np.full((len(q), stride), W.PAD_TOKEN, np.int32)
+    L = np.array([len(x) for x in q], np.int32)
+    for i, x in enumerate(q):
+        P[i, :len(x)] = x
+    assert_query_parity(index, trie, P, L)
+
+
 @pytest.mark.parametrize("name", list(CASES))
 def test_mask_range_member_parity(name):
     cfg, S, trie, index = setup_case(name)
