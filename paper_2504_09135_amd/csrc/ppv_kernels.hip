@@ -214,7 +214,10 @@ template <typename T> struct TileGeom {
     static constexpr int LANES_PER_WORD = 32 / EPL;
 };
 
-struct RawTile { uint4 r[4]; };
+struct RawTile {
+    uint4 r[4];
+    uint32_t word;   // image path: this lane's word of the tile's mask (requested together with the tile)
+};
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
@@ -253,13 +256,33 @@ __device__ inline void load_tile(const T *__restrict__ row, int V, int tile, int
     }
 }
 
-// word wi of a V-bit image, with bits at positions >= V cleared (0 beyond the image)
+// a tile known to lie wholly inside the row: four unconditional streaming loads
+template <typename T>
+__device__ inline void load_full_tile(const T *__restrict__ row, int tile, int lane, RawTile &rt) {
+    using G = TileGeom<T>;
+    const u32x4 *p = (const u32x4 *)(row + (size_t)tile * G::TILE + lane * G::EPL);
+#pragma unroll
+    for (int j = 0; j < 4; j++) {
+        u32x4 v = __builtin_nontemporal_load(p + j * WAVE);
+        rt.r[j] = make_uint4(v.x, v.y, v.z, v.w);
+    }
+}
+
+// word wi of a V-bit image, with bits at positions >= V cleared (0 beyond the image).  The load
+// itself is unconditional (clamped index): a conditional load would make later waits conservative.
 __device__ inline uint32_t image_word(const uint32_t *__restrict__ image, int wi, int V) {
     const int n_words = (V + 31) / 32;
-    if (wi >= n_words) return 0u;
-    uint32_t w = image[wi];
-    if (wi == n_words - 1 && (V & 31)) w &= (1u << (V & 31)) - 1u;
-    return w;
+    const int last = n_words - 1;
+    uint32_t w = image[wi < last ? wi : last];
+    if (wi == last && (V & 31)) w &= (1u << (V & 31)) - 1u;
+    return wi <= last ? w : 0u;
+}
+// the tile's mask word for this lane (lane l < WORDS holds word l of the tile)
+template <typename T>
+__device__ inline uint32_t tile_mask_word(const uint32_t *__restrict__ image, int tile, int lane, int V) {
+    using G = TileGeom<T>;
+    const uint32_t w = image_word(image, tile * G::WORDS + (lane < G::WORDS ? lane : 0), V);
+    return lane < G::WORDS ? w : 0u;
 }
 
 // mask bits of this lane's EPL tokens of load j, from the tile's mask words (lane l < WORDS holds word l)
@@ -425,6 +448,77 @@ struct RowOut {
 
 enum ValidMode { VALID_NONE = 0, VALID_LIST = 1, VALID_IMAGE = 2 };
 
+// Streams a row's tiles through one wavefront's share of the work: wave `wave` of `nw` takes the
+// tiles wave, wave+nw, ...  Per tile the statistics go to LDS.
+//
+// Full tiles go through a software pipeline of three register tiles X, Y, Z.  Each is reduced and
+// then at once reloaded with the tile three turns ahead, so that two tiles (8 KB per wavefront)
+// are always in flight behind the one being reduced.  The steady loop has no conditional load:
+// every wait in it is for loads issued a known number of loads ago, so the compiler's wait
+// counters leave the younger loads in flight (a conditional load anywhere on the way to a use
+// makes it wait for everything).  The row's ragged last tile, if any, is taken with the guarded
+// loader by the wave whose turn it is.
+template <typename T, bool IMAGE>
+__device__ inline void stream_tiles(const T *__restrict__ row, int V, const RawTile &first,
+                                    const uint32_t *__restrict__ image, RowShared &sh, int lane, int wave_v,
+                                    int nw) {
+    using G = TileGeom<T>;
+    const int wave = __builtin_amdgcn_readfirstlane(wave_v);   // scalar: loop control stays uniform
+    const int nt = (V + G::TILE - 1) / G::TILE;
+    const int nfull = V / G::TILE;
+    if (wave >= nt) return;
+    auto reduce_tile = [&](const RawTile &t, int k) {
+        float m, zall, zval;
+        tile_stats<T, IMAGE>(t, IMAGE ? t.word : 0u, lane, m, zall, zval);
+        if (lane == 0) {
+            sh.tile_m[k] = m;
+            sh.tile_zall[k] = zall;
+            sh.tile_zval[k] = zval;
+            sh.tile_ref[k] = m;
+        }
+    };
+    auto fetch = [&](RawTile &t, int k) {   // a full tile and, on the image path, its mask word
+        load_full_tile<T>(row, k, lane, t);
+        if (IMAGE) t.word = tile_mask_word<T>(image, k, lane, V);
+    };
+    // this wave's full tiles are wave + i*nw for i in [0, cnt); `first` is i = 0 (or the ragged tile)
+    const int cnt = wave < nfull ? (nfull - wave + nw - 1) / nw : 0;
+    int i = 0;
+    RawTile X = first, Y, Z;   // the same three register tiles serve every path below
+    if (IMAGE) X.word = tile_mask_word<T>(image, wave, lane, V);
+    if (cnt >= 6) {
+        fetch(Y, wave + nw);
+        fetch(Z, wave + 2 * nw);
+        while (i + 5 < cnt) {
+            reduce_tile(X, wave + i * nw);
+            fetch(X, wave + (i + 3) * nw);
+            reduce_tile(Y, wave + (i + 1) * nw);
+            fetch(Y, wave + (i + 4) * nw);
+            reduce_tile(Z, wave + (i + 2) * nw);
+            fetch(Z, wave + (i + 5) * nw);
+            i += 3;
+        }
+        reduce_tile(X, wave + i * nw);
+        reduce_tile(Y, wave + (i + 1) * nw);
+        reduce_tile(Z, wave + (i + 2) * nw);
+        i += 3;
+    } else if (cnt > 0 || wave == nfull) {
+        reduce_tile(X, wave);   // a single full tile, or the ragged one when the wave has nothing else
+        i = 1;
+    }
+    // what is left (a turn of fewer than six tiles is not pipelined: a second pipeline for short turns
+    // cost 30 more registers and was slower), and perhaps the ragged tail
+    for (; i < cnt; i++) {
+        fetch(Z, wave + i * nw);
+        reduce_tile(Z, wave + i * nw);
+    }
+    if (nfull < nt && nfull % nw == wave && wave != nfull) {
+        load_tile<T>(row, V, nfull, lane, Z);
+        if (IMAGE) Z.word = tile_mask_word<T>(image, nfull, lane, V);
+        reduce_tile(Z, nfull);
+    }
+}
+
 // Streams the row and samples.  Called by every thread of the workgroup with uniform arguments.
 //   first        this wave's first tile, already loaded (the wave owns tiles wave, wave+nw, ...)
 //   mode         VALID_LIST: sh.list_tok[0..n_list) holds the valid tokens (in LDS, barrier done)
@@ -450,27 +544,9 @@ __device__ inline RowOut row_sample(const T *__restrict__ row, int V, const RawT
         }
     }
 
-    // ---- stream: every tile once; the wave's next tile is requested before the current one is reduced
-    RawTile rt = first;
-    for (int k = wave; k < nt; k += nw) {
-        RawTile nx;
-        const bool more = k + nw < nt;
-        if (more) load_tile<T>(row, V, k + nw, lane, nx);
-        float m, zall, zval;
-        if (mode == VALID_IMAGE) {
-            const uint32_t word = (lane < G::WORDS) ? image_word(image, k * G::WORDS + lane, V) : 0u;
-            tile_stats<T, true>(rt, word, lane, m, zall, zval);
-        } else {
-            tile_stats<T, false>(rt, 0u, lane, m, zall, zval);
-        }
-        if (lane == 0) {
-            sh.tile_m[k] = m;
-            sh.tile_zall[k] = zall;
-            sh.tile_zval[k] = zval;
-            sh.tile_ref[k] = m;
-        }
-        if (more) rt = nx;
-    }
+    // ---- stream: every tile once
+    if (mode == VALID_IMAGE) stream_tiles<T, true>(row, V, first, image, sh, lane, wave, nw);
+    else stream_tiles<T, false>(row, V, first, image, sh, lane, wave, nw);
     // ---- list path, part 2: sums per slice of 64 listed tokens, relative to the slice maximum
     if (mode == VALID_LIST) {
         for (int s = wave; s < ns; s += nw) {
@@ -523,9 +599,10 @@ __device__ inline RowOut row_sample(const T *__restrict__ row, int V, const RawT
     // to the maximum over valid tokens (the row is re-read; it is still in cache).
     if (mode == VALID_IMAGE && zv < 3.814697265625e-06) {
         __syncthreads();  // everyone has read tile_zval
+        RawTile rt;
         for (int k = wave; k < nt; k += nw) {
             load_tile<T>(row, V, k, lane, rt);
-            const uint32_t word = (lane < G::WORDS) ? image_word(image, k * G::WORDS + lane, V) : 0u;
+            const uint32_t word = tile_mask_word<T>(image, k, lane, V);
             const float mv = tile_valid_max<T>(rt, word, lane);
             if (lane == 0) sh.tile_ref[k] = mv;
         }
@@ -537,7 +614,7 @@ __device__ inline RowOut row_sample(const T *__restrict__ row, int V, const RawT
         if (Mv != -INFINITY) {
             for (int k = wave; k < nt; k += nw) {
                 load_tile<T>(row, V, k, lane, rt);
-                const uint32_t word = (lane < G::WORDS) ? image_word(image, k * G::WORDS + lane, V) : 0u;
+                const uint32_t word = tile_mask_word<T>(image, k, lane, V);
                 const float z = tile_valid_sum<T>(rt, word, lane, Mv);
                 if (lane == 0) {
                     sh.tile_zval[k] = z;
@@ -594,7 +671,7 @@ __device__ inline RowOut row_sample(const T *__restrict__ row, int V, const RawT
                 }
                 RawTile lt;
                 load_tile<T>(row, V, kt, lane, lt);
-                const uint32_t word = (lane < G::WORDS) ? image_word(image, kt * G::WORDS + lane, V) : 0u;
+                const uint32_t word = tile_mask_word<T>(image, kt, lane, V);
                 id = locate_in_tile<T>(lt, word, kt, lane, sh.tile_ref[kt], target);
             }
         } else if (mode == VALID_LIST) {
@@ -671,7 +748,7 @@ __global__ __launch_bounds__(MAX_WAVES *WAVE) void sample_kernel(const T *__rest
 
     // bits per tile (a tile's mask words are consecutive: one word per lane)
     for (int k = wave; k < nt; k += nw) {
-        const uint32_t w = (lane < G::WORDS) ? image_word(mrow, k * G::WORDS + lane, V) : 0u;
+        const uint32_t w = tile_mask_word<T>(mrow, k, lane, V);
         const int c = wave_sum((int)__popc(w));
         if (lane == 0) sh.tile_cnt[k] = c;
     }
@@ -686,7 +763,7 @@ __global__ __launch_bounds__(MAX_WAVES *WAVE) void sample_kernel(const T *__rest
             for (int q = lane; q < k; q += WAVE) base += sh.tile_cnt[q];
             base = wave_sum(base);
             const int wi = k * G::WORDS + lane;
-            uint32_t w = (lane < G::WORDS) ? image_word(mrow, wi, V) : 0u;
+            uint32_t w = tile_mask_word<T>(mrow, k, lane, V);
             int at = base + wave_incl_scan((int)__popc(w)) - (int)__popc(w);
             while (w) {
                 const int bit = __ffs((int)w) - 1;
@@ -828,15 +905,18 @@ ppv_status check_logits_args(const void *logits, ppv_dtype dt, int64_t row_strid
     return PPV_OK;
 }
 
-// Wavefronts per row (a power of two, at most one per tile).  A small batch is bound by latency:
-// eight wavefronts per row keep the whole row in flight at once (sixteen measured no better).
-// A large batch is bound by throughput: four wavefronts per row let several rows share a compute
-// unit, so that one row's reduction and sampling overlap another row's loads (measured on the
-// N=1M, V=32k decode loop: 2.1 TB/s with 16, 4.3 TB/s with 4 at B=4096).
+// Wavefronts per row: a power of two, at most one per tile and at most MAX_WAVES.  The aim is about
+// 8192 wavefronts per launch (32 per compute unit): a small batch is bound by latency and wants
+// every row spread over many wavefronts so that the whole row is in flight at once; a large batch
+// is bound by throughput and wants several rows per compute unit, so that one row's reduction and
+// sampling phase overlaps another row's loads.  Measured on the N=1M, V=32k decode loop at
+// B=4096: 2.1 TB/s with 16 wavefronts per row, 4.3 TB/s with 4; at V=256k, B=256: 1.3 TB/s with
+// 2, 3.8 TB/s with 16.
 int waves_for(int V, ppv_dtype dt, int B) {
     const int tile = (dt == PPV_F32) ? TileGeom<float>::TILE : TileGeom<uint16_t>::TILE;
     const int nt = (V + tile - 1) / tile;
-    int cap = (B <= 512) ? 8 : 4;
+    int cap = 4;
+    while (cap < MAX_WAVES && (int64_t)cap * B < 8192) cap <<= 1;
     if (const char *e = getenv("PPV_WAVES_PER_ROW")) {  // tuning aid
         const int v = atoi(e);
         if (v >= 1 && v <= MAX_WAVES) cap = v;
