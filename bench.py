@@ -55,6 +55,7 @@ class LoopBench:
         self.logx = torch.zeros((B,), dtype=torch.float32, device=dev)
         self.ids = torch.zeros((B,), dtype=torch.int32, device=dev)
         self.lz = torch.zeros((B,), dtype=torch.float32, device=dev)
+        self.logits, self.uniforms = logits, uniforms
         self.step_logits = [logits[s] for s in range(L)]
         self.step_uniforms = [uniforms[s] for s in range(L)]
         self.loop()                                            # eager once: loads the kernels
@@ -86,18 +87,27 @@ class LoopBench:
             if events is not None:
                 events[s][1].record()
 
-    def time(self, warmup, steps):
+    def single_launch(self):
+        """The same loop as ONE ppv_decode_loop launch (possible here because every step's logits are resident up front)."""
+        ppv = self.ppv
+        self.lens.zero_()
+        ppv.ppv_decode_begin(self.index, self.prefixes, self.lens, self.state, self.active, self.logx)
+        ppv.ppv_decode_loop(self.index, self.prefixes, self.lens, self.active, self.logits, self.uniforms, None, None,
+                            self.logx, state=self.state)
+
+    def time(self, warmup, steps, single_launch=False):
         """Wall-clock seconds of `steps` loops (synchronised on both sides), the same region in GPU time
         by HIP events on the launch stream, and the rows' final lengths."""
         torch = self.torch
+        run = self.single_launch if single_launch else self.run
         for _ in range(warmup):
-            self.run()
+            run()
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         torch.cuda.synchronize()
         t0 = time.perf_counter()
         e0.record()
         for _ in range(steps):
-            self.run()
+            run()
         e1.record()
         torch.cuda.synchronize()
         elapsed = time.perf_counter() - t0
@@ -225,6 +235,17 @@ def main() -> int:
         "index_build_s": round(t_build, 3), "index_device_MB": round(index.device_bytes / 1e6, 1),
     }
 
+    # The same loop, same rows, as one launch (ppv_decode_loop): every workgroup stays with its row, so there
+    # is no launch boundary between decode steps.  Only possible because the logits of all steps are resident up
+    # front; with a model between the steps the per-step launch above is the real path.
+    ref_seqs, ref_lens = lb.prefixes.clone(), lb.lens.clone()
+    el1, fl1 = lb.time(args.warmup, args.steps, single_launch=True)
+    assert torch.equal(lb.prefixes, ref_seqs) and torch.equal(lb.lens, ref_lens), "single-launch loop differs"
+    out["single_launch_loop"] = {"prefix_steps_per_s": round(prefix_steps * args.steps / el1, 1),
+                                 "ms_per_loop": round(el1 / args.steps * 1e3, 4),
+                                 "GBs": round(float(bytes_per_launch.sum()) * args.steps / el1 / 1e9, 1),
+                                 "frac_of_peak": round(float(bytes_per_launch.sum()) * args.steps / el1 / 1e9 / HBM_PEAK_GBS, 4)}
+
     if not args.no_sweep:
         # Same loop with R replicas of the batch (logits drawn on the device: same distribution, not
         # checked against the oracle) to show where the kernel goes once the launch is large enough.
@@ -240,10 +261,13 @@ def main() -> int:
             sb = LoopBench(torch, ppv, W, index, lg, un, use_graph=not args.no_graph)
             el, fl = sb.time(2, 10)
             ps = int(fl.sum())
+            el1, _ = sb.time(2, 10, single_launch=True)
+            bps = algorithmic_bytes_per_prefix_step(V, 2, 1.0)
             out["batch_sweep"].append({"B": Bs, "prefix_steps_per_s": round(ps * 10 / el, 1),
-                                       "GBs": round(ps * algorithmic_bytes_per_prefix_step(V, 2, 1.0) * 10 / el / 1e9, 1),
-                                       "frac_of_peak": round(ps * algorithmic_bytes_per_prefix_step(V, 2, 1.0) * 10 / el
-                                                             / 1e9 / HBM_PEAK_GBS, 4)})
+                                       "GBs": round(ps * bps * 10 / el / 1e9, 1),
+                                       "frac_of_peak": round(ps * bps * 10 / el / 1e9 / HBM_PEAK_GBS, 4),
+                                       "single_launch_prefix_steps_per_s": round(ps * 10 / el1, 1),
+                                       "single_launch_GBs": round(ps * bps * 10 / el1 / 1e9, 1)})
             del sb, lg, un
 
     if not args.no_cpu_baseline:

@@ -173,6 +173,25 @@ ppv_status ppv_decode_step(const ppv_index_t *index, int32_t *prefixes, int32_t 
                            const float *uniforms, int32_t B, int32_t *ids, float *logZ_valid, float *logx,
                            void *stream);
 
+/*
+ * ppv_decode_loop -- the whole while loop of Algorithm 1's SampleCandidate in one launch: n_steps
+ * iterations of ppv_decode_step, each workgroup staying with its row (cursor in registers, the next
+ * step's logits requested while the current step is sampled).  For callers that hold the logits of
+ * every step up front, i.e. whose distributions do not depend on the sampled tokens (scoring a fixed
+ * proposal, replay, benchmarking the path without a model in between).  Results are identical to
+ * n_steps calls of ppv_decode_step.
+ * Arguments as in ppv_decode_step, except:
+ *   logits       step s, row b starts at element s*step_stride + b*row_stride
+ *   step_stride  elements between the [B, V] blocks of consecutive steps (a multiple of 4 (f32) / 8 (bf16))
+ *   uniforms     float[n_steps, B]
+ *   ids, logZ_valid   int32 / float [n_steps, B] or NULL; entries of steps a row did not take are not written
+ * Errors: as ppv_decode_step; PPV_EINVAL also for n_steps < 0 or a misaligned step_stride.
+ */
+ppv_status ppv_decode_loop(const ppv_index_t *index, int32_t *prefixes, int32_t prefix_stride, int32_t *lens,
+                           uint8_t *active, uint32_t *state, const void *logits, ppv_dtype dt, int64_t row_stride,
+                           int64_t step_stride, const float *uniforms, int32_t n_steps, int32_t B, int32_t *ids,
+                           float *logZ_valid, float *logx, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -23,7 +23,7 @@ PPV_MAX_VOCAB = 262144
 PPV_STATE_WORDS = 4
 
 SYMBOLS = ("ppv_status_string", "ppv_build_index", "ppv_index_info", "ppv_index_export", "ppv_free_index",
-           "ppv_next_token_mask", "constrained_sample", "ppv_decode_begin", "ppv_decode_step")
+           "ppv_next_token_mask", "constrained_sample", "ppv_decode_begin", "ppv_decode_step", "ppv_decode_loop")
 
 _lib = None
 
@@ -62,6 +62,8 @@ def load_library() -> C.CDLL:
     lib.ppv_decode_begin.argtypes = [p, p, i32, p, i32, p, p, p, p]
     lib.ppv_decode_step.restype = C.c_int
     lib.ppv_decode_step.argtypes = [p, p, i32, p, p, p, p, C.c_int, i64, p, i32, p, p, p, p]
+    lib.ppv_decode_loop.restype = C.c_int
+    lib.ppv_decode_loop.argtypes = [p, p, i32, p, p, p, p, C.c_int, i64, i64, p, i32, i32, p, p, p, p]
     _lib = lib
     return lib
 
@@ -231,3 +233,33 @@ def ppv_decode_step(index: PPVIndex, prefixes: torch.Tensor, lens: torch.Tensor,
         _dev(uniforms, torch.float32, "uniforms"), B, _dev(ids, torch.int32, "ids"),
         _dev(logZ_valid, torch.float32, "logZ_valid"), _dev(logx, torch.float32, "logx"), _stream(stream))
     _check(st, "ppv_decode_step")
+
+
+def ppv_decode_loop(index: PPVIndex, prefixes: torch.Tensor, lens: torch.Tensor, active: torch.Tensor,
+                    logits: torch.Tensor, uniforms: torch.Tensor, ids: Optional[torch.Tensor] = None,
+                    logZ_valid: Optional[torch.Tensor] = None, logx: Optional[torch.Tensor] = None,
+                    state: Optional[torch.Tensor] = None, stream=None) -> None:
+    """The whole decode loop in one launch: logits [n_steps, B, V] (f32/bf16), uniforms f32 [n_steps, B],
+    ids int32 / logZ_valid f32 [n_steps, B] (optional); everything else as ppv_decode_step."""
+    if logits.dim() != 3 or not logits.is_cuda or logits.stride(2) != 1:
+        raise ValueError("logits: need a 3-D GPU tensor [n_steps, B, V] with unit stride along the vocabulary")
+    n_steps, B, V = (int(x) for x in logits.shape)
+    dt = {torch.float32: PPV_F32, torch.bfloat16: PPV_BF16}.get(logits.dtype)
+    if dt is None:
+        raise TypeError(f"logits: float32 or bfloat16, got {logits.dtype}")
+    stride = int(prefixes.shape[1])
+    if int(prefixes.shape[0]) != B or V != index.vocab or tuple(lens.shape) != (B,) or tuple(active.shape) != (B,) \
+            or tuple(uniforms.shape) != (n_steps, B) \
+            or (state is not None and tuple(state.shape) != (B, PPV_STATE_WORDS)) \
+            or (logx is not None and tuple(logx.shape) != (B,)):
+        raise ValueError("ppv_decode_loop: shape mismatch")
+    for t, nm in ((ids, "ids"), (logZ_valid, "logZ_valid")):
+        if t is not None and tuple(t.shape) != (n_steps, B):
+            raise ValueError(f"ppv_decode_loop: {nm} must have shape [n_steps, B]")
+    st = load_library().ppv_decode_loop(
+        index.handle, _dev(prefixes, torch.int32, "prefixes"), stride, _dev(lens, torch.int32, "lens"),
+        _dev(active, torch.uint8, "active"), _dev(state, torch.int32, "state"), C.c_void_p(logits.data_ptr()), dt,
+        int(logits.stride(1)), int(logits.stride(0)), _dev(uniforms, torch.float32, "uniforms"), n_steps, B,
+        _dev(ids, torch.int32, "ids"), _dev(logZ_valid, torch.float32, "logZ_valid"),
+        _dev(logx, torch.float32, "logx"), _stream(stream))
+    _check(st, "ppv_decode_loop")

@@ -22,6 +22,7 @@ namespace {
 
 constexpr int MASK_THREADS = 256;
 constexpr int MAX_WAVES = 16;                 // wavefronts per row (workgroup of up to 1024 threads)
+constexpr int LOOP_WAVES = 8;                 // the decode-loop kernel holds more in registers: at most 512 threads
 constexpr int MAX_TILES = 256;                // PPV_MAX_VOCAB / 1024 (fp32 tiles are 1024 tokens)
 constexpr int MAX_SLICES = PPV_LIST_MAX / WAVE;
 constexpr float LOG2E = 1.44269504088896340736f;
@@ -521,12 +522,14 @@ __device__ inline void stream_tiles(const T *__restrict__ row, int V, const RawT
 
 // Streams the row and samples.  Called by every thread of the workgroup with uniform arguments.
 //   first        this wave's first tile, already loaded (the wave owns tiles wave, wave+nw, ...)
+//   next_row     optional: another row whose first tile (per wave) is to be requested into *next_first
 //   mode         VALID_LIST: sh.list_tok[0..n_list) holds the valid tokens (in LDS, barrier done)
 //                VALID_IMAGE: image (global memory, V bits) is the valid set
 //                VALID_NONE: the valid set is empty
 template <typename T>
 __device__ inline RowOut row_sample(const T *__restrict__ row, int V, const RawTile &first, int mode, int n_list,
-                                    const uint32_t *__restrict__ image, float u, RowShared &sh, int tid, int nw) {
+                                    const uint32_t *__restrict__ image, float u, RowShared &sh, int tid, int nw,
+                                    const T *__restrict__ next_row = nullptr, RawTile *next_first = nullptr) {
     using G = TileGeom<T>;
     const int lane = tid & (WAVE - 1), wave = tid / WAVE;
     const int nt = (V + G::TILE - 1) / G::TILE;
@@ -575,6 +578,9 @@ __device__ inline RowOut row_sample(const T *__restrict__ row, int V, const RawT
             }
         }
     }
+    // (decode loop) the row of the next step is known already: ask for this wave's first tile of it
+    // now, so that it travels while this row is combined and sampled
+    if (next_row && wave < nt) load_tile<T>(next_row, V, wave, lane, *next_first);
     __syncthreads();
 
     // ---- combine (every wave computes the same row totals from LDS; cheap, and saves a broadcast)
@@ -806,24 +812,28 @@ __global__ __launch_bounds__(MASK_THREADS) void decode_begin_kernel(IndexView ix
     }
 }
 
-// ppv_decode_step: take the children of the row's prefix as the valid set (list, or the ready-made
-// image of a heavy node), stream + sample, append, and report whether the extended row is in S.
-template <typename T>
-__global__ __launch_bounds__(MAX_WAVES *WAVE) void decode_step_kernel(
+// ppv_decode_step / ppv_decode_loop: take the children of the row's prefix as the valid set (list, or
+// the ready-made image of a heavy node), stream + sample, append, and report whether the extended
+// row is in S.  LOOP: the same for n_steps steps in one launch, one workgroup staying with its row;
+// the cursor lives in registers and the next step's first tiles are requested before the current
+// step is sampled (only when no child of the current prefix is a member, i.e. the row is certain to
+// go on, so nothing is fetched in vain).
+template <typename T, bool LOOP>
+__global__ __launch_bounds__(LOOP ? LOOP_WAVES * WAVE : MAX_WAVES * WAVE) void decode_kernel(
     IndexView ix, int32_t *__restrict__ prefixes, int32_t stride, int32_t *__restrict__ lens,
     uint8_t *__restrict__ active, RowState *__restrict__ state, const T *__restrict__ logits, int64_t row_stride,
-    const float *__restrict__ uniforms, int32_t *__restrict__ ids, float *__restrict__ logZ_valid,
-    float *__restrict__ logx) {
+    int64_t step_stride, const float *__restrict__ uniforms, int n_steps, int B, int32_t *__restrict__ ids,
+    float *__restrict__ logZ_valid, float *__restrict__ logx) {
     using G = TileGeom<T>;
     __shared__ RowShared sh;
     const int b = blockIdx.x, tid = threadIdx.x, lane = tid & (WAVE - 1), wave = tid / WAVE;
     const int nw = blockDim.x / WAVE;
-    // the three independent per-row loads go out together
+    // the independent per-row loads go out together
     const uint8_t on = active[b];
     int t = lens[b];
     RowState st;
     if (state) st = state[b];
-    const float u = uniforms[b];
+    float u = uniforms[b];
     if (!on) return;  // uniform for the workgroup
     const int V = ix.vocab;
     const T *row = logits + (size_t)b * (size_t)row_stride;
@@ -845,53 +855,107 @@ __global__ __launch_bounds__(MAX_WAVES *WAVE) void decode_step_kernel(
         st.cb = (uint32_t)sh.bc_i[5];
         st.ce = (uint32_t)sh.bc_i[6];
         st.slot = (st.node != PPV_NO_SLOT && st.ce - st.cb > ix.heavy_min) ? heavy_slot_of(ix, st.node) : PPV_NO_SLOT;
-    }
-    const uint32_t cb = st.cb, ce = st.ce, slot = st.slot;
-    const int nchild = (int)(ce - cb);
-    const int mode = nchild == 0 ? VALID_NONE : (slot != PPV_NO_SLOT ? VALID_IMAGE : VALID_LIST);
-    const uint32_t *image = ix.heavy_bits + (size_t)(slot != PPV_NO_SLOT ? slot : 0) * (size_t)ix.n_words;
-    if (mode == VALID_LIST) {
-        // children are sorted by token: the list is ready as it is.  One entry more than the
-        // children is taken along: it closes the last child's own children range.
-        for (int i = tid; i <= nchild; i += nw * WAVE) {
-            const NodeEnt e = ix.ent[cb + i];
-            sh.list_tok[i] = e.tok;
-            sh.list_child[i] = e.child;
-        }
         __syncthreads();
     }
-    RowOut r = row_sample<T>(row, V, first, mode, mode == VALID_LIST ? nchild : 0, image, u, sh, tid, nw);
-    if (tid == 0) {
-        const bool room = t < stride;
-        int32_t id = -1;
-        bool done = true;  // no valid token or no room: the row cannot continue
-        if (r.id >= 0 && room) {
-            id = r.id;
-            RowState nx;
-            uint32_t tokw;
-            if (mode == VALID_LIST) {
-                nx.node = cb + (uint32_t)r.pos;
-                tokw = sh.list_tok[r.pos];
-                nx.cb = sh.list_child[r.pos];
-                nx.ce = sh.list_child[r.pos + 1];
-            } else {  // child index = children before the token's word + set bits below it in the word
-                const uint32_t wv = image[id >> 5];
-                nx.node = cb + ix.heavy_rank[(size_t)slot * (size_t)ix.n_words + (id >> 5)] +
-                          (uint32_t)__popc(wv & ((1u << (id & 31)) - 1u));
-                const NodeEnt e0 = ix.ent[nx.node], e1 = ix.ent[nx.node + 1];
-                tokw = e0.tok;
-                nx.cb = e0.child;
-                nx.ce = e1.child;
+    // running log importance score (tid 0); started from the stored value so that the additions happen in
+    // the same order as with one launch per step
+    float lx = (LOOP && logx && tid == 0) ? logx[b] : 0.f;
+    bool done = false;
+    for (int s = 0; s < n_steps; s++) {
+        const uint32_t cb = st.cb, ce = st.ce, slot = st.slot;
+        const int nchild = (int)(ce - cb);
+        const int mode = nchild == 0 ? VALID_NONE : (slot != PPV_NO_SLOT ? VALID_IMAGE : VALID_LIST);
+        const uint32_t *image = ix.heavy_bits + (size_t)(slot != PPV_NO_SLOT ? slot : 0) * (size_t)ix.n_words;
+        int member_child = 0;
+        if (mode == VALID_LIST) {
+            // children are sorted by token: the list is ready as it is.  One entry more than the
+            // children is taken along: it closes the last child's own children range.
+            for (int i = tid; i <= nchild; i += nw * WAVE) {
+                const NodeEnt e = ix.ent[cb + i];
+                sh.list_tok[i] = e.tok;
+                sh.list_child[i] = e.child;
+                if (i < nchild && (e.tok & PPV_NODE_TERMINAL)) member_child = 1;
             }
-            nx.slot = (tokw & PPV_NODE_HEAVY) ? heavy_slot_of(ix, nx.node) : PPV_NO_SLOT;
-            done = (tokw & PPV_NODE_TERMINAL) != 0u;   // the extended row is itself a member
-            prefixes[(size_t)b * (size_t)stride + t] = id;
-            lens[b] = t + 1;
-            if (state) state[b] = nx;
-            if (logx) logx[b] += r.logZ_valid;
+            if (LOOP) member_child = __syncthreads_or(member_child);
+            else __syncthreads();
         }
-        if (ids) ids[b] = id;
-        if (logZ_valid) logZ_valid[b] = r.logZ_valid;
+        const bool more = LOOP && s + 1 < n_steps && t + 1 < stride && mode != VALID_NONE && !member_child;
+        RawTile next_first;
+        const T *next_row = more ? row + step_stride : nullptr;
+        float next_u = 0.f;
+        if (more) next_u = uniforms[(size_t)(s + 1) * (size_t)B + b];
+        RowOut r = row_sample<T>(row, V, first, mode, mode == VALID_LIST ? nchild : 0, image, u, sh, tid, nw,
+                                 next_row, &next_first);
+        if (tid == 0) {
+            const bool room = t < stride;
+            int32_t id = -1;
+            done = true;  // no valid token or no room: the row cannot continue
+            RowState nx = st;
+            if (r.id >= 0 && room) {
+                id = r.id;
+                uint32_t tokw;
+                if (mode == VALID_LIST) {
+                    nx.node = cb + (uint32_t)r.pos;
+                    tokw = sh.list_tok[r.pos];
+                    nx.cb = sh.list_child[r.pos];
+                    nx.ce = sh.list_child[r.pos + 1];
+                } else {  // child index = children before the token's word + set bits below it in the word
+                    const uint32_t wv = image[id >> 5];
+                    nx.node = cb + ix.heavy_rank[(size_t)slot * (size_t)ix.n_words + (id >> 5)] +
+                              (uint32_t)__popc(wv & ((1u << (id & 31)) - 1u));
+                    const NodeEnt e0 = ix.ent[nx.node], e1 = ix.ent[nx.node + 1];
+                    tokw = e0.tok;
+                    nx.cb = e0.child;
+                    nx.ce = e1.child;
+                }
+                nx.slot = (tokw & PPV_NODE_HEAVY) ? heavy_slot_of(ix, nx.node) : PPV_NO_SLOT;
+                done = (tokw & PPV_NODE_TERMINAL) != 0u;   // the extended row is itself a member
+                prefixes[(size_t)b * (size_t)stride + t] = id;
+                lx += r.logZ_valid;
+            }
+            if (ids) ids[(size_t)s * (size_t)B + b] = id;
+            if (logZ_valid) logZ_valid[(size_t)s * (size_t)B + b] = r.logZ_valid;
+            if (LOOP) {
+                sh.bc_i[2] = done ? 1 : 0;
+                sh.bc_i[3] = id >= 0 ? 1 : 0;
+                sh.bc_i[4] = (int)nx.node;
+                sh.bc_i[5] = (int)nx.cb;
+                sh.bc_i[6] = (int)nx.ce;
+                sh.bc_i[7] = (int)nx.slot;
+            } else {
+                if (id >= 0) {
+                    lens[b] = t + 1;
+                    if (state) state[b] = nx;
+                    if (logx) logx[b] += lx;
+                }
+                if (done) active[b] = 0;
+            }
+        }
+        if (!LOOP) return;
+        __syncthreads();
+        done = sh.bc_i[2] != 0;
+        if (sh.bc_i[3]) {
+            t += 1;
+            st.node = (uint32_t)sh.bc_i[4];
+            st.cb = (uint32_t)sh.bc_i[5];
+            st.ce = (uint32_t)sh.bc_i[6];
+            st.slot = (uint32_t)sh.bc_i[7];
+        }
+        __syncthreads();   // everyone has the new cursor before LDS is reused
+        if (done || s + 1 == n_steps) break;
+        row += step_stride;
+        if (more) {
+            first = next_first;
+            u = next_u;
+        } else {
+            if (wave < nt) load_tile<T>(row, V, wave, lane, first);
+            u = uniforms[(size_t)(s + 1) * (size_t)B + b];
+        }
+    }
+    if (LOOP && tid == 0) {
+        lens[b] = t;
+        if (state) state[b] = st;
+        if (logx) logx[b] = lx;
         if (done) active[b] = 0;
     }
 }
@@ -978,24 +1042,60 @@ extern "C" ppv_status ppv_decode_begin(const ppv_index_t *ix, const int32_t *pre
     return PPV_OK;
 }
 
+namespace {
+ppv_status launch_decode(const ppv_index_t *ix, int32_t *prefixes, int32_t prefix_stride, int32_t *lens, uint8_t *active,
+                         uint32_t *state, const void *logits, ppv_dtype dt, int64_t row_stride, int64_t step_stride,
+                         const float *uniforms, int32_t n_steps, int32_t B, int32_t *ids, float *logZ_valid, float *logx,
+                         void *stream, bool loop) {
+    if (!ix || B < 0 || prefix_stride < 0 || n_steps < 0) return PPV_EINVAL;
+    if (B == 0 || n_steps == 0) return PPV_OK;
+    if (!prefixes || !lens || !active || !uniforms) return PPV_EINVAL;
+    ppv_status st = check_logits_args(logits, dt, row_stride, ix->view.vocab);
+    if (st != PPV_OK) return st;
+    if (loop && n_steps > 1) {
+        const int64_t per16 = (dt == PPV_F32) ? 4 : 8;
+        if (step_stride % per16 != 0 || step_stride < 0) return PPV_EINVAL;
+    }
+    int nw = waves_for(ix->view.vocab, dt, B);
+    if (loop && nw > LOOP_WAVES) nw = LOOP_WAVES;
+    const dim3 grid((unsigned)B), block(nw * WAVE);
+    hipStream_t hs = (hipStream_t)stream;
+    RowState *rs = (RowState *)state;
+    if (dt == PPV_F32) {
+        const float *lg = (const float *)logits;
+        if (loop)
+            hipLaunchKernelGGL((decode_kernel<float, true>), grid, block, 0, hs, ix->view, prefixes, prefix_stride, lens,
+                               active, rs, lg, row_stride, step_stride, uniforms, n_steps, B, ids, logZ_valid, logx);
+        else
+            hipLaunchKernelGGL((decode_kernel<float, false>), grid, block, 0, hs, ix->view, prefixes, prefix_stride, lens,
+                               active, rs, lg, row_stride, step_stride, uniforms, 1, B, ids, logZ_valid, logx);
+    } else {
+        const uint16_t *lg = (const uint16_t *)logits;
+        if (loop)
+            hipLaunchKernelGGL((decode_kernel<uint16_t, true>), grid, block, 0, hs, ix->view, prefixes, prefix_stride,
+                               lens, active, rs, lg, row_stride, step_stride, uniforms, n_steps, B, ids, logZ_valid,
+                               logx);
+        else
+            hipLaunchKernelGGL((decode_kernel<uint16_t, false>), grid, block, 0, hs, ix->view, prefixes, prefix_stride,
+                               lens, active, rs, lg, row_stride, step_stride, uniforms, 1, B, ids, logZ_valid, logx);
+    }
+    PPV_HIP_TRY(hipGetLastError());
+    return PPV_OK;
+}
+}  // namespace
+
 extern "C" ppv_status ppv_decode_step(const ppv_index_t *ix, int32_t *prefixes, int32_t prefix_stride, int32_t *lens,
                                       uint8_t *active, uint32_t *state, const void *logits, ppv_dtype dt,
                                       int64_t row_stride, const float *uniforms, int32_t B, int32_t *ids,
                                       float *logZ_valid, float *logx, void *stream) {
-    if (!ix || B < 0 || prefix_stride < 0) return PPV_EINVAL;
-    if (B == 0) return PPV_OK;
-    if (!prefixes || !lens || !active || !uniforms) return PPV_EINVAL;
-    ppv_status st = check_logits_args(logits, dt, row_stride, ix->view.vocab);
-    if (st != PPV_OK) return st;
-    const int threads = waves_for(ix->view.vocab, dt, B) * WAVE;
-    if (dt == PPV_F32)
-        hipLaunchKernelGGL(decode_step_kernel<float>, dim3((unsigned)B), dim3(threads), 0, (hipStream_t)stream,
-                           ix->view, prefixes, prefix_stride, lens, active, (RowState *)state, (const float *)logits,
-                           row_stride, uniforms, ids, logZ_valid, logx);
-    else
-        hipLaunchKernelGGL(decode_step_kernel<uint16_t>, dim3((unsigned)B), dim3(threads), 0, (hipStream_t)stream,
-                           ix->view, prefixes, prefix_stride, lens, active, (RowState *)state,
-                           (const uint16_t *)logits, row_stride, uniforms, ids, logZ_valid, logx);
-    PPV_HIP_TRY(hipGetLastError());
-    return PPV_OK;
+    return launch_decode(ix, prefixes, prefix_stride, lens, active, state, logits, dt, row_stride, 0, uniforms, 1, B, ids,
+                         logZ_valid, logx, stream, false);
+}
+
+extern "C" ppv_status ppv_decode_loop(const ppv_index_t *ix, int32_t *prefixes, int32_t prefix_stride, int32_t *lens,
+                                      uint8_t *active, uint32_t *state, const void *logits, ppv_dtype dt,
+                                      int64_t row_stride, int64_t step_stride, const float *uniforms, int32_t n_steps,
+                                      int32_t B, int32_t *ids, float *logZ_valid, float *logx, void *stream) {
+    return launch_decode(ix, prefixes, prefix_stride, lens, active, state, logits, dt, row_stride, step_stride, uniforms,
+                         n_steps, B, ids, logZ_valid, logx, stream, true);
 }

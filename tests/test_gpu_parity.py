@@ -212,6 +212,50 @@ def test_decode_loop_parity_small(use_state):
     assert np.allclose(logx.cpu().numpy(), res.logx, rtol=1e-3, atol=1e-3)
 
 
+@pytest.mark.parametrize("name,B", [("C3s", 96), ("C1", 16), ("C2", 64)])
+def test_decode_loop_launch_equals_single_steps(name, B):
+    """ppv_decode_loop (one launch for all steps) gives bit for bit what the same number of
+    ppv_decode_step calls give: tokens, lengths, flags, cursor, per-step ids / masses, logx."""
+    cfg, S, trie, index = setup_case(name)
+    L = index.l_max
+    logits = torch.stack([logits_to_dev(cfg, W.make_logits(cfg, batch=B, step=200 + s)) for s in range(L)])
+    un = torch.stack([to_dev(W.make_uniforms(cfg, batch=B, step=200 + s)) for s in range(L)])
+    outs = []
+    for use_loop in (False, True):
+        P = torch.full((B, L), W.PAD_TOKEN, dtype=torch.int32, device=DEV)
+        lens = torch.zeros(B, dtype=torch.int32, device=DEV)
+        act = torch.zeros(B, dtype=torch.uint8, device=DEV)
+        state = torch.zeros((B, ppv.PPV_STATE_WORDS), dtype=torch.int32, device=DEV)
+        logx = torch.zeros(B, dtype=torch.float32, device=DEV)
+        ids = torch.full((L, B), -5, dtype=torch.int32, device=DEV)
+        lz = torch.full((L, B), 2.0, dtype=torch.float32, device=DEV)
+        ppv.ppv_decode_begin(index, P, lens, state, act, logx)
+        if use_loop:
+            ppv.ppv_decode_loop(index, P, lens, act, logits, un, ids, lz, logx, state=state)
+        else:
+            for s in range(L):
+                ppv.ppv_decode_step(index, P, lens, act, logits[s], un[s], ids[s], lz[s], logx, state=state)
+        torch.cuda.synchronize()
+        outs.append([t.cpu().numpy() for t in (P, lens, act, ids, lz.view(torch.int32), logx.view(torch.int32))]
+                    + [state.cpu().numpy()])
+    for a, b in zip(*outs):
+        assert np.array_equal(a, b)
+    assert not outs[0][2].any() and (outs[0][1] > 0).all()
+    # a second launch on finished rows changes nothing; a launch of fewer steps than needed can be resumed
+    P = torch.full((B, L), W.PAD_TOKEN, dtype=torch.int32, device=DEV)
+    lens = torch.zeros(B, dtype=torch.int32, device=DEV)
+    act = torch.zeros(B, dtype=torch.uint8, device=DEV)
+    state = torch.zeros((B, ppv.PPV_STATE_WORDS), dtype=torch.int32, device=DEV)
+    logx = torch.zeros(B, dtype=torch.float32, device=DEV)
+    ppv.ppv_decode_begin(index, P, lens, state, act, logx)
+    half = max(1, L // 3)
+    ppv.ppv_decode_loop(index, P, lens, act, logits[:half], un[:half], None, None, logx, state=state)
+    ppv.ppv_decode_loop(index, P, lens, act, logits[half:], un[half:], None, None, logx, state=state)
+    torch.cuda.synchronize()
+    assert np.array_equal(P.cpu().numpy(), outs[0][0]) and np.array_equal(lens.cpu().numpy(), outs[0][1])
+    assert np.array_equal(logx.view(torch.int32).cpu().numpy(), outs[0][5])
+
+
 def test_decode_begin_from_given_prefixes():
     """Resuming from arbitrary prefixes: active = (prefix of a member) and not (member); one step with
     the cursor equals one step without it."""
