@@ -192,6 +192,29 @@ ppv_status ppv_decode_loop(const ppv_index_t *index, int32_t *prefixes, int32_t 
                            int64_t step_stride, const float *uniforms, int32_t n_steps, int32_t B, int32_t *ids,
                            float *logZ_valid, float *logx, void *stream);
 
+/*
+ * ppv_disc_select -- Algorithm 1 after SampleCandidate: "Accept with probability x", at most K rounds,
+ * then importance resampling among K candidates with probability x_k / sum x_k.  The candidates of all
+ * queries have been drawn beforehand (rows of ppv_decode_step / ppv_decode_loop; logx is their log
+ * importance score), so the selection is a function of logx and the supplied uniforms.
+ * Arguments (all device pointers):
+ *   logx        float[n_candidates, Q]: candidate c of query q; candidates 0..K-1 go through the
+ *               accept/reject rounds in order, candidates K..2K-1 are the fallback's fresh ones
+ *   n_candidates  >= 2K, or >= K with reuse_rejected
+ *   accept_u    float[K, Q] in [0,1): candidate k is accepted iff exp(logx) > accept_u (compared in fp64)
+ *   resample_u  float[Q] in [0,1): the fallback takes, in candidate order, the first whose cumulative
+ *               score exceeds resample_u * (sum of scores); the last one if rounding lets none exceed it
+ *   reuse_rejected  0: the fallback uses K new candidates (the algorithm as printed); 1: it resamples among
+ *               the K rejected ones (then K = 1 is plain constrained decoding, Section 4.1 "Methods")
+ *   chosen      int32[Q]: index of the returned candidate
+ *   n_draws     int32[Q] or NULL: candidates consumed (the k of Theorem 3.1: round of acceptance, else 2K / K)
+ *   accepted    uint8[Q] or NULL: 1 iff returned by an accept round
+ * Errors: PPV_EINVAL (K <= 0, Q < 0, too few candidates, null pointer), PPV_EDEVICE.
+ */
+ppv_status ppv_disc_select(const float *logx, int32_t n_candidates, int32_t K, int32_t Q, const float *accept_u,
+                           const float *resample_u, int32_t reuse_rejected, int32_t *chosen, int32_t *n_draws,
+                           uint8_t *accepted, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -195,3 +195,52 @@ def decode_loop(trie: Trie, B: int, logits_f32_for_step: Callable[[int, np.ndarr
         step += 1
     out.steps = step
     return out
+
+
+def disc_select(logx: np.ndarray, K: int, accept_u: np.ndarray, resample_u: np.ndarray, reuse_rejected: bool = False):
+    """Algorithm 1 after SampleCandidate: the accept / reject rounds and the importance-resampling fallback,
+    for Q independent queries whose candidates have already been drawn.
+
+    logx[c, q]      log importance score of candidate c of query q (x = exp(logx) in (0, 1]); candidates
+                    0..K-1 are the ones offered to the accept/reject rounds, in order; candidates K..2K-1 are
+                    the K fresh ones of the fallback (not needed when reuse_rejected)
+    accept_u[k, q]  the uniform epsilon of round k: candidate k is accepted iff x > epsilon
+    resample_u[q]   the uniform that drives the fallback: among its K candidates, in order, the first whose
+                    cumulative score exceeds u * (sum of scores), i.e. candidate j with probability x_j / sum x
+                    (the paper fixes no procedure; the last candidate if rounding lets none exceed it)
+    reuse_rejected  False: the fallback draws K new candidates, as the algorithm is printed;
+                    True: it resamples among the K rejected ones (the reading under which K = 1 coincides with
+                    plain constrained decoding, Section 4.1 "Methods")
+    Returns chosen[q] (candidate index), n_draws[q] (candidates consumed: k+1 on acceptance in round k, else
+    2K, or K when reusing), accepted[q] (1 iff returned by an accept round).  Double precision throughout."""
+    logx = np.asarray(logx, dtype=np.float64)
+    accept_u = np.asarray(accept_u, dtype=np.float64)
+    resample_u = np.asarray(resample_u, dtype=np.float64)
+    n_cand, Q = logx.shape
+    assert accept_u.shape == (K, Q) and resample_u.shape == (Q,)
+    assert n_cand >= (K if reuse_rejected else 2 * K)
+    chosen = np.empty(Q, dtype=np.int32)
+    n_draws = np.empty(Q, dtype=np.int32)
+    accepted = np.zeros(Q, dtype=np.int32)
+    for q in range(Q):
+        done = False
+        for k in range(K):
+            if np.exp(logx[k, q]) > accept_u[k, q]:
+                chosen[q], n_draws[q], accepted[q] = k, k + 1, 1
+                done = True
+                break
+        if done:
+            continue
+        first = 0 if reuse_rejected else K
+        lw = logx[first:first + K, q]
+        w = np.exp(lw - lw.max())
+        tau = resample_u[q] * w.sum()
+        c, pick = 0.0, K - 1
+        for j in range(K):
+            c += w[j]
+            if c > tau:
+                pick = j
+                break
+        chosen[q] = first + pick
+        n_draws[q] = K if reuse_rejected else 2 * K
+    return chosen, n_draws, accepted

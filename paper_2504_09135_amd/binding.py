@@ -23,7 +23,7 @@ PPV_MAX_VOCAB = 262144
 PPV_STATE_WORDS = 4
 
 SYMBOLS = ("ppv_status_string", "ppv_build_index", "ppv_index_info", "ppv_index_export", "ppv_free_index",
-           "ppv_next_token_mask", "constrained_sample", "ppv_decode_begin", "ppv_decode_step", "ppv_decode_loop")
+           "ppv_next_token_mask", "constrained_sample", "ppv_decode_begin", "ppv_decode_step", "ppv_decode_loop", "ppv_disc_select")
 
 _lib = None
 
@@ -64,6 +64,8 @@ def load_library() -> C.CDLL:
     lib.ppv_decode_step.argtypes = [p, p, i32, p, p, p, p, C.c_int, i64, p, i32, p, p, p, p]
     lib.ppv_decode_loop.restype = C.c_int
     lib.ppv_decode_loop.argtypes = [p, p, i32, p, p, p, p, C.c_int, i64, i64, p, i32, i32, p, p, p, p]
+    lib.ppv_disc_select.restype = C.c_int
+    lib.ppv_disc_select.argtypes = [p, i32, i32, i32, p, p, i32, p, p, p, p]
     _lib = lib
     return lib
 
@@ -263,3 +265,19 @@ def ppv_decode_loop(index: PPVIndex, prefixes: torch.Tensor, lens: torch.Tensor,
         _dev(ids, torch.int32, "ids"), _dev(logZ_valid, torch.float32, "logZ_valid"),
         _dev(logx, torch.float32, "logx"), _stream(stream))
     _check(st, "ppv_decode_loop")
+
+
+def ppv_disc_select(logx: torch.Tensor, K: int, accept_u: torch.Tensor, resample_u: torch.Tensor,
+                    chosen: torch.Tensor, n_draws: Optional[torch.Tensor] = None,
+                    accepted: Optional[torch.Tensor] = None, reuse_rejected: bool = False, stream=None) -> None:
+    """DISC accept/reject rounds + importance-resampling fallback: logx f32 [n_candidates, Q], accept_u f32 [K, Q],
+    resample_u f32 [Q] -> chosen int32 [Q], n_draws int32 [Q], accepted uint8 [Q]."""
+    n_cand, Q = int(logx.shape[0]), int(logx.shape[1])
+    if tuple(accept_u.shape) != (K, Q) or tuple(resample_u.shape) != (Q,) or tuple(chosen.shape) != (Q,):
+        raise ValueError("ppv_disc_select: shape mismatch")
+    st = load_library().ppv_disc_select(
+        _dev(logx, torch.float32, "logx"), n_cand, int(K), Q, _dev(accept_u, torch.float32, "accept_u"),
+        _dev(resample_u, torch.float32, "resample_u"), 1 if reuse_rejected else 0,
+        _dev(chosen, torch.int32, "chosen"), _dev(n_draws, torch.int32, "n_draws"),
+        _dev(accepted, torch.uint8, "accepted"), _stream(stream))
+    _check(st, "ppv_disc_select")

@@ -165,13 +165,24 @@ __global__ __launch_bounds__(MASK_THREADS) void mask_kernel(IndexView ix, const 
     const bool found = bc[1] != 0u;
     const uint32_t cb = bc[2], ce = bc[3];
     uint32_t *out = mask + (size_t)b * (size_t)n_words;
+    // rows are written 16 bytes per lane when every row starts on a 16-byte boundary
+    const bool wide = (n_words & 3) == 0 && (((uintptr_t)mask) & 15u) == 0;
+    const int n_quads = n_words >> 2;
     if (found && ce - cb > ix.heavy_min) {  // ready-made image: plain copy
         const uint32_t *src = ix.heavy_bits + (size_t)heavy_slot_of(ix, node) * (size_t)n_words;
-        for (int i = tid; i < n_words; i += MASK_THREADS) out[i] = src[i];
+        if (wide && (((uintptr_t)ix.heavy_bits) & 15u) == 0) {
+            for (int i = tid; i < n_quads; i += MASK_THREADS) ((uint4 *)out)[i] = ((const uint4 *)src)[i];
+        } else {
+            for (int i = tid; i < n_words; i += MASK_THREADS) out[i] = src[i];
+        }
         return;
     }
     if (cb == ce) {  // not in S, or a member without extensions
-        for (int i = tid; i < n_words; i += MASK_THREADS) out[i] = 0u;
+        if (wide) {
+            for (int i = tid; i < n_quads; i += MASK_THREADS) ((uint4 *)out)[i] = make_uint4(0u, 0u, 0u, 0u);
+        } else {
+            for (int i = tid; i < n_words; i += MASK_THREADS) out[i] = 0u;
+        }
         return;
     }
     for (int i = tid; i < n_words; i += MASK_THREADS) img[i] = 0u;
@@ -181,7 +192,11 @@ __global__ __launch_bounds__(MASK_THREADS) void mask_kernel(IndexView ix, const 
         atomicOr(&img[v >> 5], 1u << (v & 31u));
     }
     __syncthreads();
-    for (int i = tid; i < n_words; i += MASK_THREADS) out[i] = img[i];
+    if (wide) {
+        for (int i = tid; i < n_quads; i += MASK_THREADS) ((uint4 *)out)[i] = ((const uint4 *)img)[i];
+    } else {
+        for (int i = tid; i < n_words; i += MASK_THREADS) out[i] = img[i];
+    }
 }
 
 // ------------------------------------------------------------------------------------------

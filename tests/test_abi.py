@@ -61,4 +61,6 @@ def test_argument_errors_without_device(lib):
     assert lib.constrained_sample(None, 0, 8, None, None, 0, 8, None, None, None, None) == 0
     assert lib.ppv_decode_step(None, None, 0, None, None, None, None, 0, 0, None, 0, None, None, None, None) == EINVAL
     assert lib.ppv_decode_begin(None, None, 0, None, 0, None, None, None, None) == EINVAL
+    assert lib.ppv_disc_select(None, 2, 1, 5, None, None, 0, None, None, None, None) == EINVAL
+    assert lib.ppv_disc_select(None, 1, 1, 5, None, None, 0, None, None, None, None) == EINVAL
     assert lib.ppv_decode_loop(None, None, 0, None, None, None, None, 0, 0, 0, None, 1, 1, None, None, None, None) == EINVAL

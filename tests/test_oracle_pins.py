@@ -400,3 +400,69 @@ def test_figure_1_caption_numbers():
     assert pl == pytest.approx(g["pl_used_soccer_shoes"], abs=tol)
     assert pcd == pytest.approx(g["pcd_used_soccer_shoes"], abs=tol)
     assert m == pytest.approx([g["mass_root"], g["mass_after_used"], g["mass_after_used_soccer"]], abs=tol)
+
+
+# ------------------------------------------------------------------ DISC outer loop (accept / reject / resample)
+def test_disc_expected_number_of_draws_closed_form():
+    """E[k] = (1 - p_b^K)/(1 - p_b) + K p_b^K (Theorem 3.1) when every draw is accepted with probability
+    1 - p_b independently: scores x ~ Beta(2, 3) have mean 0.4, so p_b = 0.6."""
+    rng = np.random.default_rng(12)
+    Q = 120_000
+    for K in (1, 2, 4):
+        x = rng.beta(2.0, 3.0, size=(2 * K, Q))
+        ch, nd, acc = oracle.disc_select(np.log(x), K, rng.random((K, Q)), rng.random(Q))
+        pb = 0.6
+        want = (1 - pb ** K) / (1 - pb) + K * pb ** K
+        se = nd.std() / math.sqrt(Q)
+        assert abs(nd.mean() - want) < 5 * se + 1e-9, (K, nd.mean(), want)
+        assert abs(acc.mean() - (1 - pb ** K)) < 5 * math.sqrt(pb ** K * (1 - pb ** K) / Q)
+        assert ((ch < K) == (acc == 1)).all() and ((nd == 2 * K) == (acc == 0)).all()
+
+
+def test_disc_accepted_samples_follow_P_S_on_the_theorem_2_1_toy():
+    """Candidates drawn from P^CD of the two-token construction with their scores x(a): a sample returned
+    by an accept round has law P_S = P_L(a)/P_L(S) (appendix, "Unbiased distribution for the accepted sample")."""
+    g = read_golden("thm21_construction.txt")
+    pcd = np.array([g["pcd_v1v1"], g["pcd_v1v2"], g["pcd_v2v1"]])
+    xs = np.array([g["x_v1v1"], g["x_v1v2"], g["x_v2v1"]])
+    pl = pcd * xs
+    ps = pl / pl.sum()
+    assert pl.sum() == pytest.approx(g["accept"], abs=1e-12)
+    rng = np.random.default_rng(13)
+    Q, K = 150_000, 3
+    cand = rng.choice(3, size=(2 * K, Q), p=pcd)
+    ch, nd, acc = oracle.disc_select(np.log(xs)[cand], K, rng.random((K, Q)), rng.random(Q))
+    out = cand[ch, np.arange(Q)]
+    got = np.bincount(out[acc == 1], minlength=3)
+    assert chisquare(got, ps * got.sum()).pvalue > 1e-4
+    # every round accepts with probability P_L(S)
+    assert abs((nd[acc == 1] == 1).sum() / Q - g["accept"]) < 5 * math.sqrt(g["accept"] * (1 - g["accept"]) / Q)
+    # the fallback is importance resampling among K fresh candidates: exact law by enumeration of the K-tuples
+    import itertools
+    qlaw = np.zeros(3)
+    for tup in itertools.product(range(3), repeat=K):
+        p = np.prod(pcd[list(tup)])
+        w = xs[list(tup)]
+        for j, a in enumerate(tup):
+            qlaw[a] += p * w[j] / w.sum()
+    rej = np.bincount(out[acc == 0], minlength=3)
+    assert rej.sum() > 200 and chisquare(rej, qlaw * rej.sum()).pvalue > 1e-4
+
+
+def test_disc_fallback_is_proportional_to_scores_and_K1_reuse_is_plain_constrained_decoding():
+    rng = np.random.default_rng(14)
+    Q, K = 60_000, 4
+    x = np.array([0.05, 0.2, 0.4, 0.1, 0.3, 0.15, 0.05, 0.5])
+    logx = np.log(np.tile(x[:, None], (1, Q)))
+    never = np.ones((K, Q))                                    # epsilon = 1: x > 1 never holds
+    ch, nd, acc = oracle.disc_select(logx, K, never, rng.random(Q))
+    assert (acc == 0).all() and (nd == 2 * K).all() and (ch >= K).all()
+    assert chisquare(np.bincount(ch - K, minlength=K), x[K:] / x[K:].sum() * Q).pvalue > 1e-4
+    ch, nd, acc = oracle.disc_select(logx, K, never, rng.random(Q), reuse_rejected=True)
+    assert (nd == K).all() and chisquare(np.bincount(ch, minlength=K), x[:K] / x[:K].sum() * Q).pvalue > 1e-4
+    # K = 1, reuse: whatever happens, the one constrained-decoding sample is returned
+    ch, nd, acc = oracle.disc_select(logx[:1], 1, rng.random((1, Q)), rng.random(Q), reuse_rejected=True)
+    assert (ch == 0).all() and (nd == 1).all()
+    # u = 0 picks the first fallback candidate, u -> 1 the last
+    ch, _, _ = oracle.disc_select(logx[:, :2], K, never[:, :2], np.array([0.0, 1.0 - 2 ** -40]))
+    assert ch.tolist() == [K, 2 * K - 1]
