@@ -217,7 +217,7 @@ def main() -> int:
     avg_launch_s = gpu_seconds / (args.steps * n_launch)
     bytes_per_launch_avg = float(bytes_per_launch.sum() / n_launch)
     achieved = bytes_per_launch_avg / avg_launch_s / 1e9
-    roofline = {"bound": "hbm", "kernel": "decode_step_kernel<bf16>", "achieved": round(achieved, 1),
+    roofline = {"bound": "hbm", "kernel": "decode_kernel<bf16, per-step>", "achieved": round(achieved, 1),
                 "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
                 "traffic": TRAFFIC_BYTES_PER_LAUNCH.get((cfg.name, B)),
                 "avg_launch_us": round(avg_launch_s * 1e6, 2), "launches_per_step": n_launch,

@@ -7,6 +7,9 @@ package; the HIP path never does, and this package imports nothing from the HIP 
 ``Trie.query``      valid-next-token masks, rank ranges [lo,hi) in sorted S, membership
 ``Trie.step``       query + one constrained decoding step per row (Algorithm 1, SampleCandidate body)
 ``decode_loop``     Algorithm 1's SampleCandidate for a batch of rows: extend until the row is in S
+``SortedArray``     Algorithm 2 as printed: sorted array X, top-M candidates, one binary search per candidate
+``masked_sample``   masked softmax mass + inverse-CDF sample for given masks
+``disc_select``     Algorithm 1 after SampleCandidate: accept / reject rounds and the resampling fallback
 """
 from __future__ import annotations
 
@@ -51,6 +54,15 @@ def _load():
     lib.oracle_step_batch.restype = None
     lib.oracle_step_batch.argtypes = [p, p, C.c_int32, p, C.c_int32, p, p, p, p, p, p, p, p, p, p, p, C.c_int32]
     lib.oracle_max_threads.restype = C.c_int32
+    lib.oracle_sorted_build.restype = p
+    lib.oracle_sorted_build.argtypes = [p, p, C.c_int64, C.c_int32]
+    lib.oracle_sorted_free.argtypes = [p]
+    lib.oracle_sorted_rows.restype = C.c_int64
+    lib.oracle_sorted_rows.argtypes = [p]
+    lib.oracle_topm_batch.restype = None
+    lib.oracle_topm_batch.argtypes = [p, p, C.c_int32, p, C.c_int32, p, C.c_int32, p, p, p, C.c_int32]
+    lib.oracle_sample_batch.restype = None
+    lib.oracle_sample_batch.argtypes = [p, C.c_int64, p, p, C.c_int32, p, p, p, p, p, C.c_int32]
     _lib = lib
     return lib
 
@@ -135,6 +147,72 @@ class Trie:
     def step(self, prefixes, lens, logits_f32, uniforms, want_mask: bool = True, threads: int = 1) -> StepResult:
         """query + masked softmax mass + inverse-CDF sample per row."""
         return self._run(prefixes, lens, logits_f32, uniforms, want_mask, threads)
+
+
+@dataclass
+class TopMResult:
+    top_ids: np.ndarray       # int32 [B, M] candidates in order of decreasing probability (ties: smaller id first), -1 beyond min(M, V)
+    mask_V: np.ndarray        # uint8 [B, M] verdict per candidate
+    mask: Optional[np.ndarray]  # uint8 [B, V] the extended mask
+
+
+class SortedArray:
+    """Algorithm 2 as printed: the members of S as a lexicographically sorted array, searched per candidate."""
+
+    def __init__(self, tokens: np.ndarray, offsets: np.ndarray, vocab: int):
+        lib = _load()
+        tokens = np.ascontiguousarray(tokens, dtype=np.int32)
+        offsets = np.ascontiguousarray(offsets, dtype=np.int64)
+        self.vocab = int(vocab)
+        self._h = lib.oracle_sorted_build(_ptr(tokens), _ptr(offsets), int(offsets.shape[0] - 1), int(vocab))
+        if not self._h:
+            raise ValueError("oracle_sorted_build rejected S")
+        self.n_rows = int(lib.oracle_sorted_rows(self._h))
+
+    def close(self):
+        if getattr(self, "_h", None):
+            _load().oracle_sorted_free(self._h)
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def topm(self, prefixes, lens, logits_f32, M: int, want_mask: bool = True, threads: int = 1) -> TopMResult:
+        prefixes = np.ascontiguousarray(prefixes, dtype=np.int32)
+        if prefixes.ndim == 1:
+            prefixes = prefixes[None, :]
+        lens = np.ascontiguousarray(lens, dtype=np.int32)
+        logits = np.ascontiguousarray(logits_f32, dtype=np.float32)
+        B, stride = prefixes.shape
+        assert lens.shape == (B,) and (lens >= 0).all() and (lens <= stride).all()
+        assert logits.shape == (B, self.vocab) and M >= 1
+        top = np.empty((B, M), dtype=np.int32)
+        mv = np.empty((B, M), dtype=np.uint8)
+        mask = np.empty((B, self.vocab), dtype=np.uint8) if want_mask else None
+        _load().oracle_topm_batch(self._h, _ptr(prefixes), stride, _ptr(lens), B, _ptr(logits), int(M), _ptr(top),
+                                  _ptr(mv), _ptr(mask), int(threads))
+        return TopMResult(top, mv, mask)
+
+
+def masked_sample(logits_f32: np.ndarray, mask: np.ndarray, uniforms: np.ndarray, threads: int = 1) -> StepResult:
+    """Algorithm 1's "sample a token from P (.) mask / |P (.) mask|_1" and its mass for given masks (uint8 [B, V])."""
+    logits = np.ascontiguousarray(logits_f32, dtype=np.float32)
+    mask = np.ascontiguousarray(mask, dtype=np.uint8)
+    un = np.ascontiguousarray(uniforms, dtype=np.float32)
+    B, V = logits.shape
+    assert mask.shape == (B, V) and un.shape == (B,)
+    res = StepResult(mask, None, None, None)
+    res.ids = np.empty(B, dtype=np.int32)
+    res.logZ_valid = np.empty(B, dtype=np.float64)
+    res.logZ_all = np.empty(B, dtype=np.float64)
+    res.cdf_lo = np.empty(B, dtype=np.float64)
+    res.cdf_hi = np.empty(B, dtype=np.float64)
+    _load().oracle_sample_batch(_ptr(logits), V, _ptr(mask), _ptr(un), B, _ptr(res.ids), _ptr(res.logZ_valid),
+                                _ptr(res.logZ_all), _ptr(res.cdf_lo), _ptr(res.cdf_hi), int(threads))
+    return res
 
 
 @dataclass

@@ -22,6 +22,9 @@
  *     inverse-CDF over the valid tokens in increasing token id with a supplied uniform u:
  *     the first valid v whose cumulative weight exceeds u * (total valid weight).
  *
+ *   - Algorithm 2 as printed, with M candidates instead of the whole vocabulary (second half of
+ *     this file): sorted array, top M, one binary search per candidate row, prefix check.
+ *
  * Everything floating point is done in double, sequentially in increasing token id.
  * Query tokens are compared as unsigned 32-bit integers, so a token outside [0,V) simply
  * matches nothing and sorts after every real token.
@@ -252,6 +255,155 @@ void oracle_step_batch(const otrie *t, const int32_t *prefixes, int32_t stride, 
         }
         if (!mask_out) free(mrow);
     }
+}
+
+/* ------------------------------------------------------------------------------------------
+ * Algorithm 2 as printed (the variant with M < |V| candidates), by its own steps and on its own
+ * data structure: the array X of all members in lexicographic order, searched row against row.
+ * Nothing here uses the prefix tree above.
+ *
+ *   Prepare        X = the distinct members of S sorted by token id, left to right; the padding
+ *                  that fills a shorter row sorts before every token, so a member precedes its
+ *                  extensions (rows are kept at their own length; "past the end" plays the pad).
+ *   top M          the M tokens of largest probability.  P = softmax(logits) is increasing in the
+ *                  logit, so the order is the logits' order; equal logits (always present with
+ *                  bf16) are ordered by increasing token id so that the set is unique.
+ *   candidates     V_i = a + [t_i]
+ *   search         i_m = the first row of X that is not smaller than V_i (binary search)
+ *   check          mask_V[i] = 1 iff V_i is a prefix of X[i_m]
+ *   extend         mask[t_i] = mask_V[i], every other token 0
+ */
+typedef struct {
+    int32_t *tok;   /* rows back to back */
+    int64_t *off;   /* [n + 1] */
+    int64_t n;
+    int32_t vocab;
+} osorted;
+
+static const int32_t *g_sort_tok;   /* qsort has no context argument; builds are not concurrent */
+static const int64_t *g_sort_off;
+
+/* lexicographic order of two token strings, unsigned token compare, the shorter first on a tie */
+static int lex_cmp(const int32_t *a, int64_t la, const int32_t *b, int64_t lb) {
+    int64_t m = la < lb ? la : lb;
+    for (int64_t i = 0; i < m; i++) {
+        uint32_t x = (uint32_t)a[i], y = (uint32_t)b[i];
+        if (x != y) return x < y ? -1 : 1;
+    }
+    return la < lb ? -1 : (la > lb ? 1 : 0);
+}
+static int row_cmp(const void *pa, const void *pb) {
+    int64_t a = *(const int64_t *)pa, b = *(const int64_t *)pb;
+    return lex_cmp(g_sort_tok + g_sort_off[a], g_sort_off[a + 1] - g_sort_off[a], g_sort_tok + g_sort_off[b],
+                   g_sort_off[b + 1] - g_sort_off[b]);
+}
+
+void oracle_sorted_free(osorted *x) {
+    if (!x) return;
+    free(x->tok);
+    free(x->off);
+    free(x);
+}
+
+osorted *oracle_sorted_build(const int32_t *tokens, const int64_t *offsets, int64_t n_seq, int32_t vocab) {
+    if (n_seq <= 0 || vocab <= 0) return NULL;
+    for (int64_t i = 0; i < n_seq; i++) {
+        if (offsets[i + 1] <= offsets[i]) return NULL;
+        for (int64_t j = offsets[i]; j < offsets[i + 1]; j++)
+            if (tokens[j] < 0 || tokens[j] >= vocab) return NULL;
+    }
+    int64_t *order = (int64_t *)malloc((size_t)n_seq * sizeof(int64_t));
+    osorted *x = (osorted *)calloc(1, sizeof(osorted));
+    if (!order || !x) { free(order); free(x); return NULL; }
+    for (int64_t i = 0; i < n_seq; i++) order[i] = i;
+    g_sort_tok = tokens;
+    g_sort_off = offsets;
+    qsort(order, (size_t)n_seq, sizeof(int64_t), row_cmp);
+    x->tok = (int32_t *)malloc((size_t)(offsets[n_seq] > 0 ? offsets[n_seq] : 1) * sizeof(int32_t));
+    x->off = (int64_t *)malloc((size_t)(n_seq + 1) * sizeof(int64_t));
+    if (!x->tok || !x->off) { free(order); oracle_sorted_free(x); return NULL; }
+    x->vocab = vocab;
+    x->off[0] = 0;
+    for (int64_t i = 0; i < n_seq; i++) {
+        int64_t r = order[i], len = offsets[r + 1] - offsets[r];
+        if (x->n > 0 && lex_cmp(tokens + offsets[r], len, x->tok + x->off[x->n - 1], x->off[x->n] - x->off[x->n - 1]) == 0)
+            continue; /* S is a set */
+        memcpy(x->tok + x->off[x->n], tokens + offsets[r], (size_t)len * sizeof(int32_t));
+        x->off[x->n + 1] = x->off[x->n] + len;
+        x->n++;
+    }
+    free(order);
+    return x;
+}
+int64_t oracle_sorted_rows(const osorted *x) { return x->n; }
+
+typedef struct { float l; int32_t id; } scored;
+static int scored_cmp(const void *pa, const void *pb) { /* larger logit first, then smaller id */
+    const scored *a = (const scored *)pa, *b = (const scored *)pb;
+    if (a->l > b->l) return -1;
+    if (a->l < b->l) return 1;
+    return a->id < b->id ? -1 : (a->id > b->id ? 1 : 0);
+}
+
+/* One row.  top_ids[M] and mask_V[M]: candidate i and its verdict, in order of decreasing
+ * probability; only the first min(M, V) are meaningful, the rest are -1 / 0.  mask[V] (may be
+ * NULL): one byte per token.  Returns the number of candidates, or -1 when memory runs out. */
+int32_t oracle_topm_row(const osorted *x, const int32_t *prefix, int32_t len, const float *logits, int32_t M,
+                        int32_t *top_ids, uint8_t *mask_V, uint8_t *mask) {
+    const int64_t V = x->vocab;
+    scored *sc = (scored *)malloc((size_t)V * sizeof(scored));
+    int32_t *cand = (int32_t *)malloc(((size_t)len + 1) * sizeof(int32_t));
+    if (!sc || !cand) { free(sc); free(cand); return -1; }
+    for (int64_t v = 0; v < V; v++) { sc[v].l = logits[v]; sc[v].id = (int32_t)v; }
+    qsort(sc, (size_t)V, sizeof(scored), scored_cmp);
+    const int32_t m = M < V ? M : (int32_t)V;
+    if (mask) memset(mask, 0, (size_t)V);
+    memcpy(cand, prefix, (size_t)len * sizeof(int32_t));
+    for (int32_t i = 0; i < M; i++) {
+        top_ids[i] = -1;
+        mask_V[i] = 0;
+        if (i >= m) continue;
+        top_ids[i] = sc[i].id;
+        cand[len] = sc[i].id;
+        int64_t lo = 0, hi = x->n; /* first row that is not smaller than the candidate */
+        while (lo < hi) {
+            int64_t mid = lo + (hi - lo) / 2;
+            if (lex_cmp(x->tok + x->off[mid], x->off[mid + 1] - x->off[mid], cand, (int64_t)len + 1) < 0) lo = mid + 1;
+            else hi = mid;
+        }
+        if (lo < x->n && x->off[lo + 1] - x->off[lo] >= (int64_t)len + 1 &&
+            lex_cmp(x->tok + x->off[lo], (int64_t)len + 1, cand, (int64_t)len + 1) == 0)
+            mask_V[i] = 1;
+        if (mask && mask_V[i]) mask[sc[i].id] = 1;
+    }
+    free(sc);
+    free(cand);
+    return m;
+}
+
+void oracle_topm_batch(const osorted *x, const int32_t *prefixes, int32_t stride, const int32_t *lens, int32_t B,
+                       const float *logits /* [B, V] */, int32_t M, int32_t *top_ids /* [B, M] */,
+                       uint8_t *mask_V /* [B, M] */, uint8_t *mask /* [B, V] or NULL */, int32_t threads) {
+    const int64_t V = x->vocab;
+#ifdef _OPENMP
+#pragma omp parallel for schedule(dynamic, 1) num_threads(threads > 0 ? threads : 1)
+#endif
+    for (int32_t b = 0; b < B; b++)
+        oracle_topm_row(x, prefixes + (size_t)b * (size_t)stride, lens[b], logits + (size_t)b * (size_t)V, M,
+                        top_ids + (size_t)b * (size_t)M, mask_V + (size_t)b * (size_t)M,
+                        mask ? mask + (size_t)b * (size_t)V : NULL);
+}
+
+/* masked softmax mass + inverse-CDF sample for rows whose masks are given (one byte per token) */
+void oracle_sample_batch(const float *logits, int64_t V, const uint8_t *mask, const float *uniforms, int32_t B,
+                         int32_t *ids, double *logZ_valid, double *logZ_all, double *cdf_lo, double *cdf_hi,
+                         int32_t threads) {
+#ifdef _OPENMP
+#pragma omp parallel for schedule(dynamic, 1) num_threads(threads > 0 ? threads : 1)
+#endif
+    for (int32_t b = 0; b < B; b++)
+        oracle_masked_sample(logits + (size_t)b * (size_t)V, V, mask + (size_t)b * (size_t)V, (double)uniforms[b],
+                             ids + b, logZ_valid + b, logZ_all + b, cdf_lo + b, cdf_hi + b);
 }
 
 int32_t oracle_max_threads(void) {

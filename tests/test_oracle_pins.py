@@ -466,3 +466,102 @@ def test_disc_fallback_is_proportional_to_scores_and_K1_reuse_is_plain_constrain
     # u = 0 picks the first fallback candidate, u -> 1 the last
     ch, _, _ = oracle.disc_select(logx[:, :2], K, never[:, :2], np.array([0.0, 1.0 - 2 ** -40]))
     assert ch.tolist() == [K, 2 * K - 1]
+
+
+# ------------------------------------------------------------------ Algorithm 2 as printed (top-M candidates)
+def brute_topm(S_lists, prefix, logits_row, M):
+    """Top M by python's sort (larger logit first, smaller id first on ties); a candidate is valid iff some
+    member of S starts with prefix + [t] -- the definition, by scanning S."""
+    V = len(logits_row)
+    order = sorted(range(V), key=lambda v: (-float(logits_row[v]), v))[:min(M, V)]
+    x = [u32(t) for t in prefix]
+    verdict = []
+    for t in order:
+        c = x + [t]
+        verdict.append(int(any(len(s) >= len(c) and [u32(a) for a in s[:len(c)]] == c for s in S_lists)))
+    return order, verdict
+
+
+def test_topm_vs_bruteforce_tiny_sets():
+    rng = np.random.default_rng(11)
+    for trial in range(30):
+        V = int(rng.integers(3, 40))
+        n = int(rng.integers(1, 60))
+        S_lists = [rng.integers(0, V, size=int(rng.integers(1, 6))).tolist() for _ in range(n)]
+        S = W.constraint_set_from_lists(S_lists, V)
+        X = oracle.SortedArray(S.tokens, S.offsets, V)
+        assert X.n_rows == len({tuple(s) for s in S_lists})
+        prefixes = [[]] + [s[:k] for s in S_lists[:8] for k in range(len(s) + 1)] + [[V + 5], [0, 0, 0, 0, 0, 0, 0]]
+        # coarse logits so that ties at the cut are common
+        for M in (1, 2, V // 2 + 1, V, V + 3):
+            for p in prefixes:
+                lg = (rng.integers(-3, 4, size=V) * 0.5).astype(np.float32)
+                P = np.full((1, 8), W.PAD_TOKEN, dtype=np.int32)
+                P[0, :len(p)] = p
+                r = X.topm(P, np.array([len(p)], np.int32), lg[None, :], M)
+                order, verdict = brute_topm(S_lists, p, lg, M)
+                m = len(order)
+                assert r.top_ids[0, :m].tolist() == order and (r.top_ids[0, m:] == -1).all()
+                assert r.mask_V[0, :m].tolist() == verdict and (r.mask_V[0, m:] == 0).all()
+                want = np.zeros(V, np.uint8)
+                for t, ok in zip(order, verdict):
+                    want[t] = ok
+                assert np.array_equal(r.mask[0], want)
+
+
+def test_topm_mask_is_full_mask_intersected_with_top_M_second_route():
+    """mask_topM = A_{a,S} restricted to the top-M tokens: the printed algorithm (sorted array + binary search per
+    candidate) against the prefix tree's full mask and numpy's stable argsort -- two routes that share no code."""
+    cfg = W.CONFIGS["C2"]
+    S = W.make_constraint_set(cfg)
+    X = oracle.SortedArray(S.tokens, S.offsets, cfg.vocab)
+    trie = oracle.Trie(S.tokens, S.offsets, cfg.vocab)
+    assert X.n_rows == trie.n_members
+    pb = W.make_prefix_batch(cfg, S)
+    B = min(cfg.batch, 48)
+    P, L = pb.prefixes[:B], pb.lens[:B]
+    L = L.copy()
+    L[:4] = 0                                            # the root too (largest fan-out)
+    lg = W.logits_as_f32(cfg, W.make_logits(cfg))[:B]
+    full = trie.query(P, L).mask
+    for M in (1, 50, 500, 1000, cfg.vocab):
+        r = X.topm(P, L, lg, M, threads=4)
+        m = min(M, cfg.vocab)
+        for b in range(B):
+            order = np.argsort(-lg[b].astype(np.float64), kind="stable")[:m]     # stable: ties keep increasing id
+            assert np.array_equal(r.top_ids[b, :m], order)
+            want = np.zeros(cfg.vocab, np.uint8)
+            want[order] = full[b, order]
+            assert np.array_equal(r.mask[b], want)
+            assert np.array_equal(r.mask_V[b, :m], full[b, order])
+        if M == cfg.vocab:
+            assert np.array_equal(r.mask, full)           # "in theory M = |V|": nothing is missed
+
+
+def test_topm_ties_and_signed_zero():
+    """Equal probabilities are ordered by token id; -0.0 and +0.0 are the same logit."""
+    S = W.constraint_set_from_lists([[0], [1], [2], [3], [4], [5]], 6)
+    X = oracle.SortedArray(S.tokens, S.offsets, 6)
+    lg = np.array([[0.0, -0.0, 1.0, -0.0, 0.0, -1.0]], np.float32)
+    r = X.topm(np.zeros((1, 1), np.int32), np.zeros(1, np.int32), lg, 3)
+    assert r.top_ids[0].tolist() == [2, 0, 1]
+    assert r.mask_V[0].tolist() == [1, 1, 1]
+
+
+def test_masked_sample_with_topm_mask_matches_renormalised_top_M_distribution():
+    """With every token valid in S, sampling through the top-M mask is sampling from P renormalised over the top
+    M tokens, and the reported mass is their total probability (checked against scipy)."""
+    V, M = 50, 7
+    S = W.constraint_set_from_lists([[v] for v in range(V)], V)
+    X = oracle.SortedArray(S.tokens, S.offsets, V)
+    rng = np.random.default_rng(5)
+    lg = rng.normal(0, 2, size=(1, V)).astype(np.float32)
+    r = X.topm(np.zeros((1, 1), np.int32), np.zeros(1, np.int32), lg, M)
+    top = np.sort(r.top_ids[0])
+    logp = lg[0].astype(np.float64) - logsumexp(lg[0].astype(np.float64))
+    p_top = np.exp(logp[top])
+    for u in (0.0, 0.3, 0.77, 0.999):
+        s = oracle.masked_sample(lg, r.mask, np.array([u], np.float32))
+        assert abs(s.logZ_valid[0] - math.log(p_top.sum())) < 1e-12
+        cdf = np.cumsum(p_top) / p_top.sum()
+        assert s.ids[0] == top[np.searchsorted(cdf, np.float32(u), side="right")]
