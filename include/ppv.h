@@ -46,6 +46,7 @@ typedef enum {
 typedef enum { PPV_F32 = 0, PPV_BF16 = 1 } ppv_dtype;
 
 #define PPV_MAX_VOCAB 262144 /* the per-row bit image (V/8 bytes) is staged in one workgroup's LDS */
+#define PPV_TOPM_MAX 1024    /* largest M of ppv_topm_mask (the paper's experiments use 50 to 1000) */
 
 const char *ppv_status_string(ppv_status s);
 
@@ -191,6 +192,32 @@ ppv_status ppv_decode_loop(const ppv_index_t *index, int32_t *prefixes, int32_t 
                            uint8_t *active, uint32_t *state, const void *logits, ppv_dtype dt, int64_t row_stride,
                            int64_t step_stride, const float *uniforms, int32_t n_steps, int32_t B, int32_t *ids,
                            float *logZ_valid, float *logx, void *stream);
+
+/*
+ * ppv_topm_mask -- Algorithm 2 with M < |V| candidates, as the paper ran it (M = 50; 100, 500, 1000
+ * in the appendix study of M): "Compute the top M entries of P", "Construct a candidate matrix" with
+ * rows a + [t_i], "Simultaneously perform a binary search for each candidate", "Extend mask_V to
+ * mask"; Section 3.2 "Selection of top candidate tokens".  The result is the mask of
+ * ppv_next_token_mask restricted to the top-M tokens; feed it to constrained_sample for the
+ * sampling step of Algorithm 1.
+ * The top M are the M largest logits of the row (P = softmax(logits) has the same order); equal
+ * logits are taken in increasing token id, -0 and +0 are equal; NaNs are ordered by bit pattern
+ * (positive NaNs above +inf).  The M candidate rows share their first |a| tokens: the prefix is
+ * located once per row and each candidate is then searched by its last token.
+ * Arguments (device pointers unless noted):
+ *   index, prefixes, prefix_stride, lens   as in ppv_next_token_mask
+ *   logits      device, [B, row_stride] of dt, 16-byte aligned, row_stride >= V and a multiple of
+ *               4 (f32) / 8 (bf16); the model's next-token logits per row (temperature 1)
+ *   M           host, 1 .. PPV_TOPM_MAX; a row has min(M, V) candidates
+ *   top_ids     int32[B, M] or NULL: the row's candidates t_i in increasing token id; -1 beyond min(M, V)
+ *   mask_V      uint8[B, M] or NULL: mask_V[b, i] = 1 iff a + [top_ids[b, i]] is a prefix of a member
+ *   mask        uint32[B, ceil(V/32)]: bit t set iff t is a candidate and its mask_V is 1
+ * Errors: PPV_EINVAL (null pointer, M < 1, bad dtype / alignment / stride), PPV_ERANGE (M > PPV_TOPM_MAX),
+ * PPV_EDEVICE.  B == 0 is PPV_OK.
+ */
+ppv_status ppv_topm_mask(const ppv_index_t *index, const int32_t *prefixes, int32_t prefix_stride,
+                         const int32_t *lens, const void *logits, ppv_dtype dt, int64_t row_stride, int32_t M,
+                         int32_t B, int32_t *top_ids, uint8_t *mask_V, uint32_t *mask, void *stream);
 
 /*
  * ppv_disc_select -- Algorithm 1 after SampleCandidate: "Accept with probability x", at most K rounds,

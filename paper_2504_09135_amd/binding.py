@@ -19,11 +19,13 @@ LIB_PATH = os.path.join(_PKG, "libppv_hip.so")
 PPV_OK = 0
 PPV_F32, PPV_BF16 = 0, 1
 PPV_MAX_VOCAB = 262144
+PPV_TOPM_MAX = 1024
 
 PPV_STATE_WORDS = 4
 
 SYMBOLS = ("ppv_status_string", "ppv_build_index", "ppv_index_info", "ppv_index_export", "ppv_free_index",
-           "ppv_next_token_mask", "constrained_sample", "ppv_decode_begin", "ppv_decode_step", "ppv_decode_loop", "ppv_disc_select")
+           "ppv_next_token_mask", "constrained_sample", "ppv_decode_begin", "ppv_decode_step", "ppv_decode_loop", "ppv_topm_mask",
+           "ppv_disc_select")
 
 _lib = None
 
@@ -64,6 +66,8 @@ def load_library() -> C.CDLL:
     lib.ppv_decode_step.argtypes = [p, p, i32, p, p, p, p, C.c_int, i64, p, i32, p, p, p, p]
     lib.ppv_decode_loop.restype = C.c_int
     lib.ppv_decode_loop.argtypes = [p, p, i32, p, p, p, p, C.c_int, i64, i64, p, i32, i32, p, p, p, p]
+    lib.ppv_topm_mask.restype = C.c_int
+    lib.ppv_topm_mask.argtypes = [p, p, i32, p, p, C.c_int, i64, i32, i32, p, p, p, p]
     lib.ppv_disc_select.restype = C.c_int
     lib.ppv_disc_select.argtypes = [p, i32, i32, i32, p, p, i32, p, p, p, p]
     _lib = lib
@@ -265,6 +269,26 @@ def ppv_decode_loop(index: PPVIndex, prefixes: torch.Tensor, lens: torch.Tensor,
         _dev(ids, torch.int32, "ids"), _dev(logZ_valid, torch.float32, "logZ_valid"),
         _dev(logx, torch.float32, "logx"), _stream(stream))
     _check(st, "ppv_decode_loop")
+
+
+def ppv_topm_mask(index: PPVIndex, prefixes: torch.Tensor, lens: torch.Tensor, logits: torch.Tensor, M: int,
+                  mask: torch.Tensor, top_ids: Optional[torch.Tensor] = None, mask_V: Optional[torch.Tensor] = None,
+                  stream=None) -> None:
+    """Algorithm 2 with M candidates: prefixes int32 [B, stride], lens int32 [B], logits [B, V] f32/bf16 ->
+    mask int32 [B, ceil(V/32)], top_ids int32 [B, M] (optional), mask_V uint8 [B, M] (optional)."""
+    ptr, dt, row_stride = _logits_args(logits)
+    B, stride = (int(prefixes.shape[0]), int(prefixes.shape[1])) if prefixes.dim() == 2 else (0, 0)
+    if prefixes.dim() != 2 or tuple(lens.shape) != (B,) or tuple(mask.shape) != (B, index.n_words) \
+            or tuple(logits.shape) != (B, index.vocab):
+        raise ValueError("ppv_topm_mask: shape mismatch")
+    for t, nm in ((top_ids, "top_ids"), (mask_V, "mask_V")):
+        if t is not None and tuple(t.shape) != (B, M):
+            raise ValueError(f"ppv_topm_mask: {nm} must have shape [B, M]")
+    st = load_library().ppv_topm_mask(
+        index.handle, _dev(prefixes, torch.int32, "prefixes"), stride, _dev(lens, torch.int32, "lens"), ptr, dt,
+        row_stride, int(M), B, _dev(top_ids, torch.int32, "top_ids"), _dev(mask_V, torch.uint8, "mask_V"),
+        _dev(mask, torch.int32, "mask"), _stream(stream))
+    _check(st, "ppv_topm_mask")
 
 
 def ppv_disc_select(logx: torch.Tensor, K: int, accept_u: torch.Tensor, resample_u: torch.Tensor,

@@ -63,4 +63,9 @@ def test_argument_errors_without_device(lib):
     assert lib.ppv_decode_begin(None, None, 0, None, 0, None, None, None, None) == EINVAL
     assert lib.ppv_disc_select(None, 2, 1, 5, None, None, 0, None, None, None, None) == EINVAL
     assert lib.ppv_disc_select(None, 1, 1, 5, None, None, 0, None, None, None, None) == EINVAL
+    fake = C.c_void_p(16)   # never dereferenced: the checks below come first
+    assert lib.ppv_topm_mask(None, None, 0, None, None, 0, 8, 5, 1, None, None, None, None) == EINVAL
+    assert lib.ppv_topm_mask(fake, None, 0, None, None, 0, 8, 0, 0, None, None, None, None) == EINVAL
+    assert lib.ppv_topm_mask(fake, None, 0, None, None, 0, 8, 1025, 0, None, None, None, None) == ERANGE
+    assert lib.ppv_topm_mask(fake, None, 0, None, None, 0, 8, 5, 0, None, None, None, None) == 0
     assert lib.ppv_decode_loop(None, None, 0, None, None, None, None, 0, 0, 0, None, 1, 1, None, None, None, None) == EINVAL

@@ -1,0 +1,184 @@
+"""Parity of ppv_topm_mask (Algorithm 2 with M candidates) with the oracle that follows the printed
+algorithm on its own sorted array: candidate sets, verdicts and masks bit for bit; then the
+sampling step of Algorithm 1 through that mask."""
+import sys
+import time
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2504_09135_amd import binding as ppv
+from paper_2504_09135_amd import workloads as W
+
+from gpu_helpers import DEV, check_sample_rows, gpu_query, gpu_sample, logits_to_dev, to_dev, unpack_mask
+from test_gpu_parity import setup_case
+
+pytestmark = [pytest.mark.gpu, pytest.mark.timeout(600)]
+
+_sorted = {}
+
+
+def say(msg):
+    print(f"[{time.strftime('%H:%M:%S')}] {msg}", file=sys.stderr, flush=True)
+
+
+def sorted_array(name):
+    if name not in _sorted:
+        cfg, S, trie, index = setup_case(name)
+        _sorted[name] = oracle.SortedArray(S.tokens, S.offsets, cfg.vocab)
+    return _sorted[name]
+
+
+def gpu_topm(index, prefixes, lens, logits_dev, M):
+    B = prefixes.shape[0]
+    mask = torch.full((B, index.n_words), -1, dtype=torch.int32, device=DEV)
+    top = torch.full((B, M), -9, dtype=torch.int32, device=DEV)
+    mv = torch.full((B, M), 9, dtype=torch.uint8, device=DEV)
+    ppv.ppv_topm_mask(index, to_dev(prefixes), to_dev(lens), logits_dev, M, mask, top, mv)
+    torch.cuda.synchronize()
+    return mask, top.cpu().numpy(), mv.cpu().numpy()
+
+
+def assert_topm_parity(index, X, prefixes, lens, logits_f32, logits_dev, M, threads=8):
+    V = index.vocab
+    ref = X.topm(prefixes, lens, logits_f32, M, threads=threads)
+    dmask, top, mv = gpu_topm(index, prefixes, lens, logits_dev, M)
+    m = min(M, V)
+    # the oracle lists candidates by decreasing probability, the library by increasing token id: same set,
+    # and each candidate's verdict travels with it
+    order = np.argsort(ref.top_ids[:, :m], axis=1, kind="stable")
+    want_ids = np.take_along_axis(ref.top_ids[:, :m], order, axis=1)
+    want_mv = np.take_along_axis(ref.mask_V[:, :m], order, axis=1)
+    bad = np.nonzero((top[:, :m] != want_ids).any(axis=1))[0]
+    assert bad.size == 0, f"candidate sets differ in rows {bad[:8]} (M={M})"
+    assert np.array_equal(mv[:, :m], want_mv)
+    assert (top[:, m:] == -1).all() and (mv[:, m:] == 0).all()
+    got = unpack_mask(dmask.cpu().numpy().view(np.uint32), V)
+    assert np.array_equal(got, ref.mask)
+    return dmask, ref
+
+
+@pytest.mark.parametrize("name", ["C1", "C2", "C3s", "C4s", "C5s"])
+def test_topm_candidates_verdicts_and_mask(name):
+    cfg, S, trie, index = setup_case(name)
+    X = sorted_array(name)
+    pb = W.make_prefix_batch(cfg, S)
+    lens = pb.lens.copy()
+    lens[:3] = 0                                              # the empty prefix: heavy node, image path
+    logits = W.make_logits(cfg)
+    lf = W.logits_as_f32(cfg, logits)
+    ld = logits_to_dev(cfg, logits)
+    for M in (1, 50, 100, 500, 1000, ppv.PPV_TOPM_MAX):
+        say(f"{name}: M = {M}")
+        dmask, ref = assert_topm_parity(index, X, pb.prefixes, lens, lf, ld, M)
+        if M >= cfg.vocab:                                    # "in theory M = |V|": the full-vocabulary mask
+            _, words, _, _, _ = gpu_query(index, pb.prefixes, lens)
+            assert np.array_equal(dmask.cpu().numpy().view(np.uint32), words)
+    # the top-M mask is the full mask restricted to the candidates (independent of the oracle above)
+    dmask, top, mv = gpu_topm(index, pb.prefixes, lens, ld, 50)
+    _, words, _, _, _ = gpu_query(index, pb.prefixes, lens)
+    full = unpack_mask(words, cfg.vocab)
+    m = min(50, cfg.vocab)
+    assert np.array_equal(mv[:, :m], np.take_along_axis(full, top[:, :m].astype(np.int64), axis=1))
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_topm_ties_special_values_and_ragged_rows(dtype):
+    """Coarse logits (many equal values at the cut), -inf, +/-0, a vocabulary that is no multiple of anything."""
+    rng = np.random.default_rng(77)
+    V = 5003
+    seqs = [rng.integers(0, V, size=int(rng.integers(1, 5))).tolist() for _ in range(4000)]
+    seqs += [[int(v)] for v in range(0, V, 2)]                # wide fan-out at the root
+    S = W.constraint_set_from_lists(seqs, V)
+    X = oracle.SortedArray(S.tokens, S.offsets, V)
+    index = ppv.ppv_build_index(S.tokens, S.offsets, V)
+    B = 24
+    P = np.full((B, 4), W.PAD_TOKEN, np.int32)
+    L = np.zeros(B, np.int32)
+    for b in range(B):
+        s = seqs[b]
+        k = int(rng.integers(0, len(s) + 1))
+        P[b, :k] = s[:k]
+        L[b] = k
+    lg = (rng.integers(-4, 5, size=(B, V)) * 0.5).astype(np.float32)
+    lg[0, :] = 1.5                                            # every token equal: the first M ids
+    lg[1, ::3] = -np.inf
+    lg[2, ::2] = -0.0
+    lg[2, 1::2] = 0.0
+    lg[3, :] = -np.inf
+    lg[3, 4000:] = -3.0
+    lg[4, :] = np.linspace(-20, 20, V, dtype=np.float32)      # all distinct, increasing
+    lg[5, :] = np.linspace(20, -20, V, dtype=np.float32)
+    if dtype == "bf16":
+        Vp = (V + 7) // 8 * 8                                 # rows must start 16-byte aligned
+        bits = (lg.view(np.uint32) >> 16).astype(np.uint16)   # these values are exact in bf16 except the linspace rows
+        lf = (bits.astype(np.uint32) << 16).view(np.float32)
+        padded = np.zeros((B, Vp), np.uint16)
+        padded[:, :V] = bits
+        ld = to_dev(padded.view(np.int16)).view(torch.bfloat16)[:, :V]
+    else:
+        Vp = (V + 3) // 4 * 4
+        lf = lg
+        padded = np.zeros((B, Vp), np.float32)
+        padded[:, :V] = lg
+        ld = to_dev(padded)[:, :V]
+    for M in (1, 7, 64, 1000):
+        assert_topm_parity(index, X, P, L, lf, ld, M)
+
+
+def test_topm_then_sample_is_the_step_of_algorithm_1():
+    """mask from ppv_topm_mask -> constrained_sample, against the oracle's top-M mask -> masked sample."""
+    name = "C3s"
+    cfg, S, trie, index = setup_case(name)
+    X = sorted_array(name)
+    pb = W.make_prefix_batch(cfg, S)
+    lens = pb.lens.copy()
+    lens[:8] = 0
+    logits = W.make_logits(cfg)
+    lf = W.logits_as_f32(cfg, logits)
+    ld = logits_to_dev(cfg, logits)
+    un = W.make_uniforms(cfg)
+    for M in (50, 1000):
+        dmask, ref_t = assert_topm_parity(index, X, pb.prefixes, lens, lf, ld, M)
+        ref = oracle.masked_sample(lf, ref_t.mask, un, threads=8)
+        ids, lzv, lza = gpu_sample(cfg, ld, dmask, un)
+        check_sample_rows(cfg.dtype, ref, lambda b: ref_t.mask[b], un, ids, lzv, lza)
+        assert (ref.ids >= 0).sum() > 0
+
+
+def test_topm_full_size_C3():
+    """|S| = 1M, V = 32k, B = 256, M = 50 and 1000 at the shape bench.py times, every row against the oracle."""
+    cfg = W.CONFIGS["C3"]
+    say("C3: S, sorted array, device index")
+    S = W.make_constraint_set(cfg)
+    X = oracle.SortedArray(S.tokens, S.offsets, cfg.vocab)
+    index = ppv.ppv_build_index(S.tokens, S.offsets, cfg.vocab)
+    assert X.n_rows == index.n_distinct
+    pb = W.make_prefix_batch(cfg, S)
+    lens = pb.lens.copy()
+    lens[:16] = 0
+    logits = W.make_logits(cfg)
+    lf = W.logits_as_f32(cfg, logits)
+    ld = logits_to_dev(cfg, logits)
+    for M in (50, 1000):
+        say(f"C3: M = {M}")
+        assert_topm_parity(index, X, pb.prefixes, lens, lf, ld, M, threads=16)
+
+
+def test_topm_bad_arguments():
+    cfg, S, trie, index = setup_case("C1")
+    B = 2
+    P = torch.zeros((B, 4), dtype=torch.int32, device=DEV)
+    L = torch.zeros(B, dtype=torch.int32, device=DEV)
+    lg = torch.zeros((B, cfg.vocab), dtype=torch.float32, device=DEV)
+    mask = torch.zeros((B, index.n_words), dtype=torch.int32, device=DEV)
+    with pytest.raises(ppv.PPVError):
+        ppv.ppv_topm_mask(index, P, L, lg, 0, mask)
+    with pytest.raises(ppv.PPVError):
+        ppv.ppv_topm_mask(index, P, L, lg, ppv.PPV_TOPM_MAX + 1, mask)
+    with pytest.raises(ValueError):
+        ppv.ppv_topm_mask(index, P, L, lg[:, :-1], 5, mask)
+    ppv.ppv_topm_mask(index, P[:0], L[:0], lg[:0], 5, mask[:0])  # empty batch: nothing to do
+    torch.cuda.synchronize()
