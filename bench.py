@@ -274,10 +274,52 @@ def main() -> int:
                                        "single_launch_GBs": round(ps * bps * 10 / el1 / 1e9, 1)})
             del sb, lg, un
 
+    if not args.no_sweep:
+        out["topm_sweep"] = topm_sweep(cfg, S, index, logits[0], torch, ppv, W, dev)
+
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg, S, B, seqs, final_lens)
     print(json.dumps(out))
     return 0
+
+
+def topm_sweep(cfg, S, index, logits0, torch, ppv, W, dev, reps=40):
+    """Algorithm 2 with M candidates (ppv_topm_mask) against the full-vocabulary mask (ppv_next_token_mask) on
+    the config's prefix batch: microseconds per call, HIP events on the launch stream."""
+    pb = W.make_prefix_batch(cfg, S)
+    B = pb.prefixes.shape[0]
+    P, Ln = torch.from_numpy(pb.prefixes).to(dev), torch.from_numpy(pb.lens).to(dev)
+    mask = torch.zeros((B, index.n_words), dtype=torch.int32, device=dev)
+
+    def us_per_call(fn):
+        # `reps` calls captured in one HIP graph: the figure is GPU time per call (launch gaps included), not the
+        # rate at which Python can issue calls
+        fn()
+        torch.cuda.synchronize()
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            fn()
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            for _ in range(reps):
+                fn()
+        graph.replay()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        e0.record()
+        graph.replay()
+        graph.replay()
+        e1.record()
+        torch.cuda.synchronize()
+        return round(e0.elapsed_time(e1) * 1e3 / (2 * reps), 2)
+
+    res = {"B": B, "full_mask_us": us_per_call(lambda: ppv.ppv_next_token_mask(index, P, Ln, mask)), "topm_us": {}}
+    for M in (50, 100, 500, 1000):
+        res["topm_us"][str(M)] = us_per_call(lambda: ppv.ppv_topm_mask(index, P, Ln, logits0, M, mask))
+    return res
 
 
 def single_call_bench(args, cfg, torch, ppv, W, dev):

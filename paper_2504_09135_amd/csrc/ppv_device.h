@@ -57,6 +57,18 @@ __device__ inline float wave_max(float x) {
     x = fmaxf(x, dpp_self<DPP_ROW_BCAST31, 0xC>(x));     // rows 2, 3 take in lane 31
     return last_lane(x);
 }
+template <int CTRL, int ROW_MASK = 0xF, int BANK_MASK = 0xF> __device__ inline uint32_t dpp_self(uint32_t x) {
+    return (uint32_t)__builtin_amdgcn_update_dpp((int)x, (int)x, CTRL, ROW_MASK, BANK_MASK, false);
+}
+__device__ inline uint32_t wave_max(uint32_t x) {
+    x = max(x, dpp_self<DPP_QUAD_XOR1>(x));
+    x = max(x, dpp_self<DPP_QUAD_XOR2>(x));
+    x = max(x, dpp_self<DPP_ROW_HALF_MIRROR>(x));
+    x = max(x, dpp_self<DPP_ROW_MIRROR>(x));
+    x = max(x, dpp_self<DPP_ROW_BCAST15, 0xA>(x));
+    x = max(x, dpp_self<DPP_ROW_BCAST31, 0xC>(x));
+    return last_lane(x);
+}
 template <typename V> __device__ inline V wave_sum(V x) {
     x += dpp0<DPP_QUAD_XOR1>(x);
     x += dpp0<DPP_QUAD_XOR2>(x);

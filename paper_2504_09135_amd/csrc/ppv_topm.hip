@@ -3,13 +3,20 @@
 //
 // One workgroup per row.
 //   select   P = softmax(logits) is increasing in the logit, so the top M are found on the logits'
-//            bit patterns: an order-preserving 32-bit key per token, then a radix select from the
-//            most significant digit down (11 + 11 + 10 bits for fp32; bf16 keys are settled after
-//            the first two digits).  Each digit is one pass over the row with a histogram in LDS;
-//            the passes after the first find the row in cache.  Equal logits are taken in
-//            increasing token id, so the set is unique.
-//   gather   one more pass writes the selected tokens in increasing token id (each wavefront owns a
-//            contiguous part of the row, so positions come from prefix counts, not from atomics).
+//            bit patterns, through an order-preserving 32-bit key per token.  M is small against
+//            |V|, so almost every token can be turned away with one comparison:
+//              A. one pass over the row takes the maximum of every 16-byte group of tokens and
+//                 histograms the groups' maxima by their leading 13 key bits; the bin that holds
+//                 the M-th largest group maximum gives a bound L that at least M tokens reach;
+//              B. a second pass (the row is in cache now) lists the tokens that are not below L,
+//                 in token order, in LDS: usually 1.1 to 1.5 M of them;
+//              C. a radix select over that short list (13 + 10 + 9 key bits for fp32, 13 + 3 for
+//                 bf16) finds the key T of the M-th largest token; the list is then cut to the
+//                 tokens above T and the first few equal to T, in increasing token id, so the set
+//                 is unique.
+//            If the list does not fit (a flat row with thousands of equal logits at the cut, or a
+//            workgroup too small to hold it) the same radix select runs over the whole row instead,
+//            one histogram pass per digit and two more passes to gather in token order.
 //   verify   the M candidate rows share their first |a| tokens, so the prefix is located once
 //            (the same walk the full-vocabulary mask uses) and each candidate then needs one
 //            binary search for its last token among the prefix's children -- or one bit test in
@@ -24,14 +31,19 @@
 
 namespace {
 
-constexpr int TOPM_BINS = 2048;   // 11-bit digits
+constexpr int TOPM_BINS = 8192;   // the first digit has 13 bits; the histogram shares its LDS with the mask row
 constexpr int TOPM_WAVES = 16;
+constexpr int TOPM_LIST = 4096;   // capacity of the candidate list (tokens not below the bound), split evenly over the wavefronts
+constexpr int TOPM_SLOTS = 16;    // list entries per thread at most: the list path needs at least 256 threads
 
 // Bit pattern -> key with the same order as the float value (-0 and +0 share a key).
 __device__ inline uint32_t order_key(uint32_t bits) {
     if (bits == 0x80000000u) bits = 0u;
     return bits ^ ((uint32_t)((int32_t)bits >> 31) | 0x80000000u);
 }
+
+// the bit pattern whose key is k
+__device__ inline uint32_t key_to_bits(uint32_t k) { return (k & 0x80000000u) ? (k & 0x7FFFFFFFu) : ~k; }
 
 template <typename T> struct KeyChunk;   // what one 16-byte load per lane covers
 template <> struct KeyChunk<float> {
@@ -73,6 +85,54 @@ __device__ inline int load_keys(const T *__restrict__ row, int V, int c, int lan
     return n;
 }
 
+// The raw 16 bytes of this lane's tokens of chunk c; tokens at or beyond V read as -inf (memory there is
+// never touched).
+template <typename T> __device__ inline uint4 load_raw(const T *__restrict__ row, int V, int c, int lane) {
+    constexpr int EPL = KeyChunk<T>::EPL;
+    const int g = (c * WAVE + lane) * EPL;
+    if (g + EPL <= V) return *(const uint4 *)(row + g);
+    const uint32_t pad = sizeof(T) == 4 ? 0xFF800000u : 0xFF80FF80u;
+    uint32_t w[4] = {pad, pad, pad, pad};
+    for (int j = 0; j < EPL; j++)
+        if (g + j < V) {
+            if (sizeof(T) == 4) {
+                w[j % 4] = ((const uint32_t *)row)[g + j];
+            } else {
+                const uint32_t h = ((const uint16_t *)row)[g + j];
+                w[(j >> 1) % 4] = (j & 1) ? ((w[(j >> 1) % 4] & 0x0000FFFFu) | (h << 16))
+                                          : ((w[(j >> 1) % 4] & 0xFFFF0000u) | h);
+            }
+        }
+    return make_uint4(w[0], w[1], w[2], w[3]);
+}
+// four chunks at once (c .. c+3, those below c1): four loads in flight per lane
+template <typename T>
+__device__ inline void load_chunks(const T *__restrict__ row, int V, int c, int c1, int lane, uint4 (&r)[4]) {
+    const uint32_t pad = sizeof(T) == 4 ? 0xFF800000u : 0xFF80FF80u;
+#pragma unroll
+    for (int u = 0; u < 4; u++)
+        r[u] = (c + u < c1) ? load_raw<T>(row, V, c + u, lane) : make_uint4(pad, pad, pad, pad);
+}
+// how many of this lane's tokens of chunk c lie inside the row
+template <typename T> __device__ inline int n_inside(int V, int c, int lane) {
+    constexpr int EPL = KeyChunk<T>::EPL;
+    const int r = V - (c * WAVE + lane) * EPL;
+    return r < 0 ? 0 : (r > EPL ? EPL : r);
+}
+template <typename T> __device__ inline void unpack_vals(const uint4 &r, float x[KeyChunk<T>::EPL]) {
+    if (sizeof(T) == 4) {
+        x[0] = __uint_as_float(r.x); x[1] = __uint_as_float(r.y);
+        x[2 % KeyChunk<T>::EPL] = __uint_as_float(r.z); x[3 % KeyChunk<T>::EPL] = __uint_as_float(r.w);
+    } else {
+        const uint32_t w[4] = {r.x, r.y, r.z, r.w};
+#pragma unroll
+        for (int j = 0; j < 4; j++) {
+            x[(2 * j) % KeyChunk<T>::EPL] = __uint_as_float(w[j] << 16);
+            x[(2 * j + 1) % KeyChunk<T>::EPL] = __uint_as_float(w[j] & 0xFFFF0000u);
+        }
+    }
+}
+
 // inclusive prefix sum of x over the workgroup's threads in thread order; nw wavefronts
 __device__ inline uint32_t block_incl_scan(uint32_t x, uint32_t *wave_tot, int nw) {
     const int lane = threadIdx.x & (WAVE - 1), wave = threadIdx.x / WAVE;
@@ -86,92 +146,98 @@ __device__ inline uint32_t block_incl_scan(uint32_t x, uint32_t *wave_tot, int n
     return before + incl;
 }
 
-template <typename T>
-__global__ __launch_bounds__(TOPM_WAVES *WAVE) void topm_kernel(IndexView ix, const int32_t *__restrict__ prefixes,
-                                                                int32_t stride, const int32_t *__restrict__ lens,
-                                                                const T *__restrict__ logits, int64_t row_stride, int M,
-                                                                int32_t *__restrict__ top_ids,
-                                                                uint8_t *__restrict__ mask_V,
-                                                                uint32_t *__restrict__ mask) {
-    constexpr int EPL = KeyChunk<T>::EPL;
-    extern __shared__ __align__(16) uint32_t img[];   // [n_words] the row of the mask
-    __shared__ uint32_t hist[TOPM_BINS];
-    __shared__ uint32_t sel[PPV_TOPM_MAX];
-    __shared__ uint32_t seg_gt[TOPM_WAVES], seg_eq[TOPM_WAVES], wave_tot[TOPM_WAVES];
-    __shared__ uint32_t bc[8];
-    const int b = blockIdx.x, tid = threadIdx.x, lane = tid & (WAVE - 1);
-    const int wave = __builtin_amdgcn_readfirstlane(tid / WAVE);
-    const int nthreads = blockDim.x, nw = nthreads / WAVE;
-    const int V = ix.vocab, n_words = ix.n_words;
-    const int m = M < V ? M : V;                      // candidates of this row
-    const T *row = logits + (size_t)b * (size_t)row_stride;
-
-    if (wave == 0) {   // the part every candidate row shares: locate the prefix once
-        int t = lens[b];
-        t = t < 0 ? 0 : (t > stride ? stride : t);
-        const Walk w = walk_prefix(ix, prefixes + (size_t)b * (size_t)stride, t, lane);
-        if (lane == 0) {
-            bc[0] = w.node;
-            bc[1] = w.found ? 1u : 0u;
-            bc[2] = w.found ? w.cb : 0u;
-            bc[3] = w.found ? w.ce : 0u;
+// The histogram hist[0..bins) is filled.  Finds the digit d with #(digit > d) < need <= #(digit >= d) and
+// leaves it in bc[4], with need - #(digit > d) in bc[5].  If fewer than `need` entries were counted,
+// bc[4] = 0 and bc[5] = need.  Every thread calls; ends with a barrier.
+__device__ inline void pick_digit(const uint32_t *hist, int bins, uint32_t need, uint32_t *wave_tot, uint32_t *bc,
+                                  int nthreads) {
+    const int tid = threadIdx.x;
+    if (tid == 0) {
+        bc[4] = 0u;
+        bc[5] = need;
+    }
+    // thread t takes the `per` bins that end at bin top_bin (from the top); bins below 0 do not exist
+    const int per = (bins + nthreads - 1) / nthreads;
+    const int top_bin = bins - 1 - tid * per;
+    const int low_bin = top_bin - per + 1;
+    uint32_t s = 0;
+    if (low_bin >= 0 && (per & 3) == 0 && (bins & 3) == 0) {   // whole share present and 16-byte aligned
+        for (int j = 0; j < per; j += 4) {
+            const uint4 h = *(const uint4 *)(hist + low_bin + j);
+            s += h.x + h.y + h.z + h.w;
+        }
+    } else {
+        for (int j = 0; j < per; j++)
+            if (top_bin - j >= 0) s += hist[top_bin - j];
+    }
+    const uint32_t incl = block_incl_scan(s, wave_tot, nthreads / WAVE);
+    if (incl - s < need && need <= incl) {   // at most one thread
+        uint32_t acc = incl - s;
+        for (int j = 0; j < per; j++) {
+            const uint32_t h = top_bin - j >= 0 ? hist[top_bin - j] : 0u;
+            if (acc + h >= need) {
+                bc[4] = (uint32_t)(top_bin - j);
+                bc[5] = need - acc;
+                break;
+            }
+            acc += h;
         }
     }
-    for (int i = tid; i < n_words; i += nthreads) img[i] = 0u;
+    __syncthreads();
+}
 
-    // this wavefront's contiguous share of the row, in chunks of one 16-byte load per lane
-    const int nc = (V + WAVE * EPL - 1) / (WAVE * EPL);
-    const int cpw = (nc + nw - 1) / nw;
-    const int c0 = wave * cpw, c1 = (c0 + cpw < nc) ? c0 + cpw : nc;
+// digit p of the radix select: key bits [shift, previous shift)
+template <typename T> __device__ inline int digit_shift(int pass) {
+    return pass == 0 ? 19 : (sizeof(T) == 4 ? (pass == 1 ? 9 : 0) : 16);
+}
+// bf16: the low 16 bits of a key follow from its sign, so the upper half settles the whole key
+template <typename T> __device__ inline uint32_t full_key(uint32_t hi_part) {
+    return sizeof(T) == 4 ? hi_part : ((hi_part << 16) | ((hi_part >> 15) & 1u ? 0u : 0xFFFFu));
+}
 
-    // ---- select: the key T of the m-th largest token, digit by digit
+struct TopmLds {
+    uint32_t *hist;       // [TOPM_BINS]
+    uint32_t *list_tok;   // [TOPM_LIST]
+    uint32_t *sel;        // [PPV_TOPM_MAX]
+    uint32_t *seg_a, *seg_b, *wave_tot;   // [TOPM_WAVES] each
+    uint32_t *bc;         // [8]
+};
+
+// Radix select over the whole row (any workgroup size, any row): fills sel[0..m) in increasing token id.
+template <typename T>
+__device__ inline void select_streaming(const T *__restrict__ row, int V, int c0, int c1, int m, const TopmLds &s,
+                                        int lane, int wave, int nthreads) {
+    constexpr int EPL = KeyChunk<T>::EPL;
+    const int tid = threadIdx.x, nw = nthreads / WAVE;
     const int n_pass = sizeof(T) == 4 ? 3 : 2;
-    uint32_t hi_part = 0;      // digits settled so far, as the key's leading bits
+    uint32_t hi_part = 0;          // digits settled so far, as the key's leading bits
     uint32_t need = (uint32_t)m;   // how many tokens are still to be taken among those that match hi_part
+    int prev_shift = 32;
     for (int pass = 0; pass < n_pass; pass++) {
-        const int shift = pass == 0 ? 21 : (pass == 1 ? 10 : 0);
-        const int bins = pass == 2 ? 1024 : 2048;
-        for (int i = tid; i < TOPM_BINS; i += nthreads) hist[i] = 0u;
+        const int shift = digit_shift<T>(pass);
+        const int bins = 1 << (prev_shift - shift);
+        for (int i = tid; i < bins; i += nthreads) s.hist[i] = 0u;
         __syncthreads();
         for (int c = c0; c < c1; c++) {
             uint32_t k[EPL];
             const int n = load_keys<T>(row, V, c, lane, k);
 #pragma unroll
             for (int j = 0; j < EPL; j++) {
-                const bool match = pass == 0 || (k[j] >> (pass == 1 ? 21 : 10)) == hi_part;
-                if (j < n && match) atomicAdd(&hist[(k[j] >> shift) & (uint32_t)(bins - 1)], 1u);
+                const bool match = pass == 0 || (k[j] >> prev_shift) == hi_part;
+                if (j < n && match) atomicAdd(&s.hist[(k[j] >> shift) & (uint32_t)(bins - 1)], 1u);
             }
         }
         __syncthreads();
-        // bins from the top: the digit d with  #(digit > d) < need <= #(digit >= d)
-        const int per = bins / nthreads > 0 ? bins / nthreads : 1;   // consecutive bins per thread, descending
-        uint32_t s = 0;
-        const int top_bin = bins - 1 - tid * per;
-        if (top_bin >= 0)
-            for (int j = 0; j < per; j++) s += hist[top_bin - j];
-        const uint32_t incl = block_incl_scan(s, wave_tot, nw);
-        if (top_bin >= 0 && incl - s < need && need <= incl) {   // exactly one thread
-            uint32_t acc = incl - s;
-            for (int j = 0; j < per; j++) {
-                const uint32_t h = hist[top_bin - j];
-                if (acc + h >= need) {
-                    bc[4] = (uint32_t)(top_bin - j);
-                    bc[5] = need - acc;
-                    break;
-                }
-                acc += h;
-            }
-        }
-        __syncthreads();
-        hi_part = (hi_part << (pass == 2 ? 10 : 11)) | bc[4];
-        need = bc[5];
+        pick_digit(s.hist, bins, need, s.wave_tot, s.bc, nthreads);
+        hi_part = (hi_part << (prev_shift - shift)) | s.bc[4];
+        need = s.bc[5];
+        prev_shift = shift;
         __syncthreads();
     }
-    // bf16: the low 16 bits of a key follow from its sign, so two digits settle the whole key
-    const uint32_t T_key = sizeof(T) == 4 ? hi_part : ((hi_part << 10) | ((hi_part >> 21) & 1u ? 0u : 0x3FFu));
+    const uint32_t T_key = full_key<T>(hi_part);
     const uint32_t take_eq = need;   // of the tokens whose key equals T_key, the first take_eq in token order
 
-    // ---- gather in token order
+    // gather in token order: counts per wavefront share, then positions from prefix counts
     uint32_t n_gt = 0, n_eq = 0;
     for (int c = c0; c < c1; c++) {
         uint32_t k[EPL];
@@ -185,15 +251,15 @@ __global__ __launch_bounds__(TOPM_WAVES *WAVE) void topm_kernel(IndexView ix, co
     n_gt = wave_sum(n_gt);
     n_eq = wave_sum(n_eq);
     if (lane == 0) {
-        seg_gt[wave] = n_gt;
-        seg_eq[wave] = n_eq;
+        s.seg_a[wave] = n_gt;
+        s.seg_b[wave] = n_eq;
     }
     __syncthreads();
     uint32_t gt_base = 0, eq_base = 0;   // tokens of either kind in the wavefronts before this one
     for (int w = 0; w < nw; w++)
         if (w < wave) {
-            gt_base += seg_gt[w];
-            eq_base += seg_eq[w];
+            gt_base += s.seg_a[w];
+            eq_base += s.seg_b[w];
         }
     for (int c = c0; c < c1; c++) {
         uint32_t k[EPL];
@@ -212,12 +278,12 @@ __global__ __launch_bounds__(TOPM_WAVES *WAVE) void topm_kernel(IndexView ix, co
             if (j >= n) continue;
             if (k[j] > T_key) {
                 const uint32_t pos = gt_before + (eq_before < take_eq ? eq_before : take_eq);
-                if (pos < (uint32_t)m) sel[pos] = first_tok + j;
+                if (pos < (uint32_t)m) s.sel[pos] = first_tok + j;
                 gt_before++;
             } else if (k[j] == T_key) {
                 if (eq_before < take_eq) {
                     const uint32_t pos = gt_before + eq_before;
-                    if (pos < (uint32_t)m) sel[pos] = first_tok + j;
+                    if (pos < (uint32_t)m) s.sel[pos] = first_tok + j;
                 }
                 eq_before++;
             }
@@ -225,6 +291,205 @@ __global__ __launch_bounds__(TOPM_WAVES *WAVE) void topm_kernel(IndexView ix, co
         gt_base += last_lane(gi);
         eq_base += last_lane(ei);
     }
+    __syncthreads();
+}
+
+// Bound, short list, radix select over the list.  Needs nthreads >= TOPM_LIST / TOPM_SLOTS.  Returns false
+// (for every thread alike) when the list did not fit; sel is then untouched.
+template <typename T>
+__device__ inline bool select_listed(const T *__restrict__ row, int V, int c0, int c1, int m, const TopmLds &s, int lane,
+                                     int wave, int nthreads, uint4 (&r)[4]) {
+    constexpr int EPL = KeyChunk<T>::EPL;
+    const int tid = threadIdx.x, nw = nthreads / WAVE;
+    // ---- A. maxima of the 16-byte groups, histogram of their leading key bits.  The row is taken four chunks
+    // at a time (four loads in flight per lane); a share of at most four chunks stays in registers for B.
+    for (int i = tid; i < TOPM_BINS; i += nthreads) s.hist[i] = 0u;
+    if (tid == 0) s.bc[6] = 0u;
+    auto load_batch = [&](int c) { load_chunks<T>(row, V, c, c1, lane, r); };   // r arrives holding the batch at c0
+    __syncthreads();
+    for (int c = c0; c < c1; c += 4) {
+        if (c != c0) load_batch(c);
+#pragma unroll
+        for (int u = 0; u < 4; u++) {
+            float x[EPL];
+            unpack_vals<T>(r[u], x);
+            float gm = x[0];
+#pragma unroll
+            for (int j = 1; j < EPL; j++) gm = fmaxf(gm, x[j]);
+            if (c + u < c1 && n_inside<T>(V, c + u, lane) > 0)
+                atomicAdd(&s.hist[order_key(__float_as_uint(gm)) >> 19], 1u);
+        }
+    }
+    const bool kept = c1 - c0 <= 4;   // r still holds the whole share
+    __syncthreads();
+    pick_digit(s.hist, TOPM_BINS, (uint32_t)m, s.wave_tot, s.bc, nthreads);
+    // At least m groups have their maximum in this bin or above, so at least m tokens are not below the bin's
+    // lower edge.  With fewer than m groups in the row the bin is 0 and its edge is a NaN: nothing is below it.
+    const float L = __uint_as_float(key_to_bits(s.bc[4] << 19));
+    for (int i = tid; i < TOPM_BINS; i += nthreads) s.hist[i] = 0u;   // for C; the barrier after B orders it
+    // ---- B. the tokens that are not below L, in token order, each wavefront into its own part of the list
+    const uint32_t R = (uint32_t)(TOPM_LIST / nw);
+    const uint32_t base = (uint32_t)wave * R;
+    uint32_t cnt = 0;   // wave-uniform
+    for (int c = c0; c < c1; c += 4) {
+        if (!kept) load_batch(c);
+#pragma unroll
+        for (int u = 0; u < 4; u++) {
+            if (c + u >= c1) continue;
+            float x[EPL];
+            unpack_vals<T>(r[u], x);
+            const int n = n_inside<T>(V, c + u, lane);
+            uint32_t pm = 0;
+#pragma unroll
+            for (int j = 0; j < EPL; j++)
+                if (j < n && !(x[j] < L)) pm |= 1u << j;
+            const uint32_t pc = (uint32_t)__popc(pm);
+            const uint32_t incl = wave_incl_scan(pc);
+            const uint32_t tot = last_lane(incl);
+            if (tot == 0u) continue;
+            uint32_t at = cnt + incl - pc;
+            const uint32_t first_tok = (uint32_t)(((c + u) * WAVE + lane) * EPL);
+            while (pm) {
+                const int j = __ffs((int)pm) - 1;
+                if (at < R) s.list_tok[base + at] = first_tok + (uint32_t)j;
+                at++;
+                pm &= pm - 1u;
+            }
+            cnt += tot;
+        }
+    }
+    if (lane == 0) {
+        s.seg_a[wave] = cnt < R ? cnt : R;
+        if (cnt > R) atomicOr(&s.bc[6], 1u);
+    }
+    __syncthreads();
+    if (s.bc[6] != 0u) return false;
+
+    // ---- C. the key T of the m-th largest token, from the list.  Thread t holds the entries t*S .. t*S+S-1 of
+    // the list, which lie in its own wavefront's part (S = R / 64); their keys stay in registers.
+    const int S = TOPM_LIST / nthreads;
+    const uint32_t mine = s.seg_a[wave];
+    uint32_t kk[TOPM_SLOTS], tk[TOPM_SLOTS];
+    uint32_t vm = 0;
+#pragma unroll
+    for (int q = 0; q < TOPM_SLOTS; q++) {   // the gathers go out together: no condition on the way to a load
+        const uint32_t o = (uint32_t)(lane * S + q);
+        const bool have = q < S && o < mine;
+        tk[q] = have ? s.list_tok[base + o] : 0u;
+        kk[q] = q < S ? KeyChunk<T>::bits_of(row, (int)tk[q]) : 0u;
+        if (have) vm |= 1u << q;
+    }
+    // Every listed token's key is at or above the edge key (NaNs that slipped through the float comparison
+    // aside: they are dropped here), so the upper 16 key bits, counted from the edge, are small numbers: one
+    // histogram over them settles the upper half of T.  A row whose tail reaches further than the histogram
+    // is long (thousands of bf16 values above the m-th largest) goes to the whole-row select.
+    const uint32_t edge16 = s.bc[4] << 3;
+#pragma unroll
+    for (int q = 0; q < TOPM_SLOTS; q++) {   // (the histogram was cleared before B)
+        kk[q] = order_key(kk[q]);
+        if (((vm >> q) & 1u) && (kk[q] >> 16) < edge16) vm &= ~(1u << q);
+        if ((vm >> q) & 1u) {
+            uint32_t rel = (kk[q] >> 16) - edge16;
+            rel = rel < (uint32_t)(TOPM_BINS - 1) ? rel : (uint32_t)(TOPM_BINS - 1);
+            atomicAdd(&s.hist[rel], 1u);
+        }
+    }
+    __syncthreads();
+    pick_digit(s.hist, TOPM_BINS, (uint32_t)m, s.wave_tot, s.bc, nthreads);
+    if (s.bc[4] == (uint32_t)(TOPM_BINS - 1)) return false;   // T lies in the overflow bin
+    uint32_t hi_part = edge16 + s.bc[4], need = s.bc[5];
+    if (sizeof(T) == 4) {   // fp32: the lower half of T, eight bits at a time
+        for (int shift = 8; shift >= 0; shift -= 8) {
+            __syncthreads();
+            for (int i = tid; i < 256; i += nthreads) s.hist[i] = 0u;
+            __syncthreads();
+#pragma unroll
+            for (int q = 0; q < TOPM_SLOTS; q++)
+                if (((vm >> q) & 1u) && (kk[q] >> (shift + 8)) == hi_part)
+                    atomicAdd(&s.hist[(kk[q] >> shift) & 255u], 1u);
+            __syncthreads();
+            pick_digit(s.hist, 256, need, s.wave_tot, s.bc, nthreads);
+            hi_part = (hi_part << 8) | s.bc[4];
+            need = s.bc[5];
+        }
+    }
+    const uint32_t T_key = full_key<T>(hi_part);
+    const uint32_t take_eq = need;
+    // positions: list order is token order, and threads hold consecutive entries
+    uint32_t g = 0, e = 0;
+#pragma unroll
+    for (int q = 0; q < TOPM_SLOTS; q++) {
+        g += (((vm >> q) & 1u) && kk[q] > T_key) ? 1u : 0u;
+        e += (((vm >> q) & 1u) && kk[q] == T_key) ? 1u : 0u;
+    }
+    const uint32_t packed = g | (e << 16);   // both counts stay below 2^16 (the list has 4096 entries)
+    const uint32_t before = block_incl_scan(packed, s.wave_tot, nw) - packed;
+    uint32_t gt_before = before & 0xFFFFu, eq_before = before >> 16;
+#pragma unroll
+    for (int q = 0; q < TOPM_SLOTS; q++) {
+        if (!((vm >> q) & 1u)) continue;
+        if (kk[q] > T_key) {
+            const uint32_t pos = gt_before + (eq_before < take_eq ? eq_before : take_eq);
+            if (pos < (uint32_t)m) s.sel[pos] = tk[q];
+            gt_before++;
+        } else if (kk[q] == T_key) {
+            if (eq_before < take_eq) {
+                const uint32_t pos = gt_before + eq_before;
+                if (pos < (uint32_t)m) s.sel[pos] = tk[q];
+            }
+            eq_before++;
+        }
+    }
+    __syncthreads();
+    return true;
+}
+
+template <typename T>
+__global__ __launch_bounds__(TOPM_WAVES *WAVE) void topm_kernel(IndexView ix, const int32_t *__restrict__ prefixes,
+                                                                int32_t stride, const int32_t *__restrict__ lens,
+                                                                const T *__restrict__ logits, int64_t row_stride, int M,
+                                                                int force_streaming, int32_t *__restrict__ top_ids,
+                                                                uint8_t *__restrict__ mask_V,
+                                                                uint32_t *__restrict__ mask) {
+    constexpr int EPL = KeyChunk<T>::EPL;
+    extern __shared__ __align__(16) uint32_t smem[];  // max(TOPM_BINS, n_words) words
+    uint32_t *img = smem;                             // [n_words] the row of the mask, once the histogram is done with
+    __shared__ uint32_t list_tok[TOPM_LIST];
+    __shared__ uint32_t sel[PPV_TOPM_MAX];
+    __shared__ uint32_t seg_a[TOPM_WAVES], seg_b[TOPM_WAVES], wave_tot[TOPM_WAVES];
+    __shared__ uint32_t bc[8];
+    const TopmLds lds = {smem, list_tok, sel, seg_a, seg_b, wave_tot, bc};
+    const int b = blockIdx.x, tid = threadIdx.x, lane = tid & (WAVE - 1);
+    const int wave = __builtin_amdgcn_readfirstlane(tid / WAVE);
+    const int nthreads = blockDim.x, nw = nthreads / WAVE;
+    const int V = ix.vocab, n_words = ix.n_words;
+    const int m = M < V ? M : V;                      // candidates of this row
+    const T *row = logits + (size_t)b * (size_t)row_stride;
+
+    // this wavefront's contiguous share of the row, in chunks of one 16-byte load per lane
+    const int nc = (V + WAVE * EPL - 1) / (WAVE * EPL);
+    const int cpw = (nc + nw - 1) / nw;
+    const int c0 = wave * cpw, c1 = (c0 + cpw < nc) ? c0 + cpw : nc;
+
+    const bool listed = !force_streaming && nthreads * TOPM_SLOTS >= TOPM_LIST;
+    uint4 r[4];
+    if (listed) load_chunks<T>(row, V, c0, c1, lane, r);   // in flight while the prefix is located
+    if (wave == 0) {   // the part every candidate row shares: locate the prefix once
+        int t = lens[b];
+        t = t < 0 ? 0 : (t > stride ? stride : t);
+        const Walk w = walk_prefix(ix, prefixes + (size_t)b * (size_t)stride, t, lane);
+        if (lane == 0) {
+            bc[0] = w.node;
+            bc[1] = w.found ? 1u : 0u;
+            bc[2] = w.found ? w.cb : 0u;
+            bc[3] = w.found ? w.ce : 0u;
+        }
+    }
+    // ---- select
+    bool done = false;
+    if (listed) done = select_listed<T>(row, V, c0, c1, m, lds, lane, wave, nthreads, r);
+    if (!done) select_streaming<T>(row, V, c0, c1, m, lds, lane, wave, nthreads);
+    for (int i = tid; i < n_words; i += nthreads) img[i] = 0u;   // the histogram's LDS becomes the mask row
     __syncthreads();
 
     // ---- verify: one candidate per thread
@@ -236,7 +501,7 @@ __global__ __launch_bounds__(TOPM_WAVES *WAVE) void topm_kernel(IndexView ix, co
     for (int i = tid; i < M; i += nthreads) {
         int32_t t = -1;
         uint32_t ok = 0;
-        if (i < m) {
+        if (i < m && sel[i] < (uint32_t)V) {
             t = (int32_t)sel[i];
             if (slot != PPV_NO_SLOT) {
                 ok = (image[t >> 5] >> (t & 31)) & 1u;
@@ -269,7 +534,11 @@ __global__ __launch_bounds__(TOPM_WAVES *WAVE) void topm_kernel(IndexView ix, co
 int topm_waves(int V, ppv_dtype dt, int B) {
     const int per = (dt == PPV_F32 ? 4 : 8) * WAVE;
     const int nc = (V + per - 1) / per;
-    const int cap = B <= 512 ? TOPM_WAVES : (B <= 1024 ? 8 : 4);
+    int cap = B <= 512 ? TOPM_WAVES : (B <= 1024 ? 8 : 4);
+    if (const char *e = getenv("PPV_TOPM_WAVES")) {  // tuning aid
+        const int v = atoi(e);
+        if (v >= 1 && v <= TOPM_WAVES) cap = v;
+    }
     int nw = 1;
     while (nw * 2 <= cap && nw * 2 <= nc) nw <<= 1;
     return nw;
@@ -290,14 +559,18 @@ extern "C" ppv_status ppv_topm_mask(const ppv_index_t *ix, const int32_t *prefix
     const int64_t per16 = (dt == PPV_F32) ? 4 : 8;
     if (row_stride < V || row_stride % per16 != 0 || ((uintptr_t)logits & 15u) != 0) return PPV_EINVAL;
     const int threads = topm_waves(V, dt, B) * WAVE;
-    const size_t lds = (size_t)ix->view.n_words * sizeof(uint32_t);
+    // testing aid: PPV_TOPM_STREAMING=1 sends every row through the whole-row radix select
+    const char *fs = getenv("PPV_TOPM_STREAMING");
+    const int force_streaming = (fs && fs[0] == '1') ? 1 : 0;
+    const size_t lds = (size_t)(ix->view.n_words > TOPM_BINS ? ix->view.n_words : TOPM_BINS) * sizeof(uint32_t);
     if (dt == PPV_F32)
         hipLaunchKernelGGL(topm_kernel<float>, dim3((unsigned)B), dim3(threads), lds, (hipStream_t)stream, ix->view,
-                           prefixes, prefix_stride, lens, (const float *)logits, row_stride, M, top_ids, mask_V, mask);
+                           prefixes, prefix_stride, lens, (const float *)logits, row_stride, M, force_streaming, top_ids, mask_V,
+                           mask);
     else
         hipLaunchKernelGGL(topm_kernel<uint16_t>, dim3((unsigned)B), dim3(threads), lds, (hipStream_t)stream, ix->view,
-                           prefixes, prefix_stride, lens, (const uint16_t *)logits, row_stride, M, top_ids, mask_V,
-                           mask);
+                           prefixes, prefix_stride, lens, (const uint16_t *)logits, row_stride, M, force_streaming, top_ids,
+                           mask_V, mask);
     PPV_HIP_TRY(hipGetLastError());
     return PPV_OK;
 }

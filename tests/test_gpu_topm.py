@@ -128,6 +128,21 @@ def test_topm_ties_special_values_and_ragged_rows(dtype):
         assert_topm_parity(index, X, P, L, lf, ld, M)
 
 
+def test_topm_whole_row_select_path(monkeypatch):
+    """The selection has two routes (bound + short list; radix select over the whole row when the list would not
+    fit).  PPV_TOPM_STREAMING=1 sends every row down the second one: same results."""
+    monkeypatch.setenv("PPV_TOPM_STREAMING", "1")
+    for name in ("C2", "C3s", "C5s"):
+        cfg, S, trie, index = setup_case(name)
+        X = sorted_array(name)
+        pb = W.make_prefix_batch(cfg, S)
+        logits = W.make_logits(cfg)
+        lf = W.logits_as_f32(cfg, logits)
+        ld = logits_to_dev(cfg, logits)
+        for M in (1, 50, 1000):
+            assert_topm_parity(index, X, pb.prefixes, pb.lens, lf, ld, M)
+
+
 def test_topm_then_sample_is_the_step_of_algorithm_1():
     """mask from ppv_topm_mask -> constrained_sample, against the oracle's top-M mask -> masked sample."""
     name = "C3s"
