@@ -184,6 +184,14 @@ def main() -> int:
     torch.cuda.synchronize()
     t_build = time.perf_counter() - t0
     L = index.l_max
+    import tempfile
+    with tempfile.TemporaryDirectory() as td:                  # persistence: written once, loaded instead of rebuilt
+        t0 = time.perf_counter()
+        ppv.ppv_index_save(index, os.path.join(td, "index.ppv"))
+        t_save = time.perf_counter() - t0
+        t0 = time.perf_counter()
+        ppv.ppv_index_load(os.path.join(td, "index.ppv")).free()
+        t_load = time.perf_counter() - t0
 
     # every decode step's logits and uniforms, resident in HBM before anything is timed
     logits = torch.empty((L, B, V), dtype=torch.bfloat16, device=dev)
@@ -237,6 +245,7 @@ def main() -> int:
                               ", no host sync inside a loop")},
         "roofline": roofline,
         "index_build_s": round(t_build, 3), "index_device_MB": round(index.device_bytes / 1e6, 1),
+        "index_save_s": round(t_save, 3), "index_load_s": round(t_load, 3),
     }
 
     # The same loop, same rows, as one launch (ppv_decode_loop): every workgroup stays with its row, so there

@@ -40,7 +40,8 @@ typedef enum {
     PPV_EINVAL = -1,  /* bad argument: null pointer, bad size, empty S, empty sequence, token out of range */
     PPV_ENOMEM = -2,  /* host or device allocation failed */
     PPV_EDEVICE = -3, /* a HIP call failed (no device, launch error) */
-    PPV_ERANGE = -4   /* a size exceeds what the library supports (see PPV_MAX_VOCAB) */
+    PPV_ERANGE = -4,  /* a size exceeds what the library supports (see PPV_MAX_VOCAB) */
+    PPV_EIO = -5      /* a file could not be opened, read or written */
 } ppv_status;
 
 typedef enum { PPV_F32 = 0, PPV_BF16 = 1 } ppv_dtype;
@@ -82,6 +83,24 @@ ppv_status ppv_index_info(const ppv_index_t *index, int64_t *n_distinct, int32_t
 ppv_status ppv_index_export(const ppv_index_t *index, int32_t *tokens_out, int64_t *offsets_out, int64_t *n_tokens);
 
 void ppv_free_index(ppv_index_t *index); /* NULL is allowed */
+
+/*
+ * ppv_index_save / ppv_index_load -- Section 3.2 "Array Preparation": the array is prepared once and
+ * kept (the paper splits it by length only to save disk space; the flat layout here has no padding to
+ * save); Section 3.2 "Advantages over prefix trees" counts loading a prepared array, instead of
+ * building a tree, among the gains.  The file holds the per-depth entries, the rank ranges and the flat
+ * sorted S behind a 128-byte header with a checksum; the heavy prefixes' images are rebuilt at load.
+ * Little-endian; a file is only good for the library version that wrote it (the header says which).
+ *   path   host, NUL-terminated
+ *   out    host; *out receives a new index on the current device, *out = NULL on failure
+ * ppv_index_load trusts nothing in the file: sizes are checked against the file's length, the checksum
+ * against its contents, and a device pass checks that every offset, rank and token stays inside its
+ * array, so that an index that loads cannot send a kernel out of bounds.
+ * Errors: PPV_EINVAL (null argument; not an index file; sizes, checksum or structure wrong),
+ * PPV_EIO (open / read / write failed), PPV_ERANGE, PPV_ENOMEM, PPV_EDEVICE.
+ */
+ppv_status ppv_index_save(const ppv_index_t *index, const char *path);
+ppv_status ppv_index_load(const char *path, ppv_index_t **out);
 
 /*
  * ppv_next_token_mask -- Algorithm 2 with M = |V| (verification of every token at once);

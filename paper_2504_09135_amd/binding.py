@@ -24,6 +24,7 @@ PPV_TOPM_MAX = 1024
 PPV_STATE_WORDS = 4
 
 SYMBOLS = ("ppv_status_string", "ppv_build_index", "ppv_index_info", "ppv_index_export", "ppv_free_index",
+           "ppv_index_save", "ppv_index_load",
            "ppv_next_token_mask", "constrained_sample", "ppv_decode_begin", "ppv_decode_step", "ppv_decode_loop", "ppv_topm_mask",
            "ppv_disc_select")
 
@@ -54,6 +55,10 @@ def load_library() -> C.CDLL:
     lib.ppv_index_info.argtypes = [p, C.POINTER(i64), C.POINTER(i32), C.POINTER(i32), C.POINTER(i64), C.POINTER(i64)]
     lib.ppv_index_export.restype = C.c_int
     lib.ppv_index_export.argtypes = [p, p, p, C.POINTER(i64)]
+    lib.ppv_index_save.restype = C.c_int
+    lib.ppv_index_save.argtypes = [p, C.c_char_p]
+    lib.ppv_index_load.restype = C.c_int
+    lib.ppv_index_load.argtypes = [C.c_char_p, C.POINTER(p)]
     lib.ppv_free_index.restype = None
     lib.ppv_free_index.argtypes = [p]
     lib.ppv_next_token_mask.restype = C.c_int
@@ -131,6 +136,18 @@ def ppv_build_index(tokens: np.ndarray, offsets: np.ndarray, vocab: int) -> PPVI
     st = lib.ppv_build_index(tokens.ctypes.data_as(C.c_void_p), offsets.ctypes.data_as(C.c_void_p),
                              int(offsets.shape[0]) - 1, int(vocab), C.byref(out))
     _check(st, "ppv_build_index")
+    return PPVIndex(out.value)
+
+
+def ppv_index_save(index: PPVIndex, path: str) -> None:
+    """Write the index to a file (ppv_index_load reads it back)."""
+    _check(load_library().ppv_index_save(index.handle, os.fsencode(path)), "ppv_index_save")
+
+
+def ppv_index_load(path: str) -> PPVIndex:
+    """Read an index written by ppv_index_save onto the current device."""
+    out = C.c_void_p()
+    _check(load_library().ppv_index_load(os.fsencode(path), C.byref(out)), "ppv_index_load")
     return PPVIndex(out.value)
 
 

@@ -16,6 +16,8 @@
 //      its last child ends, or one row after it opens if it has no child);
 //   6. images and per-word child counts of the heavy prefixes.
 #include <algorithm>
+#include <cstdio>
+#include <cstring>
 #include <new>
 
 #include "ppv_device.h"
@@ -28,6 +30,7 @@ extern "C" const char *ppv_status_string(ppv_status s) {
         case PPV_ENOMEM: return "PPV_ENOMEM: out of memory";
         case PPV_EDEVICE: return "PPV_EDEVICE: HIP call failed";
         case PPV_ERANGE: return "PPV_ERANGE: size beyond what the library supports";
+        case PPV_EIO: return "PPV_EIO: file could not be opened, read or written";
     }
     return "unknown ppv_status";
 }
@@ -411,6 +414,56 @@ template <typename T> ppv_status keep_alloc(T **out, size_t count, int64_t *byte
 
 inline unsigned blocks_for(uint64_t n) { return (unsigned)((n + BT - 1) / BT); }
 
+// 6. Images and per-word child counts of the heavy prefixes, from the finished entries (G of them plus the
+// sentinel).  Sets the heavy part of the index and of its view.
+ppv_status finish_heavy(ppv_index *ix, uint32_t G, int32_t vocab, hipStream_t st) {
+    DeviceBuffers tmp;
+    const int n_words = (vocab + 31) / 32;
+    const uint32_t heavy_min = (uint32_t)std::min<int64_t>(vocab / 32, PPV_LIST_MAX);
+    uint32_t *slot_of, *sums, *d_total;
+    TRY(tmp.alloc(&slot_of, G));
+    TRY(tmp.alloc(&sums, (size_t)(((uint64_t)G + SCAN_CHUNK - 1) / SCAN_CHUNK)));
+    TRY(tmp.alloc(&d_total, 1));
+    TRY(exclusive_scan(G, IsHeavy{ix->d_ent, heavy_min}, slot_of, sums, d_total, st));
+    uint32_t n_heavy;
+    PPV_HIP_TRY(hipMemcpyAsync(&n_heavy, d_total, sizeof(uint32_t), hipMemcpyDeviceToHost, st));
+    PPV_HIP_TRY(hipStreamSynchronize(st));
+    // Breadth-first order puts the heavy prefixes (shallow ones) at small entry numbers, so the slot
+    // table only has to reach past the last of them: the first entry that has all n_heavy before it.
+    uint32_t heavy_limit = 0;
+    if (n_heavy > 0) {
+        uint32_t lo = 0, hi = G;
+        while (lo < hi) {
+            const uint32_t mid = lo + (hi - lo) / 2;
+            uint32_t v;
+            PPV_HIP_TRY(hipMemcpy(&v, slot_of + mid, sizeof(uint32_t), hipMemcpyDeviceToHost));
+            if (v >= n_heavy) hi = mid; else lo = mid + 1;
+        }
+        heavy_limit = lo;
+    }
+    uint32_t *heavy_node;
+    TRY(tmp.alloc(&heavy_node, n_heavy));
+    TRY(keep_alloc(&ix->d_heavy_slot, heavy_limit, &ix->device_bytes));
+    TRY(keep_alloc(&ix->d_heavy_bits, (size_t)n_heavy * n_words, &ix->device_bytes));
+    TRY(keep_alloc(&ix->d_heavy_rank, (size_t)n_heavy * n_words, &ix->device_bytes));
+    PPV_HIP_TRY(hipMemsetAsync(ix->d_heavy_bits, 0, std::max<size_t>((size_t)n_heavy * n_words, 1) * sizeof(uint32_t), st));
+    hipLaunchKernelGGL(mark_heavy, dim3(blocks_for(G)), dim3(BT), 0, st, ix->d_ent, G, heavy_min,
+                       (const uint32_t *)slot_of, heavy_limit, ix->d_heavy_slot, heavy_node);
+    if (n_heavy > 0)
+        hipLaunchKernelGGL(fill_heavy, dim3(n_heavy), dim3(BT), 0, st, (const NodeEnt *)ix->d_ent,
+                           (const uint32_t *)heavy_node, n_words, ix->d_heavy_bits, ix->d_heavy_rank);
+    PPV_HIP_TRY(hipGetLastError());
+    PPV_HIP_TRY(hipStreamSynchronize(st));
+    ix->n_heavy = n_heavy;
+    ix->view.heavy_slot = ix->d_heavy_slot;
+    ix->view.heavy_bits = ix->d_heavy_bits;
+    ix->view.heavy_rank = ix->d_heavy_rank;
+    ix->view.heavy_limit = heavy_limit;
+    ix->view.heavy_min = heavy_min;
+    ix->view.n_words = n_words;
+    return PPV_OK;
+}
+
 ppv_status build_on_device(const int32_t *tokens, const int64_t *offsets, int64_t n_seq, int32_t vocab, ppv_index *ix) {
     if (offsets[0] != 0) return PPV_EINVAL;
     const int64_t total = offsets[n_seq];
@@ -542,55 +595,15 @@ ppv_status build_on_device(const int32_t *tokens, const int64_t *offsets, int64_
     PPV_HIP_TRY(hipGetLastError());
 
     // ---- 6. heavy prefixes
-    const int n_words = (vocab + 31) / 32;
-    const uint32_t heavy_min = (uint32_t)std::min<int64_t>(vocab / 32, PPV_LIST_MAX);
-    uint32_t *slot_of;
-    TRY(tmp.alloc(&slot_of, G));
-    TRY(exclusive_scan(G, IsHeavy{ix->d_ent, heavy_min}, slot_of, sums, d_total + 3, st));
-    uint32_t n_heavy;
-    PPV_HIP_TRY(hipMemcpyAsync(&n_heavy, d_total + 3, sizeof(uint32_t), hipMemcpyDeviceToHost, st));
-    PPV_HIP_TRY(hipStreamSynchronize(st));
-    // Breadth-first order puts the heavy prefixes (shallow ones) at small entry numbers, so the slot
-    // table only has to reach past the last of them: the first entry that has all n_heavy before it.
-    uint32_t heavy_limit = 0;
-    if (n_heavy > 0) {
-        uint32_t lo = 0, hi = G;
-        while (lo < hi) {
-            const uint32_t mid = lo + (hi - lo) / 2;
-            uint32_t v;
-            PPV_HIP_TRY(hipMemcpy(&v, slot_of + mid, sizeof(uint32_t), hipMemcpyDeviceToHost));
-            if (v >= n_heavy) hi = mid; else lo = mid + 1;
-        }
-        heavy_limit = lo;
-    }
-    uint32_t *heavy_node;
-    TRY(tmp.alloc(&heavy_node, n_heavy));
-    TRY(keep_alloc(&ix->d_heavy_slot, heavy_limit, &ix->device_bytes));
-    TRY(keep_alloc(&ix->d_heavy_bits, (size_t)n_heavy * n_words, &ix->device_bytes));
-    TRY(keep_alloc(&ix->d_heavy_rank, (size_t)n_heavy * n_words, &ix->device_bytes));
-    PPV_HIP_TRY(hipMemsetAsync(ix->d_heavy_bits, 0, std::max<size_t>((size_t)n_heavy * n_words, 1) * sizeof(uint32_t), st));
-    hipLaunchKernelGGL(mark_heavy, dim3(blocks_for(G)), dim3(BT), 0, st, ix->d_ent, G, heavy_min,
-                       (const uint32_t *)slot_of, heavy_limit, ix->d_heavy_slot, heavy_node);
-    if (n_heavy > 0)
-        hipLaunchKernelGGL(fill_heavy, dim3(n_heavy), dim3(BT), 0, st, (const NodeEnt *)ix->d_ent,
-                           (const uint32_t *)heavy_node, n_words, ix->d_heavy_bits, ix->d_heavy_rank);
-    PPV_HIP_TRY(hipGetLastError());
-    PPV_HIP_TRY(hipStreamSynchronize(st));
+    TRY(finish_heavy(ix, G, vocab, st));
 
     ix->n_tokens = n_tok;
-    ix->n_heavy = n_heavy;
     ix->view.ent = ix->d_ent;
     ix->view.node_lo = ix->d_node_lo;
     ix->view.node_hi = ix->d_node_hi;
-    ix->view.heavy_slot = ix->d_heavy_slot;
-    ix->view.heavy_bits = ix->d_heavy_bits;
-    ix->view.heavy_rank = ix->d_heavy_rank;
-    ix->view.heavy_limit = heavy_limit;
-    ix->view.heavy_min = heavy_min;
     ix->view.n_nodes = G;
     ix->view.n_rows = n_rows;
     ix->view.vocab = vocab;
-    ix->view.n_words = n_words;
     ix->view.l_max = l_max;
     return PPV_OK;
 }
@@ -606,6 +619,212 @@ void release(ppv_index *ix) {
     (void)hipFree(ix->d_x_tok);
     (void)hipFree(ix->d_x_off);
     delete ix;
+}
+
+// ------------------------------------------------------------------------------------------
+// Persistence.  The file holds what cannot be recomputed cheaply -- the entries (heavy flag cleared), the rank
+// ranges and the flat sorted S -- behind a fixed header; the heavy prefixes' images are rebuilt at load.
+// Little-endian, as the machine is.
+struct FileHeader {
+    char magic[8];
+    uint32_t version, header_bytes;
+    int32_t vocab, l_max;
+    uint64_t n_rows, n_nodes, n_tokens;
+    uint64_t checksum;      // over the sections, in file order
+    uint64_t reserved[9];
+};
+static_assert(sizeof(FileHeader) == 128, "file header layout");
+const char FILE_MAGIC[8] = {'P', 'P', 'V', 'I', 'D', 'X', 0, 1};
+constexpr size_t IO_CHUNK = 32u << 20;   // bytes staged per copy
+
+// 64-bit multiply-xor checksum over 8-byte words (the tail is zero-padded); `h` carries across calls whose
+// lengths are multiples of 8 except the last of a section
+inline uint64_t checksum_words(uint64_t h, const unsigned char *p, size_t n) {
+    size_t i = 0;
+    for (; i + 8 <= n; i += 8) {
+        uint64_t w;
+        memcpy(&w, p + i, 8);
+        h = (h ^ w) * 0x100000001B3ull;
+        h ^= h >> 29;
+    }
+    if (i < n) {
+        uint64_t w = 0;
+        memcpy(&w, p + i, n - i);
+        h = (h ^ w) * 0x100000001B3ull;
+        h ^= h >> 29;
+    }
+    return h;
+}
+
+struct Section {
+    void *dev;
+    size_t bytes;
+    bool entries;   // NodeEnt array: the heavy flag is not stored
+};
+
+// structural checks of a loaded index: whatever the file held, the kernels must stay inside the arrays
+__global__ __launch_bounds__(BT) void check_loaded_nodes(const NodeEnt *__restrict__ ent,
+                                                         const uint32_t *__restrict__ node_lo,
+                                                         const uint32_t *__restrict__ node_hi, uint32_t n_nodes,
+                                                         uint32_t n_rows, uint32_t vocab, int32_t *__restrict__ err) {
+    const uint32_t g = blockIdx.x * BT + threadIdx.x;
+    if (g >= n_nodes) return;
+    const uint32_t c0 = ent[g].child, c1 = ent[g + 1].child;
+    bool bad = c0 > c1 || c1 > n_nodes || (c1 > c0 && c0 <= g);   // children lie after their parent
+    bad = bad || (ent[g].tok & PPV_NODE_HEAVY) != 0u || (g > 0 && (ent[g].tok & PPV_NODE_TOKEN) >= vocab);
+    bad = bad || !(node_lo[g] < node_hi[g] && node_hi[g] <= n_rows);
+    if (g == 0) bad = bad || c0 != 1u;
+    if (g == n_nodes - 1) bad = bad || c1 != n_nodes || (ent[n_nodes].tok & PPV_NODE_HEAVY) != 0u;
+    if (!bad)
+        for (uint32_t c = c0; c + 1 < c1; c++)   // siblings in strictly increasing token order
+            if ((ent[c].tok & PPV_NODE_TOKEN) >= (ent[c + 1].tok & PPV_NODE_TOKEN)) {
+                bad = true;
+                break;
+            }
+    if (bad) atomicOr(err, 1);
+}
+__global__ __launch_bounds__(BT) void check_loaded_rows(const int32_t *__restrict__ x_tok, const int64_t *__restrict__ x_off,
+                                                        uint64_t n_rows, uint64_t n_tokens, int32_t vocab, int32_t l_max,
+                                                        int32_t *__restrict__ err) {
+    const uint64_t i = (uint64_t)blockIdx.x * BT + threadIdx.x;
+    bool bad = false;
+    if (i < n_rows) {
+        const int64_t a = x_off[i], b = x_off[i + 1];
+        bad = a < 0 || b <= a || b - a > l_max || (uint64_t)b > n_tokens || (i == 0 && a != 0) ||
+              (i == n_rows - 1 && (uint64_t)b != n_tokens);
+    }
+    if (i < n_tokens) bad = bad || x_tok[i] < 0 || x_tok[i] >= vocab;
+    if (bad) atomicOr(err, 2);
+}
+
+ppv_status save_to_file(const ppv_index *ix, const char *path) {
+    PPV_HIP_TRY(hipSetDevice(ix->device));
+    FILE *f = fopen(path, "wb");
+    if (!f) return PPV_EIO;
+    unsigned char *stage = new (std::nothrow) unsigned char[IO_CHUNK];
+    if (!stage) {
+        fclose(f);
+        return PPV_ENOMEM;
+    }
+    FileHeader h;
+    memset(&h, 0, sizeof(h));
+    memcpy(h.magic, FILE_MAGIC, 8);
+    h.version = 1;
+    h.header_bytes = sizeof(FileHeader);
+    h.vocab = ix->view.vocab;
+    h.l_max = ix->view.l_max;
+    h.n_rows = ix->view.n_rows;
+    h.n_nodes = ix->view.n_nodes;
+    h.n_tokens = (uint64_t)ix->n_tokens;
+    const Section sec[5] = {{ix->d_ent, ((size_t)h.n_nodes + 1) * sizeof(NodeEnt), true},
+                            {ix->d_node_lo, (size_t)h.n_nodes * sizeof(uint32_t), false},
+                            {ix->d_node_hi, (size_t)h.n_nodes * sizeof(uint32_t), false},
+                            {ix->d_x_off, ((size_t)h.n_rows + 1) * sizeof(int64_t), false},
+                            {ix->d_x_tok, (size_t)h.n_tokens * sizeof(int32_t), false}};
+    ppv_status st = PPV_OK;
+    if (fwrite(&h, sizeof(h), 1, f) != 1) st = PPV_EIO;
+    uint64_t sum = 0xCBF29CE484222325ull;
+    for (int k = 0; k < 5 && st == PPV_OK; k++)
+        for (size_t at = 0; at < sec[k].bytes && st == PPV_OK; at += IO_CHUNK) {
+            const size_t n = std::min(IO_CHUNK, sec[k].bytes - at);
+            if (hipMemcpy(stage, (const unsigned char *)sec[k].dev + at, n, hipMemcpyDeviceToHost) != hipSuccess) {
+                (void)hipGetLastError();
+                st = PPV_EDEVICE;
+                break;
+            }
+            if (sec[k].entries)
+                for (size_t e = 0; e < n / sizeof(NodeEnt); e++) {
+                    NodeEnt ne;
+                    memcpy(&ne, stage + e * sizeof(NodeEnt), sizeof(NodeEnt));
+                    ne.tok &= ~PPV_NODE_HEAVY;
+                    memcpy(stage + e * sizeof(NodeEnt), &ne, sizeof(NodeEnt));
+                }
+            sum = checksum_words(sum, stage, n);
+            if (fwrite(stage, 1, n, f) != n) st = PPV_EIO;
+        }
+    delete[] stage;
+    if (st == PPV_OK) {
+        h.checksum = sum;
+        if (fseek(f, 0, SEEK_SET) != 0 || fwrite(&h, sizeof(h), 1, f) != 1) st = PPV_EIO;
+    }
+    if (fclose(f) != 0 && st == PPV_OK) st = PPV_EIO;
+    return st;
+}
+
+ppv_status load_from_file(FILE *f, ppv_index *ix) {
+    FileHeader h;
+    if (fread(&h, sizeof(h), 1, f) != 1) return PPV_EINVAL;   // shorter than a header: not an index file
+    if (memcmp(h.magic, FILE_MAGIC, 8) != 0 || h.version != 1 || h.header_bytes != sizeof(FileHeader)) return PPV_EINVAL;
+    if (h.vocab <= 0 || h.l_max <= 0 || h.n_rows == 0 || h.n_nodes < 2 || h.n_tokens < h.n_rows) return PPV_EINVAL;
+    if (h.vocab > PPV_MAX_VOCAB || h.n_rows > 0xFFFFFFF0ull || h.n_nodes > 0xFFFFFFF0ull || h.n_tokens > 0xFFFFFFF0ull)
+        return PPV_ERANGE;
+    const size_t bytes[5] = {((size_t)h.n_nodes + 1) * sizeof(NodeEnt), (size_t)h.n_nodes * sizeof(uint32_t),
+                             (size_t)h.n_nodes * sizeof(uint32_t), ((size_t)h.n_rows + 1) * sizeof(int64_t),
+                             (size_t)h.n_tokens * sizeof(int32_t)};
+    if (fseek(f, 0, SEEK_END) != 0) return PPV_EIO;
+    const long end = ftell(f);
+    if (end < 0 || (uint64_t)end != sizeof(h) + bytes[0] + bytes[1] + bytes[2] + bytes[3] + bytes[4]) return PPV_EINVAL;
+    if (fseek(f, (long)sizeof(h), SEEK_SET) != 0) return PPV_EIO;
+
+    if (hipGetDevice(&ix->device) != hipSuccess) {
+        (void)hipGetLastError();
+        return PPV_EDEVICE;
+    }
+    ix->device_bytes = 0;
+    TRY(keep_alloc(&ix->d_ent, (size_t)h.n_nodes + 1, &ix->device_bytes));
+    TRY(keep_alloc(&ix->d_node_lo, (size_t)h.n_nodes, &ix->device_bytes));
+    TRY(keep_alloc(&ix->d_node_hi, (size_t)h.n_nodes, &ix->device_bytes));
+    TRY(keep_alloc(&ix->d_x_off, (size_t)h.n_rows + 1, &ix->device_bytes));
+    TRY(keep_alloc(&ix->d_x_tok, (size_t)h.n_tokens, &ix->device_bytes));
+    void *dev[5] = {ix->d_ent, ix->d_node_lo, ix->d_node_hi, ix->d_x_off, ix->d_x_tok};
+    unsigned char *stage = new (std::nothrow) unsigned char[IO_CHUNK];
+    if (!stage) return PPV_ENOMEM;
+    ppv_status st = PPV_OK;
+    uint64_t sum = 0xCBF29CE484222325ull;
+    for (int k = 0; k < 5 && st == PPV_OK; k++)
+        for (size_t at = 0; at < bytes[k] && st == PPV_OK; at += IO_CHUNK) {
+            const size_t n = std::min(IO_CHUNK, bytes[k] - at);
+            if (fread(stage, 1, n, f) != n) {
+                st = PPV_EIO;
+                break;
+            }
+            sum = checksum_words(sum, stage, n);
+            if (hipMemcpy((unsigned char *)dev[k] + at, stage, n, hipMemcpyHostToDevice) != hipSuccess) {
+                (void)hipGetLastError();
+                st = PPV_EDEVICE;
+            }
+        }
+    delete[] stage;
+    if (st != PPV_OK) return st;
+    if (sum != h.checksum) return PPV_EINVAL;
+
+    // the checksum guards against damage; these checks guard the kernels against a file that was wrong when written
+    hipStream_t s0 = nullptr;
+    DeviceBuffers tmp;
+    int32_t *d_err;
+    TRY(tmp.alloc(&d_err, 1));
+    PPV_HIP_TRY(hipMemsetAsync(d_err, 0, sizeof(int32_t), s0));
+    hipLaunchKernelGGL(check_loaded_nodes, dim3(blocks_for(h.n_nodes)), dim3(BT), 0, s0, (const NodeEnt *)ix->d_ent,
+                       (const uint32_t *)ix->d_node_lo, (const uint32_t *)ix->d_node_hi, (uint32_t)h.n_nodes,
+                       (uint32_t)h.n_rows, (uint32_t)h.vocab, d_err);
+    hipLaunchKernelGGL(check_loaded_rows, dim3(blocks_for(std::max(h.n_rows, h.n_tokens))), dim3(BT), 0, s0,
+                       (const int32_t *)ix->d_x_tok, (const int64_t *)ix->d_x_off, h.n_rows, h.n_tokens, h.vocab, h.l_max,
+                       d_err);
+    PPV_HIP_TRY(hipGetLastError());
+    int32_t err = 0;
+    PPV_HIP_TRY(hipMemcpy(&err, d_err, sizeof(int32_t), hipMemcpyDeviceToHost));
+    if (err != 0) return PPV_EINVAL;
+
+    TRY(finish_heavy(ix, (uint32_t)h.n_nodes, h.vocab, s0));
+    ix->n_tokens = (int64_t)h.n_tokens;
+    ix->view.ent = ix->d_ent;
+    ix->view.node_lo = ix->d_node_lo;
+    ix->view.node_hi = ix->d_node_hi;
+    ix->view.n_nodes = (uint32_t)h.n_nodes;
+    ix->view.n_rows = (uint32_t)h.n_rows;
+    ix->view.vocab = h.vocab;
+    ix->view.l_max = h.l_max;
+    return PPV_OK;
 }
 
 }  // namespace
@@ -658,3 +877,36 @@ extern "C" ppv_status ppv_index_export(const ppv_index_t *ix, int32_t *tokens_ou
 }
 
 extern "C" void ppv_free_index(ppv_index_t *ix) { release(ix); }
+
+extern "C" ppv_status ppv_index_save(const ppv_index_t *ix, const char *path) {
+    if (!ix || !path || !path[0]) return PPV_EINVAL;
+    return save_to_file(ix, path);
+}
+
+extern "C" ppv_status ppv_index_load(const char *path, ppv_index_t **out) {
+    if (!out) return PPV_EINVAL;
+    *out = nullptr;
+    if (!path || !path[0]) return PPV_EINVAL;
+    FILE *f = fopen(path, "rb");
+    if (!f) return PPV_EIO;
+    ppv_index *ix = new (std::nothrow) ppv_index();
+    if (!ix) {
+        fclose(f);
+        return PPV_ENOMEM;
+    }
+    ix->device = -1;
+    const ppv_status st = load_from_file(f, ix);
+    fclose(f);
+    if (st != PPV_OK) {
+        if (ix->device >= 0) {   // the device was touched: let its work drain before the buffers go
+            (void)hipDeviceSynchronize();
+            (void)hipGetLastError();
+            release(ix);
+        } else {
+            delete ix;
+        }
+        return st;
+    }
+    *out = ix;
+    return PPV_OK;
+}

@@ -34,7 +34,7 @@ def test_header_and_binding_agree(lib):
 
 
 def test_status_strings(lib):
-    for s in (0, -1, -2, -3, -4, 77):
+    for s in (0, -1, -2, -3, -4, -5, 77):
         assert isinstance(lib.ppv_status_string(s), bytes)
 
 
@@ -63,9 +63,46 @@ def test_argument_errors_without_device(lib):
     assert lib.ppv_decode_begin(None, None, 0, None, 0, None, None, None, None) == EINVAL
     assert lib.ppv_disc_select(None, 2, 1, 5, None, None, 0, None, None, None, None) == EINVAL
     assert lib.ppv_disc_select(None, 1, 1, 5, None, None, 0, None, None, None, None) == EINVAL
+    EIO = -5
+    assert lib.ppv_index_save(None, b"/tmp/x") == EINVAL
+    assert lib.ppv_index_load(None, C.byref(out)) == EINVAL
+    assert lib.ppv_index_load(b"/nonexistent/dir/index.ppv", C.byref(out)) == EIO
+    assert lib.ppv_index_load(b"/nonexistent/dir/index.ppv", None) == EINVAL
     fake = C.c_void_p(16)   # never dereferenced: the checks below come first
     assert lib.ppv_topm_mask(None, None, 0, None, None, 0, 8, 5, 1, None, None, None, None) == EINVAL
     assert lib.ppv_topm_mask(fake, None, 0, None, None, 0, 8, 0, 0, None, None, None, None) == EINVAL
     assert lib.ppv_topm_mask(fake, None, 0, None, None, 0, 8, 1025, 0, None, None, None, None) == ERANGE
     assert lib.ppv_topm_mask(fake, None, 0, None, None, 0, 8, 5, 0, None, None, None, None) == 0
     assert lib.ppv_decode_loop(None, None, 0, None, None, None, None, 0, 0, 0, None, 1, 1, None, None, None, None) == EINVAL
+
+
+def test_index_load_rejects_files_that_are_not_an_index(lib, tmp_path):
+    """Everything that can be told from the header and the file's length is refused before any device call."""
+    out = C.c_void_p()
+    EINVAL, ERANGE = -1, -4
+    junk = tmp_path / "junk.ppv"
+    junk.write_bytes(b"not an index")
+    assert lib.ppv_index_load(str(junk).encode(), C.byref(out)) == EINVAL and out.value is None
+    junk.write_bytes(bytes(4096))
+    assert lib.ppv_index_load(str(junk).encode(), C.byref(out)) == EINVAL
+
+    def header(vocab=8, l_max=2, n_rows=2, n_nodes=4, n_tokens=3, version=1):
+        h = bytearray(128)
+        h[0:8] = b"PPVIDX\x00\x01"
+        h[8:12] = np.uint32(version).tobytes()
+        h[12:16] = np.uint32(128).tobytes()
+        h[16:20] = np.int32(vocab).tobytes()
+        h[20:24] = np.int32(l_max).tobytes()
+        h[24:32] = np.uint64(n_rows).tobytes()
+        h[32:40] = np.uint64(n_nodes).tobytes()
+        h[40:48] = np.uint64(n_tokens).tobytes()
+        return bytes(h)
+    junk.write_bytes(header(version=2) + bytes(200))
+    assert lib.ppv_index_load(str(junk).encode(), C.byref(out)) == EINVAL
+    junk.write_bytes(header(vocab=0) + bytes(200))
+    assert lib.ppv_index_load(str(junk).encode(), C.byref(out)) == EINVAL
+    junk.write_bytes(header(vocab=1 << 20) + bytes(200))
+    assert lib.ppv_index_load(str(junk).encode(), C.byref(out)) == ERANGE
+    junk.write_bytes(header() + bytes(7))                     # sections shorter than the header promises
+    assert lib.ppv_index_load(str(junk).encode(), C.byref(out)) == EINVAL
+    assert out.value is None
