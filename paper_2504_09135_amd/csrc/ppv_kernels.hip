@@ -890,18 +890,19 @@ ppv_status check_logits_args(const void *logits, ppv_dtype dt, int64_t row_strid
     return PPV_OK;
 }
 
-// Wavefronts per row: a power of two, at most one per tile and at most MAX_WAVES.  The aim is about
-// 8192 wavefronts per launch (32 per compute unit): a small batch is bound by latency and wants
-// every row spread over many wavefronts so that the whole row is in flight at once; a large batch
-// is bound by throughput and wants several rows per compute unit, so that one row's reduction and
-// sampling phase overlaps another row's loads.  Measured on the N=1M, V=32k decode loop at
-// B=4096: 2.1 TB/s with 16 wavefronts per row, 4.3 TB/s with 4; at V=256k, B=256: 1.3 TB/s with
-// 2, 3.8 TB/s with 16.
+// Wavefronts per row: a power of two, at most one per tile and at most MAX_WAVES.  A small batch is
+// bound by latency and wants every row spread over many wavefronts so that the whole row is in
+// flight at once; a large batch is bound by throughput and wants several rows per compute unit, so
+// that one row's reduction and sampling phase overlaps another row's loads.  The steps below are
+// measured, on the N=1M, V=32k decode loop (TB/s of logits over the whole loop): B=256: 1.05 with
+// 16 wavefronts per row, 1.08 with 8, 0.93 with 4; B=512: 1.31 / 1.64 / 1.57; B=1024: 2.28 with 8,
+// 2.50 with 4, 2.37 with 2; B=4096: 2.1 with 16, 3.4 with 8, 4.3 with 4, 4.1 with 2; and at
+// V=256k: B=256: 3.8 with 16, 1.3 with 2; B=1024: 5.05 with 4, 5.09 with 8, 4.4 with 16.
 int waves_for(int V, ppv_dtype dt, int B) {
     const int tile = (dt == PPV_F32) ? TileGeom<float>::TILE : TileGeom<uint16_t>::TILE;
     const int nt = (V + tile - 1) / tile;
-    int cap = 4;
-    while (cap < MAX_WAVES && (int64_t)cap * B < 8192) cap <<= 1;
+    int cap = B <= 128 ? 16 : (B <= 512 ? 8 : 4);
+    if (nt >= 64 && B <= 256) cap = 16;   // long rows in a small batch: one row per compute unit, all of it in flight
     if (const char *e = getenv("PPV_WAVES_PER_ROW")) {  // tuning aid
         const int v = atoi(e);
         if (v >= 1 && v <= MAX_WAVES) cap = v;
