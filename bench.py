@@ -379,9 +379,29 @@ def single_call_bench(args, cfg, torch, ppv, W, dev):
 
     for k in range(args.warmup):
         step(k)
-    elapsed, _ = region(step, args.steps)
-    _, t_mask = region(lambda k: ppv.ppv_next_token_mask(index, P, Ln, mask, lo, hi, mem), args.steps)
-    _, t_samp = region(lambda k: ppv.constrained_sample(bufs[k % n_buf], mask, un, ids, lz), args.steps)
+    torch.cuda.synchronize()
+
+    def graph_region(fn, n):
+        """(wall seconds, GPU seconds) of n calls captured in one HIP graph and replayed once: the GPU's figure, not
+        the rate at which Python issues calls."""
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            fn(0)
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            for k in range(n):
+                fn(k)
+        graph.replay()
+        return region(lambda k: graph.replay(), 1)
+
+    timed = region if args.no_graph else graph_region
+    launch = "launched eagerly" if args.no_graph else f"{args.steps} steps captured in one HIP graph and replayed"
+    elapsed, _ = timed(step, args.steps)
+    _, t_mask = timed(lambda k: ppv.ppv_next_token_mask(index, P, Ln, mask, lo, hi, mem), args.steps)
+    _, t_samp = timed(lambda k: ppv.constrained_sample(bufs[k % n_buf], mask, un, ids, lz), args.steps)
     step(0)
     torch.cuda.synchronize()
     n_valid = int((ids >= 0).sum().item())
@@ -393,7 +413,7 @@ def single_call_bench(args, cfg, torch, ppv, W, dev):
         "ms_per_step": round(elapsed / args.steps * 1e3, 4), "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": f"{cfg.dtype} logits, f32/f64 accumulate, u32 index", "data": "synthetic",
         "config": {"workload": f"{cfg.name}: |S|={index.n_distinct} V={V} B={B} ({n_valid} rows with a valid token); "
-                               "one ppv_next_token_mask + one constrained_sample per step, launched eagerly"},
+                               "one ppv_next_token_mask + one constrained_sample per step, " + launch},
         "roofline": {"bound": "hbm", "kernel": f"sample_kernel<{cfg.dtype}>", "achieved": round(achieved, 1),
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
                      "avg_launch_us": round(t_samp / args.steps * 1e6, 2), "bytes_per_launch": int(bytes_sample)},
