@@ -20,8 +20,11 @@
 #include <cstring>
 #include <new>
 
+#include <cstdlib>
+
 #include "ppv_device.h"
 #include "ppv_internal.h"
+#include "ppv_walk.h"
 
 extern "C" const char *ppv_status_string(ppv_status s) {
     switch (s) {
@@ -464,6 +467,101 @@ ppv_status finish_heavy(ppv_index *ix, uint32_t G, int32_t vocab, hipStream_t st
     return PPV_OK;
 }
 
+// 7. Look-up table of whole prefixes: every node is entered under the hash of its token string (the first
+// tokens of the first member under it).  Also the per-depth node ranges the look-up checks a hit against.
+__global__ __launch_bounds__(BT) void insert_nodes(const uint32_t *__restrict__ node_lo, const int32_t *__restrict__ x_tok,
+                                                   const int64_t *__restrict__ x_off,
+                                                   const uint32_t *__restrict__ depth_base, int32_t l_max,
+                                                   uint32_t n_nodes, uint64_t *__restrict__ table, uint32_t size,
+                                                   uint32_t fp_mask, int32_t *__restrict__ err) {
+    const uint32_t g = 1u + blockIdx.x * BT + threadIdx.x;   // node 0 is the empty prefix: not looked up
+    if (g >= n_nodes) return;
+    int lo = 1, hi = l_max;                                   // depth d with depth_base[d] <= g < depth_base[d+1]
+    while (lo < hi) {
+        const int mid = (lo + hi + 1) / 2;
+        if (depth_base[mid] <= g) lo = mid; else hi = mid - 1;
+    }
+    const uint32_t r = node_lo[g];
+    const int64_t a = x_off[r];
+    if (x_off[r + 1] - a < lo) {   // (a loaded file) the first member under a node is at least as long as the node is deep
+        atomicOr(err, 4);
+        return;
+    }
+    uint64_t h = PREFIX_HASH_SEED;
+    for (int i = 0; i < lo; i++) h = prefix_hash_step(h, (uint32_t)x_tok[a + i]);
+    uint32_t slot, fp;
+    prefix_hash_finish(h, size, fp_mask, &slot, &fp);
+    const unsigned long long entry = ((unsigned long long)fp << 32) | g;
+    for (uint32_t n = 0; n < size; n++) {   // the table has twice as many slots as nodes
+        if (atomicCAS((unsigned long long *)&table[slot], 0ull, entry) == 0ull) return;
+        slot = slot + 1u == size ? 0u : slot + 1u;
+    }
+}
+
+ppv_status finish_lookup(ppv_index *ix, uint32_t G, int32_t l_max, hipStream_t st) {
+    // nodes of depth d start where the children of the first node of depth d-1 start
+    uint32_t *h_base = new (std::nothrow) uint32_t[(size_t)l_max + 2];
+    if (!h_base) return PPV_ENOMEM;
+    h_base[0] = 0u;
+    h_base[1] = 1u;
+    ppv_status rc = PPV_OK;
+    for (int d = 1; d < l_max && rc == PPV_OK; d++) {
+        if (h_base[d] >= G) {
+            h_base[d + 1] = G;
+            continue;
+        }
+        if (hipMemcpy(&h_base[d + 1], &ix->d_ent[h_base[d]].child, sizeof(uint32_t), hipMemcpyDeviceToHost) != hipSuccess) {
+            (void)hipGetLastError();
+            rc = PPV_EDEVICE;
+        } else if (h_base[d + 1] < h_base[d] || h_base[d + 1] > G) {
+            rc = PPV_EINVAL;
+        }
+    }
+    h_base[l_max + 1] = G;
+    if (rc == PPV_OK) rc = keep_alloc(&ix->d_depth_base, (size_t)l_max + 2, &ix->device_bytes);
+    if (rc == PPV_OK && hipMemcpy(ix->d_depth_base, h_base, ((size_t)l_max + 2) * sizeof(uint32_t), hipMemcpyHostToDevice) !=
+                            hipSuccess) {
+        (void)hipGetLastError();
+        rc = PPV_EDEVICE;
+    }
+    delete[] h_base;
+    if (rc != PPV_OK) return rc;
+    ix->view.depth_base = ix->d_depth_base;
+    ix->view.x_tok = ix->d_x_tok;
+    ix->view.x_off = ix->d_x_off;
+    ix->view.lookup = nullptr;
+    ix->view.lookup_size = 0;
+    ix->view.lookup_fp_mask = 0xFFFFFFFFu;
+    // PPV_LOOKUP=0: no table (every prefix is located by the descent; saves 16 bytes per prefix of device memory).
+    // PPV_LOOKUP_WEAK=1 (tests): one fingerprint for all, so that every probe is a false hit and the exact check
+    // has to turn it away.
+    const char *e = getenv("PPV_LOOKUP");
+    if (e && e[0] == '0') return PPV_OK;
+    const char *wk = getenv("PPV_LOOKUP_WEAK");
+    if (wk && wk[0] == '1') ix->view.lookup_fp_mask = 0u;
+    const uint64_t want = 2ull * G;
+    const uint32_t size = (uint32_t)std::min<uint64_t>(want, 0xFFFFFFF0ull);
+    DeviceBuffers tmp;
+    int32_t *d_err;
+    TRY(tmp.alloc(&d_err, 1));
+    TRY(keep_alloc(&ix->d_lookup, size, &ix->device_bytes));
+    PPV_HIP_TRY(hipMemsetAsync(d_err, 0, sizeof(int32_t), st));
+    PPV_HIP_TRY(hipMemsetAsync(ix->d_lookup, 0, (size_t)size * sizeof(uint64_t), st));
+    if (G > 1)
+        hipLaunchKernelGGL(insert_nodes, dim3(blocks_for(G - 1)), dim3(BT), 0, st, (const uint32_t *)ix->d_node_lo,
+                           (const int32_t *)ix->d_x_tok, (const int64_t *)ix->d_x_off,
+                           (const uint32_t *)ix->d_depth_base, l_max, G, ix->d_lookup, size, ix->view.lookup_fp_mask,
+                           d_err);
+    PPV_HIP_TRY(hipGetLastError());
+    int32_t err = 0;
+    PPV_HIP_TRY(hipMemcpyAsync(&err, d_err, sizeof(int32_t), hipMemcpyDeviceToHost, st));
+    PPV_HIP_TRY(hipStreamSynchronize(st));
+    if (err != 0) return PPV_EINVAL;
+    ix->view.lookup = ix->d_lookup;
+    ix->view.lookup_size = size;
+    return PPV_OK;
+}
+
 ppv_status build_on_device(const int32_t *tokens, const int64_t *offsets, int64_t n_seq, int32_t vocab, ppv_index *ix) {
     if (offsets[0] != 0) return PPV_EINVAL;
     const int64_t total = offsets[n_seq];
@@ -596,6 +694,7 @@ ppv_status build_on_device(const int32_t *tokens, const int64_t *offsets, int64_
 
     // ---- 6. heavy prefixes
     TRY(finish_heavy(ix, G, vocab, st));
+    TRY(finish_lookup(ix, G, l_max, st));
 
     ix->n_tokens = n_tok;
     ix->view.ent = ix->d_ent;
@@ -616,6 +715,8 @@ void release(ppv_index *ix) {
     (void)hipFree(ix->d_heavy_slot);
     (void)hipFree(ix->d_heavy_bits);
     (void)hipFree(ix->d_heavy_rank);
+    (void)hipFree(ix->d_lookup);
+    (void)hipFree(ix->d_depth_base);
     (void)hipFree(ix->d_x_tok);
     (void)hipFree(ix->d_x_off);
     delete ix;
@@ -816,6 +917,7 @@ ppv_status load_from_file(FILE *f, ppv_index *ix) {
     if (err != 0) return PPV_EINVAL;
 
     TRY(finish_heavy(ix, (uint32_t)h.n_nodes, h.vocab, s0));
+    TRY(finish_lookup(ix, (uint32_t)h.n_nodes, h.l_max, s0));
     ix->n_tokens = (int64_t)h.n_tokens;
     ix->view.ent = ix->d_ent;
     ix->view.node_lo = ix->d_node_lo;

@@ -35,6 +35,15 @@ struct IndexView {
     const uint32_t *heavy_slot;  // [heavy_limit] slot of a heavy node, PPV_NO_SLOT otherwise
     const uint32_t *heavy_bits;  // [n_heavy, n_words] valid-set images
     const uint32_t *heavy_rank;  // [n_heavy, n_words] children before each word
+    // Hashed look-up of whole prefixes (all lengths of a query are probed at once instead of one level after
+    // the other): open addressing, 8 bytes per slot = fingerprint << 32 | node, 0 = empty; lookup_size == 0:
+    // no table.  A hit is only a hint: it is checked against the node's depth and the tokens of its first member.
+    const uint64_t *lookup;      // [lookup_size]
+    const uint32_t *depth_base;  // [l_max + 2] nodes of depth d are depth_base[d] .. depth_base[d+1]
+    const int32_t *x_tok;        // sorted S, flat: row r is x_tok[x_off[r] .. x_off[r+1])
+    const int64_t *x_off;        // [n_rows + 1]
+    uint32_t lookup_size;
+    uint32_t lookup_fp_mask;     // fingerprint bits in use (all of them; 0 in a test mode that makes every probe a false hit)
     uint32_t heavy_limit;        // nodes >= heavy_limit are not heavy
     uint32_t heavy_min;          // a node is heavy iff it has more than heavy_min children
     uint32_t n_nodes;            // including node 0
@@ -57,6 +66,8 @@ struct ppv_index {
     NodeEnt *d_ent;
     uint32_t *d_node_lo, *d_node_hi;
     uint32_t *d_heavy_slot, *d_heavy_bits, *d_heavy_rank;
+    uint64_t *d_lookup;
+    uint32_t *d_depth_base;
     int32_t *d_x_tok;    // sorted S, flat, no padding: row r is d_x_tok[d_x_off[r] .. d_x_off[r+1])
     int64_t *d_x_off;    // [n_rows + 1]
     int64_t n_tokens;

@@ -60,17 +60,19 @@ __device__ inline uint32_t wave_search(const NodeEnt *__restrict__ ent, uint32_t
     return lo + (uint32_t)c;
 }
 
-__device__ inline Walk walk_prefix(const IndexView &ix, const int32_t *__restrict__ prefix, int t, int lane) {
+// The descent from a known node: token i of the prefix is searched among the children of the node reached
+// by tokens 0..i-1, for i = start .. t-1.  `mine` is lane l's token l of the prefix (the first 64 tokens
+// in one coalesced load; token i is broadcast from lane i).
+__device__ inline Walk walk_from(const IndexView &ix, const int32_t *__restrict__ prefix, int t, int lane, int32_t mine,
+                                 int start, uint32_t node, uint32_t tokw, uint32_t cb, uint32_t ce) {
     Walk w;
-    w.node = 0;
-    w.cb = ix.ent[0].child;
-    w.ce = ix.ent[1].child;
-    w.tok = 0;
+    w.node = node;
+    w.cb = cb;
+    w.ce = ce;
+    w.tok = tokw;
     w.found = true;
     w.member = false;
-    // the first 64 tokens in one coalesced load; token i is broadcast from lane i
-    const int32_t mine = (lane < t) ? prefix[lane] : 0;
-    for (int i = 0; i < t; i++) {
+    for (int i = start; i < t; i++) {
         const uint32_t key = (uint32_t)((i < WAVE) ? lane_value(mine, i) : prefix[i]);
         NodeEnt hit;
         uint32_t next_child = 0;
@@ -94,6 +96,63 @@ __device__ inline Walk walk_prefix(const IndexView &ix, const int32_t *__restric
     w.hi = w.node ? ix.node_hi[w.node] : ix.n_rows;
     w.member = (w.tok & PPV_NODE_TERMINAL) != 0u;
     return w;
+}
+
+// Hash of a token string, one token at a time; the same function fills the table and probes it.
+constexpr uint64_t PREFIX_HASH_SEED = 0x243F6A8885A308D3ull, PREFIX_HASH_MUL = 0x9E3779B97F4A7C15ull;
+__device__ inline uint64_t prefix_hash_step(uint64_t h, uint32_t tok) { return (h ^ tok) * PREFIX_HASH_MUL; }
+__device__ inline void prefix_hash_finish(uint64_t h, uint32_t size, uint32_t fp_mask, uint32_t *slot, uint32_t *fp) {
+    h ^= h >> 32;
+    h *= 0xD6E8FEB86659FD93ull;
+    h ^= h >> 29;
+    *slot = __umulhi((uint32_t)(h >> 32), size);
+    *fp = ((uint32_t)h & fp_mask) | 1u;
+}
+
+// Locates the prefix.  With a look-up table every length of the prefix is probed at once (lane d hashes
+// tokens 0..d); the deepest hit is checked exactly -- its node must have that depth and the first member
+// under it must begin with these tokens -- and the descent then starts there: nothing is left to descend
+// when the whole prefix is in the index, one failing step (which yields the rank) when it is not.  A hit
+// that fails the check (a fingerprint collision) only costs the shortcut: the descent starts at the root.
+__device__ inline Walk walk_prefix(const IndexView &ix, const int32_t *__restrict__ prefix, int t, int lane) {
+    const int32_t mine = (lane < t) ? prefix[lane] : 0;
+    const uint32_t root_cb = ix.ent[0].child, root_ce = ix.ent[1].child;
+    int tl = t < WAVE ? t : WAVE;
+    tl = tl < ix.l_max ? tl : ix.l_max;   // nothing longer than the longest member is in the index
+    if (ix.lookup_size != 0u && tl > 0) {
+        uint64_t h = PREFIX_HASH_SEED;
+        for (int i = 0; i < tl; i++) {
+            const uint64_t hn = prefix_hash_step(h, (uint32_t)lane_value(mine, i));
+            h = (i <= lane) ? hn : h;
+        }
+        uint32_t slot, fp;
+        prefix_hash_finish(h, ix.lookup_size, ix.lookup_fp_mask, &slot, &fp);
+        uint32_t cand = PPV_NO_SLOT;
+        if (lane < tl) {
+            for (uint32_t n = 0; n < ix.lookup_size; n++) {   // ends at the first empty slot (the table is half empty)
+                const uint64_t e = ix.lookup[slot];
+                if (e == 0ull) break;
+                if ((uint32_t)(e >> 32) == fp) {
+                    cand = (uint32_t)e;
+                    break;
+                }
+                slot = slot + 1u == ix.lookup_size ? 0u : slot + 1u;
+            }
+        }
+        const uint64_t hits = __ballot(cand != PPV_NO_SLOT);
+        if (hits) {
+            const int D = 63 - __clzll((long long)hits);   // deepest level with a hit: prefix length D + 1
+            const uint32_t g = lane_value(cand, D);
+            if (g >= ix.depth_base[D + 1] && g < ix.depth_base[D + 2]) {
+                const NodeEnt e0 = ix.ent[g], e1 = ix.ent[g + 1];
+                const int64_t a = ix.x_off[ix.node_lo[g]];   // a node of depth D+1: its first member has D+1 tokens or more
+                const bool same = lane > D || ix.x_tok[a + lane] == mine;
+                if (__ballot(!same) == 0ull)
+                    return walk_from(ix, prefix, t, lane, mine, D + 1, g, e0.tok, e0.child, e1.child);
+            }
+        }
+    }
+    return walk_from(ix, prefix, t, lane, mine, 0, 0u, 0u, root_cb, root_ce);
 }
 
 __device__ inline uint32_t heavy_slot_of(const IndexView &ix, uint32_t node) {

@@ -438,3 +438,32 @@ def test_binding_rejects_bad_arguments():
         ppv.constrained_sample(base[:, :1022], torch.zeros((2, 32), dtype=torch.int32, device=DEV),
                                torch.zeros(2, device=DEV), torch.zeros(2, dtype=torch.int32, device=DEV),
                                torch.zeros(2, device=DEV))
+
+
+@pytest.mark.parametrize("mode", ["weak", "off"])
+def test_prefix_lookup_modes(mode, monkeypatch):
+    """Prefixes are located through a hash table whose hits are only hints.  PPV_LOOKUP_WEAK=1 builds the table
+    with a single fingerprint, so that every probe returns some node and the exact check has to turn the wrong
+    ones away; PPV_LOOKUP=0 builds none.  Masks, ranges and membership must not change, for valid, corrupted,
+    random, over-long and empty prefixes alike."""
+    monkeypatch.setenv("PPV_LOOKUP_WEAK" if mode == "weak" else "PPV_LOOKUP", "1" if mode == "weak" else "0")
+    cfg, S, trie, _ = setup_case("C2")
+    index = ppv.ppv_build_index(S.tokens, S.offsets, cfg.vocab)
+    pb = W.make_prefix_batch(cfg, S)
+    B = pb.prefixes.shape[0]
+    stride = 80                                               # longer than a wavefront and than any member
+    P = np.full((B + 4, stride), W.PAD_TOKEN, np.int32)
+    L = np.zeros(B + 4, np.int32)
+    P[:B, :pb.stride] = pb.prefixes
+    L[:B] = pb.lens
+    m0 = S.seq(0)
+    P[B, :len(m0)] = m0                                       # a member followed by 70 more tokens
+    P[B, len(m0):] = 1
+    L[B] = stride
+    P[B + 1, :len(m0)] = m0                                   # exactly a member
+    L[B + 1] = len(m0)
+    P[B + 2, :] = m0[0]                                       # one token repeated 80 times
+    L[B + 2] = stride
+    L[B + 3] = 0
+    assert_query_parity(index, trie, P, L)
+    index.free()
