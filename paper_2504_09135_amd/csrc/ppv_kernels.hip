@@ -14,6 +14,7 @@
 // Nothing here is a dense contraction, so no MFMA; the bound is HBM bandwidth, with the exp
 // (quarter-rate v_exp_f32) as the main ALU cost.
 #include <cstdlib>
+#include <type_traits>
 
 #include "ppv_device.h"
 #include "ppv_internal.h"
@@ -25,7 +26,6 @@ constexpr int MASK_THREADS = 256;
 constexpr int MAX_WAVES = 16;                 // wavefronts per row (workgroup of up to 1024 threads)
 constexpr int LOOP_WAVES = 8;                 // the decode-loop kernel holds more in registers: at most 512 threads
 constexpr int MAX_TILES = 256;                // PPV_MAX_VOCAB / 1024 (fp32 tiles are 1024 tokens)
-constexpr int MAX_SLICES = PPV_LIST_MAX / WAVE;
 constexpr float LOG2E = 1.44269504088896340736f;
 constexpr float LN2F = 0.693147180559945309417f;
 static_assert(PPV_MAX_VOCAB <= MAX_TILES * 1024, "tile bookkeeping too small");
@@ -346,20 +346,25 @@ __device__ inline int locate_in_tile(const RawTile &rt, uint32_t tile_word, int 
 
 // ------------------------------------------------------------------------------------------
 // One row by one workgroup of `nw` wavefronts.
-struct RowShared {
-    float tile_m[MAX_TILES];
-    float tile_zall[MAX_TILES];
-    float tile_zval[MAX_TILES];
-    float tile_ref[MAX_TILES];         // what tile_zval is relative to (the tile maximum, or the valid maximum)
-    uint32_t list_tok[PPV_LIST_MAX + 1];    // valid tokens in increasing order (list path), flags in the top bits
-    uint32_t list_child[PPV_LIST_MAX + 1];  // decode step: child offsets of the listed entries
-    float list_e[PPV_LIST_MAX];        // exp(l - slice max) per listed token
-    float slice_m[MAX_SLICES];
-    float slice_z[MAX_SLICES];
-    int tile_cnt[MAX_TILES];           // valid tokens per tile (mask -> list conversion)
+template <int TILES, int LIST> struct RowSharedT {
+    float tile_m[TILES];
+    float tile_zall[TILES];
+    float tile_zval[TILES];
+    float tile_ref[TILES];             // what tile_zval is relative to (the tile maximum, or the valid maximum)
+    uint32_t list_tok[LIST + 1];       // valid tokens in increasing order (list path), flags in the top bits
+    uint32_t list_child[LIST + 1];     // decode step: child offsets of the listed entries
+    float list_e[LIST];                // exp(l - slice max) per listed token
+    float slice_m[LIST / WAVE];
+    float slice_z[LIST / WAVE];
+    int tile_cnt[TILES];               // valid tokens per tile (mask -> list conversion)
     int bc_i[8];
     float bc_f[4];
 };
+using RowShared = RowSharedT<MAX_TILES, PPV_LIST_MAX>;
+// Rows of at most SMALL_TILES tiles whose lists hold at most SMALL_LIST tokens (V <= 2048: the list limit is
+// V / 32): 1 KB of LDS per row instead of 18 KB, so that the compute unit is filled by registers, not by LDS.
+constexpr int SMALL_TILES = 4, SMALL_LIST = 64;
+using RowSharedSmall = RowSharedT<SMALL_TILES, SMALL_LIST>;
 
 struct RowOut {
     int32_t id;        // sampled token or -1
@@ -380,9 +385,9 @@ enum ValidMode { VALID_NONE = 0, VALID_LIST = 1, VALID_IMAGE = 2 };
 // counters leave the younger loads in flight (a conditional load anywhere on the way to a use
 // makes it wait for everything).  The row's ragged last tile, if any, is taken with the guarded
 // loader by the wave whose turn it is.
-template <typename T, bool IMAGE>
+template <typename T, bool IMAGE, typename SH>
 __device__ inline void stream_tiles(const T *__restrict__ row, int V, const RawTile &first,
-                                    const uint32_t *__restrict__ image, RowShared &sh, int lane, int wave_v,
+                                    const uint32_t *__restrict__ image, SH &sh, int lane, int wave_v,
                                     int nw) {
     using G = TileGeom<T>;
     const int wave = __builtin_amdgcn_readfirstlane(wave_v);   // scalar: loop control stays uniform
@@ -447,9 +452,9 @@ __device__ inline void stream_tiles(const T *__restrict__ row, int V, const RawT
 //   mode         VALID_LIST: sh.list_tok[0..n_list) holds the valid tokens (in LDS, barrier done)
 //                VALID_IMAGE: image (global memory, V bits) is the valid set
 //                VALID_NONE: the valid set is empty
-template <typename T>
+template <typename T, typename SH>
 __device__ inline RowOut row_sample(const T *__restrict__ row, int V, const RawTile &first, int mode, int n_list,
-                                    const uint32_t *__restrict__ image, float u, RowShared &sh, int tid, int nw,
+                                    const uint32_t *__restrict__ image, float u, SH &sh, int tid, int nw,
                                     const T *__restrict__ next_row = nullptr, RawTile *next_first = nullptr) {
     using G = TileGeom<T>;
     const int lane = tid & (WAVE - 1), wave = tid / WAVE;
@@ -469,8 +474,8 @@ __device__ inline RowOut row_sample(const T *__restrict__ row, int V, const RawT
     }
 
     // ---- stream: every tile once
-    if (mode == VALID_IMAGE) stream_tiles<T, true>(row, V, first, image, sh, lane, wave, nw);
-    else stream_tiles<T, false>(row, V, first, image, sh, lane, wave, nw);
+    if (mode == VALID_IMAGE) stream_tiles<T, true, SH>(row, V, first, image, sh, lane, wave, nw);
+    else stream_tiles<T, false, SH>(row, V, first, image, sh, lane, wave, nw);
     // ---- list path, part 2: sums per slice of 64 listed tokens, relative to the slice maximum
     if (mode == VALID_LIST) {
         for (int s = wave; s < ns; s += nw) {
@@ -655,8 +660,8 @@ __device__ inline RowOut row_sample(const T *__restrict__ row, int V, const RawT
 // ------------------------------------------------------------------------------------------
 // constrained_sample: the valid set arrives as a packed mask.  Count its bits; a small set is
 // unpacked into the token list, a large one is used as an image.
-template <typename T>
-__global__ __launch_bounds__(MAX_WAVES *WAVE) void sample_kernel(const T *__restrict__ logits, int64_t row_stride,
+template <typename T, bool SMALL>
+__global__ __launch_bounds__(SMALL ? SMALL_TILES * WAVE : MAX_WAVES * WAVE) void sample_kernel(const T *__restrict__ logits, int64_t row_stride,
                                                                   const uint32_t *__restrict__ mask,
                                                                   const float *__restrict__ uniforms, int V,
                                                                   int n_words, int list_max,
@@ -664,7 +669,8 @@ __global__ __launch_bounds__(MAX_WAVES *WAVE) void sample_kernel(const T *__rest
                                                                   float *__restrict__ logZ_valid,
                                                                   float *__restrict__ logZ_all) {
     using G = TileGeom<T>;
-    __shared__ RowShared sh;
+    using SH = typename std::conditional<SMALL, RowSharedSmall, RowShared>::type;
+    __shared__ SH sh;
     const int b = blockIdx.x, tid = threadIdx.x, lane = tid & (WAVE - 1), wave = tid / WAVE;
     const int nw = blockDim.x / WAVE;
     const T *row = logits + (size_t)b * (size_t)row_stride;
@@ -700,7 +706,7 @@ __global__ __launch_bounds__(MAX_WAVES *WAVE) void sample_kernel(const T *__rest
         }
         __syncthreads();
     }
-    RowOut r = row_sample<T>(row, V, first, mode, mode == VALID_LIST ? total : 0, mrow, uniforms[b], sh, tid, nw);
+    RowOut r = row_sample<T, SH>(row, V, first, mode, mode == VALID_LIST ? total : 0, mrow, uniforms[b], sh, tid, nw);
     if (tid == 0) {
         ids[b] = r.id;
         logZ_valid[b] = r.logZ_valid;
@@ -805,7 +811,7 @@ __global__ __launch_bounds__(LOOP ? LOOP_WAVES * WAVE : MAX_WAVES * WAVE) void d
         const T *next_row = more ? row + step_stride : nullptr;
         float next_u = 0.f;
         if (more) next_u = uniforms[(size_t)(s + 1) * (size_t)B + b];
-        RowOut r = row_sample<T>(row, V, first, mode, mode == VALID_LIST ? nchild : 0, image, u, sh, tid, nw,
+        RowOut r = row_sample<T, RowShared>(row, V, first, mode, mode == VALID_LIST ? nchild : 0, image, u, sh, tid, nw,
                                  next_row, &next_first);
         if (tid == 0) {
             const bool room = t < stride;
@@ -938,14 +944,27 @@ extern "C" ppv_status constrained_sample(const void *logits, ppv_dtype dt, int64
     const int n_words = (V + 31) / 32;
     const int list_max = V / 32 < PPV_LIST_MAX ? V / 32 : PPV_LIST_MAX;
     const int threads = waves_for(V, dt, B) * WAVE;
-    if (dt == PPV_F32)
-        hipLaunchKernelGGL(sample_kernel<float>, dim3((unsigned)B), dim3(threads), 0, (hipStream_t)stream,
-                           (const float *)logits, row_stride, mask, uniforms, V, n_words, list_max, ids, logZ_valid,
-                           logZ_all);
-    else
-        hipLaunchKernelGGL(sample_kernel<uint16_t>, dim3((unsigned)B), dim3(threads), 0, (hipStream_t)stream,
-                           (const uint16_t *)logits, row_stride, mask, uniforms, V, n_words, list_max, ids,
-                           logZ_valid, logZ_all);
+    const int tile = (dt == PPV_F32) ? TileGeom<float>::TILE : TileGeom<uint16_t>::TILE;
+    const bool small = (V + tile - 1) / tile <= SMALL_TILES && list_max <= SMALL_LIST;   // then threads <= SMALL_TILES * WAVE
+    const dim3 grid((unsigned)B), block(threads);
+    hipStream_t hs = (hipStream_t)stream;
+    if (dt == PPV_F32) {
+        const float *lg = (const float *)logits;
+        if (small)
+            hipLaunchKernelGGL((sample_kernel<float, true>), grid, block, 0, hs, lg, row_stride, mask, uniforms, V, n_words,
+                               list_max, ids, logZ_valid, logZ_all);
+        else
+            hipLaunchKernelGGL((sample_kernel<float, false>), grid, block, 0, hs, lg, row_stride, mask, uniforms, V, n_words,
+                               list_max, ids, logZ_valid, logZ_all);
+    } else {
+        const uint16_t *lg = (const uint16_t *)logits;
+        if (small)
+            hipLaunchKernelGGL((sample_kernel<uint16_t, true>), grid, block, 0, hs, lg, row_stride, mask, uniforms, V,
+                               n_words, list_max, ids, logZ_valid, logZ_all);
+        else
+            hipLaunchKernelGGL((sample_kernel<uint16_t, false>), grid, block, 0, hs, lg, row_stride, mask, uniforms, V,
+                               n_words, list_max, ids, logZ_valid, logZ_all);
+    }
     PPV_HIP_TRY(hipGetLastError());
     return PPV_OK;
 }
