@@ -467,6 +467,24 @@ ppv_status finish_heavy(ppv_index *ix, uint32_t G, int32_t vocab, hipStream_t st
     return PPV_OK;
 }
 
+// Nodes of depth d are h_base[d] .. h_base[d+1] (h_base has l_max + 2 entries): depth 0 is the empty prefix, and
+// the nodes of depth d+1 start where the children of the first node of depth d start.  Reads one child offset
+// per depth from the finished entries.
+ppv_status depth_bases(const ppv_index *ix, uint32_t G, int32_t l_max, uint32_t *h_base) {
+    h_base[0] = 0u;
+    h_base[1] = 1u;
+    for (int d = 1; d < l_max; d++) {
+        if (h_base[d] >= G) {
+            h_base[d + 1] = G;
+            continue;
+        }
+        PPV_HIP_TRY(hipMemcpy(&h_base[d + 1], &ix->d_ent[h_base[d]].child, sizeof(uint32_t), hipMemcpyDeviceToHost));
+        if (h_base[d + 1] < h_base[d] || h_base[d + 1] > G) return PPV_EINVAL;
+    }
+    h_base[l_max + 1] = G;
+    return PPV_OK;
+}
+
 // 7. Look-up table of whole prefixes: every node is entered under the hash of its token string (the first
 // tokens of the first member under it).  Also the per-depth node ranges the look-up checks a hit against.
 __global__ __launch_bounds__(BT) void insert_nodes(const uint32_t *__restrict__ node_lo, const int32_t *__restrict__ x_tok,
@@ -499,25 +517,9 @@ __global__ __launch_bounds__(BT) void insert_nodes(const uint32_t *__restrict__ 
 }
 
 ppv_status finish_lookup(ppv_index *ix, uint32_t G, int32_t l_max, hipStream_t st) {
-    // nodes of depth d start where the children of the first node of depth d-1 start
     uint32_t *h_base = new (std::nothrow) uint32_t[(size_t)l_max + 2];
     if (!h_base) return PPV_ENOMEM;
-    h_base[0] = 0u;
-    h_base[1] = 1u;
-    ppv_status rc = PPV_OK;
-    for (int d = 1; d < l_max && rc == PPV_OK; d++) {
-        if (h_base[d] >= G) {
-            h_base[d + 1] = G;
-            continue;
-        }
-        if (hipMemcpy(&h_base[d + 1], &ix->d_ent[h_base[d]].child, sizeof(uint32_t), hipMemcpyDeviceToHost) != hipSuccess) {
-            (void)hipGetLastError();
-            rc = PPV_EDEVICE;
-        } else if (h_base[d + 1] < h_base[d] || h_base[d + 1] > G) {
-            rc = PPV_EINVAL;
-        }
-    }
-    h_base[l_max + 1] = G;
+    ppv_status rc = depth_bases(ix, G, l_max, h_base);
     if (rc == PPV_OK) rc = keep_alloc(&ix->d_depth_base, (size_t)l_max + 2, &ix->device_bytes);
     if (rc == PPV_OK && hipMemcpy(ix->d_depth_base, h_base, ((size_t)l_max + 2) * sizeof(uint32_t), hipMemcpyHostToDevice) !=
                             hipSuccess) {
@@ -669,20 +671,17 @@ ppv_status build_on_device(const int32_t *tokens, const int64_t *offsets, int64_
                        (const int32_t *)ix->d_x_tok, (const int64_t *)ix->d_x_off, (const int32_t *)row_lcp,
                        (const uint32_t *)pos, (uint64_t)n_rows, l_max, G, ix->d_ent, ix->d_node_lo);
 
-    // ---- 5. hi, deepest depth first; depth d holds the entries 1 + pos[d * n_rows] .. 1 + pos[(d+1) * n_rows]
-    // (the l_max + 1 bounds are read back in one strided copy)
-    uint32_t *h_base = new (std::nothrow) uint32_t[(size_t)l_max + 1];
+    // ---- 5. hi, deepest depth first (a prefix ends where its last child ends, so the children's depth comes first)
+    uint32_t *h_base = new (std::nothrow) uint32_t[(size_t)l_max + 2];
     if (!h_base) return PPV_ENOMEM;
-    hipError_t ce = hipMemcpy2DAsync(h_base, sizeof(uint32_t), pos, (size_t)n_rows * sizeof(uint32_t), sizeof(uint32_t),
-                                     (size_t)l_max + 1, hipMemcpyDeviceToHost, st);
-    if (ce == hipSuccess) ce = hipStreamSynchronize(st);
-    if (ce != hipSuccess) {
+    PPV_HIP_TRY(hipStreamSynchronize(st));
+    const ppv_status rc_base = depth_bases(ix, G, l_max, h_base);
+    if (rc_base != PPV_OK) {
         delete[] h_base;
-        (void)hipGetLastError();
-        return PPV_EDEVICE;
+        return rc_base;
     }
-    for (int d = l_max - 1; d >= 0; d--) {
-        const uint32_t g0 = 1u + h_base[d], g1 = 1u + h_base[d + 1];
+    for (int d = l_max; d >= 1; d--) {
+        const uint32_t g0 = h_base[d], g1 = h_base[d + 1];
         if (g1 > g0)
             hipLaunchKernelGGL(fill_hi, dim3(blocks_for(g1 - g0)), dim3(BT), 0, st, (const NodeEnt *)ix->d_ent,
                                (const uint32_t *)ix->d_node_lo, g0, g1, ix->d_node_hi);

@@ -1,5 +1,6 @@
-// Per-step kernels for gfx950 (wave64): prefix walk (rank range), next-token scatter (packed
-// mask), fused masked log-softmax + inverse-CDF sample, and the fused decode step.
+// Per-step kernels for gfx950 (wave64): next-token scatter (packed mask) with the prefix's rank range,
+// fused masked log-softmax + inverse-CDF sample, and the fused decode step (the prefix is located by
+// walk_prefix, shared with the top-M kernel).
 //
 // The logits row is the only large operand.  It is streamed exactly once, in tiles of 4 KB per
 // wavefront (four 16-byte loads per lane, issued before any index work so that they are in
