@@ -467,3 +467,52 @@ def test_prefix_lookup_modes(mode, monkeypatch):
     L[B + 3] = 0
     assert_query_parity(index, trie, P, L)
     index.free()
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_largest_vocabulary_and_a_large_batch(dtype):
+    """V = PPV_MAX_VOCAB (every per-row table at its limit: 256 fp32 tiles, 32 KB mask rows) with a root that
+    has tens of thousands of children, and a batch larger than 65,535 rows on a small index."""
+    V = ppv.PPV_MAX_VOCAB
+    rng = np.random.default_rng(99)
+    seqs = [[int(v)] for v in rng.choice(V, size=40_000, replace=False)]
+    seqs += [[int(a), int(b)] for a, b in rng.integers(0, V, size=(5_000, 2))]
+    seqs += [[V - 1, V - 1, V - 1], [0], [V - 1]]
+    S = W.constraint_set_from_lists(seqs, V)
+    trie = oracle.Trie(S.tokens, S.offsets, V)
+    index = ppv.ppv_build_index(S.tokens, S.offsets, V)
+    assert index.n_distinct == trie.n_members
+    B = 6
+    P = np.full((B, 3), W.PAD_TOKEN, np.int32)
+    L = np.array([0, 1, 2, 1, 0, 3], np.int32)
+    P[1, 0] = seqs[40_000][0]
+    P[2, :2] = [V - 1, V - 1]
+    P[3, 0] = V - 1
+    P[5, :3] = [V - 1, V - 1, V - 1]
+    dmask, ref_q = assert_query_parity(index, trie, P, L)
+    lg = rng.normal(0, 2, size=(B, V)).astype(np.float32)
+    lg[4, :] = -30.0
+    lg[4, V - 1] = 5.0                                        # the last token of the last tile carries the row
+    un = rng.random(B).astype(np.float32)
+    if dtype == "bf16":
+        bits = ((lg.view(np.uint32) + 0x8000) >> 16).astype(np.uint16)
+        lf = (bits.astype(np.uint32) << 16).view(np.float32)
+        ld = to_dev(bits.view(np.int16)).view(torch.bfloat16)
+    else:
+        lf, ld = lg, to_dev(lg)
+    ref = trie.step(P, L, lf, un, threads=4)
+    ids = torch.full((B,), -7, dtype=torch.int32, device=DEV)
+    lzv = torch.zeros(B, dtype=torch.float32, device=DEV)
+    lza = torch.zeros(B, dtype=torch.float32, device=DEV)
+    ppv.constrained_sample(ld, dmask, to_dev(un), ids, lzv, lza)
+    torch.cuda.synchronize()
+    check_sample_rows(dtype, ref, lambda b: ref.mask[b], un, ids.cpu().numpy(), lzv.cpu().numpy(), lza.cpu().numpy())
+    index.free()
+
+    # 70,000 rows on the C1 index: the grid's first dimension goes past 65,535
+    cfg, S1, trie1, index1 = setup_case("C1")
+    pb = W.make_prefix_batch(cfg, S1)
+    reps = 70_000 // pb.prefixes.shape[0] + 1
+    Pb = np.tile(pb.prefixes, (reps, 1))[:70_000]
+    Lb = np.tile(pb.lens, reps)[:70_000]
+    assert_query_parity(index1, trie1, Pb, Lb, threads=8)
