@@ -91,6 +91,36 @@ def test_C3_full_decode_loop_graph():
     gP, gL, gid, glz, glx = eager
     assert not active.cpu().numpy().any()
 
+    # The batch sweep of bench.py runs the same loop on 1,024 and 4,096 rows, where a row gets 4 wavefronts instead
+    # of 8.  Tiles and the order in which they are combined do not depend on that, so four replicas of this batch
+    # in one launch must reproduce the 256-row result bit for bit -- per step and as one ppv_decode_loop launch.
+    R = 4
+    big_logits = logits.repeat(1, R, 1).contiguous()
+    big_un = uniforms.repeat(1, R).contiguous()
+    for single_launch in (False, True):
+        bp = torch.full((B * R, L), W.PAD_TOKEN, dtype=torch.int32, device=DEV)
+        bl = torch.zeros(B * R, dtype=torch.int32, device=DEV)
+        ba = torch.zeros(B * R, dtype=torch.uint8, device=DEV)
+        bs = torch.zeros((B * R, ppv.PPV_STATE_WORDS), dtype=torch.int32, device=DEV)
+        bx = torch.zeros(B * R, dtype=torch.float32, device=DEV)
+        bid = torch.full((L, B * R), -5, dtype=torch.int32, device=DEV)
+        blz = torch.zeros((L, B * R), dtype=torch.float32, device=DEV)
+        ppv.ppv_decode_begin(index, bp, bl, bs, ba, bx)
+        if single_launch:
+            ppv.ppv_decode_loop(index, bp, bl, ba, big_logits, big_un, bid, blz, bx, state=bs)
+        else:
+            for s in range(L):
+                ppv.ppv_decode_step(index, bp, bl, ba, big_logits[s], big_un[s], bid[s], blz[s], bx, state=bs)
+        torch.cuda.synchronize()
+        for r in range(R):
+            rows = slice(r * B, (r + 1) * B)
+            assert np.array_equal(bp[rows].cpu().numpy(), gP) and np.array_equal(bl[rows].cpu().numpy(), gL)
+            assert np.array_equal(bid[:, rows].cpu().numpy(), gid), (single_launch, r)
+            on = gid >= 0
+            assert np.array_equal(blz[:, rows].cpu().numpy().view(np.int32)[on], glz.view(np.int32)[on])
+            assert np.array_equal(bx[rows].cpu().numpy().view(np.int32), glx.view(np.int32))
+    del big_logits, big_un
+
     say("C3: oracle loop")
     # the oracle makes its own choice at every step (recorded) but is kept on the HIP path's sequence, so
     # that a disagreement inside the CDF band at one step does not invalidate the comparison of later steps
