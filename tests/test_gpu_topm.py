@@ -128,6 +128,27 @@ def test_topm_ties_special_values_and_ragged_rows(dtype):
         assert_topm_parity(index, X, P, L, lf, ld, M)
 
 
+def test_topm_largest_vocabulary():
+    """V = PPV_MAX_VOCAB: the mask row fills the LDS that the histogram used; fp32 rows of 256 chunks per wavefront."""
+    V = ppv.PPV_MAX_VOCAB
+    rng = np.random.default_rng(5)
+    seqs = [[int(v)] for v in rng.choice(V, size=30_000, replace=False)] + [[7, int(v)] for v in range(0, V, 997)] + [[7]]
+    S = W.constraint_set_from_lists(seqs, V)
+    X = oracle.SortedArray(S.tokens, S.offsets, V)
+    index = ppv.ppv_build_index(S.tokens, S.offsets, V)
+    P = np.full((3, 2), W.PAD_TOKEN, np.int32)
+    L = np.array([0, 1, 1], np.int32)
+    P[1, 0] = 7
+    P[2, 0] = 8
+    lg = rng.normal(0, 3, size=(3, V)).astype(np.float32)
+    for M in (50, 1000):
+        assert_topm_parity(index, X, P, L, lg, to_dev(lg), M)
+    bits = ((lg.view(np.uint32) + 0x8000) >> 16).astype(np.uint16)
+    lf = (bits.astype(np.uint32) << 16).view(np.float32)
+    assert_topm_parity(index, X, P, L, lf, to_dev(bits.view(np.int16)).view(torch.bfloat16), 500)
+    index.free()
+
+
 def test_topm_whole_row_select_path(monkeypatch):
     """The selection has two routes (bound + short list; radix select over the whole row when the list would not
     fit).  PPV_TOPM_STREAMING=1 sends every row down the second one: same results."""
