@@ -516,6 +516,12 @@ __global__ __launch_bounds__(BT) void insert_nodes(const uint32_t *__restrict__ 
     }
 }
 
+__global__ __launch_bounds__(BT) void fill_xpos(const uint32_t *__restrict__ node_lo, const int64_t *__restrict__ x_off,
+                                                uint32_t n_nodes, uint32_t *__restrict__ xpos) {
+    const uint32_t g = blockIdx.x * BT + threadIdx.x;
+    if (g < n_nodes) xpos[g] = (uint32_t)x_off[node_lo[g]];
+}
+
 ppv_status finish_lookup(ppv_index *ix, uint32_t G, int32_t l_max, hipStream_t st) {
     uint32_t *h_base = new (std::nothrow) uint32_t[(size_t)l_max + 2];
     if (!h_base) return PPV_ENOMEM;
@@ -547,6 +553,9 @@ ppv_status finish_lookup(ppv_index *ix, uint32_t G, int32_t l_max, hipStream_t s
     int32_t *d_err;
     TRY(tmp.alloc(&d_err, 1));
     TRY(keep_alloc(&ix->d_lookup, size, &ix->device_bytes));
+    TRY(keep_alloc(&ix->d_node_xpos, G, &ix->device_bytes));
+    hipLaunchKernelGGL(fill_xpos, dim3(blocks_for(G)), dim3(BT), 0, st, (const uint32_t *)ix->d_node_lo,
+                       (const int64_t *)ix->d_x_off, G, ix->d_node_xpos);
     PPV_HIP_TRY(hipMemsetAsync(d_err, 0, sizeof(int32_t), st));
     PPV_HIP_TRY(hipMemsetAsync(ix->d_lookup, 0, (size_t)size * sizeof(uint64_t), st));
     if (G > 1)
@@ -560,6 +569,7 @@ ppv_status finish_lookup(ppv_index *ix, uint32_t G, int32_t l_max, hipStream_t s
     PPV_HIP_TRY(hipStreamSynchronize(st));
     if (err != 0) return PPV_EINVAL;
     ix->view.lookup = ix->d_lookup;
+    ix->view.node_xpos = ix->d_node_xpos;
     ix->view.lookup_size = size;
     return PPV_OK;
 }
@@ -716,6 +726,7 @@ void release(ppv_index *ix) {
     (void)hipFree(ix->d_heavy_rank);
     (void)hipFree(ix->d_lookup);
     (void)hipFree(ix->d_depth_base);
+    (void)hipFree(ix->d_node_xpos);
     (void)hipFree(ix->d_x_tok);
     (void)hipFree(ix->d_x_off);
     delete ix;

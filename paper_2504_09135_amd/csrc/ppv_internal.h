@@ -40,6 +40,7 @@ struct IndexView {
     // no table.  A hit is only a hint: it is checked against the node's depth and the tokens of its first member.
     const uint64_t *lookup;      // [lookup_size]
     const uint32_t *depth_base;  // [l_max + 2] nodes of depth d are depth_base[d] .. depth_base[d+1]
+    const uint32_t *node_xpos;   // [n_nodes] where the first member under the node starts in x_tok (with a table only)
     const int32_t *x_tok;        // sorted S, flat: row r is x_tok[x_off[r] .. x_off[r+1])
     const int64_t *x_off;        // [n_rows + 1]
     uint32_t lookup_size;
@@ -67,7 +68,7 @@ struct ppv_index {
     uint32_t *d_node_lo, *d_node_hi;
     uint32_t *d_heavy_slot, *d_heavy_bits, *d_heavy_rank;
     uint64_t *d_lookup;
-    uint32_t *d_depth_base;
+    uint32_t *d_depth_base, *d_node_xpos;
     int32_t *d_x_tok;    // sorted S, flat, no padding: row r is d_x_tok[d_x_off[r] .. d_x_off[r+1])
     int64_t *d_x_off;    // [n_rows + 1]
     int64_t n_tokens;

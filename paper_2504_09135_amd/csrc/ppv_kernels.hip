@@ -54,9 +54,10 @@ __global__ __launch_bounds__(MASK_THREADS) void mask_kernel(IndexView ix, const 
     uint32_t *bc = smem + n_words;   // [4]: node, found, cb, ce
     const int b = blockIdx.x, tid = threadIdx.x, lane = tid & (WAVE - 1), wave = tid / WAVE;
     if (wave == 0) {
+        const int32_t mine = first_tokens(prefixes + (size_t)b * (size_t)stride, stride, lane);
         int t = lens[b];
         t = t < 0 ? 0 : (t > stride ? stride : t);
-        Walk w = walk_prefix(ix, prefixes + (size_t)b * (size_t)stride, t, lane);
+        Walk w = walk_prefix(ix, prefixes + (size_t)b * (size_t)stride, mine, t, lane);
         if (lane == 0) {
             bc[0] = w.node;
             bc[1] = w.found ? 1u : 0u;
@@ -725,9 +726,10 @@ __global__ __launch_bounds__(MASK_THREADS) void decode_begin_kernel(IndexView ix
     const int lane = threadIdx.x & (WAVE - 1);
     const int b = blockIdx.x * (MASK_THREADS / WAVE) + threadIdx.x / WAVE;
     if (b >= B) return;  // uniform per wave
+    const int32_t mine = first_tokens(prefixes + (size_t)b * (size_t)stride, stride, lane);
     int t = lens[b];
     t = t < 0 ? 0 : (t > stride ? stride : t);
-    const Walk w = walk_prefix(ix, prefixes + (size_t)b * (size_t)stride, t, lane);
+    const Walk w = walk_prefix(ix, prefixes + (size_t)b * (size_t)stride, mine, t, lane);
     if (lane == 0) {
         RowState st;
         st.node = w.found ? w.node : PPV_NO_SLOT;
@@ -771,7 +773,8 @@ __global__ __launch_bounds__(LOOP ? LOOP_WAVES * WAVE : MAX_WAVES * WAVE) void d
     t = t < 0 ? 0 : (t > stride ? stride : t);
     if (!state) {  // no cursor: locate the prefix from the root (wave 0), then share it
         if (wave == 0) {
-            const Walk w = walk_prefix(ix, prefixes + (size_t)b * (size_t)stride, t, lane);
+            const int32_t mine = first_tokens(prefixes + (size_t)b * (size_t)stride, stride, lane);
+            const Walk w = walk_prefix(ix, prefixes + (size_t)b * (size_t)stride, mine, t, lane);
             if (lane == 0) {
                 sh.bc_i[4] = (int)(w.found ? w.node : PPV_NO_SLOT);
                 sh.bc_i[5] = (int)(w.found ? w.cb : 0u);

@@ -475,9 +475,10 @@ __global__ __launch_bounds__(TOPM_WAVES *WAVE) void topm_kernel(IndexView ix, co
     uint4 r[4];
     if (listed) load_chunks<T>(row, V, c0, c1, lane, r);   // in flight while the prefix is located
     if (wave == 0) {   // the part every candidate row shares: locate the prefix once
+        const int32_t mine = first_tokens(prefixes + (size_t)b * (size_t)stride, stride, lane);
         int t = lens[b];
         t = t < 0 ? 0 : (t > stride ? stride : t);
-        const Walk w = walk_prefix(ix, prefixes + (size_t)b * (size_t)stride, t, lane);
+        const Walk w = walk_prefix(ix, prefixes + (size_t)b * (size_t)stride, mine, t, lane);
         if (lane == 0) {
             bc[0] = w.node;
             bc[1] = w.found ? 1u : 0u;

@@ -114,8 +114,12 @@ __device__ inline void prefix_hash_finish(uint64_t h, uint32_t size, uint32_t fp
 // under it must begin with these tokens -- and the descent then starts there: nothing is left to descend
 // when the whole prefix is in the index, one failing step (which yields the rank) when it is not.  A hit
 // that fails the check (a fingerprint collision) only costs the shortcut: the descent starts at the root.
-__device__ inline Walk walk_prefix(const IndexView &ix, const int32_t *__restrict__ prefix, int t, int lane) {
-    const int32_t mine = (lane < t) ? prefix[lane] : 0;
+// `mine` = first_tokens(prefix, stride, lane), requested by the caller before the prefix's length is known.
+__device__ inline int32_t first_tokens(const int32_t *__restrict__ prefix, int stride, int lane) {
+    return (lane < stride) ? prefix[lane] : 0;
+}
+__device__ inline Walk walk_prefix(const IndexView &ix, const int32_t *__restrict__ prefix, int32_t mine, int t,
+                                   int lane) {
     const uint32_t root_cb = ix.ent[0].child, root_ce = ix.ent[1].child;
     int tl = t < WAVE ? t : WAVE;
     tl = tl < ix.l_max ? tl : ix.l_max;   // nothing longer than the longest member is in the index
@@ -145,8 +149,8 @@ __device__ inline Walk walk_prefix(const IndexView &ix, const int32_t *__restric
             const uint32_t g = lane_value(cand, D);
             if (g >= ix.depth_base[D + 1] && g < ix.depth_base[D + 2]) {
                 const NodeEnt e0 = ix.ent[g], e1 = ix.ent[g + 1];
-                const int64_t a = ix.x_off[ix.node_lo[g]];   // a node of depth D+1: its first member has D+1 tokens or more
-                const bool same = lane > D || ix.x_tok[a + lane] == mine;
+                const uint32_t a = ix.node_xpos[g];   // a node of depth D+1: its first member has D+1 tokens or more
+                const bool same = lane > D || ix.x_tok[(size_t)a + lane] == mine;
                 if (__ballot(!same) == 0ull)
                     return walk_from(ix, prefix, t, lane, mine, D + 1, g, e0.tok, e0.child, e1.child);
             }
