@@ -150,7 +150,7 @@ def main() -> int:
     args = ap.parse_args()
     if args.gpus != 1:
         print(f"bench.py: this build runs on one GPU only (got --gpus {args.gpus}); the path is data-parallel "
-              "over rows with a replicated index and needs no collective, see DESIGN.md", file=sys.stderr)
+              "over rows with a replicated index and needs no collective", file=sys.stderr)
         return 2
 
     import numpy as np
