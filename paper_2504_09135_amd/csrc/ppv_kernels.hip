@@ -387,7 +387,7 @@ enum ValidMode { VALID_NONE = 0, VALID_LIST = 1, VALID_IMAGE = 2 };
 // counters leave the younger loads in flight (a conditional load anywhere on the way to a use
 // makes it wait for everything).  The row's ragged last tile, if any, is taken with the guarded
 // loader by the wave whose turn it is.
-template <typename T, bool IMAGE, typename SH>
+template <typename T, bool IMAGE, bool PIPE, typename SH>
 __device__ inline void stream_tiles(const T *__restrict__ row, int V, const RawTile &first,
                                     const uint32_t *__restrict__ image, SH &sh, int lane, int wave_v,
                                     int nw) {
@@ -415,7 +415,7 @@ __device__ inline void stream_tiles(const T *__restrict__ row, int V, const RawT
     int i = 0;
     RawTile X = first, Y, Z;   // the same three register tiles serve every path below
     if (IMAGE) X.word = tile_mask_word<T>(image, wave, lane, V);
-    if (cnt >= 6) {
+    if (PIPE && cnt >= 6) {
         fetch(Y, wave + nw);
         fetch(Z, wave + 2 * nw);
         while (i + 5 < cnt) {
@@ -454,7 +454,7 @@ __device__ inline void stream_tiles(const T *__restrict__ row, int V, const RawT
 //   mode         VALID_LIST: sh.list_tok[0..n_list) holds the valid tokens (in LDS, barrier done)
 //                VALID_IMAGE: image (global memory, V bits) is the valid set
 //                VALID_NONE: the valid set is empty
-template <typename T, typename SH>
+template <typename T, bool PIPE, typename SH>
 __device__ inline RowOut row_sample(const T *__restrict__ row, int V, const RawTile &first, int mode, int n_list,
                                     const uint32_t *__restrict__ image, float u, SH &sh, int tid, int nw,
                                     const T *__restrict__ next_row = nullptr, RawTile *next_first = nullptr) {
@@ -476,8 +476,8 @@ __device__ inline RowOut row_sample(const T *__restrict__ row, int V, const RawT
     }
 
     // ---- stream: every tile once
-    if (mode == VALID_IMAGE) stream_tiles<T, true, SH>(row, V, first, image, sh, lane, wave, nw);
-    else stream_tiles<T, false, SH>(row, V, first, image, sh, lane, wave, nw);
+    if (mode == VALID_IMAGE) stream_tiles<T, true, PIPE, SH>(row, V, first, image, sh, lane, wave, nw);
+    else stream_tiles<T, false, PIPE, SH>(row, V, first, image, sh, lane, wave, nw);
     // ---- list path, part 2: sums per slice of 64 listed tokens, relative to the slice maximum
     if (mode == VALID_LIST) {
         for (int s = wave; s < ns; s += nw) {
@@ -662,7 +662,7 @@ __device__ inline RowOut row_sample(const T *__restrict__ row, int V, const RawT
 // ------------------------------------------------------------------------------------------
 // constrained_sample: the valid set arrives as a packed mask.  Count its bits; a small set is
 // unpacked into the token list, a large one is used as an image.
-template <typename T, bool SMALL>
+template <typename T, bool SMALL, bool PIPE>
 __global__ __launch_bounds__(SMALL ? SMALL_TILES * WAVE : MAX_WAVES * WAVE) void sample_kernel(const T *__restrict__ logits, int64_t row_stride,
                                                                   const uint32_t *__restrict__ mask,
                                                                   const float *__restrict__ uniforms, int V,
@@ -708,7 +708,7 @@ __global__ __launch_bounds__(SMALL ? SMALL_TILES * WAVE : MAX_WAVES * WAVE) void
         }
         __syncthreads();
     }
-    RowOut r = row_sample<T, SH>(row, V, first, mode, mode == VALID_LIST ? total : 0, mrow, uniforms[b], sh, tid, nw);
+    RowOut r = row_sample<T, PIPE, SH>(row, V, first, mode, mode == VALID_LIST ? total : 0, mrow, uniforms[b], sh, tid, nw);
     if (tid == 0) {
         ids[b] = r.id;
         logZ_valid[b] = r.logZ_valid;
@@ -748,7 +748,7 @@ __global__ __launch_bounds__(MASK_THREADS) void decode_begin_kernel(IndexView ix
 // the cursor lives in registers and the next step's first tiles are requested before the current
 // step is sampled (only when no child of the current prefix is a member, i.e. the row is certain to
 // go on, so nothing is fetched in vain).
-template <typename T, bool LOOP>
+template <typename T, bool LOOP, bool PIPE>
 __global__ __launch_bounds__(LOOP ? LOOP_WAVES * WAVE : MAX_WAVES * WAVE) void decode_kernel(
     IndexView ix, int32_t *__restrict__ prefixes, int32_t stride, int32_t *__restrict__ lens,
     uint8_t *__restrict__ active, RowState *__restrict__ state, const T *__restrict__ logits, int64_t row_stride,
@@ -815,7 +815,7 @@ __global__ __launch_bounds__(LOOP ? LOOP_WAVES * WAVE : MAX_WAVES * WAVE) void d
         const T *next_row = more ? row + step_stride : nullptr;
         float next_u = 0.f;
         if (more) next_u = uniforms[(size_t)(s + 1) * (size_t)B + b];
-        RowOut r = row_sample<T, RowShared>(row, V, first, mode, mode == VALID_LIST ? nchild : 0, image, u, sh, tid, nw,
+        RowOut r = row_sample<T, PIPE, RowShared>(row, V, first, mode, mode == VALID_LIST ? nchild : 0, image, u, sh, tid, nw,
                                  next_row, &next_first);
         if (tid == 0) {
             const bool room = t < stride;
@@ -922,6 +922,44 @@ int waves_for(int V, ppv_dtype dt, int B) {
     return nw;
 }
 
+// Whether some wavefront's turn has six tiles or more, i.e. whether the three-tile pipeline of stream_tiles can
+// run at all.  Kernels for shorter turns are compiled without it: 66 instead of 93 registers (bf16), which is
+// two more rows in flight per compute unit when a large batch keeps every compute unit full.
+bool long_turns(int V, ppv_dtype dt, int nw) {
+    const int tile = (dt == PPV_F32) ? TileGeom<float>::TILE : TileGeom<uint16_t>::TILE;
+    return (V / tile + nw - 1) / nw >= 6;
+}
+
+template <typename T>
+void launch_sample(bool small, bool pipe, dim3 grid, dim3 block, hipStream_t hs, const T *lg, int64_t row_stride,
+                   const uint32_t *mask, const float *uniforms, int V, int n_words, int list_max, int32_t *ids,
+                   float *logZ_valid, float *logZ_all) {
+    if (small)
+        hipLaunchKernelGGL((sample_kernel<T, true, false>), grid, block, 0, hs, lg, row_stride, mask, uniforms, V, n_words,
+                           list_max, ids, logZ_valid, logZ_all);
+    else if (pipe)
+        hipLaunchKernelGGL((sample_kernel<T, false, true>), grid, block, 0, hs, lg, row_stride, mask, uniforms, V, n_words,
+                           list_max, ids, logZ_valid, logZ_all);
+    else
+        hipLaunchKernelGGL((sample_kernel<T, false, false>), grid, block, 0, hs, lg, row_stride, mask, uniforms, V,
+                           n_words, list_max, ids, logZ_valid, logZ_all);
+}
+
+template <typename T>
+void launch_decode_kernel(bool loop, bool pipe, dim3 grid, dim3 block, hipStream_t hs, const IndexView &view,
+                          int32_t *prefixes, int32_t stride, int32_t *lens, uint8_t *active, RowState *rs, const T *lg,
+                          int64_t row_stride, int64_t step_stride, const float *uniforms, int n_steps, int B, int32_t *ids,
+                          float *logZ_valid, float *logx) {
+#define PPV_LAUNCH_DECODE(LOOP, PIPE)                                                                                 \
+    hipLaunchKernelGGL((decode_kernel<T, LOOP, PIPE>), grid, block, 0, hs, view, prefixes, stride, lens, active, rs, lg, \
+                       row_stride, step_stride, uniforms, n_steps, B, ids, logZ_valid, logx)
+    if (loop && pipe) PPV_LAUNCH_DECODE(true, true);
+    else if (loop) PPV_LAUNCH_DECODE(true, false);
+    else if (pipe) PPV_LAUNCH_DECODE(false, true);
+    else PPV_LAUNCH_DECODE(false, false);
+#undef PPV_LAUNCH_DECODE
+}
+
 }  // namespace
 
 extern "C" ppv_status ppv_next_token_mask(const ppv_index_t *ix, const int32_t *prefixes, int32_t prefix_stride,
@@ -950,25 +988,15 @@ extern "C" ppv_status constrained_sample(const void *logits, ppv_dtype dt, int64
     const int threads = waves_for(V, dt, B) * WAVE;
     const int tile = (dt == PPV_F32) ? TileGeom<float>::TILE : TileGeom<uint16_t>::TILE;
     const bool small = (V + tile - 1) / tile <= SMALL_TILES && list_max <= SMALL_LIST;   // then threads <= SMALL_TILES * WAVE
+    const bool pipe = long_turns(V, dt, threads / WAVE);
     const dim3 grid((unsigned)B), block(threads);
     hipStream_t hs = (hipStream_t)stream;
-    if (dt == PPV_F32) {
-        const float *lg = (const float *)logits;
-        if (small)
-            hipLaunchKernelGGL((sample_kernel<float, true>), grid, block, 0, hs, lg, row_stride, mask, uniforms, V, n_words,
-                               list_max, ids, logZ_valid, logZ_all);
-        else
-            hipLaunchKernelGGL((sample_kernel<float, false>), grid, block, 0, hs, lg, row_stride, mask, uniforms, V, n_words,
-                               list_max, ids, logZ_valid, logZ_all);
-    } else {
-        const uint16_t *lg = (const uint16_t *)logits;
-        if (small)
-            hipLaunchKernelGGL((sample_kernel<uint16_t, true>), grid, block, 0, hs, lg, row_stride, mask, uniforms, V,
-                               n_words, list_max, ids, logZ_valid, logZ_all);
-        else
-            hipLaunchKernelGGL((sample_kernel<uint16_t, false>), grid, block, 0, hs, lg, row_stride, mask, uniforms, V,
-                               n_words, list_max, ids, logZ_valid, logZ_all);
-    }
+    if (dt == PPV_F32)
+        launch_sample<float>(small, pipe, grid, block, hs, (const float *)logits, row_stride, mask, uniforms, V, n_words,
+                             list_max, ids, logZ_valid, logZ_all);
+    else
+        launch_sample<uint16_t>(small, pipe, grid, block, hs, (const uint16_t *)logits, row_stride, mask, uniforms, V,
+                                n_words, list_max, ids, logZ_valid, logZ_all);
     PPV_HIP_TRY(hipGetLastError());
     return PPV_OK;
 }
@@ -1006,24 +1034,16 @@ ppv_status launch_decode(const ppv_index_t *ix, int32_t *prefixes, int32_t prefi
     const dim3 grid((unsigned)B), block(nw * WAVE);
     hipStream_t hs = (hipStream_t)stream;
     RowState *rs = (RowState *)state;
-    if (dt == PPV_F32) {
-        const float *lg = (const float *)logits;
-        if (loop)
-            hipLaunchKernelGGL((decode_kernel<float, true>), grid, block, 0, hs, ix->view, prefixes, prefix_stride, lens,
-                               active, rs, lg, row_stride, step_stride, uniforms, n_steps, B, ids, logZ_valid, logx);
-        else
-            hipLaunchKernelGGL((decode_kernel<float, false>), grid, block, 0, hs, ix->view, prefixes, prefix_stride, lens,
-                               active, rs, lg, row_stride, step_stride, uniforms, 1, B, ids, logZ_valid, logx);
-    } else {
-        const uint16_t *lg = (const uint16_t *)logits;
-        if (loop)
-            hipLaunchKernelGGL((decode_kernel<uint16_t, true>), grid, block, 0, hs, ix->view, prefixes, prefix_stride,
-                               lens, active, rs, lg, row_stride, step_stride, uniforms, n_steps, B, ids, logZ_valid,
-                               logx);
-        else
-            hipLaunchKernelGGL((decode_kernel<uint16_t, false>), grid, block, 0, hs, ix->view, prefixes, prefix_stride,
-                               lens, active, rs, lg, row_stride, step_stride, uniforms, 1, B, ids, logZ_valid, logx);
-    }
+    const bool pipe = long_turns(ix->view.vocab, dt, nw);
+    if (!loop) n_steps = 1;
+    if (dt == PPV_F32)
+        launch_decode_kernel<float>(loop, pipe, grid, block, hs, ix->view, prefixes, prefix_stride, lens, active, rs,
+                                    (const float *)logits, row_stride, step_stride, uniforms, n_steps, B, ids, logZ_valid,
+                                    logx);
+    else
+        launch_decode_kernel<uint16_t>(loop, pipe, grid, block, hs, ix->view, prefixes, prefix_stride, lens, active, rs,
+                                       (const uint16_t *)logits, row_stride, step_stride, uniforms, n_steps, B, ids,
+                                       logZ_valid, logx);
     PPV_HIP_TRY(hipGetLastError());
     return PPV_OK;
 }
