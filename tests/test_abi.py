@@ -106,3 +106,14 @@ def test_index_load_rejects_files_that_are_not_an_index(lib, tmp_path):
     junk.write_bytes(header() + bytes(7))                     # sections shorter than the header promises
     assert lib.ppv_index_load(str(junk).encode(), C.byref(out)) == EINVAL
     assert out.value is None
+
+
+def test_binding_fails_loudly_without_the_library(monkeypatch):
+    """No fallback: with the shared library gone, the first call raises and names the build step."""
+    from paper_2504_09135_amd import binding
+    monkeypatch.setattr(binding, "_lib", None)
+    monkeypatch.setattr(binding, "LIB_PATH", "/nonexistent/libppv_hip.so")
+    with pytest.raises(FileNotFoundError, match="no fallback"):
+        binding.load_library()
+    with pytest.raises(FileNotFoundError):
+        binding.ppv_build_index(np.array([1], np.int32), np.array([0, 1], np.int64), 4)
