@@ -167,8 +167,8 @@ def main() -> int:
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--config", default="C3", choices=["C2", "C3", "C4", "C5"],
-                    help="C3 (default): the N=1M, V=32k decode loop the metric is quoted on; C2/C4/C5: one "
+    ap.add_argument("--config", default="C3", choices=["C1", "C2", "C3", "C4", "C5"],
+                    help="C3 (default): the N=1M, V=32k decode loop the metric is quoted on; C1/C2/C4/C5: one "
                          "ppv_next_token_mask + constrained_sample call on that config's batch")
     ap.add_argument("--n-seq", type=int, default=0, help="override |S| (debugging only; invalidates the metric)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -450,7 +450,8 @@ def single_call_bench(args, cfg, torch, ppv, W, dev):
                                "one ppv_next_token_mask + one constrained_sample per step, " + launch},
         "roofline": {"bound": "hbm", "kernel": f"sample_kernel<{cfg.dtype}>", "achieved": round(achieved, 1),
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
-                     "avg_launch_us": round(t_samp / args.steps * 1e6, 2), "bytes_per_launch": int(bytes_sample)},
+                     "avg_launch_us": round(t_samp / args.steps * 1e6, 2), "bytes_per_launch": int(bytes_sample),
+                     "device_copy_GBs": measured_copy_bandwidth(torch, dev)},
         "mask_kernel": {"avg_launch_us": round(t_mask / args.steps * 1e6, 2),
                         "GBs_written": round(B * V / 8.0 / (t_mask / args.steps) / 1e9, 1)},
         "index_build_s": round(t_build, 3), "index_device_MB": round(index.device_bytes / 1e6, 1),
@@ -469,7 +470,11 @@ def single_call_bench(args, cfg, torch, ppv, W, dev):
             reps += 1
             dt = time.perf_counter() - t0
         same = int((ref.ids == ids[:rows].cpu().numpy()).sum())
+        t0 = time.perf_counter()
+        trie.step(pb.prefixes[:rows], pb.lens[:rows], lf[:rows], unh[:rows], want_mask=True, threads=1)
+        dt1 = time.perf_counter() - t0
         out["cpu_baseline"] = {"value": round(rows * reps / dt, 1), "unit": "prefixes/s", "cores": threads, "kind": "oracle",
+                               "value_one_thread": round(rows / dt1, 1),
                                "sample": f"the first {rows} rows of the same batch, one mask + step each, {reps} times "
                                          f"({dt:.2f} s wall, about {dt * threads:.0f} core-seconds), OpenMP over rows; "
                                          f"trie build excluded; {same}/{rows} ids equal the GPU's"}
