@@ -6,11 +6,11 @@
 //            bit patterns, through an order-preserving 32-bit key per token.  M is small against
 //            |V|, so almost every token can be turned away with one comparison:
 //              A. one pass over the row takes the maximum of every 16-byte group of tokens and
-//                 histograms the groups' maxima by their leading 13 key bits; the bin that holds
+//                 histograms the groups' maxima by their leading 11 key bits; the bin that holds
 //                 the M-th largest group maximum gives a bound L that at least M tokens reach;
 //              B. a second pass (the row is in cache now) lists the tokens that are not below L,
 //                 in token order, in LDS: usually 1.1 to 1.5 M of them;
-//              C. a radix select over that short list (13 + 10 + 9 key bits for fp32, 13 + 3 for
+//              C. a radix select over that short list (11 + 10 + 11 key bits for fp32, 11 + 5 for
 //                 bf16) finds the key T of the M-th largest token; the list is then cut to the
 //                 tokens above T and the first few equal to T, in increasing token id, so the set
 //                 is unique.
@@ -31,10 +31,13 @@
 
 namespace {
 
-constexpr int TOPM_BINS = 8192;   // the first digit has 13 bits; the histogram shares its LDS with the mask row
+constexpr int TOPM_BITS = 11;             // leading key bits of the first digit
+constexpr int TOPM_BINS = 1 << TOPM_BITS;   // the histogram shares its LDS with the mask row
+constexpr int TOPM_SHIFT = 32 - TOPM_BITS;
 constexpr int TOPM_WAVES = 16;
-constexpr int TOPM_LIST = 4096;   // capacity of the candidate list (tokens not below the bound), split evenly over the wavefronts
-constexpr int TOPM_SLOTS = 16;    // list entries per thread at most: the list path needs at least 256 threads
+constexpr int TOPM_LIST_BIG = 4096, TOPM_LIST_SMALL = 1024;   // capacity of the candidate list (tokens not below the bound),
+                                                              // split evenly over the wavefronts; the small one serves M <= 128
+constexpr int TOPM_SLOTS = 16;    // list entries per thread at most: the list path needs at least LIST / 16 threads
 
 // Bit pattern -> key with the same order as the float value (-0 and +0 share a key).
 __device__ inline uint32_t order_key(uint32_t bits) {
@@ -188,7 +191,7 @@ __device__ inline void pick_digit(const uint32_t *hist, int bins, uint32_t need,
 
 // digit p of the radix select: key bits [shift, previous shift)
 template <typename T> __device__ inline int digit_shift(int pass) {
-    return pass == 0 ? 19 : (sizeof(T) == 4 ? (pass == 1 ? 9 : 0) : 16);
+    return pass == 0 ? TOPM_SHIFT : (sizeof(T) == 4 ? (pass == 1 ? TOPM_SHIFT - TOPM_BITS : 0) : 16);
 }
 // bf16: the low 16 bits of a key follow from its sign, so the upper half settles the whole key
 template <typename T> __device__ inline uint32_t full_key(uint32_t hi_part) {
@@ -197,7 +200,7 @@ template <typename T> __device__ inline uint32_t full_key(uint32_t hi_part) {
 
 struct TopmLds {
     uint32_t *hist;       // [TOPM_BINS]
-    uint32_t *list_tok;   // [TOPM_LIST]
+    uint32_t *list_tok;   // [LIST]
     uint32_t *sel;        // [PPV_TOPM_MAX]
     uint32_t *seg_a, *seg_b, *wave_tot;   // [TOPM_WAVES] each
     uint32_t *bc;         // [8]
@@ -294,9 +297,9 @@ __device__ inline void select_streaming(const T *__restrict__ row, int V, int c0
     __syncthreads();
 }
 
-// Bound, short list, radix select over the list.  Needs nthreads >= TOPM_LIST / TOPM_SLOTS.  Returns false
+// Bound, short list, radix select over the list.  Needs nthreads >= LIST / TOPM_SLOTS.  Returns false
 // (for every thread alike) when the list did not fit; sel is then untouched.
-template <typename T>
+template <typename T, int LIST>
 __device__ inline bool select_listed(const T *__restrict__ row, int V, int c0, int c1, int m, const TopmLds &s, int lane,
                                      int wave, int nthreads, uint4 (&r)[4]) {
     constexpr int EPL = KeyChunk<T>::EPL;
@@ -317,7 +320,7 @@ __device__ inline bool select_listed(const T *__restrict__ row, int V, int c0, i
 #pragma unroll
             for (int j = 1; j < EPL; j++) gm = fmaxf(gm, x[j]);
             if (c + u < c1 && n_inside<T>(V, c + u, lane) > 0)
-                atomicAdd(&s.hist[order_key(__float_as_uint(gm)) >> 19], 1u);
+                atomicAdd(&s.hist[order_key(__float_as_uint(gm)) >> TOPM_SHIFT], 1u);
         }
     }
     const bool kept = c1 - c0 <= 4;   // r still holds the whole share
@@ -325,10 +328,10 @@ __device__ inline bool select_listed(const T *__restrict__ row, int V, int c0, i
     pick_digit(s.hist, TOPM_BINS, (uint32_t)m, s.wave_tot, s.bc, nthreads);
     // At least m groups have their maximum in this bin or above, so at least m tokens are not below the bin's
     // lower edge.  With fewer than m groups in the row the bin is 0 and its edge is a NaN: nothing is below it.
-    const float L = __uint_as_float(key_to_bits(s.bc[4] << 19));
+    const float L = __uint_as_float(key_to_bits(s.bc[4] << TOPM_SHIFT));
     for (int i = tid; i < TOPM_BINS; i += nthreads) s.hist[i] = 0u;   // for C; the barrier after B orders it
     // ---- B. the tokens that are not below L, in token order, each wavefront into its own part of the list
-    const uint32_t R = (uint32_t)(TOPM_LIST / nw);
+    const uint32_t R = (uint32_t)(LIST / nw);
     const uint32_t base = (uint32_t)wave * R;
     uint32_t cnt = 0;   // wave-uniform
     for (int c = c0; c < c1; c += 4) {
@@ -367,7 +370,7 @@ __device__ inline bool select_listed(const T *__restrict__ row, int V, int c0, i
 
     // ---- C. the key T of the m-th largest token, from the list.  Thread t holds the entries t*S .. t*S+S-1 of
     // the list, which lie in its own wavefront's part (S = R / 64); their keys stay in registers.
-    const int S = TOPM_LIST / nthreads;
+    const int S = LIST / nthreads;
     const uint32_t mine = s.seg_a[wave];
     uint32_t kk[TOPM_SLOTS], tk[TOPM_SLOTS];
     uint32_t vm = 0;
@@ -383,7 +386,7 @@ __device__ inline bool select_listed(const T *__restrict__ row, int V, int c0, i
     // aside: they are dropped here), so the upper 16 key bits, counted from the edge, are small numbers: one
     // histogram over them settles the upper half of T.  A row whose tail reaches further than the histogram
     // is long (thousands of bf16 values above the m-th largest) goes to the whole-row select.
-    const uint32_t edge16 = s.bc[4] << 3;
+    const uint32_t edge16 = s.bc[4] << (16 - TOPM_BITS);
 #pragma unroll
     for (int q = 0; q < TOPM_SLOTS; q++) {   // (the histogram was cleared before B)
         kk[q] = order_key(kk[q]);
@@ -422,7 +425,7 @@ __device__ inline bool select_listed(const T *__restrict__ row, int V, int c0, i
         g += (((vm >> q) & 1u) && kk[q] > T_key) ? 1u : 0u;
         e += (((vm >> q) & 1u) && kk[q] == T_key) ? 1u : 0u;
     }
-    const uint32_t packed = g | (e << 16);   // both counts stay below 2^16 (the list has 4096 entries)
+    const uint32_t packed = g | (e << 16);   // both counts stay below 2^16 (the list has at most 4096 entries)
     const uint32_t before = block_incl_scan(packed, s.wave_tot, nw) - packed;
     uint32_t gt_before = before & 0xFFFFu, eq_before = before >> 16;
 #pragma unroll
@@ -444,7 +447,7 @@ __device__ inline bool select_listed(const T *__restrict__ row, int V, int c0, i
     return true;
 }
 
-template <typename T>
+template <typename T, int LIST>
 __global__ __launch_bounds__(TOPM_WAVES *WAVE) void topm_kernel(IndexView ix, const int32_t *__restrict__ prefixes,
                                                                 int32_t stride, const int32_t *__restrict__ lens,
                                                                 const T *__restrict__ logits, int64_t row_stride, int M,
@@ -454,7 +457,7 @@ __global__ __launch_bounds__(TOPM_WAVES *WAVE) void topm_kernel(IndexView ix, co
     constexpr int EPL = KeyChunk<T>::EPL;
     extern __shared__ __align__(16) uint32_t smem[];  // max(TOPM_BINS, n_words) words
     uint32_t *img = smem;                             // [n_words] the row of the mask, once the histogram is done with
-    __shared__ uint32_t list_tok[TOPM_LIST];
+    __shared__ uint32_t list_tok[LIST];
     __shared__ uint32_t sel[PPV_TOPM_MAX];
     __shared__ uint32_t seg_a[TOPM_WAVES], seg_b[TOPM_WAVES], wave_tot[TOPM_WAVES];
     __shared__ uint32_t bc[8];
@@ -471,7 +474,7 @@ __global__ __launch_bounds__(TOPM_WAVES *WAVE) void topm_kernel(IndexView ix, co
     const int cpw = (nc + nw - 1) / nw;
     const int c0 = wave * cpw, c1 = (c0 + cpw < nc) ? c0 + cpw : nc;
 
-    const bool listed = !force_streaming && nthreads * TOPM_SLOTS >= TOPM_LIST;
+    const bool listed = !force_streaming && nthreads * TOPM_SLOTS >= LIST;
     uint4 r[4];
     if (listed) load_chunks<T>(row, V, c0, c1, lane, r);   // in flight while the prefix is located
     if (wave == 0) {   // the part every candidate row shares: locate the prefix once
@@ -488,7 +491,7 @@ __global__ __launch_bounds__(TOPM_WAVES *WAVE) void topm_kernel(IndexView ix, co
     }
     // ---- select
     bool done = false;
-    if (listed) done = select_listed<T>(row, V, c0, c1, m, lds, lane, wave, nthreads, r);
+    if (listed) done = select_listed<T, LIST>(row, V, c0, c1, m, lds, lane, wave, nthreads, r);
     if (!done) select_streaming<T>(row, V, c0, c1, m, lds, lane, wave, nthreads);
     for (int i = tid; i < n_words; i += nthreads) img[i] = 0u;   // the histogram's LDS becomes the mask row
     __syncthreads();
@@ -535,7 +538,7 @@ __global__ __launch_bounds__(TOPM_WAVES *WAVE) void topm_kernel(IndexView ix, co
 int topm_waves(int V, ppv_dtype dt, int B) {
     const int per = (dt == PPV_F32 ? 4 : 8) * WAVE;
     const int nc = (V + per - 1) / per;
-    int cap = B <= 512 ? TOPM_WAVES : (B <= 1024 ? 8 : 4);
+    int cap = B <= 512 ? 8 : 4;   // measured at V = 32k: B=256: 19.5 us with 8 or 16, 24 with 4; B=1024: 37 / 42 / 67 us with 4 / 8 / 16
     if (const char *e = getenv("PPV_TOPM_WAVES")) {  // tuning aid
         const int v = atoi(e);
         if (v >= 1 && v <= TOPM_WAVES) cap = v;
@@ -564,14 +567,20 @@ extern "C" ppv_status ppv_topm_mask(const ppv_index_t *ix, const int32_t *prefix
     const char *fs = getenv("PPV_TOPM_STREAMING");
     const int force_streaming = (fs && fs[0] == '1') ? 1 : 0;
     const size_t lds = (size_t)(ix->view.n_words > TOPM_BINS ? ix->view.n_words : TOPM_BINS) * sizeof(uint32_t);
-    if (dt == PPV_F32)
-        hipLaunchKernelGGL(topm_kernel<float>, dim3((unsigned)B), dim3(threads), lds, (hipStream_t)stream, ix->view,
-                           prefixes, prefix_stride, lens, (const float *)logits, row_stride, M, force_streaming, top_ids, mask_V,
-                           mask);
-    else
-        hipLaunchKernelGGL(topm_kernel<uint16_t>, dim3((unsigned)B), dim3(threads), lds, (hipStream_t)stream, ix->view,
-                           prefixes, prefix_stride, lens, (const uint16_t *)logits, row_stride, M, force_streaming, top_ids,
-                           mask_V, mask);
+    const dim3 grid((unsigned)B), block(threads);
+    hipStream_t hs = (hipStream_t)stream;
+#define PPV_LAUNCH_TOPM(T, LIST)                                                                                      \
+    hipLaunchKernelGGL((topm_kernel<T, LIST>), grid, block, lds, hs, ix->view, prefixes, prefix_stride, lens,          \
+                       (const T *)logits, row_stride, M, force_streaming, top_ids, mask_V, mask)
+    const bool small_list = M <= 128;   // a few hundred tokens reach the bound: a quarter of the LDS, more rows per compute unit
+    if (dt == PPV_F32) {
+        if (small_list) PPV_LAUNCH_TOPM(float, TOPM_LIST_SMALL);
+        else PPV_LAUNCH_TOPM(float, TOPM_LIST_BIG);
+    } else {
+        if (small_list) PPV_LAUNCH_TOPM(uint16_t, TOPM_LIST_SMALL);
+        else PPV_LAUNCH_TOPM(uint16_t, TOPM_LIST_BIG);
+    }
+#undef PPV_LAUNCH_TOPM
     PPV_HIP_TRY(hipGetLastError());
     return PPV_OK;
 }
