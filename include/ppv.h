@@ -21,6 +21,9 @@
  *     are ordered lexicographically, left to right, a proper prefix before its extensions
  *     (Section 3.2 "Array Preparation").  Query tokens are compared as unsigned 32-bit values:
  *     a token outside [0, V) matches nothing and sorts after every real token.
+ *   - Logits are expected to be finite or -inf.  A row with NaN or +inf logits has no meaningful sums; it
+ *     ends in a defined state (a token of its valid set, or id -1 and the row retires) and does not affect
+ *     other rows, but its id, logZ_valid and logx are unspecified.
  *   - Mask layout: row b is ceil(V/32) uint32 words; token v is bit (v & 31), least significant
  *     first, of word (v >> 5); bits at positions >= V are 0.
  */

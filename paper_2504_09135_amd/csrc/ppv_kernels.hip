@@ -603,10 +603,12 @@ __device__ inline RowOut row_sample(const T *__restrict__ row, int V, const RawT
                     kt = klast;
                     target = INFINITY;
                 }
-                RawTile lt;
-                load_tile<T>(row, V, kt, lane, lt);
-                const uint32_t word = tile_mask_word<T>(image, kt, lane, V);
-                id = locate_in_tile<T>(lt, word, kt, lane, sh.tile_ref[kt], target);
+                if (kt >= 0) {   // (no tile qualifies only when NaNs have poisoned the sums: then nothing is sampled)
+                    RawTile lt;
+                    load_tile<T>(row, V, kt, lane, lt);
+                    const uint32_t word = tile_mask_word<T>(image, kt, lane, V);
+                    id = locate_in_tile<T>(lt, word, kt, lane, sh.tile_ref[kt], target);
+                }
             }
         } else if (mode == VALID_LIST) {
             float Mv = -INFINITY;
@@ -630,17 +632,21 @@ __device__ inline RowOut row_sample(const T *__restrict__ row, int V, const RawT
                     s = __ffsll((long long)cross) - 1;
                     target = (tau - lane_value(incl - w, s)) / lane_value(sc, s);
                 } else {
-                    s = 63 - __clzll((long long)have);
+                    s = have ? 63 - __clzll((long long)have) : -1;
                     target = INFINITY;
                 }
+                // (no slice or no token qualifies only when NaNs have poisoned the sums: then nothing is sampled,
+                // and above all no position outside the list is ever formed)
                 const int i = s * WAVE + lane;
-                const float e = (i < n_list) ? sh.list_e[i] : 0.f;
+                const float e = (s >= 0 && i < n_list) ? sh.list_e[i] : 0.f;
                 const double ic = wave_incl_scan((double)e);
                 const uint64_t c2 = __ballot(e > 0.f && ic > target);
                 const uint64_t h2 = __ballot(e > 0.f);
-                const int l = c2 ? __ffsll((long long)c2) - 1 : 63 - __clzll((long long)h2);
-                pos = s * WAVE + l;
-                id = (int)(sh.list_tok[pos] & PPV_NODE_TOKEN);
+                if (c2 | h2) {
+                    const int l = c2 ? __ffsll((long long)c2) - 1 : 63 - __clzll((long long)h2);
+                    pos = s * WAVE + l;
+                    id = (int)(sh.list_tok[pos] & PPV_NODE_TOKEN);
+                }
             }
         }
         if (lane == 0) {

@@ -516,3 +516,55 @@ def test_largest_vocabulary_and_a_large_batch(dtype):
     Pb = np.tile(pb.prefixes, (reps, 1))[:70_000]
     Lb = np.tile(pb.lens, reps)[:70_000]
     assert_query_parity(index1, trie1, Pb, Lb, threads=8)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_nan_and_infinite_logits_do_not_derail_a_row(dtype):
+    """NaN or +inf logits make a row's sums meaningless; what is asked of the library is that such a row ends
+    in a defined state (a token of the valid set, or -1 and the row retires) and that its neighbours are not
+    touched.  Regression test: a poisoned row used to be able to form a list position outside its list."""
+    cfg, S, trie, index = setup_case("C3s")
+    V, B = cfg.vocab, 8
+    rng = np.random.default_rng(3)
+    lg = rng.normal(0, 2, size=(B, V)).astype(np.float32)
+    lg[0, :] = np.nan
+    lg[1, ::7] = np.nan
+    lg[2, ::5] = np.inf
+    lg[3, :] = np.inf
+    lg[4, 100] = -np.nan
+    clean = [5, 6, 7]
+    if dtype == "bf16":
+        t = torch.from_numpy(lg).to(DEV).to(torch.bfloat16)
+    else:
+        t = torch.from_numpy(lg).to(DEV)
+    un = torch.full((B,), 0.37, dtype=torch.float32, device=DEV)
+    outs = []
+    for rows in (list(range(B)), clean):
+        n = len(rows)
+        P = torch.full((n, index.l_max), W.PAD_TOKEN, dtype=torch.int32, device=DEV)
+        L = torch.zeros(n, dtype=torch.int32, device=DEV)
+        A = torch.zeros(n, dtype=torch.uint8, device=DEV)
+        st = torch.zeros((n, ppv.PPV_STATE_WORDS), dtype=torch.int32, device=DEV)
+        lx = torch.zeros(n, dtype=torch.float32, device=DEV)
+        ids = torch.full((4, n), -5, dtype=torch.int32, device=DEV)
+        lz = torch.zeros((4, n), dtype=torch.float32, device=DEV)
+        tl = t[rows].contiguous()
+        ppv.ppv_decode_begin(index, P, L, st, A, lx)
+        for s in range(4):                                    # step 0 at the root (image), then list steps
+            ppv.ppv_decode_step(index, P, L, A, tl, un[:n], ids[s], lz[s], lx, state=st)
+        mask = torch.zeros((n, index.n_words), dtype=torch.int32, device=DEV)
+        ppv.ppv_next_token_mask(index, P, L, mask)
+        sid = torch.full((n,), -5, dtype=torch.int32, device=DEV)
+        slz = torch.zeros(n, dtype=torch.float32, device=DEV)
+        ppv.constrained_sample(tl, mask, un[:n], sid, slz)
+        top = torch.full((n, 50), -9, dtype=torch.int32, device=DEV)
+        ppv.ppv_topm_mask(index, P, L, tl, 50, mask, top)
+        torch.cuda.synchronize()
+        outs.append((P.cpu().numpy(), L.cpu().numpy(), ids.cpu().numpy(), sid.cpu().numpy(), top.cpu().numpy()))
+    P, L, ids, sid, top = outs[0]
+    assert ((ids >= -5) & (ids < V)).all() and ((sid >= -1) & (sid < V)).all() and ((top >= 0) & (top < V)).all()
+    q = trie.query(P, L, want_mask=False)
+    assert (q.lo < q.hi).all()                                # every row is still a prefix of some member
+    Pc, Lc, idc, sidc, topc = outs[1]
+    assert np.array_equal(P[clean], Pc) and np.array_equal(L[clean], Lc) and np.array_equal(ids[:, clean], idc)
+    assert np.array_equal(sid[clean], sidc) and np.array_equal(top[clean], topc)
