@@ -568,3 +568,38 @@ def test_nan_and_infinite_logits_do_not_derail_a_row(dtype):
     Pc, Lc, idc, sidc, topc = outs[1]
     assert np.array_equal(P[clean], Pc) and np.array_equal(L[clean], Lc) and np.array_equal(ids[:, clean], idc)
     assert np.array_equal(sid[clean], sidc) and np.array_equal(top[clean], topc)
+
+
+def test_degenerate_sets():
+    """One member; one token vocabulary; nothing but duplicates; one long chain; a set that is all single tokens."""
+    cases = [
+        ([[0]], 1, [[], [0], [0, 0], [5]]),
+        ([[3, 1, 2]] * 500, 8, [[], [3], [3, 1], [3, 1, 2], [3, 1, 2, 0], [1]]),
+        ([list(range(40))], 64, [[], list(range(39)), list(range(40)), list(range(1, 40))]),
+        ([[v] for v in range(200)], 200, [[], [7], [199], [7, 7]]),
+        ([[1], [1, 1], [1, 1, 1], [1, 1, 1, 1]], 2, [[], [1], [1, 1], [1, 1, 1, 1], [1, 1, 1, 1, 1], [0]]),
+    ]
+    for seqs, V, queries in cases:
+        S = W.constraint_set_from_lists(seqs, V)
+        trie = oracle.Trie(S.tokens, S.offsets, V)
+        index = ppv.ppv_build_index(S.tokens, S.offsets, V)
+        assert index.n_distinct == trie.n_members and index.n_prefixes == trie.n_nodes - 1
+        stride = max(1, max(map(len, queries)))
+        P = np.full((len(queries), stride), W.PAD_TOKEN, np.int32)
+        L = np.array([len(q) for q in queries], np.int32)
+        for i, q in enumerate(queries):
+            P[i, :len(q)] = q
+        dmask, ref_q = assert_query_parity(index, trie, P, L)
+        # a sampling step on top (fp32 rows must be 16-byte aligned: pad the row stride)
+        Vp = (V + 3) // 4 * 4
+        rng = np.random.default_rng(V)
+        lg = np.zeros((len(queries), Vp), np.float32)
+        lg[:, :V] = rng.normal(0, 1, size=(len(queries), V))
+        un = rng.random(len(queries)).astype(np.float32)
+        ref = trie.step(P, L, lg[:, :V], un)
+        ids = torch.full((len(queries),), -7, dtype=torch.int32, device=DEV)
+        lzv = torch.zeros(len(queries), dtype=torch.float32, device=DEV)
+        ppv.constrained_sample(to_dev(lg)[:, :V], dmask, to_dev(un), ids, lzv)
+        torch.cuda.synchronize()
+        check_sample_rows("f32", ref, lambda b: ref.mask[b], un, ids.cpu().numpy(), lzv.cpu().numpy())
+        index.free()
