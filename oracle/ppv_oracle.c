@@ -25,6 +25,11 @@
  *   - Algorithm 2 as printed, with M candidates instead of the whole vocabulary (second half of
  *     this file): sorted array, top M, one binary search per candidate row, prefix check.
  *
+ * Every function here is pinned by tests that do not go through this file's own arithmetic (brute force from
+ * the definitions, closed forms, library routines on special cases, the paper's worked numbers).  One worked
+ * example of the paper could not be used -- parity unpinned: the PPV illustration (input [0,31,555] with
+ * candidates {35,145,111}), whose array and resulting mask exist only in a figure.
+ *
  * Everything floating point is done in double, sequentially in increasing token id.
  * Query tokens are compared as unsigned 32-bit integers, so a token outside [0,V) simply
  * matches nothing and sorts after every real token.
