@@ -603,3 +603,39 @@ def test_degenerate_sets():
         torch.cuda.synchronize()
         check_sample_rows("f32", ref, lambda b: ref.mask[b], un, ids.cpu().numpy(), lzv.cpu().numpy())
         index.free()
+
+
+def test_calls_on_two_streams_at_once():
+    """An index is immutable after it is built: mask + sample pipelines on two streams, interleaved launch by
+    launch over the same index, give what each gives alone."""
+    cfg, S, trie, index = setup_case("C3s")
+    pbs = [W.make_prefix_batch(cfg, S, index=i) for i in (11, 12)]
+    logits = [logits_to_dev(cfg, W.make_logits(cfg, step=20 + i)) for i in range(2)]
+    uns = [to_dev(W.make_uniforms(cfg, step=20 + i)) for i in range(2)]
+    Ps = [to_dev(pb.prefixes) for pb in pbs]
+    Ls = [to_dev(pb.lens) for pb in pbs]
+    B = pbs[0].prefixes.shape[0]
+
+    def buffers():
+        return (torch.zeros((B, index.n_words), dtype=torch.int32, device=DEV),
+                torch.full((B,), -7, dtype=torch.int32, device=DEV), torch.zeros(B, dtype=torch.float32, device=DEV))
+    alone = []
+    for i in range(2):
+        m, ids, lz = buffers()
+        ppv.ppv_next_token_mask(index, Ps[i], Ls[i], m)
+        ppv.constrained_sample(logits[i], m, uns[i], ids, lz)
+        torch.cuda.synchronize()
+        alone.append((m.cpu().numpy(), ids.cpu().numpy(), lz.cpu().numpy().view(np.int32)))
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    bufs = [buffers(), buffers()]
+    torch.cuda.synchronize()
+    for rep in range(20):
+        for i in range(2):
+            ppv.ppv_next_token_mask(index, Ps[i], Ls[i], bufs[i][0], stream=streams[i])
+        for i in range(2):
+            ppv.constrained_sample(logits[i], bufs[i][0], uns[i], bufs[i][1], bufs[i][2], stream=streams[i])
+    torch.cuda.synchronize()
+    for i in range(2):
+        m, ids, lz = bufs[i]
+        assert np.array_equal(m.cpu().numpy(), alone[i][0]) and np.array_equal(ids.cpu().numpy(), alone[i][1])
+        assert np.array_equal(lz.cpu().numpy().view(np.int32), alone[i][2])
