@@ -3,7 +3,6 @@
 two-token construction of Theorem 2.1, whose exact output law can be enumerated."""
 import itertools
 import math
-import os
 
 import numpy as np
 import pytest
