@@ -722,6 +722,47 @@ __global__ __launch_bounds__(SMALL ? SMALL_TILES * WAVE : MAX_WAVES * WAVE) void
     }
 }
 
+// Rows of a single tile (V <= 1,024 fp32 / 2,048 bf16 tokens): one wavefront per row, four rows per workgroup,
+// everything in registers -- no LDS, no barrier.  The valid set is applied as bits in the tile (as on the image
+// path of the general kernel, with the same rescue when the valid tokens lie far below the row maximum).
+constexpr int ONE_TILE_ROWS = 4;
+template <typename T>
+__global__ __launch_bounds__(ONE_TILE_ROWS *WAVE) void sample_one_tile_kernel(const T *__restrict__ logits, int64_t row_stride,
+                                                                              const uint32_t *__restrict__ mask,
+                                                                              const float *__restrict__ uniforms, int B,
+                                                                              int V, int n_words, int32_t *__restrict__ ids,
+                                                                              float *__restrict__ logZ_valid,
+                                                                              float *__restrict__ logZ_all) {
+    const int lane = threadIdx.x & (WAVE - 1);
+    const int b = blockIdx.x * ONE_TILE_ROWS + threadIdx.x / WAVE;
+    if (b >= B) return;   // uniform per wavefront
+    const T *row = logits + (size_t)b * (size_t)row_stride;
+    RawTile rt;
+    load_tile<T>(row, V, 0, lane, rt);
+    const uint32_t word = tile_mask_word<T>(mask + (size_t)b * (size_t)n_words, 0, lane, V);
+    const float u = uniforms[b];
+    float m, zall, zval;
+    tile_stats<T, true>(rt, word, lane, m, zall, zval);
+    const float l2za = fast_log2(zall);
+    int id = -1;
+    float lzv = -INFINITY, ref = m;
+    if (__ballot(word != 0u)) {
+        if (zval < 3.814697265625e-06f) {   // below 2^-18 of the largest term: sum again, relative to the valid maximum
+            ref = tile_valid_max<T>(rt, word, lane);
+            zval = ref != -INFINITY ? tile_valid_sum<T>(rt, word, lane, ref) : 0.f;
+        }
+        if (zval > 0.f) {
+            lzv = (ref - m) + LN2F * (fast_log2(zval) - l2za);
+            id = locate_in_tile<T>(rt, word, 0, lane, ref, (double)u * (double)zval);
+        }
+    }
+    if (lane == 0) {
+        ids[b] = id;
+        logZ_valid[b] = lzv;
+        if (logZ_all) logZ_all[b] = m + LN2F * l2za;
+    }
+}
+
 // ------------------------------------------------------------------------------------------
 // ppv_decode_begin: one wavefront per row walks the row's current prefix and leaves the cursor.
 __global__ __launch_bounds__(MASK_THREADS) void decode_begin_kernel(IndexView ix, const int32_t *__restrict__ prefixes,
@@ -997,6 +1038,17 @@ extern "C" ppv_status constrained_sample(const void *logits, ppv_dtype dt, int64
     const bool pipe = long_turns(V, dt, threads / WAVE);
     const dim3 grid((unsigned)B), block(threads);
     hipStream_t hs = (hipStream_t)stream;
+    if (V <= tile) {   // the whole row is one tile
+        const dim3 g1((unsigned)((B + ONE_TILE_ROWS - 1) / ONE_TILE_ROWS)), b1(ONE_TILE_ROWS * WAVE);
+        if (dt == PPV_F32)
+            hipLaunchKernelGGL(sample_one_tile_kernel<float>, g1, b1, 0, hs, (const float *)logits, row_stride, mask, uniforms,
+                               B, V, n_words, ids, logZ_valid, logZ_all);
+        else
+            hipLaunchKernelGGL(sample_one_tile_kernel<uint16_t>, g1, b1, 0, hs, (const uint16_t *)logits, row_stride, mask,
+                               uniforms, B, V, n_words, ids, logZ_valid, logZ_all);
+        PPV_HIP_TRY(hipGetLastError());
+        return PPV_OK;
+    }
     if (dt == PPV_F32)
         launch_sample<float>(small, pipe, grid, block, hs, (const float *)logits, row_stride, mask, uniforms, V, n_words,
                              list_max, ids, logZ_valid, logZ_all);
