@@ -639,3 +639,54 @@ def test_calls_on_two_streams_at_once():
         m, ids, lz = bufs[i]
         assert np.array_equal(m.cpu().numpy(), alone[i][0]) and np.array_equal(ids.cpu().numpy(), alone[i][1])
         assert np.array_equal(lz.cpu().numpy().view(np.int32), alone[i][2])
+
+
+def test_many_small_random_sets():
+    """A battery of small random sets of varied shape (vocabulary 1..300, lengths 1..12, heavy duplication,
+    nesting, skewed tokens): index sizes, masks, ranges, membership, a sampling step and a top-M call each,
+    all against the oracle.  Every set has its own index: this is mostly a test of the build."""
+    rng = np.random.default_rng(2025)
+    for trial in range(60):
+        V = int(rng.choice([1, 2, 3, 7, 33, 64, 65, 300]))
+        n = int(rng.choice([1, 2, 17, 400, 3000]))
+        lmax = int(rng.integers(1, 13))
+        skew = rng.random() < 0.5
+        seqs = []
+        for _ in range(n):
+            ln = int(rng.integers(1, lmax + 1))
+            t = (rng.integers(0, V, size=ln) if not skew else np.minimum(rng.geometric(0.4, size=ln) - 1, V - 1))
+            seqs.append([int(x) for x in t])
+        S = W.constraint_set_from_lists(seqs, V)
+        trie = oracle.Trie(S.tokens, S.offsets, V)
+        index = ppv.ppv_build_index(S.tokens, S.offsets, V)
+        assert (index.n_distinct, index.l_max, index.n_prefixes) == (trie.n_members, trie.l_max, trie.n_nodes - 1), trial
+        q = [[]] + [s[:int(rng.integers(0, len(s) + 1))] for s in seqs[:40]]
+        q += [s + [int(rng.integers(0, V))] for s in seqs[:10]] + [[int(rng.integers(0, V + 2)) for _ in range(3)] for _ in range(5)]
+        stride = max(1, max(map(len, q)))
+        P = np.full((len(q), stride), W.PAD_TOKEN, np.int32)
+        L = np.array([len(x) for x in q], np.int32)
+        for i, x in enumerate(q):
+            P[i, :len(x)] = x
+        dmask, ref_q = assert_query_parity(index, trie, P, L)
+        Vp = (V + 3) // 4 * 4
+        lg = np.zeros((len(q), Vp), np.float32)
+        lg[:, :V] = rng.normal(0, 2, size=(len(q), V))
+        un = rng.random(len(q)).astype(np.float32)
+        ref = trie.step(P, L, lg[:, :V], un)
+        ld = to_dev(lg)[:, :V]
+        ids = torch.full((len(q),), -7, dtype=torch.int32, device=DEV)
+        lzv = torch.zeros(len(q), dtype=torch.float32, device=DEV)
+        ppv.constrained_sample(ld, dmask, to_dev(un), ids, lzv)
+        M = int(rng.choice([1, 5, 50]))
+        tmask = torch.zeros_like(dmask)
+        top = torch.zeros((len(q), M), dtype=torch.int32, device=DEV)
+        ppv.ppv_topm_mask(index, to_dev(P), to_dev(L), ld, M, tmask, top)
+        torch.cuda.synchronize()
+        check_sample_rows("f32", ref, lambda b: ref.mask[b], un, ids.cpu().numpy(), lzv.cpu().numpy())
+        m = min(M, V)
+        order = np.argsort(-lg[:, :V].astype(np.float64), axis=1, kind="stable")[:, :m]
+        want = np.zeros((len(q), V), np.uint8)
+        np.put_along_axis(want, order, np.take_along_axis(ref_q.mask, order, axis=1), axis=1)
+        assert np.array_equal(unpack_mask(tmask.cpu().numpy().view(np.uint32), V), want), trial
+        assert np.array_equal(np.sort(order, axis=1), top.cpu().numpy()[:, :m]), trial
+        index.free()
