@@ -147,12 +147,29 @@ __device__ inline Walk walk_prefix(const IndexView &ix, const int32_t *__restric
         if (hits) {
             const int D = 63 - __clzll((long long)hits);   // deepest level with a hit: prefix length D + 1
             const uint32_t g = lane_value(cand, D);
-            if (g >= ix.depth_base[D + 1] && g < ix.depth_base[D + 2]) {
-                const NodeEnt e0 = ix.ent[g], e1 = ix.ent[g + 1];
-                const uint32_t a = ix.node_xpos[g];   // a node of depth D+1: its first member has D+1 tokens or more
+            // everything that depends on g alone goes out together (the table holds valid nodes only), the rank
+            // range included; the member's tokens wait for the depth check, which is what says they are there
+            const uint32_t d0 = ix.depth_base[D + 1], d1 = ix.depth_base[D + 2];
+            const NodeEnt e0 = ix.ent[g], e1 = ix.ent[g + 1];
+            const uint32_t a = ix.node_xpos[g];
+            const uint32_t g_lo = ix.node_lo[g], g_hi = ix.node_hi[g];
+            if (g >= d0 && g < d1) {   // a node of depth D+1: its first member has D+1 tokens or more
                 const bool same = lane > D || ix.x_tok[(size_t)a + lane] == mine;
-                if (__ballot(!same) == 0ull)
+                if (__ballot(!same) == 0ull) {
+                    if (D + 1 == t) {   // the whole prefix: nothing left to descend
+                        Walk w;
+                        w.node = g;
+                        w.cb = e0.child;
+                        w.ce = e1.child;
+                        w.tok = e0.tok;
+                        w.lo = g_lo;
+                        w.hi = g_hi;
+                        w.found = true;
+                        w.member = (e0.tok & PPV_NODE_TERMINAL) != 0u;
+                        return w;
+                    }
                     return walk_from(ix, prefix, t, lane, mine, D + 1, g, e0.tok, e0.child, e1.child);
+                }
             }
         }
     }
