@@ -505,8 +505,8 @@ __global__ __launch_bounds__(BT) void insert_nodes(const uint32_t *__restrict__ 
         atomicOr(err, 4);
         return;
     }
-    uint64_t h = PREFIX_HASH_SEED;
-    for (int i = 0; i < lo; i++) h = prefix_hash_step(h, (uint32_t)x_tok[a + i]);
+    PrefixHash h = prefix_hash_token((uint32_t)x_tok[a]);   // a node is at least one token deep
+    for (int i = 1; i < lo; i++) h = prefix_hash_join(h, prefix_hash_token((uint32_t)x_tok[a + i]));
     uint32_t slot, fp;
     prefix_hash_finish(h, size, fp_mask, &slot, &fp);
     const unsigned long long entry = ((unsigned long long)fp << 32) | g;

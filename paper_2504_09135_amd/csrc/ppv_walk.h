@@ -98,15 +98,47 @@ __device__ inline Walk walk_from(const IndexView &ix, const int32_t *__restrict_
     return w;
 }
 
-// Hash of a token string, one token at a time; the same function fills the table and probes it.
-constexpr uint64_t PREFIX_HASH_SEED = 0x243F6A8885A308D3ull, PREFIX_HASH_MUL = 0x9E3779B97F4A7C15ull;
-__device__ inline uint64_t prefix_hash_step(uint64_t h, uint32_t tok) { return (h ^ tok) * PREFIX_HASH_MUL; }
-__device__ inline void prefix_hash_finish(uint64_t h, uint32_t size, uint32_t fp_mask, uint32_t *slot, uint32_t *fp) {
+// Hash of a token string: two polynomials over the tokens, H_d = sum_{i<=d} (tok_i + 1) * K^(d-i) mod 2^32 with
+// two multipliers K, mixed into 64 bits at the end.  A polynomial, because its evaluation is associative:
+// filling the table takes the tokens one at a time (Horner), while a query needs the hashes of ALL its
+// prefixes at once, lane d that of tokens 0..d, and gets them from one prefix scan over the wavefront
+// (seven DPP steps) instead of a loop as long as the prefix.
+constexpr uint32_t PREFIX_HASH_K1 = 0x9E3779B1u, PREFIX_HASH_K2 = 0x85EBCA77u;   // odd
+struct PrefixHash {
+    uint32_t h1, p1, h2, p2;   // the two polynomial values and K^length for each
+};
+__device__ inline PrefixHash prefix_hash_token(uint32_t tok) { return {tok + 1u, PREFIX_HASH_K1, tok + 1u, PREFIX_HASH_K2}; }
+// the hash of string a followed by string b
+__device__ inline PrefixHash prefix_hash_join(const PrefixHash &a, const PrefixHash &b) {
+    return {a.h1 * b.p1 + b.h1, a.p1 * b.p1, a.h2 * b.p2 + b.h2, a.p2 * b.p2};
+}
+__device__ inline void prefix_hash_finish(const PrefixHash &x, uint32_t size, uint32_t fp_mask, uint32_t *slot,
+                                          uint32_t *fp) {
+    uint64_t h = ((uint64_t)x.h1 << 32) | x.h2;
     h ^= h >> 32;
     h *= 0xD6E8FEB86659FD93ull;
     h ^= h >> 29;
     *slot = __umulhi((uint32_t)(h >> 32), size);
     *fp = ((uint32_t)h & fp_mask) | 1u;
+}
+// lane l receives the value of the lane CTRL points to, or the empty string's hash where there is none
+template <int CTRL, int ROW_MASK = 0xF, int BANK_MASK = 0xF> __device__ inline PrefixHash prefix_hash_dpp(const PrefixHash &x) {
+    return {(uint32_t)__builtin_amdgcn_update_dpp(0, (int)x.h1, CTRL, ROW_MASK, BANK_MASK, false),
+            (uint32_t)__builtin_amdgcn_update_dpp(1, (int)x.p1, CTRL, ROW_MASK, BANK_MASK, false),
+            (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x.h2, CTRL, ROW_MASK, BANK_MASK, false),
+            (uint32_t)__builtin_amdgcn_update_dpp(1, (int)x.p2, CTRL, ROW_MASK, BANK_MASK, false)};
+}
+// lane l: the hash of the tokens of lanes 0..l (x = the lane's own token as a one-token string)
+__device__ inline PrefixHash prefix_hash_scan(const PrefixHash &x) {
+    PrefixHash t = x;
+    t = prefix_hash_join(prefix_hash_dpp<DPP_ROW_SHR1>(x), t);
+    t = prefix_hash_join(prefix_hash_dpp<DPP_ROW_SHR2>(x), t);
+    t = prefix_hash_join(prefix_hash_dpp<DPP_ROW_SHR3>(x), t);              // up to 4 consecutive lanes of the row
+    t = prefix_hash_join(prefix_hash_dpp<DPP_ROW_SHR4, 0xF, 0xE>(t), t);
+    t = prefix_hash_join(prefix_hash_dpp<DPP_ROW_SHR8, 0xF, 0xC>(t), t);    // prefix inside each row of 16
+    t = prefix_hash_join(prefix_hash_dpp<DPP_ROW_BCAST15, 0xA>(t), t);
+    t = prefix_hash_join(prefix_hash_dpp<DPP_ROW_BCAST31, 0xC>(t), t);
+    return t;
 }
 
 // Locates the prefix.  With a look-up table every length of the prefix is probed at once (lane d hashes
@@ -124,13 +156,9 @@ __device__ inline Walk walk_prefix(const IndexView &ix, const int32_t *__restric
     int tl = t < WAVE ? t : WAVE;
     tl = tl < ix.l_max ? tl : ix.l_max;   // nothing longer than the longest member is in the index
     if (ix.lookup_size != 0u && tl > 0) {
-        uint64_t h = PREFIX_HASH_SEED;
-        for (int i = 0; i < tl; i++) {
-            const uint64_t hn = prefix_hash_step(h, (uint32_t)lane_value(mine, i));
-            h = (i <= lane) ? hn : h;
-        }
         uint32_t slot, fp;
-        prefix_hash_finish(h, ix.lookup_size, ix.lookup_fp_mask, &slot, &fp);
+        prefix_hash_finish(prefix_hash_scan(prefix_hash_token((uint32_t)mine)), ix.lookup_size, ix.lookup_fp_mask, &slot,
+                           &fp);
         uint32_t cand = PPV_NO_SLOT;
         if (lane < tl) {
             for (uint32_t n = 0; n < ix.lookup_size; n++) {   // ends at the first empty slot (the table is half empty)
