@@ -203,6 +203,23 @@ def test_topm_full_size_C3():
         assert_topm_parity(index, X, pb.prefixes, lens, lf, ld, M, threads=16)
 
 
+def test_topm_full_size_C5():
+    """|S| = 5M, V = 256k, B = 1,024 (4 wavefronts per row, 125 chunks each), M = 50 and 1000: every row."""
+    cfg = W.CONFIGS["C5"]
+    say("C5: S, sorted array, device index")
+    S = W.make_constraint_set(cfg)
+    X = oracle.SortedArray(S.tokens, S.offsets, cfg.vocab)
+    index = ppv.ppv_build_index(S.tokens, S.offsets, cfg.vocab)
+    assert X.n_rows == index.n_distinct
+    pb = W.make_prefix_batch(cfg, S)
+    logits = W.make_logits(cfg)
+    lf = W.logits_as_f32(cfg, logits)
+    ld = logits_to_dev(cfg, logits)
+    for M in (50, 1000):
+        say(f"C5: M = {M}")
+        assert_topm_parity(index, X, pb.prefixes, pb.lens, lf, ld, M, threads=16)
+
+
 def test_topm_bad_arguments():
     cfg, S, trie, index = setup_case("C1")
     B = 2
