@@ -456,6 +456,8 @@ def single_call_bench(args, cfg, torch, ppv, W, dev):
                         "GBs_written": round(B * V / 8.0 / (t_mask / args.steps) / 1e9, 1)},
         "index_build_s": round(t_build, 3), "index_device_MB": round(index.device_bytes / 1e6, 1),
     }
+    if not args.no_sweep:
+        out["topm_sweep"] = topm_sweep(cfg, S, index, bufs[0], torch, ppv, W, dev, reps=10)
     if not args.no_cpu_baseline:
         import oracle
         threads = oracle.max_threads()

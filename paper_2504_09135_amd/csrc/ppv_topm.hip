@@ -36,7 +36,7 @@ constexpr int TOPM_BINS = 1 << TOPM_BITS;   // the histogram shares its LDS with
 constexpr int TOPM_SHIFT = 32 - TOPM_BITS;
 constexpr int TOPM_WAVES = 16;
 constexpr int TOPM_LIST_BIG = 4096, TOPM_LIST_SMALL = 1024;   // capacity of the candidate list (tokens not below the bound),
-                                                              // split evenly over the wavefronts; the small one serves M <= 128
+                                                              // split evenly over the wavefronts; the small one serves M <= 128 at V <= 65,536
 constexpr int TOPM_SLOTS = 16;    // list entries per thread at most: the list path needs at least LIST / 16 threads
 
 // Bit pattern -> key with the same order as the float value (-0 and +0 share a key).
@@ -572,7 +572,9 @@ extern "C" ppv_status ppv_topm_mask(const ppv_index_t *ix, const int32_t *prefix
 #define PPV_LAUNCH_TOPM(T, LIST)                                                                                      \
     hipLaunchKernelGGL((topm_kernel<T, LIST>), grid, block, lds, hs, ix->view, prefixes, prefix_stride, lens,          \
                        (const T *)logits, row_stride, M, force_streaming, top_ids, mask_V, mask)
-    const bool small_list = M <= 128;   // a few hundred tokens reach the bound: a quarter of the LDS, more rows per compute unit
+    // a few hundred tokens reach the bound when M is small and the row not too long (the bound's bin holds a share
+    // of the row): then a quarter of the LDS does, and more rows fit a compute unit
+    const bool small_list = M <= 128 && V <= 65536;
     if (dt == PPV_F32) {
         if (small_list) PPV_LAUNCH_TOPM(float, TOPM_LIST_SMALL);
         else PPV_LAUNCH_TOPM(float, TOPM_LIST_BIG);
