@@ -216,7 +216,13 @@ template <typename T> __device__ inline uint32_t lane_bits(uint32_t tile_word, i
     return (w >> ((lane % G::LANES_PER_WORD) * G::EPL)) & ((1u << G::EPL) - 1u);
 }
 
-// Statistics of one tile: its maximum m, sum_all = sum exp(x - m), and (IMAGE) sum_val over valid tokens.
+// Statistics of one tile: a reference m, sum_all = sum exp(x - m), and (IMAGE) sum_val over valid tokens.
+// Any reference near the tile's maximum gives the same sums up to rounding, so the reduction over the
+// wavefront that the exact maximum would need is avoided: m is the maximum of lane 0's own tokens (one
+// readfirstlane), as long as no token of the tile lies more than GUARD above it (one compare over the
+// lanes' maxima); otherwise, and when lane 0 holds nothing but -inf, m is the exact maximum.  Either way m
+// depends on the row's values alone, not on how the row is split over wavefronts.  m = -inf: an empty tile.
+constexpr float REF_GUARD = 40.f;   // exp(40) * 2048 tokens is far inside fp32
 template <typename T, bool IMAGE>
 __device__ inline void tile_stats(const RawTile &rt, uint32_t tile_word, int lane, float &m_out, float &zall_out,
                                   float &zval_out) {
@@ -229,16 +235,17 @@ __device__ inline void tile_stats(const RawTile &rt, uint32_t tile_word, int lan
 #pragma unroll
         for (int k = 0; k < G::EPL; k++) mx = fmaxf(mx, x[j][k]);
     }
-    mx = wave_max(mx);
-    m_out = mx;
-    if (mx == -INFINITY) {  // nothing but -inf in this tile
+    float ref = __int_as_float(__builtin_amdgcn_readfirstlane(__float_as_int(mx)));
+    if (ref == -INFINITY || __ballot(mx > ref + REF_GUARD) != 0ull) ref = wave_max(mx);   // wave-uniform branch
+    m_out = ref;
+    if (ref == -INFINITY) {  // nothing but -inf in this tile
         zall_out = 0.f;
         zval_out = 0.f;
         return;
     }
     // exp(x - m) = 2^(x*c - m*c); m*c is rounded once (mc), its residual is folded into the tile sums
-    const float mc = mx * LOG2E;
-    const float resid = fmaf(mx, LOG2E, -mc);
+    const float mc = ref * LOG2E;
+    const float resid = fmaf(ref, LOG2E, -mc);
     float zall = 0.f, zval = 0.f;
 #pragma unroll
     for (int j = 0; j < 4; j++) {

@@ -393,6 +393,57 @@ def test_sample_edge_cases():
     assert gid[0] == -1 and gid[1] == 999 and gid[4] == 77
 
 
+@pytest.mark.parametrize("V", [10_000, 900])            # several tiles per row; the one-tile kernel
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_sample_wide_dynamic_range_inside_tiles(dtype, V):
+    """Rows whose tiles hold values far apart: the tokens that the first lane of a wavefront holds lie far below,
+    slightly below, or are the only finite ones of their tile, single spikes stand 30 to 90 above everything else, and
+    whole tiles are -inf.  Sums must not depend on which token of a tile serves as the reference of its exponentials."""
+    rng = np.random.default_rng(11)
+    B = 12
+    lg = (rng.standard_normal((B, V)) * 2).astype(np.float32)
+    epl = 4 if dtype == "f32" else 8                  # tokens per 16-byte load
+    per_load = 64 * epl
+    lane0 = (np.arange(V) % per_load) < epl           # the tokens lane 0 holds in every tile
+    lg[0, lane0] = -100.0
+    lg[1, lane0] = -39.0
+    lg[2, lane0] = -41.5
+    lg[3, lane0] = -np.inf
+    lg[4, ~lane0] = -np.inf                           # lane 0 alone holds finite values
+    lg[5, lane0] = 35.0                               # lane 0 far above the rest
+    lg[6, rng.integers(0, V, 5)] = 30.0
+    lg[7, rng.integers(0, V, 3)] = 90.0
+    lg[8, :V * 2 // 5] = -np.inf                      # whole tiles without a finite value
+    lg[9, V * 2 // 5:] = -np.inf
+    lg[10] = lg[10] * 20                              # sigma = 40
+    lg[11, lane0] = -60.0; lg[11, V // 2:V // 2 + 100] = 45.0
+    mask = (rng.random((B, V)) < 0.3).astype(np.uint8)
+    mask[5] = lane0.astype(np.uint8)                  # valid = exactly the reference tokens
+    mask[6] = (~lane0).astype(np.uint8)
+    un = rng.random(B, dtype=np.float32)
+    stride = (V + 7) // 8 * 8                        # rows 16-byte aligned
+    if dtype == "bf16":
+        bits = W.f32_to_bf16_bits(lg)
+        lg = W.bf16_bits_to_f32(bits)
+        dl = torch.zeros((B, stride), dtype=torch.bfloat16, device=DEV)
+        dl[:, :V] = to_dev(bits.view(np.int16)).view(torch.bfloat16)
+    else:
+        dl = torch.zeros((B, stride), dtype=torch.float32, device=DEV)
+        dl[:, :V] = to_dev(lg)
+    dl = dl[:, :V]
+    words = np.packbits(np.pad(mask, ((0, 0), (0, (-V) % 32))), axis=1, bitorder="little").view(np.uint32)
+    ids = torch.zeros(B, dtype=torch.int32, device=DEV)
+    lzv = torch.zeros(B, dtype=torch.float32, device=DEV)
+    lza = torch.zeros(B, dtype=torch.float32, device=DEV)
+    ppv.constrained_sample(dl, to_dev(words.view(np.int32)), to_dev(un), ids, lzv, lza)
+    torch.cuda.synchronize()
+    gid, glz, gla = ids.cpu().numpy(), lzv.cpu().numpy(), lza.cpu().numpy()
+    from test_oracle_pins import one_step
+    for b in range(B):
+        r = one_step(lg[b], mask[b], un[b])
+        check_sample_rows(dtype, r, lambda i: mask[b], un[b:b + 1], gid[b:b + 1], glz[b:b + 1], gla[b:b + 1], rows=[b])
+
+
 def test_bf16_sample_matches_f32_on_same_values():
     cfg, S, trie, index = setup_case("C2")
     pb = W.make_prefix_batch(cfg, S, index=8)
