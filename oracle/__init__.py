@@ -52,7 +52,8 @@ def _load():
     lib.oracle_trie_lmax.restype = C.c_int32
     lib.oracle_trie_lmax.argtypes = [p]
     lib.oracle_step_batch.restype = None
-    lib.oracle_step_batch.argtypes = [p, p, C.c_int32, p, C.c_int32, p, p, p, p, p, p, p, p, p, p, p, C.c_int32]
+    lib.oracle_step_batch.argtypes = [p, p, C.c_int32, p, C.c_int32, p, p, p, p, p, p, p, p, p, p, p, C.c_int32,
+                                      C.c_double]
     lib.oracle_max_threads.restype = C.c_int32
     lib.oracle_sorted_build.restype = p
     lib.oracle_sorted_build.argtypes = [p, p, C.c_int64, C.c_int32]
@@ -62,7 +63,7 @@ def _load():
     lib.oracle_topm_batch.restype = None
     lib.oracle_topm_batch.argtypes = [p, p, C.c_int32, p, C.c_int32, p, C.c_int32, p, p, p, C.c_int32]
     lib.oracle_sample_batch.restype = None
-    lib.oracle_sample_batch.argtypes = [p, C.c_int64, p, p, C.c_int32, p, p, p, p, p, C.c_int32]
+    lib.oracle_sample_batch.argtypes = [p, C.c_int64, p, p, C.c_int32, p, p, p, p, p, C.c_int32, C.c_double]
     _lib = lib
     return lib
 
@@ -112,7 +113,8 @@ class Trie:
         except Exception:
             pass
 
-    def _run(self, prefixes, lens, logits, uniforms, want_mask, threads) -> StepResult:
+    def _run(self, prefixes, lens, logits, uniforms, want_mask, threads, temperature=1.0) -> StepResult:
+        assert temperature > 0.0
         prefixes = np.ascontiguousarray(prefixes, dtype=np.int32)
         if prefixes.ndim == 1:
             prefixes = prefixes[None, :]
@@ -137,16 +139,17 @@ class Trie:
         _load().oracle_step_batch(self._h, _ptr(prefixes), stride, _ptr(lens), B, _ptr(logits), _ptr(uniforms),
                                   _ptr(mask), _ptr(lo), _ptr(hi), _ptr(member), _ptr(res.ids),
                                   _ptr(res.logZ_valid), _ptr(res.logZ_all), _ptr(res.cdf_lo), _ptr(res.cdf_hi),
-                                  int(threads))
+                                  int(threads), float(temperature))
         return res
 
     def query(self, prefixes, lens, want_mask: bool = True, threads: int = 1) -> StepResult:
         """mask / [lo,hi) / member for a batch of prefixes (int32 [B, stride], lens int32 [B])."""
-        return self._run(prefixes, lens, None, None, want_mask, threads)
+        return self._run(prefixes, lens, None, None, want_mask, threads, 1.0)
 
-    def step(self, prefixes, lens, logits_f32, uniforms, want_mask: bool = True, threads: int = 1) -> StepResult:
-        """query + masked softmax mass + inverse-CDF sample per row."""
-        return self._run(prefixes, lens, logits_f32, uniforms, want_mask, threads)
+    def step(self, prefixes, lens, logits_f32, uniforms, want_mask: bool = True, threads: int = 1,
+             temperature: float = 1.0) -> StepResult:
+        """query + masked softmax mass + inverse-CDF sample per row, with P = softmax(logits / temperature)."""
+        return self._run(prefixes, lens, logits_f32, uniforms, want_mask, threads, temperature)
 
 
 @dataclass
@@ -197,13 +200,14 @@ class SortedArray:
         return TopMResult(top, mv, mask)
 
 
-def masked_sample(logits_f32: np.ndarray, mask: np.ndarray, uniforms: np.ndarray, threads: int = 1) -> StepResult:
+def masked_sample(logits_f32: np.ndarray, mask: np.ndarray, uniforms: np.ndarray, threads: int = 1,
+                  temperature: float = 1.0) -> StepResult:
     """Algorithm 1's "sample a token from P (.) mask / |P (.) mask|_1" and its mass for given masks (uint8 [B, V])."""
     logits = np.ascontiguousarray(logits_f32, dtype=np.float32)
     mask = np.ascontiguousarray(mask, dtype=np.uint8)
     un = np.ascontiguousarray(uniforms, dtype=np.float32)
     B, V = logits.shape
-    assert mask.shape == (B, V) and un.shape == (B,)
+    assert mask.shape == (B, V) and un.shape == (B,) and temperature > 0.0
     res = StepResult(mask, None, None, None)
     res.ids = np.empty(B, dtype=np.int32)
     res.logZ_valid = np.empty(B, dtype=np.float64)
@@ -211,7 +215,7 @@ def masked_sample(logits_f32: np.ndarray, mask: np.ndarray, uniforms: np.ndarray
     res.cdf_lo = np.empty(B, dtype=np.float64)
     res.cdf_hi = np.empty(B, dtype=np.float64)
     _load().oracle_sample_batch(_ptr(logits), V, _ptr(mask), _ptr(un), B, _ptr(res.ids), _ptr(res.logZ_valid),
-                                _ptr(res.logZ_all), _ptr(res.cdf_lo), _ptr(res.cdf_hi), int(threads))
+                                _ptr(res.logZ_all), _ptr(res.cdf_lo), _ptr(res.cdf_hi), int(threads), float(temperature))
     return res
 
 
@@ -230,7 +234,7 @@ class LoopResult:
 
 def decode_loop(trie: Trie, B: int, logits_f32_for_step: Callable[[int, np.ndarray, np.ndarray], np.ndarray],
                 uniforms_for_step: Callable[[int], np.ndarray], threads: int = 1,
-                force_ids: Optional[Callable[[int], np.ndarray]] = None) -> LoopResult:
+                force_ids: Optional[Callable[[int], np.ndarray]] = None, temperature: float = 1.0) -> LoopResult:
     """Algorithm 1, SampleCandidate, for B independent rows: start from the empty sequence and
     repeat {distribution, mask, sample, append, x *= valid mass} while the row is not in S.
     A row stops the first time it is a member, also when that member has extensions.
@@ -250,7 +254,7 @@ def decode_loop(trie: Trie, B: int, logits_f32_for_step: Callable[[int, np.ndarr
         rows = np.nonzero(active)[0]
         lg = logits_f32_for_step(step, seqs, lens)[rows]
         un = uniforms_for_step(step)[rows]
-        r = trie.step(seqs[rows], lens[rows], lg, un, want_mask=False, threads=threads)
+        r = trie.step(seqs[rows], lens[rows], lg, un, want_mask=False, threads=threads, temperature=temperature)
         ids = np.full(B, -1, dtype=np.int32)
         lz = np.full(B, np.nan)
         cl = np.full(B, np.nan)

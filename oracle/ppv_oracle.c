@@ -16,7 +16,8 @@
  *     "Parallel Verification", ends on);
  *   - member = (x in S), the loop condition of Algorithm 1, SampleCandidate;
  *   - one constrained decoding step of Algorithm 1 (lines "Get next token distribution" to
- *     "Update"): with P = softmax(logits) (temperature 1, Section 4.1 "Methods"),
+ *     "Update"): with P = softmax(logits / T), T the temperature that Algorithm 1 takes as input
+ *     (the experiments of Section 4.1 "Methods" use T = 1),
  *     logZ_valid = log |P (.) mask|_1 = LSE_{v in mask} l_v - LSE_{all v} l_v, and a token drawn
  *     from P (.) mask / |P (.) mask|_1.  The paper names no sampling procedure; this oracle fixes
  *     inverse-CDF over the valid tokens in increasing token id with a supplied uniform u:
@@ -188,22 +189,23 @@ void oracle_query(const otrie *t, const int32_t *prefix, int32_t len, uint8_t *m
 }
 
 /* One row of the constrained step.  logits are fp32 (a bf16 logit is widened exactly by the
- * caller), mask is one byte per token.  Outputs:
+ * caller), mask is one byte per token, T > 0 is the temperature: every logit is divided by T (in
+ * double) before anything else.  Outputs:
  *   id          sampled token, -1 when the mask is empty
  *   logZ_valid  log of the probability mass on valid tokens (-inf when the mask is empty)
  *   logZ_all    log-sum-exp of all logits
  *   cdf_lo/hi   the normalised cumulative weights just before and just after the chosen token,
  *               so that a caller can tell how close u was to a boundary. */
-void oracle_masked_sample(const float *logits, int64_t V, const uint8_t *mask, double u, int32_t *id,
+void oracle_masked_sample(const float *logits, int64_t V, const uint8_t *mask, double u, double T, int32_t *id,
                           double *logZ_valid, double *logZ_all, double *cdf_lo, double *cdf_hi) {
     double m_all = -INFINITY, m_val = -INFINITY;
     for (int64_t v = 0; v < V; v++) {
-        double l = (double)logits[v];
+        double l = (double)logits[v] / T;
         if (l > m_all) m_all = l;
         if (mask[v] && l > m_val) m_val = l;
     }
     double z_all = 0.0;
-    for (int64_t v = 0; v < V; v++) z_all += exp((double)logits[v] - m_all);
+    for (int64_t v = 0; v < V; v++) z_all += exp((double)logits[v] / T - m_all);
     *logZ_all = m_all + log(z_all);
     int any = 0;
     for (int64_t v = 0; v < V; v++) any |= mask[v];
@@ -211,14 +213,14 @@ void oracle_masked_sample(const float *logits, int64_t V, const uint8_t *mask, d
     if (!any || m_val == -INFINITY) { *id = -1; *logZ_valid = -INFINITY; *cdf_lo = 0.0; *cdf_hi = 0.0; return; }
     double z_val = 0.0;
     for (int64_t v = 0; v < V; v++)
-        if (mask[v]) z_val += exp((double)logits[v] - m_val);
+        if (mask[v]) z_val += exp((double)logits[v] / T - m_val);
     *logZ_valid = (m_val + log(z_val)) - *logZ_all;
     double tau = u * z_val, c = 0.0, c_prev = 0.0;
     int64_t pick = -1, last_pos = -1;
     double last_lo = 0.0, last_hi = 0.0;
     for (int64_t v = 0; v < V; v++) {
         if (!mask[v]) continue;
-        double w = exp((double)logits[v] - m_val);
+        double w = exp((double)logits[v] / T - m_val);
         c_prev = c;
         c += w;
         if (w > 0.0) { last_pos = v; last_lo = c_prev; last_hi = c; }
@@ -235,7 +237,8 @@ void oracle_masked_sample(const float *logits, int64_t V, const uint8_t *mask, d
 void oracle_step_batch(const otrie *t, const int32_t *prefixes, int32_t stride, const int32_t *lens, int32_t B,
                        const float *logits /* [B, V] or NULL: query only */, const float *uniforms,
                        uint8_t *mask_out, int64_t *lo, int64_t *hi, int32_t *member, int32_t *ids,
-                       double *logZ_valid, double *logZ_all, double *cdf_lo, double *cdf_hi, int32_t threads) {
+                       double *logZ_valid, double *logZ_all, double *cdf_lo, double *cdf_hi, int32_t threads,
+                       double temperature) {
     int64_t V = t->vocab;
 #ifdef _OPENMP
 #pragma omp parallel for schedule(dynamic, 1) num_threads(threads > 0 ? threads : 1)
@@ -251,7 +254,8 @@ void oracle_step_batch(const otrie *t, const int32_t *prefixes, int32_t stride, 
         if (logits) {
             int32_t id;
             double zv, za, cl, ch;
-            oracle_masked_sample(logits + (size_t)b * (size_t)V, V, mrow, (double)uniforms[b], &id, &zv, &za, &cl, &ch);
+            oracle_masked_sample(logits + (size_t)b * (size_t)V, V, mrow, (double)uniforms[b], temperature, &id, &zv, &za, &cl,
+                                 &ch);
             if (ids) ids[b] = id;
             if (logZ_valid) logZ_valid[b] = zv;
             if (logZ_all) logZ_all[b] = za;
@@ -402,13 +406,13 @@ void oracle_topm_batch(const osorted *x, const int32_t *prefixes, int32_t stride
 /* masked softmax mass + inverse-CDF sample for rows whose masks are given (one byte per token) */
 void oracle_sample_batch(const float *logits, int64_t V, const uint8_t *mask, const float *uniforms, int32_t B,
                          int32_t *ids, double *logZ_valid, double *logZ_all, double *cdf_lo, double *cdf_hi,
-                         int32_t threads) {
+                         int32_t threads, double temperature) {
 #ifdef _OPENMP
 #pragma omp parallel for schedule(dynamic, 1) num_threads(threads > 0 ? threads : 1)
 #endif
     for (int32_t b = 0; b < B; b++)
         oracle_masked_sample(logits + (size_t)b * (size_t)V, V, mask + (size_t)b * (size_t)V, (double)uniforms[b],
-                             ids + b, logZ_valid + b, logZ_all + b, cdf_lo + b, cdf_hi + b);
+                             temperature, ids + b, logZ_valid + b, logZ_all + b, cdf_lo + b, cdf_hi + b);
 }
 
 int32_t oracle_max_threads(void) {

@@ -194,6 +194,89 @@ def test_logZ_matches_library_logsumexp_and_closed_forms():
     assert re.ids[0] == -1 and re.logZ_valid[0] == -np.inf
 
 
+def test_temperature_closed_forms_and_exact_rescaling():
+    """Algorithm 1 takes a temperature T: P = softmax(logits / T).  Pins: the library log-sum-exp of l/T; the
+    two-token logistic closed form; T = 2 on even integers equals T = 1 on their halves bit for bit (the division is
+    exact); probabilities p^(1/T) renormalised for a known p; large T tends to the uniform distribution."""
+    rng = np.random.default_rng(21)
+    V = 129
+    l = (rng.standard_normal(V) * 3).astype(np.float32)
+    mask = (rng.random(V) < 0.4).astype(np.uint8)
+    S = W.constraint_set_from_lists([[int(v)] for v in np.nonzero(mask)[0]], V)
+    trie = oracle.Trie(S.tokens, S.offsets, V)
+    P0, L0 = np.full((1, 1), W.PAD_TOKEN, np.int32), np.zeros(1, np.int32)
+
+    def step(lg, u, T):
+        return trie.step(P0, L0, np.asarray(lg, np.float32)[None, :], np.array([u], np.float32), temperature=T)
+    for T in (0.5, 0.7, 1.0, 3.0):
+        r = step(l, 0.4, T)
+        ld = l.astype(np.float64) / T
+        assert r.logZ_all[0] == pytest.approx(logsumexp(ld), abs=1e-12)
+        assert r.logZ_valid[0] == pytest.approx(logsumexp(ld[mask == 1]) - logsumexp(ld), abs=1e-12)
+        # the sample: inverse CDF over the valid tokens' weights exp(l/T), written out with numpy
+        w = np.exp(ld[mask == 1] - ld[mask == 1].max())
+        cdf = np.cumsum(w) / w.sum()
+        assert r.ids[0] == np.nonzero(mask)[0][np.searchsorted(cdf, 0.4, side="right")]
+        # and through the other entry point
+        m = oracle.masked_sample(l[None, :], mask[None, :], np.array([0.4], np.float32), temperature=T)
+        assert m.ids[0] == r.ids[0] and m.logZ_valid[0] == r.logZ_valid[0] and m.logZ_all[0] == r.logZ_all[0]
+    # exact rescaling: even integers at T = 2 are their halves at T = 1
+    le = (np.round(l * 4) * 2).astype(np.float32)
+    a, b = step(le, 0.61, 2.0), step(le / 2, 0.61, 1.0)
+    assert a.logZ_valid[0] == b.logZ_valid[0] and a.logZ_all[0] == b.logZ_all[0] and a.ids[0] == b.ids[0]
+    assert a.cdf_lo[0] == b.cdf_lo[0] and a.cdf_hi[0] == b.cdf_hi[0]
+    # two valid tokens: P(first | valid) = 1 / (1 + exp((l_b - l_a) / T)), so u just below / above it picks a / b
+    S2 = W.constraint_set_from_lists([[3], [9]], 16)
+    t2 = oracle.Trie(S2.tokens, S2.offsets, 16)
+    l2 = np.zeros(16, np.float32)
+    l2[3], l2[9] = 1.0, 2.5
+    for T in (0.5, 1.0, 4.0):
+        pa = 1.0 / (1.0 + math.exp((2.5 - 1.0) / T))
+        for u, want in ((pa - 1e-4, 3), (pa + 1e-4, 9)):
+            r = t2.step(P0, L0, l2[None, :], np.array([u], np.float32), temperature=T)
+            assert r.ids[0] == want
+            assert r.cdf_hi[0] == pytest.approx(pa, abs=1e-12) if want == 3 else r.cdf_lo[0] == pytest.approx(pa, abs=1e-12)
+        mass = (math.exp(1.0 / T) + math.exp(2.5 / T)) / (14.0 + math.exp(1.0 / T) + math.exp(2.5 / T))
+        assert r.logZ_valid[0] == pytest.approx(math.log(mass), abs=1e-12)
+    # known probabilities: softmax(log p / T) = p^(1/T) / sum p^(1/T)
+    p = np.array([0.1, 0.2, 0.3, 0.4])
+    lp = np.log(p).astype(np.float32)
+    S4 = W.constraint_set_from_lists([[0], [2]], 4)
+    t4 = oracle.Trie(S4.tokens, S4.offsets, 4)
+    q = p ** 2 / (p ** 2).sum()                        # T = 0.5
+    r = t4.step(P0, L0, lp[None, :], np.array([0.5], np.float32), temperature=0.5)
+    assert r.logZ_valid[0] == pytest.approx(math.log(q[0] + q[2]), abs=1e-6)
+    assert r.cdf_hi[0] == pytest.approx(1.0, abs=1e-9) and r.cdf_lo[0] == pytest.approx(q[0] / (q[0] + q[2]), abs=1e-6) and r.ids[0] == 2
+    # T large: uniform over the vocabulary, mass = |valid| / V
+    r = step(l, 0.5, 1e9)
+    assert r.logZ_valid[0] == pytest.approx(math.log(mask.sum() / V), abs=1e-6)
+    assert r.ids[0] == np.nonzero(mask)[0][mask.sum() // 2]
+
+
+def test_decode_loop_temperature_is_the_per_step_temperature():
+    """The loop passes T to every step: its log importance score is the sum of the steps' tempered masses."""
+    S = W.constraint_set_from_lists([[1, 2, 3], [1, 2, 4], [1, 5], [6, 7, 8, 9]], 12)
+    trie = oracle.Trie(S.tokens, S.offsets, 12)
+    rng = np.random.default_rng(3)
+    B = 6
+    lg = [(rng.standard_normal((B, 12)) * 2).astype(np.float32) for _ in range(trie.l_max)]
+    un = [rng.random(B, dtype=np.float32) for _ in range(trie.l_max)]
+    for T in (0.6, 1.0, 2.0):
+        res = oracle.decode_loop(trie, B, lambda s, *_: lg[s], lambda s: un[s], temperature=T)
+        for b in range(B):
+            a, lx = [], 0.0
+            while a not in ([1, 2, 3], [1, 2, 4], [1, 5], [6, 7, 8, 9]):
+                r = trie.step(np.array([a + [W.PAD_TOKEN] * (4 - len(a))], np.int32), np.array([len(a)], np.int32),
+                              lg[len(a)][b:b + 1], un[len(a)][b:b + 1], temperature=T)
+                lx += r.logZ_valid[0]
+                a.append(int(r.ids[0]))
+            assert list(res.seqs[b, :res.lens[b]]) == a and res.logx[b] == pytest.approx(lx, abs=1e-12)
+    # different temperatures give different scores on the same draws
+    r1 = oracle.decode_loop(trie, B, lambda s, *_: lg[s], lambda s: un[s], temperature=1.0)
+    r2 = oracle.decode_loop(trie, B, lambda s, *_: lg[s], lambda s: un[s], temperature=2.0)
+    assert not np.allclose(r1.logx, r2.logx)
+
+
 def test_logZ_far_below_max_does_not_underflow():
     l = np.full(64, -900.0, np.float32)
     l[0] = 0.0
