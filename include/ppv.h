@@ -131,8 +131,8 @@ ppv_status ppv_next_token_mask(const ppv_index_t *index, const int32_t *prefixes
 /*
  * constrained_sample -- Algorithm 1, SampleCandidate: "Sample a token t from P (.) mask /
  * |P (.) mask|_1" and the factor |P (.) mask|_1 that multiplies the importance score x,
- * with P = softmax(logits) (temperature 1, Section 4.1 "Methods").
- * Per row b:
+ * with P = softmax(logits / T), T the temperature that Algorithm 1 takes as input (the experiments
+ * of Section 4.1 "Methods" use T = 1).  With l_v = logits[v] / T, per row b:
  *   logZ_valid[b] = log sum_{v in mask} exp(l_v) - log sum_{all v} exp(l_v)   (<= 0; -inf if the mask is empty)
  *   logZ_all[b]   = log sum_{all v} exp(l_v)
  *   ids[b]        = the first valid token, in increasing token id, whose cumulative weight
@@ -145,13 +145,15 @@ ppv_status ppv_next_token_mask(const ppv_index_t *index, const int32_t *prefixes
  *   mask        uint32[B, ceil(V/32)] in the layout above
  *   uniforms    float[B], each in [0, 1)
  *   ids         int32[B]     logZ_valid  float[B]     logZ_all  float[B] or NULL
+ *   temperature host, T > 0 and finite.  The division is folded into the constant of the exponentials
+ *               (no pass over the logits, no cost per token); T = 1 leaves the logits as they are.
  * Logits must be finite or -inf; accumulation is in fp32 with fp64 across partial sums.
- * Errors: PPV_EINVAL (null pointer, B < 0, V <= 0, row_stride < V or misaligned, bad dt),
- * PPV_ERANGE (V > PPV_MAX_VOCAB), PPV_EDEVICE.
+ * Errors: PPV_EINVAL (null pointer, B < 0, V <= 0, row_stride < V or misaligned, bad dt, temperature not
+ * a positive finite number), PPV_ERANGE (V > PPV_MAX_VOCAB), PPV_EDEVICE.
  */
 ppv_status constrained_sample(const void *logits, ppv_dtype dt, int64_t row_stride, const uint32_t *mask,
                               const float *uniforms, int32_t B, int32_t V, int32_t *ids, float *logZ_valid,
-                              float *logZ_all, void *stream);
+                              float *logZ_all, float temperature, void *stream);
 
 /*
  * ppv_decode_begin -- Algorithm 1, SampleCandidate: "Initialize candidate sequence a = [],
@@ -185,7 +187,7 @@ ppv_status ppv_decode_begin(const ppv_index_t *index, const int32_t *prefixes, i
  *   state     uint32[B, PPV_STATE_WORDS] from ppv_decode_begin, in/out; or NULL: the prefix is then
  *             located from the root in every call (same results, one index level per token slower).
  *             With a state the caller must not change prefixes/lens of active rows between steps.
- *   logits, dt, row_stride, uniforms   as in constrained_sample; V is the index's vocabulary
+ *   logits, dt, row_stride, uniforms, temperature   as in constrained_sample; V is the index's vocabulary
  *   ids         int32[B] or NULL: token sampled this step (-1 if none); untouched for inactive rows
  *   logZ_valid  float[B] or NULL: this step's log valid mass; untouched for inactive rows
  *   logx        float[B] or NULL, in/out: logx[b] += logZ_valid[b]  (log of the importance score x)
@@ -194,7 +196,7 @@ ppv_status ppv_decode_begin(const ppv_index_t *index, const int32_t *prefixes, i
 ppv_status ppv_decode_step(const ppv_index_t *index, int32_t *prefixes, int32_t prefix_stride, int32_t *lens,
                            uint8_t *active, uint32_t *state, const void *logits, ppv_dtype dt, int64_t row_stride,
                            const float *uniforms, int32_t B, int32_t *ids, float *logZ_valid, float *logx,
-                           void *stream);
+                           float temperature, void *stream);
 
 /*
  * ppv_decode_loop -- the whole while loop of Algorithm 1's SampleCandidate in one launch: n_steps
@@ -213,7 +215,7 @@ ppv_status ppv_decode_step(const ppv_index_t *index, int32_t *prefixes, int32_t 
 ppv_status ppv_decode_loop(const ppv_index_t *index, int32_t *prefixes, int32_t prefix_stride, int32_t *lens,
                            uint8_t *active, uint32_t *state, const void *logits, ppv_dtype dt, int64_t row_stride,
                            int64_t step_stride, const float *uniforms, int32_t n_steps, int32_t B, int32_t *ids,
-                           float *logZ_valid, float *logx, void *stream);
+                           float *logZ_valid, float *logx, float temperature, void *stream);
 
 /*
  * ppv_topm_mask -- Algorithm 2 with M < |V| candidates, as the paper ran it (M = 50; 100, 500, 1000
@@ -229,7 +231,8 @@ ppv_status ppv_decode_loop(const ppv_index_t *index, int32_t *prefixes, int32_t 
  * Arguments (device pointers unless noted):
  *   index, prefixes, prefix_stride, lens   as in ppv_next_token_mask
  *   logits      device, [B, row_stride] of dt, 16-byte aligned, row_stride >= V and a multiple of
- *               4 (f32) / 8 (bf16); the model's next-token logits per row (temperature 1)
+ *               4 (f32) / 8 (bf16); the model's next-token logits per row (a temperature T > 0 does not
+ *               change their order, so the call takes none)
  *   M           host, 1 .. PPV_TOPM_MAX; a row has min(M, V) candidates
  *   top_ids     int32[B, M] or NULL: the row's candidates t_i in increasing token id; -1 beyond min(M, V)
  *   mask_V      uint8[B, M] or NULL: mask_V[b, i] = 1 iff a + [top_ids[b, i]] is a prefix of a member

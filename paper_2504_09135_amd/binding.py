@@ -64,13 +64,13 @@ def load_library() -> C.CDLL:
     lib.ppv_next_token_mask.restype = C.c_int
     lib.ppv_next_token_mask.argtypes = [p, p, i32, p, i32, p, p, p, p, p]
     lib.constrained_sample.restype = C.c_int
-    lib.constrained_sample.argtypes = [p, C.c_int, i64, p, p, i32, i32, p, p, p, p]
+    lib.constrained_sample.argtypes = [p, C.c_int, i64, p, p, i32, i32, p, p, p, C.c_float, p]
     lib.ppv_decode_begin.restype = C.c_int
     lib.ppv_decode_begin.argtypes = [p, p, i32, p, i32, p, p, p, p]
     lib.ppv_decode_step.restype = C.c_int
-    lib.ppv_decode_step.argtypes = [p, p, i32, p, p, p, p, C.c_int, i64, p, i32, p, p, p, p]
+    lib.ppv_decode_step.argtypes = [p, p, i32, p, p, p, p, C.c_int, i64, p, i32, p, p, p, C.c_float, p]
     lib.ppv_decode_loop.restype = C.c_int
-    lib.ppv_decode_loop.argtypes = [p, p, i32, p, p, p, p, C.c_int, i64, i64, p, i32, i32, p, p, p, p]
+    lib.ppv_decode_loop.argtypes = [p, p, i32, p, p, p, p, C.c_int, i64, i64, p, i32, i32, p, p, p, C.c_float, p]
     lib.ppv_topm_mask.restype = C.c_int
     lib.ppv_topm_mask.argtypes = [p, p, i32, p, p, C.c_int, i64, i32, i32, p, p, p, p]
     lib.ppv_disc_select.restype = C.c_int
@@ -205,9 +205,10 @@ def _logits_args(logits: torch.Tensor):
 
 
 def constrained_sample(logits: torch.Tensor, mask: torch.Tensor, uniforms: torch.Tensor, ids: torch.Tensor,
-                       logZ_valid: torch.Tensor, logZ_all: Optional[torch.Tensor] = None, stream=None) -> None:
+                       logZ_valid: torch.Tensor, logZ_all: Optional[torch.Tensor] = None, stream=None,
+                       temperature: float = 1.0) -> None:
     """logits [B, V] f32/bf16, mask int32 [B, ceil(V/32)], uniforms f32 [B] -> ids int32 [B],
-    logZ_valid f32 [B], logZ_all f32 [B] (optional)."""
+    logZ_valid f32 [B], logZ_all f32 [B] (optional); P = softmax(logits / temperature)."""
     ptr, dt, row_stride = _logits_args(logits)
     B, V = int(logits.shape[0]), int(logits.shape[1])
     if tuple(mask.shape) != (B, (V + 31) // 32) or tuple(uniforms.shape) != (B,) or tuple(ids.shape) != (B,) \
@@ -216,7 +217,7 @@ def constrained_sample(logits: torch.Tensor, mask: torch.Tensor, uniforms: torch
     st = load_library().constrained_sample(
         ptr, dt, row_stride, _dev(mask, torch.int32, "mask"), _dev(uniforms, torch.float32, "uniforms"), B, V,
         _dev(ids, torch.int32, "ids"), _dev(logZ_valid, torch.float32, "logZ_valid"),
-        _dev(logZ_all, torch.float32, "logZ_all"), _stream(stream))
+        _dev(logZ_all, torch.float32, "logZ_all"), float(temperature), _stream(stream))
     _check(st, "constrained_sample")
 
 
@@ -238,9 +239,9 @@ def ppv_decode_begin(index: PPVIndex, prefixes: torch.Tensor, lens: torch.Tensor
 def ppv_decode_step(index: PPVIndex, prefixes: torch.Tensor, lens: torch.Tensor, active: torch.Tensor,
                     logits: torch.Tensor, uniforms: torch.Tensor, ids: Optional[torch.Tensor] = None,
                     logZ_valid: Optional[torch.Tensor] = None, logx: Optional[torch.Tensor] = None,
-                    state: Optional[torch.Tensor] = None, stream=None) -> None:
+                    state: Optional[torch.Tensor] = None, stream=None, temperature: float = 1.0) -> None:
     """One fused constrained decoding step, in place on prefixes / lens / active / logx (and on
-    state int32 [B, PPV_STATE_WORDS] from ppv_decode_begin when given)."""
+    state int32 [B, PPV_STATE_WORDS] from ppv_decode_begin when given); P = softmax(logits / temperature)."""
     ptr, dt, row_stride = _logits_args(logits)
     B, stride = int(prefixes.shape[0]), int(prefixes.shape[1])
     if int(logits.shape[0]) != B or int(logits.shape[1]) != index.vocab or tuple(lens.shape) != (B,) \
@@ -254,14 +255,15 @@ def ppv_decode_step(index: PPVIndex, prefixes: torch.Tensor, lens: torch.Tensor,
         index.handle, _dev(prefixes, torch.int32, "prefixes"), stride, _dev(lens, torch.int32, "lens"),
         _dev(active, torch.uint8, "active"), _dev(state, torch.int32, "state"), ptr, dt, row_stride,
         _dev(uniforms, torch.float32, "uniforms"), B, _dev(ids, torch.int32, "ids"),
-        _dev(logZ_valid, torch.float32, "logZ_valid"), _dev(logx, torch.float32, "logx"), _stream(stream))
+        _dev(logZ_valid, torch.float32, "logZ_valid"), _dev(logx, torch.float32, "logx"), float(temperature),
+        _stream(stream))
     _check(st, "ppv_decode_step")
 
 
 def ppv_decode_loop(index: PPVIndex, prefixes: torch.Tensor, lens: torch.Tensor, active: torch.Tensor,
                     logits: torch.Tensor, uniforms: torch.Tensor, ids: Optional[torch.Tensor] = None,
                     logZ_valid: Optional[torch.Tensor] = None, logx: Optional[torch.Tensor] = None,
-                    state: Optional[torch.Tensor] = None, stream=None) -> None:
+                    state: Optional[torch.Tensor] = None, stream=None, temperature: float = 1.0) -> None:
     """The whole decode loop in one launch: logits [n_steps, B, V] (f32/bf16), uniforms f32 [n_steps, B],
     ids int32 / logZ_valid f32 [n_steps, B] (optional); everything else as ppv_decode_step."""
     if logits.dim() != 3 or not logits.is_cuda or logits.stride(2) != 1:
@@ -284,7 +286,7 @@ def ppv_decode_loop(index: PPVIndex, prefixes: torch.Tensor, lens: torch.Tensor,
         _dev(active, torch.uint8, "active"), _dev(state, torch.int32, "state"), C.c_void_p(logits.data_ptr()), dt,
         int(logits.stride(1)), int(logits.stride(0)), _dev(uniforms, torch.float32, "uniforms"), n_steps, B,
         _dev(ids, torch.int32, "ids"), _dev(logZ_valid, torch.float32, "logZ_valid"),
-        _dev(logx, torch.float32, "logx"), _stream(stream))
+        _dev(logx, torch.float32, "logx"), float(temperature), _stream(stream))
     _check(st, "ppv_decode_loop")
 
 

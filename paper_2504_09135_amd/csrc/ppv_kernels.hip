@@ -4,9 +4,9 @@
 //
 // The logits row is the only large operand.  It is streamed exactly once, in tiles of 4 KB per
 // wavefront (four 16-byte loads per lane, issued before any index work so that they are in
-// flight while the prefix is located).  Each tile yields (max, sum of exp) relative to its own
-// maximum; tiles are combined afterwards, so every tile is independent and a row can be spread
-// over any number of wavefronts.  The valid set enters in one of two ways:
+// flight while the prefix is located).  Each tile yields (reference, sum of exp relative to it), the
+// reference being a value near the tile's maximum; tiles are combined afterwards, so every tile is
+// independent and a row can be spread over any number of wavefronts.  The valid set enters in one of two ways:
 //   list   at most PPV_LIST_MAX valid tokens: their logits are gathered (they were just streamed,
 //          so they come from cache), summed relative to their own maximum, and the sample is
 //          located by a scan over the list -- no per-element mask work in the stream;
@@ -14,6 +14,7 @@
 //          operations per element) and the sample is located by re-reading one tile.
 // Nothing here is a dense contraction, so no MFMA; the bound is HBM bandwidth, with the exp
 // (quarter-rate v_exp_f32) as the main ALU cost.
+#include <cmath>
 #include <cstdlib>
 #include <type_traits>
 
@@ -27,16 +28,24 @@ constexpr int MASK_THREADS = 256;
 constexpr int MAX_WAVES = 16;                 // wavefronts per row (workgroup of up to 1024 threads)
 constexpr int LOOP_WAVES = 8;                 // the decode-loop kernel holds more in registers: at most 512 threads
 constexpr int MAX_TILES = 256;                // PPV_MAX_VOCAB / 1024 (fp32 tiles are 1024 tokens)
-constexpr float LOG2E = 1.44269504088896340736f;
 constexpr float LN2F = 0.693147180559945309417f;
 static_assert(PPV_MAX_VOCAB <= MAX_TILES * 1024, "tile bookkeeping too small");
 
 __device__ inline float fast_exp2(float y) { return __builtin_amdgcn_exp2f(y); }  // v_exp_f32, 1 ulp
 __device__ inline float fast_log2(float y) { return __builtin_amdgcn_logf(y); }   // v_log_f32, 1 ulp (normal inputs)
 // exp(d) for d <= 0 with the rounding of d*log2(e) compensated (used once per tile, not per token)
-__device__ inline float exp_scale(float d) {
-    float hi = d * LOG2E;
-    float lo = fmaf(d, LOG2E, -hi);
+// Temperature (Algorithm 1's input T): P = softmax(logits / T).  The division is folded into the constant of the
+// exponentials, c = log2(e) / T, so that it costs nothing per token; differences of logits that enter a result
+// as they are (a reference minus another) are multiplied by inv = 1 / T.  T = 1 gives c = log2(e), inv = 1.
+struct Temper {
+    float c;
+    float inv;
+    float guard;   // how far above a tile's reference a logit may lie (REF_GUARD * T, see tile_stats)
+};
+
+__device__ inline float exp_scale(float d, float c) {
+    float hi = d * c;
+    float lo = fmaf(d, c, -hi);
     return fast_exp2(hi) * fmaf(lo, LN2F, 1.0f);
 }
 
@@ -219,13 +228,13 @@ template <typename T> __device__ inline uint32_t lane_bits(uint32_t tile_word, i
 // Statistics of one tile: a reference m, sum_all = sum exp(x - m), and (IMAGE) sum_val over valid tokens.
 // Any reference near the tile's maximum gives the same sums up to rounding, so the reduction over the
 // wavefront that the exact maximum would need is avoided: m is the maximum of lane 0's own tokens (one
-// readfirstlane), as long as no token of the tile lies more than GUARD above it (one compare over the
+// readfirstlane), as long as no token of the tile lies more than REF_GUARD * T above it (one compare over the
 // lanes' maxima); otherwise, and when lane 0 holds nothing but -inf, m is the exact maximum.  Either way m
 // depends on the row's values alone, not on how the row is split over wavefronts.  m = -inf: an empty tile.
 constexpr float REF_GUARD = 40.f;   // exp(40) * 2048 tokens is far inside fp32
 template <typename T, bool IMAGE>
-__device__ inline void tile_stats(const RawTile &rt, uint32_t tile_word, int lane, float &m_out, float &zall_out,
-                                  float &zval_out) {
+__device__ inline void tile_stats(const RawTile &rt, uint32_t tile_word, int lane, const Temper &tp, float &m_out,
+                                  float &zall_out, float &zval_out) {
     using G = TileGeom<T>;
     float x[4][G::EPL];
     float mx = -INFINITY;
@@ -236,7 +245,7 @@ __device__ inline void tile_stats(const RawTile &rt, uint32_t tile_word, int lan
         for (int k = 0; k < G::EPL; k++) mx = fmaxf(mx, x[j][k]);
     }
     float ref = __int_as_float(__builtin_amdgcn_readfirstlane(__float_as_int(mx)));
-    if (ref == -INFINITY || __ballot(mx > ref + REF_GUARD) != 0ull) ref = wave_max(mx);   // wave-uniform branch
+    if (ref == -INFINITY || __ballot(mx > ref + tp.guard) != 0ull) ref = wave_max(mx);   // wave-uniform branch
     m_out = ref;
     if (ref == -INFINITY) {  // nothing but -inf in this tile
         zall_out = 0.f;
@@ -244,8 +253,9 @@ __device__ inline void tile_stats(const RawTile &rt, uint32_t tile_word, int lan
         return;
     }
     // exp(x - m) = 2^(x*c - m*c); m*c is rounded once (mc), its residual is folded into the tile sums
-    const float mc = ref * LOG2E;
-    const float resid = fmaf(ref, LOG2E, -mc);
+    const float c = tp.c;
+    const float mc = ref * c;
+    const float resid = fmaf(ref, c, -mc);
     float zall = 0.f, zval = 0.f;
 #pragma unroll
     for (int j = 0; j < 4; j++) {
@@ -253,7 +263,7 @@ __device__ inline void tile_stats(const RawTile &rt, uint32_t tile_word, int lan
         if (IMAGE) bits = lane_bits<T>(tile_word, j, lane);
 #pragma unroll
         for (int k = 0; k < G::EPL; k++) {
-            float e = fast_exp2(fmaf(x[j][k], LOG2E, -mc));
+            float e = fast_exp2(fmaf(x[j][k], c, -mc));
             zall += e;
             if (IMAGE) {
                 uint32_t keep = (uint32_t)(-(int32_t)((bits >> k) & 1u));
@@ -285,10 +295,10 @@ __device__ inline float tile_valid_max(const RawTile &rt, uint32_t tile_word, in
 }
 // ... and the valid sum of a tile relative to a given reference (finite)
 template <typename T>
-__device__ inline float tile_valid_sum(const RawTile &rt, uint32_t tile_word, int lane, float ref) {
+__device__ inline float tile_valid_sum(const RawTile &rt, uint32_t tile_word, int lane, float ref, float c) {
     using G = TileGeom<T>;
-    const float mc = ref * LOG2E;
-    const float fix = fast_exp2(-fmaf(ref, LOG2E, -mc));
+    const float mc = ref * c;
+    const float fix = fast_exp2(-fmaf(ref, c, -mc));
     float z = 0.f;
 #pragma unroll
     for (int j = 0; j < 4; j++) {
@@ -297,7 +307,7 @@ __device__ inline float tile_valid_sum(const RawTile &rt, uint32_t tile_word, in
         const uint32_t bits = lane_bits<T>(tile_word, j, lane);
 #pragma unroll
         for (int k = 0; k < G::EPL; k++)
-            if ((bits >> k) & 1u) z += fast_exp2(fmaf(x[k], LOG2E, -mc));
+            if ((bits >> k) & 1u) z += fast_exp2(fmaf(x[k], c, -mc));
     }
     return wave_sum(z) * fix;
 }
@@ -308,10 +318,10 @@ __device__ inline float tile_valid_sum(const RawTile &rt, uint32_t tile_word, in
 // with positive weight is returned.
 template <typename T>
 __device__ inline int locate_in_tile(const RawTile &rt, uint32_t tile_word, int tile, int lane, float m,
-                                     double target) {
+                                     double target, float tc) {
     using G = TileGeom<T>;
-    const float mc = m * LOG2E;
-    const float fix = fast_exp2(-fmaf(m, LOG2E, -mc));
+    const float mc = m * tc;
+    const float fix = fast_exp2(-fmaf(m, tc, -mc));
     double before = 0.0;  // valid weight of the loads already passed
     int last_valid = -1;
     for (int j = 0; j < 4; j++) {
@@ -322,7 +332,7 @@ __device__ inline int locate_in_tile(const RawTile &rt, uint32_t tile_word, int 
         int my_last = -1;
 #pragma unroll
         for (int k = 0; k < G::EPL; k++) {
-            e[k] = ((bits >> k) & 1u) ? fast_exp2(fmaf(x[k], LOG2E, -mc)) * fix : 0.f;
+            e[k] = ((bits >> k) & 1u) ? fast_exp2(fmaf(x[k], tc, -mc)) * fix : 0.f;
             grp += e[k];
             if (e[k] > 0.f) my_last = k;
         }
@@ -397,7 +407,7 @@ enum ValidMode { VALID_NONE = 0, VALID_LIST = 1, VALID_IMAGE = 2 };
 template <typename T, bool IMAGE, bool PIPE, typename SH>
 __device__ inline void stream_tiles(const T *__restrict__ row, int V, const RawTile &first,
                                     const uint32_t *__restrict__ image, SH &sh, int lane, int wave_v,
-                                    int nw) {
+                                    int nw, const Temper &tp) {
     using G = TileGeom<T>;
     const int wave = __builtin_amdgcn_readfirstlane(wave_v);   // scalar: loop control stays uniform
     const int nt = (V + G::TILE - 1) / G::TILE;
@@ -405,7 +415,7 @@ __device__ inline void stream_tiles(const T *__restrict__ row, int V, const RawT
     if (wave >= nt) return;
     auto reduce_tile = [&](const RawTile &t, int k) {
         float m, zall, zval;
-        tile_stats<T, IMAGE>(t, IMAGE ? t.word : 0u, lane, m, zall, zval);
+        tile_stats<T, IMAGE>(t, IMAGE ? t.word : 0u, lane, tp, m, zall, zval);
         if (lane == 0) {
             sh.tile_m[k] = m;
             sh.tile_zall[k] = zall;
@@ -464,7 +474,8 @@ __device__ inline void stream_tiles(const T *__restrict__ row, int V, const RawT
 template <typename T, bool PIPE, typename SH>
 __device__ inline RowOut row_sample(const T *__restrict__ row, int V, const RawTile &first, int mode, int n_list,
                                     const uint32_t *__restrict__ image, float u, SH &sh, int tid, int nw,
-                                    const T *__restrict__ next_row = nullptr, RawTile *next_first = nullptr) {
+                                    const Temper &tp, const T *__restrict__ next_row = nullptr,
+                                    RawTile *next_first = nullptr) {
     using G = TileGeom<T>;
     const int lane = tid & (WAVE - 1), wave = tid / WAVE;
     const int nt = (V + G::TILE - 1) / G::TILE;
@@ -483,8 +494,8 @@ __device__ inline RowOut row_sample(const T *__restrict__ row, int V, const RawT
     }
 
     // ---- stream: every tile once
-    if (mode == VALID_IMAGE) stream_tiles<T, true, PIPE, SH>(row, V, first, image, sh, lane, wave, nw);
-    else stream_tiles<T, false, PIPE, SH>(row, V, first, image, sh, lane, wave, nw);
+    if (mode == VALID_IMAGE) stream_tiles<T, true, PIPE, SH>(row, V, first, image, sh, lane, wave, nw, tp);
+    else stream_tiles<T, false, PIPE, SH>(row, V, first, image, sh, lane, wave, nw, tp);
     // ---- list path, part 2: sums per slice of 64 listed tokens, relative to the slice maximum
     if (mode == VALID_LIST) {
         for (int s = wave; s < ns; s += nw) {
@@ -501,9 +512,9 @@ __device__ inline RowOut row_sample(const T *__restrict__ row, int V, const RawT
             const float m = wave_max(x);
             float e = 0.f;
             if (m != -INFINITY) {
-                const float mc = m * LOG2E;
-                const float fix = fast_exp2(-fmaf(m, LOG2E, -mc));
-                e = fast_exp2(fmaf(x, LOG2E, -mc)) * fix;   // x = -inf gives 0
+                const float mc = m * tp.c;
+                const float fix = fast_exp2(-fmaf(m, tp.c, -mc));
+                e = fast_exp2(fmaf(x, tp.c, -mc)) * fix;   // x = -inf gives 0
             }
             if (i < n_list) sh.list_e[i] = e;
             const float z = wave_sum(e);
@@ -526,7 +537,7 @@ __device__ inline RowOut row_sample(const T *__restrict__ row, int V, const RawT
     for (int k = lane; k < nt; k += WAVE) {
         const float m = sh.tile_m[k];
         if (m != -INFINITY) {
-            const double sc = (double)exp_scale(m - M);
+            const double sc = (double)exp_scale(m - M, tp.c);
             za += (double)sh.tile_zall[k] * sc;
             zv += (double)sh.tile_zval[k] * sc;
         }
@@ -556,7 +567,7 @@ __device__ inline RowOut row_sample(const T *__restrict__ row, int V, const RawT
             for (int k = wave; k < nt; k += nw) {
                 load_tile<T>(row, V, k, lane, rt);
                 const uint32_t word = tile_mask_word<T>(image, k, lane, V);
-                const float z = tile_valid_sum<T>(rt, word, lane, Mv);
+                const float z = tile_valid_sum<T>(rt, word, lane, Mv, tp.c);
                 if (lane == 0) {
                     sh.tile_zval[k] = z;
                     sh.tile_ref[k] = Mv;
@@ -579,7 +590,7 @@ __device__ inline RowOut row_sample(const T *__restrict__ row, int V, const RawT
         float lzv = -INFINITY;
         if (mode == VALID_IMAGE) {
             if (zv > 0.0) {
-                lzv = (R - M) + LN2F * (fast_log2((float)zv) - l2za);
+                lzv = fmaf(R - M, tp.inv, LN2F * (fast_log2((float)zv) - l2za));
                 const double tau = (double)u * zv;
                 // first tile whose cumulative valid weight exceeds tau
                 double carry = 0.0, before = 0.0;
@@ -588,7 +599,7 @@ __device__ inline RowOut row_sample(const T *__restrict__ row, int V, const RawT
                     const int k = k0 + lane;
                     double w = 0.0;
                     if (k < nt && sh.tile_zval[k] > 0.f)
-                        w = (double)sh.tile_zval[k] * (double)exp_scale(sh.tile_ref[k] - R);
+                        w = (double)sh.tile_zval[k] * (double)exp_scale(sh.tile_ref[k] - R, tp.c);
                     const double incl = carry + wave_incl_scan(w);
                     const uint64_t cross = __ballot(incl > tau);
                     const uint64_t have = __ballot(w > 0.0);
@@ -605,7 +616,7 @@ __device__ inline RowOut row_sample(const T *__restrict__ row, int V, const RawT
                 int kt;
                 if (kstar >= 0) {
                     kt = kstar;
-                    target = (tau - before) / (double)exp_scale(sh.tile_ref[kt] - R);
+                    target = (tau - before) / (double)exp_scale(sh.tile_ref[kt] - R, tp.c);
                 } else {  // rounding: the total never exceeded tau; take the last valid token
                     kt = klast;
                     target = INFINITY;
@@ -614,7 +625,7 @@ __device__ inline RowOut row_sample(const T *__restrict__ row, int V, const RawT
                     RawTile lt;
                     load_tile<T>(row, V, kt, lane, lt);
                     const uint32_t word = tile_mask_word<T>(image, kt, lane, V);
-                    id = locate_in_tile<T>(lt, word, kt, lane, sh.tile_ref[kt], target);
+                    id = locate_in_tile<T>(lt, word, kt, lane, sh.tile_ref[kt], target, tp.c);
                 }
             }
         } else if (mode == VALID_LIST) {
@@ -624,12 +635,12 @@ __device__ inline RowOut row_sample(const T *__restrict__ row, int V, const RawT
             if (Mv != -INFINITY) {
                 double w = 0.0, sc = 0.0;
                 if (lane < ns && sh.slice_m[lane] != -INFINITY) {
-                    sc = (double)exp_scale(sh.slice_m[lane] - Mv);
+                    sc = (double)exp_scale(sh.slice_m[lane] - Mv, tp.c);
                     w = (double)sh.slice_z[lane] * sc;
                 }
                 const double incl = wave_incl_scan(w);
                 const double zvl = last_lane(incl);
-                lzv = (Mv - M) + LN2F * (fast_log2((float)zvl) - l2za);
+                lzv = fmaf(Mv - M, tp.inv, LN2F * (fast_log2((float)zvl) - l2za));
                 const double tau = (double)u * zvl;
                 const uint64_t cross = __ballot(incl > tau);
                 const uint64_t have = __ballot(w > 0.0);
@@ -660,7 +671,7 @@ __device__ inline RowOut row_sample(const T *__restrict__ row, int V, const RawT
             sh.bc_i[0] = id;
             sh.bc_i[1] = pos;
             sh.bc_f[0] = lzv;
-            sh.bc_f[1] = M + LN2F * l2za;
+            sh.bc_f[1] = fmaf(M, tp.inv, LN2F * l2za);
         }
     }
     __syncthreads();
@@ -682,7 +693,7 @@ __global__ __launch_bounds__(SMALL ? SMALL_TILES * WAVE : MAX_WAVES * WAVE) void
                                                                   int n_words, int list_max,
                                                                   int32_t *__restrict__ ids,
                                                                   float *__restrict__ logZ_valid,
-                                                                  float *__restrict__ logZ_all) {
+                                                                  float *__restrict__ logZ_all, Temper tp) {
     using G = TileGeom<T>;
     using SH = typename std::conditional<SMALL, RowSharedSmall, RowShared>::type;
     __shared__ SH sh;
@@ -721,7 +732,7 @@ __global__ __launch_bounds__(SMALL ? SMALL_TILES * WAVE : MAX_WAVES * WAVE) void
         }
         __syncthreads();
     }
-    RowOut r = row_sample<T, PIPE, SH>(row, V, first, mode, mode == VALID_LIST ? total : 0, mrow, uniforms[b], sh, tid, nw);
+    RowOut r = row_sample<T, PIPE, SH>(row, V, first, mode, mode == VALID_LIST ? total : 0, mrow, uniforms[b], sh, tid, nw, tp);
     if (tid == 0) {
         ids[b] = r.id;
         logZ_valid[b] = r.logZ_valid;
@@ -739,7 +750,7 @@ __global__ __launch_bounds__(ONE_TILE_ROWS *WAVE) void sample_one_tile_kernel(co
                                                                               const float *__restrict__ uniforms, int B,
                                                                               int V, int n_words, int32_t *__restrict__ ids,
                                                                               float *__restrict__ logZ_valid,
-                                                                              float *__restrict__ logZ_all) {
+                                                                              float *__restrict__ logZ_all, Temper tp) {
     const int lane = threadIdx.x & (WAVE - 1);
     const int b = blockIdx.x * ONE_TILE_ROWS + threadIdx.x / WAVE;
     if (b >= B) return;   // uniform per wavefront
@@ -749,24 +760,24 @@ __global__ __launch_bounds__(ONE_TILE_ROWS *WAVE) void sample_one_tile_kernel(co
     const uint32_t word = tile_mask_word<T>(mask + (size_t)b * (size_t)n_words, 0, lane, V);
     const float u = uniforms[b];
     float m, zall, zval;
-    tile_stats<T, true>(rt, word, lane, m, zall, zval);
+    tile_stats<T, true>(rt, word, lane, tp, m, zall, zval);
     const float l2za = fast_log2(zall);
     int id = -1;
     float lzv = -INFINITY, ref = m;
     if (__ballot(word != 0u)) {
         if (zval < 3.814697265625e-06f) {   // below 2^-18 of the largest term: sum again, relative to the valid maximum
             ref = tile_valid_max<T>(rt, word, lane);
-            zval = ref != -INFINITY ? tile_valid_sum<T>(rt, word, lane, ref) : 0.f;
+            zval = ref != -INFINITY ? tile_valid_sum<T>(rt, word, lane, ref, tp.c) : 0.f;
         }
         if (zval > 0.f) {
-            lzv = (ref - m) + LN2F * (fast_log2(zval) - l2za);
-            id = locate_in_tile<T>(rt, word, 0, lane, ref, (double)u * (double)zval);
+            lzv = fmaf(ref - m, tp.inv, LN2F * (fast_log2(zval) - l2za));
+            id = locate_in_tile<T>(rt, word, 0, lane, ref, (double)u * (double)zval, tp.c);
         }
     }
     if (lane == 0) {
         ids[b] = id;
         logZ_valid[b] = lzv;
-        if (logZ_all) logZ_all[b] = m + LN2F * l2za;
+        if (logZ_all) logZ_all[b] = fmaf(m, tp.inv, LN2F * l2za);
     }
 }
 
@@ -807,7 +818,7 @@ __global__ __launch_bounds__(LOOP ? LOOP_WAVES * WAVE : MAX_WAVES * WAVE) void d
     IndexView ix, int32_t *__restrict__ prefixes, int32_t stride, int32_t *__restrict__ lens,
     uint8_t *__restrict__ active, RowState *__restrict__ state, const T *__restrict__ logits, int64_t row_stride,
     int64_t step_stride, const float *__restrict__ uniforms, int n_steps, int B, int32_t *__restrict__ ids,
-    float *__restrict__ logZ_valid, float *__restrict__ logx) {
+    float *__restrict__ logZ_valid, float *__restrict__ logx, Temper tp) {
     using G = TileGeom<T>;
     __shared__ RowShared sh;
     const int b = blockIdx.x, tid = threadIdx.x, lane = tid & (WAVE - 1), wave = tid / WAVE;
@@ -870,7 +881,7 @@ __global__ __launch_bounds__(LOOP ? LOOP_WAVES * WAVE : MAX_WAVES * WAVE) void d
         float next_u = 0.f;
         if (more) next_u = uniforms[(size_t)(s + 1) * (size_t)B + b];
         RowOut r = row_sample<T, PIPE, RowShared>(row, V, first, mode, mode == VALID_LIST ? nchild : 0, image, u, sh, tid, nw,
-                                 next_row, &next_first);
+                                                  tp, next_row, &next_first);
         if (tid == 0) {
             const bool room = t < stride;
             int32_t id = -1;
@@ -945,6 +956,15 @@ __global__ __launch_bounds__(LOOP ? LOOP_WAVES * WAVE : MAX_WAVES * WAVE) void d
     }
 }
 
+// T > 0 and finite, or the call is refused; the constants the kernels take (see Temper)
+bool temper_for(float temperature, Temper *tp) {
+    if (!(temperature > 0.f) || !std::isfinite(temperature)) return false;
+    tp->c = (float)(1.44269504088896340736 / (double)temperature);   // log2(e) / T
+    tp->inv = (float)(1.0 / (double)temperature);
+    tp->guard = REF_GUARD * temperature;
+    return std::isfinite(tp->c) && tp->c > 0.f;
+}
+
 ppv_status check_logits_args(const void *logits, ppv_dtype dt, int64_t row_stride, int32_t V) {
     if (!logits || V <= 0 || row_stride < V) return PPV_EINVAL;
     if (dt != PPV_F32 && dt != PPV_BF16) return PPV_EINVAL;
@@ -987,26 +1007,26 @@ bool long_turns(int V, ppv_dtype dt, int nw) {
 template <typename T>
 void launch_sample(bool small, bool pipe, dim3 grid, dim3 block, hipStream_t hs, const T *lg, int64_t row_stride,
                    const uint32_t *mask, const float *uniforms, int V, int n_words, int list_max, int32_t *ids,
-                   float *logZ_valid, float *logZ_all) {
+                   float *logZ_valid, float *logZ_all, Temper tp) {
     if (small)
         hipLaunchKernelGGL((sample_kernel<T, true, false>), grid, block, 0, hs, lg, row_stride, mask, uniforms, V, n_words,
-                           list_max, ids, logZ_valid, logZ_all);
+                           list_max, ids, logZ_valid, logZ_all, tp);
     else if (pipe)
         hipLaunchKernelGGL((sample_kernel<T, false, true>), grid, block, 0, hs, lg, row_stride, mask, uniforms, V, n_words,
-                           list_max, ids, logZ_valid, logZ_all);
+                           list_max, ids, logZ_valid, logZ_all, tp);
     else
         hipLaunchKernelGGL((sample_kernel<T, false, false>), grid, block, 0, hs, lg, row_stride, mask, uniforms, V,
-                           n_words, list_max, ids, logZ_valid, logZ_all);
+                           n_words, list_max, ids, logZ_valid, logZ_all, tp);
 }
 
 template <typename T>
 void launch_decode_kernel(bool loop, bool pipe, dim3 grid, dim3 block, hipStream_t hs, const IndexView &view,
                           int32_t *prefixes, int32_t stride, int32_t *lens, uint8_t *active, RowState *rs, const T *lg,
                           int64_t row_stride, int64_t step_stride, const float *uniforms, int n_steps, int B, int32_t *ids,
-                          float *logZ_valid, float *logx) {
+                          float *logZ_valid, float *logx, Temper tp) {
 #define PPV_LAUNCH_DECODE(LOOP, PIPE)                                                                                 \
     hipLaunchKernelGGL((decode_kernel<T, LOOP, PIPE>), grid, block, 0, hs, view, prefixes, stride, lens, active, rs, lg, \
-                       row_stride, step_stride, uniforms, n_steps, B, ids, logZ_valid, logx)
+                       row_stride, step_stride, uniforms, n_steps, B, ids, logZ_valid, logx, tp)
     if (loop && pipe) PPV_LAUNCH_DECODE(true, true);
     else if (loop) PPV_LAUNCH_DECODE(true, false);
     else if (pipe) PPV_LAUNCH_DECODE(false, true);
@@ -1031,8 +1051,9 @@ extern "C" ppv_status ppv_next_token_mask(const ppv_index_t *ix, const int32_t *
 
 extern "C" ppv_status constrained_sample(const void *logits, ppv_dtype dt, int64_t row_stride, const uint32_t *mask,
                                          const float *uniforms, int32_t B, int32_t V, int32_t *ids,
-                                         float *logZ_valid, float *logZ_all, void *stream) {
-    if (B < 0) return PPV_EINVAL;
+                                         float *logZ_valid, float *logZ_all, float temperature, void *stream) {
+    Temper tp;
+    if (B < 0 || !temper_for(temperature, &tp)) return PPV_EINVAL;
     if (B == 0) return PPV_OK;
     if (!mask || !uniforms || !ids || !logZ_valid) return PPV_EINVAL;
     ppv_status st = check_logits_args(logits, dt, row_stride, V);
@@ -1049,19 +1070,19 @@ extern "C" ppv_status constrained_sample(const void *logits, ppv_dtype dt, int64
         const dim3 g1((unsigned)((B + ONE_TILE_ROWS - 1) / ONE_TILE_ROWS)), b1(ONE_TILE_ROWS * WAVE);
         if (dt == PPV_F32)
             hipLaunchKernelGGL(sample_one_tile_kernel<float>, g1, b1, 0, hs, (const float *)logits, row_stride, mask, uniforms,
-                               B, V, n_words, ids, logZ_valid, logZ_all);
+                               B, V, n_words, ids, logZ_valid, logZ_all, tp);
         else
             hipLaunchKernelGGL(sample_one_tile_kernel<uint16_t>, g1, b1, 0, hs, (const uint16_t *)logits, row_stride, mask,
-                               uniforms, B, V, n_words, ids, logZ_valid, logZ_all);
+                               uniforms, B, V, n_words, ids, logZ_valid, logZ_all, tp);
         PPV_HIP_TRY(hipGetLastError());
         return PPV_OK;
     }
     if (dt == PPV_F32)
         launch_sample<float>(small, pipe, grid, block, hs, (const float *)logits, row_stride, mask, uniforms, V, n_words,
-                             list_max, ids, logZ_valid, logZ_all);
+                             list_max, ids, logZ_valid, logZ_all, tp);
     else
         launch_sample<uint16_t>(small, pipe, grid, block, hs, (const uint16_t *)logits, row_stride, mask, uniforms, V,
-                                n_words, list_max, ids, logZ_valid, logZ_all);
+                                n_words, list_max, ids, logZ_valid, logZ_all, tp);
     PPV_HIP_TRY(hipGetLastError());
     return PPV_OK;
 }
@@ -1084,8 +1105,9 @@ namespace {
 ppv_status launch_decode(const ppv_index_t *ix, int32_t *prefixes, int32_t prefix_stride, int32_t *lens, uint8_t *active,
                          uint32_t *state, const void *logits, ppv_dtype dt, int64_t row_stride, int64_t step_stride,
                          const float *uniforms, int32_t n_steps, int32_t B, int32_t *ids, float *logZ_valid, float *logx,
-                         void *stream, bool loop) {
-    if (!ix || B < 0 || prefix_stride < 0 || n_steps < 0) return PPV_EINVAL;
+                         float temperature, void *stream, bool loop) {
+    Temper tp;
+    if (!ix || B < 0 || prefix_stride < 0 || n_steps < 0 || !temper_for(temperature, &tp)) return PPV_EINVAL;
     if (B == 0 || n_steps == 0) return PPV_OK;
     if (!prefixes || !lens || !active || !uniforms) return PPV_EINVAL;
     ppv_status st = check_logits_args(logits, dt, row_stride, ix->view.vocab);
@@ -1104,11 +1126,11 @@ ppv_status launch_decode(const ppv_index_t *ix, int32_t *prefixes, int32_t prefi
     if (dt == PPV_F32)
         launch_decode_kernel<float>(loop, pipe, grid, block, hs, ix->view, prefixes, prefix_stride, lens, active, rs,
                                     (const float *)logits, row_stride, step_stride, uniforms, n_steps, B, ids, logZ_valid,
-                                    logx);
+                                    logx, tp);
     else
         launch_decode_kernel<uint16_t>(loop, pipe, grid, block, hs, ix->view, prefixes, prefix_stride, lens, active, rs,
                                        (const uint16_t *)logits, row_stride, step_stride, uniforms, n_steps, B, ids,
-                                       logZ_valid, logx);
+                                       logZ_valid, logx, tp);
     PPV_HIP_TRY(hipGetLastError());
     return PPV_OK;
 }
@@ -1117,15 +1139,16 @@ ppv_status launch_decode(const ppv_index_t *ix, int32_t *prefixes, int32_t prefi
 extern "C" ppv_status ppv_decode_step(const ppv_index_t *ix, int32_t *prefixes, int32_t prefix_stride, int32_t *lens,
                                       uint8_t *active, uint32_t *state, const void *logits, ppv_dtype dt,
                                       int64_t row_stride, const float *uniforms, int32_t B, int32_t *ids,
-                                      float *logZ_valid, float *logx, void *stream) {
+                                      float *logZ_valid, float *logx, float temperature, void *stream) {
     return launch_decode(ix, prefixes, prefix_stride, lens, active, state, logits, dt, row_stride, 0, uniforms, 1, B, ids,
-                         logZ_valid, logx, stream, false);
+                         logZ_valid, logx, temperature, stream, false);
 }
 
 extern "C" ppv_status ppv_decode_loop(const ppv_index_t *ix, int32_t *prefixes, int32_t prefix_stride, int32_t *lens,
                                       uint8_t *active, uint32_t *state, const void *logits, ppv_dtype dt,
                                       int64_t row_stride, int64_t step_stride, const float *uniforms, int32_t n_steps,
-                                      int32_t B, int32_t *ids, float *logZ_valid, float *logx, void *stream) {
+                                      int32_t B, int32_t *ids, float *logZ_valid, float *logx, float temperature,
+                                      void *stream) {
     return launch_decode(ix, prefixes, prefix_stride, lens, active, state, logits, dt, row_stride, step_stride, uniforms,
-                         n_steps, B, ids, logZ_valid, logx, stream, true);
+                         n_steps, B, ids, logZ_valid, logx, temperature, stream, true);
 }

@@ -92,11 +92,11 @@ def check_sample_rows(dtype: str, ref, ref_mask_rows, uniforms, ids, lzv, lza=No
     return excused
 
 
-def gpu_sample(cfg, logits_dev, dmask, uniforms: np.ndarray):
+def gpu_sample(cfg, logits_dev, dmask, uniforms: np.ndarray, temperature: float = 1.0):
     B = logits_dev.shape[0]
     ids = torch.full((B,), -7, dtype=torch.int32, device=DEV)
     lzv = torch.full((B,), 3.0, dtype=torch.float32, device=DEV)
     lza = torch.full((B,), 3.0, dtype=torch.float32, device=DEV)
-    ppv.constrained_sample(logits_dev, dmask, to_dev(uniforms), ids, lzv, lza)
+    ppv.constrained_sample(logits_dev, dmask, to_dev(uniforms), ids, lzv, lza, temperature=temperature)
     torch.cuda.synchronize()
     return ids.cpu().numpy(), lzv.cpu().numpy(), lza.cpu().numpy()

@@ -56,10 +56,12 @@ def test_argument_errors_without_device(lib):
     assert lib.ppv_index_export(None, None, None, None) == EINVAL
     lib.ppv_free_index(None)
     assert lib.ppv_next_token_mask(None, None, 0, None, 0, None, None, None, None, None) == EINVAL
-    assert lib.constrained_sample(None, 0, 8, None, None, 1, 8, None, None, None, None) == EINVAL
-    assert lib.constrained_sample(None, 0, 8, None, None, -1, 8, None, None, None, None) == EINVAL
-    assert lib.constrained_sample(None, 0, 8, None, None, 0, 8, None, None, None, None) == 0
-    assert lib.ppv_decode_step(None, None, 0, None, None, None, None, 0, 0, None, 0, None, None, None, None) == EINVAL
+    assert lib.constrained_sample(None, 0, 8, None, None, 1, 8, None, None, None, 1.0, None) == EINVAL
+    assert lib.constrained_sample(None, 0, 8, None, None, -1, 8, None, None, None, 1.0, None) == EINVAL
+    assert lib.constrained_sample(None, 0, 8, None, None, 0, 8, None, None, None, 1.0, None) == 0
+    for bad_t in (0.0, -1.0, float("inf"), float("nan")):       # the temperature is checked before anything is launched
+        assert lib.constrained_sample(None, 0, 8, None, None, 0, 8, None, None, None, bad_t, None) == EINVAL
+    assert lib.ppv_decode_step(None, None, 0, None, None, None, None, 0, 0, None, 0, None, None, None, 1.0, None) == EINVAL
     assert lib.ppv_decode_begin(None, None, 0, None, 0, None, None, None, None) == EINVAL
     assert lib.ppv_disc_select(None, 2, 1, 5, None, None, 0, None, None, None, None) == EINVAL
     assert lib.ppv_disc_select(None, 1, 1, 5, None, None, 0, None, None, None, None) == EINVAL
@@ -73,7 +75,7 @@ def test_argument_errors_without_device(lib):
     assert lib.ppv_topm_mask(fake, None, 0, None, None, 0, 8, 0, 0, None, None, None, None) == EINVAL
     assert lib.ppv_topm_mask(fake, None, 0, None, None, 0, 8, 1025, 0, None, None, None, None) == ERANGE
     assert lib.ppv_topm_mask(fake, None, 0, None, None, 0, 8, 5, 0, None, None, None, None) == 0
-    assert lib.ppv_decode_loop(None, None, 0, None, None, None, None, 0, 0, 0, None, 1, 1, None, None, None, None) == EINVAL
+    assert lib.ppv_decode_loop(None, None, 0, None, None, None, None, 0, 0, 0, None, 1, 1, None, None, None, 1.0, None) == EINVAL
 
 
 def test_index_load_rejects_files_that_are_not_an_index(lib, tmp_path):

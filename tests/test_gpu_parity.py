@@ -105,6 +105,30 @@ def test_constrained_sample_parity(name):
     assert (lzv <= 1e-6).all()
 
 
+@pytest.mark.parametrize("temperature", [0.05, 0.5, 1.7, 8.0, 100.0])
+@pytest.mark.parametrize("name", list(CASES))
+def test_constrained_sample_parity_with_temperature(name, temperature):
+    """P = softmax(logits / T) (Algorithm 1's input T): masses, samples and logZ_all against the oracle at T != 1, and
+    T = 1 passed explicitly gives bit for bit what the default gives."""
+    cfg, S, trie, index = setup_case(name)
+    pb = W.make_prefix_batch(cfg, S, index=5)
+    dmask, _ = assert_query_parity(index, trie, pb.prefixes, pb.lens)
+    logits = W.make_logits(cfg, step=5)
+    un = W.make_uniforms(cfg, step=5)
+    ref = trie.step(pb.prefixes, pb.lens, W.logits_as_f32(cfg, logits), un, threads=8, temperature=temperature)
+    dl = logits_to_dev(cfg, logits)
+    ids, lzv, lza = gpu_sample(cfg, dl, dmask, un, temperature=temperature)
+    check_sample_rows(cfg.dtype, ref, lambda b: ref.mask[b], un, ids, lzv, lza)
+    assert (lzv <= 1e-6).all()
+    a, b = gpu_sample(cfg, dl, dmask, un), gpu_sample(cfg, dl, dmask, un, temperature=1.0)
+    assert all(np.array_equal(x.view(np.int32), y.view(np.int32)) for x, y in zip(a, b))
+    ref1 = trie.step(pb.prefixes, pb.lens, W.logits_as_f32(cfg, logits), un, threads=8)
+    fin = np.isfinite(ref.logZ_valid)
+    assert not np.allclose(ref.logZ_valid[fin], ref1.logZ_valid[fin])          # the temperature does something
+    with pytest.raises(ppv.PPVError):
+        gpu_sample(cfg, dl, dmask, un, temperature=0.0)
+
+
 @pytest.mark.parametrize("name", ["C1", "C2", "C3s"])
 def test_decode_step_equals_mask_plus_sample(name):
     cfg, S, trie, index = setup_case(name)
@@ -150,10 +174,10 @@ def test_decode_step_equals_mask_plus_sample(name):
     assert np.array_equal(gA[ext], (q.member == 0).astype(np.uint8))
 
 
-@pytest.mark.parametrize("use_state", [False, True])
-def test_decode_loop_parity_small(use_state):
+@pytest.mark.parametrize("use_state,temperature", [(False, 1.0), (True, 1.0), (True, 0.6), (False, 2.5)])
+def test_decode_loop_parity_small(use_state, temperature):
     """Algorithm 1's SampleCandidate loop on a scaled C3, step by step against the oracle's loop,
-    with the cursor kept by ppv_decode_begin/ppv_decode_step and without it."""
+    with the cursor kept by ppv_decode_begin/ppv_decode_step and without it, at several temperatures."""
     cfg, S, trie, index = setup_case("C3s")
     B = 64
     stride = index.l_max
@@ -180,11 +204,11 @@ def test_decode_loop_parity_small(use_state):
             break
         ids.fill_(-5)
         ppv.ppv_decode_step(index, dP, dL, dA, logits_to_dev(cfg, W.make_logits(cfg, batch=B, step=100 + s)),
-                            to_dev(un(s)), ids, lz, logx, state=state)
+                            to_dev(un(s)), ids, lz, logx, state=state, temperature=temperature)
         torch.cuda.synchronize()
         all_ids.append((act_before, ids.cpu().numpy(), lz.cpu().numpy()))
     # the oracle makes its own choice at every step but is kept on the HIP path's sequence
-    res = oracle.decode_loop(trie, B, lg, un, threads=8, force_ids=lambda s: all_ids[s][1])
+    res = oracle.decode_loop(trie, B, lg, un, threads=8, force_ids=lambda s: all_ids[s][1], temperature=temperature)
     assert res.steps == len(all_ids)
     excused = 0
     for s in range(res.steps):
@@ -212,8 +236,8 @@ def test_decode_loop_parity_small(use_state):
     assert np.allclose(logx.cpu().numpy(), res.logx, rtol=1e-3, atol=1e-3)
 
 
-@pytest.mark.parametrize("name,B", [("C3s", 96), ("C1", 16), ("C2", 64)])
-def test_decode_loop_launch_equals_single_steps(name, B):
+@pytest.mark.parametrize("name,B,temperature", [("C3s", 96, 1.0), ("C1", 16, 1.0), ("C2", 64, 1.0), ("C3s", 40, 1.7)])
+def test_decode_loop_launch_equals_single_steps(name, B, temperature):
     """ppv_decode_loop (one launch for all steps) gives bit for bit what the same number of
     ppv_decode_step calls give: tokens, lengths, flags, cursor, per-step ids / masses, logx."""
     cfg, S, trie, index = setup_case(name)
@@ -231,10 +255,11 @@ def test_decode_loop_launch_equals_single_steps(name, B):
         lz = torch.full((L, B), 2.0, dtype=torch.float32, device=DEV)
         ppv.ppv_decode_begin(index, P, lens, state, act, logx)
         if use_loop:
-            ppv.ppv_decode_loop(index, P, lens, act, logits, un, ids, lz, logx, state=state)
+            ppv.ppv_decode_loop(index, P, lens, act, logits, un, ids, lz, logx, state=state, temperature=temperature)
         else:
             for s in range(L):
-                ppv.ppv_decode_step(index, P, lens, act, logits[s], un[s], ids[s], lz[s], logx, state=state)
+                ppv.ppv_decode_step(index, P, lens, act, logits[s], un[s], ids[s], lz[s], logx, state=state,
+                                    temperature=temperature)
         torch.cuda.synchronize()
         outs.append([t.cpu().numpy() for t in (P, lens, act, ids, lz.view(torch.int32), logx.view(torch.int32))]
                     + [state.cpu().numpy()])
@@ -249,8 +274,8 @@ def test_decode_loop_launch_equals_single_steps(name, B):
     logx = torch.zeros(B, dtype=torch.float32, device=DEV)
     ppv.ppv_decode_begin(index, P, lens, state, act, logx)
     half = max(1, L // 3)
-    ppv.ppv_decode_loop(index, P, lens, act, logits[:half], un[:half], None, None, logx, state=state)
-    ppv.ppv_decode_loop(index, P, lens, act, logits[half:], un[half:], None, None, logx, state=state)
+    ppv.ppv_decode_loop(index, P, lens, act, logits[:half], un[:half], None, None, logx, state=state, temperature=temperature)
+    ppv.ppv_decode_loop(index, P, lens, act, logits[half:], un[half:], None, None, logx, state=state, temperature=temperature)
     torch.cuda.synchronize()
     assert np.array_equal(P.cpu().numpy(), outs[0][0]) and np.array_equal(lens.cpu().numpy(), outs[0][1])
     assert np.array_equal(logx.view(torch.int32).cpu().numpy(), outs[0][5])
