@@ -702,12 +702,15 @@ __global__ __launch_bounds__(SMALL ? SMALL_TILES * WAVE : MAX_WAVES * WAVE) void
     const T *row = logits + (size_t)b * (size_t)row_stride;
     const uint32_t *mrow = mask + (size_t)b * (size_t)n_words;
     const int nt = (V + G::TILE - 1) / G::TILE;
+    // the mask word of the wave's first tile is requested before the tile itself: memory answers a wavefront in
+    // the order of its requests, so the few bytes the next steps wait for must not queue behind the 4 KB tile
+    const uint32_t w_first = tile_mask_word<T>(mrow, wave < nt ? wave : 0, lane, V);
     RawTile first;
     if (wave < nt) load_tile<T>(row, V, wave, lane, first);   // in flight during the mask work
 
     // bits per tile (a tile's mask words are consecutive: one word per lane)
     for (int k = wave; k < nt; k += nw) {
-        const uint32_t w = tile_mask_word<T>(mrow, k, lane, V);
+        const uint32_t w = k == wave ? w_first : tile_mask_word<T>(mrow, k, lane, V);
         const int c = wave_sum((int)__popc(w));
         if (lane == 0) sh.tile_cnt[k] = c;
     }
@@ -722,7 +725,7 @@ __global__ __launch_bounds__(SMALL ? SMALL_TILES * WAVE : MAX_WAVES * WAVE) void
             for (int q = lane; q < k; q += WAVE) base += sh.tile_cnt[q];
             base = wave_sum(base);
             const int wi = k * G::WORDS + lane;
-            uint32_t w = tile_mask_word<T>(mrow, k, lane, V);
+            uint32_t w = k == wave ? w_first : tile_mask_word<T>(mrow, k, lane, V);
             int at = base + wave_incl_scan((int)__popc(w)) - (int)__popc(w);
             while (w) {
                 const int bit = __ffs((int)w) - 1;
@@ -755,10 +758,10 @@ __global__ __launch_bounds__(ONE_TILE_ROWS *WAVE) void sample_one_tile_kernel(co
     const int b = blockIdx.x * ONE_TILE_ROWS + threadIdx.x / WAVE;
     if (b >= B) return;   // uniform per wavefront
     const T *row = logits + (size_t)b * (size_t)row_stride;
-    RawTile rt;
-    load_tile<T>(row, V, 0, lane, rt);
     const uint32_t word = tile_mask_word<T>(mask + (size_t)b * (size_t)n_words, 0, lane, V);
     const float u = uniforms[b];
+    RawTile rt;
+    load_tile<T>(row, V, 0, lane, rt);
     float m, zall, zval;
     tile_stats<T, true>(rt, word, lane, tp, m, zall, zval);
     const float l2za = fast_log2(zall);
