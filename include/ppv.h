@@ -225,8 +225,10 @@ ppv_status ppv_decode_loop(const ppv_index_t *index, int32_t *prefixes, int32_t 
  * ppv_next_token_mask restricted to the top-M tokens; feed it to constrained_sample for the
  * sampling step of Algorithm 1.
  * The top M are the M largest logits of the row (P = softmax(logits) has the same order); equal
- * logits are taken in increasing token id, -0 and +0 are equal; NaNs are ordered by bit pattern
- * (positive NaNs above +inf).  The M candidate rows share their first |a| tokens: the prefix is
+ * logits are taken in increasing token id, -0 and +0 are equal.  Logits are finite or +/-inf: a row
+ * that holds NaNs ends in a defined state (ids inside [0, V) or -1, nothing out of bounds), but its
+ * candidates are unspecified.
+ * The M candidate rows share their first |a| tokens: the prefix is
  * located once per row and each candidate is then searched by its last token.
  * Arguments (device pointers unless noted):
  *   index, prefixes, prefix_stride, lens   as in ppv_next_token_mask

@@ -87,6 +87,31 @@ def test_topm_candidates_verdicts_and_mask(name):
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 def test_topm_ties_special_values_and_ragged_rows(dtype):
     """Coarse logits (many equal values at the cut), -inf, +/-0, a vocabulary that is no multiple of anything."""
+    ties_and_special_values(dtype)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_topm_noted_group_maxima_path(dtype, monkeypatch):
+    """Long rows are not read twice: the first pass notes every 16-byte group's maximum and the second asks memory
+    only for the groups that reach the bound.  PPV_TOPM_NOTED=1 with one or two wavefronts per row sends short rows
+    down that route too: same results on the rows of ties and special values, and on the scaled configs."""
+    monkeypatch.setenv("PPV_TOPM_NOTED", "1")
+    for waves in ("1", "2"):
+        monkeypatch.setenv("PPV_TOPM_WAVES", waves)
+        ties_and_special_values(dtype, Ms=(1, 7, 64, 128))
+    monkeypatch.setenv("PPV_TOPM_WAVES", "4")
+    for name in ("C2", "C3s", "C5s"):
+        cfg, S, trie, index = setup_case(name)
+        if cfg.dtype != dtype:
+            continue
+        X = sorted_array(name)
+        pb = W.make_prefix_batch(cfg, S)
+        logits = W.make_logits(cfg)
+        for M in (1, 50, 1000):
+            assert_topm_parity(index, X, pb.prefixes, pb.lens, W.logits_as_f32(cfg, logits), logits_to_dev(cfg, logits), M)
+
+
+def ties_and_special_values(dtype, Ms=(1, 7, 64, 1000)):
     rng = np.random.default_rng(77)
     V = 5003
     seqs = [rng.integers(0, V, size=int(rng.integers(1, 5))).tolist() for _ in range(4000)]
@@ -124,8 +149,9 @@ def test_topm_ties_special_values_and_ragged_rows(dtype):
         padded = np.zeros((B, Vp), np.float32)
         padded[:, :V] = lg
         ld = to_dev(padded)[:, :V]
-    for M in (1, 7, 64, 1000):
+    for M in Ms:
         assert_topm_parity(index, X, P, L, lf, ld, M)
+    index.free()
 
 
 def test_topm_largest_vocabulary():
