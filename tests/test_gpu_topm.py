@@ -190,6 +190,41 @@ def test_topm_whole_row_select_path(monkeypatch):
             assert_topm_parity(index, X, pb.prefixes, pb.lens, lf, ld, M)
 
 
+@pytest.mark.parametrize("noted", ["0", "1"])
+def test_topm_rows_with_nans_stay_in_bounds(noted, monkeypatch):
+    """A row that holds NaNs has unspecified candidates, but its ids stay inside [0, V) or -1, its mask only holds
+    tokens of the full mask, and the rows beside it are as the oracle says."""
+    monkeypatch.setenv("PPV_TOPM_NOTED", noted)
+    monkeypatch.setenv("PPV_TOPM_WAVES", "2")
+    name = "C3s"
+    cfg, S, trie, index = setup_case(name)
+    X = sorted_array(name)
+    pb = W.make_prefix_batch(cfg, S)
+    logits = W.make_logits(cfg)
+    lf = W.logits_as_f32(cfg, logits).copy()
+    rng = np.random.default_rng(5)
+    bad_rows = [1, 4, 9]
+    lf[1, rng.integers(0, cfg.vocab, 500)] = np.nan
+    lf[4, :] = np.nan
+    lf[9, ::2] = np.nan
+    lf[9, 1::2] = np.inf
+    bits = W.f32_to_bf16_bits(lf)
+    bits[np.isnan(lf)] = 0x7FC1                                # a quiet NaN in bf16, whatever the rounding made of it
+    bits[9, 10::64] = 0xFFC0                                   # negative NaNs too
+    ld = to_dev(bits.view(np.int16)).view(torch.bfloat16)
+    lf = W.bf16_bits_to_f32(bits)
+    good = np.setdiff1d(np.arange(lf.shape[0]), bad_rows)
+    full = trie.query(pb.prefixes, pb.lens).mask
+    for M in (50, 1000):
+        dmask, top, mv = gpu_topm(index, pb.prefixes, pb.lens, ld, M)
+        assert ((top >= -1) & (top < cfg.vocab)).all()
+        got = unpack_mask(dmask.cpu().numpy().view(np.uint32), cfg.vocab)
+        assert not (got & ~full).any()
+        ref = X.topm(pb.prefixes[good], pb.lens[good], lf[good], M, threads=8)
+        assert np.array_equal(got[good], ref.mask)
+        assert np.array_equal(top[good], np.sort(ref.top_ids, axis=1))
+
+
 def test_topm_then_sample_is_the_step_of_algorithm_1():
     """mask from ppv_topm_mask -> constrained_sample, against the oracle's top-M mask -> masked sample."""
     name = "C3s"
