@@ -9,9 +9,7 @@
 //                 histograms the groups' maxima by their leading 11 key bits; the bin that holds
 //                 the M-th largest group maximum gives a bound L that at least M tokens reach;
 //              B. a second pass (the row is in cache now) lists the tokens that are not below L,
-//                 in token order, in LDS: usually 1.1 to 1.5 M of them; for the longest rows, which no
-//                 cache holds, A notes every group's maximum in LDS (two bytes per group) and B asks
-//                 memory only for the groups that reach L;
+//                 in token order, in LDS: usually 1.1 to 1.5 M of them;
 //              C. a radix select over that short list (11 + 10 + 11 key bits for fp32, 11 + 5 for
 //                 bf16) finds the key T of the M-th largest token; the list is then cut to the
 //                 tokens above T and the first few equal to T, in increasing token id, so the set
@@ -39,9 +37,6 @@ constexpr int TOPM_SHIFT = 32 - TOPM_BITS;
 constexpr int TOPM_WAVES = 16;
 constexpr int TOPM_LIST_BIG = 4096, TOPM_LIST_SMALL = 1024;   // capacity of the candidate list (tokens not below the bound),
                                                               // split evenly over the wavefronts; the small one serves M <= 128 at V <= 65,536
-constexpr size_t TOPM_GMAX_LDS = 100 * 1024;   // dynamic LDS of a workgroup at most (mask row + group maxima)
-constexpr size_t TOPM_CU_LDS = 160 * 1024;     // LDS of a compute unit
-constexpr int TOPM_NOTED_CHUNKS = 384;         // rows of at least this many KB note their group maxima (see ppv_topm_mask)
 constexpr int TOPM_SLOTS = 16;    // list entries per thread at most: the list path needs at least LIST / 16 threads
 
 // Bit pattern -> key with the same order as the float value (-0 and +0 share a key).
@@ -204,7 +199,6 @@ template <typename T> __device__ inline uint32_t full_key(uint32_t hi_part) {
 }
 
 struct TopmLds {
-    uint16_t *gmax;       // [chunks * 64] upper key half of every 16-byte group's maximum, or null (no room)
     uint32_t *hist;       // [TOPM_BINS]
     uint32_t *list_tok;   // [LIST]
     uint32_t *sel;        // [PPV_TOPM_MAX]
@@ -305,7 +299,7 @@ __device__ inline void select_streaming(const T *__restrict__ row, int V, int c0
 
 // Bound, short list, radix select over the list.  Needs nthreads >= LIST / TOPM_SLOTS.  Returns false
 // (for every thread alike) when the list did not fit; sel is then untouched.
-template <typename T, int LIST, bool NOTED>
+template <typename T, int LIST>
 __device__ inline bool select_listed(const T *__restrict__ row, int V, int c0, int c1, int m, const TopmLds &s, int lane,
                                      int wave, int nthreads, uint4 (&r)[4]) {
     constexpr int EPL = KeyChunk<T>::EPL;
@@ -315,10 +309,6 @@ __device__ inline bool select_listed(const T *__restrict__ row, int V, int c0, i
     for (int i = tid; i < TOPM_BINS; i += nthreads) s.hist[i] = 0u;
     if (tid == 0) s.bc[6] = 0u;
     auto load_batch = [&](int c) { load_chunks<T>(row, V, c, c1, lane, r); };   // r arrives holding the batch at c0
-    const bool kept = c1 - c0 <= 4;   // r holds the whole share from A to B
-    // A longer share is not read a second time in B: A notes every group's maximum (its upper key half) in LDS,
-    // and B asks memory only for the groups whose maximum reaches the bound -- a few hundred 16-byte loads.
-    const bool noted = NOTED && !kept && s.gmax != nullptr;
     __syncthreads();
     for (int c = c0; c < c1; c += 4) {
         if (c != c0) load_batch(c);
@@ -329,11 +319,11 @@ __device__ inline bool select_listed(const T *__restrict__ row, int V, int c0, i
             float gm = x[0];
 #pragma unroll
             for (int j = 1; j < EPL; j++) gm = fmaxf(gm, x[j]);
-            const uint32_t gk = order_key(__float_as_uint(gm));
-            if (c + u < c1 && n_inside<T>(V, c + u, lane) > 0) atomicAdd(&s.hist[gk >> TOPM_SHIFT], 1u);
-            if (NOTED && noted && c + u < c1) s.gmax[(c + u) * WAVE + lane] = (uint16_t)(gk >> 16);
+            if (c + u < c1 && n_inside<T>(V, c + u, lane) > 0)
+                atomicAdd(&s.hist[order_key(__float_as_uint(gm)) >> TOPM_SHIFT], 1u);
         }
     }
+    const bool kept = c1 - c0 <= 4;   // r still holds the whole share
     __syncthreads();
     pick_digit(s.hist, TOPM_BINS, (uint32_t)m, s.wave_tot, s.bc, nthreads);
     // At least m groups have their maximum in this bin or above, so at least m tokens are not below the bin's
@@ -344,28 +334,14 @@ __device__ inline bool select_listed(const T *__restrict__ row, int V, int c0, i
     const uint32_t R = (uint32_t)(LIST / nw);
     const uint32_t base = (uint32_t)wave * R;
     uint32_t cnt = 0;   // wave-uniform
-    const uint32_t D0 = s.bc[4];
     for (int c = c0; c < c1; c += 4) {
-        uint32_t flags = 0xFu;   // bit u: this lane's group of chunk c + u may hold a token that reaches the bound
-        if (NOTED && noted) {
-            flags = 0u;
-#pragma unroll
-            for (int u = 0; u < 4; u++)
-                if (c + u < c1 && ((uint32_t)s.gmax[(c + u) * WAVE + lane] >> (16 - TOPM_BITS)) >= D0) flags |= 1u << u;
-            if (__ballot(flags != 0u) == 0ull) continue;   // (wave-uniform) nothing in these four chunks
-            const uint32_t pad = sizeof(T) == 4 ? 0xFF800000u : 0xFF80FF80u;
-#pragma unroll
-            for (int u = 0; u < 4; u++)
-                r[u] = ((flags >> u) & 1u) ? load_raw<T>(row, V, c + u, lane) : make_uint4(pad, pad, pad, pad);
-        } else if (!kept) {
-            load_batch(c);
-        }
+        if (!kept) load_batch(c);
 #pragma unroll
         for (int u = 0; u < 4; u++) {
             if (c + u >= c1) continue;
             float x[EPL];
             unpack_vals<T>(r[u], x);
-            const int n = (!NOTED || ((flags >> u) & 1u)) ? n_inside<T>(V, c + u, lane) : 0;
+            const int n = n_inside<T>(V, c + u, lane);
             uint32_t pm = 0;
 #pragma unroll
             for (int j = 0; j < EPL; j++)
@@ -471,24 +447,21 @@ __device__ inline bool select_listed(const T *__restrict__ row, int V, int c0, i
     return true;
 }
 
-template <typename T, int LIST, bool NOTED>
+template <typename T, int LIST>
 __global__ __launch_bounds__(TOPM_WAVES *WAVE) void topm_kernel(IndexView ix, const int32_t *__restrict__ prefixes,
                                                                 int32_t stride, const int32_t *__restrict__ lens,
                                                                 const T *__restrict__ logits, int64_t row_stride, int M,
-                                                                int force_streaming, int gmax_words,
-                                                                int32_t *__restrict__ top_ids,
+                                                                int force_streaming, int32_t *__restrict__ top_ids,
                                                                 uint8_t *__restrict__ mask_V,
                                                                 uint32_t *__restrict__ mask) {
     constexpr int EPL = KeyChunk<T>::EPL;
-    extern __shared__ __align__(16) uint32_t smem[];  // max(TOPM_BINS, n_words) words, then gmax_words words
+    extern __shared__ __align__(16) uint32_t smem[];  // max(TOPM_BINS, n_words) words
     uint32_t *img = smem;                             // [n_words] the row of the mask, once the histogram is done with
     __shared__ uint32_t list_tok[LIST];
     __shared__ uint32_t sel[PPV_TOPM_MAX];
     __shared__ uint32_t seg_a[TOPM_WAVES], seg_b[TOPM_WAVES], wave_tot[TOPM_WAVES];
     __shared__ uint32_t bc[8];
-    const int head_words = ix.n_words > TOPM_BINS ? ix.n_words : TOPM_BINS;
-    const TopmLds lds = {gmax_words > 0 ? (uint16_t *)(smem + head_words) : nullptr, smem, list_tok, sel, seg_a, seg_b,
-                         wave_tot, bc};
+    const TopmLds lds = {smem, list_tok, sel, seg_a, seg_b, wave_tot, bc};
     const int b = blockIdx.x, tid = threadIdx.x, lane = tid & (WAVE - 1);
     const int wave = __builtin_amdgcn_readfirstlane(tid / WAVE);
     const int nthreads = blockDim.x, nw = nthreads / WAVE;
@@ -518,7 +491,7 @@ __global__ __launch_bounds__(TOPM_WAVES *WAVE) void topm_kernel(IndexView ix, co
     }
     // ---- select
     bool done = false;
-    if (listed) done = select_listed<T, LIST, NOTED>(row, V, c0, c1, m, lds, lane, wave, nthreads, r);
+    if (listed) done = select_listed<T, LIST>(row, V, c0, c1, m, lds, lane, wave, nthreads, r);
     if (!done) select_streaming<T>(row, V, c0, c1, m, lds, lane, wave, nthreads);
     for (int i = tid; i < n_words; i += nthreads) img[i] = 0u;   // the histogram's LDS becomes the mask row
     __syncthreads();
@@ -566,6 +539,10 @@ int topm_waves(int V, ppv_dtype dt, int B) {
     const int per = (dt == PPV_F32 ? 4 : 8) * WAVE;
     const int nc = (V + per - 1) / per;
     int cap = B <= 512 ? 8 : 4;   // measured at V = 32k: B=256: 19.5 us with 8 or 16, 24 with 4; B=1024: 37 / 42 / 67 us with 4 / 8 / 16
+    // long rows (bf16, M = 50, us per call with 4 / 8 / 16 wavefronts): V = 128k: B=128: 50 / 31 / 27, B=1024: 101 / 103 / 130;
+    // V = 256k: B=128: - / 55 / 44, B=1024: 250 / 210 / 215
+    if (nc >= 128 && B <= 256) cap = 16;
+    if (nc >= 384 && B <= 2048 && cap < 8) cap = 8;
     if (const char *e = getenv("PPV_TOPM_WAVES")) {  // tuning aid
         const int v = atoi(e);
         if (v >= 1 && v <= TOPM_WAVES) cap = v;
@@ -589,40 +566,19 @@ extern "C" ppv_status ppv_topm_mask(const ppv_index_t *ix, const int32_t *prefix
     const int V = ix->view.vocab;
     const int64_t per16 = (dt == PPV_F32) ? 4 : 8;
     if (row_stride < V || row_stride % per16 != 0 || ((uintptr_t)logits & 15u) != 0) return PPV_EINVAL;
-    int nw = topm_waves(V, dt, B);
+    const int threads = topm_waves(V, dt, B) * WAVE;
     // testing aid: PPV_TOPM_STREAMING=1 sends every row through the whole-row radix select
     const char *fs = getenv("PPV_TOPM_STREAMING");
     const int force_streaming = (fs && fs[0] == '1') ? 1 : 0;
-    const size_t head = (size_t)(ix->view.n_words > TOPM_BINS ? ix->view.n_words : TOPM_BINS) * sizeof(uint32_t);
-    // Room for the group maxima (two bytes per 16-byte group of the row), for rows so long that a second pass
-    // would come from HBM again.  Measured (bf16, M = 50, us per call, second pass / notes): V = 256k: B = 128:
-    // 56 / 45, B = 1,024: 269 / 187; V = 128k: B = 128: 32 / 34, B = 1,024: 100 / 100; V = 32k, B = 4,096: 100 / 94
-    // (M = 1,000: 134 / 144) -- the notes cost LDS, hence rows in flight, and pay only for the longest rows.
-    const bool small_list = M <= 128 && V <= 65536;
-    const int nc = (int)((V + per16 * WAVE - 1) / (per16 * WAVE));
-    int gmax_words = nc * WAVE / 2;
-    bool want = nc >= TOPM_NOTED_CHUNKS;
-    if (const char *e = getenv("PPV_TOPM_NOTED")) want = e[0] == '1';   // testing aid: 1 = wherever possible, 0 = never
-    if (!want || (nc + nw - 1) / nw <= 4 || head + (size_t)gmax_words * 4 > TOPM_GMAX_LDS) gmax_words = 0;
-    const size_t lds = head + (size_t)gmax_words * sizeof(uint32_t);
-    if (gmax_words > 0) {
-        // the notes take LDS: keep at least sixteen wavefronts on a compute unit by giving a row more of them
-        const size_t per_wg = lds + (size_t)(small_list ? TOPM_LIST_SMALL : TOPM_LIST_BIG) * 4 + PPV_TOPM_MAX * 4 + 512;
-        while (nw < TOPM_WAVES && (TOPM_CU_LDS / per_wg) * (size_t)nw < 16 && (nc + 2 * nw - 1) / (2 * nw) > 4) nw *= 2;
-    }
-    const int threads = nw * WAVE;
+    const size_t lds = (size_t)(ix->view.n_words > TOPM_BINS ? ix->view.n_words : TOPM_BINS) * sizeof(uint32_t);
     const dim3 grid((unsigned)B), block(threads);
     hipStream_t hs = (hipStream_t)stream;
-#define PPV_LAUNCH_TOPM_N(T, LIST, NOTED)                                                                             \
-    hipLaunchKernelGGL((topm_kernel<T, LIST, NOTED>), grid, block, lds, hs, ix->view, prefixes, prefix_stride, lens,   \
-                       (const T *)logits, row_stride, M, force_streaming, gmax_words, top_ids, mask_V, mask)
 #define PPV_LAUNCH_TOPM(T, LIST)                                                                                      \
-    do {                                                                                                              \
-        if (gmax_words > 0) PPV_LAUNCH_TOPM_N(T, LIST, true);                                                          \
-        else PPV_LAUNCH_TOPM_N(T, LIST, false);                                                                        \
-    } while (0)
+    hipLaunchKernelGGL((topm_kernel<T, LIST>), grid, block, lds, hs, ix->view, prefixes, prefix_stride, lens,          \
+                       (const T *)logits, row_stride, M, force_streaming, top_ids, mask_V, mask)
     // a few hundred tokens reach the bound when M is small and the row not too long (the bound's bin holds a share
     // of the row): then a quarter of the LDS does, and more rows fit a compute unit
+    const bool small_list = M <= 128 && V <= 65536;
     if (dt == PPV_F32) {
         if (small_list) PPV_LAUNCH_TOPM(float, TOPM_LIST_SMALL);
         else PPV_LAUNCH_TOPM(float, TOPM_LIST_BIG);
@@ -631,7 +587,6 @@ extern "C" ppv_status ppv_topm_mask(const ppv_index_t *ix, const int32_t *prefix
         else PPV_LAUNCH_TOPM(uint16_t, TOPM_LIST_BIG);
     }
 #undef PPV_LAUNCH_TOPM
-#undef PPV_LAUNCH_TOPM_N
     PPV_HIP_TRY(hipGetLastError());
     return PPV_OK;
 }
