@@ -989,7 +989,9 @@ int waves_for(int V, ppv_dtype dt, int B) {
     const int tile = (dt == PPV_F32) ? TileGeom<float>::TILE : TileGeom<uint16_t>::TILE;
     const int nt = (V + tile - 1) / tile;
     int cap = B <= 128 ? 16 : (B <= 512 ? 8 : 4);
-    if (nt >= 64 && B <= 256) cap = 16;   // long rows in a small batch: one row per compute unit, all of it in flight
+    // long rows in a small batch: one row per compute unit, all of it in flight (constrained_sample, B = 256, us per
+    // call with 8 / 16 wavefronts: 32 tiles: 13.2 / 12.0 (fp32 V = 32k), 15.2 / 14.2 (bf16 V = 64k); 63 tiles: 23.6 / 20.6)
+    if (nt >= 32 && B <= 256) cap = 16;
     if (const char *e = getenv("PPV_WAVES_PER_ROW")) {  // tuning aid
         const int v = atoi(e);
         if (v >= 1 && v <= MAX_WAVES) cap = v;
