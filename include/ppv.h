@@ -187,6 +187,8 @@ ppv_status ppv_decode_begin(const ppv_index_t *index, const int32_t *prefixes, i
  *   state     uint32[B, PPV_STATE_WORDS] from ppv_decode_begin, in/out; or NULL: the prefix is then
  *             located from the root in every call (same results, one index level per token slower).
  *             With a state the caller must not change prefixes/lens of active rows between steps.
+ *             Words that cannot be a cursor of this index (never initialised, or written for another
+ *             index) are recognised by range checks: such a row samples nothing (ids[b] = -1) and retires.
  *   logits, dt, row_stride, uniforms, temperature   as in constrained_sample; V is the index's vocabulary
  *   ids         int32[B] or NULL: token sampled this step (-1 if none); untouched for inactive rows
  *   logZ_valid  float[B] or NULL: this step's log valid mass; untouched for inactive rows

@@ -462,6 +462,7 @@ ppv_status finish_heavy(ppv_index *ix, uint32_t G, int32_t vocab, hipStream_t st
     ix->view.heavy_bits = ix->d_heavy_bits;
     ix->view.heavy_rank = ix->d_heavy_rank;
     ix->view.heavy_limit = heavy_limit;
+    ix->view.n_heavy = n_heavy;
     ix->view.heavy_min = heavy_min;
     ix->view.n_words = n_words;
     return PPV_OK;

@@ -47,6 +47,7 @@ struct IndexView {
     uint32_t lookup_fp_mask;     // fingerprint bits in use (all of them; 0 in a test mode that makes every probe a false hit)
     uint32_t heavy_limit;        // nodes >= heavy_limit are not heavy
     uint32_t heavy_min;          // a node is heavy iff it has more than heavy_min children
+    uint32_t n_heavy;            // heavy nodes, i.e. rows of heavy_bits / heavy_rank
     uint32_t n_nodes;            // including node 0
     uint32_t n_rows;             // |S| after de-duplication
     int32_t vocab;

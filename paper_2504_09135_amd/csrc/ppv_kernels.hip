@@ -856,6 +856,18 @@ __global__ __launch_bounds__(LOOP ? LOOP_WAVES * WAVE : MAX_WAVES * WAVE) void d
         st.slot = (st.node != PPV_NO_SLOT && st.ce - st.cb > ix.heavy_min) ? heavy_slot_of(ix, st.node) : PPV_NO_SLOT;
         __syncthreads();
     }
+    // The cursor comes from memory that the caller owns.  One that cannot be a cursor of this index (a state
+    // that never went through ppv_decode_begin, or of another index) must not send a load out of bounds:
+    // such a row is treated as having no valid token and retires.
+    {
+        const uint32_t nc = st.ce - st.cb;
+        const bool sane = st.node < ix.n_nodes && st.cb <= st.ce && st.ce <= ix.n_nodes &&
+                          (st.slot == PPV_NO_SLOT ? nc <= ix.heavy_min : st.slot < ix.n_heavy);
+        if (!sane) {
+            st.cb = st.ce = 0u;
+            st.slot = PPV_NO_SLOT;
+        }
+    }
     // running log importance score (tid 0); started from the stored value so that the additions happen in
     // the same order as with one launch per step
     float lx = (LOOP && logx && tid == 0) ? logx[b] : 0.f;
@@ -902,6 +914,7 @@ __global__ __launch_bounds__(LOOP ? LOOP_WAVES * WAVE : MAX_WAVES * WAVE) void d
                     const uint32_t wv = image[id >> 5];
                     nx.node = cb + ix.heavy_rank[(size_t)slot * (size_t)ix.n_words + (id >> 5)] +
                               (uint32_t)__popc(wv & ((1u << (id & 31)) - 1u));
+                    if (nx.node >= ix.n_nodes) nx.node = ix.n_nodes - 1u;   // (only a cursor that paired a slot with another node's children)
                     const NodeEnt e0 = ix.ent[nx.node], e1 = ix.ent[nx.node + 1];
                     tokw = e0.tok;
                     nx.cb = e0.child;

@@ -646,6 +646,49 @@ def test_nan_and_infinite_logits_do_not_derail_a_row(dtype):
     assert np.array_equal(sid[clean], sidc) and np.array_equal(top[clean], topc)
 
 
+@pytest.mark.parametrize("loop", [False, True])
+def test_a_state_that_is_no_cursor_retires_the_row(loop):
+    """The state is the caller's memory.  Words that are no cursor of this index (never initialised, or of another
+    index) are recognised by the kernel's own range checks: the row samples nothing (id -1) and retires; the rows
+    beside it, and later calls on the index, are not affected."""
+    cfg, S, trie, index = setup_case("C3s")
+    B, L = 32, index.l_max
+    rng = np.random.default_rng(8)
+    P = torch.full((B, L), W.PAD_TOKEN, dtype=torch.int32, device=DEV)
+    lens = torch.zeros(B, dtype=torch.int32, device=DEV)
+    act = torch.zeros(B, dtype=torch.uint8, device=DEV)
+    state = torch.zeros((B, ppv.PPV_STATE_WORDS), dtype=torch.int32, device=DEV)
+    logx = torch.zeros(B, dtype=torch.float32, device=DEV)
+    ppv.ppv_decode_begin(index, P, lens, state, act, logx)
+    good = state.cpu().numpy().copy()
+    bad = good.copy()
+    junk = rng.integers(0, 2 ** 32, size=(B, ppv.PPV_STATE_WORDS), dtype=np.uint64).astype(np.uint32).view(np.int32)
+    rows = np.arange(0, B, 2)
+    bad[rows] = junk[rows]
+    bad[2] = [5, 10, 3, -1]                      # children range that ends before it begins
+    bad[4] = [0, 0, 2_000_000_000, -1]           # a list far beyond the index
+    bad[6] = [1, 1, 2, 123456789]                # an image slot that does not exist
+    bad[8] = [-2, 0, 1, -1]                      # a node number beyond the index
+    state.copy_(to_dev(bad))
+    n = 3
+    logits = torch.stack([logits_to_dev(cfg, W.make_logits(cfg, batch=B, step=300 + s)) for s in range(n)])
+    un = torch.stack([to_dev(W.make_uniforms(cfg, batch=B, step=300 + s)) for s in range(n)])
+    ids = torch.full((n, B), -5, dtype=torch.int32, device=DEV)
+    if loop:
+        ppv.ppv_decode_loop(index, P, lens, act, logits, un, ids, None, logx, state=state)
+    else:
+        for s in range(n):
+            ppv.ppv_decode_step(index, P, lens, act, logits[s], un[s], ids[s], None, logx, state=state)
+    torch.cuda.synchronize()
+    gi, ga, gl = ids.cpu().numpy(), act.cpu().numpy(), lens.cpu().numpy()
+    assert (gi[0, rows] == -1).all() and (ga[rows] == 0).all() and (gl[rows] == 0).all()
+    others = np.setdiff1d(np.arange(B), rows)
+    assert (gi[0, others] >= 0).all() and (gl[others] >= 1).all()
+    # the index is as good as before
+    pb = W.make_prefix_batch(cfg, S, index=4)
+    assert_query_parity(index, trie, pb.prefixes, pb.lens)
+
+
 def test_degenerate_sets():
     """One member; one token vocabulary; nothing but duplicates; one long chain; a set that is all single tokens."""
     cases = [
