@@ -349,7 +349,7 @@ __device__ inline int locate_in_tile(const RawTile &rt, uint32_t tile_word, int 
                     if (e[k] > 0.f && c > target) { id = k; break; }
                 }
                 if (id < 0) id = my_last;  // rounding inside the group
-                id += first_tok + lane * G::EPL;
+                if (id >= 0) id += first_tok + lane * G::EPL;   // (-1: a target below zero met a lane without a valid token)
             }
             return lane_value(id, l);
         }

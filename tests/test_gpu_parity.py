@@ -469,6 +469,29 @@ def test_sample_wide_dynamic_range_inside_tiles(dtype, V):
         check_sample_rows(dtype, r, lambda i: mask[b], un[b:b + 1], gid[b:b + 1], glz[b:b + 1], gla[b:b + 1], rows=[b])
 
 
+def test_uniforms_outside_the_unit_interval_stay_defined():
+    """uniforms are in [0, 1) by contract; 1, 2, -0.5, NaN and inf must still end in a valid token or -1."""
+    for name in ("C2", "C1", "C5s"):                  # list and image rows, one-tile kernel, long rows
+        cfg, S, trie, index = setup_case(name)
+        pb = W.make_prefix_batch(cfg, S, index=6)
+        dmask, _ = assert_query_parity(index, trie, pb.prefixes, pb.lens)
+        full = trie.query(pb.prefixes, pb.lens).mask
+        B = pb.prefixes.shape[0]
+        un = np.resize(np.array([1.0, 2.0, -0.5, np.nan, np.inf, -np.inf, 0.999999], np.float32), B)
+        ids, lzv, _ = gpu_sample(cfg, logits_to_dev(cfg, W.make_logits(cfg, step=6)), dmask, un)
+        ref = trie.step(pb.prefixes, pb.lens, W.logits_as_f32(cfg, W.make_logits(cfg, step=6)),
+                        np.full(B, 0.5, np.float32), threads=8)
+        for b in range(B):
+            assert ids[b] == -1 or full[b, ids[b]] == 1, (name, b, ids[b], un[b])
+            if ref.ids[b] >= 0 and un[b] >= 1.0:       # at or past the end of the CDF: the last valid token of positive weight
+                lf = W.logits_as_f32(cfg, W.make_logits(cfg, step=6))[b]
+                pos = np.nonzero((full[b] == 1) & (lf > -np.inf))[0]
+                assert ids[b] == pos[-1], (name, b)
+        fin = np.isfinite(ref.logZ_valid)
+        tol = 1e-5 if cfg.dtype == "f32" else 1e-3     # the mass does not depend on the uniform
+        assert np.all(np.abs(lzv[fin] - ref.logZ_valid[fin]) <= tol * np.maximum(1.0, np.abs(ref.logZ_valid[fin])))
+
+
 def test_bf16_sample_matches_f32_on_same_values():
     cfg, S, trie, index = setup_case("C2")
     pb = W.make_prefix_batch(cfg, S, index=8)
