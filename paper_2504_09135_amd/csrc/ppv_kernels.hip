@@ -116,6 +116,43 @@ __global__ __launch_bounds__(MASK_THREADS) void mask_kernel(IndexView ix, const 
     }
 }
 
+// The same for vocabularies of at most 2,048 tokens (a mask row is at most 64 words: one word per lane): one
+// wavefront per prefix, four prefixes per workgroup, no LDS and no barrier.  A listed node has at most V / 32 <= 64
+// children here, one per lane; each child's bit is set by the lane that holds its word.
+constexpr int MASK_SMALL_WORDS = WAVE;
+__global__ __launch_bounds__(MASK_THREADS) void mask_rows_kernel(IndexView ix, const int32_t *__restrict__ prefixes,
+                                                                 int32_t stride, const int32_t *__restrict__ lens, int B,
+                                                                 uint32_t *__restrict__ mask,
+                                                                 uint32_t *__restrict__ range_lo,
+                                                                 uint32_t *__restrict__ range_hi,
+                                                                 uint8_t *__restrict__ member) {
+    const int lane = threadIdx.x & (WAVE - 1);
+    const int b = blockIdx.x * (MASK_THREADS / WAVE) + threadIdx.x / WAVE;
+    if (b >= B) return;  // uniform per wavefront
+    const int n_words = ix.n_words;
+    const int32_t mine = first_tokens(prefixes + (size_t)b * (size_t)stride, stride, lane);
+    int t = lens[b];
+    t = t < 0 ? 0 : (t > stride ? stride : t);
+    const Walk w = walk_prefix(ix, prefixes + (size_t)b * (size_t)stride, mine, t, lane);
+    if (lane == 0) {
+        if (range_lo) range_lo[b] = w.lo;
+        if (range_hi) range_hi[b] = w.hi;
+        if (member) member[b] = w.member ? 1 : 0;
+    }
+    uint32_t word = 0u;
+    const uint32_t nchild = w.found ? w.ce - w.cb : 0u;
+    if (nchild > ix.heavy_min) {   // ready-made image
+        if (lane < n_words) word = ix.heavy_bits[(size_t)heavy_slot_of(ix, w.node) * (size_t)n_words + lane];
+    } else if (nchild > 0u) {      // nchild <= heavy_min <= 64
+        const uint32_t tok = (uint32_t)lane < nchild ? (ix.ent[w.cb + (uint32_t)lane].tok & PPV_NODE_TOKEN) : 0u;
+        for (uint32_t i = 0; i < nchild; i++) {   // uniform trip count
+            const uint32_t v = (uint32_t)__builtin_amdgcn_readlane((int)tok, (int)i);
+            if ((uint32_t)lane == (v >> 5)) word |= 1u << (v & 31u);
+        }
+    }
+    if (lane < n_words) mask[(size_t)b * (size_t)n_words + lane] = word;
+}
+
 // ------------------------------------------------------------------------------------------
 // Tiles.  A tile is what one wavefront loads with four 16-byte loads per lane: 2048 bf16 or 1024
 // fp32 tokens.  Load j of lane l holds the EPL consecutive tokens starting at
@@ -1060,9 +1097,16 @@ extern "C" ppv_status ppv_next_token_mask(const ppv_index_t *ix, const int32_t *
     if (!ix || B < 0 || prefix_stride < 0) return PPV_EINVAL;
     if (B == 0) return PPV_OK;  // nothing to do; the (possibly null) buffers are not looked at
     if (!prefixes || !lens || !mask) return PPV_EINVAL;
-    const size_t lds = ((size_t)ix->view.n_words + 4) * sizeof(uint32_t);
-    hipLaunchKernelGGL(mask_kernel, dim3((unsigned)B), dim3(MASK_THREADS), lds, (hipStream_t)stream, ix->view,
-                       prefixes, prefix_stride, lens, mask, range_lo, range_hi, member);
+    if (ix->view.n_words <= MASK_SMALL_WORDS) {
+        const int rows_per_wg = MASK_THREADS / WAVE;
+        hipLaunchKernelGGL(mask_rows_kernel, dim3((unsigned)((B + rows_per_wg - 1) / rows_per_wg)), dim3(MASK_THREADS), 0,
+                           (hipStream_t)stream, ix->view, prefixes, prefix_stride, lens, B, mask, range_lo, range_hi,
+                           member);
+    } else {
+        const size_t lds = ((size_t)ix->view.n_words + 4) * sizeof(uint32_t);
+        hipLaunchKernelGGL(mask_kernel, dim3((unsigned)B), dim3(MASK_THREADS), lds, (hipStream_t)stream, ix->view,
+                           prefixes, prefix_stride, lens, mask, range_lo, range_hi, member);
+    }
     PPV_HIP_TRY(hipGetLastError());
     return PPV_OK;
 }
