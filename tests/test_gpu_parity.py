@@ -747,6 +747,60 @@ def test_degenerate_sets():
         index.free()
 
 
+def test_members_longer_than_a_wavefront():
+    """Members of 80 to 150 tokens behind a common stem of 70: prefixes of 63, 64, 65 and more tokens (the look-up
+    covers the first 64, the descent goes on from there), wrong tokens beyond position 64, and the decode loop to the end."""
+    rng = np.random.default_rng(31)
+    V = 50
+    stem = rng.integers(0, V, 70).tolist()
+    seqs = [stem + rng.integers(0, V, int(rng.integers(10, 81))).tolist() for _ in range(300)]
+    seqs += [rng.integers(0, V, int(rng.integers(1, 140))).tolist() for _ in range(200)]
+    seqs += [stem[:40], stem[:64], stem[:65]]
+    S = W.constraint_set_from_lists(seqs, V)
+    trie = oracle.Trie(S.tokens, S.offsets, V)
+    index = ppv.ppv_build_index(S.tokens, S.offsets, V)
+    assert index.l_max == max(map(len, seqs)) and index.n_distinct == trie.n_members
+    queries = []
+    for s in seqs[:40]:
+        for k in (0, 10, 63, 64, 65, 70, 71, 79, len(s) - 1, len(s)):
+            queries.append(s[:k])
+        bad = list(s)
+        bad[66] = (bad[66] + 1) % V
+        queries.append(bad[:75])
+        bad = list(s)
+        bad[-1] = (bad[-1] + 1) % V
+        queries.append(bad)
+        queries.append(s + [3])
+    stride = max(map(len, queries))
+    P = np.full((len(queries), stride), W.PAD_TOKEN, np.int32)
+    L = np.array([len(q) for q in queries], np.int32)
+    for i, q in enumerate(queries):
+        P[i, :len(q)] = q
+    assert_query_parity(index, trie, P, L)
+    # the whole loop, one launch, from the empty prefix
+    B, Lm = 64, index.l_max
+    Vp = (V + 3) // 4 * 4
+    lg = np.zeros((Lm, B, Vp), np.float32)
+    lg[:, :, :V] = rng.normal(0, 1, size=(Lm, B, V))
+    un = rng.random((Lm, B)).astype(np.float32)
+    dP = torch.full((B, Lm), W.PAD_TOKEN, dtype=torch.int32, device=DEV)
+    dL = torch.zeros(B, dtype=torch.int32, device=DEV)
+    dA = torch.zeros(B, dtype=torch.uint8, device=DEV)
+    state = torch.zeros((B, ppv.PPV_STATE_WORDS), dtype=torch.int32, device=DEV)
+    logx = torch.zeros(B, dtype=torch.float32, device=DEV)
+    ppv.ppv_decode_begin(index, dP, dL, state, dA, logx)
+    ppv.ppv_decode_loop(index, dP, dL, dA, to_dev(lg)[:, :, :V], to_dev(un), None, None, logx, state=state)
+    torch.cuda.synchronize()
+    res = oracle.decode_loop(trie, B, lambda s, *_: lg[s, :, :V], lambda s: un[s], threads=8)
+    gL, gP = dL.cpu().numpy(), dP.cpu().numpy()
+    same = sum(int(gL[b] == res.lens[b] and np.array_equal(gP[b, :gL[b]], res.seqs[b, :res.lens[b]])) for b in range(B))
+    assert same >= B - 1, same                                 # (a uniform on a CDF boundary may split one row)
+    assert not dA.cpu().numpy().any() and (gL > 64).any()
+    rows = [b for b in range(B) if gL[b] == res.lens[b] and np.array_equal(gP[b, :gL[b]], res.seqs[b, :res.lens[b]])]
+    assert np.allclose(logx.cpu().numpy()[rows], res.logx[rows], rtol=1e-4, atol=1e-4)
+    index.free()
+
+
 def test_calls_on_two_streams_at_once():
     """An index is immutable after it is built: mask + sample pipelines on two streams, interleaved launch by
     launch over the same index, give what each gives alone."""
