@@ -260,6 +260,8 @@ def main() -> int:
     roofline = {"bound": "hbm", "kernel": "decode_kernel<bf16, per-step>", "achieved": round(achieved, 1),
                 "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
                 "traffic": TRAFFIC_BYTES_PER_LAUNCH.get((cfg.name, B)),
+                "traffic_source": ("profiles/decode_step_C3_B256.md: counters of an earlier build of this kernel with the "
+                                   "same data movement" if (cfg.name, B) in TRAFFIC_BYTES_PER_LAUNCH else None),
                 "avg_launch_us": round(avg_launch_s * 1e6, 2), "launches_per_step": n_launch,
                 "bytes_per_launch": int(bytes_per_launch_avg),
                 "rows_per_launch_avg": round(float(active_per_step.mean()), 1),
