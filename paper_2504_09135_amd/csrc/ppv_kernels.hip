@@ -508,7 +508,8 @@ __device__ inline void stream_tiles(const T *__restrict__ row, int V, const RawT
 //   mode         VALID_LIST: sh.list_tok[0..n_list) holds the valid tokens (in LDS, barrier done)
 //                VALID_IMAGE: image (global memory, V bits) is the valid set
 //                VALID_NONE: the valid set is empty
-template <typename T, bool PIPE, typename SH>
+//   ALL          every thread gets the result (one more barrier); otherwise only wavefront 0 does
+template <typename T, bool PIPE, typename SH, bool ALL>
 __device__ inline RowOut row_sample(const T *__restrict__ row, int V, const RawTile &first, int mode, int n_list,
                                     const uint32_t *__restrict__ image, float u, SH &sh, int tid, int nw,
                                     const Temper &tp, const T *__restrict__ next_row = nullptr,
@@ -566,6 +567,16 @@ __device__ inline RowOut row_sample(const T *__restrict__ row, int V, const RawT
     if (next_row && wave < nt) load_tile<T>(next_row, V, wave, lane, *next_first);
     __syncthreads();
 
+    // Nobody but wavefront 0 has anything left to do when the result goes to it alone and the set is not an
+    // image (whose rare second pass needs every wavefront): the others leave its SIMD to it.
+    if (!ALL && mode != VALID_IMAGE && wave != 0) {
+        RowOut none;
+        none.id = -1;
+        none.pos = -1;
+        none.logZ_valid = -INFINITY;
+        none.logZ_all = 0.f;
+        return none;
+    }
     // ---- combine (every wave computes the same row totals from LDS; cheap, and saves a broadcast)
     float M = -INFINITY;
     for (int k = lane; k < nt; k += WAVE) M = fmaxf(M, sh.tile_m[k]);
@@ -621,6 +632,11 @@ __device__ inline RowOut row_sample(const T *__restrict__ row, int V, const RawT
     }
 
     // ---- locate: wave 0
+    RowOut out;
+    out.id = -1;
+    out.pos = -1;
+    out.logZ_valid = -INFINITY;
+    out.logZ_all = 0.f;
     if (wave == 0) {
         const float l2za = fast_log2((float)za);
         int id = -1, pos = -1;
@@ -704,19 +720,24 @@ __device__ inline RowOut row_sample(const T *__restrict__ row, int V, const RawT
                 }
             }
         }
-        if (lane == 0) {
-            sh.bc_i[0] = id;
-            sh.bc_i[1] = pos;
-            sh.bc_f[0] = lzv;
-            sh.bc_f[1] = fmaf(M, tp.inv, LN2F * l2za);
+        out.id = id;   // all four are wave-uniform
+        out.pos = pos;
+        out.logZ_valid = lzv;
+        out.logZ_all = fmaf(M, tp.inv, LN2F * l2za);
+        if (ALL && lane == 0) {
+            sh.bc_i[0] = out.id;
+            sh.bc_i[1] = out.pos;
+            sh.bc_f[0] = out.logZ_valid;
+            sh.bc_f[1] = out.logZ_all;
         }
     }
-    __syncthreads();
-    RowOut out;
-    out.id = sh.bc_i[0];
-    out.pos = sh.bc_i[1];
-    out.logZ_valid = sh.bc_f[0];
-    out.logZ_all = sh.bc_f[1];
+    if (ALL) {
+        __syncthreads();
+        out.id = sh.bc_i[0];
+        out.pos = sh.bc_i[1];
+        out.logZ_valid = sh.bc_f[0];
+        out.logZ_all = sh.bc_f[1];
+    }
     return out;
 }
 
@@ -772,7 +793,7 @@ __global__ __launch_bounds__(SMALL ? SMALL_TILES * WAVE : MAX_WAVES * WAVE) void
         }
         __syncthreads();
     }
-    RowOut r = row_sample<T, PIPE, SH>(row, V, first, mode, mode == VALID_LIST ? total : 0, mrow, uniforms[b], sh, tid, nw, tp);
+    RowOut r = row_sample<T, PIPE, SH, false>(row, V, first, mode, mode == VALID_LIST ? total : 0, mrow, uniforms[b], sh, tid, nw, tp);
     if (tid == 0) {
         ids[b] = r.id;
         logZ_valid[b] = r.logZ_valid;
@@ -869,6 +890,9 @@ __global__ __launch_bounds__(LOOP ? LOOP_WAVES * WAVE : MAX_WAVES * WAVE) void d
     RowState st;
     if (state) st = state[b];
     float u = uniforms[b];
+    // the running score is read now, not when it is updated at the very end (a load there would stand between the
+    // sample and the kernel's last store); unconditional, from an address that always exists
+    const float logx_in = (logx ? logx : uniforms)[b];
     if (!on) return;  // uniform for the workgroup
     const int V = ix.vocab;
     const T *row = logits + (size_t)b * (size_t)row_stride;
@@ -907,7 +931,7 @@ __global__ __launch_bounds__(LOOP ? LOOP_WAVES * WAVE : MAX_WAVES * WAVE) void d
     }
     // running log importance score (tid 0); started from the stored value so that the additions happen in
     // the same order as with one launch per step
-    float lx = (LOOP && logx && tid == 0) ? logx[b] : 0.f;
+    float lx = (LOOP && logx) ? logx_in : 0.f;
     bool done = false;
     for (int s = 0; s < n_steps; s++) {
         const uint32_t cb = st.cb, ce = st.ce, slot = st.slot;
@@ -932,7 +956,7 @@ __global__ __launch_bounds__(LOOP ? LOOP_WAVES * WAVE : MAX_WAVES * WAVE) void d
         const T *next_row = more ? row + step_stride : nullptr;
         float next_u = 0.f;
         if (more) next_u = uniforms[(size_t)(s + 1) * (size_t)B + b];
-        RowOut r = row_sample<T, PIPE, RowShared>(row, V, first, mode, mode == VALID_LIST ? nchild : 0, image, u, sh, tid, nw,
+        RowOut r = row_sample<T, PIPE, RowShared, LOOP>(row, V, first, mode, mode == VALID_LIST ? nchild : 0, image, u, sh, tid, nw,
                                                   tp, next_row, &next_first);
         if (tid == 0) {
             const bool room = t < stride;
@@ -975,7 +999,7 @@ __global__ __launch_bounds__(LOOP ? LOOP_WAVES * WAVE : MAX_WAVES * WAVE) void d
                 if (id >= 0) {
                     lens[b] = t + 1;
                     if (state) state[b] = nx;
-                    if (logx) logx[b] += lx;
+                    if (logx) logx[b] = logx_in + lx;
                 }
                 if (done) active[b] = 0;
             }
