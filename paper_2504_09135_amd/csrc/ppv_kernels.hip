@@ -441,10 +441,12 @@ enum ValidMode { VALID_NONE = 0, VALID_LIST = 1, VALID_IMAGE = 2 };
 // counters leave the younger loads in flight (a conditional load anywhere on the way to a use
 // makes it wait for everything).  The row's ragged last tile, if any, is taken with the guarded
 // loader by the wave whose turn it is.
-template <typename T, bool IMAGE, bool PIPE, typename SH>
+// `mid` is work of the caller's that needs no tile (the sums over the listed tokens): it is run once, at the first
+// point where this wavefront has just asked for a tile and would only wait for it; never, if there is no such point.
+template <typename T, bool IMAGE, bool PIPE, typename SH, typename MID>
 __device__ inline void stream_tiles(const T *__restrict__ row, int V, const RawTile &first,
                                     const uint32_t *__restrict__ image, SH &sh, int lane, int wave_v,
-                                    int nw, const Temper &tp) {
+                                    int nw, const Temper &tp, MID &mid) {
     using G = TileGeom<T>;
     const int wave = __builtin_amdgcn_readfirstlane(wave_v);   // scalar: loop control stays uniform
     const int nt = (V + G::TILE - 1) / G::TILE;
@@ -467,11 +469,14 @@ __device__ inline void stream_tiles(const T *__restrict__ row, int V, const RawT
     // this wave's full tiles are wave + i*nw for i in [0, cnt); `first` is i = 0 (or the ragged tile)
     const int cnt = wave < nfull ? (nfull - wave + nw - 1) / nw : 0;
     int i = 0;
+    bool mid_done = false;
     RawTile X = first, Y, Z;   // the same three register tiles serve every path below
     if (IMAGE) X.word = tile_mask_word<T>(image, wave, lane, V);
     if (PIPE && cnt >= 6) {
         fetch(Y, wave + nw);
         fetch(Z, wave + 2 * nw);
+        mid();
+        mid_done = true;
         while (i + 5 < cnt) {
             reduce_tile(X, wave + i * nw);
             fetch(X, wave + (i + 3) * nw);
@@ -493,6 +498,10 @@ __device__ inline void stream_tiles(const T *__restrict__ row, int V, const RawT
     // cost 30 more registers and was slower), and perhaps the ragged tail
     for (; i < cnt; i++) {
         fetch(Z, wave + i * nw);
+        if (!mid_done) {
+            mid();
+            mid_done = true;
+        }
         reduce_tile(Z, wave + i * nw);
     }
     if (nfull < nt && nfull % nw == wave && wave != nfull) {
@@ -531,11 +540,12 @@ __device__ inline RowOut row_sample(const T *__restrict__ row, int V, const RawT
         }
     }
 
-    // ---- stream: every tile once
-    if (mode == VALID_IMAGE) stream_tiles<T, true, PIPE, SH>(row, V, first, image, sh, lane, wave, nw, tp);
-    else stream_tiles<T, false, PIPE, SH>(row, V, first, image, sh, lane, wave, nw, tp);
-    // ---- list path, part 2: sums per slice of 64 listed tokens, relative to the slice maximum
-    if (mode == VALID_LIST) {
+    // ---- list path, part 2: sums per slice of 64 listed tokens, relative to the slice maximum.  Run from inside
+    // the stream, while the wavefront waits for a tile it has just asked for; after it when there is no such wait.
+    bool list_done = false;
+    auto list_sums = [&]() {
+        list_done = true;
+        if (mode != VALID_LIST) return;
         for (int s = wave; s < ns; s += nw) {
             const int i = s * WAVE + lane;
             float x = gx;
@@ -561,7 +571,11 @@ __device__ inline RowOut row_sample(const T *__restrict__ row, int V, const RawT
                 sh.slice_z[s] = z;
             }
         }
-    }
+    };
+    // ---- stream: every tile once
+    if (mode == VALID_IMAGE) stream_tiles<T, true, PIPE, SH>(row, V, first, image, sh, lane, wave, nw, tp, list_sums);
+    else stream_tiles<T, false, PIPE, SH>(row, V, first, image, sh, lane, wave, nw, tp, list_sums);
+    if (!list_done) list_sums();
     // (decode loop) the row of the next step is known already: ask for this wave's first tile of it
     // now, so that it travels while this row is combined and sampled
     if (next_row && wave < nt) load_tile<T>(next_row, V, wave, lane, *next_first);
@@ -587,11 +601,11 @@ __device__ inline RowOut row_sample(const T *__restrict__ row, int V, const RawT
         if (m != -INFINITY) {
             const double sc = (double)exp_scale(m - M, tp.c);
             za += (double)sh.tile_zall[k] * sc;
-            zv += (double)sh.tile_zval[k] * sc;
+            if (mode == VALID_IMAGE) zv += (double)sh.tile_zval[k] * sc;   // (the other modes have no per-tile valid sums)
         }
     }
     za = wave_sum(za);
-    zv = wave_sum(zv);
+    if (mode == VALID_IMAGE) zv = wave_sum(zv);
     float R = M;  // reference of the valid sums of the image path
 
     // ---- image path, rare case: the valid mass is below 2^-18 of the row's largest term, so sums
@@ -683,29 +697,45 @@ __device__ inline RowOut row_sample(const T *__restrict__ row, int V, const RawT
             }
         } else if (mode == VALID_LIST) {
             float Mv = -INFINITY;
-            if (lane < ns) Mv = sh.slice_m[lane];
-            Mv = wave_max(Mv);
+            if (ns == 1) {   // one slice (at most 64 listed tokens, the usual case): nothing to scan over
+                Mv = sh.slice_m[0];
+            } else {
+                if (lane < ns) Mv = sh.slice_m[lane];
+                Mv = wave_max(Mv);
+            }
             if (Mv != -INFINITY) {
-                double w = 0.0, sc = 0.0;
-                if (lane < ns && sh.slice_m[lane] != -INFINITY) {
-                    sc = (double)exp_scale(sh.slice_m[lane] - Mv, tp.c);
-                    w = (double)sh.slice_z[lane] * sc;
-                }
-                const double incl = wave_incl_scan(w);
-                const double zvl = last_lane(incl);
-                lzv = fmaf(Mv - M, tp.inv, LN2F * (fast_log2((float)zvl) - l2za));
-                const double tau = (double)u * zvl;
-                const uint64_t cross = __ballot(incl > tau);
-                const uint64_t have = __ballot(w > 0.0);
                 int s;
-                double target;
-                if (cross) {
-                    s = __ffsll((long long)cross) - 1;
-                    target = (tau - lane_value(incl - w, s)) / lane_value(sc, s);
+                double target, zvl;
+                if (ns == 1) {   // the general case below, written out for one slice: same values bit for bit
+                    zvl = (double)sh.slice_z[0];
+                    const double tau = (double)u * zvl;
+                    if (zvl > tau) {
+                        s = 0;
+                        target = tau;
+                    } else {
+                        s = zvl > 0.0 ? 0 : -1;
+                        target = INFINITY;
+                    }
                 } else {
-                    s = have ? 63 - __clzll((long long)have) : -1;
-                    target = INFINITY;
+                    double w = 0.0, sc = 0.0;
+                    if (lane < ns && sh.slice_m[lane] != -INFINITY) {
+                        sc = (double)exp_scale(sh.slice_m[lane] - Mv, tp.c);
+                        w = (double)sh.slice_z[lane] * sc;
+                    }
+                    const double incl = wave_incl_scan(w);
+                    zvl = last_lane(incl);
+                    const double tau = (double)u * zvl;
+                    const uint64_t cross = __ballot(incl > tau);
+                    const uint64_t have = __ballot(w > 0.0);
+                    if (cross) {
+                        s = __ffsll((long long)cross) - 1;
+                        target = (tau - lane_value(incl - w, s)) / lane_value(sc, s);
+                    } else {
+                        s = have ? 63 - __clzll((long long)have) : -1;
+                        target = INFINITY;
+                    }
                 }
+                lzv = fmaf(Mv - M, tp.inv, LN2F * (fast_log2((float)zvl) - l2za));
                 // (no slice or no token qualifies only when NaNs have poisoned the sums: then nothing is sampled,
                 // and above all no position outside the list is ever formed)
                 const int i = s * WAVE + lane;
