@@ -1106,7 +1106,7 @@ int waves_for(int V, ppv_dtype dt, int B) {
 }
 
 // Whether some wavefront's turn has six tiles or more, i.e. whether the three-tile pipeline of stream_tiles can
-// run at all.  Kernels for shorter turns are compiled without it: 66 instead of 93 registers (bf16), which is
+// run at all.  Kernels for shorter turns are compiled without it: 62 instead of 92 registers (bf16), which is
 // two more rows in flight per compute unit when a large batch keeps every compute unit full.
 bool long_turns(int V, ppv_dtype dt, int nw) {
     const int tile = (dt == PPV_F32) ? TileGeom<float>::TILE : TileGeom<uint16_t>::TILE;
