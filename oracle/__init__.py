@@ -14,8 +14,8 @@ package; the HIP path never does, and this package imports nothing from the HIP 
 from __future__ import annotations
 
 import ctypes as C
+import hashlib
 import os
-import subprocess
 from dataclasses import dataclass
 from typing import Callable, Optional
 
@@ -27,20 +27,27 @@ _LIB = os.path.join(_HERE, "liboracle.so")
 _lib = None
 
 
-def build_oracle(force: bool = False) -> str:
-    """Compile the C oracle with gcc (plain C, OpenMP over rows)."""
-    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
-        cmd = ["gcc", "-O2", "-std=c11", "-fopenmp", "-fPIC", "-shared", "-o", _LIB, _SRC, "-lm"]
-        subprocess.run(cmd, check=True)
-    return _LIB
+def source_digest() -> str:
+    """SHA-256 of ppv_oracle.c as it is on disk; the build stamps the same digest into liboracle.so."""
+    with open(_SRC, "rb") as f:
+        return hashlib.sha256(f.read()).hexdigest()
 
 
 def _load():
+    """Load liboracle.so.  Never compiles: a process that checks the HIP path has the GPU open, and no compiler
+    (no child process at all) is started from there.  The library is built by `python -m oracle.build`
+    (`__graft_entry__.build()` runs it); a missing library, or one built from another ppv_oracle.c, is an error."""
     global _lib
     if _lib is not None:
         return _lib
-    build_oracle()
+    if not os.path.exists(_LIB):
+        raise RuntimeError(f"{_LIB} is missing: build it first with `python -m oracle.build`")
     lib = C.CDLL(_LIB)
+    lib.oracle_source_digest.restype = C.c_char_p
+    built_from = lib.oracle_source_digest().decode()
+    if built_from != source_digest():
+        raise RuntimeError(f"{_LIB} was built from another ppv_oracle.c (digest {built_from[:12]}..., source "
+                           f"{source_digest()[:12]}...): rebuild it with `python -m oracle.build`")
     p = C.c_void_p
     lib.oracle_trie_build.restype = p
     lib.oracle_trie_build.argtypes = [p, p, C.c_int64, C.c_int32]
@@ -224,30 +231,34 @@ class LoopResult:
     seqs: np.ndarray        # int32 [B, l_max] generated sequences (unused slots = -1)
     lens: np.ndarray        # int32 [B]
     logx: np.ndarray        # float64 [B]: log of the importance score x = prod of per-step valid masses
-    steps: int              # decode steps run until every row was in S
+    steps: int              # decode steps run until every row had stopped
     ids_per_step: list      # list of int32 [B] (-1 for rows already finished)
     logZ_per_step: list     # list of float64 [B] (nan for rows already finished)
     cdf_lo_per_step: list
     cdf_hi_per_step: list
     active_per_step: list   # list of bool [B]: row took part in that step
+    dead: np.ndarray        # bool [B]: the row stopped outside S (see decode_loop); its logx is -inf
 
 
 def decode_loop(trie: Trie, B: int, logits_f32_for_step: Callable[[int, np.ndarray, np.ndarray], np.ndarray],
                 uniforms_for_step: Callable[[int], np.ndarray], threads: int = 1,
-                force_ids: Optional[Callable[[int], np.ndarray]] = None, temperature: float = 1.0) -> LoopResult:
+                temperature: float = 1.0) -> LoopResult:
     """Algorithm 1, SampleCandidate, for B independent rows: start from the empty sequence and
     repeat {distribution, mask, sample, append, x *= valid mass} while the row is not in S.
     A row stops the first time it is a member, also when that member has extensions.
     `logits_f32_for_step(step, seqs, lens)` returns the [B, V] logits of that step (the stand-in
     for L(a, T); it may look at the rows' current sequences).
-    `force_ids(step)` (tests only) overrides the sampled tokens so that two implementations can be
-    kept on the same path after an excused boundary disagreement."""
+
+    A row whose valid tokens all have probability 0 cannot draw a token: the update of Algorithm 1 multiplies
+    its x by |P (.) mask|_1 = 0, so the row stops where it is, outside S, with logx = -inf (`dead`): the
+    accept test x > epsilon of the outer loop can never pass for it and it has weight 0 in the resampling."""
     l_max = trie.l_max
     seqs = np.full((B, l_max), -1, dtype=np.int32)
     lens = np.zeros(B, dtype=np.int32)
     logx = np.zeros(B, dtype=np.float64)
     active = np.ones(B, dtype=bool)
-    out = LoopResult(seqs, lens, logx, 0, [], [], [], [], [])
+    dead = np.zeros(B, dtype=bool)
+    out = LoopResult(seqs, lens, logx, 0, [], [], [], [], [], dead)
     step = 0
     while active.any():
         assert step < l_max, "a row outlived the longest member of S"
@@ -261,19 +272,20 @@ def decode_loop(trie: Trie, B: int, logits_f32_for_step: Callable[[int, np.ndarr
         ch = np.full(B, np.nan)
         ids[rows], lz[rows], cl[rows], ch[rows] = r.ids, r.logZ_valid, r.cdf_lo, r.cdf_hi
         out.ids_per_step.append(ids.copy())
-        if force_ids is not None:
-            f = force_ids(step)
-            ids[rows] = f[rows]
         out.logZ_per_step.append(lz)
         out.cdf_lo_per_step.append(cl)
         out.cdf_hi_per_step.append(ch)
         out.active_per_step.append(active.copy())
-        assert (ids[rows] >= 0).all(), "an active row had an empty mask"
-        seqs[rows, lens[rows]] = ids[rows]
-        lens[rows] += 1
-        logx[rows] += lz[rows]
-        q = trie.query(seqs[rows], lens[rows], want_mask=False, threads=threads)
-        active[rows] = q.member == 0
+        took = rows[ids[rows] >= 0]
+        stuck = rows[ids[rows] < 0]
+        dead[stuck] = True
+        logx[stuck] = -np.inf
+        active[stuck] = False
+        seqs[took, lens[took]] = ids[took]
+        lens[took] += 1
+        logx[took] += lz[took]
+        q = trie.query(seqs[took], lens[took], want_mask=False, threads=threads)
+        active[took] = q.member == 0
         step += 1
     out.steps = step
     return out
@@ -289,7 +301,9 @@ def disc_select(logx: np.ndarray, K: int, accept_u: np.ndarray, resample_u: np.n
     accept_u[k, q]  the uniform epsilon of round k: candidate k is accepted iff x > epsilon
     resample_u[q]   the uniform that drives the fallback: among its K candidates, in order, the first whose
                     cumulative score exceeds u * (sum of scores), i.e. candidate j with probability x_j / sum x
-                    (the paper fixes no procedure; the last candidate if rounding lets none exceed it)
+                    (the paper fixes no procedure; the last candidate of positive score if rounding lets none
+                    exceed it).  A candidate of score 0 (logx = -inf: it stopped outside S) is never returned;
+                    when all K scores are 0 nothing can be returned and chosen[q] = -1
     reuse_rejected  False: the fallback draws K new candidates, as the algorithm is printed;
                     True: it resamples among the K rejected ones (the reading under which K = 1 coincides with
                     plain constrained decoding, Section 4.1 "Methods")
@@ -315,14 +329,18 @@ def disc_select(logx: np.ndarray, K: int, accept_u: np.ndarray, resample_u: np.n
             continue
         first = 0 if reuse_rejected else K
         lw = logx[first:first + K, q]
+        n_draws[q] = K if reuse_rejected else 2 * K
+        if lw.max() == -np.inf:                 # every score is 0: x_k / sum x is undefined, nothing is returned
+            chosen[q] = -1
+            continue
         w = np.exp(lw - lw.max())
         tau = resample_u[q] * w.sum()
-        c, pick = 0.0, K - 1
+        c, pick = 0.0, -1
         for j in range(K):
             c += w[j]
-            if c > tau:
+            if w[j] > 0.0:
                 pick = j
-                break
+                if c > tau:
+                    break
         chosen[q] = first + pick
-        n_draws[q] = K if reuse_rejected else 2 * K
     return chosen, n_draws, accepted

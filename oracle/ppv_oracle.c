@@ -415,6 +415,12 @@ void oracle_sample_batch(const float *logits, int64_t V, const uint8_t *mask, co
                              temperature, ids + b, logZ_valid + b, logZ_all + b, cdf_lo + b, cdf_hi + b);
 }
 
+/* which ppv_oracle.c this library was compiled from (the build passes the digest of the source file) */
+#ifndef ORACLE_SOURCE_DIGEST
+#define ORACLE_SOURCE_DIGEST "unstamped"
+#endif
+const char *oracle_source_digest(void) { return ORACLE_SOURCE_DIGEST; }
+
 int32_t oracle_max_threads(void) {
 #ifdef _OPENMP
     return omp_get_max_threads();

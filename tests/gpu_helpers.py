@@ -100,3 +100,47 @@ def gpu_sample(cfg, logits_dev, dmask, uniforms: np.ndarray, temperature: float 
     ppv.constrained_sample(logits_dev, dmask, to_dev(uniforms), ids, lzv, lza, temperature=temperature)
     torch.cuda.synchronize()
     return ids.cpu().numpy(), lzv.cpu().numpy(), lza.cpu().numpy()
+
+
+def follow_loop(trie: oracle.Trie, B: int, logits_f32_for_step, uniforms_for_step, taken_ids_for_step, threads: int = 1,
+                temperature: float = 1.0) -> oracle.LoopResult:
+    """The oracle's own choice at every step of the decode loop (one Trie.step per decode step, recorded), with the
+    rows then moved along the tokens the HIP path took (`taken_ids_for_step(step)` -> int32 [B]), so that one
+    excused disagreement inside the CDF band does not invalidate the comparison of the steps after it.  The
+    free-running loop is oracle.decode_loop; this one exists for the parity tests only."""
+    l_max = trie.l_max
+    seqs = np.full((B, l_max), -1, dtype=np.int32)
+    lens = np.zeros(B, dtype=np.int32)
+    logx = np.zeros(B, dtype=np.float64)
+    active = np.ones(B, dtype=bool)
+    dead = np.zeros(B, dtype=bool)
+    out = oracle.LoopResult(seqs, lens, logx, 0, [], [], [], [], [], dead)
+    step = 0
+    while active.any():
+        assert step < l_max, "a row outlived the longest member of S"
+        rows = np.nonzero(active)[0]
+        r = trie.step(seqs[rows], lens[rows], logits_f32_for_step(step, seqs, lens)[rows], uniforms_for_step(step)[rows],
+                      want_mask=False, threads=threads, temperature=temperature)
+        ids = np.full(B, -1, dtype=np.int32)
+        lz, cl, ch = np.full(B, np.nan), np.full(B, np.nan), np.full(B, np.nan)
+        ids[rows], lz[rows], cl[rows], ch[rows] = r.ids, r.logZ_valid, r.cdf_lo, r.cdf_hi
+        out.ids_per_step.append(ids)
+        out.logZ_per_step.append(lz)
+        out.cdf_lo_per_step.append(cl)
+        out.cdf_hi_per_step.append(ch)
+        out.active_per_step.append(active.copy())
+        stuck = rows[ids[rows] < 0]                 # the oracle found nothing to sample: the row stops outside S
+        took = rows[ids[rows] >= 0]
+        dead[stuck] = True
+        logx[stuck] = -np.inf
+        active[stuck] = False
+        taken = np.asarray(taken_ids_for_step(step))[took]
+        assert (taken >= 0).all(), "the HIP path sampled nothing where the oracle sampled a token"
+        seqs[took, lens[took]] = taken
+        lens[took] += 1
+        logx[took] += lz[took]
+        q = trie.query(seqs[took], lens[took], want_mask=False, threads=threads)
+        active[took] = q.member == 0
+        step += 1
+    out.steps = step
+    return out

@@ -13,7 +13,7 @@ import oracle
 from paper_2504_09135_amd import binding as ppv
 from paper_2504_09135_amd import workloads as W
 
-from gpu_helpers import DEV, assert_query_parity, check_sample_rows, gpu_sample, logits_to_dev, to_dev
+from gpu_helpers import DEV, assert_query_parity, check_sample_rows, follow_loop, gpu_sample, logits_to_dev, to_dev
 
 pytestmark = [pytest.mark.gpu, pytest.mark.timeout(900)]
 
@@ -124,8 +124,8 @@ def test_C3_full_decode_loop_graph():
     say("C3: oracle loop")
     # the oracle makes its own choice at every step (recorded) but is kept on the HIP path's sequence, so
     # that a disagreement inside the CDF band at one step does not invalidate the comparison of later steps
-    res = oracle.decode_loop(trie, B, lambda s, *_: W.logits_as_f32(cfg, host_logits[s]), lambda s: host_un[s],
-                             threads=16, force_ids=lambda s: gid[s])
+    res = follow_loop(trie, B, lambda s, *_: W.logits_as_f32(cfg, host_logits[s]), lambda s: host_un[s],
+                      lambda s: gid[s], threads=16)
     say("C3: comparing")
     excused = 0
     for s in range(res.steps):

@@ -8,8 +8,8 @@ import oracle
 from paper_2504_09135_amd import binding as ppv
 from paper_2504_09135_amd import workloads as W
 
-from gpu_helpers import (DEV, assert_query_parity, check_sample_rows, gpu_query, gpu_sample, logits_to_dev, to_dev,
-                         unpack_mask)
+from gpu_helpers import (DEV, assert_query_parity, check_sample_rows, follow_loop, gpu_query, gpu_sample, logits_to_dev,
+                         to_dev, unpack_mask)
 
 pytestmark = pytest.mark.gpu
 
@@ -208,7 +208,7 @@ def test_decode_loop_parity_small(use_state, temperature):
         torch.cuda.synchronize()
         all_ids.append((act_before, ids.cpu().numpy(), lz.cpu().numpy()))
     # the oracle makes its own choice at every step but is kept on the HIP path's sequence
-    res = oracle.decode_loop(trie, B, lg, un, threads=8, force_ids=lambda s: all_ids[s][1], temperature=temperature)
+    res = follow_loop(trie, B, lg, un, lambda s: all_ids[s][1], threads=8, temperature=temperature)
     assert res.steps == len(all_ids)
     excused = 0
     for s in range(res.steps):

@@ -648,3 +648,129 @@ def test_masked_sample_with_topm_mask_matches_renormalised_top_M_distribution():
         assert abs(s.logZ_valid[0] - math.log(p_top.sum())) < 1e-12
         cdf = np.cumsum(p_top) / p_top.sum()
         assert s.ids[0] == top[np.searchsorted(cdf, np.float32(u), side="right")]
+
+
+# ------------------------------------------------------------------ rows that cannot draw a token
+def test_valid_tokens_all_of_probability_zero_sample_nothing():
+    """Algorithm 1 samples from P (.) mask / |P (.) mask|_1, which is undefined when the mass is 0.  The reading:
+    a valid set that is not empty but whose tokens all have logit -inf yields no token (id -1) and log mass -inf,
+    for every u, while the log-sum-exp over the whole vocabulary is still the library's.  The neighbouring case,
+    one valid token of positive probability among such ones, yields that token for every u, with mass = its
+    softmax probability.  Expected values are written out here, not taken from the oracle's formula."""
+    rng = np.random.default_rng(16)
+    V = 37
+    l = (rng.standard_normal(V) * 2).astype(np.float32)
+    mask = np.zeros(V, np.uint8)
+    valid = [3, 4, 17, 36]
+    mask[valid] = 1
+    dead = l.copy()
+    dead[valid] = -np.inf
+    lse_all = logsumexp(dead.astype(np.float64))
+    for u in (0.0, 0.25, 0.5, float(np.float32(1.0) - np.float32(2 ** -24))):
+        r = one_step(dead, mask, u)
+        assert r.ids[0] == -1 and r.logZ_valid[0] == -np.inf
+        assert r.logZ_all[0] == pytest.approx(lse_all, abs=1e-12)
+        m = oracle.masked_sample(dead[None, :], mask[None, :], np.array([u], np.float32))
+        assert m.ids[0] == -1 and m.logZ_valid[0] == -np.inf and m.logZ_all[0] == pytest.approx(lse_all, abs=1e-12)
+    one = dead.copy()
+    one[17] = 0.7
+    lse_one = logsumexp(one.astype(np.float64))
+    for u in (0.0, 0.25, 0.5, float(np.float32(1.0) - np.float32(2 ** -24))):
+        r = one_step(one, mask, u)
+        assert r.ids[0] == 17
+        assert r.logZ_valid[0] == pytest.approx(float(np.float32(0.7)) - lse_one, abs=1e-12)
+        assert r.cdf_lo[0] == 0.0 and r.cdf_hi[0] == 1.0
+        assert r.logZ_all[0] == pytest.approx(lse_one, abs=1e-12)
+    # a single valid token at -inf: the same
+    single = np.zeros(V, np.uint8)
+    single[9] = 1
+    l9 = l.copy()
+    l9[9] = -np.inf
+    r = one_step(l9, single, 0.4)
+    assert r.ids[0] == -1 and r.logZ_valid[0] == -np.inf
+
+
+def test_decode_loop_row_without_valid_mass_stops_outside_S_with_score_zero():
+    """Algorithm 1's update multiplies x by the valid mass; when that mass is 0 the row can neither draw a token
+    nor ever be accepted.  The loop leaves such a row where it is, outside S, with logx = -inf, and the rows
+    beside it are unaffected."""
+    V = 4
+    seqs = [[0, 1], [0, 2], [1, 3]]
+    S = W.constraint_set_from_lists(seqs, V)
+    trie = oracle.Trie(S.tokens, S.offsets, V)
+    B = 40
+    rng = np.random.default_rng(2)
+    un = rng.random((2, B), dtype=np.float32)
+    first = np.log(np.array([0.5, 0.25, 0.125, 0.125])).astype(np.float32)
+    after0 = np.array([0.3, -np.inf, -np.inf, 0.1], np.float32)      # both continuations of [0] have probability 0
+    after1 = np.log(np.array([0.1, 0.2, 0.3, 0.4])).astype(np.float32)
+
+    def logits_for_step(step, seqs_now, lens_now):
+        if step == 0:
+            return np.broadcast_to(first, (B, V)).copy()
+        return np.stack([after0 if seqs_now[b, 0] == 0 else after1 for b in range(B)])
+    res = oracle.decode_loop(trie, B, logits_for_step, lambda s: un[s])
+    went0 = un[0] < 0.5 / 0.75                                       # P(0 | valid) = 0.5 / (0.5 + 0.25)
+    assert went0.any() and (~went0).any()
+    assert np.array_equal(res.dead, went0)
+    assert (res.lens[went0] == 1).all() and (res.seqs[went0, 0] == 0).all() and (res.logx[went0] == -np.inf).all()
+    assert (res.lens[~went0] == 2).all() and (res.seqs[~went0, 1] == 3).all()
+    assert np.allclose(res.logx[~went0], math.log(0.75) + math.log(0.4), atol=1e-7)
+    assert res.steps == 2
+    # the outer loop never returns such a candidate: not through an accept round (x = 0 > epsilon is false also
+    # for epsilon = 0), not through the resampling (weight 0)
+    K = 2
+    logx = np.array([[-np.inf, -np.inf, math.log(0.3), -np.inf],
+                     [math.log(0.2), -np.inf, -np.inf, -np.inf],
+                     [-np.inf, -np.inf, math.log(0.3), math.log(0.01)],
+                     [math.log(0.6), -np.inf, -np.inf, -np.inf]])     # [2K candidates, Q = 4 queries]
+    zero = np.zeros((K, 4))
+    for u in (0.0, 0.3, 0.7, 0.999999):
+        ch, nd, acc = oracle.disc_select(logx, K, zero, np.full(4, u))
+        assert list(ch[:3]) == [1, -1, 0] and list(acc[:3]) == [1, 0, 1] and list(nd[:3]) == [2, 4, 1]
+        assert ch[3] == 2 and acc[3] == 0 and nd[3] == 4             # rejected twice (eps = 1 below), then the only live one
+        ch, nd, acc = oracle.disc_select(logx, K, np.full((K, 4), 0.999999), np.full(4, u))
+        assert ch[0] == 3 and ch[1] == -1 and ch[3] == 2 and not acc.any() and (nd == 4).all()
+        ch, nd, acc = oracle.disc_select(logx, K, np.full((K, 4), 0.999999), np.full(4, u), reuse_rejected=True)
+        assert list(ch) == [1, -1, 0, -1] and (nd == 2).all()
+    # ... and with probability proportional to the scores among the live ones (0.3 : 0.01 in the last query's
+    # fallback would need candidates 2, 3 of query 3: they are (log 0.01, -inf) above, so take a direct case)
+    lx = np.log(np.array([[0.5], [1e-300], [0.2], [0.6]]))
+    lx[1, 0] = -np.inf
+    us = (np.arange(1000) + 0.5) / 1000
+    picks = [int(oracle.disc_select(np.repeat(lx, 1, axis=1), 2, np.full((2, 1), 0.999999), np.array([u]))[0][0]) for u in us]
+    assert set(picks) == {2, 3} and picks.count(2) == 250            # 0.2 / (0.2 + 0.6)
+
+
+def test_loading_the_oracle_starts_no_process_and_refuses_a_stale_library(monkeypatch, tmp_path):
+    """The oracle is loaded inside processes that have a GPU open; nothing may be compiled (no child process at
+    all) from there.  A library built from another source file is refused, not rebuilt."""
+    import importlib
+    import subprocess
+
+    def forbidden(*a, **k):
+        raise AssertionError("a process was started while loading the oracle")
+    for mod, name in ((subprocess, "Popen"), (subprocess, "run"), (os, "system"), (os, "fork"), (os, "posix_spawn"),
+                      (os, "execv"), (os, "execve"), (os, "popen")):
+        monkeypatch.setattr(mod, name, forbidden)
+    fresh = importlib.reload(oracle)
+    try:
+        assert fresh._lib is None
+        assert fresh.max_threads() >= 1                               # first call: loads the library
+        S = W.constraint_set_from_lists([[1, 2], [3]], 5)
+        t = fresh.Trie(S.tokens, S.offsets, 5)
+        assert t.n_members == 2
+        # another source file: refused
+        other = tmp_path / "ppv_oracle.c"
+        other.write_bytes(open(fresh._SRC, "rb").read() + b"\n/* changed */\n")
+        monkeypatch.setattr(fresh, "_SRC", str(other))
+        monkeypatch.setattr(fresh, "_lib", None)
+        with pytest.raises(RuntimeError, match="built from another"):
+            fresh.max_threads()
+        # no library at all: refused
+        monkeypatch.setattr(fresh, "_LIB", str(tmp_path / "missing.so"))
+        with pytest.raises(RuntimeError, match="missing"):
+            fresh.max_threads()
+    finally:
+        monkeypatch.undo()
+        importlib.reload(oracle)
