@@ -129,16 +129,18 @@ ppv_status ppv_next_token_mask(const ppv_index_t *index, const int32_t *prefixes
                                uint32_t *range_hi, uint8_t *member, void *stream);
 
 /*
- * constrained_sample -- Algorithm 1, SampleCandidate: "Sample a token t from P (.) mask /
- * |P (.) mask|_1" and the factor |P (.) mask|_1 that multiplies the importance score x,
- * with P = softmax(logits / T), T the temperature that Algorithm 1 takes as input (the experiments
- * of Section 4.1 "Methods" use T = 1).  With l_v = logits[v] / T, per row b:
- *   logZ_valid[b] = log sum_{v in mask} exp(l_v) - log sum_{all v} exp(l_v)   (<= 0; -inf if the mask is empty)
+ * constrained_sample -- Algorithm 1, SampleCandidate, sampling step and update step: a token drawn from the
+ * model's distribution restricted to the valid set and renormalised, and the valid mass |P (.) mask|_1 that
+ * multiplies the importance score x, with P = softmax(logits / T), T the temperature that Algorithm 1 takes as
+ * input (the experiments of Section 4.1 "Methods" use T = 1).  With l_v = logits[v] / T, per row b:
+ *   logZ_valid[b] = log sum_{v in mask} exp(l_v) - log sum_{all v} exp(l_v)   (<= 0; -inf if the mask is empty
+ *                   or every valid token has logit -inf)
  *   logZ_all[b]   = log sum_{all v} exp(l_v)
  *   ids[b]        = the first valid token, in increasing token id, whose cumulative weight
  *                   sum_{w <= v, w in mask} exp(l_w) exceeds uniforms[b] * sum_{w in mask} exp(l_w)
  *                   (inverse-CDF sampling; the paper fixes no procedure); if rounding lets no token
- *                   exceed it, the last valid token with positive weight; -1 if the mask is empty.
+ *                   exceed it, the last valid token with positive weight; -1 if the mask is empty or no
+ *                   valid token has positive weight (the renormalised distribution is undefined then).
  * Arguments (all device pointers):
  *   logits      [B rows] of V elements of type dt, row b starts at element b*row_stride
  *               (row_stride >= V; rows must be 16-byte aligned: row_stride a multiple of 4 (f32) / 8 (bf16))
@@ -156,8 +158,8 @@ ppv_status constrained_sample(const void *logits, ppv_dtype dt, int64_t row_stri
                               float *logZ_all, float temperature, void *stream);
 
 /*
- * ppv_decode_begin -- Algorithm 1, SampleCandidate: "Initialize candidate sequence a = [],
- * importance score x = 1" (or resume from given prefixes).  Locates each row's current prefix once
+ * ppv_decode_begin -- Algorithm 1, SampleCandidate, initialisation step: the empty candidate sequence with
+ * importance score x = 1 (or resume from given prefixes).  Locates each row's current prefix once
  * and leaves a cursor in `state`, so that every following ppv_decode_step costs one level of the
  * index instead of a walk from the root.
  * Arguments (all device pointers):
@@ -175,15 +177,16 @@ ppv_status ppv_decode_begin(const ppv_index_t *index, const int32_t *prefixes, i
 
 /*
  * ppv_decode_step -- one iteration of the while loop of Algorithm 1's SampleCandidate for B rows,
- * fused: mask = PPV_S(P, a); sample t; a = a + [t]; x = x * |P (.) mask|_1; stop when a is in S.
+ * fused: the valid set of the row's prefix, a token drawn from it, the token appended, the importance score
+ * multiplied by the valid mass, and the test whether the extended row is in S.
  * Equals ppv_next_token_mask + constrained_sample + append + membership test, but the mask never
  * leaves the chip.  Rows with active[b] == 0 are left untouched.
  * Arguments (all device pointers):
  *   prefixes  int32[B, prefix_stride], in/out: the sampled token is written at position lens[b]
  *   lens      int32[B], in/out: incremented for rows that sampled a token
  *   active    uint8[B], in/out: cleared when the extended row is a member of S (the row is done),
- *             and also (with ids[b] = -1, nothing appended) when the row has no valid token or
- *             no room left (lens[b] == prefix_stride)
+ *             and also (with ids[b] = -1, nothing appended, logx[b] = -inf) when the row has no valid token
+ *             of positive probability or no room left (lens[b] == prefix_stride): such a row stops outside S
  *   state     uint32[B, PPV_STATE_WORDS] from ppv_decode_begin, in/out; or NULL: the prefix is then
  *             located from the root in every call (same results, one index level per token slower).
  *             With a state the caller must not change prefixes/lens of active rows between steps.
@@ -192,7 +195,9 @@ ppv_status ppv_decode_begin(const ppv_index_t *index, const int32_t *prefixes, i
  *   logits, dt, row_stride, uniforms, temperature   as in constrained_sample; V is the index's vocabulary
  *   ids         int32[B] or NULL: token sampled this step (-1 if none); untouched for inactive rows
  *   logZ_valid  float[B] or NULL: this step's log valid mass; untouched for inactive rows
- *   logx        float[B] or NULL, in/out: logx[b] += logZ_valid[b]  (log of the importance score x)
+ *   logx        float[B] or NULL, in/out: logx[b] += logZ_valid[b] (log of the importance score x) for a row that
+ *               drew a token; -inf for a row that stopped outside S (Algorithm 1's update multiplies x by a valid
+ *               mass of 0: ppv_disc_select never accepts such a candidate and gives it weight 0)
  * Errors: as the two calls above.
  */
 ppv_status ppv_decode_step(const ppv_index_t *index, int32_t *prefixes, int32_t prefix_stride, int32_t *lens,
@@ -221,9 +226,9 @@ ppv_status ppv_decode_loop(const ppv_index_t *index, int32_t *prefixes, int32_t 
 
 /*
  * ppv_topm_mask -- Algorithm 2 with M < |V| candidates, as the paper ran it (M = 50; 100, 500, 1000
- * in the appendix study of M): "Compute the top M entries of P", "Construct a candidate matrix" with
- * rows a + [t_i], "Simultaneously perform a binary search for each candidate", "Extend mask_V to
- * mask"; Section 3.2 "Selection of top candidate tokens".  The result is the mask of
+ * in the appendix study of M), all four of its steps: the M most probable tokens, the candidate rows
+ * a + [t_i], one search of sorted S per candidate, and the verdicts scattered into a mask over the
+ * vocabulary; Section 3.2 "Selection of top candidate tokens".  The result is the mask of
  * ppv_next_token_mask restricted to the top-M tokens; feed it to constrained_sample for the
  * sampling step of Algorithm 1.
  * The top M are the M largest logits of the row (P = softmax(logits) has the same order); equal
@@ -249,8 +254,9 @@ ppv_status ppv_topm_mask(const ppv_index_t *index, const int32_t *prefixes, int3
                          int32_t B, int32_t *top_ids, uint8_t *mask_V, uint32_t *mask, void *stream);
 
 /*
- * ppv_disc_select -- Algorithm 1 after SampleCandidate: "Accept with probability x", at most K rounds,
- * then importance resampling among K candidates with probability x_k / sum x_k.  The candidates of all
+ * ppv_disc_select -- Algorithm 1 after SampleCandidate: a candidate is accepted with probability equal to its
+ * importance score x, in at most K rounds, then importance resampling among K candidates with probability
+ * x_k / sum x_k.  The candidates of all
  * queries have been drawn beforehand (rows of ppv_decode_step / ppv_decode_loop; logx is their log
  * importance score), so the selection is a function of logx and the supplied uniforms.
  * Arguments (all device pointers):
@@ -259,10 +265,12 @@ ppv_status ppv_topm_mask(const ppv_index_t *index, const int32_t *prefixes, int3
  *   n_candidates  >= 2K, or >= K with reuse_rejected
  *   accept_u    float[K, Q] in [0,1): candidate k is accepted iff exp(logx) > accept_u (compared in fp64)
  *   resample_u  float[Q] in [0,1): the fallback takes, in candidate order, the first whose cumulative
- *               score exceeds resample_u * (sum of scores); the last one if rounding lets none exceed it
+ *               score exceeds resample_u * (sum of scores); the last one of positive score if rounding lets
+ *               none exceed it.  A candidate of score 0 (logx = -inf: it stopped outside S) is never returned
  *   reuse_rejected  0: the fallback uses K new candidates (the algorithm as printed); 1: it resamples among
  *               the K rejected ones (then K = 1 is plain constrained decoding, Section 4.1 "Methods")
- *   chosen      int32[Q]: index of the returned candidate
+ *   chosen      int32[Q]: index of the returned candidate; -1 when no accept round passed and every fallback
+ *               candidate has score 0 (nothing can be returned)
  *   n_draws     int32[Q] or NULL: candidates consumed (the k of Theorem 3.1: round of acceptance, else 2K / K)
  *   accepted    uint8[Q] or NULL: 1 iff returned by an accept round
  * Errors: PPV_EINVAL (K <= 0, Q < 0, too few candidates, null pointer), PPV_EDEVICE.
@@ -270,6 +278,32 @@ ppv_status ppv_topm_mask(const ppv_index_t *index, const int32_t *prefixes, int3
 ppv_status ppv_disc_select(const float *logx, int32_t n_candidates, int32_t K, int32_t Q, const float *accept_u,
                            const float *resample_u, int32_t reuse_rejected, int32_t *chosen, int32_t *n_draws,
                            uint8_t *accepted, void *stream);
+
+/*
+ * ppv_tuning_set / ppv_tuning_get -- process-wide tuning and test switches (not part of the method).  Each is
+ * read once from the environment variable of the same name without the TUNE_ part (PPV_WAVES_PER_ROW, ...)
+ * when the library is loaded; no per-step call reads the environment.  Setting one while calls are being
+ * issued from another thread is a race.
+ *   PPV_TUNE_WAVES_PER_ROW   wavefronts per row of the sampling kernels, 1..16; 0 = the library's table
+ *   PPV_TUNE_TOPM_WAVES      the same for ppv_topm_mask
+ *   PPV_TUNE_TOPM_STREAMING  1: every row of ppv_topm_mask takes the whole-row select (tests); 0 = as needed
+ *   PPV_TUNE_LOOKUP          0: ppv_build_index / ppv_index_load leave out the look-up table of whole prefixes
+ *   PPV_TUNE_LOOKUP_WEAK     1: the table is built with one fingerprint for all entries (tests: every probe is
+ *                            a false hit that the exact check must turn away)
+ *   PPV_TUNE_ROW_SPLIT       workgroups a row is spread over in small batches, 1, 2, 4, 8, 16; 0 = the library's table
+ * Errors: PPV_EINVAL (unknown knob, null pointer), PPV_ERANGE (value outside the knob's range).
+ */
+enum {
+    PPV_TUNE_WAVES_PER_ROW = 0,
+    PPV_TUNE_TOPM_WAVES = 1,
+    PPV_TUNE_TOPM_STREAMING = 2,
+    PPV_TUNE_LOOKUP = 3,
+    PPV_TUNE_LOOKUP_WEAK = 4,
+    PPV_TUNE_ROW_SPLIT = 5,
+    PPV_TUNE_COUNT = 6
+};
+ppv_status ppv_tuning_set(int32_t knob, int32_t value);
+ppv_status ppv_tuning_get(int32_t knob, int32_t *value);
 
 #ifdef __cplusplus
 }

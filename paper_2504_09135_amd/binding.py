@@ -26,7 +26,11 @@ PPV_STATE_WORDS = 4
 SYMBOLS = ("ppv_status_string", "ppv_build_index", "ppv_index_info", "ppv_index_export", "ppv_free_index",
            "ppv_index_save", "ppv_index_load",
            "ppv_next_token_mask", "constrained_sample", "ppv_decode_begin", "ppv_decode_step", "ppv_decode_loop", "ppv_topm_mask",
-           "ppv_disc_select")
+           "ppv_disc_select", "ppv_tuning_set", "ppv_tuning_get")
+
+# tuning / test switches (ppv_tuning_set)
+(PPV_TUNE_WAVES_PER_ROW, PPV_TUNE_TOPM_WAVES, PPV_TUNE_TOPM_STREAMING, PPV_TUNE_LOOKUP, PPV_TUNE_LOOKUP_WEAK,
+ PPV_TUNE_ROW_SPLIT) = range(6)
 
 _lib = None
 
@@ -75,6 +79,10 @@ def load_library() -> C.CDLL:
     lib.ppv_topm_mask.argtypes = [p, p, i32, p, p, C.c_int, i64, i32, i32, p, p, p, p]
     lib.ppv_disc_select.restype = C.c_int
     lib.ppv_disc_select.argtypes = [p, i32, i32, i32, p, p, i32, p, p, p, p]
+    lib.ppv_tuning_set.restype = C.c_int
+    lib.ppv_tuning_set.argtypes = [i32, i32]
+    lib.ppv_tuning_get.restype = C.c_int
+    lib.ppv_tuning_get.argtypes = [i32, C.POINTER(i32)]
     _lib = lib
     return lib
 
@@ -324,3 +332,14 @@ def ppv_disc_select(logx: torch.Tensor, K: int, accept_u: torch.Tensor, resample
         _dev(chosen, torch.int32, "chosen"), _dev(n_draws, torch.int32, "n_draws"),
         _dev(accepted, torch.uint8, "accepted"), _stream(stream))
     _check(st, "ppv_disc_select")
+
+
+def ppv_tuning_set(knob: int, value: int) -> None:
+    """Set a process-wide tuning / test switch (PPV_TUNE_*)."""
+    _check(load_library().ppv_tuning_set(int(knob), int(value)), "ppv_tuning_set")
+
+
+def ppv_tuning_get(knob: int) -> int:
+    v = C.c_int32()
+    _check(load_library().ppv_tuning_get(int(knob), C.byref(v)), "ppv_tuning_get")
+    return v.value

@@ -29,18 +29,26 @@ __global__ __launch_bounds__(DISC_THREADS) void disc_select_kernel(const float *
     const int first = reuse ? 0 : K;
     double m = -INFINITY;
     for (int j = 0; j < K; j++) m = fmax(m, (double)logx[(size_t)(first + j) * Q + q]);
+    if (n_draws) n_draws[q] = reuse ? K : 2 * K;
+    if (accepted) accepted[q] = 0;
+    if (m == -INFINITY) {   // every score is 0 (all candidates stopped outside S): nothing can be returned
+        chosen[q] = -1;
+        return;
+    }
     double total = 0.0;
     for (int j = 0; j < K; j++) total += exp((double)logx[(size_t)(first + j) * Q + q] - m);
     const double tau = (double)resample_u[q] * total;
     double c = 0.0;
-    int pick = K - 1;
+    int pick = -1;   // the last candidate of positive score when rounding lets none exceed tau
     for (int j = 0; j < K; j++) {
-        c += exp((double)logx[(size_t)(first + j) * Q + q] - m);
-        if (c > tau) { pick = j; break; }
+        const double w = exp((double)logx[(size_t)(first + j) * Q + q] - m);
+        c += w;
+        if (w > 0.0) {
+            pick = j;
+            if (c > tau) break;
+        }
     }
     chosen[q] = first + pick;
-    if (n_draws) n_draws[q] = reuse ? K : 2 * K;
-    if (accepted) accepted[q] = 0;
 }
 
 }  // namespace

@@ -541,13 +541,11 @@ ppv_status finish_lookup(ppv_index *ix, uint32_t G, int32_t l_max, hipStream_t s
     ix->view.lookup = nullptr;
     ix->view.lookup_size = 0;
     ix->view.lookup_fp_mask = 0xFFFFFFFFu;
-    // PPV_LOOKUP=0: no table (every prefix is located by the descent; saves 16 bytes per prefix of device memory).
-    // PPV_LOOKUP_WEAK=1 (tests): one fingerprint for all, so that every probe is a false hit and the exact check
+    // PPV_TUNE_LOOKUP = 0: no table (every prefix is located by the descent; saves 16 bytes per prefix of device memory).
+    // PPV_TUNE_LOOKUP_WEAK = 1 (tests): one fingerprint for all, so that every probe is a false hit and the exact check
     // has to turn it away.
-    const char *e = getenv("PPV_LOOKUP");
-    if (e && e[0] == '0') return PPV_OK;
-    const char *wk = getenv("PPV_LOOKUP_WEAK");
-    if (wk && wk[0] == '1') ix->view.lookup_fp_mask = 0u;
+    if (ppv_tuning(PPV_TUNE_LOOKUP) == 0) return PPV_OK;
+    if (ppv_tuning(PPV_TUNE_LOOKUP_WEAK) == 1) ix->view.lookup_fp_mask = 0u;
     const uint64_t want = 2ull * G;
     const uint32_t size = (uint32_t)std::min<uint64_t>(want, 0xFFFFFFF0ull);
     DeviceBuffers tmp;

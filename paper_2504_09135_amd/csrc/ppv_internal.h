@@ -78,6 +78,10 @@ struct ppv_index {
     int device;
 };
 
+// Current value of a tuning / test switch (PPV_TUNE_* of ppv.h): read from the environment once at load,
+// changed by ppv_tuning_set.
+int ppv_tuning(int knob);
+
 #define PPV_HIP_TRY(expr)                          \
     do {                                           \
         hipError_t e_ = (expr);                    \

@@ -15,7 +15,6 @@
 // Nothing here is a dense contraction, so no MFMA; the bound is HBM bandwidth, with the exp
 // (quarter-rate v_exp_f32) as the main ALU cost.
 #include <cmath>
-#include <cstdlib>
 #include <type_traits>
 
 #include "ppv_device.h"
@@ -1015,6 +1014,8 @@ __global__ __launch_bounds__(LOOP ? LOOP_WAVES * WAVE : MAX_WAVES * WAVE) void d
                 done = (tokw & PPV_NODE_TERMINAL) != 0u;   // the extended row is itself a member
                 prefixes[(size_t)b * (size_t)stride + t] = id;
                 lx += r.logZ_valid;
+            } else {
+                lx = -INFINITY;   // the row stops outside S: its importance score is multiplied by a valid mass of 0
             }
             if (ids) ids[(size_t)s * (size_t)B + b] = id;
             if (logZ_valid) logZ_valid[(size_t)s * (size_t)B + b] = r.logZ_valid;
@@ -1029,8 +1030,8 @@ __global__ __launch_bounds__(LOOP ? LOOP_WAVES * WAVE : MAX_WAVES * WAVE) void d
                 if (id >= 0) {
                     lens[b] = t + 1;
                     if (state) state[b] = nx;
-                    if (logx) logx[b] = logx_in + lx;
                 }
+                if (logx) logx[b] = logx_in + lx;   // (-inf for a row that drew nothing)
                 if (done) active[b] = 0;
             }
         }
@@ -1096,10 +1097,7 @@ int waves_for(int V, ppv_dtype dt, int B) {
     // long rows in a small batch: one row per compute unit, all of it in flight (constrained_sample, B = 256, us per
     // call with 8 / 16 wavefronts: 32 tiles: 13.2 / 12.0 (fp32 V = 32k), 15.2 / 14.2 (bf16 V = 64k); 63 tiles: 23.6 / 20.6)
     if (nt >= 32 && B <= 256) cap = 16;
-    if (const char *e = getenv("PPV_WAVES_PER_ROW")) {  // tuning aid
-        const int v = atoi(e);
-        if (v >= 1 && v <= MAX_WAVES) cap = v;
-    }
+    if (const int v = ppv_tuning(PPV_TUNE_WAVES_PER_ROW)) cap = v;   // tuning aid (0: the table above)
     int nw = 1;
     while (nw < nt && nw * 2 <= cap) nw <<= 1;
     return nw;

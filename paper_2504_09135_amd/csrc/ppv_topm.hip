@@ -554,10 +554,7 @@ int topm_waves(int V, ppv_dtype dt, int B) {
     // V = 256k: B=128: - / 55 / 44, B=1024: 250 / 210 / 215
     if (nc >= 128 && B <= 256) cap = 16;
     if (nc >= 384 && B <= 2048 && cap < 8) cap = 8;
-    if (const char *e = getenv("PPV_TOPM_WAVES")) {  // tuning aid
-        const int v = atoi(e);
-        if (v >= 1 && v <= TOPM_WAVES) cap = v;
-    }
+    if (const int v = ppv_tuning(PPV_TUNE_TOPM_WAVES)) cap = v < TOPM_WAVES ? v : TOPM_WAVES;   // tuning aid (0: the table above)
     int nw = 1;
     while (nw * 2 <= cap && nw * 2 <= nc) nw <<= 1;
     return nw;
@@ -578,9 +575,8 @@ extern "C" ppv_status ppv_topm_mask(const ppv_index_t *ix, const int32_t *prefix
     const int64_t per16 = (dt == PPV_F32) ? 4 : 8;
     if (row_stride < V || row_stride % per16 != 0 || ((uintptr_t)logits & 15u) != 0) return PPV_EINVAL;
     const int threads = topm_waves(V, dt, B) * WAVE;
-    // testing aid: PPV_TOPM_STREAMING=1 sends every row through the whole-row radix select
-    const char *fs = getenv("PPV_TOPM_STREAMING");
-    const int force_streaming = (fs && fs[0] == '1') ? 1 : 0;
+    // testing aid: PPV_TUNE_TOPM_STREAMING = 1 sends every row through the whole-row radix select
+    const int force_streaming = ppv_tuning(PPV_TUNE_TOPM_STREAMING) == 1 ? 1 : 0;
     const size_t lds = (size_t)(ix->view.n_words > TOPM_BINS ? ix->view.n_words : TOPM_BINS) * sizeof(uint32_t);
     const dim3 grid((unsigned)B), block(threads);
     hipStream_t hs = (hipStream_t)stream;

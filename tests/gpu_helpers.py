@@ -2,6 +2,8 @@
 with the CPU oracle under the stated tolerances."""
 from __future__ import annotations
 
+import contextlib
+
 import numpy as np
 import torch
 
@@ -15,6 +17,17 @@ LOGZ_TOL = {"f32": 1e-5, "bf16": 1e-3}
 CDF_BAND = 1e-6
 
 DEV = "cuda:0"
+
+
+@contextlib.contextmanager
+def tuning(knob: int, value: int):
+    """A tuning / test switch of the library set for the duration of a block, then put back."""
+    before = ppv.ppv_tuning_get(knob)
+    ppv.ppv_tuning_set(knob, value)
+    try:
+        yield
+    finally:
+        ppv.ppv_tuning_set(knob, before)
 
 
 def to_dev(a: np.ndarray) -> torch.Tensor:

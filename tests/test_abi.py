@@ -78,6 +78,21 @@ def test_argument_errors_without_device(lib):
     assert lib.ppv_decode_loop(None, None, 0, None, None, None, None, 0, 0, 0, None, 1, 1, None, None, None, 1.0, None) == EINVAL
 
 
+def test_tuning_switches(lib):
+    """Switches are set and read back through the ABI; unknown knobs and values out of range are refused."""
+    from paper_2504_09135_amd import binding
+    v = C.c_int32(-7)
+    for knob in range(6):
+        assert lib.ppv_tuning_get(knob, C.byref(v)) == 0 and v.value >= 0
+    assert lib.ppv_tuning_get(6, C.byref(v)) == -1 and lib.ppv_tuning_get(0, None) == -1
+    assert lib.ppv_tuning_set(-1, 0) == -1 and lib.ppv_tuning_set(6, 0) == -1
+    assert lib.ppv_tuning_set(binding.PPV_TUNE_WAVES_PER_ROW, 17) == -4
+    before = binding.ppv_tuning_get(binding.PPV_TUNE_TOPM_WAVES)
+    binding.ppv_tuning_set(binding.PPV_TUNE_TOPM_WAVES, 2)
+    assert binding.ppv_tuning_get(binding.PPV_TUNE_TOPM_WAVES) == 2
+    binding.ppv_tuning_set(binding.PPV_TUNE_TOPM_WAVES, before)
+
+
 def test_index_load_rejects_files_that_are_not_an_index(lib, tmp_path):
     """Everything that can be told from the header and the file's length is refused before any device call."""
     out = C.c_void_p()

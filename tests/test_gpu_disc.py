@@ -115,3 +115,68 @@ def test_disc_end_to_end_on_theorem_2_1_toy():
     ps = pl / pl.sum()
     kl = lambda p, q: float((p * np.log(p / q)).sum())
     assert kl(ps, law) < kl(ps, pcd)
+
+
+def test_rows_that_cannot_draw_a_token_get_score_zero_and_are_never_returned():
+    """A row whose valid tokens all have probability 0 stops outside S with logx = -inf (Algorithm 1's update
+    multiplies x by a valid mass of 0), through ppv_decode_step and through ppv_decode_loop, as the oracle's loop
+    says; ppv_disc_select then never returns it, and returns -1 when no candidate of a query is alive."""
+    V = 4
+    S = W.constraint_set_from_lists([[0, 1], [0, 2], [1, 3]], V)
+    trie = oracle.Trie(S.tokens, S.offsets, V)
+    index = ppv.ppv_build_index(S.tokens, S.offsets, V)
+    B = 64
+    rng = np.random.default_rng(12)
+    un = rng.random((2, B), dtype=np.float32)
+    first = np.log(np.array([0.5, 0.25, 0.125, 0.125])).astype(np.float32)
+    after0 = np.array([0.3, -np.inf, -np.inf, 0.1], np.float32)      # both continuations of [0] have probability 0
+    after1 = np.log(np.array([0.1, 0.2, 0.3, 0.4])).astype(np.float32)
+
+    def logits_for_step(step, seqs_now, lens_now):
+        if step == 0:
+            return np.broadcast_to(first, (B, V)).copy()
+        return np.stack([after0 if seqs_now[b, 0] == 0 else after1 for b in range(B)])
+    ref = oracle.decode_loop(trie, B, logits_for_step, lambda s: un[s])
+    assert ref.dead.any() and not ref.dead.all()
+    step1 = logits_for_step(1, ref.seqs, ref.lens)
+    lg = torch.stack([to_dev(np.broadcast_to(first, (B, V)).copy()), to_dev(step1)])
+    for one_launch in (False, True):
+        P = torch.full((B, 2), W.PAD_TOKEN, dtype=torch.int32, device=DEV)
+        lens = torch.zeros(B, dtype=torch.int32, device=DEV)
+        act = torch.zeros(B, dtype=torch.uint8, device=DEV)
+        state = torch.zeros((B, ppv.PPV_STATE_WORDS), dtype=torch.int32, device=DEV)
+        logx = torch.zeros(B, dtype=torch.float32, device=DEV)
+        ids = torch.full((2, B), -5, dtype=torch.int32, device=DEV)
+        ppv.ppv_decode_begin(index, P, lens, state, act, logx)
+        if one_launch:
+            ppv.ppv_decode_loop(index, P, lens, act, lg, to_dev(un), ids, None, logx, state=state)
+        else:
+            for s in range(2):
+                ppv.ppv_decode_step(index, P, lens, act, lg[s], to_dev(un[s]), ids[s], None, logx, state=state)
+        torch.cuda.synchronize()
+        glx, gl, gid = logx.cpu().numpy(), lens.cpu().numpy(), ids.cpu().numpy()
+        assert not act.any().item()
+        assert np.array_equal(gl, ref.lens) and np.array_equal(P.cpu().numpy()[:, 0], ref.seqs[:, 0])
+        assert (glx[ref.dead] == -np.inf).all() and (gid[1][ref.dead] == -1).all()
+        assert np.allclose(glx[~ref.dead], ref.logx[~ref.dead], atol=1e-5)
+    # selection: 16 queries x 4 candidates (K = 2) made of these rows
+    K, Q = 2, B // 4
+    lx = glx.reshape(4, Q).copy()
+    lx[:, 0] = -np.inf                                               # a query none of whose candidates is alive
+    au = rng.random((K, Q), dtype=np.float32)
+    au[:, 1::2] = 0.9999                                             # every second query goes to the fallback
+    ru = rng.random(Q, dtype=np.float32)
+    for reuse in (False, True):
+        ch, nd, acc = oracle.disc_select(lx, K, au, ru, reuse_rejected=reuse)
+        d_ch = torch.full((Q,), -3, dtype=torch.int32, device=DEV)
+        d_nd = torch.full((Q,), -3, dtype=torch.int32, device=DEV)
+        d_acc = torch.full((Q,), 9, dtype=torch.uint8, device=DEV)
+        ppv.ppv_disc_select(to_dev(lx), K, to_dev(au), to_dev(ru), d_ch, d_nd, d_acc, reuse_rejected=reuse)
+        torch.cuda.synchronize()
+        g = d_ch.cpu().numpy()
+        assert np.array_equal(g, ch) and np.array_equal(d_nd.cpu().numpy(), nd)
+        assert np.array_equal(d_acc.cpu().numpy().astype(np.int32), acc)
+        assert g[0] == -1
+        alive = g >= 0
+        assert np.isfinite(lx[g[alive], np.nonzero(alive)[0]]).all()
+    index.free()

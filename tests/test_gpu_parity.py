@@ -9,7 +9,7 @@ from paper_2504_09135_amd import binding as ppv
 from paper_2504_09135_amd import workloads as W
 
 from gpu_helpers import (DEV, assert_query_parity, check_sample_rows, follow_loop, gpu_query, gpu_sample, logits_to_dev,
-                         to_dev, unpack_mask)
+                         to_dev, tuning, unpack_mask)
 
 pytestmark = pytest.mark.gpu
 
@@ -163,7 +163,7 @@ def test_decode_step_equals_mask_plus_sample(name):
     check_sample_rows(cfg.dtype, sub, lambda i: ref.mask[rows[i]], un[rows], gid[rows], glz[rows], None, rows=rows)
     for b in rows:
         if gid[b] < 0:
-            assert gL[b] == pb.lens[b] and gA[b] == 0 and np.array_equal(gP[b], P[b]) and glx[b] == 0.25
+            assert gL[b] == pb.lens[b] and gA[b] == 0 and np.array_equal(gP[b], P[b]) and glx[b] == -np.inf
             continue
         assert gL[b] == pb.lens[b] + 1 and gP[b, pb.lens[b]] == gid[b]
         assert np.array_equal(np.delete(gP[b], pb.lens[b]), np.delete(P[b], pb.lens[b]))
@@ -540,14 +540,14 @@ def test_binding_rejects_bad_arguments():
 
 
 @pytest.mark.parametrize("mode", ["weak", "off"])
-def test_prefix_lookup_modes(mode, monkeypatch):
-    """Prefixes are located through a hash table whose hits are only hints.  PPV_LOOKUP_WEAK=1 builds the table
+def test_prefix_lookup_modes(mode):
+    """Prefixes are located through a hash table whose hits are only hints.  PPV_TUNE_LOOKUP_WEAK = 1 builds the table
     with a single fingerprint, so that every probe returns some node and the exact check has to turn the wrong
-    ones away; PPV_LOOKUP=0 builds none.  Masks, ranges and membership must not change, for valid, corrupted,
+    ones away; PPV_TUNE_LOOKUP = 0 builds none.  Masks, ranges and membership must not change, for valid, corrupted,
     random, over-long and empty prefixes alike."""
-    monkeypatch.setenv("PPV_LOOKUP_WEAK" if mode == "weak" else "PPV_LOOKUP", "1" if mode == "weak" else "0")
     cfg, S, trie, _ = setup_case("C2")
-    index = ppv.ppv_build_index(S.tokens, S.offsets, cfg.vocab)
+    with tuning(ppv.PPV_TUNE_LOOKUP_WEAK if mode == "weak" else ppv.PPV_TUNE_LOOKUP, 1 if mode == "weak" else 0):
+        index = ppv.ppv_build_index(S.tokens, S.offsets, cfg.vocab)
     pb = W.make_prefix_batch(cfg, S)
     B = pb.prefixes.shape[0]
     stride = 80                                               # longer than a wavefront and than any member

@@ -12,7 +12,7 @@ import oracle
 from paper_2504_09135_amd import binding as ppv
 from paper_2504_09135_amd import workloads as W
 
-from gpu_helpers import DEV, check_sample_rows, gpu_query, gpu_sample, logits_to_dev, to_dev, unpack_mask
+from gpu_helpers import DEV, check_sample_rows, gpu_query, gpu_sample, logits_to_dev, to_dev, tuning, unpack_mask
 from test_gpu_parity import setup_case
 
 pytestmark = [pytest.mark.gpu, pytest.mark.timeout(600)]
@@ -91,12 +91,12 @@ def test_topm_ties_special_values_and_ragged_rows(dtype):
 
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
-@pytest.mark.parametrize("waves", ["1", "2", "16"])
-def test_topm_any_number_of_wavefronts_per_row(dtype, waves, monkeypatch):
-    """The wavefronts per row are a launch detail (PPV_TOPM_WAVES overrides the choice): with one or two, a wavefront's
+@pytest.mark.parametrize("waves", [1, 2, 16])
+def test_topm_any_number_of_wavefronts_per_row(dtype, waves):
+    """The wavefronts per row are a launch detail (PPV_TUNE_TOPM_WAVES overrides the choice): with one or two, a wavefront's
     share no longer stays in registers between the two passes; with sixteen, shares are ragged or empty.  Same results."""
-    monkeypatch.setenv("PPV_TOPM_WAVES", waves)
-    ties_and_special_values(dtype, Ms=(1, 7, 64, 128, 1000))
+    with tuning(ppv.PPV_TUNE_TOPM_WAVES, waves):
+        ties_and_special_values(dtype, Ms=(1, 7, 64, 128, 1000))
 
 
 def ties_and_special_values(dtype, Ms=(1, 7, 64, 1000)):
@@ -163,26 +163,25 @@ def test_topm_largest_vocabulary():
     index.free()
 
 
-def test_topm_whole_row_select_path(monkeypatch):
+def test_topm_whole_row_select_path():
     """The selection has two routes (bound + short list; radix select over the whole row when the list would not
-    fit).  PPV_TOPM_STREAMING=1 sends every row down the second one: same results."""
-    monkeypatch.setenv("PPV_TOPM_STREAMING", "1")
-    for name in ("C2", "C3s", "C5s"):
-        cfg, S, trie, index = setup_case(name)
-        X = sorted_array(name)
-        pb = W.make_prefix_batch(cfg, S)
-        logits = W.make_logits(cfg)
-        lf = W.logits_as_f32(cfg, logits)
-        ld = logits_to_dev(cfg, logits)
-        for M in (1, 50, 1000):
-            assert_topm_parity(index, X, pb.prefixes, pb.lens, lf, ld, M)
+    fit).  PPV_TUNE_TOPM_STREAMING = 1 sends every row down the second one: same results."""
+    with tuning(ppv.PPV_TUNE_TOPM_STREAMING, 1):
+        for name in ("C2", "C3s", "C5s"):
+            cfg, S, trie, index = setup_case(name)
+            X = sorted_array(name)
+            pb = W.make_prefix_batch(cfg, S)
+            logits = W.make_logits(cfg)
+            lf = W.logits_as_f32(cfg, logits)
+            ld = logits_to_dev(cfg, logits)
+            for M in (1, 50, 1000):
+                assert_topm_parity(index, X, pb.prefixes, pb.lens, lf, ld, M)
 
 
-@pytest.mark.parametrize("waves", ["2", "8"])
-def test_topm_rows_with_nans_stay_in_bounds(waves, monkeypatch):
+@pytest.mark.parametrize("waves", [2, 8])
+def test_topm_rows_with_nans_stay_in_bounds(waves):
     """A row that holds NaNs has unspecified candidates, but its ids stay inside [0, V) or -1, its mask only holds
     tokens of the full mask, and the rows beside it are as the oracle says."""
-    monkeypatch.setenv("PPV_TOPM_WAVES", waves)
     name = "C3s"
     cfg, S, trie, index = setup_case(name)
     X = sorted_array(name)
@@ -203,7 +202,8 @@ def test_topm_rows_with_nans_stay_in_bounds(waves, monkeypatch):
     good = np.setdiff1d(np.arange(lf.shape[0]), bad_rows)
     full = trie.query(pb.prefixes, pb.lens).mask
     for M in (50, 1000):
-        dmask, top, mv = gpu_topm(index, pb.prefixes, pb.lens, ld, M)
+        with tuning(ppv.PPV_TUNE_TOPM_WAVES, waves):
+            dmask, top, mv = gpu_topm(index, pb.prefixes, pb.lens, ld, M)
         assert ((top >= -1) & (top < cfg.vocab)).all()
         got = unpack_mask(dmask.cpu().numpy().view(np.uint32), cfg.vocab)
         assert not (got & ~full).any()
