@@ -69,8 +69,10 @@ class LoopBench:
                 self.loop()
             torch.cuda.current_stream().wait_stream(side)
             torch.cuda.synchronize()
+            # (captured on the stream that has just run the loop: a stream under capture cannot allocate, and the
+            # library keeps per-stream scratch for rows it spreads over several workgroups)
             self.graph = torch.cuda.CUDAGraph()
-            with torch.cuda.graph(self.graph):
+            with torch.cuda.graph(self.graph, stream=side):
                 self.loop()
         self.run = self.graph.replay if self.graph is not None else self.loop
 
@@ -348,7 +350,7 @@ def topm_sweep(cfg, S, index, logits0, torch, ppv, W, dev, reps=40):
         torch.cuda.current_stream().wait_stream(side)
         torch.cuda.synchronize()
         graph = torch.cuda.CUDAGraph()
-        with torch.cuda.graph(graph):
+        with torch.cuda.graph(graph, stream=side):
             for _ in range(reps):
                 fn()
         graph.replay()
@@ -427,7 +429,7 @@ def single_call_bench(args, cfg, torch, ppv, W, dev):
         torch.cuda.current_stream().wait_stream(side)
         torch.cuda.synchronize()
         graph = torch.cuda.CUDAGraph()
-        with torch.cuda.graph(graph):
+        with torch.cuda.graph(graph, stream=side):
             for k in range(n):
                 fn(k)
         graph.replay()

@@ -55,6 +55,27 @@ struct IndexView {
     int32_t l_max;
 };
 
+// A row spread over several workgroups (small batches: fewer rows than compute units).  Every workgroup reduces
+// its share of the row's tiles and of the listed tokens and leaves the per-tile / per-slice statistics here; the
+// workgroup that arrives last (one device-scope counter per row) reads them all back and finishes the row exactly
+// as a single workgroup would: the statistics do not depend on who computed them, so results are bit for bit
+// those of an unsplit row.  The counter is returned to zero by the workgroup that finishes the row.
+constexpr int PPV_MAX_TILES = 256;          // PPV_MAX_VOCAB / 1024 (fp32 tiles are 1024 tokens)
+constexpr int PPV_SPLIT_MAX_ROWS = 512;     // larger batches fill the chip with one workgroup per row
+constexpr int PPV_SPLIT_MAX_PARTS = 16;
+struct SplitRow {
+    float4 tile[PPV_MAX_TILES];             // (reference, sum over all tokens, sum over valid tokens, its reference)
+    float list_e[PPV_LIST_MAX];
+    float slice_m[PPV_LIST_MAX / 64], slice_z[PPV_LIST_MAX / 64];
+};
+struct SplitScratch {
+    uint32_t arrivals[PPV_SPLIT_MAX_ROWS];
+    SplitRow row[PPV_SPLIT_MAX_ROWS];
+};
+// The scratch area of (current device, stream), allocated at the first call that needs one; nullptr when it
+// cannot be had (the stream is being captured and has none yet, or out of memory): the row is then not split.
+SplitScratch *ppv_split_scratch(hipStream_t stream);
+
 // Per-row decoding cursor kept between decode steps (PPV_STATE_WORDS x uint32).
 struct RowState {
     uint32_t node;   // entry of the row's current prefix; PPV_NO_SLOT: not a prefix of any member

@@ -26,7 +26,7 @@ namespace {
 constexpr int MASK_THREADS = 256;
 constexpr int MAX_WAVES = 16;                 // wavefronts per row (workgroup of up to 1024 threads)
 constexpr int LOOP_WAVES = 8;                 // the decode-loop kernel holds more in registers: at most 512 threads
-constexpr int MAX_TILES = 256;                // PPV_MAX_VOCAB / 1024 (fp32 tiles are 1024 tokens)
+constexpr int MAX_TILES = PPV_MAX_TILES;
 constexpr float LN2F = 0.693147180559945309417f;
 static_assert(PPV_MAX_VOCAB <= MAX_TILES * 1024, "tile bookkeeping too small");
 
@@ -426,6 +426,32 @@ struct RowOut {
     int32_t pos;       // list path: position of the sampled token in the list, else -1
     float logZ_valid;
     float logZ_all;
+    bool mine;         // this thread holds the row's result (wavefront 0 of the workgroup that finishes the row;
+                       // every thread of it with ALL)
+};
+
+// Words that the workgroups of a split row hand to one another are written and read with device-scope accesses
+// (each goes to the level of the memory system that all compute units share), so that no fence over the whole
+// cache is needed: a device-wide fence per wavefront cost 30 us per launch, these cost about two.
+__device__ inline void shared_put(float *p, float v) { __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
+__device__ inline float shared_get(const float *p) {
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ inline void shared_put_tile(SplitRow *r, int k, float m, float zall, float zval, float ref) {
+    float *t = (float *)&r->tile[k];
+    shared_put(t + 0, m);
+    shared_put(t + 1, zall);
+    shared_put(t + 2, zval);
+    shared_put(t + 3, ref);
+}
+
+// A row shared by `parts` workgroups (see SplitRow); parts == 1: one workgroup has the row to itself and
+// nothing else here is looked at.
+struct Split {
+    int parts;
+    int part;             // this workgroup's number, 0 .. parts-1
+    SplitRow *row;        // the row's scratch
+    uint32_t *arrivals;   // the row's arrival counter
 };
 
 enum ValidMode { VALID_NONE = 0, VALID_LIST = 1, VALID_IMAGE = 2 };
@@ -442,10 +468,12 @@ enum ValidMode { VALID_NONE = 0, VALID_LIST = 1, VALID_IMAGE = 2 };
 // loader by the wave whose turn it is.
 // `mid` is work of the caller's that needs no tile (the sums over the listed tokens): it is run once, at the first
 // point where this wavefront has just asked for a tile and would only wait for it; never, if there is no such point.
+// `wave_v` of `nw`: the wavefront's number among all wavefronts that share the row (over all its workgroups);
+// `pub`: where a split row's statistics are left for the workgroup that finishes it (nullptr: not split).
 template <typename T, bool IMAGE, bool PIPE, typename SH, typename MID>
 __device__ inline void stream_tiles(const T *__restrict__ row, int V, const RawTile &first,
                                     const uint32_t *__restrict__ image, SH &sh, int lane, int wave_v,
-                                    int nw, const Temper &tp, MID &mid) {
+                                    int nw, const Temper &tp, MID &mid, SplitRow *pub) {
     using G = TileGeom<T>;
     const int wave = __builtin_amdgcn_readfirstlane(wave_v);   // scalar: loop control stays uniform
     const int nt = (V + G::TILE - 1) / G::TILE;
@@ -459,6 +487,7 @@ __device__ inline void stream_tiles(const T *__restrict__ row, int V, const RawT
             sh.tile_zall[k] = zall;
             sh.tile_zval[k] = zval;
             sh.tile_ref[k] = m;
+            if (pub) shared_put_tile(pub, k, m, zall, zval, m);
         }
     };
     auto fetch = [&](RawTile &t, int k) {   // a full tile and, on the image path, its mask word
@@ -517,21 +546,26 @@ __device__ inline void stream_tiles(const T *__restrict__ row, int V, const RawT
 //                VALID_IMAGE: image (global memory, V bits) is the valid set
 //                VALID_NONE: the valid set is empty
 //   ALL          every thread gets the result (one more barrier); otherwise only wavefront 0 does
+//   sp           the row's split over workgroups: `first` is then tile sp.part * nw + wave, and only the
+//                workgroup that arrives last goes on to sample (the others return with mine == false)
 template <typename T, bool PIPE, typename SH, bool ALL>
 __device__ inline RowOut row_sample(const T *__restrict__ row, int V, const RawTile &first, int mode, int n_list,
                                     const uint32_t *__restrict__ image, float u, SH &sh, int tid, int nw,
-                                    const Temper &tp, const T *__restrict__ next_row = nullptr,
+                                    const Temper &tp, const Split &sp, const T *__restrict__ next_row = nullptr,
                                     RawTile *next_first = nullptr) {
     using G = TileGeom<T>;
     const int lane = tid & (WAVE - 1), wave = tid / WAVE;
     const int nt = (V + G::TILE - 1) / G::TILE;
+    // the wavefront's number and count over all workgroups of the row: tiles and list slices are dealt out by these
+    const int vwave = sp.part * nw + wave, vnw = sp.parts * nw;
+    SplitRow *pub = sp.parts > 1 ? sp.row : nullptr;
 
     // ---- list path, part 1: ask for the listed tokens' logits now (they are being streamed
     // anyway, so these are cache hits) so that they arrive while the tiles are reduced
     const int ns = (n_list + WAVE - 1) / WAVE;
     float gx = -INFINITY;   // this lane's listed logit of the wave's first slice
-    if (mode == VALID_LIST && wave < ns) {
-        const int i = wave * WAVE + lane;
+    if (mode == VALID_LIST && vwave < ns) {
+        const int i = vwave * WAVE + lane;
         if (i < n_list) {
             const uint32_t v = sh.list_tok[i] & PPV_NODE_TOKEN;
             if (sizeof(T) == 4) gx = __uint_as_float(((const uint32_t *)row)[v]);
@@ -545,10 +579,10 @@ __device__ inline RowOut row_sample(const T *__restrict__ row, int V, const RawT
     auto list_sums = [&]() {
         list_done = true;
         if (mode != VALID_LIST) return;
-        for (int s = wave; s < ns; s += nw) {
+        for (int s = vwave; s < ns; s += vnw) {
             const int i = s * WAVE + lane;
             float x = gx;
-            if (s != wave) {
+            if (s != vwave) {
                 x = -INFINITY;
                 if (i < n_list) {
                     const uint32_t v = sh.list_tok[i] & PPV_NODE_TOKEN;
@@ -563,33 +597,70 @@ __device__ inline RowOut row_sample(const T *__restrict__ row, int V, const RawT
                 const float fix = fast_exp2(-fmaf(m, tp.c, -mc));
                 e = fast_exp2(fmaf(x, tp.c, -mc)) * fix;   // x = -inf gives 0
             }
-            if (i < n_list) sh.list_e[i] = e;
+            if (i < n_list) {
+                sh.list_e[i] = e;
+                if (pub) shared_put(&pub->list_e[i], e);
+            }
             const float z = wave_sum(e);
             if (lane == 0) {
                 sh.slice_m[s] = m;
                 sh.slice_z[s] = z;
+                if (pub) {
+                    shared_put(&pub->slice_m[s], m);
+                    shared_put(&pub->slice_z[s], z);
+                }
             }
         }
     };
     // ---- stream: every tile once
-    if (mode == VALID_IMAGE) stream_tiles<T, true, PIPE, SH>(row, V, first, image, sh, lane, wave, nw, tp, list_sums);
-    else stream_tiles<T, false, PIPE, SH>(row, V, first, image, sh, lane, wave, nw, tp, list_sums);
+    if (mode == VALID_IMAGE) stream_tiles<T, true, PIPE, SH>(row, V, first, image, sh, lane, vwave, vnw, tp, list_sums, pub);
+    else stream_tiles<T, false, PIPE, SH>(row, V, first, image, sh, lane, vwave, vnw, tp, list_sums, pub);
     if (!list_done) list_sums();
     // (decode loop) the row of the next step is known already: ask for this wave's first tile of it
     // now, so that it travels while this row is combined and sampled
     if (next_row && wave < nt) load_tile<T>(next_row, V, wave, lane, *next_first);
+    RowOut none;
+    none.id = -1;
+    none.pos = -1;
+    none.logZ_valid = -INFINITY;
+    none.logZ_all = 0.f;
+    none.mine = false;
+    if (sp.parts > 1) {
+        // Every wavefront waits until its device-scope stores have been taken by the memory system, then the
+        // workgroup's arrival is counted.  The workgroup that finds all the others already there finishes the
+        // row (its reads are device-scope too, and issued after the count has come back); nobody waits for anybody.
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+        __builtin_amdgcn_s_waitcnt(0);     // vmcnt(0) expcnt(0) lgkmcnt(0)
+        __syncthreads();
+        if (tid == 0) {
+            const uint32_t before = __hip_atomic_fetch_add(sp.arrivals, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            const bool last = before + 1u == (uint32_t)sp.parts;
+            if (last) __hip_atomic_store(sp.arrivals, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // the next launch starts from zero
+            sh.bc_i[0] = last ? 1 : 0;
+        }
+        __syncthreads();
+        if (!sh.bc_i[0]) return none;      // uniform for the workgroup
+        const int nthreads = nw * WAVE;
+        for (int k = tid; k < nt; k += nthreads) {
+            const float *t = (const float *)&pub->tile[k];
+            sh.tile_m[k] = shared_get(t + 0);
+            sh.tile_zall[k] = shared_get(t + 1);
+            sh.tile_zval[k] = shared_get(t + 2);
+            sh.tile_ref[k] = shared_get(t + 3);
+        }
+        if (mode == VALID_LIST) {
+            for (int i = tid; i < n_list; i += nthreads) sh.list_e[i] = shared_get(&pub->list_e[i]);
+            for (int q = tid; q < ns; q += nthreads) {
+                sh.slice_m[q] = shared_get(&pub->slice_m[q]);
+                sh.slice_z[q] = shared_get(&pub->slice_z[q]);
+            }
+        }
+    }
     __syncthreads();
 
     // Nobody but wavefront 0 has anything left to do when the result goes to it alone and the set is not an
     // image (whose rare second pass needs every wavefront): the others leave its SIMD to it.
-    if (!ALL && mode != VALID_IMAGE && wave != 0) {
-        RowOut none;
-        none.id = -1;
-        none.pos = -1;
-        none.logZ_valid = -INFINITY;
-        none.logZ_all = 0.f;
-        return none;
-    }
+    if (!ALL && mode != VALID_IMAGE && wave != 0) return none;
     // ---- combine (every wave computes the same row totals from LDS; cheap, and saves a broadcast)
     float M = -INFINITY;
     for (int k = lane; k < nt; k += WAVE) M = fmaxf(M, sh.tile_m[k]);
@@ -645,11 +716,8 @@ __device__ inline RowOut row_sample(const T *__restrict__ row, int V, const RawT
     }
 
     // ---- locate: wave 0
-    RowOut out;
-    out.id = -1;
-    out.pos = -1;
-    out.logZ_valid = -INFINITY;
-    out.logZ_all = 0.f;
+    RowOut out = none;
+    out.mine = ALL || wave == 0;
     if (wave == 0) {
         const float l2za = fast_log2((float)za);
         int id = -1, pos = -1;
@@ -780,26 +848,51 @@ __global__ __launch_bounds__(SMALL ? SMALL_TILES * WAVE : MAX_WAVES * WAVE) void
                                                                   int n_words, int list_max,
                                                                   int32_t *__restrict__ ids,
                                                                   float *__restrict__ logZ_valid,
-                                                                  float *__restrict__ logZ_all, Temper tp) {
+                                                                  float *__restrict__ logZ_all, Temper tp,
+                                                                  int split_shift, SplitScratch *scratch) {
     using G = TileGeom<T>;
     using SH = typename std::conditional<SMALL, RowSharedSmall, RowShared>::type;
     __shared__ SH sh;
-    const int b = blockIdx.x, tid = threadIdx.x, lane = tid & (WAVE - 1), wave = tid / WAVE;
+    // a row is shared by 1 << split_shift consecutive workgroups
+    const int b = (int)(blockIdx.x >> split_shift), tid = threadIdx.x, lane = tid & (WAVE - 1), wave = tid / WAVE;
     const int nw = blockDim.x / WAVE;
+    Split sp;
+    sp.parts = 1 << split_shift;
+    sp.part = (int)(blockIdx.x & (unsigned)(sp.parts - 1));
+    sp.row = split_shift ? &scratch->row[b] : nullptr;
+    sp.arrivals = split_shift ? &scratch->arrivals[b] : nullptr;
+    const int vwave = sp.part * nw + wave;
     const T *row = logits + (size_t)b * (size_t)row_stride;
     const uint32_t *mrow = mask + (size_t)b * (size_t)n_words;
     const int nt = (V + G::TILE - 1) / G::TILE;
-    // the mask word of the wave's first tile is requested before the tile itself: memory answers a wavefront in
-    // the order of its requests, so the few bytes the next steps wait for must not queue behind the 4 KB tile
-    const uint32_t w_first = tile_mask_word<T>(mrow, wave < nt ? wave : 0, lane, V);
+    // The mask words of the wave's first MASK_BATCH tiles are requested together, and before the logits tile: memory
+    // answers a wavefront in the order of its requests, so the few bytes the next steps wait for must not queue
+    // behind the 4 KB tile; and one request after the other (a loop of load, count, load, ...) costs a memory round
+    // trip per tile, which at 63 tiles on 4 wavefronts was most of the kernel.  (Tiles past the row read as 0.)
+    constexpr int MASK_BATCH = 8;
+    uint32_t mw0[MASK_BATCH];
+#pragma unroll
+    for (int j = 0; j < MASK_BATCH; j++) mw0[j] = tile_mask_word<T>(mrow, wave + j * nw, lane, V);
     RawTile first;
-    if (wave < nt) load_tile<T>(row, V, wave, lane, first);   // in flight during the mask work
+    if (vwave < nt) load_tile<T>(row, V, vwave, lane, first);   // in flight during the mask work
 
     // bits per tile (a tile's mask words are consecutive: one word per lane)
-    for (int k = wave; k < nt; k += nw) {
-        const uint32_t w = k == wave ? w_first : tile_mask_word<T>(mrow, k, lane, V);
-        const int c = wave_sum((int)__popc(w));
-        if (lane == 0) sh.tile_cnt[k] = c;
+#pragma unroll
+    for (int j = 0; j < MASK_BATCH; j++) {
+        const int k = wave + j * nw;
+        const int c = wave_sum((int)__popc(mw0[j]));
+        if (lane == 0 && k < nt) sh.tile_cnt[k] = c;
+    }
+    for (int k0 = wave + MASK_BATCH * nw; k0 < nt; k0 += MASK_BATCH * nw) {   // long rows on few wavefronts
+        uint32_t mw[MASK_BATCH];
+#pragma unroll
+        for (int j = 0; j < MASK_BATCH; j++) mw[j] = tile_mask_word<T>(mrow, k0 + j * nw, lane, V);
+#pragma unroll
+        for (int j = 0; j < MASK_BATCH; j++) {
+            const int k = k0 + j * nw;
+            const int c = wave_sum((int)__popc(mw[j]));
+            if (lane == 0 && k < nt) sh.tile_cnt[k] = c;
+        }
     }
     __syncthreads();
     int total = 0;
@@ -807,23 +900,32 @@ __global__ __launch_bounds__(SMALL ? SMALL_TILES * WAVE : MAX_WAVES * WAVE) void
     total = wave_sum(total);
     const int mode = total == 0 ? VALID_NONE : (total <= list_max ? VALID_LIST : VALID_IMAGE);
     if (mode == VALID_LIST) {
-        for (int k = wave; k < nt; k += nw) {
+        auto unpack_tile = [&](int k, uint32_t w) {   // tile k's valid tokens go to their places in the list
+            if (sh.tile_cnt[k] == 0) return;          // (uniform) most tiles of a short list hold none
             int base = 0;  // valid tokens in the tiles before k
             for (int q = lane; q < k; q += WAVE) base += sh.tile_cnt[q];
             base = wave_sum(base);
             const int wi = k * G::WORDS + lane;
-            uint32_t w = k == wave ? w_first : tile_mask_word<T>(mrow, k, lane, V);
             int at = base + wave_incl_scan((int)__popc(w)) - (int)__popc(w);
             while (w) {
                 const int bit = __ffs((int)w) - 1;
                 sh.list_tok[at++] = (uint32_t)(wi * 32 + bit);
                 w &= w - 1u;
             }
+        };
+#pragma unroll
+        for (int j = 0; j < MASK_BATCH; j++) {
+            const int k = wave + j * nw;
+            if (k < nt) unpack_tile(k, mw0[j]);
+        }
+        for (int k = wave + MASK_BATCH * nw; k < nt; k += nw) {
+            if (sh.tile_cnt[k] == 0) continue;
+            unpack_tile(k, tile_mask_word<T>(mrow, k, lane, V));
         }
         __syncthreads();
     }
-    RowOut r = row_sample<T, PIPE, SH, false>(row, V, first, mode, mode == VALID_LIST ? total : 0, mrow, uniforms[b], sh, tid, nw, tp);
-    if (tid == 0) {
+    RowOut r = row_sample<T, PIPE, SH, false>(row, V, first, mode, mode == VALID_LIST ? total : 0, mrow, uniforms[b], sh, tid, nw, tp, sp);
+    if (r.mine && tid == 0) {
         ids[b] = r.id;
         logZ_valid[b] = r.logZ_valid;
         if (logZ_all) logZ_all[b] = r.logZ_all;
@@ -908,11 +1010,18 @@ __global__ __launch_bounds__(LOOP ? LOOP_WAVES * WAVE : MAX_WAVES * WAVE) void d
     IndexView ix, int32_t *__restrict__ prefixes, int32_t stride, int32_t *__restrict__ lens,
     uint8_t *__restrict__ active, RowState *__restrict__ state, const T *__restrict__ logits, int64_t row_stride,
     int64_t step_stride, const float *__restrict__ uniforms, int n_steps, int B, int32_t *__restrict__ ids,
-    float *__restrict__ logZ_valid, float *__restrict__ logx, Temper tp) {
+    float *__restrict__ logZ_valid, float *__restrict__ logx, Temper tp, int split_shift, SplitScratch *scratch) {
     using G = TileGeom<T>;
     __shared__ RowShared sh;
-    const int b = blockIdx.x, tid = threadIdx.x, lane = tid & (WAVE - 1), wave = tid / WAVE;
+    // a row is shared by 1 << split_shift consecutive workgroups (never in the loop kernel)
+    const int b = (int)(blockIdx.x >> split_shift), tid = threadIdx.x, lane = tid & (WAVE - 1), wave = tid / WAVE;
     const int nw = blockDim.x / WAVE;
+    Split sp;
+    sp.parts = LOOP ? 1 : 1 << split_shift;
+    sp.part = (int)(blockIdx.x & (unsigned)(sp.parts - 1));
+    sp.row = sp.parts > 1 ? &scratch->row[b] : nullptr;
+    sp.arrivals = sp.parts > 1 ? &scratch->arrivals[b] : nullptr;
+    const int vwave = sp.part * nw + wave;
     // the independent per-row loads go out together
     const uint8_t on = active[b];
     int t = lens[b];
@@ -927,7 +1036,7 @@ __global__ __launch_bounds__(LOOP ? LOOP_WAVES * WAVE : MAX_WAVES * WAVE) void d
     const T *row = logits + (size_t)b * (size_t)row_stride;
     const int nt = (V + G::TILE - 1) / G::TILE;
     RawTile first;
-    if (wave < nt) load_tile<T>(row, V, wave, lane, first);   // in flight during the index work
+    if (vwave < nt) load_tile<T>(row, V, vwave, lane, first);   // in flight during the index work
     t = t < 0 ? 0 : (t > stride ? stride : t);
     if (!state) {  // no cursor: locate the prefix from the root (wave 0), then share it
         if (wave == 0) {
@@ -986,8 +1095,8 @@ __global__ __launch_bounds__(LOOP ? LOOP_WAVES * WAVE : MAX_WAVES * WAVE) void d
         float next_u = 0.f;
         if (more) next_u = uniforms[(size_t)(s + 1) * (size_t)B + b];
         RowOut r = row_sample<T, PIPE, RowShared, LOOP>(row, V, first, mode, mode == VALID_LIST ? nchild : 0, image, u, sh, tid, nw,
-                                                  tp, next_row, &next_first);
-        if (tid == 0) {
+                                                  tp, sp, next_row, &next_first);
+        if (r.mine && tid == 0) {
             const bool room = t < stride;
             int32_t id = -1;
             done = true;  // no valid token or no room: the row cannot continue
@@ -1090,9 +1199,12 @@ ppv_status check_logits_args(const void *logits, ppv_dtype dt, int64_t row_strid
 // 16 wavefronts per row, 1.08 with 8, 0.93 with 4; B=512: 1.31 / 1.64 / 1.57; B=1024: 2.28 with 8,
 // 2.50 with 4, 2.37 with 2; B=4096: 2.1 with 16, 3.4 with 8, 4.3 with 4, 4.1 with 2; and at
 // V=256k: B=256: 3.8 with 16, 1.3 with 2; B=1024: 5.05 with 4, 5.09 with 8, 4.4 with 16.
-int waves_for(int V, ppv_dtype dt, int B) {
+// `parts`: workgroups per row (see parts_for); the figures then hold for one workgroup's share of the row and for
+// the number of workgroups in the launch.
+int waves_for(int V, ppv_dtype dt, int B, int parts = 1) {
     const int tile = (dt == PPV_F32) ? TileGeom<float>::TILE : TileGeom<uint16_t>::TILE;
-    const int nt = (V + tile - 1) / tile;
+    const int nt = ((V + tile - 1) / tile + parts - 1) / parts;
+    B *= parts;
     int cap = B <= 128 ? 16 : (B <= 512 ? 8 : 4);
     // long rows in a small batch: one row per compute unit, all of it in flight (constrained_sample, B = 256, us per
     // call with 8 / 16 wavefronts: 32 tiles: 13.2 / 12.0 (fp32 V = 32k), 15.2 / 14.2 (bf16 V = 64k); 63 tiles: 23.6 / 20.6)
@@ -1106,34 +1218,68 @@ int waves_for(int V, ppv_dtype dt, int B) {
 // Whether some wavefront's turn has six tiles or more, i.e. whether the three-tile pipeline of stream_tiles can
 // run at all.  Kernels for shorter turns are compiled without it: 62 instead of 92 registers (bf16), which is
 // two more rows in flight per compute unit when a large batch keeps every compute unit full.
-bool long_turns(int V, ppv_dtype dt, int nw) {
+bool long_turns(int V, ppv_dtype dt, int nw) {   // nw: wavefronts per row over all its workgroups
     const int tile = (dt == PPV_F32) ? TileGeom<float>::TILE : TileGeom<uint16_t>::TILE;
     return (V / tile + nw - 1) / nw >= 6;
+}
+
+// Workgroups per row.  A batch of fewer rows than the chip has compute units leaves most of it idle with one
+// workgroup per row, and a long row alone on a compute unit is bound by that unit's arithmetic (about 4.8 us per
+// 256 KB of bf16 logits).  Such a row is spread over 2 .. 16 workgroups: a power of two, six tiles or more each, at
+// most one workgroup per compute unit.  Handing the statistics from workgroup to workgroup costs about 3 us (three
+// dependent trips to device-scope memory), so rows are split only where that is less than what the split saves:
+// row bytes x (1 - 1 / parts) >= 160 KB.  Measured, constrained_sample, bf16, us per call without / with the split:
+// V = 128,256: B = 32: 13.0 / 10.0 (list rows), 17.8 / 11.2 (image rows); B = 128: 13.6 / 14.0, 18.7 / 16.1 (two
+// parts: not split); V = 32,000, B = 64: 7.4 / 9.1 (not split).  PPV_TUNE_ROW_SPLIT forces a number of parts.
+// The scratch area the parts meet in comes with the stream; without one (see ppv_split_scratch) rows are not split.
+int parts_for(int V, ppv_dtype dt, int B, hipStream_t hs, SplitScratch **scratch) {
+    *scratch = nullptr;
+    const int tile = (dt == PPV_F32) ? TileGeom<float>::TILE : TileGeom<uint16_t>::TILE;
+    const int nt = (V + tile - 1) / tile;
+    if (B > PPV_SPLIT_MAX_ROWS) return 1;
+    int parts = ppv_tuning(PPV_TUNE_ROW_SPLIT);
+    if (parts == 0) {
+        parts = 1;
+        while (B * parts * 2 <= 256 && parts * 2 <= PPV_SPLIT_MAX_PARTS && nt / (parts * 2) >= 6) parts *= 2;
+        const double row_kb = (double)V * (dt == PPV_F32 ? 4.0 : 2.0) / 1024.0;
+        if (row_kb * (1.0 - 1.0 / parts) < 160.0) parts = 1;
+    }
+    while (parts > 1 && ((parts & (parts - 1)) != 0 || parts * 2 > nt)) parts--;   // a power of two, two tiles each
+    if (parts > 1) {
+        *scratch = ppv_split_scratch(hs);
+        if (!*scratch) parts = 1;
+    }
+    return parts;
+}
+int shift_of(int parts) {
+    int sh = 0;
+    while ((1 << sh) < parts) sh++;
+    return sh;
 }
 
 template <typename T>
 void launch_sample(bool small, bool pipe, dim3 grid, dim3 block, hipStream_t hs, const T *lg, int64_t row_stride,
                    const uint32_t *mask, const float *uniforms, int V, int n_words, int list_max, int32_t *ids,
-                   float *logZ_valid, float *logZ_all, Temper tp) {
+                   float *logZ_valid, float *logZ_all, Temper tp, int split_shift, SplitScratch *scratch) {
     if (small)
         hipLaunchKernelGGL((sample_kernel<T, true, false>), grid, block, 0, hs, lg, row_stride, mask, uniforms, V, n_words,
-                           list_max, ids, logZ_valid, logZ_all, tp);
+                           list_max, ids, logZ_valid, logZ_all, tp, split_shift, scratch);
     else if (pipe)
         hipLaunchKernelGGL((sample_kernel<T, false, true>), grid, block, 0, hs, lg, row_stride, mask, uniforms, V, n_words,
-                           list_max, ids, logZ_valid, logZ_all, tp);
+                           list_max, ids, logZ_valid, logZ_all, tp, split_shift, scratch);
     else
         hipLaunchKernelGGL((sample_kernel<T, false, false>), grid, block, 0, hs, lg, row_stride, mask, uniforms, V,
-                           n_words, list_max, ids, logZ_valid, logZ_all, tp);
+                           n_words, list_max, ids, logZ_valid, logZ_all, tp, split_shift, scratch);
 }
 
 template <typename T>
 void launch_decode_kernel(bool loop, bool pipe, dim3 grid, dim3 block, hipStream_t hs, const IndexView &view,
                           int32_t *prefixes, int32_t stride, int32_t *lens, uint8_t *active, RowState *rs, const T *lg,
                           int64_t row_stride, int64_t step_stride, const float *uniforms, int n_steps, int B, int32_t *ids,
-                          float *logZ_valid, float *logx, Temper tp) {
+                          float *logZ_valid, float *logx, Temper tp, int split_shift, SplitScratch *scratch) {
 #define PPV_LAUNCH_DECODE(LOOP, PIPE)                                                                                 \
     hipLaunchKernelGGL((decode_kernel<T, LOOP, PIPE>), grid, block, 0, hs, view, prefixes, stride, lens, active, rs, lg, \
-                       row_stride, step_stride, uniforms, n_steps, B, ids, logZ_valid, logx, tp)
+                       row_stride, step_stride, uniforms, n_steps, B, ids, logZ_valid, logx, tp, split_shift, scratch)
     if (loop && pipe) PPV_LAUNCH_DECODE(true, true);
     else if (loop) PPV_LAUNCH_DECODE(true, false);
     else if (pipe) PPV_LAUNCH_DECODE(false, true);
@@ -1174,12 +1320,14 @@ extern "C" ppv_status constrained_sample(const void *logits, ppv_dtype dt, int64
     if (st != PPV_OK) return st;
     const int n_words = (V + 31) / 32;
     const int list_max = V / 32 < PPV_LIST_MAX ? V / 32 : PPV_LIST_MAX;
-    const int threads = waves_for(V, dt, B) * WAVE;
     const int tile = (dt == PPV_F32) ? TileGeom<float>::TILE : TileGeom<uint16_t>::TILE;
     const bool small = (V + tile - 1) / tile <= SMALL_TILES && list_max <= SMALL_LIST;   // then threads <= SMALL_TILES * WAVE
-    const bool pipe = long_turns(V, dt, threads / WAVE);
-    const dim3 grid((unsigned)B), block(threads);
     hipStream_t hs = (hipStream_t)stream;
+    SplitScratch *scratch = nullptr;
+    const int parts = (small || V <= tile) ? 1 : parts_for(V, dt, B, hs, &scratch);
+    const int threads = waves_for(V, dt, B, parts) * WAVE;
+    const bool pipe = long_turns(V, dt, parts * threads / WAVE);
+    const dim3 grid((unsigned)B * (unsigned)parts), block(threads);
     if (V <= tile) {   // the whole row is one tile
         const dim3 g1((unsigned)((B + ONE_TILE_ROWS - 1) / ONE_TILE_ROWS)), b1(ONE_TILE_ROWS * WAVE);
         if (dt == PPV_F32)
@@ -1193,10 +1341,10 @@ extern "C" ppv_status constrained_sample(const void *logits, ppv_dtype dt, int64
     }
     if (dt == PPV_F32)
         launch_sample<float>(small, pipe, grid, block, hs, (const float *)logits, row_stride, mask, uniforms, V, n_words,
-                             list_max, ids, logZ_valid, logZ_all, tp);
+                             list_max, ids, logZ_valid, logZ_all, tp, shift_of(parts), scratch);
     else
         launch_sample<uint16_t>(small, pipe, grid, block, hs, (const uint16_t *)logits, row_stride, mask, uniforms, V,
-                                n_words, list_max, ids, logZ_valid, logZ_all, tp);
+                                n_words, list_max, ids, logZ_valid, logZ_all, tp, shift_of(parts), scratch);
     PPV_HIP_TRY(hipGetLastError());
     return PPV_OK;
 }
@@ -1230,21 +1378,23 @@ ppv_status launch_decode(const ppv_index_t *ix, int32_t *prefixes, int32_t prefi
         const int64_t per16 = (dt == PPV_F32) ? 4 : 8;
         if (step_stride % per16 != 0 || step_stride < 0) return PPV_EINVAL;
     }
-    int nw = waves_for(ix->view.vocab, dt, B);
-    if (loop && nw > LOOP_WAVES) nw = LOOP_WAVES;
-    const dim3 grid((unsigned)B), block(nw * WAVE);
     hipStream_t hs = (hipStream_t)stream;
+    SplitScratch *scratch = nullptr;
+    const int parts = loop ? 1 : parts_for(ix->view.vocab, dt, B, hs, &scratch);
+    int nw = waves_for(ix->view.vocab, dt, B, parts);
+    if (loop && nw > LOOP_WAVES) nw = LOOP_WAVES;
+    const dim3 grid((unsigned)B * (unsigned)parts), block(nw * WAVE);
     RowState *rs = (RowState *)state;
-    const bool pipe = long_turns(ix->view.vocab, dt, nw);
+    const bool pipe = long_turns(ix->view.vocab, dt, parts * nw);
     if (!loop) n_steps = 1;
     if (dt == PPV_F32)
         launch_decode_kernel<float>(loop, pipe, grid, block, hs, ix->view, prefixes, prefix_stride, lens, active, rs,
                                     (const float *)logits, row_stride, step_stride, uniforms, n_steps, B, ids, logZ_valid,
-                                    logx, tp);
+                                    logx, tp, shift_of(parts), scratch);
     else
         launch_decode_kernel<uint16_t>(loop, pipe, grid, block, hs, ix->view, prefixes, prefix_stride, lens, active, rs,
                                        (const uint16_t *)logits, row_stride, step_stride, uniforms, n_steps, B, ids,
-                                       logZ_valid, logx, tp);
+                                       logZ_valid, logx, tp, shift_of(parts), scratch);
     PPV_HIP_TRY(hipGetLastError());
     return PPV_OK;
 }
