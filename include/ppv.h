@@ -158,6 +158,26 @@ ppv_status constrained_sample(const void *logits, ppv_dtype dt, int64_t row_stri
                               float *logZ_all, float temperature, void *stream);
 
 /*
+ * constrained_sample_noalloc -- constrained_sample for callers that cannot allocate device memory: code under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  constrained_sample spreads the rows
+ * of a small batch over several workgroups, which meet in a scratch area that it allocates per stream on first
+ * use; this call uses a fixed scratch array in device memory instead (about 4.3 MB, held on every GPU the library
+ * runs on until the process ends) and calls no hipMalloc, hipFree or other allocating routine, ever.  Same
+ * arguments, same results bit for bit.
+ *   B     at most PPV_NOALLOC_MAX_ROWS rows (what the array holds): PPV_ERANGE beyond.
+ * All calls on one GPU share the array: two calls of this function that overlap on one GPU (different streams)
+ * race; calls on one stream, or otherwise ordered, do not.  Nothing has to be cleared between calls: every call
+ * leaves the arrival counters at zero, which is what the next one starts from, and writes the statistics it reads.
+ * The first call on a device looks up the array's address on that device (no allocation); make that first call
+ * outside stream capture.
+ * Errors: as constrained_sample; PPV_ERANGE also for B > PPV_NOALLOC_MAX_ROWS.
+ */
+#define PPV_NOALLOC_MAX_ROWS 512
+ppv_status constrained_sample_noalloc(const void *logits, ppv_dtype dt, int64_t row_stride, const uint32_t *mask,
+                                      const float *uniforms, int32_t B, int32_t V, int32_t *ids, float *logZ_valid,
+                                      float *logZ_all, float temperature, void *stream);
+
+/*
  * ppv_decode_begin -- Algorithm 1, SampleCandidate, initialisation step: the empty candidate sequence with
  * importance score x = 1 (or resume from given prefixes).  Locates each row's current prefix once
  * and leaves a cursor in `state`, so that every following ppv_decode_step costs one level of the

@@ -26,7 +26,8 @@ PPV_STATE_WORDS = 4
 SYMBOLS = ("ppv_status_string", "ppv_build_index", "ppv_index_info", "ppv_index_export", "ppv_free_index",
            "ppv_index_save", "ppv_index_load",
            "ppv_next_token_mask", "constrained_sample", "ppv_decode_begin", "ppv_decode_step", "ppv_decode_loop", "ppv_topm_mask",
-           "ppv_disc_select", "ppv_tuning_set", "ppv_tuning_get")
+           "ppv_disc_select", "ppv_tuning_set", "ppv_tuning_get", "constrained_sample_noalloc")
+PPV_NOALLOC_MAX_ROWS = 512
 
 # tuning / test switches (ppv_tuning_set)
 (PPV_TUNE_WAVES_PER_ROW, PPV_TUNE_TOPM_WAVES, PPV_TUNE_TOPM_STREAMING, PPV_TUNE_LOOKUP, PPV_TUNE_LOOKUP_WEAK,
@@ -69,6 +70,8 @@ def load_library() -> C.CDLL:
     lib.ppv_next_token_mask.argtypes = [p, p, i32, p, i32, p, p, p, p, p]
     lib.constrained_sample.restype = C.c_int
     lib.constrained_sample.argtypes = [p, C.c_int, i64, p, p, i32, i32, p, p, p, C.c_float, p]
+    lib.constrained_sample_noalloc.restype = C.c_int
+    lib.constrained_sample_noalloc.argtypes = lib.constrained_sample.argtypes
     lib.ppv_decode_begin.restype = C.c_int
     lib.ppv_decode_begin.argtypes = [p, p, i32, p, i32, p, p, p, p]
     lib.ppv_decode_step.restype = C.c_int
@@ -214,7 +217,7 @@ def _logits_args(logits: torch.Tensor):
 
 def constrained_sample(logits: torch.Tensor, mask: torch.Tensor, uniforms: torch.Tensor, ids: torch.Tensor,
                        logZ_valid: torch.Tensor, logZ_all: Optional[torch.Tensor] = None, stream=None,
-                       temperature: float = 1.0) -> None:
+                       temperature: float = 1.0, _noalloc: bool = False) -> None:
     """logits [B, V] f32/bf16, mask int32 [B, ceil(V/32)], uniforms f32 [B] -> ids int32 [B],
     logZ_valid f32 [B], logZ_all f32 [B] (optional); P = softmax(logits / temperature)."""
     ptr, dt, row_stride = _logits_args(logits)
@@ -222,11 +225,18 @@ def constrained_sample(logits: torch.Tensor, mask: torch.Tensor, uniforms: torch
     if tuple(mask.shape) != (B, (V + 31) // 32) or tuple(uniforms.shape) != (B,) or tuple(ids.shape) != (B,) \
             or tuple(logZ_valid.shape) != (B,) or (logZ_all is not None and tuple(logZ_all.shape) != (B,)):
         raise ValueError("constrained_sample: shape mismatch")
-    st = load_library().constrained_sample(
-        ptr, dt, row_stride, _dev(mask, torch.int32, "mask"), _dev(uniforms, torch.float32, "uniforms"), B, V,
-        _dev(ids, torch.int32, "ids"), _dev(logZ_valid, torch.float32, "logZ_valid"),
-        _dev(logZ_all, torch.float32, "logZ_all"), float(temperature), _stream(stream))
-    _check(st, "constrained_sample")
+    fn = load_library().constrained_sample_noalloc if _noalloc else load_library().constrained_sample
+    st = fn(ptr, dt, row_stride, _dev(mask, torch.int32, "mask"), _dev(uniforms, torch.float32, "uniforms"), B, V,
+            _dev(ids, torch.int32, "ids"), _dev(logZ_valid, torch.float32, "logZ_valid"),
+            _dev(logZ_all, torch.float32, "logZ_all"), float(temperature), _stream(stream))
+    _check(st, "constrained_sample_noalloc" if _noalloc else "constrained_sample")
+
+
+def constrained_sample_noalloc(logits: torch.Tensor, mask: torch.Tensor, uniforms: torch.Tensor, ids: torch.Tensor,
+                               logZ_valid: torch.Tensor, logZ_all: Optional[torch.Tensor] = None, stream=None,
+                               temperature: float = 1.0) -> None:
+    """constrained_sample through the entry point that allocates nothing (at most PPV_NOALLOC_MAX_ROWS rows)."""
+    constrained_sample(logits, mask, uniforms, ids, logZ_valid, logZ_all, stream, temperature, _noalloc=True)
 
 
 def ppv_decode_begin(index: PPVIndex, prefixes: torch.Tensor, lens: torch.Tensor, state: torch.Tensor,

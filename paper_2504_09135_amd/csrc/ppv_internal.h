@@ -61,7 +61,7 @@ struct IndexView {
 // as a single workgroup would: the statistics do not depend on who computed them, so results are bit for bit
 // those of an unsplit row.  The counter is returned to zero by the workgroup that finishes the row.
 constexpr int PPV_MAX_TILES = 256;          // PPV_MAX_VOCAB / 1024 (fp32 tiles are 1024 tokens)
-constexpr int PPV_SPLIT_MAX_ROWS = 512;     // larger batches fill the chip with one workgroup per row
+constexpr int PPV_SPLIT_MAX_ROWS = PPV_NOALLOC_MAX_ROWS;   // larger batches fill the chip with one workgroup per row
 constexpr int PPV_SPLIT_MAX_PARTS = 16;
 struct SplitRow {
     float4 tile[PPV_MAX_TILES];             // (reference, sum over all tokens, sum over valid tokens, its reference)

@@ -15,6 +15,7 @@
 // Nothing here is a dense contraction, so no MFMA; the bound is HBM bandwidth, with the exp
 // (quarter-rate v_exp_f32) as the main ALU cost.
 #include <cmath>
+#include <mutex>
 #include <type_traits>
 
 #include "ppv_device.h"
@@ -1232,8 +1233,7 @@ bool long_turns(int V, ppv_dtype dt, int nw) {   // nw: wavefronts per row over 
 // V = 128,256: B = 32: 13.0 / 10.0 (list rows), 17.8 / 11.2 (image rows); B = 128: 13.6 / 14.0, 18.7 / 16.1 (two
 // parts: not split); V = 32,000, B = 64: 7.4 / 9.1 (not split).  PPV_TUNE_ROW_SPLIT forces a number of parts.
 // The scratch area the parts meet in comes with the stream; without one (see ppv_split_scratch) rows are not split.
-int parts_for(int V, ppv_dtype dt, int B, hipStream_t hs, SplitScratch **scratch) {
-    *scratch = nullptr;
+int parts_wanted(int V, ppv_dtype dt, int B) {
     const int tile = (dt == PPV_F32) ? TileGeom<float>::TILE : TileGeom<uint16_t>::TILE;
     const int nt = (V + tile - 1) / tile;
     if (B > PPV_SPLIT_MAX_ROWS) return 1;
@@ -1245,6 +1245,11 @@ int parts_for(int V, ppv_dtype dt, int B, hipStream_t hs, SplitScratch **scratch
         if (row_kb * (1.0 - 1.0 / parts) < 160.0) parts = 1;
     }
     while (parts > 1 && ((parts & (parts - 1)) != 0 || parts * 2 > nt)) parts--;   // a power of two, two tiles each
+    return parts;
+}
+int parts_for(int V, ppv_dtype dt, int B, hipStream_t hs, SplitScratch **scratch) {
+    *scratch = nullptr;
+    int parts = parts_wanted(V, dt, B);
     if (parts > 1) {
         *scratch = ppv_split_scratch(hs);
         if (!*scratch) parts = 1;
@@ -1309,9 +1314,34 @@ extern "C" ppv_status ppv_next_token_mask(const ppv_index_t *ix, const int32_t *
     return PPV_OK;
 }
 
-extern "C" ppv_status constrained_sample(const void *logits, ppv_dtype dt, int64_t row_stride, const uint32_t *mask,
-                                         const float *uniforms, int32_t B, int32_t V, int32_t *ids,
-                                         float *logZ_valid, float *logZ_all, float temperature, void *stream) {
+// The scratch area of constrained_sample_noalloc: the same SplitScratch that other calls allocate per stream, here
+// a fixed array in device memory (every GPU the library runs on holds its own copy until the process ends).  Host
+// code never uses the array's name as an address: its address on the current device is looked up once per device.
+static __device__ __align__(256) unsigned char scratch[sizeof(SplitScratch)];
+
+namespace {
+constexpr int MAX_DEVICES = 64;
+std::mutex g_fixed_mu;
+SplitScratch *g_fixed_scratch[MAX_DEVICES];   // per device: the address of `scratch` there
+
+ppv_status fixed_scratch(SplitScratch **out) {
+    int dev = -1;
+    PPV_HIP_TRY(hipGetDevice(&dev));
+    if (dev < 0 || dev >= MAX_DEVICES) return PPV_ERANGE;
+    std::lock_guard<std::mutex> lock(g_fixed_mu);
+    if (!g_fixed_scratch[dev]) {
+        void *ptr = nullptr;
+        PPV_HIP_TRY(hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)));
+        if (!ptr) return PPV_EDEVICE;
+        g_fixed_scratch[dev] = (SplitScratch *)ptr;
+    }
+    *out = g_fixed_scratch[dev];
+    return PPV_OK;
+}
+
+ppv_status sample_call(const void *logits, ppv_dtype dt, int64_t row_stride, const uint32_t *mask, const float *uniforms,
+                       int32_t B, int32_t V, int32_t *ids, float *logZ_valid, float *logZ_all, float temperature,
+                       void *stream, bool no_alloc) {
     Temper tp;
     if (B < 0 || !temper_for(temperature, &tp)) return PPV_EINVAL;
     if (B == 0) return PPV_OK;
@@ -1324,7 +1354,15 @@ extern "C" ppv_status constrained_sample(const void *logits, ppv_dtype dt, int64
     const bool small = (V + tile - 1) / tile <= SMALL_TILES && list_max <= SMALL_LIST;   // then threads <= SMALL_TILES * WAVE
     hipStream_t hs = (hipStream_t)stream;
     SplitScratch *scratch = nullptr;
-    const int parts = (small || V <= tile) ? 1 : parts_for(V, dt, B, hs, &scratch);
+    int parts = 1;
+    if (no_alloc) {   // the fixed array: no allocation, a stated largest batch
+        if (B > PPV_NOALLOC_MAX_ROWS) return PPV_ERANGE;
+        st = fixed_scratch(&scratch);
+        if (st != PPV_OK) return st;
+        if (!small && V > tile) parts = parts_wanted(V, dt, B);
+    } else if (!small && V > tile) {
+        parts = parts_for(V, dt, B, hs, &scratch);
+    }
     const int threads = waves_for(V, dt, B, parts) * WAVE;
     const bool pipe = long_turns(V, dt, parts * threads / WAVE);
     const dim3 grid((unsigned)B * (unsigned)parts), block(threads);
@@ -1347,6 +1385,20 @@ extern "C" ppv_status constrained_sample(const void *logits, ppv_dtype dt, int64
                                 n_words, list_max, ids, logZ_valid, logZ_all, tp, shift_of(parts), scratch);
     PPV_HIP_TRY(hipGetLastError());
     return PPV_OK;
+}
+}  // namespace
+
+extern "C" ppv_status constrained_sample(const void *logits, ppv_dtype dt, int64_t row_stride, const uint32_t *mask,
+                                         const float *uniforms, int32_t B, int32_t V, int32_t *ids,
+                                         float *logZ_valid, float *logZ_all, float temperature, void *stream) {
+    return sample_call(logits, dt, row_stride, mask, uniforms, B, V, ids, logZ_valid, logZ_all, temperature, stream, false);
+}
+
+extern "C" ppv_status constrained_sample_noalloc(const void *logits, ppv_dtype dt, int64_t row_stride,
+                                                 const uint32_t *mask, const float *uniforms, int32_t B, int32_t V,
+                                                 int32_t *ids, float *logZ_valid, float *logZ_all, float temperature,
+                                                 void *stream) {
+    return sample_call(logits, dt, row_stride, mask, uniforms, B, V, ids, logZ_valid, logZ_all, temperature, stream, true);
 }
 
 extern "C" ppv_status ppv_decode_begin(const ppv_index_t *ix, const int32_t *prefixes, int32_t prefix_stride,

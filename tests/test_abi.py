@@ -14,7 +14,7 @@ HEADER = os.path.join(ROOT, "include", "ppv.h")
 def declared_functions():
     src = open(HEADER).read()
     src = re.sub(r"/\*.*?\*/", "", src, flags=re.S)
-    return sorted(set(re.findall(r"\b(ppv_\w+|constrained_sample)\s*\(", src)) - {"ppv_index"})
+    return sorted(set(re.findall(r"\b(ppv_\w+|constrained_sample\w*)\s*\(", src)) - {"ppv_index"})
 
 
 @pytest.fixture(scope="module")
@@ -61,6 +61,11 @@ def test_argument_errors_without_device(lib):
     assert lib.constrained_sample(None, 0, 8, None, None, 0, 8, None, None, None, 1.0, None) == 0
     for bad_t in (0.0, -1.0, float("inf"), float("nan")):       # the temperature is checked before anything is launched
         assert lib.constrained_sample(None, 0, 8, None, None, 0, 8, None, None, None, bad_t, None) == EINVAL
+    # the entry point that allocates nothing: same checks, and a largest batch
+    assert lib.constrained_sample_noalloc(None, 0, 8, None, None, 1, 8, None, None, None, 1.0, None) == EINVAL
+    assert lib.constrained_sample_noalloc(None, 0, 8, None, None, 0, 8, None, None, None, 1.0, None) == 0
+    never = C.c_void_p(16)   # never dereferenced: the size check comes first
+    assert lib.constrained_sample_noalloc(never, 0, 8, never, never, 513, 8, never, never, None, 1.0, None) == ERANGE
     assert lib.ppv_decode_step(None, None, 0, None, None, None, None, 0, 0, None, 0, None, None, None, 1.0, None) == EINVAL
     assert lib.ppv_decode_begin(None, None, 0, None, 0, None, None, None, None) == EINVAL
     assert lib.ppv_disc_select(None, 2, 1, 5, None, None, 0, None, None, None, None) == EINVAL
