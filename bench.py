@@ -437,27 +437,60 @@ def single_call_bench(args, cfg, torch, ppv, W, dev):
 
     timed = region if args.no_graph else graph_region
     launch = "launched eagerly" if args.no_graph else f"{args.steps} steps captured in one HIP graph and replayed"
-    elapsed, _ = timed(step, args.steps)
+
+    def fused(k):
+        ppv.ppv_sample_next(index, P, Ln, bufs[k % n_buf], un, ids1, lz1)
+    ids1, lz1 = torch.zeros_like(ids), torch.zeros_like(lz)
+    fused(0)
+    torch.cuda.synchronize()
+    elapsed2, _ = timed(step, args.steps)                                # mask call + sample call
     _, t_mask = timed(lambda k: ppv.ppv_next_token_mask(index, P, Ln, mask, lo, hi, mem), args.steps)
     _, t_samp = timed(lambda k: ppv.constrained_sample(bufs[k % n_buf], mask, un, ids, lz), args.steps)
+    elapsed1, t_fused = timed(fused, args.steps)                         # one call, the mask never written
     step(0)
+    fused(0)
     torch.cuda.synchronize()
     n_valid = int((ids >= 0).sum().item())
-    bytes_sample = B * (V * e + V / 8.0 + 12.0)                          # logits once, mask once, u / id / logZ
-    achieved = bytes_sample / (t_samp / args.steps) / 1e9
+    same = int((ids == ids1).sum().item())
+    # algorithmic bytes: two calls = logits once, mask written and read, scalars; one call = logits once, the
+    # children entries (or the heavy prefix's image), scalars
+    children = np.unpackbits(mask.cpu().numpy().view(np.uint8), axis=1).sum(axis=1).astype(np.float64)
+    bytes_sample = B * (V * e + V / 8.0 + 12.0)
+    bytes_two = B * (V * e + 2.0 * V / 8.0 + 96.0)
+    bytes_fused = float(sum(algorithmic_bytes_per_prefix_step(V, e, c) for c in children))
+    two = {"prefixes_per_s": round(B * args.steps / elapsed2, 1), "us_per_step": round(elapsed2 / args.steps * 1e6, 2),
+           "GBs": round(bytes_two / (elapsed2 / args.steps) / 1e9, 1),
+           "frac_of_peak": round(bytes_two / (elapsed2 / args.steps) / 1e9 / HBM_PEAK_GBS, 4),
+           "mask_us": round(t_mask / args.steps * 1e6, 2), "sample_us": round(t_samp / args.steps * 1e6, 2),
+           "sample_GBs": round(bytes_sample / (t_samp / args.steps) / 1e9, 1),
+           "mask_GBs_written": round(B * V / 8.0 / (t_mask / args.steps) / 1e9, 1)}
+    one = {"prefixes_per_s": round(B * args.steps / elapsed1, 1), "us_per_step": round(elapsed1 / args.steps * 1e6, 2),
+           "GBs": round(bytes_fused / (t_fused / args.steps) / 1e9, 1),
+           "frac_of_peak": round(bytes_fused / (t_fused / args.steps) / 1e9 / HBM_PEAK_GBS, 4),
+           "ids_equal_to_two_calls": f"{same}/{B}"}
+    use_fused = elapsed1 <= elapsed2
+    elapsed = elapsed1 if use_fused else elapsed2
+    one_tile = V <= (1024 if cfg.dtype == "f32" else 2048)
+    if use_fused:
+        kernel = f"sample_next_one_tile_kernel<{cfg.dtype}>" if one_tile else f"decode_kernel<{cfg.dtype}> (ppv_sample_next)"
+        k_bytes, k_time = bytes_fused, t_fused
+    else:
+        kernel, k_bytes, k_time = f"sample_kernel<{cfg.dtype}>", bytes_sample, t_samp
+    achieved = k_bytes / (k_time / args.steps) / 1e9
     out = {
         "metric": f"constrained decode steps (prefixes)/sec on config {cfg.name}", "value": round(B * args.steps / elapsed, 1),
         "unit": "prefixes/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(elapsed / args.steps * 1e3, 4), "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": f"{cfg.dtype} logits, f32/f64 accumulate, u32 index", "data": "synthetic",
-        "config": {"workload": f"{cfg.name}: |S|={index.n_distinct} V={V} B={B} ({n_valid} rows with a valid token); "
-                               "one ppv_next_token_mask + one constrained_sample per step, " + launch},
-        "roofline": {"bound": "hbm", "kernel": f"sample_kernel<{cfg.dtype}>", "achieved": round(achieved, 1),
+        "config": {"workload": f"{cfg.name}: |S|={index.n_distinct} V={V} B={B} ({n_valid} rows with a valid token); " +
+                               ("one ppv_sample_next call per step (valid set and sample fused, no mask written), "
+                                if use_fused else "one ppv_next_token_mask + one constrained_sample per step, ") + launch},
+        "roofline": {"bound": "hbm", "kernel": kernel, "achieved": round(achieved, 1),
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
-                     "avg_launch_us": round(t_samp / args.steps * 1e6, 2), "bytes_per_launch": int(bytes_sample),
+                     "traffic_source": "not measured for this shape",
+                     "avg_launch_us": round(k_time / args.steps * 1e6, 2), "bytes_per_launch": int(k_bytes),
                      "device_copy_GBs": measured_copy_bandwidth(torch, dev)},
-        "mask_kernel": {"avg_launch_us": round(t_mask / args.steps * 1e6, 2),
-                        "GBs_written": round(B * V / 8.0 / (t_mask / args.steps) / 1e9, 1)},
+        "pipelines": {"one_call": one, "two_calls": two},
         "index_build_s": round(t_build, 3), "index_device_MB": round(index.device_bytes / 1e6, 1),
     }
     if not args.no_sweep:
@@ -475,7 +508,7 @@ def single_call_bench(args, cfg, torch, ppv, W, dev):
             ref = trie.step(pb.prefixes[:rows], pb.lens[:rows], lf[:rows], unh[:rows], want_mask=True, threads=threads)
             reps += 1
             dt = time.perf_counter() - t0
-        same = int((ref.ids == ids[:rows].cpu().numpy()).sum())
+        same = int((ref.ids == (ids1 if use_fused else ids)[:rows].cpu().numpy()).sum())
         t0 = time.perf_counter()
         trie.step(pb.prefixes[:rows], pb.lens[:rows], lf[:rows], unh[:rows], want_mask=True, threads=1)
         dt1 = time.perf_counter() - t0

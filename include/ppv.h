@@ -226,6 +226,27 @@ ppv_status ppv_decode_step(const ppv_index_t *index, int32_t *prefixes, int32_t 
                            float temperature, void *stream);
 
 /*
+ * ppv_sample_next -- ppv_next_token_mask and constrained_sample in one call, for callers that want the token and
+ * the valid mass but not the mask itself: the three steps of the loop body of Algorithm 1's SampleCandidate that
+ * do not change the candidate (valid set by PPV with M = |V|, draw, valid mass).  The valid set is read off the
+ * index inside the kernel and never written to memory: per row this saves the V/8 bytes of mask written and read
+ * back, and one launch.  Nothing of the caller's rows is changed.
+ * Arguments (all device pointers):
+ *   prefixes, prefix_stride, lens   as in ppv_next_token_mask (read only)
+ *   logits, dt, row_stride, uniforms, temperature   as in constrained_sample; V is the index's vocabulary
+ *   ids         int32[B]: the drawn token; -1 when the prefix has no valid next token of positive probability
+ *               (it is a prefix of no member, a member without extensions, or all its valid tokens are at -inf)
+ *   logZ_valid  float[B] or NULL: log of the valid mass (-inf with ids[b] = -1)
+ * Results equal ppv_next_token_mask followed by constrained_sample up to the rounding of sums taken in another
+ * order (both are within the stated tolerance of the exact value).
+ * Errors: PPV_EINVAL (null index/prefixes/lens/uniforms/ids, B < 0, prefix_stride < 0, bad logits arguments or
+ * temperature), PPV_ERANGE, PPV_EDEVICE.
+ */
+ppv_status ppv_sample_next(const ppv_index_t *index, const int32_t *prefixes, int32_t prefix_stride,
+                           const int32_t *lens, int32_t B, const void *logits, ppv_dtype dt, int64_t row_stride,
+                           const float *uniforms, int32_t *ids, float *logZ_valid, float temperature, void *stream);
+
+/*
  * ppv_decode_loop -- the whole while loop of Algorithm 1's SampleCandidate in one launch: n_steps
  * iterations of ppv_decode_step, each workgroup staying with its row (cursor in registers, the next
  * step's logits requested while the current step is sampled).  For callers that hold the logits of

@@ -26,7 +26,8 @@ PPV_STATE_WORDS = 4
 SYMBOLS = ("ppv_status_string", "ppv_build_index", "ppv_index_info", "ppv_index_export", "ppv_free_index",
            "ppv_index_save", "ppv_index_load",
            "ppv_next_token_mask", "constrained_sample", "ppv_decode_begin", "ppv_decode_step", "ppv_decode_loop", "ppv_topm_mask",
-           "ppv_disc_select", "ppv_tuning_set", "ppv_tuning_get", "constrained_sample_noalloc")
+           "ppv_disc_select", "ppv_tuning_set", "ppv_tuning_get", "constrained_sample_noalloc",
+           "ppv_sample_next")
 PPV_NOALLOC_MAX_ROWS = 512
 
 # tuning / test switches (ppv_tuning_set)
@@ -72,6 +73,8 @@ def load_library() -> C.CDLL:
     lib.constrained_sample.argtypes = [p, C.c_int, i64, p, p, i32, i32, p, p, p, C.c_float, p]
     lib.constrained_sample_noalloc.restype = C.c_int
     lib.constrained_sample_noalloc.argtypes = lib.constrained_sample.argtypes
+    lib.ppv_sample_next.restype = C.c_int
+    lib.ppv_sample_next.argtypes = [p, p, i32, p, i32, p, C.c_int, i64, p, p, p, C.c_float, p]
     lib.ppv_decode_begin.restype = C.c_int
     lib.ppv_decode_begin.argtypes = [p, p, i32, p, i32, p, p, p, p]
     lib.ppv_decode_step.restype = C.c_int
@@ -353,3 +356,21 @@ def ppv_tuning_get(knob: int) -> int:
     v = C.c_int32()
     _check(load_library().ppv_tuning_get(int(knob), C.byref(v)), "ppv_tuning_get")
     return v.value
+
+
+def ppv_sample_next(index: PPVIndex, prefixes: torch.Tensor, lens: torch.Tensor, logits: torch.Tensor,
+                    uniforms: torch.Tensor, ids: torch.Tensor, logZ_valid: Optional[torch.Tensor] = None, stream=None,
+                    temperature: float = 1.0) -> None:
+    """Mask + sample fused, nothing of the caller's rows changed: prefixes int32 [B, stride], lens int32 [B],
+    logits [B, V] f32/bf16, uniforms f32 [B] -> ids int32 [B], logZ_valid f32 [B] (optional)."""
+    ptr, dt, row_stride = _logits_args(logits)
+    B, stride = (int(prefixes.shape[0]), int(prefixes.shape[1])) if prefixes.dim() == 2 else (0, 0)
+    if prefixes.dim() != 2 or tuple(lens.shape) != (B,) or tuple(logits.shape) != (B, index.vocab) \
+            or tuple(uniforms.shape) != (B,) or tuple(ids.shape) != (B,) \
+            or (logZ_valid is not None and tuple(logZ_valid.shape) != (B,)):
+        raise ValueError("ppv_sample_next: shape mismatch")
+    st = load_library().ppv_sample_next(
+        index.handle, _dev(prefixes, torch.int32, "prefixes"), stride, _dev(lens, torch.int32, "lens"), B, ptr, dt,
+        row_stride, _dev(uniforms, torch.float32, "uniforms"), _dev(ids, torch.int32, "ids"),
+        _dev(logZ_valid, torch.float32, "logZ_valid"), float(temperature), _stream(stream))
+    _check(st, "ppv_sample_next")

@@ -549,7 +549,8 @@ __device__ inline void stream_tiles(const T *__restrict__ row, int V, const RawT
 //   ALL          every thread gets the result (one more barrier); otherwise only wavefront 0 does
 //   sp           the row's split over workgroups: `first` is then tile sp.part * nw + wave, and only the
 //                workgroup that arrives last goes on to sample (the others return with mine == false)
-template <typename T, bool PIPE, typename SH, bool ALL>
+//   SPLIT        compiled in only for kernels that may share a row between workgroups (the others pay nothing for it)
+template <typename T, bool PIPE, typename SH, bool ALL, bool SPLIT>
 __device__ inline RowOut row_sample(const T *__restrict__ row, int V, const RawTile &first, int mode, int n_list,
                                     const uint32_t *__restrict__ image, float u, SH &sh, int tid, int nw,
                                     const Temper &tp, const Split &sp, const T *__restrict__ next_row = nullptr,
@@ -558,8 +559,9 @@ __device__ inline RowOut row_sample(const T *__restrict__ row, int V, const RawT
     const int lane = tid & (WAVE - 1), wave = tid / WAVE;
     const int nt = (V + G::TILE - 1) / G::TILE;
     // the wavefront's number and count over all workgroups of the row: tiles and list slices are dealt out by these
-    const int vwave = sp.part * nw + wave, vnw = sp.parts * nw;
-    SplitRow *pub = sp.parts > 1 ? sp.row : nullptr;
+    const int parts = SPLIT ? sp.parts : 1;
+    const int vwave = SPLIT ? sp.part * nw + wave : wave, vnw = parts * nw;
+    SplitRow *pub = SPLIT && parts > 1 ? sp.row : nullptr;
 
     // ---- list path, part 1: ask for the listed tokens' logits now (they are being streamed
     // anyway, so these are cache hits) so that they arrive while the tiles are reduced
@@ -626,7 +628,7 @@ __device__ inline RowOut row_sample(const T *__restrict__ row, int V, const RawT
     none.logZ_valid = -INFINITY;
     none.logZ_all = 0.f;
     none.mine = false;
-    if (sp.parts > 1) {
+    if (SPLIT && parts > 1) {
         // Every wavefront waits until its device-scope stores have been taken by the memory system, then the
         // workgroup's arrival is counted.  The workgroup that finds all the others already there finishes the
         // row (its reads are device-scope too, and issued after the count has come back); nobody waits for anybody.
@@ -635,7 +637,7 @@ __device__ inline RowOut row_sample(const T *__restrict__ row, int V, const RawT
         __syncthreads();
         if (tid == 0) {
             const uint32_t before = __hip_atomic_fetch_add(sp.arrivals, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            const bool last = before + 1u == (uint32_t)sp.parts;
+            const bool last = before + 1u == (uint32_t)parts;
             if (last) __hip_atomic_store(sp.arrivals, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // the next launch starts from zero
             sh.bc_i[0] = last ? 1 : 0;
         }
@@ -842,7 +844,7 @@ __device__ inline RowOut row_sample(const T *__restrict__ row, int V, const RawT
 // ------------------------------------------------------------------------------------------
 // constrained_sample: the valid set arrives as a packed mask.  Count its bits; a small set is
 // unpacked into the token list, a large one is used as an image.
-template <typename T, bool SMALL, bool PIPE>
+template <typename T, bool SMALL, bool PIPE, bool SPLIT>
 __global__ __launch_bounds__(SMALL ? SMALL_TILES * WAVE : MAX_WAVES * WAVE) void sample_kernel(const T *__restrict__ logits, int64_t row_stride,
                                                                   const uint32_t *__restrict__ mask,
                                                                   const float *__restrict__ uniforms, int V,
@@ -854,78 +856,87 @@ __global__ __launch_bounds__(SMALL ? SMALL_TILES * WAVE : MAX_WAVES * WAVE) void
     using G = TileGeom<T>;
     using SH = typename std::conditional<SMALL, RowSharedSmall, RowShared>::type;
     __shared__ SH sh;
-    // a row is shared by 1 << split_shift consecutive workgroups
-    const int b = (int)(blockIdx.x >> split_shift), tid = threadIdx.x, lane = tid & (WAVE - 1), wave = tid / WAVE;
+    // SPLIT: a row is shared by 1 << split_shift consecutive workgroups
+    const int b = SPLIT ? (int)(blockIdx.x >> split_shift) : (int)blockIdx.x;
+    const int tid = threadIdx.x, lane = tid & (WAVE - 1), wave = tid / WAVE;
     const int nw = blockDim.x / WAVE;
     Split sp;
-    sp.parts = 1 << split_shift;
-    sp.part = (int)(blockIdx.x & (unsigned)(sp.parts - 1));
-    sp.row = split_shift ? &scratch->row[b] : nullptr;
-    sp.arrivals = split_shift ? &scratch->arrivals[b] : nullptr;
+    sp.parts = SPLIT ? 1 << split_shift : 1;
+    sp.part = SPLIT ? (int)(blockIdx.x & (unsigned)(sp.parts - 1)) : 0;
+    sp.row = SPLIT ? &scratch->row[b] : nullptr;
+    sp.arrivals = SPLIT ? &scratch->arrivals[b] : nullptr;
     const int vwave = sp.part * nw + wave;
     const T *row = logits + (size_t)b * (size_t)row_stride;
     const uint32_t *mrow = mask + (size_t)b * (size_t)n_words;
     const int nt = (V + G::TILE - 1) / G::TILE;
-    // The mask words of the wave's first MASK_BATCH tiles are requested together, and before the logits tile: memory
-    // answers a wavefront in the order of its requests, so the few bytes the next steps wait for must not queue
-    // behind the 4 KB tile; and one request after the other (a loop of load, count, load, ...) costs a memory round
-    // trip per tile, which at 63 tiles on 4 wavefronts was most of the kernel.  (Tiles past the row read as 0.)
-    constexpr int MASK_BATCH = 8;
-    uint32_t mw0[MASK_BATCH];
+    // The mask row is read as quads of four words per lane: one wavefront load covers 256 words (8,192 tokens), so a
+    // wavefront has few loads to wait for, and those it has are requested two at a time and before the logits tile
+    // (memory answers a wavefront in the order of its requests: the few bytes the next steps wait for must not queue
+    // behind the 4 KB tile; one word per lane and tile at a time cost a memory round trip per tile, which at 63
+    // tiles on 4 wavefronts was most of the kernel).  Words past the row read as 0.
+    const int n_groups = ((n_words + 3) / 4 + WAVE - 1) / WAVE;   // <= 32 (PPV_MAX_VOCAB / 8192)
+    struct Quad {
+        uint32_t w[4];
+    };
+    auto load_quad = [&](int g) {
+        Quad q;
+        const int wi = (g * WAVE + lane) * 4;
+        if (wi + 4 < n_words) {   // inside the row and not its last word: four loads off one address
+            const uint32_t *p = mrow + wi;
 #pragma unroll
-    for (int j = 0; j < MASK_BATCH; j++) mw0[j] = tile_mask_word<T>(mrow, wave + j * nw, lane, V);
+            for (int j = 0; j < 4; j++) q.w[j] = p[j];
+        } else {                  // the row's end: clamped loads, bits past V cleared, 0 beyond
+#pragma unroll
+            for (int j = 0; j < 4; j++) q.w[j] = image_word(mrow, wi + j, V);
+        }
+        return q;
+    };
+    auto bits_of = [](const Quad &q) { return (int)(__popc(q.w[0]) + __popc(q.w[1]) + __popc(q.w[2]) + __popc(q.w[3])); };
+    const Quad q0 = load_quad(wave), q1 = load_quad(wave + nw);   // (a group past the row: all zero)
     RawTile first;
     if (vwave < nt) load_tile<T>(row, V, vwave, lane, first);   // in flight during the mask work
 
-    // bits per tile (a tile's mask words are consecutive: one word per lane)
-#pragma unroll
-    for (int j = 0; j < MASK_BATCH; j++) {
-        const int k = wave + j * nw;
-        const int c = wave_sum((int)__popc(mw0[j]));
-        if (lane == 0 && k < nt) sh.tile_cnt[k] = c;
-    }
-    for (int k0 = wave + MASK_BATCH * nw; k0 < nt; k0 += MASK_BATCH * nw) {   // long rows on few wavefronts
-        uint32_t mw[MASK_BATCH];
-#pragma unroll
-        for (int j = 0; j < MASK_BATCH; j++) mw[j] = tile_mask_word<T>(mrow, k0 + j * nw, lane, V);
-#pragma unroll
-        for (int j = 0; j < MASK_BATCH; j++) {
-            const int k = k0 + j * nw;
-            const int c = wave_sum((int)__popc(mw[j]));
-            if (lane == 0 && k < nt) sh.tile_cnt[k] = c;
+    // valid tokens per group of 64 quads (kept in the tile_cnt array: there are fewer groups than tiles)
+    const int incl0 = wave_incl_scan(bits_of(q0));
+    {
+        const int incl1 = wave_incl_scan(bits_of(q1));
+        if (lane == WAVE - 1) {
+            if (wave < n_groups) sh.tile_cnt[wave] = incl0;
+            if (wave + nw < n_groups) sh.tile_cnt[wave + nw] = incl1;
         }
+    }
+    for (int g = wave + 2 * nw; g < n_groups; g += nw) {   // long rows on few wavefronts
+        const int c = wave_sum(bits_of(load_quad(g)));
+        if (lane == 0) sh.tile_cnt[g] = c;
     }
     __syncthreads();
-    int total = 0;
-    for (int k = lane; k < nt; k += WAVE) total += sh.tile_cnt[k];
-    total = wave_sum(total);
+    const int total = wave_sum(lane < n_groups ? sh.tile_cnt[lane] : 0);
     const int mode = total == 0 ? VALID_NONE : (total <= list_max ? VALID_LIST : VALID_IMAGE);
     if (mode == VALID_LIST) {
-        auto unpack_tile = [&](int k, uint32_t w) {   // tile k's valid tokens go to their places in the list
-            if (sh.tile_cnt[k] == 0) return;          // (uniform) most tiles of a short list hold none
-            int base = 0;  // valid tokens in the tiles before k
-            for (int q = lane; q < k; q += WAVE) base += sh.tile_cnt[q];
-            base = wave_sum(base);
-            const int wi = k * G::WORDS + lane;
-            int at = base + wave_incl_scan((int)__popc(w)) - (int)__popc(w);
-            while (w) {
-                const int bit = __ffs((int)w) - 1;
-                sh.list_tok[at++] = (uint32_t)(wi * 32 + bit);
-                w &= w - 1u;
+        // a group's valid tokens go to their places in the list: after those of the groups before it, in lane order
+        auto unpack_group = [&](int g, const Quad &q, int incl) {
+            const int before = wave_sum(lane < g ? sh.tile_cnt[lane] : 0);
+            int at = before + incl - bits_of(q);
+            const int wi = (g * WAVE + lane) * 4;
+#pragma unroll
+            for (int j = 0; j < 4; j++) {
+                uint32_t w = q.w[j];
+                while (w) {
+                    const int bit = __ffs((int)w) - 1;
+                    sh.list_tok[at++] = (uint32_t)((wi + j) * 32 + bit);
+                    w &= w - 1u;
+                }
             }
         };
-#pragma unroll
-        for (int j = 0; j < MASK_BATCH; j++) {
-            const int k = wave + j * nw;
-            if (k < nt) unpack_tile(k, mw0[j]);
-        }
-        for (int k = wave + MASK_BATCH * nw; k < nt; k += nw) {
-            if (sh.tile_cnt[k] == 0) continue;
-            unpack_tile(k, tile_mask_word<T>(mrow, k, lane, V));
+        if (wave < n_groups && sh.tile_cnt[wave] != 0) unpack_group(wave, q0, incl0);
+        for (int g = wave + nw; g < n_groups; g += nw) {
+            if (sh.tile_cnt[g] == 0) continue;   // (uniform) most groups of a short list hold nothing
+            const Quad q = g == wave + nw ? q1 : load_quad(g);
+            unpack_group(g, q, wave_incl_scan(bits_of(q)));
         }
         __syncthreads();
     }
-    RowOut r = row_sample<T, PIPE, SH, false>(row, V, first, mode, mode == VALID_LIST ? total : 0, mrow, uniforms[b], sh, tid, nw, tp, sp);
+    RowOut r = row_sample<T, PIPE, SH, false, SPLIT>(row, V, first, mode, mode == VALID_LIST ? total : 0, mrow, uniforms[b], sh, tid, nw, tp, sp);
     if (r.mine && tid == 0) {
         ids[b] = r.id;
         logZ_valid[b] = r.logZ_valid;
@@ -974,6 +985,58 @@ __global__ __launch_bounds__(ONE_TILE_ROWS *WAVE) void sample_one_tile_kernel(co
     }
 }
 
+// ppv_sample_next for rows of a single tile: the prefix walk of mask_rows_kernel and the arithmetic of
+// sample_one_tile_kernel in one wavefront per row; the valid set never exists outside this wavefront's registers
+// (lane l holds word l of it, which is also word l of the tile's mask).
+template <typename T>
+__global__ __launch_bounds__(ONE_TILE_ROWS *WAVE) void sample_next_one_tile_kernel(
+    IndexView ix, const int32_t *__restrict__ prefixes, int32_t stride, const int32_t *__restrict__ lens,
+    const T *__restrict__ logits, int64_t row_stride, const float *__restrict__ uniforms, int B, int32_t *__restrict__ ids,
+    float *__restrict__ logZ_valid, uint8_t *__restrict__ member, Temper tp) {
+    const int lane = threadIdx.x & (WAVE - 1);
+    const int b = blockIdx.x * ONE_TILE_ROWS + threadIdx.x / WAVE;
+    if (b >= B) return;   // uniform per wavefront
+    const int V = ix.vocab, n_words = ix.n_words;
+    const int32_t mine = first_tokens(prefixes + (size_t)b * (size_t)stride, stride, lane);   // before the tile: answers come in order
+    int t = lens[b];
+    const float u = uniforms[b];
+    RawTile rt;
+    load_tile<T>(logits + (size_t)b * (size_t)row_stride, V, 0, lane, rt);   // in flight during the walk
+    t = t < 0 ? 0 : (t > stride ? stride : t);
+    const Walk w = walk_prefix(ix, prefixes + (size_t)b * (size_t)stride, mine, t, lane);
+    uint32_t word = 0u;
+    const uint32_t nchild = w.found ? w.ce - w.cb : 0u;
+    if (nchild > ix.heavy_min) {   // ready-made image
+        if (lane < n_words) word = ix.heavy_bits[(size_t)heavy_slot_of(ix, w.node) * (size_t)n_words + lane];
+    } else if (nchild > 0u) {      // nchild <= heavy_min <= 64: one child per lane
+        const uint32_t tok = (uint32_t)lane < nchild ? (ix.ent[w.cb + (uint32_t)lane].tok & PPV_NODE_TOKEN) : 0u;
+        for (uint32_t i = 0; i < nchild; i++) {   // uniform trip count
+            const uint32_t v = (uint32_t)__builtin_amdgcn_readlane((int)tok, (int)i);
+            if ((uint32_t)lane == (v >> 5)) word |= 1u << (v & 31u);
+        }
+    }
+    float m, zall, zval;
+    tile_stats<T, true>(rt, word, lane, tp, m, zall, zval);
+    const float l2za = fast_log2(zall);
+    int id = -1;
+    float lzv = -INFINITY, ref = m;
+    if (__ballot(word != 0u)) {
+        if (zval < 3.814697265625e-06f) {   // below 2^-18 of the largest term: sum again, relative to the valid maximum
+            ref = tile_valid_max<T>(rt, word, lane);
+            zval = ref != -INFINITY ? tile_valid_sum<T>(rt, word, lane, ref, tp.c) : 0.f;
+        }
+        if (zval > 0.f) {
+            lzv = fmaf(ref - m, tp.inv, LN2F * (fast_log2(zval) - l2za));
+            id = locate_in_tile<T>(rt, word, 0, lane, ref, (double)u * (double)zval, tp.c);
+        }
+    }
+    if (lane == 0) {
+        ids[b] = id;
+        if (logZ_valid) logZ_valid[b] = lzv;
+        if (member) member[b] = w.member ? 1 : 0;
+    }
+}
+
 // ------------------------------------------------------------------------------------------
 // ppv_decode_begin: one wavefront per row walks the row's current prefix and leaves the cursor.
 __global__ __launch_bounds__(MASK_THREADS) void decode_begin_kernel(IndexView ix, const int32_t *__restrict__ prefixes,
@@ -1006,25 +1069,30 @@ __global__ __launch_bounds__(MASK_THREADS) void decode_begin_kernel(IndexView ix
 // the cursor lives in registers and the next step's first tiles are requested before the current
 // step is sampled (only when no child of the current prefix is a member, i.e. the row is certain to
 // go on, so nothing is fetched in vain).
-template <typename T, bool LOOP, bool PIPE>
+template <typename T, bool LOOP, bool PIPE, bool SPLIT>
 __global__ __launch_bounds__(LOOP ? LOOP_WAVES * WAVE : MAX_WAVES * WAVE) void decode_kernel(
     IndexView ix, int32_t *__restrict__ prefixes, int32_t stride, int32_t *__restrict__ lens,
     uint8_t *__restrict__ active, RowState *__restrict__ state, const T *__restrict__ logits, int64_t row_stride,
     int64_t step_stride, const float *__restrict__ uniforms, int n_steps, int B, int32_t *__restrict__ ids,
-    float *__restrict__ logZ_valid, float *__restrict__ logx, Temper tp, int split_shift, SplitScratch *scratch) {
+    float *__restrict__ logZ_valid, float *__restrict__ logx, Temper tp, int split_shift, SplitScratch *scratch,
+    int advance) {
+    // advance == 0 (ppv_sample_next): every row takes part, a token is drawn, and nothing of the caller's rows is
+    // changed (no append, no cursor, no flags)
     using G = TileGeom<T>;
     __shared__ RowShared sh;
-    // a row is shared by 1 << split_shift consecutive workgroups (never in the loop kernel)
-    const int b = (int)(blockIdx.x >> split_shift), tid = threadIdx.x, lane = tid & (WAVE - 1), wave = tid / WAVE;
+    // SPLIT: a row is shared by 1 << split_shift consecutive workgroups (never in the loop kernel)
+    static_assert(!(LOOP && SPLIT), "the loop kernel keeps a row in one workgroup");
+    const int b = SPLIT ? (int)(blockIdx.x >> split_shift) : (int)blockIdx.x;
+    const int tid = threadIdx.x, lane = tid & (WAVE - 1), wave = tid / WAVE;
     const int nw = blockDim.x / WAVE;
     Split sp;
-    sp.parts = LOOP ? 1 : 1 << split_shift;
-    sp.part = (int)(blockIdx.x & (unsigned)(sp.parts - 1));
-    sp.row = sp.parts > 1 ? &scratch->row[b] : nullptr;
-    sp.arrivals = sp.parts > 1 ? &scratch->arrivals[b] : nullptr;
+    sp.parts = SPLIT ? 1 << split_shift : 1;
+    sp.part = SPLIT ? (int)(blockIdx.x & (unsigned)(sp.parts - 1)) : 0;
+    sp.row = SPLIT ? &scratch->row[b] : nullptr;
+    sp.arrivals = SPLIT ? &scratch->arrivals[b] : nullptr;
     const int vwave = sp.part * nw + wave;
     // the independent per-row loads go out together
-    const uint8_t on = active[b];
+    const uint8_t on = active ? active[b] : (uint8_t)1;
     int t = lens[b];
     RowState st;
     if (state) st = state[b];
@@ -1095,10 +1163,10 @@ __global__ __launch_bounds__(LOOP ? LOOP_WAVES * WAVE : MAX_WAVES * WAVE) void d
         const T *next_row = more ? row + step_stride : nullptr;
         float next_u = 0.f;
         if (more) next_u = uniforms[(size_t)(s + 1) * (size_t)B + b];
-        RowOut r = row_sample<T, PIPE, RowShared, LOOP>(row, V, first, mode, mode == VALID_LIST ? nchild : 0, image, u, sh, tid, nw,
+        RowOut r = row_sample<T, PIPE, RowShared, LOOP, SPLIT>(row, V, first, mode, mode == VALID_LIST ? nchild : 0, image, u, sh, tid, nw,
                                                   tp, sp, next_row, &next_first);
         if (r.mine && tid == 0) {
-            const bool room = t < stride;
+            const bool room = t < stride || !advance;
             int32_t id = -1;
             done = true;  // no valid token or no room: the row cannot continue
             RowState nx = st;
@@ -1122,7 +1190,7 @@ __global__ __launch_bounds__(LOOP ? LOOP_WAVES * WAVE : MAX_WAVES * WAVE) void d
                 }
                 nx.slot = (tokw & PPV_NODE_HEAVY) ? heavy_slot_of(ix, nx.node) : PPV_NO_SLOT;
                 done = (tokw & PPV_NODE_TERMINAL) != 0u;   // the extended row is itself a member
-                prefixes[(size_t)b * (size_t)stride + t] = id;
+                if (advance) prefixes[(size_t)b * (size_t)stride + t] = id;
                 lx += r.logZ_valid;
             } else {
                 lx = -INFINITY;   // the row stops outside S: its importance score is multiplied by a valid mass of 0
@@ -1136,7 +1204,7 @@ __global__ __launch_bounds__(LOOP ? LOOP_WAVES * WAVE : MAX_WAVES * WAVE) void d
                 sh.bc_i[5] = (int)nx.cb;
                 sh.bc_i[6] = (int)nx.ce;
                 sh.bc_i[7] = (int)nx.slot;
-            } else {
+            } else if (advance) {
                 if (id >= 0) {
                     lens[b] = t + 1;
                     if (state) state[b] = nx;
@@ -1266,14 +1334,17 @@ template <typename T>
 void launch_sample(bool small, bool pipe, dim3 grid, dim3 block, hipStream_t hs, const T *lg, int64_t row_stride,
                    const uint32_t *mask, const float *uniforms, int V, int n_words, int list_max, int32_t *ids,
                    float *logZ_valid, float *logZ_all, Temper tp, int split_shift, SplitScratch *scratch) {
-    if (small)
-        hipLaunchKernelGGL((sample_kernel<T, true, false>), grid, block, 0, hs, lg, row_stride, mask, uniforms, V, n_words,
+    if (split_shift)   // (a split row's turns are short; the kernel without the three-tile pipeline serves all of them)
+        hipLaunchKernelGGL((sample_kernel<T, false, false, true>), grid, block, 0, hs, lg, row_stride, mask, uniforms, V,
+                           n_words, list_max, ids, logZ_valid, logZ_all, tp, split_shift, scratch);
+    else if (small)
+        hipLaunchKernelGGL((sample_kernel<T, true, false, false>), grid, block, 0, hs, lg, row_stride, mask, uniforms, V, n_words,
                            list_max, ids, logZ_valid, logZ_all, tp, split_shift, scratch);
     else if (pipe)
-        hipLaunchKernelGGL((sample_kernel<T, false, true>), grid, block, 0, hs, lg, row_stride, mask, uniforms, V, n_words,
+        hipLaunchKernelGGL((sample_kernel<T, false, true, false>), grid, block, 0, hs, lg, row_stride, mask, uniforms, V, n_words,
                            list_max, ids, logZ_valid, logZ_all, tp, split_shift, scratch);
     else
-        hipLaunchKernelGGL((sample_kernel<T, false, false>), grid, block, 0, hs, lg, row_stride, mask, uniforms, V,
+        hipLaunchKernelGGL((sample_kernel<T, false, false, false>), grid, block, 0, hs, lg, row_stride, mask, uniforms, V,
                            n_words, list_max, ids, logZ_valid, logZ_all, tp, split_shift, scratch);
 }
 
@@ -1281,14 +1352,16 @@ template <typename T>
 void launch_decode_kernel(bool loop, bool pipe, dim3 grid, dim3 block, hipStream_t hs, const IndexView &view,
                           int32_t *prefixes, int32_t stride, int32_t *lens, uint8_t *active, RowState *rs, const T *lg,
                           int64_t row_stride, int64_t step_stride, const float *uniforms, int n_steps, int B, int32_t *ids,
-                          float *logZ_valid, float *logx, Temper tp, int split_shift, SplitScratch *scratch) {
-#define PPV_LAUNCH_DECODE(LOOP, PIPE)                                                                                 \
-    hipLaunchKernelGGL((decode_kernel<T, LOOP, PIPE>), grid, block, 0, hs, view, prefixes, stride, lens, active, rs, lg, \
-                       row_stride, step_stride, uniforms, n_steps, B, ids, logZ_valid, logx, tp, split_shift, scratch)
-    if (loop && pipe) PPV_LAUNCH_DECODE(true, true);
-    else if (loop) PPV_LAUNCH_DECODE(true, false);
-    else if (pipe) PPV_LAUNCH_DECODE(false, true);
-    else PPV_LAUNCH_DECODE(false, false);
+                          float *logZ_valid, float *logx, Temper tp, int split_shift, SplitScratch *scratch, int advance) {
+#define PPV_LAUNCH_DECODE(LOOP, PIPE, SPLIT)                                                                          \
+    hipLaunchKernelGGL((decode_kernel<T, LOOP, PIPE, SPLIT>), grid, block, 0, hs, view, prefixes, stride, lens, active, \
+                       rs, lg, row_stride, step_stride, uniforms, n_steps, B, ids, logZ_valid, logx, tp, split_shift,  \
+                       scratch, advance)
+    if (split_shift && !loop) PPV_LAUNCH_DECODE(false, false, true);   // (a split row's turns are short)
+    else if (loop && pipe) PPV_LAUNCH_DECODE(true, true, false);
+    else if (loop) PPV_LAUNCH_DECODE(true, false, false);
+    else if (pipe) PPV_LAUNCH_DECODE(false, true, false);
+    else PPV_LAUNCH_DECODE(false, false, false);
 #undef PPV_LAUNCH_DECODE
 }
 
@@ -1419,11 +1492,11 @@ namespace {
 ppv_status launch_decode(const ppv_index_t *ix, int32_t *prefixes, int32_t prefix_stride, int32_t *lens, uint8_t *active,
                          uint32_t *state, const void *logits, ppv_dtype dt, int64_t row_stride, int64_t step_stride,
                          const float *uniforms, int32_t n_steps, int32_t B, int32_t *ids, float *logZ_valid, float *logx,
-                         float temperature, void *stream, bool loop) {
+                         float temperature, void *stream, bool loop, bool advance = true) {
     Temper tp;
     if (!ix || B < 0 || prefix_stride < 0 || n_steps < 0 || !temper_for(temperature, &tp)) return PPV_EINVAL;
     if (B == 0 || n_steps == 0) return PPV_OK;
-    if (!prefixes || !lens || !active || !uniforms) return PPV_EINVAL;
+    if (!prefixes || !lens || (advance && !active) || !uniforms) return PPV_EINVAL;
     ppv_status st = check_logits_args(logits, dt, row_stride, ix->view.vocab);
     if (st != PPV_OK) return st;
     if (loop && n_steps > 1) {
@@ -1442,11 +1515,11 @@ ppv_status launch_decode(const ppv_index_t *ix, int32_t *prefixes, int32_t prefi
     if (dt == PPV_F32)
         launch_decode_kernel<float>(loop, pipe, grid, block, hs, ix->view, prefixes, prefix_stride, lens, active, rs,
                                     (const float *)logits, row_stride, step_stride, uniforms, n_steps, B, ids, logZ_valid,
-                                    logx, tp, shift_of(parts), scratch);
+                                    logx, tp, shift_of(parts), scratch, advance ? 1 : 0);
     else
         launch_decode_kernel<uint16_t>(loop, pipe, grid, block, hs, ix->view, prefixes, prefix_stride, lens, active, rs,
                                        (const uint16_t *)logits, row_stride, step_stride, uniforms, n_steps, B, ids,
-                                       logZ_valid, logx, tp, shift_of(parts), scratch);
+                                       logZ_valid, logx, tp, shift_of(parts), scratch, advance ? 1 : 0);
     PPV_HIP_TRY(hipGetLastError());
     return PPV_OK;
 }
@@ -1467,4 +1540,35 @@ extern "C" ppv_status ppv_decode_loop(const ppv_index_t *ix, int32_t *prefixes, 
                                       void *stream) {
     return launch_decode(ix, prefixes, prefix_stride, lens, active, state, logits, dt, row_stride, step_stride, uniforms,
                          n_steps, B, ids, logZ_valid, logx, temperature, stream, true);
+}
+
+extern "C" ppv_status ppv_sample_next(const ppv_index_t *ix, const int32_t *prefixes, int32_t prefix_stride,
+                                      const int32_t *lens, int32_t B, const void *logits, ppv_dtype dt,
+                                      int64_t row_stride, const float *uniforms, int32_t *ids, float *logZ_valid,
+                                      float temperature, void *stream) {
+    Temper tp;
+    if (!ix || B < 0 || prefix_stride < 0 || !temper_for(temperature, &tp)) return PPV_EINVAL;
+    if (B == 0) return PPV_OK;
+    if (!prefixes || !lens || !uniforms || !ids) return PPV_EINVAL;
+    const int V = ix->view.vocab;
+    const ppv_status st = check_logits_args(logits, dt, row_stride, V);
+    if (st != PPV_OK) return st;
+    const int tile = (dt == PPV_F32) ? TileGeom<float>::TILE : TileGeom<uint16_t>::TILE;
+    if (V <= tile && ix->view.n_words <= MASK_SMALL_WORDS) {   // the whole row is one tile: one wavefront per row
+        const dim3 g1((unsigned)((B + ONE_TILE_ROWS - 1) / ONE_TILE_ROWS)), b1(ONE_TILE_ROWS * WAVE);
+        if (dt == PPV_F32)
+            hipLaunchKernelGGL(sample_next_one_tile_kernel<float>, g1, b1, 0, (hipStream_t)stream, ix->view, prefixes,
+                               prefix_stride, lens, (const float *)logits, row_stride, uniforms, B, ids, logZ_valid,
+                               (uint8_t *)nullptr, tp);
+        else
+            hipLaunchKernelGGL(sample_next_one_tile_kernel<uint16_t>, g1, b1, 0, (hipStream_t)stream, ix->view, prefixes,
+                               prefix_stride, lens, (const uint16_t *)logits, row_stride, uniforms, B, ids, logZ_valid,
+                               (uint8_t *)nullptr, tp);
+        PPV_HIP_TRY(hipGetLastError());
+        return PPV_OK;
+    }
+    // longer rows: the fused decode step without a cursor, told to change nothing of the caller's rows
+    return launch_decode(ix, const_cast<int32_t *>(prefixes), prefix_stride, const_cast<int32_t *>(lens), nullptr, nullptr,
+                         logits, dt, row_stride, 0, uniforms, 1, B, ids, logZ_valid, nullptr, temperature, stream, false,
+                         false);
 }

@@ -66,6 +66,9 @@ def test_argument_errors_without_device(lib):
     assert lib.constrained_sample_noalloc(None, 0, 8, None, None, 0, 8, None, None, None, 1.0, None) == 0
     never = C.c_void_p(16)   # never dereferenced: the size check comes first
     assert lib.constrained_sample_noalloc(never, 0, 8, never, never, 513, 8, never, never, None, 1.0, None) == ERANGE
+    assert lib.ppv_sample_next(None, None, 0, None, 0, None, 0, 8, None, None, None, 1.0, None) == EINVAL
+    assert lib.ppv_sample_next(never, None, 0, None, 0, None, 0, 8, None, None, None, 1.0, None) == 0      # B = 0
+    assert lib.ppv_sample_next(never, None, 0, None, 1, None, 0, 8, None, None, None, 1.0, None) == EINVAL
     assert lib.ppv_decode_step(None, None, 0, None, None, None, None, 0, 0, None, 0, None, None, None, 1.0, None) == EINVAL
     assert lib.ppv_decode_begin(None, None, 0, None, 0, None, None, None, None) == EINVAL
     assert lib.ppv_disc_select(None, 2, 1, 5, None, None, 0, None, None, None, None) == EINVAL

@@ -177,5 +177,13 @@ def test_full_size_mask_and_sample(name):
     ids, lzv, lza = gpu_sample(cfg, logits_to_dev(cfg, logits), dmask, un)
     ex = check_sample_rows(cfg.dtype, ref, lambda b: ref_q.mask[b], un, ids, lzv, lza)
     say(f"{name}: done, {ex} rows inside the CDF band")
+    say(f"{name}: the same in one call, no mask written (ppv_sample_next)")
+    B = cfg.batch
+    ids1 = torch.full((B,), -7, dtype=torch.int32, device=DEV)
+    lzv1 = torch.full((B,), 3.0, dtype=torch.float32, device=DEV)
+    ppv.ppv_sample_next(index, to_dev(pb.prefixes), to_dev(pb.lens), logits_to_dev(cfg, logits), to_dev(un), ids1, lzv1)
+    torch.cuda.synchronize()
+    ex1 = check_sample_rows(cfg.dtype, ref, lambda b: ref_q.mask[b], un, ids1.cpu().numpy(), lzv1.cpu().numpy(), None)
+    say(f"{name}: done, {ex1} rows inside the CDF band")
     n_valid = int((ref.ids >= 0).sum())
     assert n_valid >= cfg.batch * cfg.valid_frac * 0.9

@@ -384,6 +384,32 @@ def test_empty_batch_and_null_outputs():
     assert np.array_equal(unpack_mask(mask.cpu().numpy().view(np.uint32), cfg.vocab), ref.mask)
 
 
+@pytest.mark.parametrize("name", list(CASES))
+@pytest.mark.parametrize("temperature", [1.0, 0.7])
+def test_sample_next_is_mask_plus_sample_without_the_mask(name, temperature):
+    """ppv_sample_next (valid set read off the index inside the kernel, never written) against the oracle's step on
+    every workload, invalid prefixes included; the caller's rows are left as they were."""
+    cfg, S, trie, index = setup_case(name)
+    pb = W.make_prefix_batch(cfg, S, index=3)
+    B = pb.prefixes.shape[0]
+    logits = W.make_logits(cfg, step=7)
+    un = W.make_uniforms(cfg, step=7)
+    ref = trie.step(pb.prefixes, pb.lens, W.logits_as_f32(cfg, logits), un, threads=8, temperature=temperature)
+    dP, dL = to_dev(pb.prefixes), to_dev(pb.lens)
+    ids = torch.full((B,), -7, dtype=torch.int32, device=DEV)
+    lzv = torch.full((B,), 3.0, dtype=torch.float32, device=DEV)
+    ppv.ppv_sample_next(index, dP, dL, logits_to_dev(cfg, logits), to_dev(un), ids, lzv, temperature=temperature)
+    torch.cuda.synchronize()
+    check_sample_rows(cfg.dtype, ref, lambda b: ref.mask[b], un, ids.cpu().numpy(), lzv.cpu().numpy(), None)
+    assert np.array_equal(dP.cpu().numpy(), pb.prefixes) and np.array_equal(dL.cpu().numpy(), pb.lens)
+    assert (ref.ids >= 0).any()
+    # the mass is optional
+    ids2 = torch.full((B,), -7, dtype=torch.int32, device=DEV)
+    ppv.ppv_sample_next(index, dP, dL, logits_to_dev(cfg, logits), to_dev(un), ids2, temperature=temperature)
+    torch.cuda.synchronize()
+    assert torch.equal(ids, ids2)
+
+
 def test_sample_edge_cases():
     """Hand-made masks: empty row, single token, all tokens, valid tokens far below the maximum,
     -inf logits, u = 0 and u -> 1, V not a multiple of 32, padded row stride."""
