@@ -190,7 +190,7 @@ ppv_status constrained_sample_noalloc(const void *logits, ppv_dtype dt, int64_t 
  *   logx      float[B] or NULL: set to 0 (log of the importance score x = 1)
  * Errors: PPV_EINVAL (null index/prefixes/lens/state/active, B < 0, prefix_stride < 0), PPV_EDEVICE.
  */
-#define PPV_STATE_WORDS 4
+#define PPV_STATE_WORDS 8
 ppv_status ppv_decode_begin(const ppv_index_t *index, const int32_t *prefixes, int32_t prefix_stride,
                             const int32_t *lens, int32_t B, uint32_t *state, uint8_t *active, float *logx,
                             void *stream);

@@ -21,7 +21,7 @@ PPV_F32, PPV_BF16 = 0, 1
 PPV_MAX_VOCAB = 262144
 PPV_TOPM_MAX = 1024
 
-PPV_STATE_WORDS = 4
+PPV_STATE_WORDS = 8
 
 SYMBOLS = ("ppv_status_string", "ppv_build_index", "ppv_index_info", "ppv_index_export", "ppv_free_index",
            "ppv_index_save", "ppv_index_load",

@@ -15,6 +15,9 @@ HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
     # packed fp32 instructions stay off for every kernel of this library
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+    # no multiply-add fusing beyond the fmaf calls in the sources: several kernels promise each other's results bit
+    # for bit, which must not hinge on where the compiler happens to find a multiply next to an add
+    "-ffp-contract=off",
     "-Wall", "-Wno-unused-command-line-argument", "-Wno-unknown-warning-option",
 ]
 

@@ -76,11 +76,19 @@ struct SplitScratch {
 // cannot be had (the stream is being captured and has none yet, or out of memory): the row is then not split.
 SplitScratch *ppv_split_scratch(hipStream_t stream);
 
-// Per-row decoding cursor kept between decode steps (PPV_STATE_WORDS x uint32).
+// Per-row decoding cursor kept between decode steps (PPV_STATE_WORDS x uint32).  The second half looks one level
+// ahead: the entry of the node's first child and the child offset of the entry after it.  For a node with exactly
+// one child -- nearly every node below the first few levels of a set of long sequences -- that is the whole valid
+// set and the child's own children range, so a decode step on such a node needs no load from the index before it
+// can ask for the listed token's logit.  `flags` says whether that half is filled in; it is a cache, never required.
 struct RowState {
     uint32_t node;   // entry of the row's current prefix; PPV_NO_SLOT: not a prefix of any member
     uint32_t cb, ce; // its children
     uint32_t slot;   // heavy slot or PPV_NO_SLOT
+    uint32_t tok0;   // ent[cb].tok   (token | flags of the first child)      -- when flags == 1
+    uint32_t child0; // ent[cb].child (where the first child's children begin)
+    uint32_t child1; // ent[cb + 1].child (where they end, if the node has one child)
+    uint32_t flags;  // 1: tok0 / child0 / child1 are filled in; anything else: they are not
 };
 static_assert(sizeof(RowState) == PPV_STATE_WORDS * sizeof(uint32_t), "state layout");
 

@@ -540,6 +540,94 @@ __device__ inline void stream_tiles(const T *__restrict__ row, int V, const RawT
     }
 }
 
+// Row totals from the per-tile statistics in LDS: the largest tile reference M, the sum over all tokens relative
+// to it and (image rows) the sum over valid tokens.  Called by a whole wavefront; results are uniform.
+template <typename SH>
+__device__ inline void combine_tiles(const SH &sh, int nt, int lane, const Temper &tp, bool image, float &M, double &za,
+                                     double &zv) {
+    M = -INFINITY;
+    for (int k = lane; k < nt; k += WAVE) M = fmaxf(M, sh.tile_m[k]);
+    M = wave_max(M);
+    za = 0.0;
+    zv = 0.0;
+    for (int k = lane; k < nt; k += WAVE) {
+        const float m = sh.tile_m[k];
+        if (m != -INFINITY) {
+            const double sc = (double)exp_scale(m - M, tp.c);
+            za += (double)sh.tile_zall[k] * sc;
+            if (image) zv += (double)sh.tile_zval[k] * sc;   // (the other modes have no per-tile valid sums)
+        }
+    }
+    za = wave_sum(za);
+    if (image) zv = wave_sum(zv);
+}
+
+// A list of at most 63 valid tokens that one wavefront holds in registers, entry i in lane i (the per-step decode
+// kernel): the sums over the list and the sample, with the arithmetic of the list path of row_sample for a list of
+// one slice, so that both give the same bits.  gx: lane i < n_list holds the listed token's logit, the others -inf.
+struct RegList {
+    bool on;         // (uniform) the row's valid set is held this way
+    bool have_gx;    // (uniform) the listed logits have been requested already and are in gx
+    uint32_t tokw;   // lane i < n_list: the entry's token word (token | flags)
+    float gx;
+};
+struct ListPick {
+    int id, pos;     // sampled token and its position in the list; -1: nothing can be sampled
+    float Mv;        // largest listed logit (-inf: no listed token has positive weight)
+    double zvl;      // sum of the listed tokens' weights relative to Mv
+};
+__device__ inline ListPick reg_list_pick(float gx, uint32_t tokw, int n_list, float u, int lane, const Temper &tp) {
+    ListPick pk;
+    pk.id = -1;
+    pk.pos = -1;
+    pk.zvl = 0.0;
+    if (n_list == 1) {
+        // One listed token: what the general case below computes, without its reductions and scans over the lanes
+        // (every other lane contributes an exact zero): the weight exp(x - x), through the same rounded steps, is
+        // the sum; the token is drawn whatever u is, unless its weight is 0.
+        const float g = __int_as_float(__builtin_amdgcn_readfirstlane(__float_as_int(gx)));
+        const float m = g == g ? g : -INFINITY;   // (a NaN is passed over, as the maximum over the lanes does)
+        pk.Mv = m;
+        if (m == -INFINITY) return pk;
+        const float mc = m * tp.c;
+        const float e = fast_exp2(fmaf(m, tp.c, -mc)) * fast_exp2(-fmaf(m, tp.c, -mc));
+        pk.zvl = (double)e;
+        if (e > 0.f) {
+            pk.pos = 0;
+            pk.id = (int)((uint32_t)__builtin_amdgcn_readfirstlane((int)tokw) & PPV_NODE_TOKEN);
+        }
+        return pk;
+    }
+    const float m = wave_max(gx);
+    pk.Mv = m;
+    if (m == -INFINITY) return pk;
+    const float mc = m * tp.c;
+    const float fix = fast_exp2(-fmaf(m, tp.c, -mc));
+    float e = fast_exp2(fmaf(gx, tp.c, -mc)) * fix;   // gx = -inf gives 0
+    const double zvl = (double)wave_sum(e);
+    pk.zvl = zvl;
+    const double tau = (double)u * zvl;
+    double target;
+    int s;
+    if (zvl > tau) {
+        s = 0;
+        target = tau;
+    } else {
+        s = zvl > 0.0 ? 0 : -1;
+        target = INFINITY;
+    }
+    if (!(s >= 0 && lane < n_list)) e = 0.f;
+    const double ic = wave_incl_scan((double)e);
+    const uint64_t c2 = __ballot(e > 0.f && ic > target);
+    const uint64_t h2 = __ballot(e > 0.f);
+    if (c2 | h2) {
+        const int l = c2 ? __ffsll((long long)c2) - 1 : 63 - __clzll((long long)h2);
+        pk.pos = l;
+        pk.id = (int)(lane_value(tokw, l) & PPV_NODE_TOKEN);
+    }
+    return pk;
+}
+
 // Streams the row and samples.  Called by every thread of the workgroup with uniform arguments.
 //   first        this wave's first tile, already loaded (the wave owns tiles wave, wave+nw, ...)
 //   next_row     optional: another row whose first tile (per wave) is to be requested into *next_first
@@ -665,20 +753,9 @@ __device__ inline RowOut row_sample(const T *__restrict__ row, int V, const RawT
     // image (whose rare second pass needs every wavefront): the others leave its SIMD to it.
     if (!ALL && mode != VALID_IMAGE && wave != 0) return none;
     // ---- combine (every wave computes the same row totals from LDS; cheap, and saves a broadcast)
-    float M = -INFINITY;
-    for (int k = lane; k < nt; k += WAVE) M = fmaxf(M, sh.tile_m[k]);
-    M = wave_max(M);
-    double za = 0.0, zv = 0.0;
-    for (int k = lane; k < nt; k += WAVE) {
-        const float m = sh.tile_m[k];
-        if (m != -INFINITY) {
-            const double sc = (double)exp_scale(m - M, tp.c);
-            za += (double)sh.tile_zall[k] * sc;
-            if (mode == VALID_IMAGE) zv += (double)sh.tile_zval[k] * sc;   // (the other modes have no per-tile valid sums)
-        }
-    }
-    za = wave_sum(za);
-    if (mode == VALID_IMAGE) zv = wave_sum(zv);
+    float M;
+    double za, zv;
+    combine_tiles(sh, nt, lane, tp, mode == VALID_IMAGE, M, za, zv);
     float R = M;  // reference of the valid sums of the image path
 
     // ---- image path, rare case: the valid mass is below 2^-18 of the row's largest term, so sums
@@ -1057,6 +1134,7 @@ __global__ __launch_bounds__(MASK_THREADS) void decode_begin_kernel(IndexView ix
         st.cb = w.found ? w.cb : 0u;
         st.ce = w.found ? w.ce : 0u;
         st.slot = (w.found && w.ce - w.cb > ix.heavy_min) ? heavy_slot_of(ix, w.node) : PPV_NO_SLOT;
+        st.tok0 = st.child0 = st.child1 = st.flags = 0u;   // nothing looked ahead
         state[b] = st;
         active[b] = (w.found && !w.member) ? 1 : 0;
         if (logx) logx[b] = 0.f;
@@ -1069,7 +1147,7 @@ __global__ __launch_bounds__(MASK_THREADS) void decode_begin_kernel(IndexView ix
 // the cursor lives in registers and the next step's first tiles are requested before the current
 // step is sampled (only when no child of the current prefix is a member, i.e. the row is certain to
 // go on, so nothing is fetched in vain).
-template <typename T, bool LOOP, bool PIPE, bool SPLIT>
+template <typename T, bool LOOP, bool PIPE, bool SPLIT, bool REG>
 __global__ __launch_bounds__(LOOP ? LOOP_WAVES * WAVE : MAX_WAVES * WAVE) void decode_kernel(
     IndexView ix, int32_t *__restrict__ prefixes, int32_t stride, int32_t *__restrict__ lens,
     uint8_t *__restrict__ active, RowState *__restrict__ state, const T *__restrict__ logits, int64_t row_stride,
@@ -1091,11 +1169,16 @@ __global__ __launch_bounds__(LOOP ? LOOP_WAVES * WAVE : MAX_WAVES * WAVE) void d
     sp.row = SPLIT ? &scratch->row[b] : nullptr;
     sp.arrivals = SPLIT ? &scratch->arrivals[b] : nullptr;
     const int vwave = sp.part * nw + wave;
+    // REG: the per-step kernel of small batches keeps a list of at most 63 children in wavefront 0's registers and
+    // looks one level ahead for the next cursor (see RowState); the loop kernel, split rows, long rows and large
+    // batches (where the registers this costs would mean fewer rows per compute unit) use the list in LDS
+    static_assert(!REG || (!LOOP && !SPLIT && !PIPE), "the register list is for the plain per-step kernel");
     // the independent per-row loads go out together
     const uint8_t on = active ? active[b] : (uint8_t)1;
     int t = lens[b];
     RowState st;
     if (state) st = state[b];
+    else st.flags = 0u;
     float u = uniforms[b];
     // the running score is read now, not when it is updated at the very end (a load there would stand between the
     // sample and the kernel's last store); unconditional, from an address that always exists
@@ -1104,6 +1187,63 @@ __global__ __launch_bounds__(LOOP ? LOOP_WAVES * WAVE : MAX_WAVES * WAVE) void d
     const int V = ix.vocab;
     const T *row = logits + (size_t)b * (size_t)row_stride;
     const int nt = (V + G::TILE - 1) / G::TILE;
+    // The cursor comes from memory that the caller owns.  One that cannot be a cursor of this index (a state
+    // that never went through ppv_decode_begin, or of another index) must not send a load out of bounds:
+    // such a row is treated as having no valid token and retires; a look-ahead that cannot be one is ignored.
+    auto check_cursor = [&]() {
+        const uint32_t nc = st.ce - st.cb;
+        const bool sane = st.node < ix.n_nodes && st.cb <= st.ce && st.ce <= ix.n_nodes &&
+                          (st.slot == PPV_NO_SLOT ? nc <= ix.heavy_min : st.slot < ix.n_heavy);
+        if (!sane) {
+            st.cb = st.ce = 0u;
+            st.slot = PPV_NO_SLOT;
+        }
+        if (st.flags != 1u || (st.tok0 & PPV_NODE_TOKEN) >= (uint32_t)V || st.child0 > st.child1 || st.child1 > ix.n_nodes)
+            st.flags = 0u;
+    };
+    // Register list (wavefront 0): entry i of the node's children in lane i, one entry more than there are children
+    // (it closes the last child's own range), and under each child the look-ahead for the next cursor.
+    RegList rl;
+    rl.on = false;
+    rl.have_gx = false;
+    rl.tokw = 0u;
+    rl.gx = -INFINITY;
+    uint32_t rl_child = 0u;                              // lane i <= n: child offset of entry i
+    uint32_t ahead_tok = 0u, ahead_child = 0u, ahead_next = 0u;   // lane i < n: ent[child_i].tok / .child, ent[child_i + 1].child
+    auto look_ahead = [&](int n) {   // (wavefront 0) every address is clamped into the entry array
+        if (lane < n) {
+            const uint32_t a0 = rl_child < ix.n_nodes ? rl_child : ix.n_nodes;
+            const uint32_t a1 = a0 < ix.n_nodes ? a0 + 1u : ix.n_nodes;
+            const NodeEnt e0 = ix.ent[a0];
+            ahead_tok = e0.tok;
+            ahead_child = e0.child;
+            ahead_next = ix.ent[a1].child;
+        }
+    };
+    if (REG && state) {
+        // with a cursor the small loads go out before the 4 KB tile: memory answers a wavefront in request order
+        check_cursor();
+        const uint32_t nc = st.ce - st.cb;
+        rl.on = nc >= 1u && nc < (uint32_t)WAVE && st.slot == PPV_NO_SLOT;   // (uniform)
+        if (rl.on && wave == 0) {
+            if (nc == 1u && st.flags == 1u) {   // the cursor knows its only child: its logit can be asked for at once
+                rl.tokw = lane == 0 ? st.tok0 : 0u;
+                rl_child = lane == 0 ? st.child0 : st.child1;
+                rl.have_gx = true;
+                if (lane == 0) {
+                    const uint32_t v = st.tok0 & PPV_NODE_TOKEN;
+                    if (sizeof(T) == 4) rl.gx = __uint_as_float(((const uint32_t *)row)[v]);
+                    else rl.gx = __uint_as_float(((uint32_t)((const uint16_t *)row)[v]) << 16);
+                }
+                look_ahead(1);
+            } else if ((uint32_t)lane <= nc) {
+                const NodeEnt e = ix.ent[st.cb + (uint32_t)lane];
+                rl.tokw = e.tok;
+                rl_child = e.child;
+            }
+        }
+        rl.have_gx = __builtin_amdgcn_readfirstlane(rl.have_gx ? 1 : 0) != 0 && wave == 0;
+    }
     RawTile first;
     if (vwave < nt) load_tile<T>(row, V, vwave, lane, first);   // in flight during the index work
     t = t < 0 ? 0 : (t > stride ? stride : t);
@@ -1124,17 +1264,79 @@ __global__ __launch_bounds__(LOOP ? LOOP_WAVES * WAVE : MAX_WAVES * WAVE) void d
         st.slot = (st.node != PPV_NO_SLOT && st.ce - st.cb > ix.heavy_min) ? heavy_slot_of(ix, st.node) : PPV_NO_SLOT;
         __syncthreads();
     }
-    // The cursor comes from memory that the caller owns.  One that cannot be a cursor of this index (a state
-    // that never went through ppv_decode_begin, or of another index) must not send a load out of bounds:
-    // such a row is treated as having no valid token and retires.
-    {
-        const uint32_t nc = st.ce - st.cb;
-        const bool sane = st.node < ix.n_nodes && st.cb <= st.ce && st.ce <= ix.n_nodes &&
-                          (st.slot == PPV_NO_SLOT ? nc <= ix.heavy_min : st.slot < ix.n_heavy);
-        if (!sane) {
-            st.cb = st.ce = 0u;
-            st.slot = PPV_NO_SLOT;
+    if (!(REG && state)) check_cursor();
+    if (REG && rl.on) {
+        // ---- a short list in wavefront 0's registers.  The sample depends on the listed logits alone, not on the
+        // row's totals: wavefront 0 draws the token and works out the next cursor while its tile is still on its
+        // way; after the barrier only the stores, the totals and the two masses are left.  (Nothing is stored before
+        // the barrier: the other wavefronts read the row's flags and cursor when they start, and one that starts
+        // late must not find them changed.)
+        const int n = (int)(st.ce - st.cb);
+        ListPick pk;
+        pk.id = -1;
+        pk.pos = -1;
+        pk.Mv = -INFINITY;
+        pk.zvl = 0.0;
+        bool drew = false;
+        RowState nx = st;
+        uint32_t tokw = 0u;
+        if (wave == 0) {
+            if (!rl.have_gx) {   // (waits for the entries)
+                if (lane < n) {
+                    const uint32_t v = rl.tokw & PPV_NODE_TOKEN;
+                    if (sizeof(T) == 4) rl.gx = __uint_as_float(((const uint32_t *)row)[v]);
+                    else rl.gx = __uint_as_float(((uint32_t)((const uint16_t *)row)[v]) << 16);
+                }
+                look_ahead(n);
+            }
+            pk = reg_list_pick(rl.gx, rl.tokw, n, u, lane, tp);
+            const bool room = t < stride || !advance;
+            drew = pk.id >= 0 && room;
+            if (drew) {   // (uniform) the sampled child's entry, the one after it and its look-ahead, out of the lanes
+                nx.node = st.cb + (uint32_t)pk.pos;
+                tokw = lane_value(rl.tokw, pk.pos);
+                nx.cb = lane_value(rl_child, pk.pos);
+                nx.ce = lane_value(rl_child, pk.pos + 1);
+                nx.tok0 = lane_value(ahead_tok, pk.pos);
+                nx.child0 = lane_value(ahead_child, pk.pos);
+                nx.child1 = lane_value(ahead_next, pk.pos);
+                nx.flags = 1u;
+                nx.slot = (tokw & PPV_NODE_HEAVY) ? heavy_slot_of(ix, nx.node) : PPV_NO_SLOT;
+            }
         }
+        struct {
+            __device__ void operator()() const {}
+        } nothing;
+        stream_tiles<T, false, false, RowShared>(row, V, first, nullptr, sh, lane, wave, nw, tp, nothing, nullptr);
+        __syncthreads();
+        if (wave != 0) return;
+        if (lane == 0) {
+            if (ids) ids[b] = drew ? pk.id : -1;
+            if (drew) {
+                if (advance) {
+                    prefixes[(size_t)b * (size_t)stride + t] = pk.id;
+                    lens[b] = t + 1;
+                    state[b] = nx;
+                    if (tokw & PPV_NODE_TERMINAL) active[b] = 0;   // the extended row is itself a member
+                }
+            } else if (advance) {   // the row stops outside S: no valid token of positive weight, or no room
+                if (logx) logx[b] = -INFINITY;
+                active[b] = 0;
+            }
+        }
+        if (pk.Mv == -INFINITY) {   // (uniform) no listed token has positive weight
+            if (lane == 0 && logZ_valid) logZ_valid[b] = -INFINITY;
+            return;
+        }
+        float M;
+        double za, zv;
+        combine_tiles(sh, nt, lane, tp, false, M, za, zv);
+        const float lzv = fmaf(pk.Mv - M, tp.inv, LN2F * (fast_log2((float)pk.zvl) - fast_log2((float)za)));
+        if (lane == 0) {
+            if (logZ_valid) logZ_valid[b] = lzv;
+            if (advance && logx && drew) logx[b] = logx_in + lzv;
+        }
+        return;
     }
     // running log importance score (tid 0); started from the stored value so that the additions happen in
     // the same order as with one launch per step
@@ -1163,13 +1365,14 @@ __global__ __launch_bounds__(LOOP ? LOOP_WAVES * WAVE : MAX_WAVES * WAVE) void d
         const T *next_row = more ? row + step_stride : nullptr;
         float next_u = 0.f;
         if (more) next_u = uniforms[(size_t)(s + 1) * (size_t)B + b];
-        RowOut r = row_sample<T, PIPE, RowShared, LOOP, SPLIT>(row, V, first, mode, mode == VALID_LIST ? nchild : 0, image, u, sh, tid, nw,
-                                                  tp, sp, next_row, &next_first);
+        RowOut r = row_sample<T, PIPE, RowShared, LOOP, SPLIT>(row, V, first, mode, mode == VALID_LIST ? nchild : 0, image, u, sh,
+                                                  tid, nw, tp, sp, next_row, &next_first);
         if (r.mine && tid == 0) {
             const bool room = t < stride || !advance;
             int32_t id = -1;
             done = true;  // no valid token or no room: the row cannot continue
             RowState nx = st;
+            nx.flags = 0u;   // (the look-ahead belongs to the node it was made for)
             if (r.id >= 0 && room) {
                 id = r.id;
                 uint32_t tokw;
@@ -1222,6 +1425,7 @@ __global__ __launch_bounds__(LOOP ? LOOP_WAVES * WAVE : MAX_WAVES * WAVE) void d
             st.cb = (uint32_t)sh.bc_i[5];
             st.ce = (uint32_t)sh.bc_i[6];
             st.slot = (uint32_t)sh.bc_i[7];
+            st.flags = 0u;   // the loop kernel does not look ahead
         }
         __syncthreads();   // everyone has the new cursor before LDS is reused
         if (done || s + 1 == n_steps) break;
@@ -1270,11 +1474,16 @@ ppv_status check_logits_args(const void *logits, ppv_dtype dt, int64_t row_strid
 // V=256k: B=256: 3.8 with 16, 1.3 with 2; B=1024: 5.05 with 4, 5.09 with 8, 4.4 with 16.
 // `parts`: workgroups per row (see parts_for); the figures then hold for one workgroup's share of the row and for
 // the number of workgroups in the launch.
-int waves_for(int V, ppv_dtype dt, int B, int parts = 1) {
+// `cursor_step`: the per-step decode kernel with a cursor, which no longer waits for index entries behind the tiles
+// it has asked for: one tile per wavefront, the whole row in flight at once, also at 256 rows (C3, us per launch
+// with 8 / 16 wavefronts: 7.9 / 7.6 before the list moved into registers; tiles reduced 3.4 / 2.8 us after the
+// cursor is in).
+int waves_for(int V, ppv_dtype dt, int B, int parts = 1, bool cursor_step = false) {
     const int tile = (dt == PPV_F32) ? TileGeom<float>::TILE : TileGeom<uint16_t>::TILE;
     const int nt = ((V + tile - 1) / tile + parts - 1) / parts;
     B *= parts;
     int cap = B <= 128 ? 16 : (B <= 512 ? 8 : 4);
+    if (cursor_step && B <= 256) cap = 16;
     // long rows in a small batch: one row per compute unit, all of it in flight (constrained_sample, B = 256, us per
     // call with 8 / 16 wavefronts: 32 tiles: 13.2 / 12.0 (fp32 V = 32k), 15.2 / 14.2 (bf16 V = 64k); 63 tiles: 23.6 / 20.6)
     if (nt >= 32 && B <= 256) cap = 16;
@@ -1348,20 +1557,22 @@ void launch_sample(bool small, bool pipe, dim3 grid, dim3 block, hipStream_t hs,
                            n_words, list_max, ids, logZ_valid, logZ_all, tp, split_shift, scratch);
 }
 
+constexpr int REG_MAX_ROWS = 1024;   // batches up to here run the per-step kernel with the list in registers
 template <typename T>
 void launch_decode_kernel(bool loop, bool pipe, dim3 grid, dim3 block, hipStream_t hs, const IndexView &view,
                           int32_t *prefixes, int32_t stride, int32_t *lens, uint8_t *active, RowState *rs, const T *lg,
                           int64_t row_stride, int64_t step_stride, const float *uniforms, int n_steps, int B, int32_t *ids,
                           float *logZ_valid, float *logx, Temper tp, int split_shift, SplitScratch *scratch, int advance) {
-#define PPV_LAUNCH_DECODE(LOOP, PIPE, SPLIT)                                                                          \
-    hipLaunchKernelGGL((decode_kernel<T, LOOP, PIPE, SPLIT>), grid, block, 0, hs, view, prefixes, stride, lens, active, \
-                       rs, lg, row_stride, step_stride, uniforms, n_steps, B, ids, logZ_valid, logx, tp, split_shift,  \
-                       scratch, advance)
-    if (split_shift && !loop) PPV_LAUNCH_DECODE(false, false, true);   // (a split row's turns are short)
-    else if (loop && pipe) PPV_LAUNCH_DECODE(true, true, false);
-    else if (loop) PPV_LAUNCH_DECODE(true, false, false);
-    else if (pipe) PPV_LAUNCH_DECODE(false, true, false);
-    else PPV_LAUNCH_DECODE(false, false, false);
+#define PPV_LAUNCH_DECODE(LOOP, PIPE, SPLIT, REG)                                                                     \
+    hipLaunchKernelGGL((decode_kernel<T, LOOP, PIPE, SPLIT, REG>), grid, block, 0, hs, view, prefixes, stride, lens,   \
+                       active, rs, lg, row_stride, step_stride, uniforms, n_steps, B, ids, logZ_valid, logx, tp,        \
+                       split_shift, scratch, advance)
+    if (split_shift && !loop) PPV_LAUNCH_DECODE(false, false, true, false);   // (a split row's turns are short)
+    else if (loop && pipe) PPV_LAUNCH_DECODE(true, true, false, false);
+    else if (loop) PPV_LAUNCH_DECODE(true, false, false, false);
+    else if (pipe) PPV_LAUNCH_DECODE(false, true, false, false);
+    else if (rs && B <= REG_MAX_ROWS) PPV_LAUNCH_DECODE(false, false, false, true);
+    else PPV_LAUNCH_DECODE(false, false, false, false);
 #undef PPV_LAUNCH_DECODE
 }
 
@@ -1506,7 +1717,7 @@ ppv_status launch_decode(const ppv_index_t *ix, int32_t *prefixes, int32_t prefi
     hipStream_t hs = (hipStream_t)stream;
     SplitScratch *scratch = nullptr;
     const int parts = loop ? 1 : parts_for(ix->view.vocab, dt, B, hs, &scratch);
-    int nw = waves_for(ix->view.vocab, dt, B, parts);
+    int nw = waves_for(ix->view.vocab, dt, B, parts, !loop && state != nullptr);
     if (loop && nw > LOOP_WAVES) nw = LOOP_WAVES;
     const dim3 grid((unsigned)B * (unsigned)parts), block(nw * WAVE);
     RowState *rs = (RowState *)state;

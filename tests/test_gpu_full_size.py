@@ -22,7 +22,18 @@ def say(msg):
     print(f"[{time.strftime('%H:%M:%S')}] {msg}", file=sys.stderr, flush=True)
 
 
+_built = {}
+
+
 def build_both(cfg):
+    if cfg.name in _built:
+        return _built[cfg.name]
+    _built.clear()                                              # one full-size set at a time (host memory)
+    _built[cfg.name] = _build_both(cfg)
+    return _built[cfg.name]
+
+
+def _build_both(cfg):
     say(f"{cfg.name}: generating S")
     S = W.make_constraint_set(cfg)
     say(f"{cfg.name}: oracle trie over {S.n} sequences")
@@ -159,6 +170,65 @@ def test_C3_full_decode_loop_graph():
     # every finished row is a member of S
     q = trie.query(gP, gL, want_mask=False)
     assert (q.member == 1).all()
+
+
+@pytest.mark.parametrize("B", [4096, 16384])
+def test_C3_decode_loop_at_the_batch_sizes_of_the_sweep(B):
+    """bench.py's batch sweep runs the C3 decode loop on 4,096 and 16,384 rows (four wavefronts per row, several
+    rows per compute unit).  Here the same launches are checked against the oracle: at six decode steps the logits
+    come from the host generator and a few hundred active rows are compared (ids, log masses) with the oracle's step
+    on the rows' prefixes at that point; the other steps run on logits drawn on the device, as in the sweep.  At the
+    end every row must be a member of S whose tokens are all valid continuations."""
+    cfg = W.CONFIGS["C3"]
+    S, trie, index = build_both(cfg)
+    V, L = cfg.vocab, index.l_max
+    checked = (0, 1, 2, 4, 8, 14)
+    n_rows = 400 if B == 4096 else 150
+    gen = torch.Generator(device=DEV)
+    gen.manual_seed(900 + B)
+    rng = np.random.default_rng(B)
+    P = torch.full((B, L), W.PAD_TOKEN, dtype=torch.int32, device=DEV)
+    lens = torch.zeros(B, dtype=torch.int32, device=DEV)
+    act = torch.zeros(B, dtype=torch.uint8, device=DEV)
+    state = torch.zeros((B, ppv.PPV_STATE_WORDS), dtype=torch.int32, device=DEV)
+    logx = torch.zeros(B, dtype=torch.float32, device=DEV)
+    ids = torch.zeros(B, dtype=torch.int32, device=DEV)
+    lz = torch.zeros(B, dtype=torch.float32, device=DEV)
+    ppv.ppv_decode_begin(index, P, lens, state, act, logx)
+    excused = compared = 0
+    for s in range(L):
+        on = act.cpu().numpy().astype(bool)
+        if not on.any():
+            break
+        un = torch.rand(B, generator=gen, device=DEV)
+        if s in checked:
+            say(f"C3, B = {B}: step {s}, host logits")
+            rows = np.nonzero(on)[0]
+            rows = np.sort(rng.choice(rows, min(n_rows, len(rows)), replace=False))
+            host = np.zeros((B, V), np.uint16)                   # rows that are not compared keep logit 0
+            piece = W.make_logits(cfg, batch=len(rows), step=700 + s)
+            host[rows] = piece
+            lg = to_dev(host.view(np.int16)).view(torch.bfloat16)
+            before_P, before_L = P.cpu().numpy()[rows], lens.cpu().numpy()[rows]
+        else:
+            lg = (torch.randn((B, V), generator=gen, device=DEV) * cfg.sigma).to(torch.bfloat16)
+        ids.fill_(-5)
+        ppv.ppv_decode_step(index, P, lens, act, lg, un, ids, lz, logx, state=state)
+        torch.cuda.synchronize()
+        if s in checked:
+            unh = un.cpu().numpy()[rows]
+            ref = trie.step(before_P, before_L, W.logits_as_f32(cfg, piece), unh, want_mask=True, threads=16)
+            excused += check_sample_rows(cfg.dtype, ref, lambda i: ref.mask[i], unh, ids.cpu().numpy()[rows],
+                                         lz.cpu().numpy()[rows], None, rows=rows)
+            compared += len(rows)
+        del lg
+    assert not act.any().item()
+    gP, gL = P.cpu().numpy(), lens.cpu().numpy()
+    say(f"C3, B = {B}: {compared} prefix-steps compared with the oracle, {excused} inside the CDF band; membership of all rows")
+    assert excused <= 0.01 * compared and compared >= 5 * n_rows // 2
+    q = trie.query(gP, gL, want_mask=False, threads=16)
+    assert (q.member == 1).all() and (gL >= 4).all()
+    assert np.isfinite(logx.cpu().numpy()).all()
 
 
 @pytest.mark.parametrize("name", ["C4", "C5"])

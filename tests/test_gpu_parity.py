@@ -262,7 +262,7 @@ def test_decode_loop_launch_equals_single_steps(name, B, temperature):
                                     temperature=temperature)
         torch.cuda.synchronize()
         outs.append([t.cpu().numpy() for t in (P, lens, act, ids, lz.view(torch.int32), logx.view(torch.int32))]
-                    + [state.cpu().numpy()])
+                    + [state.cpu().numpy()[:, :4]])            # the cursor proper (the rest is its look-ahead cache)
     for a, b in zip(*outs):
         assert np.array_equal(a, b)
     assert not outs[0][2].any() and (outs[0][1] > 0).all()
@@ -714,10 +714,16 @@ def test_a_state_that_is_no_cursor_retires_the_row(loop):
     junk = rng.integers(0, 2 ** 32, size=(B, ppv.PPV_STATE_WORDS), dtype=np.uint64).astype(np.uint32).view(np.int32)
     rows = np.arange(0, B, 2)
     bad[rows] = junk[rows]
-    bad[2] = [5, 10, 3, -1]                      # children range that ends before it begins
-    bad[4] = [0, 0, 2_000_000_000, -1]           # a list far beyond the index
-    bad[6] = [1, 1, 2, 123456789]                # an image slot that does not exist
-    bad[8] = [-2, 0, 1, -1]                      # a node number beyond the index
+    bad[2, :4] = [5, 10, 3, -1]                  # children range that ends before it begins
+    bad[4, :4] = [0, 0, 2_000_000_000, -1]       # a list far beyond the index
+    bad[6, :4] = [1, 1, 2, 123456789]            # an image slot that does not exist
+    bad[8, :4] = [-2, 0, 1, -1]                  # a node number beyond the index
+    # good cursors whose look-ahead half claims to be filled in but cannot be one: it is ignored, the row goes on
+    bad[1, 4:] = [cfg.vocab, 0, 1, 1]            # a token outside the vocabulary
+    bad[3, 4:] = [7, 9, 3, 1]                    # a children range that ends before it begins
+    bad[5, 4:] = [7, 0, 2_000_000_000, 1]        # ... that lies beyond the index
+    bad[7, 4:] = junk[7, 4:]
+    bad[9, 4:] = [7, 0, 1, 2]                    # flags that are neither 0 nor 1
     state.copy_(to_dev(bad))
     n = 3
     logits = torch.stack([logits_to_dev(cfg, W.make_logits(cfg, batch=B, step=300 + s)) for s in range(n)])
