@@ -541,21 +541,23 @@ __device__ inline void stream_tiles(const T *__restrict__ row, int V, const RawT
 }
 
 // Row totals from the per-tile statistics in LDS: the largest tile reference M, the sum over all tokens relative
-// to it and (image rows) the sum over valid tokens.  Called by a whole wavefront; results are uniform.
+// to it and (image rows) the sum over valid tokens.  Called by a whole wavefront; results are uniform.  The sum over
+// all tokens only ever enters a logarithm, so it is added up in fp32 (a tree over at most 256 positive terms: a few
+// 1e-7 relative); the valid sum sets the sampling threshold and is added up in fp64.
 template <typename SH>
-__device__ inline void combine_tiles(const SH &sh, int nt, int lane, const Temper &tp, bool image, float &M, double &za,
+__device__ inline void combine_tiles(const SH &sh, int nt, int lane, const Temper &tp, bool image, float &M, float &za,
                                      double &zv) {
     M = -INFINITY;
     for (int k = lane; k < nt; k += WAVE) M = fmaxf(M, sh.tile_m[k]);
     M = wave_max(M);
-    za = 0.0;
+    za = 0.f;
     zv = 0.0;
     for (int k = lane; k < nt; k += WAVE) {
         const float m = sh.tile_m[k];
         if (m != -INFINITY) {
-            const double sc = (double)exp_scale(m - M, tp.c);
-            za += (double)sh.tile_zall[k] * sc;
-            if (image) zv += (double)sh.tile_zval[k] * sc;   // (the other modes have no per-tile valid sums)
+            const float sc = exp_scale(m - M, tp.c);
+            za += sh.tile_zall[k] * sc;
+            if (image) zv += (double)sh.tile_zval[k] * (double)sc;   // (the other modes have no per-tile valid sums)
         }
     }
     za = wave_sum(za);
@@ -753,8 +755,8 @@ __device__ inline RowOut row_sample(const T *__restrict__ row, int V, const RawT
     // image (whose rare second pass needs every wavefront): the others leave its SIMD to it.
     if (!ALL && mode != VALID_IMAGE && wave != 0) return none;
     // ---- combine (every wave computes the same row totals from LDS; cheap, and saves a broadcast)
-    float M;
-    double za, zv;
+    float M, za;
+    double zv;
     combine_tiles(sh, nt, lane, tp, mode == VALID_IMAGE, M, za, zv);
     float R = M;  // reference of the valid sums of the image path
 
@@ -799,7 +801,7 @@ __device__ inline RowOut row_sample(const T *__restrict__ row, int V, const RawT
     RowOut out = none;
     out.mine = ALL || wave == 0;
     if (wave == 0) {
-        const float l2za = fast_log2((float)za);
+        const float l2za = fast_log2(za);
         int id = -1, pos = -1;
         float lzv = -INFINITY;
         if (mode == VALID_IMAGE) {
@@ -1328,10 +1330,10 @@ __global__ __launch_bounds__(LOOP ? LOOP_WAVES * WAVE : MAX_WAVES * WAVE) void d
             if (lane == 0 && logZ_valid) logZ_valid[b] = -INFINITY;
             return;
         }
-        float M;
-        double za, zv;
+        float M, za;
+        double zv;
         combine_tiles(sh, nt, lane, tp, false, M, za, zv);
-        const float lzv = fmaf(pk.Mv - M, tp.inv, LN2F * (fast_log2((float)pk.zvl) - fast_log2((float)za)));
+        const float lzv = fmaf(pk.Mv - M, tp.inv, LN2F * (fast_log2((float)pk.zvl) - fast_log2(za)));
         if (lane == 0) {
             if (logZ_valid) logZ_valid[b] = lzv;
             if (advance && logx && drew) logx[b] = logx_in + lzv;
