@@ -27,6 +27,7 @@ namespace {
 constexpr int MASK_THREADS = 256;
 constexpr int MAX_WAVES = 16;                 // wavefronts per row (workgroup of up to 1024 threads)
 constexpr int LOOP_WAVES = 8;                 // the decode-loop kernel holds more in registers: at most 512 threads
+constexpr int CHAIN_WAVES = 10;               // ... or, with one wavefront that only draws tokens beside up to nine that stream, 640
 constexpr int MAX_TILES = PPV_MAX_TILES;
 constexpr float LN2F = 0.693147180559945309417f;
 static_assert(PPV_MAX_VOCAB <= MAX_TILES * 1024, "tile bookkeeping too small");
@@ -236,6 +237,30 @@ __device__ inline void load_full_tile(const T *__restrict__ row, int tile, int l
         u32x4 v = __builtin_nontemporal_load(p + j * WAVE);
         rt.r[j] = make_uint4(v.x, v.y, v.z, v.w);
     }
+}
+
+// A tile requested with four unconditional 16-byte loads wherever it lies: a group of tokens past the row's end is
+// read from the row's last whole group instead (valid memory), and pad_tile_tail, called when the tile is used, puts
+// -inf there.  Nothing is conditional between request and use, so the compiler can count the loads in flight and
+// wait for exactly the ones a use needs.  Needs V % EPL == 0 (no group straddles the row's end).
+template <typename T>
+__device__ inline void load_tile_clamped(const T *__restrict__ row, int V, int tile, int lane, RawTile &rt) {
+    using G = TileGeom<T>;
+    const int base = tile * G::TILE + lane * G::EPL;
+#pragma unroll
+    for (int j = 0; j < 4; j++) {
+        const int g = base + j * G::PER_LOAD;
+        const int gc = g < V ? g : V - G::EPL;
+        u32x4 v = __builtin_nontemporal_load((const u32x4 *)(row + gc));
+        rt.r[j] = make_uint4(v.x, v.y, v.z, v.w);
+    }
+}
+template <typename T> __device__ inline void pad_tile_tail(RawTile &rt, int V, int tile, int lane) {
+    using G = TileGeom<T>;
+    const int base = tile * G::TILE + lane * G::EPL;
+#pragma unroll
+    for (int j = 0; j < 4; j++)
+        if (base + j * G::PER_LOAD >= V) rt.r[j] = make_uint4(Elem<T>::pad(), Elem<T>::pad(), Elem<T>::pad(), Elem<T>::pad());
 }
 
 // word wi of a V-bit image, with bits at positions >= V cleared (0 beyond the image).  The load
@@ -1150,7 +1175,7 @@ __global__ __launch_bounds__(MASK_THREADS) void decode_begin_kernel(IndexView ix
 // step is sampled (only when no child of the current prefix is a member, i.e. the row is certain to
 // go on, so nothing is fetched in vain).
 template <typename T, bool LOOP, bool PIPE, bool SPLIT, bool REG>
-__global__ __launch_bounds__(LOOP ? LOOP_WAVES * WAVE : MAX_WAVES * WAVE) void decode_kernel(
+__global__ __launch_bounds__(LOOP ? (REG ? CHAIN_WAVES : LOOP_WAVES) * WAVE : MAX_WAVES * WAVE) void decode_kernel(
     IndexView ix, int32_t *__restrict__ prefixes, int32_t stride, int32_t *__restrict__ lens,
     uint8_t *__restrict__ active, RowState *__restrict__ state, const T *__restrict__ logits, int64_t row_stride,
     int64_t step_stride, const float *__restrict__ uniforms, int n_steps, int B, int32_t *__restrict__ ids,
@@ -1159,7 +1184,10 @@ __global__ __launch_bounds__(LOOP ? LOOP_WAVES * WAVE : MAX_WAVES * WAVE) void d
     // advance == 0 (ppv_sample_next): every row takes part, a token is drawn, and nothing of the caller's rows is
     // changed (no append, no cursor, no flags)
     using G = TileGeom<T>;
-    __shared__ RowShared sh;
+    constexpr bool STEP_REG = REG && !LOOP, LOOP_REG = REG && LOOP;
+    // (the loop kernel's fast steps alternate between two sets of tile statistics, see below)
+    __shared__ RowShared shs[LOOP_REG ? 2 : 1];
+    RowShared &sh = shs[0];
     // SPLIT: a row is shared by 1 << split_shift consecutive workgroups (never in the loop kernel)
     static_assert(!(LOOP && SPLIT), "the loop kernel keeps a row in one workgroup");
     const int b = SPLIT ? (int)(blockIdx.x >> split_shift) : (int)blockIdx.x;
@@ -1174,7 +1202,7 @@ __global__ __launch_bounds__(LOOP ? LOOP_WAVES * WAVE : MAX_WAVES * WAVE) void d
     // REG: the per-step kernel of small batches keeps a list of at most 63 children in wavefront 0's registers and
     // looks one level ahead for the next cursor (see RowState); the loop kernel, split rows, long rows and large
     // batches (where the registers this costs would mean fewer rows per compute unit) use the list in LDS
-    static_assert(!REG || (!LOOP && !SPLIT && !PIPE), "the register list is for the plain per-step kernel");
+    static_assert(!REG || (!SPLIT && !PIPE), "the register list is for short turns in unsplit rows");
     // the independent per-row loads go out together
     const uint8_t on = active ? active[b] : (uint8_t)1;
     int t = lens[b];
@@ -1222,7 +1250,7 @@ __global__ __launch_bounds__(LOOP ? LOOP_WAVES * WAVE : MAX_WAVES * WAVE) void d
             ahead_next = ix.ent[a1].child;
         }
     };
-    if (REG && state) {
+    if (STEP_REG && state) {
         // with a cursor the small loads go out before the 4 KB tile: memory answers a wavefront in request order
         check_cursor();
         const uint32_t nc = st.ce - st.cb;
@@ -1266,8 +1294,8 @@ __global__ __launch_bounds__(LOOP ? LOOP_WAVES * WAVE : MAX_WAVES * WAVE) void d
         st.slot = (st.node != PPV_NO_SLOT && st.ce - st.cb > ix.heavy_min) ? heavy_slot_of(ix, st.node) : PPV_NO_SLOT;
         __syncthreads();
     }
-    if (!(REG && state)) check_cursor();
-    if (REG && rl.on) {
+    if (!(STEP_REG && state)) check_cursor();
+    if (STEP_REG && rl.on) {
         // ---- a short list in wavefront 0's registers.  The sample depends on the listed logits alone, not on the
         // row's totals: wavefront 0 draws the token and works out the next cursor while its tile is still on its
         // way; after the barrier only the stores, the totals and the two masses are left.  (Nothing is stored before
@@ -1344,10 +1372,251 @@ __global__ __launch_bounds__(LOOP ? LOOP_WAVES * WAVE : MAX_WAVES * WAVE) void d
     // the same order as with one launch per step
     float lx = (LOOP && logx) ? logx_in : 0.f;
     bool done = false;
+    // LOOP_REG: hand-over from wavefront 0 to the workgroup, written before a fast step's barrier and read after it
+    __shared__ struct {
+        int done, drew;
+        RowState nx;
+    } hand[2];
     for (int s = 0; s < n_steps; s++) {
         const uint32_t cb = st.cb, ce = st.ce, slot = st.slot;
         const int nchild = (int)(ce - cb);
         const int mode = nchild == 0 ? VALID_NONE : (slot != PPV_NO_SLOT ? VALID_IMAGE : VALID_LIST);
+        if (LOOP_REG && mode == VALID_LIST && nchild == 1 && st.flags == 1u && V % G::EPL == 0 && nw >= 2 &&
+            nt <= 2 * (nw - 1) && !(st.tok0 & PPV_NODE_TERMINAL) && s + 1 < n_steps && t + 1 < stride) {
+            // ---- A chain of prefixes with one child each, the cursor knowing the child (nearly all of a long
+            // sequence below its first levels).  Wavefront 0 only draws tokens: each step it takes the listed
+            // logit that it asked for a step earlier, advances the cursor, asks for the next step's logit and
+            // look-ahead, and after the step's barrier adds up the row's totals.  The other wavefronts only stream:
+            // two tiles each, the next row's tiles requested before this row's are reduced, in two sets of registers
+            // that swap roles from step to step, so that there is no copy of, no condition on and no wait for a
+            // tile that is still on its way.  One barrier per step; statistics and hand-over alternate between two
+            // buffers as in the fast step below.  The chain ends with the row, or at a prefix that is not of this
+            // kind, which the code below takes from there.
+            const int ntw = nw - 1;
+            const int wave_s = __builtin_amdgcn_readfirstlane(wave);
+            auto next_in_chain = [&](const RowState &c) {
+                return c.ce - c.cb == 1u && c.flags == 1u && c.slot == PPV_NO_SLOT;
+            };
+            auto row_goes_on = [&]() { return !(st.tok0 & PPV_NODE_TERMINAL) && s + 1 < n_steps && t + 1 < stride; };
+            bool finished = false;   // the row is done, or out of steps
+            if (wave_s == 0) {
+                float gx = -INFINITY;
+                uint32_t a_tok = 0u, a_child = 0u, a_next = 0u;
+                auto ask = [&](const T *r, const RowState &c, float &g, uint32_t &x0, uint32_t &x1, uint32_t &x2) {
+                    if (lane == 0) {
+                        const uint32_t v = c.tok0 & PPV_NODE_TOKEN;
+                        if (sizeof(T) == 4) g = __uint_as_float(((const uint32_t *)r)[v]);
+                        else g = __uint_as_float(((uint32_t)((const uint16_t *)r)[v]) << 16);
+                        const uint32_t a0 = c.child0 < ix.n_nodes ? c.child0 : ix.n_nodes;
+                        const uint32_t a1 = a0 < ix.n_nodes ? a0 + 1u : ix.n_nodes;
+                        const NodeEnt g0 = ix.ent[a0];
+                        x0 = g0.tok;
+                        x1 = g0.child;
+                        x2 = ix.ent[a1].child;
+                    }
+                };
+                ask(row, st, gx, a_tok, a_child, a_next);
+                for (;;) {
+                    const bool more = row_goes_on();
+                    const ListPick pk = reg_list_pick(gx, lane == 0 ? st.tok0 : 0u, 1, u, lane, tp);
+                    const bool drew = pk.id >= 0 && t < stride;
+                    RowState nx = st;
+                    nx.flags = 0u;
+                    if (drew) {
+                        nx.node = st.cb;
+                        nx.cb = st.child0;
+                        nx.ce = st.child1;
+                        nx.tok0 = (uint32_t)__builtin_amdgcn_readfirstlane((int)a_tok);
+                        nx.child0 = (uint32_t)__builtin_amdgcn_readfirstlane((int)a_child);
+                        nx.child1 = (uint32_t)__builtin_amdgcn_readfirstlane((int)a_next);
+                        nx.flags = 1u;
+                        nx.slot = (st.tok0 & PPV_NODE_HEAVY) ? heavy_slot_of(ix, nx.node) : PPV_NO_SLOT;
+                    }
+                    const bool chain_on = drew && more && next_in_chain(nx) && !(nx.tok0 & PPV_NODE_TERMINAL) && s + 2 < n_steps &&
+                                          t + 2 < stride;
+                    // (the answers go straight into the registers the next step reads, whose old contents are used up:
+                    // a copy of a value that is still on its way would have to wait for it)
+                    const float mv = pk.Mv;
+                    const double zvl = pk.zvl;
+                    const int drawn = pk.id;
+                    if (chain_on) ask(row + step_stride, nx, gx, a_tok, a_child, a_next);
+                    if (drew && s + 1 < n_steps) u = uniforms[(size_t)(s + 1) * (size_t)B + b];
+                    const bool ends = !drew || (st.tok0 & PPV_NODE_TERMINAL) != 0u;
+                    if (lane == 0) {
+                        hand[s & 1].done = ends ? 1 : 0;
+                        hand[s & 1].drew = drew ? 1 : 0;
+                        hand[s & 1].nx = nx;
+                        if (drew) prefixes[(size_t)b * (size_t)stride + t] = drawn;
+                        if (ids) ids[(size_t)s * (size_t)B + b] = drew ? drawn : -1;
+                        if (!drew) lx = -INFINITY;   // the row stops outside S
+                        if (logZ_valid && mv == -INFINITY) logZ_valid[(size_t)s * (size_t)B + b] = -INFINITY;
+                    }
+                    __syncthreads();
+                    if (mv != -INFINITY) {
+                        float M, za;
+                        double zv;
+                        combine_tiles(shs[s & 1], nt, lane, tp, false, M, za, zv);
+                        const float lzv = fmaf(mv - M, tp.inv, LN2F * (fast_log2((float)zvl) - fast_log2(za)));
+                        if (lane == 0) {
+                            if (logZ_valid) logZ_valid[(size_t)s * (size_t)B + b] = lzv;
+                            if (drew) lx += lzv;
+                        }
+                    }
+                    done = ends;
+                    if (drew) {
+                        t += 1;
+                        st = nx;
+                    }
+                    if (ends || s + 1 == n_steps) {
+                        finished = true;
+                        break;
+                    }
+                    s += 1;
+                    row += step_stride;
+                    if (!chain_on) break;
+                }
+            } else {
+                const int k0 = wave_s - 1, k1 = wave_s - 1 + ntw;   // (a tile past the row reads as -inf and is not recorded)
+                RawTile A0, A1, B0, B1;
+                load_tile_clamped<T>(row, V, k0, lane, A0);
+                load_tile_clamped<T>(row, V, k1, lane, A1);
+                auto reduce = [&](RawTile &tile, int k, RowShared &cur) {
+                    pad_tile_tail<T>(tile, V, k, lane);
+                    float m, zall, zval;
+                    tile_stats<T, false>(tile, 0u, lane, tp, m, zall, zval);
+                    if (lane == 0 && k < nt) {
+                        cur.tile_m[k] = m;
+                        cur.tile_zall[k] = zall;
+                        cur.tile_zval[k] = zval;
+                        cur.tile_ref[k] = m;
+                    }
+                };
+                // one step on the tiles (c0, c1), the next row's tiles requested into (n0, n1) first.
+                // Returns true while the chain goes on.
+                auto chain_step = [&](RawTile &c0, RawTile &c1, RawTile &n0, RawTile &n1) {
+                    load_tile_clamped<T>(row + step_stride, V, k0, lane, n0);
+                    load_tile_clamped<T>(row + step_stride, V, k1, lane, n1);
+                    reduce(c0, k0, shs[s & 1]);
+                    reduce(c1, k1, shs[s & 1]);
+                    const bool more = row_goes_on();
+                    __syncthreads();
+                    const bool ends = hand[s & 1].done != 0;
+                    const bool drew = hand[s & 1].drew != 0;
+                    done = ends;
+                    if (drew) {
+                        t += 1;
+                        st = hand[s & 1].nx;
+                    }
+                    if (ends || s + 1 == n_steps) {
+                        finished = true;
+                        return false;
+                    }
+                    s += 1;
+                    row += step_stride;
+                    return drew && more && next_in_chain(st) && row_goes_on();
+                };
+                while (chain_step(A0, A1, B0, B1) && chain_step(B0, B1, A0, A1)) {
+                }
+            }
+            if (finished) break;
+            // a prefix of another kind: its step starts below from the row's first tile as the other steps know it
+            if (wave < nt) load_tile<T>(row, V, wave, lane, first);
+            if (wave_s != 0) u = uniforms[(size_t)s * (size_t)B + b];
+            s -= 1;
+            continue;
+        }
+        if (LOOP_REG && mode == VALID_LIST && nchild < WAVE) {
+            // ---- A fast step: the children are a short list in wavefront 0's registers.  Wavefront 0 draws the
+            // token and works out the next cursor (with its look-ahead) while the tiles are on their way, and hands
+            // both to the workgroup through LDS; the step's one barrier says that the tiles' statistics and the
+            // hand-over are there.  After it the other wavefronts go straight on to the next step while wavefront 0
+            // adds up the row's totals: statistics and hand-over alternate between two buffers, and a buffer is not
+            // written again before everybody has passed the barrier after the one it was read behind.
+            RowShared &cur = shs[s & 1];
+            const bool known = nchild == 1 && st.flags == 1u;   // the cursor knows its only child
+            uint32_t e_tok = 0u, e_child = 0u, a_tok = 0u, a_child = 0u, a_next = 0u;
+            float gx = -INFINITY;
+            if (wave == 0) {
+                if (known) {
+                    e_tok = lane == 0 ? st.tok0 : 0u;
+                    e_child = lane == 0 ? st.child0 : st.child1;
+                } else if (lane <= nchild) {
+                    const NodeEnt e = ix.ent[cb + (uint32_t)lane];
+                    e_tok = e.tok;
+                    e_child = e.child;
+                }
+                if (lane < nchild) {
+                    const uint32_t v = e_tok & PPV_NODE_TOKEN;
+                    if (sizeof(T) == 4) gx = __uint_as_float(((const uint32_t *)row)[v]);
+                    else gx = __uint_as_float(((uint32_t)((const uint16_t *)row)[v]) << 16);
+                    const uint32_t a0 = e_child < ix.n_nodes ? e_child : ix.n_nodes;
+                    const uint32_t a1 = a0 < ix.n_nodes ? a0 + 1u : ix.n_nodes;
+                    const NodeEnt g0 = ix.ent[a0];
+                    a_tok = g0.tok;
+                    a_child = g0.child;
+                    a_next = ix.ent[a1].child;
+                }
+            }
+            ListPick pk;
+            pk.id = -1;
+            pk.pos = -1;
+            pk.Mv = -INFINITY;
+            pk.zvl = 0.0;
+            if (wave == 0) {
+                pk = reg_list_pick(gx, e_tok, nchild, u, lane, tp);
+                const bool drew = pk.id >= 0 && t < stride;
+                RowState nx = st;
+                nx.flags = 0u;
+                uint32_t tokw = 0u;
+                if (drew) {
+                    nx.node = cb + (uint32_t)pk.pos;
+                    tokw = lane_value(e_tok, pk.pos);
+                    nx.cb = lane_value(e_child, pk.pos);
+                    nx.ce = lane_value(e_child, pk.pos + 1);
+                    nx.tok0 = lane_value(a_tok, pk.pos);
+                    nx.child0 = lane_value(a_child, pk.pos);
+                    nx.child1 = lane_value(a_next, pk.pos);
+                    nx.flags = 1u;
+                    nx.slot = (tokw & PPV_NODE_HEAVY) ? heavy_slot_of(ix, nx.node) : PPV_NO_SLOT;
+                }
+                if (lane == 0) {
+                    hand[s & 1].done = (!drew || (tokw & PPV_NODE_TERMINAL)) ? 1 : 0;
+                    hand[s & 1].drew = drew ? 1 : 0;
+                    hand[s & 1].nx = nx;
+                    if (drew) prefixes[(size_t)b * (size_t)stride + t] = pk.id;
+                    if (ids) ids[(size_t)s * (size_t)B + b] = drew ? pk.id : -1;
+                    if (!drew) lx = -INFINITY;   // the row stops outside S
+                    if (logZ_valid && pk.Mv == -INFINITY) logZ_valid[(size_t)s * (size_t)B + b] = -INFINITY;
+                }
+            }
+            struct {
+                __device__ void operator()() const {}
+            } nothing;
+            stream_tiles<T, false, false, RowShared>(row, V, first, nullptr, cur, lane, wave, nw, tp, nothing, nullptr);
+            __syncthreads();
+            done = hand[s & 1].done != 0;
+            const bool drew = hand[s & 1].drew != 0;
+            if (drew) {
+                t += 1;
+                st = hand[s & 1].nx;
+            }
+            if (wave == 0 && pk.Mv != -INFINITY) {
+                float M, za;
+                double zv;
+                combine_tiles(cur, nt, lane, tp, false, M, za, zv);
+                const float lzv = fmaf(pk.Mv - M, tp.inv, LN2F * (fast_log2((float)pk.zvl) - fast_log2(za)));
+                if (lane == 0) {
+                    if (logZ_valid) logZ_valid[(size_t)s * (size_t)B + b] = lzv;
+                    if (drew) lx += lzv;
+                }
+            }
+            if (done || s + 1 == n_steps) break;
+            row += step_stride;
+            if (wave < nt) load_tile<T>(row, V, wave, lane, first);
+            u = uniforms[(size_t)(s + 1) * (size_t)B + b];
+            continue;
+        }
+        if (LOOP_REG) __syncthreads();   // (wavefront 0 may still be reading the statistics of a fast step before this one)
         const uint32_t *image = ix.heavy_bits + (size_t)(slot != PPV_NO_SLOT ? slot : 0) * (size_t)ix.n_words;
         int member_child = 0;
         if (mode == VALID_LIST) {
@@ -1571,6 +1840,7 @@ void launch_decode_kernel(bool loop, bool pipe, dim3 grid, dim3 block, hipStream
                        split_shift, scratch, advance)
     if (split_shift && !loop) PPV_LAUNCH_DECODE(false, false, true, false);   // (a split row's turns are short)
     else if (loop && pipe) PPV_LAUNCH_DECODE(true, true, false, false);
+    else if (loop && rs && B <= REG_MAX_ROWS) PPV_LAUNCH_DECODE(true, false, false, true);
     else if (loop) PPV_LAUNCH_DECODE(true, false, false, false);
     else if (pipe) PPV_LAUNCH_DECODE(false, true, false, false);
     else if (rs && B <= REG_MAX_ROWS) PPV_LAUNCH_DECODE(false, false, false, true);
@@ -1721,6 +1991,13 @@ ppv_status launch_decode(const ppv_index_t *ix, int32_t *prefixes, int32_t prefi
     const int parts = loop ? 1 : parts_for(ix->view.vocab, dt, B, hs, &scratch);
     int nw = waves_for(ix->view.vocab, dt, B, parts, !loop && state != nullptr);
     if (loop && nw > LOOP_WAVES) nw = LOOP_WAVES;
+    {   // the loop kernel with the list in registers: one wavefront draws, the others stream two tiles each
+        const int tile = (dt == PPV_F32) ? TileGeom<float>::TILE : TileGeom<uint16_t>::TILE;
+        const int nt = (ix->view.vocab + tile - 1) / tile;
+        if (loop && state && B <= REG_MAX_ROWS && !long_turns(ix->view.vocab, dt, nw) && nt >= 2 && (nt + 1) / 2 + 1 <= CHAIN_WAVES &&
+            ppv_tuning(PPV_TUNE_WAVES_PER_ROW) == 0)
+            nw = (nt + 1) / 2 + 1;
+    }
     const dim3 grid((unsigned)B * (unsigned)parts), block(nw * WAVE);
     RowState *rs = (RowState *)state;
     const bool pipe = long_turns(ix->view.vocab, dt, parts * nw);
