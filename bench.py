@@ -29,7 +29,12 @@ HBM_PEAK_GBS = 8000.0  # MI355X published peak HBM3E bandwidth
 # HBM bytes per launch of the dominant kernel from rocprofv3 counter runs (FETCH_SIZE + WRITE_SIZE, each
 # scaled by what the same counter reads for a plain copy of known size); see profiles/.  Keyed by
 # (workload, batch); None until measured for that shape.
-TRAFFIC_BYTES_PER_LAUNCH = {("C3", 256): 9795931}   # profiles/decode_step_C3_B256.md
+TRAFFIC_BYTES_PER_LAUNCH = {
+    ("C3", 256): (9770611, "profiles/decode_kernel_C3_B256.md: FETCH_SIZE + WRITE_SIZE of the per-step decode_kernel, "
+                           "mean over the 32 launches of a loop, copy-calibrated"),
+    ("C5", 1024): (529855501, "profiles/mask_sample_kernels_C5.md: FETCH_SIZE + WRITE_SIZE of the one-call kernel, "
+                              "copy-calibrated"),
+}
 
 
 def algorithmic_bytes_per_prefix_step(V: int, elem: int, n_children: float) -> float:
@@ -261,9 +266,8 @@ def main() -> int:
     achieved = bytes_per_launch_avg / avg_launch_s / 1e9
     roofline = {"bound": "hbm", "kernel": "decode_kernel<bf16, per-step>", "achieved": round(achieved, 1),
                 "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
-                "traffic": TRAFFIC_BYTES_PER_LAUNCH.get((cfg.name, B)),
-                "traffic_source": ("profiles/decode_step_C3_B256.md: counters of an earlier build of this kernel with the "
-                                   "same data movement" if (cfg.name, B) in TRAFFIC_BYTES_PER_LAUNCH else None),
+                "traffic": TRAFFIC_BYTES_PER_LAUNCH.get((cfg.name, B), (None, None))[0],
+                "traffic_source": TRAFFIC_BYTES_PER_LAUNCH.get((cfg.name, B), (None, "not measured for this shape"))[1],
                 "avg_launch_us": round(avg_launch_s * 1e6, 2), "launches_per_step": n_launch,
                 "bytes_per_launch": int(bytes_per_launch_avg),
                 "rows_per_launch_avg": round(float(active_per_step.mean()), 1),
@@ -486,8 +490,10 @@ def single_call_bench(args, cfg, torch, ppv, W, dev):
                                ("one ppv_sample_next call per step (valid set and sample fused, no mask written), "
                                 if use_fused else "one ppv_next_token_mask + one constrained_sample per step, ") + launch},
         "roofline": {"bound": "hbm", "kernel": kernel, "achieved": round(achieved, 1),
-                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
-                     "traffic_source": "not measured for this shape",
+                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
+                     "traffic": TRAFFIC_BYTES_PER_LAUNCH.get((cfg.name, B), (None, None))[0] if use_fused else None,
+                     "traffic_source": (TRAFFIC_BYTES_PER_LAUNCH.get((cfg.name, B), (None, "not measured for this shape"))[1]
+                                        if use_fused else "not measured for this pipeline"),
                      "avg_launch_us": round(k_time / args.steps * 1e6, 2), "bytes_per_launch": int(k_bytes),
                      "device_copy_GBs": measured_copy_bandwidth(torch, dev)},
         "pipelines": {"one_call": one, "two_calls": two},
