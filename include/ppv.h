@@ -327,7 +327,8 @@ ppv_status ppv_disc_select(const float *logx, int32_t n_candidates, int32_t K, i
  * issued from another thread is a race.
  *   PPV_TUNE_WAVES_PER_ROW   wavefronts per row of the sampling kernels, 1..16; 0 = the library's table
  *   PPV_TUNE_TOPM_WAVES      the same for ppv_topm_mask
- *   PPV_TUNE_TOPM_STREAMING  1: every row of ppv_topm_mask takes the whole-row select (tests); 0 = as needed
+ *   PPV_TUNE_TOPM_STREAMING  1: every row of ppv_topm_mask takes the whole-row select (tests); 2: the usual select,
+ *                            but also for mask-only calls on prefixes with few children (no counting); 0 = as needed
  *   PPV_TUNE_LOOKUP          0: ppv_build_index / ppv_index_load leave out the look-up table of whole prefixes
  *   PPV_TUNE_LOOKUP_WEAK     1: the table is built with one fingerprint for all entries (tests: every probe is
  *                            a false hit that the exact check must turn away)

@@ -22,6 +22,11 @@
 //            binary search for its last token among the prefix's children -- or one bit test in
 //            the ready-made image of a heavy prefix.  One thread per candidate.
 //   extend   the mask row is assembled in LDS and written with whole words.
+//   count    a caller that wants only the mask (no candidate list, no verdicts) does not need the top M at all
+//            when the prefix has few continuations: token t is among the M most probable iff fewer than M
+//            tokens come before it in the order (logit descending, token id ascending).  Those are counted
+//            for each child in one pass over the row, two instructions per token and child, with no
+//            histogram, no list and no second pass.
 // Nothing here is a dense contraction; the row is read from HBM once (64 KB at V = 32k, bf16).
 #include <cstdlib>
 
@@ -458,6 +463,180 @@ __device__ inline bool select_listed(const T *__restrict__ row, int V, int c0, i
     return true;
 }
 
+
+// ---- mask-only calls, prefixes with at most TOPM_COUNT_MAX children ----
+constexpr int TOPM_COUNT_MAX = 8;
+
+// This lane's 16 bytes of chunk c, from an address that is always inside the row: a chunk beyond the last one
+// reads the last one again, a lane beyond the row's end reads the row's first bytes (the caller discards both).
+// No condition stands between the caller and the load, so loads for the next batch can be in flight while this
+// batch is counted.
+template <typename T> __device__ inline uint4 load_raw_clamped(const T *__restrict__ row, int V, int nc, int c, int lane) {
+    constexpr int EPL = KeyChunk<T>::EPL;
+    const int cc = c < nc ? c : nc - 1;
+    const int g = (cc * WAVE + lane) * EPL;
+    typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+    const u32x4 v = __builtin_nontemporal_load((const u32x4 *)(row + (g < V ? g : 0)));
+    return make_uint4(v.x, v.y, v.z, v.w);
+}
+
+// Two bf16 values in one word -> their two 16-bit keys, ordered as the values are (-0 just below +0: the
+// thresholds below allow for it).
+typedef short topm_s2 __attribute__((ext_vector_type(2)));
+__device__ inline uint32_t pk_keys(uint32_t w) {
+    const topm_s2 sign = __builtin_bit_cast(topm_s2, w) >> 15;   // 0xFFFF under a negative value
+    return w ^ (__builtin_bit_cast(uint32_t, sign) | 0x80008000u);
+}
+// per half: 1 if the key is above the threshold, else 0.  Two packed 16-bit instructions (saturating subtraction,
+// minimum with 1), written out because the compiler turns the same expression back into a comparison and a
+// select per half.
+__device__ inline uint32_t pk_above(uint32_t keys, uint32_t thresholds) {
+    uint32_t d, r;
+    const uint32_t ones = 0x00010001u;
+    asm("v_pk_sub_u16 %0, %1, %2 clamp" : "=v"(d) : "v"(keys), "v"(thresholds));
+    asm("v_pk_min_u16 %0, %1, %2" : "=v"(r) : "v"(d), "v"(ones));
+    return r;
+}
+// The two thresholds of a child whose logit has the bits `b` (bf16 in the upper half), each in both halves of a
+// word: a token at a smaller id comes before the child if its key is above ge, one at a larger id if above gt.
+__device__ inline void pk_thresholds(uint32_t b, uint32_t &ge, uint32_t &gt) {
+    const uint32_t h = b >> 16;
+    const uint32_t key = h ^ ((h & 0x8000u) ? 0xFFFFu : 0x8000u);
+    const bool zero = (h & 0x7FFFu) == 0u;
+    const uint32_t k_ge = zero ? 0x7FFFu : key, k_gt = zero ? 0x8000u : key;   // -0 and +0 are equal
+    const uint32_t t_ge = k_ge ? k_ge - 1u : 0u;
+    ge = t_ge | (t_ge << 16);
+    gt = k_gt | (k_gt << 16);
+}
+
+// Counts, for each of the n children (token tokc[j], logit thr[j], both wave-uniform), the tokens of chunk c that
+// come before it in the order of the top-M selection: a larger logit, or an equal one at a smaller token id.
+// cnt[j] is this lane's count; for bf16 rows two 16-bit counts side by side (a lane sees at most 4,096 tokens of
+// a row), because whole chunks are then counted two tokens at a time on 16-bit keys: three instructions per word
+// and child, none of them through a condition register.
+template <typename T>
+__device__ inline void count_chunk(const uint4 &raw, int V, int c, int lane, int n, const int (&tokc)[TOPM_COUNT_MAX],
+                                   const float (&thr)[TOPM_COUNT_MAX], uint32_t (&cnt)[TOPM_COUNT_MAX]) {
+    constexpr int EPL = KeyChunk<T>::EPL;
+    constexpr bool PACKED = sizeof(T) == 2;
+    const int first = c * WAVE * EPL;            // the chunk holds tokens first .. first + 64 * EPL - 1
+    const int g = first + lane * EPL;
+    const bool ragged = first + WAVE * EPL > V;  // (wave-uniform) the row ends inside this chunk
+    float x[EPL];
+    uint32_t keys[4] = {0u, 0u, 0u, 0u};
+    if (PACKED) {
+        const uint32_t w[4] = {raw.x, raw.y, raw.z, raw.w};
+#pragma unroll
+        for (int i = 0; i < 4; i++) keys[i] = pk_keys(w[i]);
+        if (ragged) {                            // tokens behind the row's end get the lowest key: above no threshold
+#pragma unroll
+            for (int i = 0; i < 4; i++)
+                keys[i] &= (g + 2 * i < V ? 0x0000FFFFu : 0u) | (g + 2 * i + 1 < V ? 0xFFFF0000u : 0u);
+        }
+    } else {
+        unpack_vals<T>(raw, x);
+        if (ragged) {
+#pragma unroll
+            for (int e = 0; e < EPL; e++)
+                if (g + e >= V) x[e] = -INFINITY;    // never before a child: compared with ">" (they follow every token)
+        }
+    }
+#pragma unroll
+    for (int j = 0; j < TOPM_COUNT_MAX; j++) {
+        if (j >= n) break;                       // (wave-uniform)
+        const float t = thr[j];
+        const bool before = first + WAVE * EPL <= tokc[j];   // every token of the chunk has a smaller id: ties count
+        const bool after = first > tokc[j];                   // every token has a larger id: ties do not count
+        uint32_t k = 0;
+        if (before || after) {
+            if (PACKED) {
+                uint32_t ge, gt;
+                pk_thresholds(__float_as_uint(t), ge, gt);
+                const uint32_t th = before ? ge : gt;
+#pragma unroll
+                for (int i = 0; i < 4; i++) k += pk_above(keys[i], th);
+            } else if (before) {
+#pragma unroll
+                for (int e = 0; e < EPL; e++) k += x[e] >= t ? 1u : 0u;
+            } else {
+#pragma unroll
+                for (int e = 0; e < EPL; e++) k += x[e] > t ? 1u : 0u;
+            }
+        } else {                                 // the child's own chunk (one per child and row)
+            if (PACKED) {
+                unpack_vals<T>(raw, x);
+#pragma unroll
+                for (int e = 0; e < EPL; e++)
+                    if (g + e >= V) x[e] = -INFINITY;
+            }
+#pragma unroll
+            for (int e = 0; e < EPL; e++) k += (x[e] > t || (x[e] == t && g + e < tokc[j])) ? 1u : 0u;
+        }
+        cnt[j] += k;
+    }
+}
+
+// The mask row of a prefix with n <= TOPM_COUNT_MAX children (entries cb .. cb + n - 1), restricted to the m most
+// probable tokens.  Every thread of the workgroup calls; r holds the wavefront's first four chunks; tot[] was
+// cleared before the last barrier.
+template <typename T>
+__device__ inline void count_children(const IndexView &ix, const T *__restrict__ row, int V, int nc, int c0, int c1,
+                                      int m, uint32_t cb, int n, uint4 (&r)[4], uint32_t *tot,
+                                      uint32_t *__restrict__ out, int n_words, int lane, int nthreads) {
+    // child j in lane j: its token and that token's logit
+    uint32_t ctok = 0u;
+    float cthr = 0.f;
+    if (lane < n) {
+        ctok = ix.ent[cb + (uint32_t)lane].tok & PPV_NODE_TOKEN;
+        ctok = ctok < (uint32_t)V ? ctok : 0u;   // (always inside for an index that was built or loaded)
+        cthr = __uint_as_float(KeyChunk<T>::bits_of(row, (int)ctok));
+    }
+    int tokc[TOPM_COUNT_MAX];
+    float thr[TOPM_COUNT_MAX];
+    uint32_t cnt[TOPM_COUNT_MAX];
+#pragma unroll
+    for (int j = 0; j < TOPM_COUNT_MAX; j++) {
+        tokc[j] = (int)lane_value(ctok, j);
+        thr[j] = __uint_as_float(lane_value(__float_as_uint(cthr), j));
+        cnt[j] = 0u;
+    }
+    // the two halves of r take turns: a pair of chunks is asked for again as soon as it has been counted, while
+    // the other pair is counted
+    for (int c = c0; c < c1; c += 4) {
+#pragma unroll
+        for (int h = 0; h < 4; h += 2) {
+#pragma unroll
+            for (int u = h; u < h + 2; u++)
+                if (c + u < c1) count_chunk<T>(r[u], V, c + u, lane, n, tokc, thr, cnt);
+#pragma unroll
+            for (int u = h; u < h + 2; u++) r[u] = load_raw_clamped<T>(row, V, nc, c + 4 + u, lane);
+        }
+    }
+#pragma unroll
+    for (int j = 0; j < TOPM_COUNT_MAX; j++) {
+        if (j >= n) break;
+        const uint32_t w = wave_sum(sizeof(T) == 2 ? (cnt[j] & 0xFFFFu) + (cnt[j] >> 16) : cnt[j]);
+        if (lane == 0) atomicAdd(&tot[j], w);
+    }
+    __syncthreads();
+    bool in[TOPM_COUNT_MAX];
+#pragma unroll
+    for (int j = 0; j < TOPM_COUNT_MAX; j++) in[j] = j < n && tot[j] < (uint32_t)m;
+    auto word = [&](int i) {
+        uint32_t w = 0u;
+#pragma unroll
+        for (int j = 0; j < TOPM_COUNT_MAX; j++)
+            if (in[j] && (tokc[j] >> 5) == i) w |= 1u << (tokc[j] & 31);
+        return w;
+    };
+    if ((n_words & 3) == 0 && (((uintptr_t)out) & 15u) == 0) {
+        for (int i = (int)threadIdx.x; i < (n_words >> 2); i += nthreads)
+            ((uint4 *)out)[i] = make_uint4(word(4 * i), word(4 * i + 1), word(4 * i + 2), word(4 * i + 3));
+    } else {
+        for (int i = (int)threadIdx.x; i < n_words; i += nthreads) out[i] = word(i);
+    }
+}
+
 template <typename T, int LIST>
 __global__ __launch_bounds__(TOPM_WAVES *WAVE) void topm_kernel(IndexView ix, const int32_t *__restrict__ prefixes,
                                                                 int32_t stride, const int32_t *__restrict__ lens,
@@ -485,9 +664,12 @@ __global__ __launch_bounds__(TOPM_WAVES *WAVE) void topm_kernel(IndexView ix, co
     const int cpw = (nc + nw - 1) / nw;
     const int c0 = wave * cpw, c1 = (c0 + cpw < nc) ? c0 + cpw : nc;
 
-    const bool listed = !force_streaming && nthreads * TOPM_SLOTS >= LIST;
+    const bool listed = force_streaming != 1 && nthreads * TOPM_SLOTS >= LIST;
+    // a caller that asks for the mask alone: prefixes with few children are settled by counting (see count_children)
+    const bool counting = force_streaming == 0 && !top_ids && !mask_V;
     uint4 r[4];
-    if (listed) load_chunks<T>(row, V, c0, c1, lane, r);   // in flight while the prefix is located
+    if (listed || counting) load_chunks<T>(row, V, c0, c1, lane, r);   // in flight while the prefix is located
+    if (counting && tid < TOPM_COUNT_MAX) seg_a[tid] = 0u;
     if (wave == 0) {   // the part every candidate row shares: locate the prefix once
         const int32_t mine = first_tokens(prefixes + (size_t)b * (size_t)stride, stride, lane);
         int t = lens[b];
@@ -498,6 +680,25 @@ __global__ __launch_bounds__(TOPM_WAVES *WAVE) void topm_kernel(IndexView ix, co
             bc[1] = w.found ? 1u : 0u;
             bc[2] = w.found ? w.cb : 0u;
             bc[3] = w.found ? w.ce : 0u;
+        }
+    }
+    if (counting) {
+        __syncthreads();   // the walk's verdict
+        const bool found = bc[1] != 0u;
+        const uint32_t cb = bc[2];
+        const int n = (int)(bc[3] - cb);
+        uint32_t *out = mask + (size_t)b * (size_t)n_words;
+        if (!found || n == 0) {   // no continuation at all: the row of the mask is empty, the logits do not matter
+            if ((n_words & 3) == 0 && (((uintptr_t)mask) & 15u) == 0) {
+                for (int i = tid; i < (n_words >> 2); i += nthreads) ((uint4 *)out)[i] = make_uint4(0u, 0u, 0u, 0u);
+            } else {
+                for (int i = tid; i < n_words; i += nthreads) out[i] = 0u;
+            }
+            return;
+        }
+        if (n <= TOPM_COUNT_MAX && (uint32_t)n <= ix.heavy_min) {
+            count_children<T>(ix, row, V, nc, c0, c1, m, cb, n, r, seg_a, out, n_words, lane, nthreads);
+            return;
         }
     }
     // ---- select
@@ -575,8 +776,9 @@ extern "C" ppv_status ppv_topm_mask(const ppv_index_t *ix, const int32_t *prefix
     const int64_t per16 = (dt == PPV_F32) ? 4 : 8;
     if (row_stride < V || row_stride % per16 != 0 || ((uintptr_t)logits & 15u) != 0) return PPV_EINVAL;
     const int threads = topm_waves(V, dt, B) * WAVE;
-    // testing aid: PPV_TUNE_TOPM_STREAMING = 1 sends every row through the whole-row radix select
-    const int force_streaming = ppv_tuning(PPV_TUNE_TOPM_STREAMING) == 1 ? 1 : 0;
+    // testing aid: PPV_TUNE_TOPM_STREAMING = 1 sends every row through the whole-row radix select; 2 keeps the usual
+    // select but takes the top M also where counting would do (mask-only calls)
+    const int force_streaming = ppv_tuning(PPV_TUNE_TOPM_STREAMING);
     const size_t lds = (size_t)(ix->view.n_words > TOPM_BINS ? ix->view.n_words : TOPM_BINS) * sizeof(uint32_t);
     const dim3 grid((unsigned)B), block(threads);
     hipStream_t hs = (hipStream_t)stream;

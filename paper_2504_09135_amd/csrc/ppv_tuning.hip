@@ -14,7 +14,7 @@ struct KnobSpec {
 constexpr KnobSpec KNOBS[PPV_TUNE_COUNT] = {
     {"PPV_WAVES_PER_ROW", 0, 0, 16},   // PPV_TUNE_WAVES_PER_ROW
     {"PPV_TOPM_WAVES", 0, 0, 16},      // PPV_TUNE_TOPM_WAVES
-    {"PPV_TOPM_STREAMING", 0, 0, 1},   // PPV_TUNE_TOPM_STREAMING
+    {"PPV_TOPM_STREAMING", 0, 0, 2},   // PPV_TUNE_TOPM_STREAMING
     {"PPV_LOOKUP", 1, 0, 1},           // PPV_TUNE_LOOKUP
     {"PPV_LOOKUP_WEAK", 0, 0, 1},      // PPV_TUNE_LOOKUP_WEAK
     {"PPV_ROW_SPLIT", 0, 0, 16},       // PPV_TUNE_ROW_SPLIT

@@ -31,13 +31,22 @@ def sorted_array(name):
     return _sorted[name]
 
 
-def gpu_topm(index, prefixes, lens, logits_dev, M):
+def gpu_topm(index, prefixes, lens, logits_dev, M, specified=None):
     B = prefixes.shape[0]
     mask = torch.full((B, index.n_words), -1, dtype=torch.int32, device=DEV)
     top = torch.full((B, M), -9, dtype=torch.int32, device=DEV)
     mv = torch.full((B, M), 9, dtype=torch.uint8, device=DEV)
     ppv.ppv_topm_mask(index, to_dev(prefixes), to_dev(lens), logits_dev, M, mask, top, mv)
     torch.cuda.synchronize()
+    # A caller that asks for the mask alone gets the same mask: prefixes with few children are then settled by
+    # counting the tokens that come before each child instead of selecting the top M.
+    alone = torch.full((B, index.n_words), -1, dtype=torch.int32, device=DEV)
+    ppv.ppv_topm_mask(index, to_dev(prefixes), to_dev(lens), logits_dev, M, alone)
+    torch.cuda.synchronize()
+    differ = (alone != mask).any(dim=1).nonzero().flatten().tolist()
+    if specified is not None:   # rows whose result is unspecified (NaN logits) only have to stay inside the full mask
+        differ = [r for r in differ if r in set(int(x) for x in specified)]
+    assert not differ, f"mask-only call differs from the call with candidates in rows {differ[:8]} (M={M})"
     return mask, top.cpu().numpy(), mv.cpu().numpy()
 
 
@@ -142,6 +151,59 @@ def ties_and_special_values(dtype, Ms=(1, 7, 64, 1000)):
     index.free()
 
 
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("V", [200, 4104])
+def test_topm_mask_alone_counts_the_tokens_before_each_child(dtype, V):
+    """A mask-only call settles prefixes with at most eight children by counting, per child, the tokens that come
+    before it (larger logit, or equal logit and smaller id).  Prefixes with 0 .. 12 children, on both sides of that
+    limit and of the index's own limit for listed children (6 at V = 200); logits with many ties, among them the
+    children's own values; M around the counts.  gpu_topm compares the mask-only call with the full one, and
+    assert_topm_parity both with the oracle; switch 2 sends the mask-only call through the selection as well."""
+    rng = np.random.default_rng(V)
+    seqs = []
+    for n in range(1, 13):                                    # prefix [n] has n children, [n, c] has one or two
+        kids = np.sort(rng.choice(V, size=n, replace=False))
+        for c in kids:
+            seqs.append([n, int(c), int(rng.integers(0, V))])
+            if c % 2:
+                seqs.append([n, int(c), int(rng.integers(0, V))])
+    seqs.append([V - 1])                                      # a member without continuation
+    S = W.constraint_set_from_lists(seqs, V)
+    X = oracle.SortedArray(S.tokens, S.offsets, V)
+    index = ppv.ppv_build_index(S.tokens, S.offsets, V)
+    rows = [[]] + [[n] for n in range(1, 13)] + [s[:2] for s in seqs[:40:3] if len(s) > 1] + [[V - 1], [V - 2, 3]]
+    B = len(rows)
+    P = np.full((B, 3), W.PAD_TOKEN, np.int32)
+    L = np.zeros(B, np.int32)
+    for b, r in enumerate(rows):
+        P[b, :len(r)] = r
+        L[b] = len(r)
+    lg = (rng.integers(-3, 4, size=(B, V)) * 0.25).astype(np.float32)      # seven distinct values: ties everywhere
+    lg[2, :] = 0.75                                           # every token equal: the first M ids
+    lg[3, ::2] = -np.inf
+    lg[4, :] = -np.inf
+    lg[5, ::2] = -0.0
+    lg[5, 1::2] = 0.0
+    per = 8 if dtype == "bf16" else 4
+    Vp = (V + per - 1) // per * per
+    if dtype == "bf16":
+        bits = (lg.view(np.uint32) >> 16).astype(np.uint16)   # exact in bf16
+        padded = np.full((B, Vp), 0x7F80, np.uint16)          # +inf behind the row's end: must never be counted
+        padded[:, :V] = bits
+        ld = to_dev(padded.view(np.int16)).view(torch.bfloat16)[:, :V]
+    else:
+        padded = np.full((B, Vp), np.inf, np.float32)
+        padded[:, :V] = lg
+        ld = to_dev(padded)[:, :V]
+    for M in (1, 2, 3, 17, 64, min(V // 2, 700), 1000):
+        for waves in (0, 1, 16):
+            with tuning(ppv.PPV_TUNE_TOPM_WAVES, waves):
+                assert_topm_parity(index, X, P, L, lg, ld, M)
+        with tuning(ppv.PPV_TUNE_TOPM_STREAMING, 2):
+            assert_topm_parity(index, X, P, L, lg, ld, M)
+    index.free()
+
+
 def test_topm_largest_vocabulary():
     """V = PPV_MAX_VOCAB: the mask row fills the LDS that the histogram used; fp32 rows of 256 chunks per wavefront."""
     V = ppv.PPV_MAX_VOCAB
@@ -203,7 +265,11 @@ def test_topm_rows_with_nans_stay_in_bounds(waves):
     full = trie.query(pb.prefixes, pb.lens).mask
     for M in (50, 1000):
         with tuning(ppv.PPV_TUNE_TOPM_WAVES, waves):
-            dmask, top, mv = gpu_topm(index, pb.prefixes, pb.lens, ld, M)
+            dmask, top, mv = gpu_topm(index, pb.prefixes, pb.lens, ld, M, specified=good)
+            alone = torch.full_like(dmask, -1)
+            ppv.ppv_topm_mask(index, to_dev(pb.prefixes), to_dev(pb.lens), ld, M, alone)
+            torch.cuda.synchronize()
+        assert not (unpack_mask(alone.cpu().numpy().view(np.uint32), cfg.vocab) & ~full).any()
         assert ((top >= -1) & (top < cfg.vocab)).all()
         got = unpack_mask(dmask.cpu().numpy().view(np.uint32), cfg.vocab)
         assert not (got & ~full).any()
