@@ -1991,6 +1991,11 @@ ppv_status launch_decode(const ppv_index_t *ix, int32_t *prefixes, int32_t prefi
     const int parts = loop ? 1 : parts_for(ix->view.vocab, dt, B, hs, &scratch);
     int nw = waves_for(ix->view.vocab, dt, B, parts, !loop && state != nullptr);
     if (loop && nw > LOOP_WAVES) nw = LOOP_WAVES;
+    // The loop kernel in a large batch: a workgroup stays with its row for every step, so what hides one row's
+    // dependent phases (cursor, barrier, draw) is other rows on the same compute unit, and two wavefronts per row
+    // put twice as many there as four (C3 replicas, M prefix-steps/s with 1 / 2 / 4 / 8 wavefronts per row:
+    // 4,096 rows: 72 / 81 / 66 / 39; 16,384 rows: 95 / 98 / 77 / 42 -- 6.3 TB/s; the per-step kernel is best with four).
+    if (loop && B > REG_MAX_ROWS && nw > 2 && ppv_tuning(PPV_TUNE_WAVES_PER_ROW) == 0) nw = 2;
     {   // the loop kernel with the list in registers: one wavefront draws, the others stream two tiles each
         const int tile = (dt == PPV_F32) ? TileGeom<float>::TILE : TileGeom<uint16_t>::TILE;
         const int nt = (ix->view.vocab + tile - 1) / tile;

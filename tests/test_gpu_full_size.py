@@ -231,6 +231,52 @@ def test_C3_decode_loop_at_the_batch_sizes_of_the_sweep(B):
     assert np.isfinite(logx.cpu().numpy()).all()
 
 
+def test_C3_one_launch_loop_in_a_batch_above_1024_rows():
+    """ppv_decode_loop picks another launch shape for batches above 1,024 rows (two wavefronts per row, the three-tile
+    pipeline inside the loop kernel).  It must give, bit for bit, what one ppv_decode_step per step gives on the same
+    logits -- whose results at such batch sizes are checked against the oracle in the test above."""
+    cfg = W.CONFIGS["C3"]
+    S, trie, index = build_both(cfg)
+    V, L, B = cfg.vocab, index.l_max, 2048
+    gen = torch.Generator(device=DEV)
+    gen.manual_seed(77)
+    logits = torch.empty((L, B, V), dtype=torch.bfloat16, device=DEV)
+    for s in range(L):
+        logits[s] = (torch.randn((B, V), generator=gen, device=DEV) * cfg.sigma).to(torch.bfloat16)
+    un = torch.rand((L, B), generator=gen, device=DEV)
+
+    def fresh():
+        P = torch.full((B, L), W.PAD_TOKEN, dtype=torch.int32, device=DEV)
+        lens = torch.zeros(B, dtype=torch.int32, device=DEV)
+        act = torch.zeros(B, dtype=torch.uint8, device=DEV)
+        state = torch.zeros((B, ppv.PPV_STATE_WORDS), dtype=torch.int32, device=DEV)
+        logx = torch.zeros(B, dtype=torch.float32, device=DEV)
+        ids = torch.full((L, B), -7, dtype=torch.int32, device=DEV)
+        lz = torch.full((L, B), 7.0, dtype=torch.float32, device=DEV)
+        ppv.ppv_decode_begin(index, P, lens, state, act, logx)
+        return P, lens, act, state, logx, ids, lz
+
+    say("C3, B = 2048: one launch per step")
+    P1, l1, a1, s1, x1, i1, z1 = fresh()
+    for s in range(L):
+        i1[s] = -7
+        on = a1.clone()
+        ppv.ppv_decode_step(index, P1, l1, a1, logits[s], un[s], i1[s], z1[s], x1, state=s1)
+        i1[s][on == 0] = -7                                      # the loop kernel leaves retired rows' entries alone
+        z1[s][on == 0] = 7.0
+    say("C3, B = 2048: one launch for the loop")
+    P2, l2, a2, s2, x2, i2, z2 = fresh()
+    ppv.ppv_decode_loop(index, P2, l2, a2, logits, un, i2, z2, x2, state=s2)
+    torch.cuda.synchronize()
+    assert not a1.any().item() and not a2.any().item()
+    assert torch.equal(P1, P2) and torch.equal(l1, l2)
+    assert torch.equal(x1.view(torch.int32), x2.view(torch.int32))
+    assert torch.equal(i1, i2)
+    assert torch.equal(z1.view(torch.int32), z2.view(torch.int32))
+    q = trie.query(P2.cpu().numpy(), l2.cpu().numpy(), want_mask=False, threads=16)
+    assert (q.member == 1).all()
+
+
 @pytest.mark.parametrize("name", ["C4", "C5"])
 def test_full_size_mask_and_sample(name):
     cfg = W.CONFIGS[name]
