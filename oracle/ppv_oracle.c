@@ -15,8 +15,8 @@
  *     rank at which x would be inserted (the lower bound the binary search of Section 3.2,
  *     "Parallel Verification", ends on);
  *   - member = (x in S), the loop condition of Algorithm 1, SampleCandidate;
- *   - one constrained decoding step of Algorithm 1 (lines "Get next token distribution" to
- *     "Update"): with P = softmax(logits / T), T the temperature that Algorithm 1 takes as input
+ *   - one constrained decoding step of Algorithm 1 (the body of SampleCandidate's loop: next-token
+ *     distribution, valid set, draw, update of x): with P = softmax(logits / T), T the temperature that Algorithm 1 takes as input
  *     (the experiments of Section 4.1 "Methods" use T = 1),
  *     logZ_valid = log |P (.) mask|_1 = LSE_{v in mask} l_v - LSE_{all v} l_v, and a token drawn
  *     from P (.) mask / |P (.) mask|_1.  The paper names no sampling procedure; this oracle fixes
