@@ -123,6 +123,40 @@ class LoopBench:
         final_lens = self.lens.cpu().numpy().astype("int64")
         return elapsed, final_lens
 
+    def saturated_launch_seconds(self, reps=5):
+        """GPU seconds of the launch of decode step 3 alone (every row still active: no member of S is shorter than 4
+        tokens), as the difference between two captured graphs, begin + steps 0..3 and begin + steps 0..2."""
+        torch, ppv = self.torch, self.ppv
+
+        def partial(n):
+            self.lens.zero_()
+            ppv.ppv_decode_begin(self.index, self.prefixes, self.lens, self.state, self.active, self.logx)
+            for s in range(n):
+                ppv.ppv_decode_step(self.index, self.prefixes, self.lens, self.active, self.step_logits[s],
+                                    self.step_uniforms[s], self.ids, self.lz, self.logx, state=self.state)
+
+        times = []
+        for n in (3, 4):
+            side = torch.cuda.Stream()
+            side.wait_stream(torch.cuda.current_stream())
+            with torch.cuda.stream(side):
+                partial(n)
+            torch.cuda.current_stream().wait_stream(side)
+            torch.cuda.synchronize()
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(graph, stream=side):
+                partial(n)
+            graph.replay()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            torch.cuda.synchronize()
+            e0.record()
+            for _ in range(reps):
+                graph.replay()
+            e1.record()
+            torch.cuda.synchronize()
+            times.append(e0.elapsed_time(e1) * 1e-3 / reps)
+        return max(times[1] - times[0], 1e-9)
+
     def per_loop_ms(self, n):
         """GPU milliseconds of n single loops, each between its own pair of HIP events."""
         import numpy as np
@@ -318,11 +352,18 @@ def main() -> int:
             ps = int(fl.sum())
             el1, _ = sb.time(2, 10, single_launch=True)
             bps = algorithmic_bytes_per_prefix_step(V, 2, 1.0)
+            sat = sb.saturated_launch_seconds() if not args.no_graph else None
             out["batch_sweep"].append({"B": Bs, "prefix_steps_per_s": round(ps * 10 / el, 1),
                                        "GBs": round(ps * bps * 10 / el / 1e9, 1),
                                        "frac_of_peak": round(ps * bps * 10 / el / 1e9 / HBM_PEAK_GBS, 4),
                                        "single_launch_prefix_steps_per_s": round(ps * 10 / el1, 1),
-                                       "single_launch_GBs": round(ps * bps * 10 / el1 / 1e9, 1)})
+                                       "single_launch_GBs": round(ps * bps * 10 / el1 / 1e9, 1),
+                                       # one launch with every row still active (decode step 3: no member is shorter
+                                       # than 4 tokens), the loop's own figure being an average over launches that
+                                       # get sparser as rows retire
+                                       "launch_all_rows_active": None if sat is None else {
+                                           "us": round(sat * 1e6, 2), "GBs": round(Bs * bps / sat / 1e9, 1),
+                                           "frac_of_peak": round(Bs * bps / sat / 1e9 / HBM_PEAK_GBS, 4)}})
             del sb, lg, un
 
     if not args.no_sweep:
