@@ -1382,7 +1382,7 @@ __global__ __launch_bounds__(LOOP ? (REG ? CHAIN_WAVES : LOOP_WAVES) * WAVE : MA
         const int nchild = (int)(ce - cb);
         const int mode = nchild == 0 ? VALID_NONE : (slot != PPV_NO_SLOT ? VALID_IMAGE : VALID_LIST);
         if (LOOP_REG && mode == VALID_LIST && nchild == 1 && st.flags == 1u && V % G::EPL == 0 && nw >= 2 &&
-            nt <= 2 * (nw - 1) && !(st.tok0 & PPV_NODE_TERMINAL) && s + 1 < n_steps && t + 1 < stride) {
+            nt <= 2 * (nw - 1)) {
             // ---- A chain of prefixes with one child each, the cursor knowing the child (nearly all of a long
             // sequence below its first levels).  Wavefront 0 only draws tokens: each step it takes the listed
             // logit that it asked for a step earlier, advances the cursor, asks for the next step's logit and
@@ -1390,13 +1390,15 @@ __global__ __launch_bounds__(LOOP ? (REG ? CHAIN_WAVES : LOOP_WAVES) * WAVE : MA
             // two tiles each, the next row's tiles requested before this row's are reduced, in two sets of registers
             // that swap roles from step to step, so that there is no copy of, no condition on and no wait for a
             // tile that is still on its way.  One barrier per step; statistics and hand-over alternate between two
-            // buffers as in the fast step below.  The chain ends with the row, or at a prefix that is not of this
-            // kind, which the code below takes from there.
+            // buffers as in the fast step below.  The chain ends with the row (its last step asks for 16 bytes of
+            // its own row instead of a next row), or at a prefix that is not of this kind, which the code below
+            // takes from there.
             const int ntw = nw - 1;
             const int wave_s = __builtin_amdgcn_readfirstlane(wave);
             auto next_in_chain = [&](const RowState &c) {
                 return c.ce - c.cb == 1u && c.flags == 1u && c.slot == PPV_NO_SLOT;
             };
+            // whether the row has a step after this one (known from the cursor before the token is drawn)
             auto row_goes_on = [&]() { return !(st.tok0 & PPV_NODE_TERMINAL) && s + 1 < n_steps && t + 1 < stride; };
             bool finished = false;   // the row is done, or out of steps
             if (wave_s == 0) {
@@ -1432,8 +1434,7 @@ __global__ __launch_bounds__(LOOP ? (REG ? CHAIN_WAVES : LOOP_WAVES) * WAVE : MA
                         nx.flags = 1u;
                         nx.slot = (st.tok0 & PPV_NODE_HEAVY) ? heavy_slot_of(ix, nx.node) : PPV_NO_SLOT;
                     }
-                    const bool chain_on = drew && more && next_in_chain(nx) && !(nx.tok0 & PPV_NODE_TERMINAL) && s + 2 < n_steps &&
-                                          t + 2 < stride;
+                    const bool chain_on = drew && more && next_in_chain(nx);
                     // (the answers go straight into the registers the next step reads, whose old contents are used up:
                     // a copy of a value that is still on its way would have to wait for it)
                     const float mv = pk.Mv;
@@ -1494,11 +1495,13 @@ __global__ __launch_bounds__(LOOP ? (REG ? CHAIN_WAVES : LOOP_WAVES) * WAVE : MA
                 // one step on the tiles (c0, c1), the next row's tiles requested into (n0, n1) first.
                 // Returns true while the chain goes on.
                 auto chain_step = [&](RawTile &c0, RawTile &c1, RawTile &n0, RawTile &n1) {
-                    load_tile_clamped<T>(row + step_stride, V, k0, lane, n0);
-                    load_tile_clamped<T>(row + step_stride, V, k1, lane, n1);
+                    const bool more = row_goes_on();
+                    const T *nrow = more ? row + step_stride : row;   // no next row: one line of this one (same loads,
+                    const int Vn = more ? V : G::EPL;                 // all clamped to the row's first 16 bytes)
+                    load_tile_clamped<T>(nrow, Vn, k0, lane, n0);
+                    load_tile_clamped<T>(nrow, Vn, k1, lane, n1);
                     reduce(c0, k0, shs[s & 1]);
                     reduce(c1, k1, shs[s & 1]);
-                    const bool more = row_goes_on();
                     __syncthreads();
                     const bool ends = hand[s & 1].done != 0;
                     const bool drew = hand[s & 1].drew != 0;
@@ -1513,7 +1516,7 @@ __global__ __launch_bounds__(LOOP ? (REG ? CHAIN_WAVES : LOOP_WAVES) * WAVE : MA
                     }
                     s += 1;
                     row += step_stride;
-                    return drew && more && next_in_chain(st) && row_goes_on();
+                    return drew && more && next_in_chain(st);
                 };
                 while (chain_step(A0, A1, B0, B1) && chain_step(B0, B1, A0, A1)) {
                 }
