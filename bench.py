@@ -335,6 +335,13 @@ def main() -> int:
                                  "GBs": round(float(bytes_per_launch.sum()) * args.steps / el1 / 1e9, 1),
                                  "frac_of_peak": round(float(bytes_per_launch.sum()) * args.steps / el1 / 1e9 / HBM_PEAK_GBS, 4)}
 
+    if not args.no_graph:
+        # one launch of the timed kernel with all B rows active (decode step 3), beside the loop's average launch
+        sat = lb.saturated_launch_seconds(reps=20)
+        bps1 = algorithmic_bytes_per_prefix_step(V, 2, 1.0)
+        out["roofline"]["launch_all_rows_active"] = {"us": round(sat * 1e6, 2), "GBs": round(B * bps1 / sat / 1e9, 1),
+                                                     "frac_of_peak": round(B * bps1 / sat / 1e9 / HBM_PEAK_GBS, 4)}
+
     if not args.no_sweep:
         # Same loop with R replicas of the batch (logits drawn on the device: same distribution, not
         # checked against the oracle) to show where the kernel goes once the launch is large enough.
