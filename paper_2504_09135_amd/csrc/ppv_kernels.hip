@@ -572,6 +572,24 @@ __device__ inline void stream_tiles(const T *__restrict__ row, int V, const RawT
 template <typename SH>
 __device__ inline void combine_tiles(const SH &sh, int nt, int lane, const Temper &tp, bool image, float &M, float &za,
                                      double &zv) {
+    if (nt <= WAVE) {   // (uniform) one tile per lane at most: both words in one round of LDS reads, no loops; the
+                        // same operations in the same order as below, so the same bits
+        const bool have = lane < nt;
+        const float m = have ? sh.tile_m[have ? lane : 0] : -INFINITY;
+        const float z = have ? sh.tile_zall[have ? lane : 0] : 0.f;
+        const float zval = (image && have) ? sh.tile_zval[have ? lane : 0] : 0.f;
+        M = wave_max(m);
+        float a = 0.f;
+        double v = 0.0;
+        if (m != -INFINITY) {
+            const float sc = exp_scale(m - M, tp.c);
+            a = z * sc;
+            if (image) v = (double)zval * (double)sc;
+        }
+        za = wave_sum(a);
+        zv = image ? wave_sum(v) : 0.0;
+        return;
+    }
     M = -INFINITY;
     for (int k = lane; k < nt; k += WAVE) M = fmaxf(M, sh.tile_m[k]);
     M = wave_max(M);
