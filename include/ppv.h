@@ -287,6 +287,10 @@ ppv_status ppv_decode_loop(const ppv_index_t *index, int32_t *prefixes, int32_t 
  *   top_ids     int32[B, M] or NULL: the row's candidates t_i in increasing token id; -1 beyond min(M, V)
  *   mask_V      uint8[B, M] or NULL: mask_V[b, i] = 1 iff a + [top_ids[b, i]] is a prefix of a member
  *   mask        uint32[B, ceil(V/32)]: bit t set iff t is a candidate and its mask_V is 1
+ * A call that asks for the mask alone (top_ids and mask_V both NULL) returns the same mask, but where the prefix
+ * has no more than eight continuations it does not select the M candidates at all: a continuation t is a candidate
+ * iff fewer than M tokens come before it in the order above, and those are counted in one pass over the row; a
+ * prefix without continuations reads no logits.
  * Errors: PPV_EINVAL (null pointer, M < 1, bad dtype / alignment / stride), PPV_ERANGE (M > PPV_TOPM_MAX),
  * PPV_EDEVICE.  B == 0 is PPV_OK.
  */
