@@ -84,8 +84,7 @@ class LoopBench:
     def loop(self, events=None):
         """One whole decode loop: start from the empty prefix, then l_max fused step launches."""
         ppv = self.ppv
-        self.lens.zero_()                                      # a fill kernel (no memset node in a graph)
-        ppv.ppv_decode_begin(self.index, self.prefixes, self.lens, self.state, self.active, self.logx)
+        ppv.ppv_decode_begin_empty(self.index, self.lens, self.state, self.active, self.logx)   # a = [], x = 1
         for s in range(self.L):
             if events is not None:
                 events[s][0].record()
@@ -97,8 +96,7 @@ class LoopBench:
     def single_launch(self):
         """The same loop as ONE ppv_decode_loop launch (possible here because every step's logits are resident up front)."""
         ppv = self.ppv
-        self.lens.zero_()
-        ppv.ppv_decode_begin(self.index, self.prefixes, self.lens, self.state, self.active, self.logx)
+        ppv.ppv_decode_begin_empty(self.index, self.lens, self.state, self.active, self.logx)
         ppv.ppv_decode_loop(self.index, self.prefixes, self.lens, self.active, self.logits, self.uniforms, None, None,
                             self.logx, state=self.state)
 
@@ -129,8 +127,7 @@ class LoopBench:
         torch, ppv = self.torch, self.ppv
 
         def partial(n):
-            self.lens.zero_()
-            ppv.ppv_decode_begin(self.index, self.prefixes, self.lens, self.state, self.active, self.logx)
+            ppv.ppv_decode_begin_empty(self.index, self.lens, self.state, self.active, self.logx)
             for s in range(n):
                 ppv.ppv_decode_step(self.index, self.prefixes, self.lens, self.active, self.step_logits[s],
                                     self.step_uniforms[s], self.ids, self.lz, self.logx, state=self.state)
@@ -282,7 +279,7 @@ def main() -> int:
 
     # ---- dominant kernel (the fused decode step): algorithmic bytes per launch / average launch duration.
     # Average duration = GPU time of the timed region (HIP events on the launch stream) / launches in it;
-    # the region also holds one tiny fill and one ppv_decode_begin per loop (about 1 % of it).
+    # the region also holds one ppv_decode_begin_empty per loop (about 1 % of it).
     gpu_seconds = lb.gpu_seconds
     dur_ms = lb.launch_durations() if args.verbose else None
     seqs = lb.prefixes.cpu().numpy()
@@ -316,7 +313,7 @@ def main() -> int:
         "config": {"workload": f"{cfg.name}: |S|={index.n_distinct} lengths U[4,32] Zipf(1.1) V={V}; full decode loop, "
                                f"B={B} rows from the empty prefix, {L} fused step launches per loop, "
                                f"{prefix_steps} prefix-steps per loop",
-                   "launch": ("ppv_decode_begin + one ppv_decode_step per decode step through the C ABI, " +
+                   "launch": ("ppv_decode_begin_empty + one ppv_decode_step per decode step through the C ABI, " +
                               ("captured once in a HIP graph and replayed" if lb.graph is not None else "launched eagerly") +
                               ", no host sync inside a loop")},
         "roofline": roofline,

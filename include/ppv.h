@@ -196,6 +196,18 @@ ppv_status ppv_decode_begin(const ppv_index_t *index, const int32_t *prefixes, i
                             void *stream);
 
 /*
+ * ppv_decode_begin_empty -- the same initialisation step for the case Algorithm 1 itself starts from: every row's
+ * candidate is the empty sequence.  No prefix is read and nothing is located: all rows get the root's cursor, and
+ * the lengths are written as well, so that a decode loop needs no separate fill of `lens`.  The results are those of
+ * ppv_decode_begin with lens[b] = 0 for every row, bit for bit.
+ *   lens    int32[B], written: 0            state, active, logx   as in ppv_decode_begin (active[b] = 1: the empty
+ *           sequence is a prefix of every member and, members being non-empty, no member itself)
+ * Errors: PPV_EINVAL (null index/lens/state/active, B < 0), PPV_EDEVICE.
+ */
+ppv_status ppv_decode_begin_empty(const ppv_index_t *index, int32_t B, int32_t *lens, uint32_t *state, uint8_t *active,
+                                  float *logx, void *stream);
+
+/*
  * ppv_decode_step -- one iteration of the while loop of Algorithm 1's SampleCandidate for B rows,
  * fused: the valid set of the row's prefix, a token drawn from it, the token appended, the importance score
  * multiplied by the valid mass, and the test whether the extended row is in S.

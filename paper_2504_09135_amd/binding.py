@@ -27,7 +27,7 @@ SYMBOLS = ("ppv_status_string", "ppv_build_index", "ppv_index_info", "ppv_index_
            "ppv_index_save", "ppv_index_load",
            "ppv_next_token_mask", "constrained_sample", "ppv_decode_begin", "ppv_decode_step", "ppv_decode_loop", "ppv_topm_mask",
            "ppv_disc_select", "ppv_tuning_set", "ppv_tuning_get", "constrained_sample_noalloc",
-           "ppv_sample_next")
+           "ppv_sample_next", "ppv_decode_begin_empty")
 PPV_NOALLOC_MAX_ROWS = 512
 
 # tuning / test switches (ppv_tuning_set)
@@ -77,6 +77,8 @@ def load_library() -> C.CDLL:
     lib.ppv_sample_next.argtypes = [p, p, i32, p, i32, p, C.c_int, i64, p, p, p, C.c_float, p]
     lib.ppv_decode_begin.restype = C.c_int
     lib.ppv_decode_begin.argtypes = [p, p, i32, p, i32, p, p, p, p]
+    lib.ppv_decode_begin_empty.restype = C.c_int
+    lib.ppv_decode_begin_empty.argtypes = [p, i32, p, p, p, p, p]
     lib.ppv_decode_step.restype = C.c_int
     lib.ppv_decode_step.argtypes = [p, p, i32, p, p, p, p, C.c_int, i64, p, i32, p, p, p, C.c_float, p]
     lib.ppv_decode_loop.restype = C.c_int
@@ -255,6 +257,20 @@ def ppv_decode_begin(index: PPVIndex, prefixes: torch.Tensor, lens: torch.Tensor
         _dev(state, torch.int32, "state"), _dev(active, torch.uint8, "active"), _dev(logx, torch.float32, "logx"),
         _stream(stream))
     _check(st, "ppv_decode_begin")
+
+
+def ppv_decode_begin_empty(index: PPVIndex, lens: torch.Tensor, state: torch.Tensor, active: torch.Tensor,
+                           logx: Optional[torch.Tensor] = None, stream=None) -> None:
+    """SampleCandidate initialisation from the empty candidate for every row: lens int32 [B] (written 0),
+    state int32 [B, PPV_STATE_WORDS], active uint8 [B], logx f32 [B] (optional) are written."""
+    B = int(lens.shape[0])
+    if tuple(lens.shape) != (B,) or tuple(state.shape) != (B, PPV_STATE_WORDS) or tuple(active.shape) != (B,) \
+            or (logx is not None and tuple(logx.shape) != (B,)):
+        raise ValueError("ppv_decode_begin_empty: shape mismatch")
+    st = load_library().ppv_decode_begin_empty(
+        index.handle, B, _dev(lens, torch.int32, "lens"), _dev(state, torch.int32, "state"),
+        _dev(active, torch.uint8, "active"), _dev(logx, torch.float32, "logx"), _stream(stream))
+    _check(st, "ppv_decode_begin_empty")
 
 
 def ppv_decode_step(index: PPVIndex, prefixes: torch.Tensor, lens: torch.Tensor, active: torch.Tensor,

@@ -1186,6 +1186,26 @@ __global__ __launch_bounds__(MASK_THREADS) void decode_begin_kernel(IndexView ix
     }
 }
 
+// ppv_decode_begin_empty: every row starts from the empty candidate.  The cursor is the root's, the same for all
+// rows: no prefix to read, no walk; the lengths are written too, so that a decode loop needs no separate fill.
+__global__ __launch_bounds__(MASK_THREADS) void decode_begin_empty_kernel(IndexView ix, int B, int32_t *__restrict__ lens,
+                                                                          RowState *__restrict__ state,
+                                                                          uint8_t *__restrict__ active,
+                                                                          float *__restrict__ logx) {
+    const int b = blockIdx.x * MASK_THREADS + threadIdx.x;
+    if (b >= B) return;
+    RowState st;
+    st.node = 0u;
+    st.cb = ix.ent[0].child;
+    st.ce = ix.ent[1].child;
+    st.slot = st.ce - st.cb > ix.heavy_min ? heavy_slot_of(ix, 0u) : PPV_NO_SLOT;
+    st.tok0 = st.child0 = st.child1 = st.flags = 0u;   // nothing looked ahead
+    lens[b] = 0;
+    state[b] = st;
+    active[b] = 1;   // the empty sequence is a prefix of every member and is no member itself (members are not empty)
+    if (logx) logx[b] = 0.f;
+}
+
 // ppv_decode_step / ppv_decode_loop: take the children of the row's prefix as the valid set (list, or
 // the ready-made image of a heavy node), stream + sample, append, and report whether the extended
 // row is in S.  LOOP: the same for n_steps steps in one launch, one workgroup staying with its row;
@@ -1988,6 +2008,17 @@ extern "C" ppv_status ppv_decode_begin(const ppv_index_t *ix, const int32_t *pre
     hipLaunchKernelGGL(decode_begin_kernel, dim3((unsigned)((B + rows_per_wg - 1) / rows_per_wg)), dim3(MASK_THREADS), 0,
                        (hipStream_t)stream, ix->view, prefixes, prefix_stride, lens, B, (RowState *)state, active,
                        logx);
+    PPV_HIP_TRY(hipGetLastError());
+    return PPV_OK;
+}
+
+extern "C" ppv_status ppv_decode_begin_empty(const ppv_index_t *ix, int32_t B, int32_t *lens, uint32_t *state,
+                                             uint8_t *active, float *logx, void *stream) {
+    if (!ix || B < 0) return PPV_EINVAL;
+    if (B == 0) return PPV_OK;
+    if (!lens || !state || !active) return PPV_EINVAL;
+    hipLaunchKernelGGL(decode_begin_empty_kernel, dim3((unsigned)((B + MASK_THREADS - 1) / MASK_THREADS)), dim3(MASK_THREADS),
+                       0, (hipStream_t)stream, ix->view, B, lens, (RowState *)state, active, logx);
     PPV_HIP_TRY(hipGetLastError());
     return PPV_OK;
 }

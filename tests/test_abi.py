@@ -71,6 +71,9 @@ def test_argument_errors_without_device(lib):
     assert lib.ppv_sample_next(never, None, 0, None, 1, None, 0, 8, None, None, None, 1.0, None) == EINVAL
     assert lib.ppv_decode_step(None, None, 0, None, None, None, None, 0, 0, None, 0, None, None, None, 1.0, None) == EINVAL
     assert lib.ppv_decode_begin(None, None, 0, None, 0, None, None, None, None) == EINVAL
+    assert lib.ppv_decode_begin_empty(None, 1, None, None, None, None, None) == EINVAL
+    assert lib.ppv_decode_begin_empty(never, 0, None, None, None, None, None) == 0          # B = 0
+    assert lib.ppv_decode_begin_empty(never, 1, None, None, None, None, None) == EINVAL
     assert lib.ppv_disc_select(None, 2, 1, 5, None, None, 0, None, None, None, None) == EINVAL
     assert lib.ppv_disc_select(None, 1, 1, 5, None, None, 0, None, None, None, None) == EINVAL
     EIO = -5

@@ -321,6 +321,41 @@ def test_decode_begin_from_given_prefixes():
     assert (outs[0][3][want_active == 0] == -9).all() and (outs[0][3][want_active == 1] >= 0).all()
 
 
+@pytest.mark.parametrize("name", ["C1", "C2", "C3s", "C4s", "C5s"])
+def test_decode_begin_empty_is_decode_begin_on_empty_prefixes(name):
+    """ppv_decode_begin_empty writes, without reading any prefix, what ppv_decode_begin writes for lens = 0: the same
+    cursor words, flags and scores bit for bit, and the lengths; a decode step from either state gives the same rows."""
+    cfg, S, trie, index = setup_case(name)
+    B = 37
+    L = max(index.l_max, 1)
+    P = torch.full((B, L), W.PAD_TOKEN, dtype=torch.int32, device=DEV)
+    outs = []
+    logits = logits_to_dev(cfg, W.make_logits(cfg, batch=B, step=3))
+    un = to_dev(W.make_uniforms(cfg, batch=B, step=3))
+    for empty in (False, True):
+        lens = torch.full((B,), 0 if not empty else 5, dtype=torch.int32, device=DEV)
+        state = torch.full((B, ppv.PPV_STATE_WORDS), -7, dtype=torch.int32, device=DEV)
+        act = torch.full((B,), 3, dtype=torch.uint8, device=DEV)
+        logx = torch.full((B,), 4.0, dtype=torch.float32, device=DEV)
+        if empty:
+            ppv.ppv_decode_begin_empty(index, lens, state, act, logx)
+        else:
+            ppv.ppv_decode_begin(index, P, lens, state, act, logx)
+        torch.cuda.synchronize()
+        first = [t.clone() for t in (lens, state, act, logx)]
+        rows = P.clone()
+        ids = torch.full((B,), -9, dtype=torch.int32, device=DEV)
+        lz = torch.full((B,), 5.0, dtype=torch.float32, device=DEV)
+        ppv.ppv_decode_step(index, rows, lens, act, logits, un, ids, lz, logx, state=state)
+        torch.cuda.synchronize()
+        outs.append(first + [rows, lens, state, act, logx, ids, lz])
+    for a, b in zip(*outs):
+        assert torch.equal(a.view(torch.int32) if a.dtype == torch.float32 else a,
+                           b.view(torch.int32) if b.dtype == torch.float32 else b)
+    assert (outs[1][0] == 0).all() and (outs[1][2] == 1).all() and (outs[1][3] == 0).all()
+    assert (outs[1][9] >= 0).all()                            # every row drew a token from the root's valid set
+
+
 # ------------------------------------------------------------------------------------------ edge cases
 def brute_rows(S_lists, V, prefixes):
     from test_oracle_pins import brute
