@@ -217,7 +217,12 @@ def _logits_args(logits: torch.Tensor):
         dt = PPV_BF16
     else:
         raise TypeError(f"logits: float32 or bfloat16, got {logits.dtype}")
-    return C.c_void_p(logits.data_ptr()), dt, int(logits.stride(0)) if logits.shape[0] > 1 else int(logits.shape[1])
+    # a single row: torch's stride of a size-1 dimension carries no meaning unless it covers the row (a row cut out
+    # of a padded buffer keeps the buffer's stride, which is what says that the padding is there)
+    row_stride = int(logits.stride(0))
+    if logits.shape[0] <= 1 and row_stride < int(logits.shape[1]):
+        row_stride = int(logits.shape[1])
+    return C.c_void_p(logits.data_ptr()), dt, row_stride
 
 
 def constrained_sample(logits: torch.Tensor, mask: torch.Tensor, uniforms: torch.Tensor, ids: torch.Tensor,

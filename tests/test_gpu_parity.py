@@ -356,6 +356,52 @@ def test_decode_begin_empty_is_decode_begin_on_empty_prefixes(name):
     assert (outs[1][9] >= 0).all()                            # every row drew a token from the root's valid set
 
 
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_single_row_cut_out_of_a_padded_buffer(dtype):
+    """A batch of one row whose vocabulary is no multiple of a 16-byte group, given as a slice of a padded buffer: the
+    binding passes the buffer's row stride (which is what says the padding is there), not the vocabulary, and the
+    sampling calls take it; values behind the row's end (+inf here) are never read as logits."""
+    V = 2049
+    rng = np.random.default_rng(3)
+    seqs = [[int(v)] for v in rng.choice(V, size=300, replace=False)] + [[5, 7], [5, 2048]]
+    S = W.constraint_set_from_lists(seqs, V)
+    trie = oracle.Trie(S.tokens, S.offsets, V)
+    index = ppv.ppv_build_index(S.tokens, S.offsets, V)
+    per = 8 if dtype == "bf16" else 4
+    Vp = (V + per - 1) // per * per
+    lg = rng.normal(0, 2, size=(1, V)).astype(np.float32)
+    if dtype == "bf16":
+        bits = W.f32_to_bf16_bits(lg)
+        lf = W.bf16_bits_to_f32(bits)
+        pad = np.full((1, Vp), 0x7F80, np.uint16)
+        pad[:, :V] = bits
+        ld = to_dev(pad.view(np.int16)).view(torch.bfloat16)[:, :V]
+    else:
+        lf = lg
+        pad = np.full((1, Vp), np.inf, np.float32)
+        pad[:, :V] = lg
+        ld = to_dev(pad)[:, :V]
+    for prefix in ([], [5]):
+        P = np.full((1, 2), W.PAD_TOKEN, np.int32)
+        P[0, :len(prefix)] = prefix
+        Ln = np.array([len(prefix)], np.int32)
+        un = np.array([0.37], np.float32)
+        ref = trie.step(P, Ln, lf, un, want_mask=True)
+        dmask = torch.zeros((1, index.n_words), dtype=torch.int32, device=DEV)
+        ppv.ppv_next_token_mask(index, to_dev(P), to_dev(Ln), dmask)
+        ids = torch.full((1,), -9, dtype=torch.int32, device=DEV)
+        lz = torch.zeros(1, device=DEV)
+        la = torch.zeros(1, device=DEV)
+        ppv.constrained_sample(ld, dmask, to_dev(un), ids, lz, la)
+        ids1 = torch.full((1,), -9, dtype=torch.int32, device=DEV)
+        lz1 = torch.zeros(1, device=DEV)
+        ppv.ppv_sample_next(index, to_dev(P), to_dev(Ln), ld, to_dev(un), ids1, lz1)
+        torch.cuda.synchronize()
+        check_sample_rows(dtype, ref, lambda b: ref.mask[b], un, ids.cpu().numpy(), lz.cpu().numpy(), la.cpu().numpy())
+        check_sample_rows(dtype, ref, lambda b: ref.mask[b], un, ids1.cpu().numpy(), lz1.cpu().numpy())
+    index.free()
+
+
 # ------------------------------------------------------------------------------------------ edge cases
 def brute_rows(S_lists, V, prefixes):
     from test_oracle_pins import brute
