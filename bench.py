@@ -84,12 +84,13 @@ class LoopBench:
     def loop(self, events=None):
         """One whole decode loop: start from the empty prefix, then l_max fused step launches."""
         ppv = self.ppv
-        ppv.ppv_decode_begin_empty(self.index, self.lens, self.state, self.active, self.logx)   # a = [], x = 1
         for s in range(self.L):
             if events is not None:
                 events[s][0].record()
-            ppv.ppv_decode_step(self.index, self.prefixes, self.lens, self.active, self.step_logits[s],
-                                self.step_uniforms[s], self.ids, self.lz, self.logx, state=self.state)
+            # the first step starts every row from the empty candidate (a = [], x = 1) in the same launch
+            step = ppv.ppv_decode_first_step if s == 0 else ppv.ppv_decode_step
+            step(self.index, self.prefixes, self.lens, self.active, self.step_logits[s],
+                 self.step_uniforms[s], self.ids, self.lz, self.logx, state=self.state)
             if events is not None:
                 events[s][1].record()
 
@@ -127,10 +128,10 @@ class LoopBench:
         torch, ppv = self.torch, self.ppv
 
         def partial(n):
-            ppv.ppv_decode_begin_empty(self.index, self.lens, self.state, self.active, self.logx)
             for s in range(n):
-                ppv.ppv_decode_step(self.index, self.prefixes, self.lens, self.active, self.step_logits[s],
-                                    self.step_uniforms[s], self.ids, self.lz, self.logx, state=self.state)
+                step = ppv.ppv_decode_first_step if s == 0 else ppv.ppv_decode_step
+                step(self.index, self.prefixes, self.lens, self.active, self.step_logits[s],
+                     self.step_uniforms[s], self.ids, self.lz, self.logx, state=self.state)
 
         times = []
         for n in (3, 4):
@@ -279,7 +280,7 @@ def main() -> int:
 
     # ---- dominant kernel (the fused decode step): algorithmic bytes per launch / average launch duration.
     # Average duration = GPU time of the timed region (HIP events on the launch stream) / launches in it;
-    # the region also holds one ppv_decode_begin_empty per loop (about 1 % of it).
+    # (the first launch of a loop is ppv_decode_first_step, which also starts the rows)
     gpu_seconds = lb.gpu_seconds
     dur_ms = lb.launch_durations() if args.verbose else None
     seqs = lb.prefixes.cpu().numpy()
@@ -313,7 +314,7 @@ def main() -> int:
         "config": {"workload": f"{cfg.name}: |S|={index.n_distinct} lengths U[4,32] Zipf(1.1) V={V}; full decode loop, "
                                f"B={B} rows from the empty prefix, {L} fused step launches per loop, "
                                f"{prefix_steps} prefix-steps per loop",
-                   "launch": ("ppv_decode_begin_empty + one ppv_decode_step per decode step through the C ABI, " +
+                   "launch": ("one ppv_decode_step per decode step through the C ABI (the first one ppv_decode_first_step, which starts the rows from the empty prefix), " +
                               ("captured once in a HIP graph and replayed" if lb.graph is not None else "launched eagerly") +
                               ", no host sync inside a loop")},
         "roofline": roofline,

@@ -238,6 +238,17 @@ ppv_status ppv_decode_step(const ppv_index_t *index, int32_t *prefixes, int32_t 
                            float temperature, void *stream);
 
 /*
+ * ppv_decode_first_step -- ppv_decode_begin_empty and the first ppv_decode_step in one launch: the first iteration
+ * of Algorithm 1's SampleCandidate, which always starts from the empty candidate.  Same arguments as
+ * ppv_decode_step; what lens, active, state and logx hold on entry does not matter (every row's entry is overwritten;
+ * state must not be NULL).  The results are those of the two calls, bit for bit.
+ */
+ppv_status ppv_decode_first_step(const ppv_index_t *index, int32_t *prefixes, int32_t prefix_stride, int32_t *lens,
+                                 uint8_t *active, uint32_t *state, const void *logits, ppv_dtype dt,
+                                 int64_t row_stride, const float *uniforms, int32_t B, int32_t *ids,
+                                 float *logZ_valid, float *logx, float temperature, void *stream);
+
+/*
  * ppv_sample_next -- ppv_next_token_mask and constrained_sample in one call, for callers that want the token and
  * the valid mass but not the mask itself: the three steps of the loop body of Algorithm 1's SampleCandidate that
  * do not change the candidate (valid set by PPV with M = |V|, draw, valid mass).  The valid set is read off the

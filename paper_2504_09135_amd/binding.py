@@ -27,7 +27,7 @@ SYMBOLS = ("ppv_status_string", "ppv_build_index", "ppv_index_info", "ppv_index_
            "ppv_index_save", "ppv_index_load",
            "ppv_next_token_mask", "constrained_sample", "ppv_decode_begin", "ppv_decode_step", "ppv_decode_loop", "ppv_topm_mask",
            "ppv_disc_select", "ppv_tuning_set", "ppv_tuning_get", "constrained_sample_noalloc",
-           "ppv_sample_next", "ppv_decode_begin_empty")
+           "ppv_sample_next", "ppv_decode_begin_empty", "ppv_decode_first_step")
 PPV_NOALLOC_MAX_ROWS = 512
 
 # tuning / test switches (ppv_tuning_set)
@@ -81,6 +81,8 @@ def load_library() -> C.CDLL:
     lib.ppv_decode_begin_empty.argtypes = [p, i32, p, p, p, p, p]
     lib.ppv_decode_step.restype = C.c_int
     lib.ppv_decode_step.argtypes = [p, p, i32, p, p, p, p, C.c_int, i64, p, i32, p, p, p, C.c_float, p]
+    lib.ppv_decode_first_step.restype = C.c_int
+    lib.ppv_decode_first_step.argtypes = [p, p, i32, p, p, p, p, C.c_int, i64, p, i32, p, p, p, C.c_float, p]
     lib.ppv_decode_loop.restype = C.c_int
     lib.ppv_decode_loop.argtypes = [p, p, i32, p, p, p, p, C.c_int, i64, i64, p, i32, i32, p, p, p, C.c_float, p]
     lib.ppv_topm_mask.restype = C.c_int
@@ -281,7 +283,8 @@ def ppv_decode_begin_empty(index: PPVIndex, lens: torch.Tensor, state: torch.Ten
 def ppv_decode_step(index: PPVIndex, prefixes: torch.Tensor, lens: torch.Tensor, active: torch.Tensor,
                     logits: torch.Tensor, uniforms: torch.Tensor, ids: Optional[torch.Tensor] = None,
                     logZ_valid: Optional[torch.Tensor] = None, logx: Optional[torch.Tensor] = None,
-                    state: Optional[torch.Tensor] = None, stream=None, temperature: float = 1.0) -> None:
+                    state: Optional[torch.Tensor] = None, stream=None, temperature: float = 1.0,
+                    _first: bool = False) -> None:
     """One fused constrained decoding step, in place on prefixes / lens / active / logx (and on
     state int32 [B, PPV_STATE_WORDS] from ppv_decode_begin when given); P = softmax(logits / temperature)."""
     ptr, dt, row_stride = _logits_args(logits)
@@ -293,13 +296,23 @@ def ppv_decode_step(index: PPVIndex, prefixes: torch.Tensor, lens: torch.Tensor,
     for t, nm in ((ids, "ids"), (logZ_valid, "logZ_valid"), (logx, "logx")):
         if t is not None and tuple(t.shape) != (B,):
             raise ValueError(f"ppv_decode_step: {nm} must have shape [B]")
-    st = load_library().ppv_decode_step(
+    fn = load_library().ppv_decode_first_step if _first else load_library().ppv_decode_step
+    st = fn(
         index.handle, _dev(prefixes, torch.int32, "prefixes"), stride, _dev(lens, torch.int32, "lens"),
         _dev(active, torch.uint8, "active"), _dev(state, torch.int32, "state"), ptr, dt, row_stride,
         _dev(uniforms, torch.float32, "uniforms"), B, _dev(ids, torch.int32, "ids"),
         _dev(logZ_valid, torch.float32, "logZ_valid"), _dev(logx, torch.float32, "logx"), float(temperature),
         _stream(stream))
-    _check(st, "ppv_decode_step")
+    _check(st, "ppv_decode_first_step" if _first else "ppv_decode_step")
+
+
+def ppv_decode_first_step(index: PPVIndex, prefixes: torch.Tensor, lens: torch.Tensor, active: torch.Tensor,
+                          logits: torch.Tensor, uniforms: torch.Tensor, ids: Optional[torch.Tensor] = None,
+                          logZ_valid: Optional[torch.Tensor] = None, logx: Optional[torch.Tensor] = None,
+                          state: Optional[torch.Tensor] = None, stream=None, temperature: float = 1.0) -> None:
+    """ppv_decode_begin_empty and the first ppv_decode_step in one launch (state is required)."""
+    ppv_decode_step(index, prefixes, lens, active, logits, uniforms, ids, logZ_valid, logx, state, stream, temperature,
+                    _first=True)
 
 
 def ppv_decode_loop(index: PPVIndex, prefixes: torch.Tensor, lens: torch.Tensor, active: torch.Tensor,

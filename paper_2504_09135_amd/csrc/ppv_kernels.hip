@@ -1218,7 +1218,11 @@ __global__ __launch_bounds__(LOOP ? (REG ? CHAIN_WAVES : LOOP_WAVES) * WAVE : MA
     uint8_t *__restrict__ active, RowState *__restrict__ state, const T *__restrict__ logits, int64_t row_stride,
     int64_t step_stride, const float *__restrict__ uniforms, int n_steps, int B, int32_t *__restrict__ ids,
     float *__restrict__ logZ_valid, float *__restrict__ logx, Temper tp, int split_shift, SplitScratch *scratch,
-    int advance) {
+    int flags) {
+    // flags bit 1 (ppv_decode_first_step): every row starts from the empty candidate here and now -- no flags, length
+    // or cursor are read, the root's cursor is taken instead, and all of them are written at the end.
+    const int advance = flags & 1;
+    const bool fresh = (flags & 2) != 0;
     // advance == 0 (ppv_sample_next): every row takes part, a token is drawn, and nothing of the caller's rows is
     // changed (no append, no cursor, no flags)
     using G = TileGeom<T>;
@@ -1242,7 +1246,7 @@ __global__ __launch_bounds__(LOOP ? (REG ? CHAIN_WAVES : LOOP_WAVES) * WAVE : MA
     // batches (where the registers this costs would mean fewer rows per compute unit) use the list in LDS
     static_assert(!REG || (!SPLIT && !PIPE), "the register list is for short turns in unsplit rows");
     // the independent per-row loads go out together
-    const uint8_t on = active ? active[b] : (uint8_t)1;
+    uint8_t on = active ? active[b] : (uint8_t)1;
     int t = lens[b];
     RowState st;
     if (state) st = state[b];
@@ -1250,7 +1254,18 @@ __global__ __launch_bounds__(LOOP ? (REG ? CHAIN_WAVES : LOOP_WAVES) * WAVE : MA
     float u = uniforms[b];
     // the running score is read now, not when it is updated at the very end (a load there would stand between the
     // sample and the kernel's last store); unconditional, from an address that always exists
-    const float logx_in = (logx ? logx : uniforms)[b];
+    float logx_in = (logx ? logx : uniforms)[b];
+    if (fresh) {   // (uniform) what was loaded is set aside -- the loads themselves stay unconditional, so that the
+                   // waits after them stay exact -- for the root's cursor, as ppv_decode_begin_empty writes it
+        on = 1;
+        t = 0;
+        logx_in = 0.f;
+        st.node = 0u;
+        st.cb = ix.ent[0].child;
+        st.ce = ix.ent[1].child;
+        st.slot = st.ce - st.cb > ix.heavy_min ? heavy_slot_of(ix, 0u) : PPV_NO_SLOT;
+        st.tok0 = st.child0 = st.child1 = st.flags = 0u;
+    }
     if (!on) return;  // uniform for the workgroup
     const int V = ix.vocab;
     const T *row = logits + (size_t)b * (size_t)row_stride;
@@ -1386,10 +1401,15 @@ __global__ __launch_bounds__(LOOP ? (REG ? CHAIN_WAVES : LOOP_WAVES) * WAVE : MA
                     lens[b] = t + 1;
                     state[b] = nx;
                     if (tokw & PPV_NODE_TERMINAL) active[b] = 0;   // the extended row is itself a member
+                    else if (fresh) active[b] = 1;
                 }
             } else if (advance) {   // the row stops outside S: no valid token of positive weight, or no room
                 if (logx) logx[b] = -INFINITY;
                 active[b] = 0;
+                if (fresh) {
+                    lens[b] = 0;
+                    state[b] = st;
+                }
             }
         }
         if (pk.Mv == -INFINITY) {   // (uniform) no listed token has positive weight
@@ -1723,9 +1743,13 @@ __global__ __launch_bounds__(LOOP ? (REG ? CHAIN_WAVES : LOOP_WAVES) * WAVE : MA
                 if (id >= 0) {
                     lens[b] = t + 1;
                     if (state) state[b] = nx;
+                } else if (fresh) {
+                    lens[b] = 0;
+                    if (state) state[b] = st;
                 }
                 if (logx) logx[b] = logx_in + lx;   // (-inf for a row that drew nothing)
                 if (done) active[b] = 0;
+                else if (fresh) active[b] = 1;
             }
         }
         if (!LOOP) return;
@@ -1874,11 +1898,11 @@ template <typename T>
 void launch_decode_kernel(bool loop, bool pipe, dim3 grid, dim3 block, hipStream_t hs, const IndexView &view,
                           int32_t *prefixes, int32_t stride, int32_t *lens, uint8_t *active, RowState *rs, const T *lg,
                           int64_t row_stride, int64_t step_stride, const float *uniforms, int n_steps, int B, int32_t *ids,
-                          float *logZ_valid, float *logx, Temper tp, int split_shift, SplitScratch *scratch, int advance) {
+                          float *logZ_valid, float *logx, Temper tp, int split_shift, SplitScratch *scratch, int flags) {
 #define PPV_LAUNCH_DECODE(LOOP, PIPE, SPLIT, REG)                                                                     \
     hipLaunchKernelGGL((decode_kernel<T, LOOP, PIPE, SPLIT, REG>), grid, block, 0, hs, view, prefixes, stride, lens,   \
                        active, rs, lg, row_stride, step_stride, uniforms, n_steps, B, ids, logZ_valid, logx, tp,        \
-                       split_shift, scratch, advance)
+                       split_shift, scratch, flags)
     if (split_shift && !loop) PPV_LAUNCH_DECODE(false, false, true, false);   // (a split row's turns are short)
     else if (loop && pipe) PPV_LAUNCH_DECODE(true, true, false, false);
     else if (loop && rs && B <= REG_MAX_ROWS) PPV_LAUNCH_DECODE(true, false, false, true);
@@ -2027,7 +2051,7 @@ namespace {
 ppv_status launch_decode(const ppv_index_t *ix, int32_t *prefixes, int32_t prefix_stride, int32_t *lens, uint8_t *active,
                          uint32_t *state, const void *logits, ppv_dtype dt, int64_t row_stride, int64_t step_stride,
                          const float *uniforms, int32_t n_steps, int32_t B, int32_t *ids, float *logZ_valid, float *logx,
-                         float temperature, void *stream, bool loop, bool advance = true) {
+                         float temperature, void *stream, bool loop, bool advance = true, bool fresh = false) {
     Temper tp;
     if (!ix || B < 0 || prefix_stride < 0 || n_steps < 0 || !temper_for(temperature, &tp)) return PPV_EINVAL;
     if (B == 0 || n_steps == 0) return PPV_OK;
@@ -2040,7 +2064,7 @@ ppv_status launch_decode(const ppv_index_t *ix, int32_t *prefixes, int32_t prefi
     }
     hipStream_t hs = (hipStream_t)stream;
     SplitScratch *scratch = nullptr;
-    const int parts = loop ? 1 : parts_for(ix->view.vocab, dt, B, hs, &scratch);
+    const int parts = (loop || fresh) ? 1 : parts_for(ix->view.vocab, dt, B, hs, &scratch);
     int nw = waves_for(ix->view.vocab, dt, B, parts, !loop && state != nullptr);
     if (loop && nw > LOOP_WAVES) nw = LOOP_WAVES;
     // The loop kernel in a large batch: a workgroup stays with its row for every step, so what hides one row's
@@ -2062,11 +2086,11 @@ ppv_status launch_decode(const ppv_index_t *ix, int32_t *prefixes, int32_t prefi
     if (dt == PPV_F32)
         launch_decode_kernel<float>(loop, pipe, grid, block, hs, ix->view, prefixes, prefix_stride, lens, active, rs,
                                     (const float *)logits, row_stride, step_stride, uniforms, n_steps, B, ids, logZ_valid,
-                                    logx, tp, shift_of(parts), scratch, advance ? 1 : 0);
+                                    logx, tp, shift_of(parts), scratch, (advance ? 1 : 0) | (fresh ? 2 : 0));
     else
         launch_decode_kernel<uint16_t>(loop, pipe, grid, block, hs, ix->view, prefixes, prefix_stride, lens, active, rs,
                                        (const uint16_t *)logits, row_stride, step_stride, uniforms, n_steps, B, ids,
-                                       logZ_valid, logx, tp, shift_of(parts), scratch, advance ? 1 : 0);
+                                       logZ_valid, logx, tp, shift_of(parts), scratch, (advance ? 1 : 0) | (fresh ? 2 : 0));
     PPV_HIP_TRY(hipGetLastError());
     return PPV_OK;
 }
@@ -2078,6 +2102,15 @@ extern "C" ppv_status ppv_decode_step(const ppv_index_t *ix, int32_t *prefixes, 
                                       float *logZ_valid, float *logx, float temperature, void *stream) {
     return launch_decode(ix, prefixes, prefix_stride, lens, active, state, logits, dt, row_stride, 0, uniforms, 1, B, ids,
                          logZ_valid, logx, temperature, stream, false);
+}
+
+extern "C" ppv_status ppv_decode_first_step(const ppv_index_t *ix, int32_t *prefixes, int32_t prefix_stride, int32_t *lens,
+                                            uint8_t *active, uint32_t *state, const void *logits, ppv_dtype dt,
+                                            int64_t row_stride, const float *uniforms, int32_t B, int32_t *ids,
+                                            float *logZ_valid, float *logx, float temperature, void *stream) {
+    if (!state) return PPV_EINVAL;
+    return launch_decode(ix, prefixes, prefix_stride, lens, active, state, logits, dt, row_stride, 0, uniforms, 1, B, ids,
+                         logZ_valid, logx, temperature, stream, false, true, true);
 }
 
 extern "C" ppv_status ppv_decode_loop(const ppv_index_t *ix, int32_t *prefixes, int32_t prefix_stride, int32_t *lens,

@@ -72,6 +72,8 @@ def test_argument_errors_without_device(lib):
     assert lib.ppv_decode_step(None, None, 0, None, None, None, None, 0, 0, None, 0, None, None, None, 1.0, None) == EINVAL
     assert lib.ppv_decode_begin(None, None, 0, None, 0, None, None, None, None) == EINVAL
     assert lib.ppv_decode_begin_empty(None, 1, None, None, None, None, None) == EINVAL
+    assert lib.ppv_decode_first_step(None, None, 0, None, None, None, None, 0, 0, None, 0, None, None, None, 1.0, None) == EINVAL
+    assert lib.ppv_decode_first_step(never, never, 4, never, never, None, never, 0, 8, never, 1, None, None, None, 1.0, None) == EINVAL   # no state
     assert lib.ppv_decode_begin_empty(never, 0, None, None, None, None, None) == 0          # B = 0
     assert lib.ppv_decode_begin_empty(never, 1, None, None, None, None, None) == EINVAL
     assert lib.ppv_disc_select(None, 2, 1, 5, None, None, 0, None, None, None, None) == EINVAL

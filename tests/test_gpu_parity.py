@@ -356,6 +356,44 @@ def test_decode_begin_empty_is_decode_begin_on_empty_prefixes(name):
     assert (outs[1][9] >= 0).all()                            # every row drew a token from the root's valid set
 
 
+@pytest.mark.parametrize("name", ["C1", "C2", "C3s", "C4s", "C5s"])
+@pytest.mark.parametrize("temperature", [1.0, 1.7])
+def test_decode_first_step_is_begin_empty_plus_step(name, temperature):
+    """ppv_decode_first_step = ppv_decode_begin_empty + ppv_decode_step in one launch: every output bit for bit, on rows
+    whose buffers hold junk before the call (nothing of them may be read); one row is given logits of -inf only, so
+    that it stops outside S in its first step."""
+    cfg, S, trie, index = setup_case(name)
+    B = 41
+    L = max(index.l_max, 1)
+    lg = W.make_logits(cfg, batch=B, step=5)
+    if cfg.dtype == "bf16":
+        lg[7, :] = 0xFF80
+    else:
+        lg[7, :] = -np.inf
+    logits = logits_to_dev(cfg, lg)
+    un = to_dev(W.make_uniforms(cfg, batch=B, step=5))
+    outs = []
+    for fused in (False, True):
+        P = torch.full((B, L), W.PAD_TOKEN, dtype=torch.int32, device=DEV)
+        lens = torch.full((B,), 9, dtype=torch.int32, device=DEV)
+        state = torch.full((B, ppv.PPV_STATE_WORDS), -7, dtype=torch.int32, device=DEV)
+        act = torch.full((B,), 0 if fused else 3, dtype=torch.uint8, device=DEV)
+        logx = torch.full((B,), 4.0, dtype=torch.float32, device=DEV)
+        ids = torch.full((B,), -9, dtype=torch.int32, device=DEV)
+        lz = torch.full((B,), 5.0, dtype=torch.float32, device=DEV)
+        if fused:
+            ppv.ppv_decode_first_step(index, P, lens, act, logits, un, ids, lz, logx, state=state, temperature=temperature)
+        else:
+            ppv.ppv_decode_begin_empty(index, lens, state, act, logx)
+            ppv.ppv_decode_step(index, P, lens, act, logits, un, ids, lz, logx, state=state, temperature=temperature)
+        torch.cuda.synchronize()
+        outs.append([P, lens, state, act, logx.view(torch.int32), ids, lz.view(torch.int32)])
+    for a, b in zip(*outs):
+        assert torch.equal(a, b)
+    assert outs[1][5][7].item() == -1 and outs[1][3][7].item() == 0 and outs[1][1][7].item() == 0
+    assert (outs[1][5][:7] >= 0).all()
+
+
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 def test_single_row_cut_out_of_a_padded_buffer(dtype):
     """A batch of one row whose vocabulary is no multiple of a 16-byte group, given as a slice of a padded buffer: the
