@@ -5,13 +5,21 @@
 //   select   P = softmax(logits) is increasing in the logit, so the top M are found on the logits'
 //            bit patterns, through an order-preserving 32-bit key per token.  M is small against
 //            |V|, so almost every token can be turned away with one comparison:
-//              A. one pass over the row takes the maximum of every 16-byte group of tokens and
-//                 histograms the groups' maxima by their leading 11 key bits; the bin that holds
-//                 the M-th largest group maximum gives a bound L that at least M tokens reach;
-//              B. a second pass (the row is in cache now) lists the tokens that are not below L,
-//                 in token order, in LDS: usually 1.1 to 1.5 M of them;
-//              C. a radix select over that short list (11 + 10 + 11 key bits for fp32, 11 + 5 for
-//                 bf16) finds the key T of the M-th largest token; the list is then cut to the
+//              A. the maximum of every 16-byte group of tokens is histogrammed by its leading 11 key
+//                 bits; the bin that holds the M-th largest group maximum gives a bound L that at
+//                 least M tokens reach.  A wavefront holds eight chunks of the row (8 KB of bf16) in
+//                 registers; when its share of the row is longer, A looks only at those eight --
+//                 the M-th largest of a part of the row is still a lower bound of the row's --
+//                 provided the list has room for what the looser bound lets through;
+//              B. the tokens that are not below L are listed in LDS in token order, each with its
+//                 logit: usually 1.1 to 1.5 M of them, from registers when A saw the whole row,
+//                 else about as many times more as the share is longer than eight chunks, from the
+//                 one pass over the row (the next eight chunks are asked for before these eight are
+//                 looked at).  bf16 rows are compared two tokens at a time on 16-bit keys, and a
+//                 chunk in which no lane has a token for the list costs a ballot;
+//              C. a radix select over that short list (the keys' upper halves, counted from L, in one
+//                 histogram of 256 bins; two more digits of 8 bits for fp32) finds the key T of the
+//                 M-th largest token; the list is then cut to the
 //                 tokens above T and the first few equal to T, in increasing token id, so the set
 //                 is unique.
 //            If the list does not fit (a flat row with thousands of equal logits at the cut, or a
@@ -39,10 +47,12 @@ namespace {
 constexpr int TOPM_BITS = 11;             // leading key bits of the first digit
 constexpr int TOPM_BINS = 1 << TOPM_BITS;   // the histogram shares its LDS with the mask row
 constexpr int TOPM_SHIFT = 32 - TOPM_BITS;
+constexpr int TOPM_CBINS = 256;   // bins of the histogram over the listed tokens' keys, counted from the bound (the last one: all above)
 constexpr int TOPM_WAVES = 16;
 constexpr int TOPM_LIST_BIG = 4096, TOPM_LIST_SMALL = 1024;   // capacity of the candidate list (tokens not below the bound),
                                                               // split evenly over the wavefronts; the small one serves M <= 128 at V <= 65,536
 constexpr int TOPM_SLOTS = 16;    // list entries per thread at most: the list path needs at least LIST / 16 threads
+constexpr int TOPM_HELD = 8;      // chunks of the row a wavefront holds in registers at a time (128 bytes per lane)
 
 // Bit pattern -> key with the same order as the float value (-0 and +0 share a key).
 __device__ inline uint32_t order_key(uint32_t bits) {
@@ -93,33 +103,26 @@ __device__ inline int load_keys(const T *__restrict__ row, int V, int c, int lan
     return n;
 }
 
-// The raw 16 bytes of this lane's tokens of chunk c; tokens at or beyond V read as -inf (memory there is
-// never touched).
-template <typename T> __device__ inline uint4 load_raw(const T *__restrict__ row, int V, int c, int lane) {
+// This lane's 16 bytes of chunk c, from an address that is always inside the row: a chunk beyond the last one
+// reads the last one again, a lane beyond the row's end reads the row's first bytes (the caller discards both,
+// and the tokens of the row's last group that lie beyond its end).  No condition stands between the caller and
+// the load, so loads for the next batch can be in flight while this batch is worked on.  STREAM: the bytes are
+// not read again (they need not stay in cache).
+template <typename T, bool STREAM = true>
+__device__ inline uint4 load_raw_clamped(const T *__restrict__ row, int V, int nc, int c, int lane) {
     constexpr int EPL = KeyChunk<T>::EPL;
-    const int g = (c * WAVE + lane) * EPL;
-    if (g + EPL <= V) return *(const uint4 *)(row + g);
-    const uint32_t pad = sizeof(T) == 4 ? 0xFF800000u : 0xFF80FF80u;
-    uint32_t w[4] = {pad, pad, pad, pad};
-    for (int j = 0; j < EPL; j++)
-        if (g + j < V) {
-            if (sizeof(T) == 4) {
-                w[j % 4] = ((const uint32_t *)row)[g + j];
-            } else {
-                const uint32_t h = ((const uint16_t *)row)[g + j];
-                w[(j >> 1) % 4] = (j & 1) ? ((w[(j >> 1) % 4] & 0x0000FFFFu) | (h << 16))
-                                          : ((w[(j >> 1) % 4] & 0xFFFF0000u) | h);
-            }
-        }
-    return make_uint4(w[0], w[1], w[2], w[3]);
+    const int cc = c < nc ? c : nc - 1;
+    const int g = (cc * WAVE + lane) * EPL;
+    typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+    const u32x4 *at = (const u32x4 *)(row + (g < V ? g : 0));
+    const u32x4 v = STREAM ? __builtin_nontemporal_load(at) : *at;
+    return make_uint4(v.x, v.y, v.z, v.w);
 }
-// four chunks at once (c .. c+3, those below c1): four loads in flight per lane
-template <typename T>
-__device__ inline void load_chunks(const T *__restrict__ row, int V, int c, int c1, int lane, uint4 (&r)[4]) {
-    const uint32_t pad = sizeof(T) == 4 ? 0xFF800000u : 0xFF80FF80u;
+// four chunks at once (c .. c+3): four loads in flight per lane
+template <typename T, bool STREAM>
+__device__ inline void load_chunks(const T *__restrict__ row, int V, int nc, int c, int lane, uint4 *r) {
 #pragma unroll
-    for (int u = 0; u < 4; u++)
-        r[u] = (c + u < c1) ? load_raw<T>(row, V, c + u, lane) : make_uint4(pad, pad, pad, pad);
+    for (int u = 0; u < 4; u++) r[u] = load_raw_clamped<T, STREAM>(row, V, nc, c + u, lane);
 }
 // how many of this lane's tokens of chunk c lie inside the row
 template <typename T> __device__ inline int n_inside(int V, int c, int lane) {
@@ -217,6 +220,7 @@ template <typename T> __device__ inline uint32_t full_key(uint32_t hi_part) {
 struct TopmLds {
     uint32_t *hist;       // [TOPM_BINS]
     uint32_t *list_tok;   // [LIST]
+    uint32_t *list_key;   // [LIST] the listed tokens' logits (bit patterns, bf16 in the upper half)
     uint32_t *sel;        // [PPV_TOPM_MAX]
     uint32_t *seg_a, *seg_b, *wave_tot;   // [TOPM_WAVES] each
     uint32_t *bc;         // [8]
@@ -313,173 +317,6 @@ __device__ inline void select_streaming(const T *__restrict__ row, int V, int c0
     __syncthreads();
 }
 
-// Bound, short list, radix select over the list.  Needs nthreads >= LIST / TOPM_SLOTS.  Returns false
-// (for every thread alike) when the list did not fit; sel is then untouched.
-template <typename T, int LIST>
-__device__ inline bool select_listed(const T *__restrict__ row, int V, int c0, int c1, int m, const TopmLds &s, int lane,
-                                     int wave, int nthreads, uint4 (&r)[4]) {
-    constexpr int EPL = KeyChunk<T>::EPL;
-    const int tid = threadIdx.x, nw = nthreads / WAVE;
-    // ---- A. maxima of the 16-byte groups, histogram of their leading key bits.  The row is taken four chunks
-    // at a time (four loads in flight per lane); a share of at most four chunks stays in registers for B.
-    for (int i = tid; i < TOPM_BINS; i += nthreads) s.hist[i] = 0u;
-    if (tid == 0) s.bc[6] = 0u;
-    auto load_batch = [&](int c) { load_chunks<T>(row, V, c, c1, lane, r); };   // r arrives holding the batch at c0
-    __syncthreads();
-    for (int c = c0; c < c1; c += 4) {
-        if (c != c0) load_batch(c);
-#pragma unroll
-        for (int u = 0; u < 4; u++) {
-            float x[EPL];
-            unpack_vals<T>(r[u], x);
-            float gm = x[0];
-#pragma unroll
-            for (int j = 1; j < EPL; j++) gm = fmaxf(gm, x[j]);
-            if (c + u < c1 && n_inside<T>(V, c + u, lane) > 0)
-                atomicAdd(&s.hist[order_key(__float_as_uint(gm)) >> TOPM_SHIFT], 1u);
-        }
-    }
-    const bool kept = c1 - c0 <= 4;   // r still holds the whole share
-    __syncthreads();
-    pick_digit(s.hist, TOPM_BINS, (uint32_t)m, s.wave_tot, s.bc, nthreads);
-    // At least m groups have their maximum in this bin or above, so at least m tokens are not below the bin's
-    // lower edge.  With fewer than m groups in the row the bin is 0 and its edge is a NaN: nothing is below it.
-    const float L = __uint_as_float(key_to_bits(s.bc[4] << TOPM_SHIFT));
-    for (int i = tid; i < TOPM_BINS; i += nthreads) s.hist[i] = 0u;   // for C; the barrier after B orders it
-    // ---- B. the tokens that are not below L, in token order, each wavefront into its own part of the list
-    const uint32_t R = (uint32_t)(LIST / nw);
-    const uint32_t base = (uint32_t)wave * R;
-    uint32_t cnt = 0;   // wave-uniform
-    for (int c = c0; c < c1; c += 4) {
-        if (!kept) load_batch(c);
-#pragma unroll
-        for (int u = 0; u < 4; u++) {
-            if (c + u >= c1) continue;
-            float x[EPL];
-            unpack_vals<T>(r[u], x);
-            const int n = n_inside<T>(V, c + u, lane);
-            uint32_t pm = 0;
-#pragma unroll
-            for (int j = 0; j < EPL; j++)
-                if (j < n && !(x[j] < L)) pm |= 1u << j;
-            const uint32_t pc = (uint32_t)__popc(pm);
-            const uint32_t incl = wave_incl_scan(pc);
-            const uint32_t tot = last_lane(incl);
-            if (tot == 0u) continue;
-            uint32_t at = cnt + incl - pc;
-            const uint32_t first_tok = (uint32_t)(((c + u) * WAVE + lane) * EPL);
-            while (pm) {
-                const int j = __ffs((int)pm) - 1;
-                if (at < R) s.list_tok[base + at] = first_tok + (uint32_t)j;
-                at++;
-                pm &= pm - 1u;
-            }
-            cnt += tot;
-        }
-    }
-    if (lane == 0) {
-        s.seg_a[wave] = cnt < R ? cnt : R;
-        if (cnt > R) atomicOr(&s.bc[6], 1u);
-    }
-    __syncthreads();
-    if (s.bc[6] != 0u) return false;
-
-    // ---- C. the key T of the m-th largest token, from the list.  Thread t holds the entries t*S .. t*S+S-1 of
-    // the list, which lie in its own wavefront's part (S = R / 64); their keys stay in registers.
-    const int S = LIST / nthreads;
-    const uint32_t mine = s.seg_a[wave];
-    uint32_t kk[TOPM_SLOTS], tk[TOPM_SLOTS];
-    uint32_t vm = 0;
-#pragma unroll
-    for (int q = 0; q < TOPM_SLOTS; q++) {   // the gathers go out together: no condition on the way to a load
-        const uint32_t o = (uint32_t)(lane * S + q);
-        const bool have = q < S && o < mine;
-        tk[q] = have ? s.list_tok[base + o] : 0u;
-        kk[q] = q < S ? KeyChunk<T>::bits_of(row, (int)tk[q]) : 0u;
-        if (have) vm |= 1u << q;
-    }
-    // Every listed token's key is at or above the edge key (NaNs that slipped through the float comparison
-    // aside: they are dropped here), so the upper 16 key bits, counted from the edge, are small numbers: one
-    // histogram over them settles the upper half of T.  A row whose tail reaches further than the histogram
-    // is long (thousands of bf16 values above the m-th largest) goes to the whole-row select.
-    const uint32_t edge16 = s.bc[4] << (16 - TOPM_BITS);
-#pragma unroll
-    for (int q = 0; q < TOPM_SLOTS; q++) {   // (the histogram was cleared before B)
-        kk[q] = order_key(kk[q]);
-        if (((vm >> q) & 1u) && (kk[q] >> 16) < edge16) vm &= ~(1u << q);
-        if ((vm >> q) & 1u) {
-            uint32_t rel = (kk[q] >> 16) - edge16;
-            rel = rel < (uint32_t)(TOPM_BINS - 1) ? rel : (uint32_t)(TOPM_BINS - 1);
-            atomicAdd(&s.hist[rel], 1u);
-        }
-    }
-    __syncthreads();
-    pick_digit(s.hist, TOPM_BINS, (uint32_t)m, s.wave_tot, s.bc, nthreads);
-    if (s.bc[4] == (uint32_t)(TOPM_BINS - 1)) return false;   // T lies in the overflow bin
-    uint32_t hi_part = edge16 + s.bc[4], need = s.bc[5];
-    if (sizeof(T) == 4) {   // fp32: the lower half of T, eight bits at a time
-        for (int shift = 8; shift >= 0; shift -= 8) {
-            __syncthreads();
-            for (int i = tid; i < 256; i += nthreads) s.hist[i] = 0u;
-            __syncthreads();
-#pragma unroll
-            for (int q = 0; q < TOPM_SLOTS; q++)
-                if (((vm >> q) & 1u) && (kk[q] >> (shift + 8)) == hi_part)
-                    atomicAdd(&s.hist[(kk[q] >> shift) & 255u], 1u);
-            __syncthreads();
-            pick_digit(s.hist, 256, need, s.wave_tot, s.bc, nthreads);
-            hi_part = (hi_part << 8) | s.bc[4];
-            need = s.bc[5];
-        }
-    }
-    const uint32_t T_key = full_key<T>(hi_part);
-    const uint32_t take_eq = need;
-    // positions: list order is token order, and threads hold consecutive entries
-    uint32_t g = 0, e = 0;
-#pragma unroll
-    for (int q = 0; q < TOPM_SLOTS; q++) {
-        g += (((vm >> q) & 1u) && kk[q] > T_key) ? 1u : 0u;
-        e += (((vm >> q) & 1u) && kk[q] == T_key) ? 1u : 0u;
-    }
-    const uint32_t packed = g | (e << 16);   // both counts stay below 2^16 (the list has at most 4096 entries)
-    const uint32_t before = block_incl_scan(packed, s.wave_tot, nw) - packed;
-    uint32_t gt_before = before & 0xFFFFu, eq_before = before >> 16;
-#pragma unroll
-    for (int q = 0; q < TOPM_SLOTS; q++) {
-        if (!((vm >> q) & 1u)) continue;
-        if (kk[q] > T_key) {
-            const uint32_t pos = gt_before + (eq_before < take_eq ? eq_before : take_eq);
-            if (pos < (uint32_t)m) s.sel[pos] = tk[q];
-            gt_before++;
-        } else if (kk[q] == T_key) {
-            if (eq_before < take_eq) {
-                const uint32_t pos = gt_before + eq_before;
-                if (pos < (uint32_t)m) s.sel[pos] = tk[q];
-            }
-            eq_before++;
-        }
-    }
-    __syncthreads();
-    return true;
-}
-
-
-// ---- mask-only calls, prefixes with at most TOPM_COUNT_MAX children ----
-constexpr int TOPM_COUNT_MAX = 8;
-
-// This lane's 16 bytes of chunk c, from an address that is always inside the row: a chunk beyond the last one
-// reads the last one again, a lane beyond the row's end reads the row's first bytes (the caller discards both).
-// No condition stands between the caller and the load, so loads for the next batch can be in flight while this
-// batch is counted.
-template <typename T> __device__ inline uint4 load_raw_clamped(const T *__restrict__ row, int V, int nc, int c, int lane) {
-    constexpr int EPL = KeyChunk<T>::EPL;
-    const int cc = c < nc ? c : nc - 1;
-    const int g = (cc * WAVE + lane) * EPL;
-    typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-    const u32x4 v = __builtin_nontemporal_load((const u32x4 *)(row + (g < V ? g : 0)));
-    return make_uint4(v.x, v.y, v.z, v.w);
-}
-
 // Two bf16 values in one word -> their two 16-bit keys, ordered as the values are (-0 just below +0: the
 // thresholds below allow for it).
 typedef short topm_s2 __attribute__((ext_vector_type(2)));
@@ -497,6 +334,233 @@ __device__ inline uint32_t pk_above(uint32_t keys, uint32_t thresholds) {
     asm("v_pk_min_u16 %0, %1, %2" : "=v"(r) : "v"(d), "v"(ones));
     return r;
 }
+// Bound, short list, radix select over the list.  Needs nthreads >= LIST / TOPM_SLOTS and nthreads <= LIST.
+// Returns false (for every thread alike) when the list did not fit; sel is then untouched.  r arrives holding
+// the wavefront's first TOPM_HELD chunks.  The row is read from memory once when a wavefront's share is no longer
+// than that, and also when the share is longer but the list has room for a looser bound: the bound is then taken
+// from the chunks in r alone (at least m of THEIR groups reach it, so at least m tokens of the row do), and the
+// list grows by about the factor by which the share is longer.
+template <typename T, int LIST>
+__device__ inline bool select_listed(const T *__restrict__ row, int V, int c0, int c1, int m, const TopmLds &s, int lane,
+                                     int wave, int nthreads, uint4 (&r)[TOPM_HELD]) {
+    constexpr int EPL = KeyChunk<T>::EPL;
+    const int tid = threadIdx.x, nw = nthreads / WAVE;
+    // ---- A. maxima of the 16-byte groups, histogram of their leading key bits.  The row is taken TOPM_HELD
+    // chunks at a time (as many loads in flight per lane); first_only: only the chunks that r arrived with.
+    for (int i = tid; i < TOPM_BINS; i += nthreads) s.hist[i] = 0u;
+    if (tid == 0) s.bc[6] = 0u;
+    const int nc = (V + WAVE * EPL - 1) / (WAVE * EPL);
+    const int cpw = (nc + nw - 1) / nw;             // chunks per wavefront (the last ones may have fewer)
+    const bool kept = cpw <= TOPM_HELD;             // r holds a wavefront's whole share
+    // the list is expected to hold about 1.3 m cpw / TOPM_HELD tokens then; taken when twice that fits
+    const bool first_only = !kept && (long long)m * cpw <= 4ll * LIST;
+    const int a_end = first_only ? (c0 + TOPM_HELD < c1 ? c0 + TOPM_HELD : c1) : c1;
+    __syncthreads();
+    for (int c = c0; c < a_end; c += TOPM_HELD) {
+        if (c != c0) {   // (these chunks are read again in B: from cache)
+            load_chunks<T, false>(row, V, nc, c, lane, r);
+            load_chunks<T, false>(row, V, nc, c + 4, lane, r + 4);
+        }
+#pragma unroll
+        for (int u = 0; u < TOPM_HELD; u++) {
+            float x[EPL];
+            unpack_vals<T>(r[u], x);
+            const int n = n_inside<T>(V, c + u, lane);
+            if ((c + u + 1) * WAVE * EPL > V) {   // (wave-uniform) the row ends inside this chunk
+#pragma unroll
+                for (int j = 1; j < EPL; j++)
+                    if (j >= n) x[j] = -INFINITY;
+            }
+            float gm = x[0];
+#pragma unroll
+            for (int j = 1; j < EPL; j++) gm = fmaxf(gm, x[j]);
+            if (c + u < c1 && n > 0)
+                atomicAdd(&s.hist[order_key(__float_as_uint(gm)) >> TOPM_SHIFT], 1u);
+        }
+    }
+    __syncthreads();
+    pick_digit(s.hist, TOPM_BINS, (uint32_t)m, s.wave_tot, s.bc, nthreads);
+    // At least m groups have their maximum in this bin or above, so at least m tokens are not below the bin's
+    // lower edge.  With fewer than m groups in the row the bin is 0 and its edge is a NaN: nothing is below it.
+    const float L = __uint_as_float(key_to_bits(s.bc[4] << TOPM_SHIFT));
+    for (int i = tid; i < TOPM_CBINS; i += nthreads) s.hist[i] = 0u;   // for C; the barrier after B orders it
+    // ---- B. the tokens that are not below L, in token order, each wavefront into its own part of the list,
+    // each with its logit
+    const uint32_t R = (uint32_t)(LIST / nw);
+    const uint32_t base = (uint32_t)wave * R;
+    uint32_t cnt = 0;   // wave-uniform
+    // bf16 rows are compared two tokens at a time on 16-bit keys: everything whose key is not below the edge's.
+    // (-0 has the key just under +0's here; an edge at +0 is lowered by one so that it stays listed.  The list may
+    // hold more than the float comparison would put there, never less: C goes by the exact keys.)
+    const uint32_t edge_key16 = s.bc[4] << (16 - TOPM_BITS);
+    const uint32_t th16 = edge_key16 == 0x8000u ? 0x7FFEu : edge_key16 - 1u;   // listed: key above th16 (edge 0: all)
+    const uint32_t th_pk = th16 | (th16 << 16);
+    if (!kept && !first_only) {   // A has left its last chunks in r
+        load_chunks<T, true>(row, V, nc, c0, lane, r);
+        load_chunks<T, true>(row, V, nc, c0 + 4, lane, r + 4);
+    }
+    for (int c = c0; c < c1; c += TOPM_HELD) {
+        // the next chunks are asked for before these are looked at
+        uint4 rn[TOPM_HELD];
+        const bool more = c + TOPM_HELD < c1;   // (wave-uniform)
+        if (more) {
+            load_chunks<T, true>(row, V, nc, c + TOPM_HELD, lane, rn);
+            load_chunks<T, true>(row, V, nc, c + TOPM_HELD + 4, lane, rn + 4);
+        }
+#pragma unroll
+        for (int u = 0; u < TOPM_HELD; u++) {
+            if (c + u >= c1) continue;
+            // a[i]: word i of the lane's group; bf16: a 1 in each half whose token is listed, fp32: 1 if it is
+            uint32_t a[4];
+            const uint32_t w[4] = {r[u].x, r[u].y, r[u].z, r[u].w};
+            if (sizeof(T) == 2) {
+                if (edge_key16 == 0u) {   // (uniform)
+                    a[0] = a[1] = a[2] = a[3] = 0x00010001u;
+                } else {
+#pragma unroll
+                    for (int i = 0; i < 4; i++) a[i] = pk_above(pk_keys(w[i]), th_pk);
+                }
+            } else {
+#pragma unroll
+                for (int i = 0; i < 4; i++) a[i] = !(__uint_as_float(w[i]) < L) ? 1u : 0u;
+            }
+            if ((c + u + 1) * WAVE * EPL > V) {   // (wave-uniform) the row's last chunk: nothing behind the row's end
+                const int n = n_inside<T>(V, c + u, lane);
+#pragma unroll
+                for (int i = 0; i < 4; i++) {
+                    if (sizeof(T) == 2) a[i] &= (2 * i < n ? 0x0000FFFFu : 0u) | (2 * i + 1 < n ? 0xFFFF0000u : 0u);
+                    else a[i] = i < n ? a[i] : 0u;
+                }
+            }
+            const uint64_t hit = __ballot((a[0] | a[1] | a[2] | a[3]) != 0u);
+            if (hit == 0ull) continue;   // most chunks of a long row
+            uint32_t pm;   // bit j: token j of this lane's group is listed
+            if (sizeof(T) == 2) {
+                pm = 0u;
+#pragma unroll
+                for (int i = 0; i < 4; i++) pm |= ((a[i] | (a[i] >> 15)) & 3u) << (2 * i);
+            } else {
+                pm = a[0] | (a[1] << 1) | (a[2] << 2) | (a[3] << 3);
+            }
+            const uint32_t pc = (uint32_t)__popc(pm);
+            uint32_t at, tot;
+            if (__ballot(pc > 1u) == 0ull) {   // (wave-uniform) one token per lane at most: positions from the ballot
+                at = cnt + __builtin_amdgcn_mbcnt_hi((uint32_t)(hit >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)hit, 0u));
+                tot = (uint32_t)__popcll(hit);
+            } else {
+                const uint32_t incl = wave_incl_scan(pc);
+                tot = last_lane(incl);
+                at = cnt + incl - pc;
+            }
+            const uint32_t first_tok = (uint32_t)(((c + u) * WAVE + lane) * EPL);
+            while (pm) {
+                const uint32_t j = (uint32_t)__ffs((int)pm) - 1u;
+                // the token's logit out of the group, by masks (no branch, no indexed register)
+                uint32_t key;
+                if (sizeof(T) == 2) {
+                    const uint32_t m4 = 0u - ((j >> 2) & 1u), m2 = 0u - ((j >> 1) & 1u);
+                    const uint32_t lo = (w[2] & m4) | (w[0] & ~m4), hi = (w[3] & m4) | (w[1] & ~m4);
+                    const uint32_t ww = (hi & m2) | (lo & ~m2);
+                    key = (ww << ((~j & 1u) << 4)) & 0xFFFF0000u;
+                } else {
+                    const uint32_t m2 = 0u - ((j >> 1) & 1u), m1 = 0u - (j & 1u);
+                    const uint32_t lo = (w[1] & m1) | (w[0] & ~m1), hi = (w[3] & m1) | (w[2] & ~m1);
+                    key = (hi & m2) | (lo & ~m2);
+                }
+                if (at < R) {
+                    s.list_tok[base + at] = first_tok + j;
+                    s.list_key[base + at] = key;
+                }
+                at++;
+                pm &= pm - 1u;
+            }
+            cnt += tot;
+        }
+        if (more) {
+#pragma unroll
+            for (int u = 0; u < TOPM_HELD; u++) r[u] = rn[u];
+        }
+    }
+    if (lane == 0) {
+        s.seg_a[wave] = cnt < R ? cnt : R;
+        if (cnt > R) atomicOr(&s.bc[6], 1u);
+    }
+    __syncthreads();
+    if (s.bc[6] != 0u) return false;
+    const uint32_t edge16 = s.bc[4] << (16 - TOPM_BITS);
+
+    // ---- C. the key T of the m-th largest token, from the list.  Thread t answers for the entries t*S .. t*S+S-1
+    // of the list, which lie in its own wavefront's part (S = R / 64).
+    const int S = LIST / nthreads;
+    const uint32_t mine = s.seg_a[wave];
+    const uint32_t o0 = (uint32_t)(lane * S);
+    const uint32_t n_mine = o0 < mine ? (mine - o0 < (uint32_t)S ? mine - o0 : (uint32_t)S) : 0u;   // entries of this thread
+    const uint32_t *lk = s.list_key + base + o0, *lt = s.list_tok + base + o0;
+    // Every listed token's key is at or above the edge key (NaNs that slipped through the float comparison
+    // aside: they are dropped here), so the upper 16 key bits, counted from the edge, are small numbers: one
+    // histogram over them settles the upper half of T.  A row whose m-th largest token lies further above the
+    // bound than the histogram is long (TOPM_CBINS - 1 values of the upper half) goes to the whole-row select.
+    for (uint32_t q = 0; q < n_mine; q++) {   // (the histogram was cleared before B)
+        const uint32_t k = order_key(lk[q]);
+        if ((k >> 16) < edge16) continue;
+        uint32_t rel = (k >> 16) - edge16;
+        rel = rel < (uint32_t)(TOPM_CBINS - 1) ? rel : (uint32_t)(TOPM_CBINS - 1);
+        atomicAdd(&s.hist[rel], 1u);
+    }
+    __syncthreads();
+    pick_digit(s.hist, TOPM_CBINS, (uint32_t)m, s.wave_tot, s.bc, nthreads);
+    if (s.bc[4] == (uint32_t)(TOPM_CBINS - 1)) return false;   // T lies in the overflow bin
+    uint32_t hi_part = edge16 + s.bc[4], need = s.bc[5];
+    if (sizeof(T) == 4) {   // fp32: the lower half of T, eight bits at a time
+        for (int shift = 8; shift >= 0; shift -= 8) {
+            __syncthreads();
+            for (int i = tid; i < 256; i += nthreads) s.hist[i] = 0u;
+            __syncthreads();
+            for (uint32_t q = 0; q < n_mine; q++) {
+                const uint32_t k = order_key(lk[q]);
+                if ((k >> (shift + 8)) == hi_part) atomicAdd(&s.hist[(k >> shift) & 255u], 1u);
+            }
+            __syncthreads();
+            pick_digit(s.hist, 256, need, s.wave_tot, s.bc, nthreads);
+            hi_part = (hi_part << 8) | s.bc[4];
+            need = s.bc[5];
+        }
+    }
+    // (a key at or above T is at or above the edge: the entries dropped above do not come back below)
+    const uint32_t T_key = full_key<T>(hi_part);
+    const uint32_t take_eq = need;
+    // positions: list order is token order, and threads hold consecutive entries
+    uint32_t g = 0, e = 0;
+    for (uint32_t q = 0; q < n_mine; q++) {
+        const uint32_t k = order_key(lk[q]);
+        g += k > T_key ? 1u : 0u;
+        e += k == T_key ? 1u : 0u;
+    }
+    const uint32_t packed = g | (e << 16);   // both counts stay below 2^16 (the list has at most 4096 entries)
+    const uint32_t before = block_incl_scan(packed, s.wave_tot, nw) - packed;
+    uint32_t gt_before = before & 0xFFFFu, eq_before = before >> 16;
+    for (uint32_t q = 0; q < n_mine; q++) {
+        const uint32_t k = order_key(lk[q]);
+        if (k > T_key) {
+            const uint32_t pos = gt_before + (eq_before < take_eq ? eq_before : take_eq);
+            if (pos < (uint32_t)m) s.sel[pos] = lt[q];
+            gt_before++;
+        } else if (k == T_key) {
+            if (eq_before < take_eq) {
+                const uint32_t pos = gt_before + eq_before;
+                if (pos < (uint32_t)m) s.sel[pos] = lt[q];
+            }
+            eq_before++;
+        }
+    }
+    __syncthreads();
+    return true;
+}
+
+
+// ---- mask-only calls, prefixes with at most TOPM_COUNT_MAX children ----
+constexpr int TOPM_COUNT_MAX = 8;
+
 // The two thresholds of a child whose logit has the bits `b` (bf16 in the upper half), each in both halves of a
 // word: a token at a smaller id comes before the child if its key is above ge, one at a larger id if above gt.
 __device__ inline void pk_thresholds(uint32_t b, uint32_t &ge, uint32_t &gt) {
@@ -548,7 +612,7 @@ __device__ inline void count_chunk(const uint4 &raw, int V, int c, int lane, int
         const bool before = first + WAVE * EPL <= tokc[j];   // every token of the chunk has a smaller id: ties count
         const bool after = first > tokc[j];                   // every token has a larger id: ties do not count
         uint32_t k = 0;
-        if (before || after) {
+        if (__builtin_expect(before || after, 1)) {   // (all chunks of a row but one per child: the rest is kept out of the loop's way)
             if (PACKED) {
                 uint32_t ge, gt;
                 pk_thresholds(__float_as_uint(t), ge, gt);
@@ -647,11 +711,11 @@ __global__ __launch_bounds__(TOPM_WAVES *WAVE) void topm_kernel(IndexView ix, co
     constexpr int EPL = KeyChunk<T>::EPL;
     extern __shared__ __align__(16) uint32_t smem[];  // max(TOPM_BINS, n_words) words
     uint32_t *img = smem;                             // [n_words] the row of the mask, once the histogram is done with
-    __shared__ uint32_t list_tok[LIST];
+    __shared__ uint32_t list_tok[LIST], list_key[LIST];
     __shared__ uint32_t sel[PPV_TOPM_MAX];
     __shared__ uint32_t seg_a[TOPM_WAVES], seg_b[TOPM_WAVES], wave_tot[TOPM_WAVES];
     __shared__ uint32_t bc[8];
-    const TopmLds lds = {smem, list_tok, sel, seg_a, seg_b, wave_tot, bc};
+    const TopmLds lds = {smem, list_tok, list_key, sel, seg_a, seg_b, wave_tot, bc};
     const int b = blockIdx.x, tid = threadIdx.x, lane = tid & (WAVE - 1);
     const int wave = __builtin_amdgcn_readfirstlane(tid / WAVE);
     const int nthreads = blockDim.x, nw = nthreads / WAVE;
@@ -664,11 +728,14 @@ __global__ __launch_bounds__(TOPM_WAVES *WAVE) void topm_kernel(IndexView ix, co
     const int cpw = (nc + nw - 1) / nw;
     const int c0 = wave * cpw, c1 = (c0 + cpw < nc) ? c0 + cpw : nc;
 
-    const bool listed = force_streaming != 1 && nthreads * TOPM_SLOTS >= LIST;
+    const bool listed = force_streaming != 1 && nthreads * TOPM_SLOTS >= LIST && nthreads <= LIST;
     // a caller that asks for the mask alone: prefixes with few children are settled by counting (see count_children)
     const bool counting = force_streaming == 0 && !top_ids && !mask_V;
-    uint4 r[4];
-    if (listed || counting) load_chunks<T>(row, V, c0, c1, lane, r);   // in flight while the prefix is located
+    uint4 r[TOPM_HELD];
+    if (listed || counting) {   // in flight while the prefix is located
+        load_chunks<T, true>(row, V, nc, c0, lane, r);
+        load_chunks<T, true>(row, V, nc, c0 + 4, lane, r + 4);
+    }
     if (counting && tid < TOPM_COUNT_MAX) seg_a[tid] = 0u;
     if (wave == 0) {   // the part every candidate row shares: locate the prefix once
         const int32_t mine = first_tokens(prefixes + (size_t)b * (size_t)stride, stride, lane);
@@ -697,7 +764,8 @@ __global__ __launch_bounds__(TOPM_WAVES *WAVE) void topm_kernel(IndexView ix, co
             return;
         }
         if (n <= TOPM_COUNT_MAX && (uint32_t)n <= ix.heavy_min) {
-            count_children<T>(ix, row, V, nc, c0, c1, m, cb, n, r, seg_a, out, n_words, lane, nthreads);
+            count_children<T>(ix, row, V, nc, c0, c1, m, cb, n, *reinterpret_cast<uint4(*)[4]>(r), seg_a, out, n_words, lane,
+                              nthreads);
             return;
         }
     }
@@ -750,11 +818,11 @@ __global__ __launch_bounds__(TOPM_WAVES *WAVE) void topm_kernel(IndexView ix, co
 int topm_waves(int V, ppv_dtype dt, int B) {
     const int per = (dt == PPV_F32 ? 4 : 8) * WAVE;
     const int nc = (V + per - 1) / per;
-    int cap = B <= 512 ? 8 : 4;   // measured at V = 32k: B=256: 19.5 us with 8 or 16, 24 with 4; B=1024: 37 / 42 / 67 us with 4 / 8 / 16
-    // long rows (bf16, M = 50, us per call with 4 / 8 / 16 wavefronts): V = 128k: B=128: 50 / 31 / 27, B=1024: 101 / 103 / 130;
-    // V = 256k: B=128: - / 55 / 44, B=1024: 250 / 210 / 215
+    int cap = B <= 512 ? 8 : 4;   // measured at V = 32k, M = 50: B = 256: 11.1 / 11.9 us with 8 / 16; B = 4,096: 63 / 90 / 169 us with 4 / 8 / 16
+    // long rows (bf16, us per call with 4 / 8 / 16 wavefronts, M = 50 and 1,000): V = 128k: B = 128: 36 / 23 / 19 and 48 / 32 / 23,
+    // B = 1,024: 75 / 66 / 83 and 120 / 99 / 102; V = 256k: B = 128: 60 / 37 / 27 and 78 / 49 / 42, B = 1,024: 118 / 117 / 143 (M = 50)
     if (nc >= 128 && B <= 256) cap = 16;
-    if (nc >= 384 && B <= 2048 && cap < 8) cap = 8;
+    if (nc >= 128 && B <= 2048 && cap < 8) cap = 8;
     if (const int v = ppv_tuning(PPV_TUNE_TOPM_WAVES)) cap = v < TOPM_WAVES ? v : TOPM_WAVES;   // tuning aid (0: the table above)
     int nw = 1;
     while (nw * 2 <= cap && nw * 2 <= nc) nw <<= 1;

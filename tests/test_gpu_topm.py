@@ -152,6 +152,60 @@ def ties_and_special_values(dtype, Ms=(1, 7, 64, 1000)):
 
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_topm_long_rows_bound_from_the_first_chunks(dtype):
+    """A wavefront's share of a long row does not stay in registers; the bound on the M-th largest token then comes
+    from the chunks that each wavefront reads first, when the list has room for what that looser bound lets through
+    (M = 50, 300), and from the whole row otherwise (M = 1000).  Rows whose first chunks say little about the rest:
+    low there and high behind (the list overflows: whole-row select), high there and low behind (a short list),
+    everything large in one wavefront's share, and plain noise."""
+    rng = np.random.default_rng(4242)
+    V = 40003
+    seqs = [rng.integers(0, V, size=int(rng.integers(1, 4))).tolist() for _ in range(3000)]
+    seqs += [[int(v)] for v in range(0, V, 3)]
+    S = W.constraint_set_from_lists(seqs, V)
+    X = oracle.SortedArray(S.tokens, S.offsets, V)
+    index = ppv.ppv_build_index(S.tokens, S.offsets, V)
+    B = 12
+    P = np.full((B, 4), W.PAD_TOKEN, np.int32)
+    L = np.zeros(B, np.int32)
+    for b in range(B // 2, B):                                 # the second half of the batch: below the root
+        s = seqs[b]
+        P[b, :1] = s[:1]
+        L[b] = 1
+    per = 512 if dtype == "bf16" else 256                      # tokens per chunk
+    lg = rng.normal(0.0, 2.0, size=(B, V)).astype(np.float32)
+    for waves in (2, 4):
+        n_chunks = (V + per - 1) // per
+        share = (n_chunks + waves - 1) // waves * per         # tokens per wavefront
+        first = np.zeros(V, bool)
+        for w in range(waves):
+            first[w * share: w * share + 8 * per] = True
+        r = 0 if waves == 2 else 6
+        lg[r, first] -= 6.0                                    # low where the bound is taken
+        lg[r + 1, ~first] -= 6.0                               # high where the bound is taken
+        lg[r + 2, share: 2 * share] += 9.0                     # everything large sits in the second wavefront's share
+    if dtype == "bf16":
+        Vp = (V + 7) // 8 * 8
+        bits = (lg.view(np.uint32) >> 16).astype(np.uint16)
+        lf = (bits.astype(np.uint32) << 16).view(np.float32)
+        padded = np.zeros((B, Vp), np.uint16)
+        padded[:, :V] = bits
+        ld = to_dev(padded.view(np.int16)).view(torch.bfloat16)[:, :V]
+    else:
+        Vp = (V + 3) // 4 * 4
+        lf = lg
+        padded = np.zeros((B, Vp), np.float32)
+        padded[:, :V] = lg
+        ld = to_dev(padded)[:, :V]
+    for waves in (2, 4):
+        with tuning(ppv.PPV_TUNE_TOPM_WAVES, waves):
+            for M in (50, 300, 1000):
+                say(f"long rows {dtype} waves={waves} M={M}")
+                assert_topm_parity(index, X, P, L, lf, ld, M)
+    index.free()
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
 @pytest.mark.parametrize("V", [200, 4104])
 def test_topm_mask_alone_counts_the_tokens_before_each_child(dtype, V):
     """A mask-only call settles prefixes with at most eight children by counting, per child, the tokens that come
