@@ -399,86 +399,90 @@ __device__ inline bool select_listed(const T *__restrict__ row, int V, int c0, i
         load_chunks<T, true>(row, V, nc, c0, lane, r);
         load_chunks<T, true>(row, V, nc, c0 + 4, lane, r + 4);
     }
-    for (int c = c0; c < c1; c += TOPM_HELD) {
-        // the next chunks are asked for before these are looked at
-        uint4 rn[TOPM_HELD];
-        const bool more = c + TOPM_HELD < c1;   // (wave-uniform)
-        if (more) {
-            load_chunks<T, true>(row, V, nc, c + TOPM_HELD, lane, rn);
-            load_chunks<T, true>(row, V, nc, c + TOPM_HELD + 4, lane, rn + 4);
+    auto list_chunk = [&](const uint4 &rr, int cc) {   // chunk cc of the row, this lane's 16 bytes of it in rr
+        // a[i]: word i of the lane's group; bf16: a 1 in each half whose token is listed, fp32: 1 if it is
+        uint32_t a[4];
+        const uint32_t w[4] = {rr.x, rr.y, rr.z, rr.w};
+        if (sizeof(T) == 2) {
+            if (edge_key16 == 0u) {   // (uniform)
+                a[0] = a[1] = a[2] = a[3] = 0x00010001u;
+            } else {
+#pragma unroll
+                for (int i = 0; i < 4; i++) a[i] = pk_above(pk_keys(w[i]), th_pk);
+            }
+        } else {
+#pragma unroll
+            for (int i = 0; i < 4; i++) a[i] = !(__uint_as_float(w[i]) < L) ? 1u : 0u;
         }
+        if ((cc + 1) * WAVE * EPL > V) {   // (wave-uniform) the row's last chunk: nothing behind the row's end
+            const int n = n_inside<T>(V, cc, lane);
 #pragma unroll
-        for (int u = 0; u < TOPM_HELD; u++) {
-            if (c + u >= c1) continue;
-            // a[i]: word i of the lane's group; bf16: a 1 in each half whose token is listed, fp32: 1 if it is
-            uint32_t a[4];
-            const uint32_t w[4] = {r[u].x, r[u].y, r[u].z, r[u].w};
-            if (sizeof(T) == 2) {
-                if (edge_key16 == 0u) {   // (uniform)
-                    a[0] = a[1] = a[2] = a[3] = 0x00010001u;
-                } else {
-#pragma unroll
-                    for (int i = 0; i < 4; i++) a[i] = pk_above(pk_keys(w[i]), th_pk);
-                }
-            } else {
-#pragma unroll
-                for (int i = 0; i < 4; i++) a[i] = !(__uint_as_float(w[i]) < L) ? 1u : 0u;
+            for (int i = 0; i < 4; i++) {
+                if (sizeof(T) == 2) a[i] &= (2 * i < n ? 0x0000FFFFu : 0u) | (2 * i + 1 < n ? 0xFFFF0000u : 0u);
+                else a[i] = i < n ? a[i] : 0u;
             }
-            if ((c + u + 1) * WAVE * EPL > V) {   // (wave-uniform) the row's last chunk: nothing behind the row's end
-                const int n = n_inside<T>(V, c + u, lane);
-#pragma unroll
-                for (int i = 0; i < 4; i++) {
-                    if (sizeof(T) == 2) a[i] &= (2 * i < n ? 0x0000FFFFu : 0u) | (2 * i + 1 < n ? 0xFFFF0000u : 0u);
-                    else a[i] = i < n ? a[i] : 0u;
-                }
-            }
-            const uint64_t hit = __ballot((a[0] | a[1] | a[2] | a[3]) != 0u);
-            if (hit == 0ull) continue;   // most chunks of a long row
-            uint32_t pm;   // bit j: token j of this lane's group is listed
-            if (sizeof(T) == 2) {
-                pm = 0u;
-#pragma unroll
-                for (int i = 0; i < 4; i++) pm |= ((a[i] | (a[i] >> 15)) & 3u) << (2 * i);
-            } else {
-                pm = a[0] | (a[1] << 1) | (a[2] << 2) | (a[3] << 3);
-            }
-            const uint32_t pc = (uint32_t)__popc(pm);
-            uint32_t at, tot;
-            if (__ballot(pc > 1u) == 0ull) {   // (wave-uniform) one token per lane at most: positions from the ballot
-                at = cnt + __builtin_amdgcn_mbcnt_hi((uint32_t)(hit >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)hit, 0u));
-                tot = (uint32_t)__popcll(hit);
-            } else {
-                const uint32_t incl = wave_incl_scan(pc);
-                tot = last_lane(incl);
-                at = cnt + incl - pc;
-            }
-            const uint32_t first_tok = (uint32_t)(((c + u) * WAVE + lane) * EPL);
-            while (pm) {
-                const uint32_t j = (uint32_t)__ffs((int)pm) - 1u;
-                // the token's logit out of the group, by masks (no branch, no indexed register)
-                uint32_t key;
-                if (sizeof(T) == 2) {
-                    const uint32_t m4 = 0u - ((j >> 2) & 1u), m2 = 0u - ((j >> 1) & 1u);
-                    const uint32_t lo = (w[2] & m4) | (w[0] & ~m4), hi = (w[3] & m4) | (w[1] & ~m4);
-                    const uint32_t ww = (hi & m2) | (lo & ~m2);
-                    key = (ww << ((~j & 1u) << 4)) & 0xFFFF0000u;
-                } else {
-                    const uint32_t m2 = 0u - ((j >> 1) & 1u), m1 = 0u - (j & 1u);
-                    const uint32_t lo = (w[1] & m1) | (w[0] & ~m1), hi = (w[3] & m1) | (w[2] & ~m1);
-                    key = (hi & m2) | (lo & ~m2);
-                }
-                if (at < R) {
-                    s.list_tok[base + at] = first_tok + j;
-                    s.list_key[base + at] = key;
-                }
-                at++;
-                pm &= pm - 1u;
-            }
-            cnt += tot;
         }
-        if (more) {
+        const uint64_t hit = __ballot((a[0] | a[1] | a[2] | a[3]) != 0u);
+        if (hit == 0ull) return;   // most chunks of a long row
+        uint32_t pm;   // bit j: token j of this lane's group is listed
+        if (sizeof(T) == 2) {
+            pm = 0u;
 #pragma unroll
-            for (int u = 0; u < TOPM_HELD; u++) r[u] = rn[u];
+            for (int i = 0; i < 4; i++) pm |= ((a[i] | (a[i] >> 15)) & 3u) << (2 * i);
+        } else {
+            pm = a[0] | (a[1] << 1) | (a[2] << 2) | (a[3] << 3);
+        }
+        const uint32_t pc = (uint32_t)__popc(pm);
+        uint32_t at, tot;
+        if (__ballot(pc > 1u) == 0ull) {   // (wave-uniform) one token per lane at most: positions from the ballot
+            at = cnt + __builtin_amdgcn_mbcnt_hi((uint32_t)(hit >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)hit, 0u));
+            tot = (uint32_t)__popcll(hit);
+        } else {
+            const uint32_t incl = wave_incl_scan(pc);
+            tot = last_lane(incl);
+            at = cnt + incl - pc;
+        }
+        const uint32_t first_tok = (uint32_t)((cc * WAVE + lane) * EPL);
+        while (pm) {
+            const uint32_t j = (uint32_t)__ffs((int)pm) - 1u;
+            // the token's logit out of the group, by masks (no branch, no indexed register)
+            uint32_t key;
+            if (sizeof(T) == 2) {
+                const uint32_t m4 = 0u - ((j >> 2) & 1u), m2 = 0u - ((j >> 1) & 1u);
+                const uint32_t lo = (w[2] & m4) | (w[0] & ~m4), hi = (w[3] & m4) | (w[1] & ~m4);
+                const uint32_t ww = (hi & m2) | (lo & ~m2);
+                key = (ww << ((~j & 1u) << 4)) & 0xFFFF0000u;
+            } else {
+                const uint32_t m2 = 0u - ((j >> 1) & 1u), m1 = 0u - (j & 1u);
+                const uint32_t lo = (w[1] & m1) | (w[0] & ~m1), hi = (w[3] & m1) | (w[2] & ~m1);
+                key = (hi & m2) | (lo & ~m2);
+            }
+            if (at < R) {
+                s.list_tok[base + at] = first_tok + j;
+                s.list_key[base + at] = key;
+            }
+            at++;
+            pm &= pm - 1u;
+        }
+        cnt += tot;
+    };
+    if (kept) {
+#pragma unroll
+        for (int u = 0; u < TOPM_HELD; u++)
+            if (c0 + u < c1) list_chunk(r[u], c0 + u);
+    } else {
+        // the two halves of r take turns: four chunks are asked for again as soon as they have been looked at,
+        // from addresses that always lie inside the row, while the other four are looked at
+        constexpr int HALF = TOPM_HELD / 2;
+        for (int c = c0; c < c1; c += TOPM_HELD) {
+#pragma unroll
+            for (int h = 0; h < TOPM_HELD; h += HALF) {
+#pragma unroll
+                for (int u = h; u < h + HALF; u++)
+                    if (c + u < c1) list_chunk(r[u], c + u);
+#pragma unroll
+                for (int u = h; u < h + HALF; u++) r[u] = load_raw_clamped<T, true>(row, V, nc, c + TOPM_HELD + u, lane);
+            }
         }
     }
     if (lane == 0) {
