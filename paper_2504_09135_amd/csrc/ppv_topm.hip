@@ -630,13 +630,16 @@ __device__ inline void count_chunk(const uint4 &raw, int V, int c, int lane, int
 #pragma unroll
                 for (int e = 0; e < EPL; e++) k += x[e] > t ? 1u : 0u;
             }
-        } else {                                 // the child's own chunk (one per child and row)
-            if (PACKED) {
-                unpack_vals<T>(raw, x);
+        } else if (PACKED) {                     // the child's own chunk (one per child and row): the threshold
+                                                 // of each half follows from which side of the child its token lies on
+            uint32_t ge, gt;
+            pk_thresholds(__float_as_uint(t), ge, gt);
 #pragma unroll
-                for (int e = 0; e < EPL; e++)
-                    if (g + e >= V) x[e] = -INFINITY;
+            for (int i = 0; i < 4; i++) {
+                const uint32_t lo = g + 2 * i < tokc[j] ? ge : gt, hi = g + 2 * i + 1 < tokc[j] ? ge : gt;
+                k += pk_above(keys[i], (lo & 0x0000FFFFu) | (hi & 0xFFFF0000u));
             }
+        } else {
 #pragma unroll
             for (int e = 0; e < EPL; e++) k += (x[e] > t || (x[e] == t && g + e < tokc[j])) ? 1u : 0u;
         }
@@ -645,11 +648,11 @@ __device__ inline void count_chunk(const uint4 &raw, int V, int c, int lane, int
 }
 
 // The mask row of a prefix with n <= TOPM_COUNT_MAX children (entries cb .. cb + n - 1), restricted to the m most
-// probable tokens.  Every thread of the workgroup calls; r holds the wavefront's first four chunks; tot[] was
+// probable tokens.  Every thread of the workgroup calls; r holds the wavefront's first TOPM_HELD chunks; tot[] was
 // cleared before the last barrier.
 template <typename T>
 __device__ inline void count_children(const IndexView &ix, const T *__restrict__ row, int V, int nc, int c0, int c1,
-                                      int m, uint32_t cb, int n, uint4 (&r)[4], uint32_t *tot,
+                                      int m, uint32_t cb, int n, uint4 (&r)[TOPM_HELD], uint32_t *tot,
                                       uint32_t *__restrict__ out, int n_words, int lane, int nthreads) {
     // child j in lane j: its token and that token's logit
     uint32_t ctok = 0u;
@@ -668,16 +671,16 @@ __device__ inline void count_children(const IndexView &ix, const T *__restrict__
         thr[j] = __uint_as_float(lane_value(__float_as_uint(cthr), j));
         cnt[j] = 0u;
     }
-    // the two halves of r take turns: a pair of chunks is asked for again as soon as it has been counted, while
-    // the other pair is counted
-    for (int c = c0; c < c1; c += 4) {
+    // the pairs of r take turns: a pair of chunks is asked for again as soon as it has been counted, while the
+    // other three pairs are counted or on their way
+    for (int c = c0; c < c1; c += TOPM_HELD) {
 #pragma unroll
-        for (int h = 0; h < 4; h += 2) {
+        for (int h = 0; h < TOPM_HELD; h += 2) {
 #pragma unroll
             for (int u = h; u < h + 2; u++)
                 if (c + u < c1) count_chunk<T>(r[u], V, c + u, lane, n, tokc, thr, cnt);
 #pragma unroll
-            for (int u = h; u < h + 2; u++) r[u] = load_raw_clamped<T>(row, V, nc, c + 4 + u, lane);
+            for (int u = h; u < h + 2; u++) r[u] = load_raw_clamped<T>(row, V, nc, c + TOPM_HELD + u, lane);
         }
     }
 #pragma unroll
@@ -768,8 +771,7 @@ __global__ __launch_bounds__(TOPM_WAVES *WAVE) void topm_kernel(IndexView ix, co
             return;
         }
         if (n <= TOPM_COUNT_MAX && (uint32_t)n <= ix.heavy_min) {
-            count_children<T>(ix, row, V, nc, c0, c1, m, cb, n, *reinterpret_cast<uint4(*)[4]>(r), seg_a, out, n_words, lane,
-                              nthreads);
+            count_children<T>(ix, row, V, nc, c0, c1, m, cb, n, r, seg_a, out, n_words, lane, nthreads);
             return;
         }
     }
