@@ -27,8 +27,9 @@
 //            one histogram pass per digit and two more passes to gather in token order.
 //   verify   the M candidate rows share their first |a| tokens, so the prefix is located once
 //            (the same walk the full-vocabulary mask uses) and each candidate then needs one
-//            binary search for its last token among the prefix's children -- or one bit test in
-//            the ready-made image of a heavy prefix.  One thread per candidate.
+//            binary search for its last token among the prefix's children (their tokens are
+//            copied to LDS while the row is on its way) -- or one bit test in the ready-made
+//            image of a heavy prefix.  One thread per candidate.
 //   extend   the mask row is assembled in LDS and written with whole words.
 //   count    a caller that wants only the mask (no candidate list, no verdicts) does not need the top M at all
 //            when the prefix has few continuations: token t is among the M most probable iff fewer than M
@@ -219,6 +220,7 @@ template <typename T> __device__ inline uint32_t full_key(uint32_t hi_part) {
 
 struct TopmLds {
     uint32_t *hist;       // [TOPM_BINS]
+    uint32_t *hist2;      // [TOPM_CBINS] the listed tokens' keys, counted from the bound (filled while they are listed)
     uint32_t *list_tok;   // [LIST]
     uint32_t *list_key;   // [LIST] the listed tokens' logits (bit patterns, bf16 in the upper half)
     uint32_t *sel;        // [PPV_TOPM_MAX]
@@ -336,7 +338,7 @@ __device__ inline uint32_t pk_above(uint32_t keys, uint32_t thresholds) {
 }
 // Bound, short list, radix select over the list.  Needs nthreads >= LIST / TOPM_SLOTS and nthreads <= LIST.
 // Returns false (for every thread alike) when the list did not fit; sel is then untouched.  r arrives holding
-// the wavefront's first TOPM_HELD chunks.  The row is read from memory once when a wavefront's share is no longer
+// the wavefront's first TOPM_HELD chunks; hist, hist2 and bc[6] were cleared before the workgroup's last barrier.  The row is read from memory once when a wavefront's share is no longer
 // than that, and also when the share is longer but the list has room for a looser bound: the bound is then taken
 // from the chunks in r alone (at least m of THEIR groups reach it, so at least m tokens of the row do), and the
 // list grows by about the factor by which the share is longer.
@@ -347,15 +349,12 @@ __device__ inline bool select_listed(const T *__restrict__ row, int V, int c0, i
     const int tid = threadIdx.x, nw = nthreads / WAVE;
     // ---- A. maxima of the 16-byte groups, histogram of their leading key bits.  The row is taken TOPM_HELD
     // chunks at a time (as many loads in flight per lane); first_only: only the chunks that r arrived with.
-    for (int i = tid; i < TOPM_BINS; i += nthreads) s.hist[i] = 0u;
-    if (tid == 0) s.bc[6] = 0u;
     const int nc = (V + WAVE * EPL - 1) / (WAVE * EPL);
     const int cpw = (nc + nw - 1) / nw;             // chunks per wavefront (the last ones may have fewer)
     const bool kept = cpw <= TOPM_HELD;             // r holds a wavefront's whole share
     // the list is expected to hold about 1.3 m cpw / TOPM_HELD tokens then; taken when twice that fits
     const bool first_only = !kept && (long long)m * cpw <= 4ll * LIST;
     const int a_end = first_only ? (c0 + TOPM_HELD < c1 ? c0 + TOPM_HELD : c1) : c1;
-    __syncthreads();
     for (int c = c0; c < a_end; c += TOPM_HELD) {
         if (c != c0) {   // (these chunks are read again in B: from cache)
             load_chunks<T, false>(row, V, nc, c, lane, r);
@@ -383,7 +382,6 @@ __device__ inline bool select_listed(const T *__restrict__ row, int V, int c0, i
     // At least m groups have their maximum in this bin or above, so at least m tokens are not below the bin's
     // lower edge.  With fewer than m groups in the row the bin is 0 and its edge is a NaN: nothing is below it.
     const float L = __uint_as_float(key_to_bits(s.bc[4] << TOPM_SHIFT));
-    for (int i = tid; i < TOPM_CBINS; i += nthreads) s.hist[i] = 0u;   // for C; the barrier after B orders it
     // ---- B. the tokens that are not below L, in token order, each wavefront into its own part of the list,
     // each with its logit
     const uint32_t R = (uint32_t)(LIST / nw);
@@ -461,6 +459,13 @@ __device__ inline bool select_listed(const T *__restrict__ row, int V, int c0, i
                 s.list_tok[base + at] = first_tok + j;
                 s.list_key[base + at] = key;
             }
+            // C's histogram, while the key is at hand: the upper key half, counted from the bound (NaNs that
+            // slipped through the comparison lie below it and are left out here as they are in C)
+            const uint32_t k16 = order_key(key) >> 16;
+            if (k16 >= edge_key16) {
+                const uint32_t rel = k16 - edge_key16;
+                atomicAdd(&s.hist2[rel < (uint32_t)(TOPM_CBINS - 1) ? rel : (uint32_t)(TOPM_CBINS - 1)], 1u);
+            }
             at++;
             pm &= pm - 1u;
         }
@@ -501,18 +506,11 @@ __device__ inline bool select_listed(const T *__restrict__ row, int V, int c0, i
     const uint32_t n_mine = o0 < mine ? (mine - o0 < (uint32_t)S ? mine - o0 : (uint32_t)S) : 0u;   // entries of this thread
     const uint32_t *lk = s.list_key + base + o0, *lt = s.list_tok + base + o0;
     // Every listed token's key is at or above the edge key (NaNs that slipped through the float comparison
-    // aside: they are dropped here), so the upper 16 key bits, counted from the edge, are small numbers: one
-    // histogram over them settles the upper half of T.  A row whose m-th largest token lies further above the
-    // bound than the histogram is long (TOPM_CBINS - 1 values of the upper half) goes to the whole-row select.
-    for (uint32_t q = 0; q < n_mine; q++) {   // (the histogram was cleared before B)
-        const uint32_t k = order_key(lk[q]);
-        if ((k >> 16) < edge16) continue;
-        uint32_t rel = (k >> 16) - edge16;
-        rel = rel < (uint32_t)(TOPM_CBINS - 1) ? rel : (uint32_t)(TOPM_CBINS - 1);
-        atomicAdd(&s.hist[rel], 1u);
-    }
-    __syncthreads();
-    pick_digit(s.hist, TOPM_CBINS, (uint32_t)m, s.wave_tot, s.bc, nthreads);
+    // aside: they were left out), so the upper 16 key bits, counted from the edge, are small numbers: the one
+    // histogram over them that B has filled settles the upper half of T.  A row whose m-th largest token lies
+    // further above the bound than the histogram is long (TOPM_CBINS - 1 values of the upper half) goes to the
+    // whole-row select.
+    pick_digit(s.hist2, TOPM_CBINS, (uint32_t)m, s.wave_tot, s.bc, nthreads);
     if (s.bc[4] == (uint32_t)(TOPM_CBINS - 1)) return false;   // T lies in the overflow bin
     uint32_t hi_part = edge16 + s.bc[4], need = s.bc[5];
     if (sizeof(T) == 4) {   // fp32: the lower half of T, eight bits at a time
@@ -719,10 +717,12 @@ __global__ __launch_bounds__(TOPM_WAVES *WAVE) void topm_kernel(IndexView ix, co
     extern __shared__ __align__(16) uint32_t smem[];  // max(TOPM_BINS, n_words) words
     uint32_t *img = smem;                             // [n_words] the row of the mask, once the histogram is done with
     __shared__ uint32_t list_tok[LIST], list_key[LIST];
+    __shared__ uint32_t hist2[TOPM_CBINS];
+    __shared__ uint32_t kids[PPV_LIST_MAX];   // the tokens of the prefix's children, when they are listed (not a heavy prefix)
     __shared__ uint32_t sel[PPV_TOPM_MAX];
     __shared__ uint32_t seg_a[TOPM_WAVES], seg_b[TOPM_WAVES], wave_tot[TOPM_WAVES];
     __shared__ uint32_t bc[8];
-    const TopmLds lds = {smem, list_tok, list_key, sel, seg_a, seg_b, wave_tot, bc};
+    const TopmLds lds = {smem, hist2, list_tok, list_key, sel, seg_a, seg_b, wave_tot, bc};
     const int b = blockIdx.x, tid = threadIdx.x, lane = tid & (WAVE - 1);
     const int wave = __builtin_amdgcn_readfirstlane(tid / WAVE);
     const int nthreads = blockDim.x, nw = nthreads / WAVE;
@@ -744,6 +744,11 @@ __global__ __launch_bounds__(TOPM_WAVES *WAVE) void topm_kernel(IndexView ix, co
         load_chunks<T, true>(row, V, nc, c0 + 4, lane, r + 4);
     }
     if (counting && tid < TOPM_COUNT_MAX) seg_a[tid] = 0u;
+    if (listed) {   // what the list select starts from
+        for (int i = tid; i < TOPM_BINS; i += nthreads) smem[i] = 0u;
+        for (int i = tid; i < TOPM_CBINS; i += nthreads) hist2[i] = 0u;
+        if (tid == 0) bc[6] = 0u;
+    }
     if (wave == 0) {   // the part every candidate row shares: locate the prefix once
         const int32_t mine = first_tokens(prefixes + (size_t)b * (size_t)stride, stride, lane);
         int t = lens[b];
@@ -756,11 +761,12 @@ __global__ __launch_bounds__(TOPM_WAVES *WAVE) void topm_kernel(IndexView ix, co
             bc[3] = w.found ? w.ce : 0u;
         }
     }
+    __syncthreads();   // the walk's verdict
+    const uint32_t node = bc[0];
+    const bool found = bc[1] != 0u;
+    const uint32_t cb = bc[2], ce = bc[3];
+    const int n = (int)(ce - cb);
     if (counting) {
-        __syncthreads();   // the walk's verdict
-        const bool found = bc[1] != 0u;
-        const uint32_t cb = bc[2];
-        const int n = (int)(bc[3] - cb);
         uint32_t *out = mask + (size_t)b * (size_t)n_words;
         if (!found || n == 0) {   // no continuation at all: the row of the mask is empty, the logits do not matter
             if ((n_words & 3) == 0 && (((uintptr_t)mask) & 15u) == 0) {
@@ -775,6 +781,11 @@ __global__ __launch_bounds__(TOPM_WAVES *WAVE) void topm_kernel(IndexView ix, co
             return;
         }
     }
+    // the children's tokens go to LDS while the row is on its way: the candidates are then looked up there
+    const bool kids_listed = found && (uint32_t)n <= ix.heavy_min;
+    if (kids_listed)
+        for (int i = tid; i < n; i += nthreads) kids[i] = ix.ent[cb + (uint32_t)i].tok & PPV_NODE_TOKEN;
+    const uint32_t slot = (found && (uint32_t)n > ix.heavy_min) ? heavy_slot_of(ix, node) : PPV_NO_SLOT;
     // ---- select
     bool done = false;
     if (listed) done = select_listed<T, LIST>(row, V, c0, c1, m, lds, lane, wave, nthreads, r);
@@ -783,10 +794,6 @@ __global__ __launch_bounds__(TOPM_WAVES *WAVE) void topm_kernel(IndexView ix, co
     __syncthreads();
 
     // ---- verify: one candidate per thread
-    const uint32_t node = bc[0];
-    const bool found = bc[1] != 0u;
-    const uint32_t cb = bc[2], ce = bc[3];
-    const uint32_t slot = (found && ce - cb > ix.heavy_min) ? heavy_slot_of(ix, node) : PPV_NO_SLOT;
     const uint32_t *image = ix.heavy_bits + (size_t)(slot != PPV_NO_SLOT ? slot : 0u) * (size_t)n_words;
     for (int i = tid; i < M; i += nthreads) {
         int32_t t = -1;
@@ -795,14 +802,14 @@ __global__ __launch_bounds__(TOPM_WAVES *WAVE) void topm_kernel(IndexView ix, co
             t = (int32_t)sel[i];
             if (slot != PPV_NO_SLOT) {
                 ok = (image[t >> 5] >> (t & 31)) & 1u;
-            } else if (found) {   // first child whose token is not below t
-                uint32_t lo = cb, hi = ce;
+            } else if (kids_listed) {   // first child whose token is not below t
+                int lo = 0, hi = n;
                 while (lo < hi) {
-                    const uint32_t mid = lo + (hi - lo) / 2;
-                    if ((ix.ent[mid].tok & PPV_NODE_TOKEN) < (uint32_t)t) lo = mid + 1;
+                    const int mid = lo + (hi - lo) / 2;
+                    if (kids[mid] < (uint32_t)t) lo = mid + 1;
                     else hi = mid;
                 }
-                ok = (lo < ce && (ix.ent[lo].tok & PPV_NODE_TOKEN) == (uint32_t)t) ? 1u : 0u;
+                ok = (lo < n && kids[lo] == (uint32_t)t) ? 1u : 0u;
             }
             if (ok) atomicOr(&img[t >> 5], 1u << (t & 31));
         }
