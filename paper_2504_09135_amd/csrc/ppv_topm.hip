@@ -776,7 +776,11 @@ __global__ __launch_bounds__(TOPM_WAVES *WAVE) void topm_kernel(IndexView ix, co
             }
             return;
         }
-        if (n <= TOPM_COUNT_MAX && (uint32_t)n <= ix.heavy_min) {
+        // Counting pays where the selection would hold the row in registers anyway (it skips the bound, the list and
+        // the cut: 9 against 12 us at V = 32k) and where the selection would read the row twice; a long row that the
+        // selection reads once (bound from the first chunks) is no faster counted (V = 256k: 120 against 117 us).
+        const bool select_reads_once = listed && (cpw <= TOPM_HELD || (long long)m * cpw <= 4ll * LIST);
+        if (n <= TOPM_COUNT_MAX && (uint32_t)n <= ix.heavy_min && (cpw <= TOPM_HELD || !select_reads_once)) {
             count_children<T>(ix, row, V, nc, c0, c1, m, cb, n, r, seg_a, out, n_words, lane, nthreads);
             return;
         }
