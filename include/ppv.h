@@ -311,9 +311,9 @@ ppv_status ppv_decode_loop(const ppv_index_t *index, int32_t *prefixes, int32_t 
  *   mask_V      uint8[B, M] or NULL: mask_V[b, i] = 1 iff a + [top_ids[b, i]] is a prefix of a member
  *   mask        uint32[B, ceil(V/32)]: bit t set iff t is a candidate and its mask_V is 1
  * A call that asks for the mask alone (top_ids and mask_V both NULL) returns the same mask, but where the prefix
- * has no more than eight continuations it does not select the M candidates at all: a continuation t is a candidate
- * iff fewer than M tokens come before it in the order above, and those are counted in one pass over the row; a
- * prefix without continuations reads no logits.
+ * has no more than eight continuations it need not select the M candidates at all: a continuation t is a candidate
+ * iff fewer than M tokens come before it in the order above, and those are counted in one pass over the row (the
+ * library does so where that is the faster way); a prefix without continuations reads no logits.
  * Errors: PPV_EINVAL (null pointer, M < 1, bad dtype / alignment / stride), PPV_ERANGE (M > PPV_TOPM_MAX),
  * PPV_EDEVICE.  B == 0 is PPV_OK.
  */
