@@ -338,25 +338,33 @@ __device__ inline uint32_t pk_above(uint32_t keys, uint32_t thresholds) {
 }
 // Bound, short list, radix select over the list.  Needs nthreads >= LIST / TOPM_SLOTS and nthreads <= LIST.
 // Returns false (for every thread alike) when the list did not fit; sel is then untouched.  r arrives holding
-// the wavefront's first TOPM_HELD chunks; hist, hist2 and bc[6] were cleared before the workgroup's last barrier.  The row is read from memory once when a wavefront's share is no longer
-// than that, and also when the share is longer but the list has room for a looser bound: the bound is then taken
-// from the chunks in r alone (at least m of THEIR groups reach it, so at least m tokens of the row do), and the
-// list grows by about the factor by which the share is longer.
+// the wavefront's first TOPM_HELD chunks; hist, hist2 and bc[6] were cleared before the workgroup's last barrier.
+// The row is read from memory once: a share longer than r gives the bound from its first chunks only (at least m
+// of THEIR groups reach it, so at least m tokens of the row do) -- as many batches of TOPM_HELD chunks as it takes
+// for the list to have room for what the looser bound lets through, which is about share / those chunks times
+// more; B reads the batches after the first again, from cache, and the rest of the share for the first time.
 template <typename T, int LIST>
 __device__ inline bool select_listed(const T *__restrict__ row, int V, int c0, int c1, int m, const TopmLds &s, int lane,
                                      int wave, int nthreads, uint4 (&r)[TOPM_HELD]) {
     constexpr int EPL = KeyChunk<T>::EPL;
     const int tid = threadIdx.x, nw = nthreads / WAVE;
     // ---- A. maxima of the 16-byte groups, histogram of their leading key bits.  The row is taken TOPM_HELD
-    // chunks at a time (as many loads in flight per lane); first_only: only the chunks that r arrived with.
+    // chunks at a time (as many loads in flight per lane), a_batches batches of each wavefront's share.
     const int nc = (V + WAVE * EPL - 1) / (WAVE * EPL);
     const int cpw = (nc + nw - 1) / nw;             // chunks per wavefront (the last ones may have fewer)
     const bool kept = cpw <= TOPM_HELD;             // r holds a wavefront's whole share
-    // the list is expected to hold about 1.3 m cpw / TOPM_HELD tokens then; taken when twice that fits
-    const bool first_only = !kept && (long long)m * cpw <= 4ll * LIST;
-    const int a_end = first_only ? (c0 + TOPM_HELD < c1 ? c0 + TOPM_HELD : c1) : c1;
+    // With the bound from the whole row the list holds 1.1 to 1.5 m tokens when the keys are spread out and
+    // about 4 m for bf16 noise (a bin of the bound is 32 bf16 values wide); from a_batches batches of the share,
+    // cpw / (TOPM_HELD a_batches) times more: as few batches as leave room for 4 m times that.
+    // (A list that overflows all the same sends the row to the whole-row select.)
+    const int all_batches = (cpw + TOPM_HELD - 1) / TOPM_HELD;
+    const long long want = ((long long)m * cpw + 2ll * LIST - 1) / (2ll * LIST);
+    const int a_batches = want < 1 ? 1 : (want > all_batches ? all_batches : (int)want);
+    const uint32_t R = (uint32_t)(LIST / nw);
+    const uint32_t base = (uint32_t)wave * R;
+    const int a_end = c0 + a_batches * TOPM_HELD < c1 ? c0 + a_batches * TOPM_HELD : c1;
     for (int c = c0; c < a_end; c += TOPM_HELD) {
-        if (c != c0) {   // (these chunks are read again in B: from cache)
+        if (c != c0) {   // (chunks that A reads from memory are read again in B: from cache)
             load_chunks<T, false>(row, V, nc, c, lane, r);
             load_chunks<T, false>(row, V, nc, c + 4, lane, r + 4);
         }
@@ -384,8 +392,6 @@ __device__ inline bool select_listed(const T *__restrict__ row, int V, int c0, i
     const float L = __uint_as_float(key_to_bits(s.bc[4] << TOPM_SHIFT));
     // ---- B. the tokens that are not below L, in token order, each wavefront into its own part of the list,
     // each with its logit
-    const uint32_t R = (uint32_t)(LIST / nw);
-    const uint32_t base = (uint32_t)wave * R;
     uint32_t cnt = 0;   // wave-uniform
     // bf16 rows are compared two tokens at a time on 16-bit keys: everything whose key is not below the edge's.
     // (-0 has the key just under +0's here; an edge at +0 is lowered by one so that it stays listed.  The list may
@@ -393,7 +399,7 @@ __device__ inline bool select_listed(const T *__restrict__ row, int V, int c0, i
     const uint32_t edge_key16 = s.bc[4] << (16 - TOPM_BITS);
     const uint32_t th16 = edge_key16 == 0x8000u ? 0x7FFEu : edge_key16 - 1u;   // listed: key above th16 (edge 0: all)
     const uint32_t th_pk = th16 | (th16 << 16);
-    if (!kept && !first_only) {   // A has left its last chunks in r
+    if (a_batches > 1) {   // A has left its last chunks in r
         load_chunks<T, true>(row, V, nc, c0, lane, r);
         load_chunks<T, true>(row, V, nc, c0 + 4, lane, r + 4);
     }
@@ -777,9 +783,10 @@ __global__ __launch_bounds__(TOPM_WAVES *WAVE) void topm_kernel(IndexView ix, co
             return;
         }
         // Counting pays where the selection would hold the row in registers anyway (it skips the bound, the list and
-        // the cut: 9 against 12 us at V = 32k) and where the selection would read the row twice; a long row that the
-        // selection reads once (bound from the first chunks) is no faster counted (V = 256k: 120 against 117 us).
-        const bool select_reads_once = listed && (cpw <= TOPM_HELD || (long long)m * cpw <= 4ll * LIST);
+        // the cut: 9 against 12 us at V = 32k) and where the selection would read part of the row twice; a long row
+        // that the selection reads once (bound from its first chunks alone, see select_listed) is no faster counted
+        // (V = 256k: 120 against 117 us).
+        const bool select_reads_once = listed && (cpw <= TOPM_HELD || (long long)m * cpw <= 2ll * LIST);
         if (n <= TOPM_COUNT_MAX && (uint32_t)n <= ix.heavy_min && (cpw <= TOPM_HELD || !select_reads_once)) {
             count_children<T>(ix, row, V, nc, c0, c1, m, cb, n, r, seg_a, out, n_words, lane, nthreads);
             return;
