@@ -10,7 +10,10 @@
 //                 least M tokens reach.  A wavefront holds eight chunks of the row (8 KB of bf16) in
 //                 registers; when its share of the row is longer, A looks only at those eight --
 //                 the M-th largest of a part of the row is still a lower bound of the row's --
-//                 provided the list has room for what the looser bound lets through;
+//                 provided the list has room for what the looser bound lets through (else from as
+//                 many more of its chunks as it takes).  When A has looked at one set of eight, the
+//                 maxima inside the bound's bin are counted once more by their next five key bits
+//                 and the bound moves up inside the bin;
 //              B. the tokens that are not below L are listed in LDS in token order, each with its
 //                 logit: usually 1.1 to 1.5 M of them, from registers when A saw the whole row,
 //                 else about as many times more as the share is longer than eight chunks, from the
@@ -220,6 +223,7 @@ template <typename T> __device__ inline uint32_t full_key(uint32_t hi_part) {
 
 struct TopmLds {
     uint32_t *hist;       // [TOPM_BINS]
+    uint32_t *hist3;      // [32] the group maxima inside the bound's bin, by their next five key bits
     uint32_t *hist2;      // [TOPM_CBINS] the listed tokens' keys, counted from the bound (filled while they are listed)
     uint32_t *list_tok;   // [LIST]
     uint32_t *list_key;   // [LIST] the listed tokens' logits (bit patterns, bf16 in the upper half)
@@ -353,17 +357,21 @@ __device__ inline bool select_listed(const T *__restrict__ row, int V, int c0, i
     const int nc = (V + WAVE * EPL - 1) / (WAVE * EPL);
     const int cpw = (nc + nw - 1) / nw;             // chunks per wavefront (the last ones may have fewer)
     const bool kept = cpw <= TOPM_HELD;             // r holds a wavefront's whole share
-    // With the bound from the whole row the list holds 1.1 to 1.5 m tokens when the keys are spread out and
-    // about 4 m for bf16 noise (a bin of the bound is 32 bf16 values wide); from a_batches batches of the share,
-    // cpw / (TOPM_HELD a_batches) times more: as few batches as leave room for 4 m times that.
-    // (A list that overflows all the same sends the row to the whole-row select.)
+    // With the bound from the whole row the list holds 1.1 to 1.5 m tokens when the bound is taken to the key's
+    // upper 16 bits (below: possible when A looks at one batch) and about 4 m of a row of noise when it stays at
+    // the histogram's bin, a quarter of an octave; from a_batches batches of the share, cpw / (TOPM_HELD a_batches)
+    // times more.  One batch if the list then has room for twice 1.3 m times that, else as few as leave room for
+    // 4 m times that.  (A list that overflows all the same sends the row to the whole-row select.)
     const int all_batches = (cpw + TOPM_HELD - 1) / TOPM_HELD;
-    const long long want = ((long long)m * cpw + 2ll * LIST - 1) / (2ll * LIST);
-    const int a_batches = want < 1 ? 1 : (want > all_batches ? all_batches : (int)want);
+    const long long want = (long long)m * cpw <= 4ll * LIST ? 1 : ((long long)m * cpw + 2ll * LIST - 1) / (2ll * LIST);
+    const int a_batches = want > all_batches ? all_batches : (int)want;
     const uint32_t R = (uint32_t)(LIST / nw);
     const uint32_t base = (uint32_t)wave * R;
     const int a_end = c0 + a_batches * TOPM_HELD < c1 ? c0 + a_batches * TOPM_HELD : c1;
+    uint32_t gk[TOPM_HELD];   // the keys of this lane's group maxima in the batch A looked at last, and which of them count
+    uint32_t gvalid = 0u;
     for (int c = c0; c < a_end; c += TOPM_HELD) {
+        gvalid = 0u;
         if (c != c0) {   // (chunks that A reads from memory are read again in B: from cache)
             load_chunks<T, false>(row, V, nc, c, lane, r);
             load_chunks<T, false>(row, V, nc, c + 4, lane, r + 4);
@@ -381,22 +389,37 @@ __device__ inline bool select_listed(const T *__restrict__ row, int V, int c0, i
             float gm = x[0];
 #pragma unroll
             for (int j = 1; j < EPL; j++) gm = fmaxf(gm, x[j]);
-            if (c + u < c1 && n > 0)
-                atomicAdd(&s.hist[order_key(__float_as_uint(gm)) >> TOPM_SHIFT], 1u);
+            gk[u] = order_key(__float_as_uint(gm));
+            if (c + u < c1 && n > 0) {
+                atomicAdd(&s.hist[gk[u] >> TOPM_SHIFT], 1u);
+                gvalid |= 1u << u;
+            }
         }
     }
     __syncthreads();
     pick_digit(s.hist, TOPM_BINS, (uint32_t)m, s.wave_tot, s.bc, nthreads);
     // At least m groups have their maximum in this bin or above, so at least m tokens are not below the bin's
     // lower edge.  With fewer than m groups in the row the bin is 0 and its edge is a NaN: nothing is below it.
-    const float L = __uint_as_float(key_to_bits(s.bc[4] << TOPM_SHIFT));
+    uint32_t edge_key16 = s.bc[4] << (16 - TOPM_BITS);
+    if (a_batches == 1 && s.bc[4] != 0u) {   // (uniform)
+        // A bin is a quarter of an octave wide and holds several times m tokens of a row of noise.  The maxima that
+        // A has just seen are still in registers: those inside the bin are counted by their next five key bits, and
+        // the bound moves up to the thirty-second of the bin in which the count from the top reaches m.
+        const uint32_t bin = s.bc[4], rest = s.bc[5];
+#pragma unroll
+        for (int u = 0; u < TOPM_HELD; u++)
+            if (((gvalid >> u) & 1u) && (gk[u] >> TOPM_SHIFT) == bin) atomicAdd(&s.hist3[(gk[u] >> 16) & 31u], 1u);
+        __syncthreads();
+        pick_digit(s.hist3, 32, rest, s.wave_tot, s.bc, nthreads);
+        edge_key16 |= s.bc[4];
+    }
+    const float L = __uint_as_float(key_to_bits(edge_key16 << 16));
     // ---- B. the tokens that are not below L, in token order, each wavefront into its own part of the list,
     // each with its logit
     uint32_t cnt = 0;   // wave-uniform
     // bf16 rows are compared two tokens at a time on 16-bit keys: everything whose key is not below the edge's.
     // (-0 has the key just under +0's here; an edge at +0 is lowered by one so that it stays listed.  The list may
     // hold more than the float comparison would put there, never less: C goes by the exact keys.)
-    const uint32_t edge_key16 = s.bc[4] << (16 - TOPM_BITS);
     const uint32_t th16 = edge_key16 == 0x8000u ? 0x7FFEu : edge_key16 - 1u;   // listed: key above th16 (edge 0: all)
     const uint32_t th_pk = th16 | (th16 << 16);
     if (a_batches > 1) {   // A has left its last chunks in r
@@ -502,7 +525,7 @@ __device__ inline bool select_listed(const T *__restrict__ row, int V, int c0, i
     }
     __syncthreads();
     if (s.bc[6] != 0u) return false;
-    const uint32_t edge16 = s.bc[4] << (16 - TOPM_BITS);
+    const uint32_t edge16 = edge_key16;
 
     // ---- C. the key T of the m-th largest token, from the list.  Thread t answers for the entries t*S .. t*S+S-1
     // of the list, which lie in its own wavefront's part (S = R / 64).
@@ -723,12 +746,12 @@ __global__ __launch_bounds__(TOPM_WAVES *WAVE) void topm_kernel(IndexView ix, co
     extern __shared__ __align__(16) uint32_t smem[];  // max(TOPM_BINS, n_words) words
     uint32_t *img = smem;                             // [n_words] the row of the mask, once the histogram is done with
     __shared__ uint32_t list_tok[LIST], list_key[LIST];
-    __shared__ uint32_t hist2[TOPM_CBINS];
+    __shared__ uint32_t hist2[TOPM_CBINS], hist3[32];
     __shared__ uint32_t kids[PPV_LIST_MAX];   // the tokens of the prefix's children, when they are listed (not a heavy prefix)
     __shared__ uint32_t sel[PPV_TOPM_MAX];
     __shared__ uint32_t seg_a[TOPM_WAVES], seg_b[TOPM_WAVES], wave_tot[TOPM_WAVES];
     __shared__ uint32_t bc[8];
-    const TopmLds lds = {smem, hist2, list_tok, list_key, sel, seg_a, seg_b, wave_tot, bc};
+    const TopmLds lds = {smem, hist3, hist2, list_tok, list_key, sel, seg_a, seg_b, wave_tot, bc};
     const int b = blockIdx.x, tid = threadIdx.x, lane = tid & (WAVE - 1);
     const int wave = __builtin_amdgcn_readfirstlane(tid / WAVE);
     const int nthreads = blockDim.x, nw = nthreads / WAVE;
@@ -753,6 +776,7 @@ __global__ __launch_bounds__(TOPM_WAVES *WAVE) void topm_kernel(IndexView ix, co
     if (listed) {   // what the list select starts from
         for (int i = tid; i < TOPM_BINS; i += nthreads) smem[i] = 0u;
         for (int i = tid; i < TOPM_CBINS; i += nthreads) hist2[i] = 0u;
+        if (tid < 32) hist3[tid] = 0u;
         if (tid == 0) bc[6] = 0u;
     }
     if (wave == 0) {   // the part every candidate row shares: locate the prefix once
@@ -786,7 +810,7 @@ __global__ __launch_bounds__(TOPM_WAVES *WAVE) void topm_kernel(IndexView ix, co
         // the cut: 9 against 12 us at V = 32k) and where the selection would read part of the row twice; a long row
         // that the selection reads once (bound from its first chunks alone, see select_listed) is no faster counted
         // (V = 256k: 120 against 117 us).
-        const bool select_reads_once = listed && (cpw <= TOPM_HELD || (long long)m * cpw <= 2ll * LIST);
+        const bool select_reads_once = listed && (cpw <= TOPM_HELD || (long long)m * cpw <= 4ll * LIST);
         if (n <= TOPM_COUNT_MAX && (uint32_t)n <= ix.heavy_min && (cpw <= TOPM_HELD || !select_reads_once)) {
             count_children<T>(ix, row, V, nc, c0, c1, m, cb, n, r, seg_a, out, n_words, lane, nthreads);
             return;
