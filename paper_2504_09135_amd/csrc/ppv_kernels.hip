@@ -544,12 +544,38 @@ __device__ inline void stream_tiles(const T *__restrict__ row, int V, const RawT
         reduce_tile(Y, wave + (i + 1) * nw);
         reduce_tile(Z, wave + (i + 2) * nw);
         i += 3;
+    } else if (!PIPE && cnt >= 2) {
+        // a short turn (in the kernels without the three-tile pipeline, which have the registers for it): two tiles take turns in X and Y, the next one asked for before this one is reduced.  Every
+        // fetch stands in straight-line code with the reduction that follows it, so the waits stay exact.
+        while (i + 2 < cnt) {   // X holds tile i
+            fetch(Y, wave + (i + 1) * nw);
+            if (!mid_done) {
+                mid();
+                mid_done = true;
+            }
+            reduce_tile(X, wave + i * nw);
+            fetch(X, wave + (i + 2) * nw);
+            reduce_tile(Y, wave + (i + 1) * nw);
+            i += 2;
+        }
+        if (i + 1 < cnt) {
+            fetch(Y, wave + (i + 1) * nw);
+            if (!mid_done) {
+                mid();
+                mid_done = true;
+            }
+            reduce_tile(X, wave + i * nw);
+            reduce_tile(Y, wave + (i + 1) * nw);
+            i += 2;
+        } else {
+            reduce_tile(X, wave + i * nw);
+            i += 1;
+        }
     } else if (cnt > 0 || wave == nfull) {
         reduce_tile(X, wave);   // a single full tile, or the ragged one when the wave has nothing else
         i = 1;
     }
-    // what is left (a turn of fewer than six tiles is not pipelined: a second pipeline for short turns
-    // cost 30 more registers and was slower), and perhaps the ragged tail
+    // what is left (a short turn in a kernel with the three-tile pipeline, tile by tile), and perhaps the ragged tail
     for (; i < cnt; i++) {
         fetch(Z, wave + i * nw);
         if (!mid_done) {
