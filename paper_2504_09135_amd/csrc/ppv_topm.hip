@@ -378,6 +378,7 @@ __device__ inline bool select_listed(const T *__restrict__ row, int V, int c0, i
         }
 #pragma unroll
         for (int u = 0; u < TOPM_HELD; u++) {
+            if (c + u >= c1) continue;   // (wave-uniform) short rows: most of r is unused
             float x[EPL];
             unpack_vals<T>(r[u], x);
             const int n = n_inside<T>(V, c + u, lane);
@@ -390,7 +391,7 @@ __device__ inline bool select_listed(const T *__restrict__ row, int V, int c0, i
 #pragma unroll
             for (int j = 1; j < EPL; j++) gm = fmaxf(gm, x[j]);
             gk[u] = order_key(__float_as_uint(gm));
-            if (c + u < c1 && n > 0) {
+            if (n > 0) {
                 atomicAdd(&s.hist[gk[u] >> TOPM_SHIFT], 1u);
                 gvalid |= 1u << u;
             }
@@ -743,11 +744,10 @@ __global__ __launch_bounds__(TOPM_WAVES *WAVE) void topm_kernel(IndexView ix, co
                                                                 uint8_t *__restrict__ mask_V,
                                                                 uint32_t *__restrict__ mask) {
     constexpr int EPL = KeyChunk<T>::EPL;
-    extern __shared__ __align__(16) uint32_t smem[];  // max(TOPM_BINS, n_words) words
+    extern __shared__ __align__(16) uint32_t smem[];  // max(TOPM_BINS, n_words) words, then heavy_min words for kids
     uint32_t *img = smem;                             // [n_words] the row of the mask, once the histogram is done with
     __shared__ uint32_t list_tok[LIST], list_key[LIST];
     __shared__ uint32_t hist2[TOPM_CBINS], hist3[32];
-    __shared__ uint32_t kids[PPV_LIST_MAX];   // the tokens of the prefix's children, when they are listed (not a heavy prefix)
     __shared__ uint32_t sel[PPV_TOPM_MAX];
     __shared__ uint32_t seg_a[TOPM_WAVES], seg_b[TOPM_WAVES], wave_tot[TOPM_WAVES];
     __shared__ uint32_t bc[8];
@@ -757,6 +757,8 @@ __global__ __launch_bounds__(TOPM_WAVES *WAVE) void topm_kernel(IndexView ix, co
     const int nthreads = blockDim.x, nw = nthreads / WAVE;
     const int V = ix.vocab, n_words = ix.n_words;
     const int m = M < V ? M : V;                      // candidates of this row
+    // the tokens of the prefix's children, when they are listed (not a heavy prefix: at most heavy_min of them)
+    uint32_t *kids = smem + (n_words > TOPM_BINS ? n_words : TOPM_BINS);
     const T *row = logits + (size_t)b * (size_t)row_stride;
 
     // this wavefront's contiguous share of the row, in chunks of one 16-byte load per lane
@@ -770,7 +772,7 @@ __global__ __launch_bounds__(TOPM_WAVES *WAVE) void topm_kernel(IndexView ix, co
     uint4 r[TOPM_HELD];
     if (listed || counting) {   // in flight while the prefix is located
         load_chunks<T, true>(row, V, nc, c0, lane, r);
-        load_chunks<T, true>(row, V, nc, c0 + 4, lane, r + 4);
+        if (cpw > 4) load_chunks<T, true>(row, V, nc, c0 + 4, lane, r + 4);   // (uniform; a short row has no second half)
     }
     if (counting && tid < TOPM_COUNT_MAX) seg_a[tid] = 0u;
     if (listed) {   // what the list select starts from
@@ -895,7 +897,7 @@ extern "C" ppv_status ppv_topm_mask(const ppv_index_t *ix, const int32_t *prefix
     // testing aid: PPV_TUNE_TOPM_STREAMING = 1 sends every row through the whole-row radix select; 2 keeps the usual
     // select but takes the top M also where counting would do (mask-only calls)
     const int force_streaming = ppv_tuning(PPV_TUNE_TOPM_STREAMING);
-    const size_t lds = (size_t)(ix->view.n_words > TOPM_BINS ? ix->view.n_words : TOPM_BINS) * sizeof(uint32_t);
+    const size_t lds = ((size_t)(ix->view.n_words > TOPM_BINS ? ix->view.n_words : TOPM_BINS) + ix->view.heavy_min) * sizeof(uint32_t);
     const dim3 grid((unsigned)B), block(threads);
     hipStream_t hs = (hipStream_t)stream;
 #define PPV_LAUNCH_TOPM(T, LIST)                                                                                      \
