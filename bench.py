@@ -30,9 +30,9 @@ HBM_PEAK_GBS = 8000.0  # MI355X published peak HBM3E bandwidth
 # scaled by what the same counter reads for a plain copy of known size); see profiles/.  Keyed by
 # (workload, batch); None until measured for that shape.
 TRAFFIC_BYTES_PER_LAUNCH = {
-    ("C3", 256): (9779266, "profiles/decode_kernel_C3_B256.md: FETCH_SIZE + WRITE_SIZE of the per-step decode_kernel, "
+    ("C3", 256): (9819569, "profiles/decode_kernel_C3_B256.md: FETCH_SIZE + WRITE_SIZE of the per-step decode_kernel, "
                            "mean over the 32 launches of a loop, copy-calibrated"),
-    ("C5", 1024): (529866764, "profiles/mask_sample_kernels_C5.md: FETCH_SIZE + WRITE_SIZE of the one-call kernel, "
+    ("C5", 1024): (529872422, "profiles/mask_sample_kernels_C5.md: FETCH_SIZE + WRITE_SIZE of the one-call kernel, "
                               "copy-calibrated"),
 }
 
