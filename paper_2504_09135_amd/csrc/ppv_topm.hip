@@ -871,6 +871,7 @@ int topm_waves(int V, ppv_dtype dt, int B) {
     int cap = B <= 512 ? 8 : 4;   // measured at V = 32k, M = 50: B = 256: 11.1 / 11.9 us with 8 / 16; B = 4,096: 63 / 90 / 169 us with 4 / 8 / 16
     // long rows (bf16, us per call with 4 / 8 / 16 wavefronts, M = 50 and 1,000): V = 128k: B = 128: 36 / 23 / 19 and 48 / 32 / 23,
     // B = 1,024: 75 / 66 / 83 and 120 / 99 / 102; V = 256k: B = 128: 60 / 37 / 27 and 78 / 49 / 42, B = 1,024: 118 / 117 / 143 (M = 50)
+    if (nc <= 4 && B > 512) cap = 2;   // 4 KB rows (V = 1,024 fp32), B = 4,096, M = 50 / 1,000: 39 / 85 us with 1, 32 / 57 with 2, 36 / 64 with 4
     if (nc >= 128 && B <= 256) cap = 16;
     if (nc >= 128 && B <= 2048 && cap < 8) cap = 8;
     if (const int v = ppv_tuning(PPV_TUNE_TOPM_WAVES)) cap = v < TOPM_WAVES ? v : TOPM_WAVES;   // tuning aid (0: the table above)
